@@ -1,0 +1,117 @@
+"""CPU oracle (test infrastructure only) for the inverse convolution and its backward.
+
+Thin ctypes wrapper around ``invconv_oracle.c``.  Inputs are promoted to
+float64; every result is float64.  Only tests, the smoke check and the bench's
+``cpu_baseline`` leg may import this package; the GPU library never does.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "invconv_oracle.c")
+_LIB = os.path.join(_HERE, "libinvconv_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, OpenMP over the batch)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp",
+                               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        dp = ctypes.POINTER(ctypes.c_double)
+        ci = ctypes.c_int
+        lib.oracle_conv.argtypes = [dp, dp, dp, ci, ci, ci, ci, ci, ci]
+        lib.oracle_invconv_fwd.argtypes = [dp, dp, dp, ci, ci, ci, ci, ci, ci]
+        lib.oracle_invconv_bwd_dy.argtypes = [dp, dp, dp, ci, ci, ci, ci, ci, ci]
+        lib.oracle_invconv_bwd_dw.argtypes = [dp, dp, dp, ci, ci, ci, ci, ci, ci]
+        lib.oracle_invconv_logdet.argtypes = [dp, ci, ci, ci, ci]
+        lib.oracle_invconv_logdet.restype = ctypes.c_double
+        lib.oracle_max_threads.restype = ci
+        for f in (lib.oracle_conv, lib.oracle_invconv_fwd, lib.oracle_invconv_bwd_dy,
+                  lib.oracle_invconv_bwd_dw):
+            f.restype = None
+        _lib = lib
+    return _lib
+
+
+def _d(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _dims(act: np.ndarray, w: np.ndarray):
+    if act.ndim != 4 or w.ndim != 4:
+        raise ValueError("activations must be [B,C,H,W] and kernels [C,C,k,k]")
+    B, C, H, W = act.shape
+    if w.shape[0] != C or w.shape[1] != C or w.shape[2] != w.shape[3]:
+        raise ValueError(f"kernel shape {w.shape} does not match C={C}")
+    return B, C, H, W, w.shape[2]
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+def conv(x, w, threads: int = 1) -> np.ndarray:
+    """y = conv_w(x): masked causal convolution, Eq. 1."""
+    x, w = _d(x), _d(w)
+    B, C, H, W, k = _dims(x, w)
+    y = np.empty_like(x)
+    _load().oracle_conv(_p(x), _p(w), _p(y), B, C, H, W, k, threads)
+    return y
+
+
+def invconv_fwd(y, w, threads: int = 1) -> np.ndarray:
+    """x with conv_w(x) = y, by forward substitution in row-major order."""
+    y, w = _d(y), _d(w)
+    B, C, H, W, k = _dims(y, w)
+    x = np.empty_like(y)
+    _load().oracle_invconv_fwd(_p(y), _p(w), _p(x), B, C, H, W, k, threads)
+    return x
+
+
+def invconv_bwd_dy(g, w, threads: int = 1) -> np.ndarray:
+    """dL/dy = M^{-T} dL/dx (Eq. 2 / Theorem 1)."""
+    g, w = _d(g), _d(w)
+    B, C, H, W, k = _dims(g, w)
+    v = np.empty_like(g)
+    _load().oracle_invconv_bwd_dy(_p(g), _p(w), _p(v), B, C, H, W, k, threads)
+    return v
+
+
+def invconv_bwd_dw(x, v, k: int, threads: int = 1) -> np.ndarray:
+    """dL/dW = -sum v (x) shifted x (Eq. 4 / Theorem 2), summed over batch and pixels."""
+    x, v = _d(x), _d(v)
+    B, C, H, W = x.shape
+    dw = np.empty((C, C, k, k), dtype=np.float64)
+    _load().oracle_invconv_bwd_dw(_p(x), _p(v), _p(dw), B, C, H, W, k, threads)
+    return dw
+
+
+def invconv_bwd(x, w, g, threads: int = 1):
+    """(dL/dy, dL/dW) given the forward output x, the kernel and dL/dx."""
+    w = _d(w)
+    v = invconv_bwd_dy(g, w, threads)
+    return v, invconv_bwd_dw(x, v, w.shape[2], threads)
+
+
+def invconv_logdet(w, H: int, W: int) -> float:
+    """log|det dx/dy| of the inverse convolution for one H x W image."""
+    w = _d(w)
+    C, k = w.shape[0], w.shape[2]
+    return float(_load().oracle_invconv_logdet(_p(w), C, H, W, k))
