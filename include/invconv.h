@@ -1,0 +1,114 @@
+/*
+ * invconv.h - C ABI of the MI355X (gfx950) inverse-convolution library.
+ *
+ * The operator is the inverse of a causally masked k x k convolution
+ * (Section 3 of "Parallel Backpropagation for Inverse of a Convolution with
+ * Application to Normalizing Flows"): the input image is zero-padded with k-1
+ * rows on top and k-1 columns on the left, so output pixel (r,c) of
+ * y = conv_w(x) reads x only at (r',c') with r-k < r' <= r, c-k < c' <= c, and
+ * the bottom-right kernel tap multiplies the current pixel (Eq. 1).
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer except `stream` is a DEVICE pointer to contiguous fp32.
+ *     The caller owns all buffers; the library never allocates, frees or keeps
+ *     them.  `stream` is a hipStream_t (NULL = the default stream).  Calls are
+ *     asynchronous on `stream`: no host synchronisation, no host read-back.
+ *   - Activations (y, x, dLdx, dLdy) are [B][C][H][W].
+ *   - Kernels (w, dLdw) are [C_out = C][C_in = C][k][k] (Algorithm 1's
+ *     K[c, k_c, ., .]).  Tap (a,b) multiplies x[., r-(k-1)+a, c-(k-1)+b].
+ *   - At the current-pixel tap (a,b) = (k-1,k-1) the channel mixing is lower
+ *     triangular: entries w[o][i][k-1][k-1] with i > o are IGNORED whatever
+ *     they hold, and the matching dLdw entries are written as 0.  The diagonal
+ *     w[c][c][k-1][k-1] must be non-zero (the paper fixes it to 1); a zero
+ *     diagonal is not checked and yields IEEE inf/NaN.
+ *   - H != W, k > min(H,W) and k = 1 are valid.
+ *   - Return value: INVCONV_OK or a negative invconv_status.  On any error no
+ *     kernel has been launched and no output has been touched.
+ */
+#ifndef INVCONV_H
+#define INVCONV_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int invconv_status;
+
+enum {
+    INVCONV_OK = 0,
+    INVCONV_ERR_NULL = -1,        /* a required pointer is NULL */
+    INVCONV_ERR_SHAPE = -2,       /* B, C, H, W or k < 1, or a size overflows int */
+    INVCONV_ERR_UNSUPPORTED = -3, /* shape beyond what the kernels' on-chip buffers hold */
+    INVCONV_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than invconv_bwd_workspace_bytes() */
+    INVCONV_ERR_ALIAS = -5,       /* an output pointer equals an input pointer */
+    INVCONV_ERR_LAUNCH = -6,      /* the HIP runtime refused a launch */
+    INVCONV_ERR_VARIANT = -7      /* unknown variant, or variant not available for this shape */
+};
+
+/* Kernel variants (for measurement; INVCONV_VARIANT_AUTO is what the plain calls use). */
+enum {
+    INVCONV_VARIANT_AUTO = 0,
+    INVCONV_VARIANT_BLOCK = 1,    /* one workgroup per image, LDS window, one barrier per anti-diagonal */
+    INVCONV_VARIANT_DIAG_LAUNCH = 2 /* one kernel launch per anti-diagonal (capture it in a hipGraph) */
+};
+
+/*
+ * Forward pass of the inverse convolution: solves conv_w(x) = y for x by
+ * forward substitution, x_q = (y_q - sum_{r in Delta(q)} W_{(k,k)-q+r} x_r) / W_{k,k}
+ * (Eq. 1 rearranged, as in the proofs of Theorems 1 and 2).  Pixels on one
+ * anti-diagonal are independent and are processed in parallel; anti-diagonals
+ * are processed in increasing order (Section 3.3).
+ *   y [in]  B*C*H*W     w [in]  C*C*k*k     x [out] B*C*H*W, must not alias y.
+ */
+invconv_status invconv_fwd(const float *y, const float *w, float *x,
+                           int B, int C, int H, int W, int k, void *stream);
+
+/*
+ * Backward pass (Section 3.1-3.3, Eq. 2 and Eq. 4, Theorems 1 and 2).
+ *   dLdy = M^{-T} dLdx, M being the matrix of conv_w: the transposed system is
+ *          solved by back-substitution over anti-diagonals in decreasing order.
+ *   dLdw[o][i][a][b] = - sum_{n,r,c} dLdy[n][o][r][c] * x[n][i][r-(k-1)+a][c-(k-1)+b],
+ *          summed over batch and pixels, 0 at masked entries; computed with a
+ *          fixed-order two-pass reduction (bitwise reproducible, no atomics).
+ *   x [in] output of invconv_fwd    dLdx [in]    dLdy [out] must not alias x or dLdx
+ *   dLdw [out] C*C*k*k floats, overwritten (not accumulated)
+ *   workspace [scratch] device memory of at least invconv_bwd_workspace_bytes() bytes,
+ *          256-byte aligned; contents undefined afterwards.
+ */
+invconv_status invconv_bwd(const float *x, const float *w, const float *dLdx,
+                           float *dLdy, float *dLdw,
+                           int B, int C, int H, int W, int k,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of scratch invconv_bwd needs for this shape; 0 if the shape is invalid or unsupported. */
+size_t invconv_bwd_workspace_bytes(int B, int C, int H, int W, int k);
+
+/*
+ * log |det dx/dy| of the inverse convolution for ONE H x W image (Section 4):
+ * the Jacobian is triangular, so this is -H*W*sum_c log|w[c][c][k-1][k-1]|,
+ * exactly 0 for the paper's unit diagonal.  Independent of the data and of B.
+ *   out [out] one device float.
+ */
+invconv_status invconv_logdet(const float *w, int C, int H, int W, int k,
+                              float *out, void *stream);
+
+/* Same operations with an explicit kernel variant (INVCONV_VARIANT_*). */
+invconv_status invconv_fwd_ex(const float *y, const float *w, float *x,
+                              int B, int C, int H, int W, int k, void *stream, int variant);
+invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
+                              float *dLdy, float *dLdw,
+                              int B, int C, int H, int W, int k,
+                              void *workspace, size_t workspace_bytes, void *stream, int variant);
+
+/* Static, human-readable name of a status code. */
+const char *invconv_status_string(invconv_status status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int invconv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INVCONV_H */

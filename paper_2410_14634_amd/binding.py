@@ -1,0 +1,137 @@
+"""Thin ctypes binding over libinvconv.so: argument marshalling only.
+
+PyTorch is used for device memory and the current HIP stream; every step of
+the computation runs in the library's kernels.  There is no CPU fallback: if
+the shared library has not been built this module raises at import of the
+first symbol.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libinvconv.so")
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_ALIAS, ERR_LAUNCH, ERR_VARIANT = range(-1, -8, -1)
+VARIANT_AUTO, VARIANT_BLOCK, VARIANT_DIAG_LAUNCH = 0, 1, 2
+
+EXPORTS = (
+    "invconv_fwd", "invconv_bwd", "invconv_bwd_workspace_bytes", "invconv_logdet",
+    "invconv_fwd_ex", "invconv_bwd_ex", "invconv_status_string", "invconv_version",
+)
+
+_lib = None
+
+
+class InvconvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2410_14634_amd.build` "
+                "(or __graft_entry__.build()); there is no CPU fallback")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.invconv_fwd.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.invconv_fwd_ex.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, ci]
+        L.invconv_bwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+        L.invconv_bwd_ex.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp, ci]
+        L.invconv_bwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+        L.invconv_bwd_workspace_bytes.restype = sz
+        L.invconv_logdet.argtypes = [vp, ci, ci, ci, ci, vp, vp]
+        L.invconv_status_string.argtypes = [ci]
+        L.invconv_status_string.restype = ctypes.c_char_p
+        L.invconv_version.restype = ci
+        for name in ("invconv_fwd", "invconv_fwd_ex", "invconv_bwd", "invconv_bwd_ex", "invconv_logdet"):
+            getattr(L, name).restype = ci
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().invconv_status_string(status).decode()
+
+
+def version() -> int:
+    return int(lib().invconv_version())
+
+
+def _check(t: torch.Tensor, name: str, shape=None) -> torch.Tensor:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous float32 CUDA tensor")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return t
+
+
+def _dims(act: torch.Tensor, w: torch.Tensor):
+    if act.dim() != 4 or w.dim() != 4:
+        raise ValueError("activations must be [B,C,H,W] and kernels [C,C,k,k]")
+    B, C, H, W = act.shape
+    if w.shape[0] != C or w.shape[1] != C or w.shape[2] != w.shape[3]:
+        raise ValueError(f"kernel shape {tuple(w.shape)} does not match C={C}")
+    return B, C, H, W, w.shape[2]
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def bwd_workspace_bytes(B: int, C: int, H: int, W: int, k: int) -> int:
+    return int(lib().invconv_bwd_workspace_bytes(B, C, H, W, k))
+
+
+def invconv_fwd(y: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None,
+                variant: int = VARIANT_AUTO) -> torch.Tensor:
+    """x with conv_w(x) = y (inverse of the masked causal convolution)."""
+    _check(y, "y"), _check(w, "w")
+    B, C, H, W, k = _dims(y, w)
+    x = torch.empty_like(y) if out is None else _check(out, "out", y.shape)
+    st = lib().invconv_fwd_ex(y.data_ptr(), w.data_ptr(), x.data_ptr(), B, C, H, W, k, _stream(), variant)
+    if st != OK:
+        raise InvconvError(st, "invconv_fwd")
+    return x
+
+
+def invconv_bwd(x: torch.Tensor, w: torch.Tensor, dLdx: torch.Tensor,
+                out: tuple[torch.Tensor, torch.Tensor] | None = None,
+                workspace: torch.Tensor | None = None, variant: int = VARIANT_AUTO):
+    """(dL/dy, dL/dw) from the forward output x, the kernel and dL/dx."""
+    _check(x, "x"), _check(w, "w"), _check(dLdx, "dLdx", x.shape)
+    B, C, H, W, k = _dims(x, w)
+    if out is None:
+        dLdy, dLdw = torch.empty_like(x), torch.empty_like(w)
+    else:
+        dLdy, dLdw = _check(out[0], "out[0]", x.shape), _check(out[1], "out[1]", w.shape)
+    need = bwd_workspace_bytes(B, C, H, W, k)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    st = lib().invconv_bwd_ex(x.data_ptr(), w.data_ptr(), dLdx.data_ptr(), dLdy.data_ptr(), dLdw.data_ptr(),
+                              B, C, H, W, k, workspace.data_ptr(), ws_bytes, _stream(), variant)
+    if st != OK:
+        raise InvconvError(st, "invconv_bwd")
+    return dLdy, dLdw
+
+
+def invconv_logdet(w: torch.Tensor, H: int, W: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """log|det dx/dy| of the inverse convolution for one H x W image (a 1-element tensor)."""
+    _check(w, "w")
+    if w.dim() != 4 or w.shape[0] != w.shape[1] or w.shape[2] != w.shape[3]:
+        raise ValueError("kernel must be [C,C,k,k]")
+    res = torch.empty(1, dtype=torch.float32, device=w.device) if out is None else _check(out, "out", (1,))
+    st = lib().invconv_logdet(w.data_ptr(), w.shape[0], H, W, w.shape[2], res.data_ptr(), _stream())
+    if st != OK:
+        raise InvconvError(st, "invconv_logdet")
+    return res

@@ -1,0 +1,134 @@
+// C ABI of the inverse-convolution library: argument validation and dispatch.
+#include "invconv_launch.h"
+
+using namespace invconv;
+
+namespace {
+
+constexpr int kVersion = 100;   // 0.1.0
+
+int check_shape(int B, int C, int H, int W, int k)
+{
+    if (B < 1 || C < 1 || H < 1 || W < 1 || k < 1)
+        return INVCONV_ERR_SHAPE;
+    const long long lim = 0x7fffffffLL;
+    if ((long long)B * C * H * W > lim || (long long)C * C * k * k > lim || (long long)H + W > lim)
+        return INVCONV_ERR_SHAPE;
+    return INVCONV_OK;
+}
+
+int check_supported(int C, int H, int k)
+{
+    return solve_block_lds_bytes(C, H, k) <= kMaxLdsBytes ? INVCONV_OK : INVCONV_ERR_UNSUPPORTED;
+}
+
+int solve(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+          hipStream_t stream, int variant)
+{
+    switch (variant) {
+    case INVCONV_VARIANT_AUTO:
+    case INVCONV_VARIANT_BLOCK:
+        return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);
+    case INVCONV_VARIANT_DIAG_LAUNCH:
+        return launch_solve_diag(dir, in, w, out, B, C, H, W, k, stream);
+    default:
+        return INVCONV_ERR_VARIANT;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+invconv_status invconv_fwd_ex(const float *y, const float *w, float *x, int B, int C, int H, int W, int k,
+                              void *stream, int variant)
+{
+    if (!y || !w || !x)
+        return INVCONV_ERR_NULL;
+    if (int s = check_shape(B, C, H, W, k))
+        return s;
+    if (x == y || (const float *)x == w)
+        return INVCONV_ERR_ALIAS;
+    if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_DIAG_LAUNCH)
+        return INVCONV_ERR_VARIANT;
+    if (variant != INVCONV_VARIANT_DIAG_LAUNCH)
+        if (int s = check_supported(C, H, k))
+            return s;
+    return solve(0, y, w, x, B, C, H, W, k, (hipStream_t)stream, variant);
+}
+
+invconv_status invconv_fwd(const float *y, const float *w, float *x, int B, int C, int H, int W, int k,
+                           void *stream)
+{
+    return invconv_fwd_ex(y, w, x, B, C, H, W, k, stream, INVCONV_VARIANT_AUTO);
+}
+
+size_t invconv_bwd_workspace_bytes(int B, int C, int H, int W, int k)
+{
+    if (check_shape(B, C, H, W, k) != INVCONV_OK)
+        return 0;
+    const DwPlan p = plan_dw(B, C, H, W, k);
+    return p.rt ? p.bytes : 0;
+}
+
+invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx, float *dLdy, float *dLdw,
+                              int B, int C, int H, int W, int k, void *workspace, size_t workspace_bytes,
+                              void *stream, int variant)
+{
+    if (!x || !w || !dLdx || !dLdy || !dLdw)
+        return INVCONV_ERR_NULL;
+    if (int s = check_shape(B, C, H, W, k))
+        return s;
+    if (dLdy == dLdx || dLdy == x || (const float *)dLdy == w || dLdw == dLdy || (const float *)dLdw == w ||
+        (const float *)dLdw == x || (const float *)dLdw == dLdx)
+        return INVCONV_ERR_ALIAS;
+    if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_DIAG_LAUNCH)
+        return INVCONV_ERR_VARIANT;
+    if (variant != INVCONV_VARIANT_DIAG_LAUNCH)
+        if (int s = check_supported(C, H, k))
+            return s;
+    const DwPlan p = plan_dw(B, C, H, W, k);
+    if (!p.rt)
+        return INVCONV_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < p.bytes)
+        return INVCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (int s = solve(1, dLdx, w, dLdy, B, C, H, W, k, st, variant))
+        return s;
+    return launch_dw(x, dLdy, dLdw, (float *)workspace, p, B, C, H, W, k, st);
+}
+
+invconv_status invconv_bwd(const float *x, const float *w, const float *dLdx, float *dLdy, float *dLdw, int B,
+                           int C, int H, int W, int k, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return invconv_bwd_ex(x, w, dLdx, dLdy, dLdw, B, C, H, W, k, workspace, workspace_bytes, stream,
+                          INVCONV_VARIANT_AUTO);
+}
+
+invconv_status invconv_logdet(const float *w, int C, int H, int W, int k, float *out, void *stream)
+{
+    if (!w || !out)
+        return INVCONV_ERR_NULL;
+    if (int s = check_shape(1, C, H, W, k))
+        return s;
+    return launch_logdet(w, C, H, W, k, out, (hipStream_t)stream);
+}
+
+const char *invconv_status_string(invconv_status status)
+{
+    switch (status) {
+    case INVCONV_OK: return "ok";
+    case INVCONV_ERR_NULL: return "null pointer argument";
+    case INVCONV_ERR_SHAPE: return "invalid shape (a dimension < 1 or a size overflow)";
+    case INVCONV_ERR_UNSUPPORTED: return "shape exceeds the kernels' on-chip buffers";
+    case INVCONV_ERR_WORKSPACE: return "workspace missing or too small";
+    case INVCONV_ERR_ALIAS: return "an output buffer aliases an input buffer";
+    case INVCONV_ERR_LAUNCH: return "HIP kernel launch failed";
+    case INVCONV_ERR_VARIANT: return "unknown or unavailable kernel variant";
+    default: return "unknown status";
+    }
+}
+
+int invconv_version(void) { return kVersion; }
+
+}  // extern "C"

@@ -1,0 +1,299 @@
+// Shape-generic kernels of the inverse convolution: the anti-diagonal
+// wavefront solve (both orientations), the weight-gradient correlation with
+// its fixed-order reduction, the log-determinant, and the one-launch-per-
+// anti-diagonal comparison variant.  gfx950 only.
+#include "invconv_common.h"
+#include "invconv_launch.h"
+
+namespace invconv {
+
+// ---------------------------------------------------------------------------
+// Wavefront solve, one workgroup per image (Section 3.3: anti-diagonals in
+// order, all pixels and channels of one anti-diagonal in parallel, one
+// barrier per anti-diagonal).
+//
+// LDS holds the folded weights and a rolling window of the last 2(k-1)
+// anti-diagonals of the solution plus the one being written, stored
+// diagonal-major as win[d mod ND][row][channel] (row stride CP is odd so that
+// lanes walking down a diagonal hit different banks).  Pixel (r,c) on diagonal
+// d = r+c reads its neighbour (r-da, c-db) from diagonal d-da-db, row r-da.
+// ---------------------------------------------------------------------------
+template <int DIR>
+__global__ __launch_bounds__(kSolveBlock) void k_solve_block(const float *__restrict__ in,
+                                                            const float *__restrict__ w,
+                                                            float *__restrict__ out,
+                                                            int C, int H, int W, int k)
+{
+    extern __shared__ float smem[];
+    const int CP = C | 1;
+    const int ND = 2 * (k - 1) + 1;
+    float *sL = smem;
+    float *sLinv = sL + C * C;
+    float *sCf = sLinv + C * C;
+    float *win = sCf + k * k * C * C;
+
+    const int n = blockIdx.x;
+    const int tid = threadIdx.x;
+    fold_weights<DIR>(w, C, k, sL, sLinv, sCf);
+
+    const int ndiag = H + W - 1;
+    for (int d = 0; d < ndiag; ++d) {
+        const int rlo = d - (W - 1) > 0 ? d - (W - 1) : 0;
+        const int rhi = d < H - 1 ? d : H - 1;
+        const int npx = rhi - rlo + 1;
+        const int items = npx * C;
+        const int slot_d = d % ND;
+        for (int it = tid; it < items; it += kSolveBlock) {
+            const int px = it % npx, o = it / npx;
+            const int r = rlo + px, c = d - r;
+            float acc = 0.0f;
+            for (int j = 0; j <= o; ++j)
+                acc += sLinv[o * C + j] * in[gidx<DIR>(n, j, r, c, C, H, W)];
+            for (int da = 0; da < k && da <= r; ++da)
+                for (int db = (da == 0) ? 1 : 0; db < k && db <= c; ++db) {
+                    int slot = slot_d - (da + db);
+                    if (slot < 0)
+                        slot += ND;
+                    const float *xw = win + (slot * H + (r - da)) * CP;
+                    const float *cf = sCf + ((da * k + db) * C + o) * C;
+                    for (int i = 0; i < C; ++i)
+                        acc -= cf[i] * xw[i];
+                }
+            win[(slot_d * H + r) * CP + o] = acc;
+            out[gidx<DIR>(n, o, r, c, C, H, W)] = acc;
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Comparison variant: one launch per anti-diagonal.  One thread per
+// (image, pixel of the diagonal); the thread solves its pixel's channels in
+// order with the unfolded kernel, reading neighbours from `out` in global
+// memory (written by earlier launches on the same stream).
+// ---------------------------------------------------------------------------
+template <int DIR>
+__global__ __launch_bounds__(256) void k_solve_one_diagonal(const float *__restrict__ in,
+                                                           const float *__restrict__ w,
+                                                           float *out, int B, int C, int H, int W,
+                                                           int k, int d)
+{
+    const int rlo = d - (W - 1) > 0 ? d - (W - 1) : 0;
+    const int rhi = d < H - 1 ? d : H - 1;
+    const int npx = rhi - rlo + 1;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= B * npx)
+        return;
+    const int n = t / npx, r = rlo + t % npx, c = d - r;
+    for (int o = 0; o < C; ++o) {
+        float acc = in[gidx<DIR>(n, o, r, c, C, H, W)];
+        for (int da = 0; da < k && da <= r; ++da)
+            for (int db = (da == 0) ? 1 : 0; db < k && db <= c; ++db)
+                for (int i = 0; i < C; ++i)
+                    acc -= weff<DIR>(w, C, k, o, i, k - 1 - da, k - 1 - db) *
+                           out[gidx<DIR>(n, i, r - da, c - db, C, H, W)];
+        for (int i = 0; i < o; ++i)
+            acc -= weff<DIR>(w, C, k, o, i, k - 1, k - 1) * out[gidx<DIR>(n, i, r, c, C, H, W)];
+        out[gidx<DIR>(n, o, r, c, C, H, W)] = acc / weff<DIR>(w, C, k, o, o, k - 1, k - 1);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Weight gradient, pass 1 (Eq. 4 with Theorem 2):
+//   dw[o][i][a][b] = - sum_{n,r,c} v[n][o][r][c] * x[n][i][r-(k-1)+a][c-(k-1)+b].
+// One workgroup per (image, chunk of RT rows) stages v and x (with a zero
+// halo of k-1 rows/columns on the top/left) in LDS and writes the un-negated
+// partial sums of all P = C*C*k*k entries to part[workgroup][P].  When P is
+// smaller than the block, G = block/P thread groups split the pixels and are
+// combined in a fixed order through LDS.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kDwBlock) void k_dw_partial(const float *__restrict__ x,
+                                                        const float *__restrict__ v,
+                                                        float *__restrict__ part,
+                                                        int C, int H, int W, int k, int RT, int nchunks)
+{
+    extern __shared__ float smem[];
+    const int n = blockIdx.x / nchunks, chunk = blockIdx.x % nchunks;
+    const int r0 = chunk * RT;
+    const int rows = (H - r0 < RT) ? H - r0 : RT;
+    const int XR = RT + k - 1, XW = W + k - 1;
+    const int P = C * C * k * k;
+    const int G = (P < kDwBlock) ? kDwBlock / P : 1;
+    float *sv = smem;                 // [C][RT][W]
+    float *sx = sv + C * RT * W;      // [C][XR][XW], origin at (r0-(k-1), -(k-1))
+    float *sred = sx + C * XR * XW;   // [G][P] when G > 1
+    const int tid = threadIdx.x;
+
+    for (int idx = tid; idx < C * rows * W; idx += kDwBlock) {
+        const int c = idx % W, r = (idx / W) % rows, ch = idx / (W * rows);
+        sv[(ch * RT + r) * W + c] = v[(((size_t)n * C + ch) * H + r0 + r) * W + c];
+    }
+    const int xrows = rows + k - 1;
+    for (int idx = tid; idx < C * xrows * XW; idx += kDwBlock) {
+        const int cc = idx % XW, rr = (idx / XW) % xrows, ch = idx / (XW * xrows);
+        const int gr = r0 - (k - 1) + rr, gc = cc - (k - 1);
+        sx[(ch * XR + rr) * XW + cc] =
+            (gr >= 0 && gc >= 0) ? x[(((size_t)n * C + ch) * H + gr) * W + gc] : 0.0f;
+    }
+    __syncthreads();
+
+    const int lanesE = (G > 1) ? P : kDwBlock;
+    const int s = tid / lanesE, e0 = tid % lanesE;
+    const int npix = rows * W;
+    if (s < G) {
+        for (int e = e0; e < P; e += lanesE) {
+            const int b = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
+            const float *pv = sv + o * RT * W;
+            const float *px = sx + (i * XR + a) * XW + b;
+            float acc = 0.0f;
+            for (int p = s; p < npix; p += G) {
+                const int r = p / W, c = p - r * W;
+                acc += pv[r * W + c] * px[r * XW + c];
+            }
+            if (G > 1)
+                sred[s * P + e] = acc;
+            else
+                part[(size_t)blockIdx.x * P + e] = acc;
+        }
+    }
+    if (G > 1) {
+        __syncthreads();
+        if (tid < P) {
+            float acc = 0.0f;
+            for (int g = 0; g < G; ++g)
+                acc += sred[g * P + tid];
+            part[(size_t)blockIdx.x * P + tid] = acc;
+        }
+    }
+}
+
+// Pass 2: one thread per kernel entry adds the partials in index order (double
+// accumulator), negates, and writes 0 at masked entries.  No atomics anywhere,
+// so dw is bitwise reproducible from run to run.
+__global__ __launch_bounds__(256) void k_dw_reduce(const float *__restrict__ part, int nparts,
+                                                  float *__restrict__ dw, int C, int k)
+{
+    const int P = C * C * k * k;
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= P)
+        return;
+    const int b = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
+    double acc = 0.0;
+    for (int p = 0; p < nparts; ++p)
+        acc += (double)part[(size_t)p * P + e];
+    const bool is_masked = (a == k - 1 && b == k - 1 && i > o);
+    dw[e] = is_masked ? 0.0f : (float)(-acc);
+}
+
+// log|det dx/dy| for one image (Section 4): -H*W*sum_c log|w[c][c][k-1][k-1]|.
+__global__ __launch_bounds__(64) void k_logdet(const float *__restrict__ w, int C, int H, int W, int k,
+                                              float *__restrict__ out)
+{
+    if (threadIdx.x == 0) {
+        double s = 0.0;
+        for (int c = 0; c < C; ++c)
+            s += log(fabs((double)w[((c * C + c) * k + (k - 1)) * k + (k - 1)]));
+        out[0] = (float)(-(double)H * (double)W * s);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host-side launchers
+// ---------------------------------------------------------------------------
+size_t solve_block_lds_bytes(int C, int H, int k)
+{
+    const size_t CP = (size_t)(C | 1), ND = 2 * (size_t)(k - 1) + 1;
+    return sizeof(float) * (2 * (size_t)C * C + (size_t)k * k * C * C + ND * H * CP);
+}
+
+template <int DIR>
+static int launch_solve_block_dir(const float *in, const float *w, float *out, int B, int C, int H, int W,
+                                  int k, hipStream_t stream)
+{
+    const size_t lds = solve_block_lds_bytes(C, H, k);
+    if (lds > kMaxLdsBytes)
+        return INVCONV_ERR_UNSUPPORTED;
+    if (lds > 48 * 1024) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_solve_block<DIR>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+            (void)hipGetLastError();
+            return INVCONV_ERR_UNSUPPORTED;
+        }
+    }
+    hipLaunchKernelGGL(k_solve_block<DIR>, dim3(B), dim3(kSolveBlock), lds, stream, in, w, out, C, H, W, k);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+int launch_solve_block(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W,
+                       int k, hipStream_t stream)
+{
+    return dir ? launch_solve_block_dir<1>(in, w, out, B, C, H, W, k, stream)
+               : launch_solve_block_dir<0>(in, w, out, B, C, H, W, k, stream);
+}
+
+int launch_solve_diag(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W,
+                      int k, hipStream_t stream)
+{
+    const int ndiag = H + W - 1;
+    for (int d = 0; d < ndiag; ++d) {
+        const int rlo = d - (W - 1) > 0 ? d - (W - 1) : 0;
+        const int rhi = d < H - 1 ? d : H - 1;
+        const long long items = (long long)B * (rhi - rlo + 1);
+        const int grid = (int)((items + 255) / 256);
+        if (dir)
+            hipLaunchKernelGGL(k_solve_one_diagonal<1>, dim3(grid), dim3(256), 0, stream, in, w, out, B, C,
+                               H, W, k, d);
+        else
+            hipLaunchKernelGGL(k_solve_one_diagonal<0>, dim3(grid), dim3(256), 0, stream, in, w, out, B, C,
+                               H, W, k, d);
+        if (hipGetLastError() != hipSuccess)
+            return INVCONV_ERR_LAUNCH;
+    }
+    return INVCONV_OK;
+}
+
+DwPlan plan_dw(int B, int C, int H, int W, int k)
+{
+    DwPlan p{};
+    const size_t P = (size_t)C * C * k * k;
+    const size_t G = P < (size_t)kDwBlock ? kDwBlock / P : 1;
+    const size_t red = G > 1 ? G * P : 0;
+    // largest row chunk whose tiles fit the LDS budget
+    auto lds_for = [&](int rt) {
+        return sizeof(float) * ((size_t)C * rt * W + (size_t)C * (rt + k - 1) * (W + k - 1) + red);
+    };
+    if (lds_for(1) > kDwLdsBudget)
+        return p;   // rt == 0: unsupported
+    int want = (int)((1024 + B - 1) / B);          // aim for about a thousand workgroups
+    if (want < 1) want = 1;
+    int rt = (H + want - 1) / want;
+    if (rt < 1) rt = 1;
+    while (rt > 1 && lds_for(rt) > kDwLdsBudget)
+        --rt;
+    p.rt = rt;
+    p.nchunks = (H + rt - 1) / rt;
+    p.nparts = (size_t)B * p.nchunks;
+    p.lds = lds_for(rt);
+    p.bytes = ((p.nparts * P * sizeof(float)) + 255) / 256 * 256;
+    return p;
+}
+
+int launch_dw(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
+              int W, int k, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_dw_partial, dim3((unsigned)p.nparts), dim3(kDwBlock), p.lds, stream, x, v, part, C, H,
+                       W, k, p.rt, p.nchunks);
+    if (hipGetLastError() != hipSuccess)
+        return INVCONV_ERR_LAUNCH;
+    const int P = C * C * k * k;
+    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 255) / 256), dim3(256), 0, stream, part, (int)p.nparts, dw, C, k);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+int launch_logdet(const float *w, int C, int H, int W, int k, float *out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_logdet, dim3(1), dim3(64), 0, stream, w, C, H, W, k, out);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+}  // namespace invconv

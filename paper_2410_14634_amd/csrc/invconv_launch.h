@@ -1,0 +1,33 @@
+// Host-side launch interface between the C ABI and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+#include "invconv.h"
+
+namespace invconv {
+
+constexpr int kSolveBlock = 256;
+constexpr int kDwBlock = 256;
+constexpr size_t kMaxLdsBytes = 160 * 1024;   // LDS per workgroup on gfx950
+constexpr size_t kDwLdsBudget = 64 * 1024;
+
+struct DwPlan {
+    int rt;          // rows per chunk (0 = shape unsupported)
+    int nchunks;     // chunks per image
+    size_t nparts;   // workgroups of pass 1 = rows of the partial-sum matrix
+    size_t lds;      // dynamic LDS bytes of pass 1
+    size_t bytes;    // workspace bytes
+};
+
+size_t solve_block_lds_bytes(int C, int H, int k);
+int launch_solve_block(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W,
+                       int k, hipStream_t stream);
+int launch_solve_diag(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W,
+                      int k, hipStream_t stream);
+DwPlan plan_dw(int B, int C, int H, int W, int k);
+int launch_dw(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
+              int W, int k, hipStream_t stream);
+int launch_logdet(const float *w, int C, int H, int W, int k, float *out, hipStream_t stream);
+
+}  // namespace invconv

@@ -1,0 +1,78 @@
+"""Host-only checks of the C ABI: the library loads, exports what the header declares,
+and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2410_14634_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = [0x10000 * (i + 1) for i in range(8)]   # never dereferenced: every call below must fail validation
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "invconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(invconv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = b.lib()
+    names = declared_functions()
+    assert set(names) == set(b.EXPORTS)
+    for name in names:
+        assert getattr(L, name) is not None
+    assert b.version() >= 100
+
+
+def test_status_strings():
+    seen = {b.status_string(s) for s in range(0, -8, -1)}
+    assert len(seen) == 8 and b.status_string(-99) == "unknown status"
+
+
+def test_fwd_rejects_bad_arguments():
+    L = b.lib()
+    y, w, x = FAKE[:3]
+    assert L.invconv_fwd(None, w, x, 1, 1, 4, 4, 3, None) == b.ERR_NULL
+    assert L.invconv_fwd(y, None, x, 1, 1, 4, 4, 3, None) == b.ERR_NULL
+    assert L.invconv_fwd(y, w, None, 1, 1, 4, 4, 3, None) == b.ERR_NULL
+    for bad in [(0, 1, 4, 4, 3), (1, 0, 4, 4, 3), (1, 1, 0, 4, 3), (1, 1, 4, 0, 3), (1, 1, 4, 4, 0),
+                (-1, 1, 4, 4, 3), (2 ** 20, 64, 64, 64, 3)]:
+        assert L.invconv_fwd(y, w, x, *bad, None) == b.ERR_SHAPE
+    assert L.invconv_fwd(y, w, y, 1, 1, 4, 4, 3, None) == b.ERR_ALIAS
+    assert L.invconv_fwd_ex(y, w, x, 1, 1, 4, 4, 3, None, 99) == b.ERR_VARIANT
+    # on-chip buffers too small for this shape
+    assert L.invconv_fwd(y, w, x, 1, 64, 4096, 4096, 11, None) == b.ERR_UNSUPPORTED
+
+
+def test_bwd_rejects_bad_arguments():
+    L = b.lib()
+    x, w, g, v, dw, ws = FAKE[:6]
+    shape = (2, 3, 8, 8, 3)
+    need = b.bwd_workspace_bytes(*shape)
+    assert need > 0 and need % 256 == 0
+    assert L.invconv_bwd(None, w, g, v, dw, *shape, ws, need, None) == b.ERR_NULL
+    assert L.invconv_bwd(x, w, g, None, dw, *shape, ws, need, None) == b.ERR_NULL
+    assert L.invconv_bwd(x, w, g, v, None, *shape, ws, need, None) == b.ERR_NULL
+    assert L.invconv_bwd(x, w, g, v, dw, 2, 3, 8, 8, 0, ws, need, None) == b.ERR_SHAPE
+    assert L.invconv_bwd(x, w, g, g, dw, *shape, ws, need, None) == b.ERR_ALIAS
+    assert L.invconv_bwd(x, w, g, x, dw, *shape, ws, need, None) == b.ERR_ALIAS
+    assert L.invconv_bwd(x, w, g, v, dw, *shape, None, need, None) == b.ERR_WORKSPACE
+    assert L.invconv_bwd(x, w, g, v, dw, *shape, ws, need - 1, None) == b.ERR_WORKSPACE
+    assert L.invconv_bwd_ex(x, w, g, v, dw, *shape, ws, need, None, -1) == b.ERR_VARIANT
+    assert b.bwd_workspace_bytes(0, 3, 8, 8, 3) == 0
+
+
+def test_logdet_rejects_bad_arguments():
+    L = b.lib()
+    assert L.invconv_logdet(None, 3, 8, 8, 3, FAKE[0], None) == b.ERR_NULL
+    assert L.invconv_logdet(FAKE[0], 3, 8, 8, 3, None, None) == b.ERR_NULL
+    assert L.invconv_logdet(FAKE[0], 0, 8, 8, 3, FAKE[1], None) == b.ERR_SHAPE
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        b.invconv_fwd(torch.zeros(1, 1, 4, 4), torch.zeros(1, 1, 3, 3))
