@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the inverse-convolution hot path on one MI355X.
+
+One "step" = invconv_fwd + invconv_bwd + invconv_logdet over one batch of the
+headline workload (B=16, C=3, 32x32, k=3, fp32), inputs resident in HBM.
+Prints ONE JSON line with images/s, the roofline figures of the dominant
+kernel (timed live with HIP events on the launch stream) and the CPU oracle
+timed on the host cores as a baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1] [--all]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", type=int, default=1, help="workload id 0..4 (1 = headline)")
+    ap.add_argument("--all", action="store_true", help="also time workloads 0..4 (reported under 'workloads')")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--variant", type=int, default=0)
+    return ap.parse_args()
+
+
+class Layered:
+    """Device buffers and raw-pointer launch closures for one workload (all layers)."""
+
+    def __init__(self, cfg: int, variant: int = 0):
+        import torch
+        from paper_2410_14634_amd import binding as b
+        from paper_2410_14634_amd import inputs
+        self.b = b
+        self.torch = torch
+        wl = inputs.make_workload(cfg)
+        self.wl = wl
+        self.cfg = cfg
+        self.variant = variant
+        self.B, self.C, self.H, self.W, self.k, self.L = (wl[n] for n in ("B", "C", "H", "W", "k", "layers"))
+        self.ws_d = [torch.from_numpy(w).cuda() for w in wl["w"]]
+        self.acts = [torch.from_numpy(wl["y"]).cuda()] + [torch.empty(wl["y"].shape, device="cuda")
+                                                          for _ in range(self.L)]
+        self.g0 = torch.from_numpy(wl["g"]).cuda()
+        # gradient ping-pong buffers (dL/dy of layer l is dL/dx of layer l-1)
+        self.grads = [torch.empty_like(self.g0) for _ in range(2)]
+        self.dws = [torch.empty_like(w) for w in self.ws_d]
+        self.lds = torch.empty(self.L, device="cuda")
+        need = b.bwd_workspace_bytes(self.B, self.C, self.H, self.W, self.k)
+        self.wsp = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        self.need = need
+        self.lib = b.lib()
+        self.n_elems = self.B * self.C * self.H * self.W
+
+    # raw C-ABI calls: pointers and sizes only
+    def fwd_layer(self, l, stream):
+        st = self.lib.invconv_fwd_ex(self.acts[l].data_ptr(), self.ws_d[l].data_ptr(), self.acts[l + 1].data_ptr(),
+                                     self.B, self.C, self.H, self.W, self.k, stream, self.variant)
+        assert st == 0, self.b.status_string(st)
+
+    def bwd_layer(self, l, gin, gout, stream):
+        st = self.lib.invconv_bwd_ex(self.acts[l + 1].data_ptr(), self.ws_d[l].data_ptr(), gin.data_ptr(),
+                                     gout.data_ptr(), self.dws[l].data_ptr(), self.B, self.C, self.H, self.W,
+                                     self.k, self.wsp.data_ptr(), self.need, stream, self.variant)
+        assert st == 0, self.b.status_string(st)
+
+    def logdet_layer(self, l, stream):
+        st = self.lib.invconv_logdet(self.ws_d[l].data_ptr(), self.C, self.H, self.W, self.k,
+                                     self.lds[l:l + 1].data_ptr(), stream)
+        assert st == 0, self.b.status_string(st)
+
+    def fwd_all(self, stream):
+        for l in range(self.L):
+            self.fwd_layer(l, stream)
+
+    def bwd_all(self, stream):
+        # single layer: upstream gradient is the seeded dL/dx; chain: dL/dx_L = x_L (loss 0.5*sum x^2)
+        gin = self.g0 if self.L == 1 else self.acts[self.L]
+        for i, l in enumerate(reversed(range(self.L))):
+            gout = self.grads[i % 2]
+            self.bwd_layer(l, gin, gout, stream)
+            gin = gout
+
+    def logdet_all(self, stream):
+        for l in range(self.L):
+            self.logdet_layer(l, stream)
+
+    def step(self, stream):
+        self.fwd_all(stream)
+        self.bwd_all(stream)
+        self.logdet_all(stream)
+
+
+def time_region(torch, fn, reps, warmup):
+    """Wall-clock of `reps` calls bracketed by device synchronisation; returns ms per call."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / reps
+
+
+def event_time(torch, fn, reps, warmup):
+    """Median / mean ms of single calls, each bracketed by HIP events on the launch stream."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for e0, e1 in evs:
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    ts = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    return ts[len(ts) // 2], sum(ts) / len(ts), ts[0]
+
+
+def event_time_batch(torch, fn, reps, warmup):
+    """Mean ms per call of `reps` back-to-back calls between one pair of HIP events."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def measure_workload(cfg, steps, warmup, variant=0):
+    import torch
+    L = Layered(cfg, variant)
+    stream = torch.cuda.current_stream().cuda_stream
+    ms_step = time_region(torch, lambda: L.step(stream), steps, warmup)
+    ms_fwd = event_time_batch(torch, lambda: L.fwd_all(stream), max(steps // 4, 5), 3)
+    ms_bwd = event_time_batch(torch, lambda: L.bwd_all(stream), max(steps // 4, 5), 3)
+    bytes_step = 20.0 * L.n_elems * L.L
+    return L, dict(
+        workload=cfg, B=L.B, C=L.C, H=L.H, W=L.W, k=L.k, layers=L.L,
+        ms_per_step=ms_step, ms_fwd=ms_fwd, ms_bwd=ms_bwd,
+        images_per_s=L.B / (ms_step * 1e-3),
+        us_per_diagonal=(ms_fwd + ms_bwd) * 1e3 / (2 * L.L * (L.H + L.W - 1)),
+        algorithmic_gbs=bytes_step / (ms_step * 1e-3) / 1e9,
+        hbm_frac=bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+    )
+
+
+def cpu_baseline(cfg, seconds):
+    """The CPU oracle, as it stands, on the same workload (bounded sample), all host cores."""
+    import oracle
+    from paper_2410_14634_amd import inputs
+    wl = inputs.make_workload(cfg)
+    layers = wl["layers"]
+    B = wl["B"]
+    sample = f"workload {cfg}, full batch of {B}, fwd+bwd+logdet"
+    if cfg == 4:       # chain is ~15 GMAC per pass on the CPU: time a slice of the batch, one pass
+        B = 4
+        wl = inputs.make_workload(cfg, B=B)
+        sample = f"workload {cfg}, {B} of 32 images, all {layers} layers, fwd+bwd+logdet, one pass"
+    threads = oracle.max_threads()
+
+    def one_pass():
+        xs = [wl["y"]]
+        for w in wl["w"]:
+            xs.append(oracle.invconv_fwd(xs[-1], w, threads))
+        g = wl["g"] if layers == 1 else xs[-1]
+        for l in reversed(range(layers)):
+            g, _ = oracle.invconv_bwd(xs[l + 1], wl["w"][l], g, threads)
+            oracle.invconv_logdet(wl["w"][l], wl["H"], wl["W"])
+
+    one_pass()
+    n, t0 = 0, time.perf_counter()
+    while True:
+        one_pass()
+        n += 1
+        el = time.perf_counter() - t0
+        if el >= seconds or (cfg == 4 and n >= 1):
+            break
+    return dict(value=B * n / el, unit="images/s", cores=threads, kind="oracle",
+                sample=f"{sample}; {n} passes in {el:.1f} s")
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (every image is an independent solve, so more GPUs "
+              "would each take a slice of the batch); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2410_14634_amd import binding as b
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    b.lib()   # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    cfg = args.workload
+    L, res = measure_workload(cfg, args.steps, args.warmup, args.variant)
+
+    # dominant kernel: the wavefront solve (forward orientation), one launch per call of invconv_fwd
+    stream = torch.cuda.current_stream().cuda_stream
+    reps = max(min(args.steps, 500), 20)
+    k_med, k_mean, k_min = event_time(torch, lambda: L.fwd_layer(0, stream), reps, 20)
+    k_batch = event_time_batch(torch, lambda: L.fwd_layer(0, stream), reps, 20)
+    kernel_bytes = 8.0 * L.n_elems                       # read y, write x
+    kernel_ms = k_batch
+    achieved = kernel_bytes / (kernel_ms * 1e-3) / 1e9
+    roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
+                    traffic=None, kernel="k_solve_block<0> (wavefront solve, forward orientation)",
+                    kernel_ms_back_to_back=k_batch, kernel_ms_event_pair_median=k_med,
+                    kernel_ms_event_pair_min=k_min, algorithmic_bytes_per_launch=kernel_bytes,
+                    dependent_steps=L.H + L.W - 1,
+                    us_per_dependent_step=kernel_ms * 1e3 / (L.H + L.W - 1))
+
+    out = dict(
+        metric="inverse-conv fwd+bwd images/sec at m=32,C=3,k=3; achieved HBM GB/s fraction",
+        value=res["images_per_s"], unit="images/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+        ms_per_step=res["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None,
+        dtype="f32", data="synthetic",
+        config=dict(workload=f"workload {cfg}: B={L.B} C={L.C} H=W={L.H} k={L.k} layers={L.L}, "
+                             "step = invconv_fwd + invconv_bwd + invconv_logdet, eager launches on one stream",
+                    variant=args.variant),
+        ms_fwd=res["ms_fwd"], ms_bwd=res["ms_bwd"], algorithmic_gbs=res["algorithmic_gbs"],
+        hbm_frac_whole_step=res["hbm_frac"],
+        roofline=roofline,
+    )
+    if args.all:
+        others = {}
+        for c in range(5):
+            if c == cfg:
+                others[str(c)] = res
+                continue
+            st = {0: args.steps, 1: args.steps, 2: max(args.steps // 2, 10), 3: max(args.steps // 4, 10),
+                  4: max(args.steps // 100, 5)}[c]
+            _, r = measure_workload(c, st, max(st // 10, 2), args.variant)
+            others[str(c)] = r
+            print(f"[bench] workload {c}: {json.dumps(r)}", file=sys.stderr, flush=True)
+        out["workloads"] = others
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -51,7 +51,8 @@ enum {
 enum {
     INVCONV_VARIANT_AUTO = 0,
     INVCONV_VARIANT_BLOCK = 1,    /* one workgroup per image, LDS window, one barrier per anti-diagonal */
-    INVCONV_VARIANT_DIAG_LAUNCH = 2 /* one kernel launch per anti-diagonal (capture it in a hipGraph) */
+    INVCONV_VARIANT_DIAG_LAUNCH = 2, /* one kernel launch per anti-diagonal (capture it in a hipGraph) */
+    INVCONV_VARIANT_WAVE = 3      /* one wave per image, lane = row, register/DPP systolic solve (C <= 4, H <= 64) */
 };
 
 /*

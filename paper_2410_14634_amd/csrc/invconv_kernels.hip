@@ -167,22 +167,29 @@ __global__ __launch_bounds__(kDwBlock) void k_dw_partial(const float *__restrict
     }
 }
 
-// Pass 2: one thread per kernel entry adds the partials in index order (double
-// accumulator), negates, and writes 0 at masked entries.  No atomics anywhere,
-// so dw is bitwise reproducible from run to run.
+// Pass 2: one wave per kernel entry.  Lane l adds partial rows l, l+64, ... in
+// index order (double accumulator), the 64 lane sums are combined by a fixed
+// butterfly, the result is negated, and masked entries are written as 0.  No
+// atomics anywhere, so dw is bitwise reproducible from run to run.
 __global__ __launch_bounds__(256) void k_dw_reduce(const float *__restrict__ part, int nparts,
                                                   float *__restrict__ dw, int C, int k)
 {
     const int P = C * C * k * k;
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    const int e = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     if (e >= P)
         return;
-    const int b = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
     double acc = 0.0;
-    for (int p = 0; p < nparts; ++p)
+    for (int p = lane; p < nparts; p += 64)
         acc += (double)part[(size_t)p * P + e];
-    const bool is_masked = (a == k - 1 && b == k - 1 && i > o);
-    dw[e] = is_masked ? 0.0f : (float)(-acc);
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1)
+        acc += __shfl_xor(acc, m, 64);
+    if (lane == 0) {
+        const int b = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
+        const bool is_masked = (a == k - 1 && b == k - 1 && i > o);
+        dw[e] = is_masked ? 0.0f : (float)(-acc);
+    }
 }
 
 // log|det dx/dy| for one image (Section 4): -H*W*sum_c log|w[c][c][k-1][k-1]|.
@@ -286,7 +293,7 @@ int launch_dw(const float *x, const float *v, float *dw, float *part, const DwPl
     if (hipGetLastError() != hipSuccess)
         return INVCONV_ERR_LAUNCH;
     const int P = C * C * k * k;
-    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 255) / 256), dim3(256), 0, stream, part, (int)p.nparts, dw, C, k);
+    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 3) / 4), dim3(256), 0, stream, part, (int)p.nparts, dw, C, k);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

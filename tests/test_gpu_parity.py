@@ -10,7 +10,8 @@ from tests.util import THREADS, TOL_ACT, TOL_DW, dev, elementwise_ok, host, rel_
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [b.VARIANT_AUTO, b.VARIANT_BLOCK, b.VARIANT_DIAG_LAUNCH]
+VARIANTS = [b.VARIANT_AUTO, b.VARIANT_BLOCK, b.VARIANT_DIAG_LAUNCH, b.VARIANT_WAVE]
+WAVE_OK = {0, 1, 3}     # workloads the wave-per-image variant covers (C <= 4, H <= 64)
 
 
 def run_layer(y, w, g, variant=b.VARIANT_AUTO):
@@ -40,6 +41,8 @@ def check_layer(y, w, g, variant=b.VARIANT_AUTO):
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3])
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_workload_parity(cfg, variant):
+    if variant == b.VARIANT_WAVE and cfg not in WAVE_OK:
+        pytest.skip("variant does not cover this shape")
     wl = inputs.make_workload(cfg)
     print(f"cfg {cfg} variant {variant}", flush=True)
     print(check_layer(wl["y"], wl["w"][0], wl["g"], variant), flush=True)
@@ -54,6 +57,7 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     (1, 1, 1, 1, 1), (1, 1, 1, 1, 3), (2, 1, 5, 5, 2), (3, 2, 7, 13, 3), (2, 3, 13, 7, 3),
     (1, 4, 1, 40, 3), (1, 4, 40, 1, 3), (2, 3, 2, 2, 5), (1, 5, 9, 11, 4), (2, 16, 10, 10, 3),
     (1, 3, 70, 33, 3), (5, 2, 33, 70, 5), (1, 1, 100, 100, 7), (2, 7, 17, 19, 1),
+    (2, 3, 64, 5, 3), (3, 1, 33, 20, 3), (1, 2, 64, 64, 3), (2, 4, 63, 9, 3), (1, 3, 5, 100, 5),
 ]
 
 
