@@ -102,6 +102,11 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
     if (!workspace || workspace_bytes < p.bytes)
         return INVCONV_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
+    if ((variant == INVCONV_VARIANT_AUTO || variant == INVCONV_VARIANT_WAVE) && bwd_wave_supported(C, H, W, k)) {
+        if (int s = launch_bwd_wave(x, w, dLdx, dLdy, (float *)workspace, B, C, H, W, k, st))
+            return s;
+        return launch_dw_reduce((const float *)workspace, B, dLdw, C, k, st);
+    }
     if (int s = solve(1, dLdx, w, dLdy, B, C, H, W, k, st, variant))
         return s;
     return launch_dw(x, dLdy, dLdw, (float *)workspace, p, B, C, H, W, k, st);

@@ -193,15 +193,18 @@ __global__ __launch_bounds__(256) void k_dw_reduce(const float *__restrict__ par
 }
 
 // log|det dx/dy| for one image (Section 4): -H*W*sum_c log|w[c][c][k-1][k-1]|.
+// One wave; lane l takes channels l, l+64, ...; fixed butterfly across lanes.
 __global__ __launch_bounds__(64) void k_logdet(const float *__restrict__ w, int C, int H, int W, int k,
                                               float *__restrict__ out)
 {
-    if (threadIdx.x == 0) {
-        double s = 0.0;
-        for (int c = 0; c < C; ++c)
-            s += log(fabs((double)w[((c * C + c) * k + (k - 1)) * k + (k - 1)]));
+    double s = 0.0;
+    for (int c = threadIdx.x; c < C; c += 64)
+        s += log(fabs((double)w[((c * C + c) * k + (k - 1)) * k + (k - 1)]));
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1)
+        s += __shfl_xor(s, m, 64);
+    if (threadIdx.x == 0)
         out[0] = (float)(-(double)H * (double)W * s);
-    }
 }
 
 // ---------------------------------------------------------------------------
@@ -281,7 +284,8 @@ DwPlan plan_dw(int B, int C, int H, int W, int k)
     p.nchunks = (H + rt - 1) / rt;
     p.nparts = (size_t)B * p.nchunks;
     p.lds = lds_for(rt);
-    p.bytes = ((p.nparts * P * sizeof(float)) + 255) / 256 * 256;
+    const size_t rows = p.nparts > (size_t)B ? p.nparts : (size_t)B;   // the fused path writes one row per image
+    p.bytes = ((rows * P * sizeof(float)) + 255) / 256 * 256;
     return p;
 }
 
@@ -292,8 +296,13 @@ int launch_dw(const float *x, const float *v, float *dw, float *part, const DwPl
                        W, k, p.rt, p.nchunks);
     if (hipGetLastError() != hipSuccess)
         return INVCONV_ERR_LAUNCH;
+    return launch_dw_reduce(part, (int)p.nparts, dw, C, k, stream);
+}
+
+int launch_dw_reduce(const float *part, int nparts, float *dw, int C, int k, hipStream_t stream)
+{
     const int P = C * C * k * k;
-    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 3) / 4), dim3(256), 0, stream, part, (int)p.nparts, dw, C, k);
+    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 3) / 4), dim3(256), 0, stream, part, nparts, dw, C, k);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

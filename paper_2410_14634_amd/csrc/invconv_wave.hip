@@ -35,19 +35,18 @@ __device__ __forceinline__ float from_lane_above(float v)
 
 constexpr int kWavePF = 16;   // steps of load prefetch
 
-template <int C, int K, int DIR>
-__global__ __launch_bounds__(64) void k_solve_wave(const float *__restrict__ in, const float *__restrict__ w,
-                                                  float *__restrict__ out, int H, int W)
+// Body of the solve for image n, executed by one full wave (lanes 0..63 of the
+// calling workgroup).  With LDS_COPY the result is also written to lds_copy as a
+// [C][H][W] tile in image (not mirrored) coordinates.
+template <int C, int K, int DIR, bool LDS_COPY>
+__device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, const float *__restrict__ w,
+                                                float *__restrict__ out, int H, int W, int n, float *lds_copy)
 {
     static_assert(C >= 1 && C <= 4, "one 4-row MFMA block per pixel");
-    __shared__ float sL[C * C], sLinv[C * C], sCf[K * K * C * C];
-    __shared__ float sA[K * K * C * 4];   // -Cf[tp][o][i] stored as [tp][i][o padded to 4]
-    __shared__ float sLi[C * 4];          // Linv[o][j] stored as [j][o padded to 4]
-
     // All 64 lanes stay active to the end: the matrix instruction reads its weight
     // operand from every lane of a 4-lane block, whatever the execution mask says.
     // Lanes past the last row compute on clamped inputs and never store.
-    const int r = threadIdx.x;
+    const int r = threadIdx.x & 63;
     const bool row_ok = r < H;
     const int rr = row_ok ? r : H - 1;
     const int o_lane = r & 3;
@@ -56,14 +55,16 @@ __global__ __launch_bounds__(64) void k_solve_wave(const float *__restrict__ in,
     // Element (ch, r, c) of this image, in solve coordinates, sits at
     // chan[ch] (uniform pointer) + rowoff (per lane) +- 4c bytes: one 32-bit lane
     // offset serves all channels, the addressing form global loads take directly.
-    const size_t img = (size_t)blockIdx.x * C * H * W;
+    const size_t img = (size_t)n * C * H * W;
     const char *chan_src[C];
     char *chan_dst[C];
+    char *chan_lds[C];
 #pragma unroll
     for (int ch = 0; ch < C; ++ch) {
-        const size_t cb = img + (size_t)(DIR ? C - 1 - ch : ch) * H * W;
-        chan_src[ch] = reinterpret_cast<const char *>(in + cb);
-        chan_dst[ch] = reinterpret_cast<char *>(out + cb);
+        const size_t cb = (size_t)(DIR ? C - 1 - ch : ch) * H * W;
+        chan_src[ch] = reinterpret_cast<const char *>(in + img + cb);
+        chan_dst[ch] = reinterpret_cast<char *>(out + img + cb);
+        chan_lds[ch] = reinterpret_cast<char *>(lds_copy + cb);
     }
     constexpr int kStep = DIR ? -4 : 4;               // bytes per column in solve order
     const int row0 = 4 * (DIR ? (H - 1 - rr) * W + (W - 1) : rr * W);   // byte offset of column 0
@@ -71,7 +72,11 @@ __global__ __launch_bounds__(64) void k_solve_wave(const float *__restrict__ in,
     const int rowhi = DIR ? row0 : row0 + 4 * (W - 1);                   // inside this row
     auto clamp_row = [&](int off) -> unsigned { return (unsigned)(off < rowlo ? rowlo : (off > rowhi ? rowhi : off)); };
     auto ld = [&](int ch, unsigned off) -> float { return *reinterpret_cast<const float *>(chan_src[ch] + off); };
-    auto st = [&](int ch, unsigned off, float v) { *reinterpret_cast<float *>(chan_dst[ch] + off) = v; };
+    auto st = [&](int ch, unsigned off, float v) {
+        *reinterpret_cast<float *>(chan_dst[ch] + off) = v;
+        if (LDS_COPY)
+            *reinterpret_cast<float *>(chan_lds[ch] + off) = v;
+    };
 
     // Loads are unconditional (offset clamped into the row) so that they stay in
     // flight for kWavePF steps without the compiler having to assume the worst at
@@ -87,30 +92,62 @@ __global__ __launch_bounds__(64) void k_solve_wave(const float *__restrict__ in,
             yb[u][ch] = ld(ch, off);
     }
 
-    fold_weights<DIR>(w, C, K, sL, sLinv, sCf);
-    for (int idx = threadIdx.x; idx < K * K * C * 4; idx += 64) {
-        const int o = idx & 3, i = (idx >> 2) % C, tp = idx / (4 * C);
-        sA[idx] = (o < C) ? -sCf[(tp * C + o) * C + i] : 0.0f;
-    }
-    for (int idx = threadIdx.x; idx < C * 4; idx += 64) {
-        const int o = idx & 3, j = idx >> 2;
-        sLi[idx] = (o < C) ? sLinv[o * C + j] : 0.0f;
-    }
-    __syncthreads();
-
-    // MFMA A operands (lane holds the entry of output channel o = lane%4, 0 for o >= C):
-    // wA[a][db][i] = -Cf[a,db][o][i], wLi[j] = Linv[o][j]
+    // Weight preparation in registers, by every lane for itself (the kernel reads w
+    // with uniform addresses only): Linv = inverse of the lower-triangular
+    // current-pixel block; the lane keeps row o = lane%4 of it (zeros for o >= C) and
+    // folds it into every other tap.  MFMA A operands of this lane:
+    //   wLi[j] = Linv[o][j],   wA[a][db][i] = -(Linv W_tap)[o][i] for tap (a,db) up/left.
     float wA[K][K][C], wLi[C];
+    {
+        float Lm[C][C], Li[C][C], rd[C];
 #pragma unroll
-    for (int a = 0; a < K; ++a)
-#pragma unroll
-        for (int db = 0; db < K; ++db)
+        for (int o = 0; o < C; ++o)
 #pragma unroll
             for (int i = 0; i < C; ++i)
-                wA[a][db][i] = sA[((a * K + db) * C + i) * 4 + o_lane];
+                Lm[o][i] = weff<DIR>(w, C, K, o, i, K - 1, K - 1);
 #pragma unroll
-    for (int j = 0; j < C; ++j)
-        wLi[j] = sLi[j * 4 + o_lane];
+        for (int o = 0; o < C; ++o)
+            rd[o] = 1.0f / Lm[o][o];
+#pragma unroll
+        for (int j = 0; j < C; ++j) {
+#pragma unroll
+            for (int o = 0; o < C; ++o) {
+                if (o < j) {
+                    Li[o][j] = 0.0f;
+                } else if (o == j) {
+                    Li[o][j] = rd[j];
+                } else {
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int m = j; m < o; ++m)
+                        sum += Lm[o][m] * Li[m][j];
+                    Li[o][j] = -sum * rd[o];
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < C; ++j) {
+            float v = 0.0f;
+#pragma unroll
+            for (int o = 0; o < C; ++o)
+                v = (o_lane == o) ? Li[o][j] : v;
+            wLi[j] = v;
+        }
+#pragma unroll
+        for (int a = 0; a < K; ++a)
+#pragma unroll
+            for (int db = 0; db < K; ++db)
+#pragma unroll
+                for (int i = 0; i < C; ++i) {
+                    float sum = 0.0f;
+                    if (a != 0 || db != 0) {
+#pragma unroll
+                        for (int j = 0; j < C; ++j)
+                            sum += wLi[j] * weff<DIR>(w, C, K, j, i, K - 1 - a, K - 1 - db);
+                    }
+                    wA[a][db][i] = -sum;
+                }
+    }
 
     float xh[C][K];      // xh[i][db] = x(r, c-db), db >= 1
     f32x4 T[K];          // T[a][o], a >= 1: message for pixel (r+a, c), negated sums
@@ -214,6 +251,102 @@ __global__ __launch_bounds__(64) void k_solve_wave(const float *__restrict__ in,
     }
 }
 
+template <int C, int K, int DIR>
+__global__ __launch_bounds__(64) void k_solve_wave(const float *__restrict__ in, const float *__restrict__ w,
+                                                  float *__restrict__ out, int H, int W)
+{
+    solve_wave_body<C, K, DIR, false>(in, w, out, H, W, blockIdx.x, nullptr);
+}
+
+// ---------------------------------------------------------------------------
+// Backward pass of one image in one workgroup of four waves (Section 3.1-3.3).
+//   wave 0      transposed solve v = dL/dy (mirrored orientation), written to
+//               global memory and to an LDS tile;
+//   waves 1..3  meanwhile stage the image's x, with a zero halo of K-1 rows and
+//               columns on the top/left, in LDS;
+//   all waves   then form the image's share of the weight gradient (Eq. 4 with
+//               Theorem 2), sum_p v[o][p] * x[i][p - tap], as outer products on the
+//               matrix cores: v_mfma_f32_4x4x1 has 16 independent 4x4 blocks, block b
+//               takes pixel 16q+b, its A operand is v[o = lane%4] of that pixel and
+//               its B operand four of the C*K*K shifted-x columns.  The 16 block
+//               accumulators of the four waves are added in a fixed order through LDS.
+// Output: part[n][P] un-negated; a second kernel adds the images in index order.
+// ---------------------------------------------------------------------------
+template <int C, int K>
+__global__ __launch_bounds__(256) void k_bwd_wave(const float *__restrict__ x, const float *__restrict__ w,
+                                                 const float *__restrict__ g, float *__restrict__ v,
+                                                 float *__restrict__ part, int H, int W)
+{
+    extern __shared__ float smem[];
+    constexpr int NCOL = C * K * K;            // shifted-x columns (i, a, b)
+    constexpr int NS = (NCOL + 3) / 4;         // groups of four columns
+    constexpr int P = C * NCOL;
+    const int XR = H + K - 1, XW = W + K - 1;
+    float *sv = smem;                          // [C][H][W]
+    float *sx = sv + C * H * W;                // [C][XR][XW], origin at (-(K-1), -(K-1))
+    float *sred = smem;                        // [4*64][NS*4], reuses the tiles after the products
+    const int n = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+
+    if (wave == 0) {
+        solve_wave_body<C, K, 1, true>(g, w, v, H, W, n, sv);
+    } else {
+        const float *xi = x + (size_t)n * C * H * W;
+        for (int idx = tid - 64; idx < C * XR * XW; idx += 192) {
+            const int cc = idx % XW, rr = (idx / XW) % XR, ch = idx / (XW * XR);
+            const int gr = rr - (K - 1), gc = cc - (K - 1);
+            sx[idx] = (gr >= 0 && gc >= 0) ? xi[(ch * H + gr) * W + gc] : 0.0f;
+        }
+    }
+    __syncthreads();
+
+    // lane = (block b, j): A row o = j, B column 4s + j.  Rows o >= C and columns
+    // >= NCOL are padding: they read valid data (row/column 0) and their results
+    // are never used.
+    const int j = lane & 3, b = lane >> 2;
+    const int aoff = (j < C) ? j * H * W : 0;
+    int boff[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const int col = (4 * s + j < NCOL) ? 4 * s + j : 0;
+        const int i = col / (K * K), a = (col / K) % K, bb = col % K;
+        boff[s] = (i * XR + a) * XW + bb;
+    }
+    f32x4 acc[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int npix = H * W;
+    const int ngroups = (npix + 15) / 16;
+    for (int q = wave; q < ngroups; q += 4) {
+        const int p = q * 16 + b;
+        const bool pv = p < npix;
+        const int pr = pv ? p / W : 0, pc = pv ? p - pr * W : 0;
+        const float avl = sv[aoff + pr * W + pc];
+        const float av = pv ? avl : 0.0f;       // pixels past the end contribute nothing
+        const float *bp = sx + pr * XW + pc;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            acc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(av, bp[boff[s]], acc[s], 0, 0, 0);
+    }
+    __syncthreads();        // tiles no longer needed: reuse them for the reduction
+    // lane (b, j) register (s, o) holds block b's partial of entry (o, col = 4s + j)
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int o = 0; o < 4; ++o)
+            sred[tid * (NS * 4) + s * 4 + o] = acc[s][o];
+    __syncthreads();
+    for (int e = tid; e < P; e += 256) {
+        const int o = e / NCOL, col = e % NCOL;
+        const int s = col >> 2, jj = col & 3;
+        float sum = 0.0f;
+        for (int wv = 0; wv < 4; ++wv)
+            for (int bb = 0; bb < 16; ++bb)
+                sum += sred[(wv * 64 + bb * 4 + jj) * (NS * 4) + s * 4 + o];
+        part[(size_t)n * P + e] = sum;
+    }
+}
+
 template <int C, int K>
 static int launch_wave_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
                           hipStream_t stream)
@@ -223,6 +356,47 @@ static int launch_wave_ck(int dir, const float *in, const float *w, float *out, 
     else
         hipLaunchKernelGGL((k_solve_wave<C, K, 0>), dim3(B), dim3(64), 0, stream, in, w, out, H, W);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+size_t bwd_wave_lds_bytes(int C, int H, int W, int k)
+{
+    const size_t tiles = (size_t)C * H * W + (size_t)C * (H + k - 1) * (W + k - 1);
+    const size_t red = 256 * (size_t)((C * k * k + 3) / 4) * 4;
+    return sizeof(float) * (tiles > red ? tiles : red);
+}
+
+template <int C, int K>
+static int launch_bwd_wave_ck(const float *x, const float *w, const float *g, float *v, float *part, int B, int H,
+                              int W, hipStream_t stream)
+{
+    const size_t lds = bwd_wave_lds_bytes(C, H, W, K);
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_wave<C, K>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+        (void)hipGetLastError();
+        return INVCONV_ERR_UNSUPPORTED;
+    }
+    hipLaunchKernelGGL((k_bwd_wave<C, K>), dim3(B), dim3(256), lds, stream, x, w, g, v, part, H, W);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+bool bwd_wave_supported(int C, int H, int W, int k)
+{
+    return wave_supported(C, H, k) && bwd_wave_lds_bytes(C, H, W, k) <= kMaxLdsBytes;
+}
+
+// dL/dy and the per-image partial sums of dL/dw (part[B][C*C*k*k], un-negated) in one launch.
+int launch_bwd_wave(const float *x, const float *w, const float *g, float *v, float *part, int B, int C, int H,
+                    int W, int k, hipStream_t stream)
+{
+    if (!bwd_wave_supported(C, H, W, k))
+        return INVCONV_ERR_VARIANT;
+    if (C == 3 && k == 3) return launch_bwd_wave_ck<3, 3>(x, w, g, v, part, B, H, W, stream);
+    if (C == 3 && k == 5) return launch_bwd_wave_ck<3, 5>(x, w, g, v, part, B, H, W, stream);
+    if (C == 1 && k == 3) return launch_bwd_wave_ck<1, 3>(x, w, g, v, part, B, H, W, stream);
+    if (C == 2 && k == 3) return launch_bwd_wave_ck<2, 3>(x, w, g, v, part, B, H, W, stream);
+    if (C == 4 && k == 3) return launch_bwd_wave_ck<4, 3>(x, w, g, v, part, B, H, W, stream);
+    return INVCONV_ERR_VARIANT;
 }
 
 bool wave_supported(int C, int H, int k)
