@@ -1,0 +1,286 @@
+// Band-systolic wavefront solve for C = 8, 12 or 16 channels on the matrix
+// cores (v_mfma_f32_16x16x4_f32).  gfx950 only.
+//
+// A wave owns a band of 16 image rows.  Lane (n, g) = (lane % 16, lane / 16)
+// owns row n of the band and the channel group g: channels CG*g .. CG*g+CG-1
+// with CG = C/4.  At step t the wave holds one anti-diagonal of its band (lane
+// row n is at column c = t - n - band delay), exactly as in the few-channel
+// wave kernel: own-row history in registers, one message per step from the row
+// above (DPP row_shr:1 inside each 16-lane group; lane n = 0 takes the message
+// of the band above from LDS).
+//
+// With folded weights the update of one anti-diagonal is a dense contraction
+// out[o][pixel] += Cf_tap[o][i] * x_tap[i][pixel] over (tap, i): M = output
+// channel, N = the 16 pixels of the band, K = 4 input channels per instruction,
+// one from each lane group.  The operand layouts of the instruction line up with
+// the ownership above: the B operand of lane (n, g) is its own history value of
+// channel CG*g + jj, and the four result registers of lane (n, g) are output
+// rows 4g .. 4g+3, i.e. its own channels (row 4g+3 is padding when CG = 3).
+//
+// An image taller than 16 rows uses one wave per band inside one workgroup.
+// Band b runs kBandDelay steps behind the skew of band b-1, all waves meet at a
+// barrier once per step, and the last row of a band hands its messages to the
+// next band through a small LDS ring.
+#include "invconv_common.h"
+#include "invconv_launch.h"
+
+namespace invconv {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// value of the same channel group one image row up (row 0 of the band receives 0)
+__device__ __forceinline__ float from_row_above16(float v)
+{
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x111 /* row_shr:1 */, 0xf, 0xf, true));
+}
+
+constexpr int kBandPF = 8;      // steps of load prefetch
+constexpr int kBandDelay = 1;   // extra steps a band lags behind the band above
+constexpr int kRing = 4;        // depth of the band-to-band message ring
+
+template <int CG, int K, int DIR>
+__global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in, const float *__restrict__ w,
+                                                    float *__restrict__ out, int H, int W, int NB)
+{
+    constexpr int C = 4 * CG;
+    extern __shared__ float smem[];
+    float *sL = smem;
+    float *sLinv = sL + C * C;
+    float *sCf = sLinv + C * C;
+    float *sMsg = sCf + K * K * C * C;      // [NB][kRing][K][16 groups*4]  (a = 0 unused)
+
+    const int tid = threadIdx.x;
+    const int band = tid >> 6, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const int row = band * 16 + n;
+    const bool row_ok = row < H;
+    const int rr = row_ok ? row : H - 1;
+    const unsigned Wst = row_ok ? (unsigned)W : 0u;
+
+    // addressing: uniform pointer per (channel of this lane's group) + per-lane 32-bit byte offset
+    const size_t img = (size_t)blockIdx.x * C * H * W;
+    const char *chan_src[CG];
+    char *chan_dst[CG];
+#pragma unroll
+    for (int jj = 0; jj < CG; ++jj) {
+        const int ch = CG * g + jj;
+        const size_t cb = img + (size_t)(DIR ? C - 1 - ch : ch) * H * W;
+        chan_src[jj] = reinterpret_cast<const char *>(in + cb);
+        chan_dst[jj] = reinterpret_cast<char *>(out + cb);
+    }
+    constexpr int kStep = DIR ? -4 : 4;
+    const int row0 = 4 * (DIR ? (H - 1 - rr) * W + (W - 1) : rr * W);
+    const int rowlo = DIR ? row0 - 4 * (W - 1) : row0;
+    const int rowhi = DIR ? row0 : row0 + 4 * (W - 1);
+    auto clamp_row = [&](int off) -> unsigned { return (unsigned)(off < rowlo ? rowlo : (off > rowhi ? rowhi : off)); };
+    auto ld = [&](int jj, unsigned off) -> float { return *reinterpret_cast<const float *>(chan_src[jj] + off); };
+    auto st = [&](int jj, unsigned off, float v) { *reinterpret_cast<float *>(chan_dst[jj] + off) = v; };
+
+    // Local step tau = t - t_first of this band: lane row n is at column c = tau - n.
+    const int t_first = band * (16 + kBandDelay);
+
+    // first batch of input loads, issued before the weight preparation
+    float yb[kBandPF][CG];
+#pragma unroll
+    for (int u = 0; u < kBandPF; ++u) {
+        const unsigned off = clamp_row(row0 + kStep * (u - n));
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj)
+            yb[u][jj] = ld(jj, off);
+    }
+
+    fold_weights<DIR>(w, C, K, sL, sLinv, sCf);
+    for (int idx = tid; idx < NB * kRing * K * 64; idx += blockDim.x)
+        sMsg[idx] = 0.0f;
+
+    // A operands of this lane: output row m = lane%16 -> channel o(m) = CG*(m/4) + m%4 (padding if m%4 >= CG),
+    // K slot g -> input channel CG*g + jj
+    const int m = n;
+    const bool m_ok = (m & 3) < CG;
+    const int om = m_ok ? CG * (m >> 2) + (m & 3) : 0;
+    float wA[K][K][CG], wLi[CG];
+#pragma unroll
+    for (int a = 0; a < K; ++a)
+#pragma unroll
+        for (int db = 0; db < K; ++db)
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj) {
+                const float cf = sCf[((a * K + db) * C + om) * C + CG * g + jj];
+                wA[a][db][jj] = m_ok ? -cf : 0.0f;
+            }
+#pragma unroll
+    for (int jj = 0; jj < CG; ++jj) {
+        const float lv = sLinv[om * C + CG * g + jj];
+        wLi[jj] = m_ok ? lv : 0.0f;
+    }
+    __syncthreads();        // ring zeroed, weights read
+
+    float xh[CG][K];
+    f32x4 T[K];
+#pragma unroll
+    for (int jj = 0; jj < CG; ++jj)
+#pragma unroll
+        for (int db = 0; db < K; ++db)
+            xh[jj][db] = 0.0f;
+#pragma unroll
+    for (int a = 0; a < K; ++a)
+        T[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+    for (int u = 0; u < kBandPF; ++u)
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj)
+            asm volatile("" : "+v"(yb[u][jj]));
+
+    int c = -n;
+    int ldoff = row0 + kStep * (kBandPF - n);
+    f32x4 own = f32x4{0.f, 0.f, 0.f, 0.f};
+    {
+        const bool in_row = (unsigned)c < (unsigned)W;
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj)
+            own = __builtin_amdgcn_mfma_f32_16x16x4f32(wLi[jj], in_row ? yb[0][jj] : 0.0f, own, 0, 0, 0);
+        const unsigned off = clamp_row(ldoff);
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj)
+            yb[0][jj] = ld(jj, off);
+        ldoff += kStep;
+    }
+
+    const bool first_row = (n == 0) && (band > 0);      // takes its messages from the band above
+    const bool last_row = (n == 15) && (band + 1 < NB); // hands its messages to the band below
+    const float *msg_in = sMsg + (size_t)(band > 0 ? band - 1 : 0) * kRing * K * 64 + g * 4;
+    float *msg_out = sMsg + (size_t)band * kRing * K * 64 + g * 4;
+
+    // Every wave passes the same number of barriers: t_first before its own steps,
+    // ntau during them (the same for all bands), and the rest afterwards.
+    const int ntau = (16 + W - 1 + kBandPF - 1) / kBandPF * kBandPF;
+    if (NB > 1) {
+        for (int t = 0; t < t_first; ++t)
+            __syncthreads();
+    }
+    for (int tau0 = 0; tau0 < ntau; tau0 += kBandPF) {
+#pragma unroll
+        for (int u = 0; u < kBandPF; ++u) {
+            const int t = t_first + tau0 + u;
+            // messages handed over by the band above kBandDelay+1 steps ago (used by row 0 only)
+            const float *mi = msg_in + ((t - 1 - kBandDelay) & (kRing - 1)) * K * 64;
+            float mrow[K][CG];
+#pragma unroll
+            for (int a = 1; a < K; ++a)
+#pragma unroll
+                for (int j = 0; j < CG; ++j)
+                    mrow[a][j] = mi[a * 64 + j];
+
+            float xn[CG];
+#pragma unroll
+            for (int j = 0; j < CG; ++j) {
+                const float up = from_row_above16(T[1][j]);
+                xn[j] = own[j] + (first_row ? mrow[1][j] : up);
+            }
+            if ((unsigned)c < Wst) {
+                const unsigned off = (unsigned)(row0 + kStep * c);
+#pragma unroll
+                for (int j = 0; j < CG; ++j)
+                    st(j, off, xn[j]);
+            }
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj)
+                xh[jj][0] = xn[jj];
+#pragma unroll
+            for (int a = 1; a < K; ++a) {
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (a + 1 < K) {
+#pragma unroll
+                    for (int j = 0; j < CG; ++j) {
+                        const float up = from_row_above16(T[a + 1][j]);
+                        acc[j] = first_row ? mrow[a + 1][j] : up;
+                    }
+                }
+#pragma unroll
+                for (int db = 0; db < K; ++db)
+#pragma unroll
+                    for (int jj = 0; jj < CG; ++jj)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[a][db][jj], xh[jj][db], acc, 0, 0, 0);
+                T[a] = acc;
+            }
+            if (last_row) {
+                float *mo = msg_out + (t & (kRing - 1)) * K * 64;
+#pragma unroll
+                for (int a = 1; a < K; ++a)
+#pragma unroll
+                    for (int j = 0; j < CG; ++j)
+                        mo[a * 64 + j] = T[a][j];
+            }
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj)
+#pragma unroll
+                for (int db = K - 1; db >= 1; --db)
+                    xh[jj][db] = xh[jj][db - 1];
+            c += 1;
+            {
+                const int s = (u + 1) % kBandPF;
+                const bool in_row = (unsigned)c < (unsigned)W;
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wLi[jj], in_row ? yb[s][jj] : 0.0f, acc, 0, 0, 0);
+#pragma unroll
+                for (int db = 1; db < K; ++db)
+#pragma unroll
+                    for (int jj = 0; jj < CG; ++jj)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][db][jj], xh[jj][db], acc, 0, 0, 0);
+                own = acc;
+                const unsigned off = clamp_row(ldoff);
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    yb[s][jj] = ld(jj, off);
+                ldoff += kStep;
+            }
+            if (NB > 1)
+                __syncthreads();
+        }
+    }
+    if (NB > 1) {
+        const int rest = (NB - 1 - band) * (16 + kBandDelay);
+        for (int t = 0; t < rest; ++t)
+            __syncthreads();
+    }
+}
+
+size_t solve_band_lds_bytes(int C, int k, int NB)
+{
+    return sizeof(float) * (2 * (size_t)C * C + (size_t)k * k * C * C + (size_t)NB * kRing * k * 64);
+}
+
+bool band_supported(int C, int H, int k)
+{
+    return (C == 8 || C == 12 || C == 16) && k == 3 && H <= 128;   // at most 8 bands = 512 threads
+}
+
+template <int CG, int K>
+static int launch_band_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
+                          hipStream_t stream)
+{
+    const int NB = (H + 15) / 16;
+    const size_t lds = solve_band_lds_bytes(4 * CG, K, NB);
+    if (dir)
+        hipLaunchKernelGGL((k_solve_band<CG, K, 1>), dim3(B), dim3(64 * NB), lds, stream, in, w, out, H, W, NB);
+    else
+        hipLaunchKernelGGL((k_solve_band<CG, K, 0>), dim3(B), dim3(64 * NB), lds, stream, in, w, out, H, W, NB);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+int launch_solve_band(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                      hipStream_t stream)
+{
+    if (!band_supported(C, H, k))
+        return INVCONV_ERR_VARIANT;
+    if (C == 8) return launch_band_ck<2, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 12) return launch_band_ck<3, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 16) return launch_band_ck<4, 3>(dir, in, w, out, B, H, W, stream);
+    return INVCONV_ERR_VARIANT;
+}
+
+}  // namespace invconv

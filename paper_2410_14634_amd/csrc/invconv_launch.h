@@ -28,6 +28,9 @@ int launch_solve_diag(int dir, const float *in, const float *w, float *out, int 
 bool wave_supported(int C, int H, int k);
 int launch_solve_wave(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                       hipStream_t stream);
+bool band_supported(int C, int H, int k);
+int launch_solve_band(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                      hipStream_t stream);
 bool bwd_wave_supported(int C, int H, int W, int k);
 int launch_bwd_wave(const float *x, const float *w, const float *g, float *v, float *part, int B, int C, int H,
                     int W, int k, hipStream_t stream);

@@ -10,8 +10,9 @@ from tests.util import THREADS, TOL_ACT, TOL_DW, dev, elementwise_ok, host, rel_
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [b.VARIANT_AUTO, b.VARIANT_BLOCK, b.VARIANT_DIAG_LAUNCH, b.VARIANT_WAVE]
+VARIANTS = [b.VARIANT_AUTO, b.VARIANT_BLOCK, b.VARIANT_DIAG_LAUNCH, b.VARIANT_WAVE, b.VARIANT_BAND]
 WAVE_OK = {0, 1, 3}     # workloads the wave-per-image variant covers (C <= 4, H <= 64)
+BAND_OK = {2, 4}        # workloads the 16-row-band variant covers (C = 8, 12, 16; k = 3; H <= 128)
 
 
 def run_layer(y, w, g, variant=b.VARIANT_AUTO):
@@ -41,7 +42,7 @@ def check_layer(y, w, g, variant=b.VARIANT_AUTO):
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3])
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_workload_parity(cfg, variant):
-    if variant == b.VARIANT_WAVE and cfg not in WAVE_OK:
+    if (variant == b.VARIANT_WAVE and cfg not in WAVE_OK) or (variant == b.VARIANT_BAND and cfg not in BAND_OK):
         pytest.skip("variant does not cover this shape")
     wl = inputs.make_workload(cfg)
     print(f"cfg {cfg} variant {variant}", flush=True)
@@ -58,6 +59,8 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     (1, 4, 1, 40, 3), (1, 4, 40, 1, 3), (2, 3, 2, 2, 5), (1, 5, 9, 11, 4), (2, 16, 10, 10, 3),
     (1, 3, 70, 33, 3), (5, 2, 33, 70, 5), (1, 1, 100, 100, 7), (2, 7, 17, 19, 1),
     (2, 3, 64, 5, 3), (3, 1, 33, 20, 3), (1, 2, 64, 64, 3), (2, 4, 63, 9, 3), (1, 3, 5, 100, 5),
+    (2, 12, 16, 16, 3), (1, 12, 33, 20, 3), (2, 8, 50, 17, 3), (1, 16, 128, 40, 3), (1, 12, 7, 100, 3),
+    (3, 12, 1, 1, 3), (1, 8, 17, 2, 3), (1, 12, 129, 8, 3),
 ]
 
 
