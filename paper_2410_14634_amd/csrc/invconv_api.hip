@@ -81,7 +81,7 @@ size_t invconv_bwd_workspace_bytes(int B, int C, int H, int W, int k)
 {
     if (check_shape(B, C, H, W, k) != INVCONV_OK)
         return 0;
-    const DwPlan p = plan_dw(B, C, H, W, k);
+    const DwPlan p = plan_dw_any(B, C, H, W, k);
     return p.rt ? p.bytes : 0;
 }
 
@@ -106,7 +106,7 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
         (variant == INVCONV_VARIANT_AUTO && !wave_supported(C, H, k) && !band_supported(C, H, k)))
         if (int s = check_supported(C, H, k))
             return s;
-    const DwPlan p = plan_dw(B, C, H, W, k);
+    const DwPlan p = plan_dw_any(B, C, H, W, k);
     if (!p.rt)
         return INVCONV_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < p.bytes)
@@ -119,6 +119,8 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
     }
     if (int s = solve(1, dLdx, w, dLdy, B, C, H, W, k, st, variant))
         return s;
+    if (dw_mfma_supported(C, k) && plan_dw_mfma(B, C, H, W, k).rt)
+        return launch_dw_mfma(x, dLdy, dLdw, (float *)workspace, p, B, C, H, W, k, st);
     return launch_dw(x, dLdy, dLdw, (float *)workspace, p, B, C, H, W, k, st);
 }
 

@@ -48,7 +48,8 @@ __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in
     float *sL = smem;
     float *sLinv = sL + C * C;
     float *sCf = sLinv + C * C;
-    float *sMsg = sCf + K * K * C * C;      // [NB][kRing][K][16 groups*4]  (a = 0 unused)
+    float *sW = sCf + K * K * C * C;
+    float *sMsg = sW + K * K * C * C;       // [NB][kRing][K][16 groups*4]  (a = 0 unused)
 
     const int tid = threadIdx.x;
     const int band = tid >> 6, lane = tid & 63;
@@ -90,7 +91,7 @@ __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in
             yb[u][jj] = ld(jj, off);
     }
 
-    fold_weights<DIR>(w, C, K, sL, sLinv, sCf);
+    fold_weights<DIR>(w, C, K, sL, sLinv, sCf, sW);
     for (int idx = tid; idx < NB * kRing * K * 64; idx += blockDim.x)
         sMsg[idx] = 0.0f;
 
@@ -251,7 +252,7 @@ __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in
 
 size_t solve_band_lds_bytes(int C, int k, int NB)
 {
-    return sizeof(float) * (2 * (size_t)C * C + (size_t)k * k * C * C + (size_t)NB * kRing * k * 64);
+    return sizeof(float) * (2 * (size_t)C * C + 2 * (size_t)k * k * C * C + (size_t)NB * kRing * k * 64);
 }
 
 bool band_supported(int C, int H, int k)

@@ -43,14 +43,22 @@ __device__ __forceinline__ float weff(const float *__restrict__ w, int C, int k,
 //   x_p = Linv y_p - sum_tap Cf_tap x_{p-tap}.
 // Outputs (LDS): sLinv[C][C]; sCf[k*k][C][C] indexed by tp = da*k+db where
 // (da,db) = (k-1-a, k-1-b) is how far up/left the tap reaches (tp = 0 unused,
-// zero filled).  sL is C*C floats of scratch.  Ends with a barrier.
+// zero filled).  sL is C*C floats of scratch and sW k*k*C*C floats of scratch
+// (the oriented, masked kernel as [tp][o][i], read from global memory once).
+// Ends with a barrier.
 template <int DIR>
 __device__ void fold_weights(const float *__restrict__ w, int C, int k,
-                             float *sL, float *sLinv, float *sCf)
+                             float *sL, float *sLinv, float *sCf, float *sW)
 {
     const int tid = threadIdx.x, nt = blockDim.x;
-    for (int idx = tid; idx < C * C; idx += nt)
-        sL[idx] = weff<DIR>(w, C, k, idx / C, idx % C, k - 1, k - 1);
+    const int total = k * k * C * C;
+    for (int idx = tid; idx < total; idx += nt) {
+        const int i = idx % C, o = (idx / C) % C, tp = idx / (C * C);
+        const float val = weff<DIR>(w, C, k, o, i, k - 1 - tp / k, k - 1 - tp % k);
+        sW[idx] = val;
+        if (tp == 0)
+            sL[o * C + i] = val;
+    }
     __syncthreads();
     if (tid < C) {
         const int j = tid;
@@ -65,14 +73,14 @@ __device__ void fold_weights(const float *__restrict__ w, int C, int k,
         }
     }
     __syncthreads();
-    const int total = k * k * C * C;
     for (int idx = tid; idx < total; idx += nt) {
         const int i = idx % C, o = (idx / C) % C, tp = idx / (C * C);
         float s = 0.0f;
         if (tp != 0) {
-            const int a = k - 1 - tp / k, b = k - 1 - tp % k;
+            const float *li = sLinv + o * C;
+            const float *wt = sW + tp * C * C + i;
             for (int j = 0; j <= o; ++j)
-                s += sLinv[o * C + j] * weff<DIR>(w, C, k, j, i, a, b);
+                s += li[j] * wt[j * C];
         }
         sCf[idx] = s;
     }

@@ -1,0 +1,162 @@
+// Weight gradient on the matrix cores for C <= 16 (Eq. 4 with Theorem 2):
+//   dw[o][i][a][b] = - sum_{n,r,c} v[n][o][r][c] * x[n][i][r-(k-1)+a][c-(k-1)+b]
+// is a GEMM with M = C output channels, N = C*k*k "shifted x" columns and the
+// pixels of the whole batch as the contraction index.  gfx950 only.
+//
+// Pass 1: one workgroup (4 waves) per (image, chunk of RT rows).  v and x (with
+// a zero halo of k-1 rows/columns on the top/left) are staged in LDS.  Each
+// v_mfma_f32_16x16x4_f32 contracts 4 pixels: A[m][kk] = v[o = m][pixel 4q+kk],
+// B[kk][nn] = column 16s+nn of pixel 4q+kk, result D_s[m][nn].  Rows m >= C and
+// columns >= C*k*k are padding: they read valid data and are never written out.
+// The four waves take pixel groups round robin and are added in wave order
+// through LDS; the un-negated partial sums go to part[workgroup][P].
+// Pass 2 (k_dw_reduce in the generic file) adds the rows of `part` in a fixed order.
+#include "invconv_common.h"
+#include "invconv_launch.h"
+
+namespace invconv {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int NS>
+__global__ __launch_bounds__(256) void k_dw_partial_mfma(const float *__restrict__ x, const float *__restrict__ v,
+                                                        float *__restrict__ part, int C, int H, int W, int k,
+                                                        int RT, int nchunks)
+{
+    extern __shared__ float smem[];
+    const int n = blockIdx.x / nchunks, chunk = blockIdx.x % nchunks;
+    const int r0 = chunk * RT;
+    const int rows = (H - r0 < RT) ? H - r0 : RT;
+    const int XR = RT + k - 1, XW = W + k - 1;
+    const int NCOL = C * k * k;
+    const int P = C * NCOL;
+    float *sv = smem;                 // [C][RT][W]
+    float *sx = sv + C * RT * W;      // [C][XR][XW], origin at (r0-(k-1), -(k-1))
+    float *sred = smem;               // [4 waves][64 lanes][NS*4], reuses the tiles afterwards
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+
+    for (int idx = tid; idx < C * rows * W; idx += 256) {
+        const int c = idx % W, r = (idx / W) % rows, ch = idx / (W * rows);
+        sv[(ch * RT + r) * W + c] = v[(((size_t)n * C + ch) * H + r0 + r) * W + c];
+    }
+    const int xrows = rows + k - 1;
+    for (int idx = tid; idx < C * xrows * XW; idx += 256) {
+        const int cc = idx % XW, rr = (idx / XW) % xrows, ch = idx / (XW * xrows);
+        const int gr = r0 - (k - 1) + rr, gc = cc - (k - 1);
+        sx[(ch * XR + rr) * XW + cc] =
+            (gr >= 0 && gc >= 0) ? x[(((size_t)n * C + ch) * H + gr) * W + gc] : 0.0f;
+    }
+    __syncthreads();
+
+    const int nn = lane & 15, kk = lane >> 4;
+    const int aoff = (nn < C ? nn : 0) * RT * W;            // A row m = nn -> v[o = m]
+    int boff[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const int col = (16 * s + nn < NCOL) ? 16 * s + nn : 0;
+        const int i = col / (k * k), a = (col / k) % k, b = col % k;
+        boff[s] = (i * XR + a) * XW + b;
+    }
+    f32x4 acc[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int npix = rows * W;
+    const int ngroups = (npix + 3) / 4;
+    for (int q = wave; q < ngroups; q += 4) {
+        const int p = 4 * q + kk;
+        const bool pv = p < npix;
+        const int pr = pv ? p / W : 0, pc = pv ? p - pr * W : 0;
+        const float avl = sv[aoff + pr * W + pc];
+        const float av = pv ? avl : 0.0f;       // pixels past the end contribute nothing
+        const float *bp = sx + pr * XW + pc;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bp[boff[s]], acc[s], 0, 0, 0);
+    }
+    __syncthreads();        // tiles no longer needed
+    // lane (nn, g = kk) register (s, j) holds entry (o = 4g + j, col = 16s + nn)
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            sred[tid * (NS * 4) + s * 4 + j] = acc[s][j];
+    __syncthreads();
+    for (int e = tid; e < P; e += 256) {
+        const int o = e / NCOL, col = e % NCOL;
+        const int s = col >> 4, cn = col & 15, g = o >> 2, j = o & 3;
+        float sum = 0.0f;
+        for (int wv = 0; wv < 4; ++wv)
+            sum += sred[(wv * 64 + g * 16 + cn) * (NS * 4) + s * 4 + j];
+        part[(size_t)blockIdx.x * P + e] = sum;
+    }
+}
+
+bool dw_mfma_supported(int C, int k)
+{
+    const int ns = (C * k * k + 15) / 16;
+    return C <= 16 && ns >= 1 && ns <= 10;
+}
+
+// Row chunking of pass 1: tiles (or the reduction buffer that reuses them) must fit the LDS budget.
+DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
+{
+    DwPlan p{};
+    if (!dw_mfma_supported(C, k))
+        return p;
+    const size_t P = (size_t)C * C * k * k;
+    const size_t NS = ((size_t)C * k * k + 15) / 16;
+    const size_t red = 256 * NS * 4;
+    auto lds_for = [&](int rt) {
+        const size_t tiles = (size_t)C * rt * W + (size_t)C * (rt + k - 1) * (W + k - 1);
+        return sizeof(float) * (tiles > red ? tiles : red);
+    };
+    if (lds_for(1) > kDwLdsBudget)
+        return p;
+    int want = (int)((2048 + B - 1) / B);          // aim for a few workgroups per compute unit
+    if (want < 1) want = 1;
+    int rt = (H + want - 1) / want;
+    if (rt < 1) rt = 1;
+    while (rt > 1 && lds_for(rt) > kDwLdsBudget)
+        --rt;
+    p.rt = rt;
+    p.nchunks = (H + rt - 1) / rt;
+    p.nparts = (size_t)B * p.nchunks;
+    p.lds = lds_for(rt);
+    p.bytes = ((p.nparts * P * sizeof(float)) + 255) / 256 * 256;
+    return p;
+}
+
+template <int NS>
+static void launch_ns(const float *x, const float *v, float *part, const DwPlan &p, int C, int H, int W, int k,
+                      hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_dw_partial_mfma<NS>, dim3((unsigned)p.nparts), dim3(256), p.lds, stream, x, v, part, C, H,
+                       W, k, p.rt, p.nchunks);
+}
+
+int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
+                   int W, int k, hipStream_t stream)
+{
+    (void)B;
+    const int ns = (C * k * k + 15) / 16;
+    switch (ns) {
+    case 1: launch_ns<1>(x, v, part, p, C, H, W, k, stream); break;
+    case 2: launch_ns<2>(x, v, part, p, C, H, W, k, stream); break;
+    case 3: launch_ns<3>(x, v, part, p, C, H, W, k, stream); break;
+    case 4: launch_ns<4>(x, v, part, p, C, H, W, k, stream); break;
+    case 5: launch_ns<5>(x, v, part, p, C, H, W, k, stream); break;
+    case 6: launch_ns<6>(x, v, part, p, C, H, W, k, stream); break;
+    case 7: launch_ns<7>(x, v, part, p, C, H, W, k, stream); break;
+    case 8: launch_ns<8>(x, v, part, p, C, H, W, k, stream); break;
+    case 9: launch_ns<9>(x, v, part, p, C, H, W, k, stream); break;
+    case 10: launch_ns<10>(x, v, part, p, C, H, W, k, stream); break;
+    default: return INVCONV_ERR_UNSUPPORTED;
+    }
+    if (hipGetLastError() != hipSuccess)
+        return INVCONV_ERR_LAUNCH;
+    return launch_dw_reduce(part, (int)p.nparts, dw, C, k, stream);
+}
+
+}  // namespace invconv

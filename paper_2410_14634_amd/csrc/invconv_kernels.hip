@@ -30,11 +30,12 @@ __global__ __launch_bounds__(kSolveBlock) void k_solve_block(const float *__rest
     float *sL = smem;
     float *sLinv = sL + C * C;
     float *sCf = sLinv + C * C;
-    float *win = sCf + k * k * C * C;
+    float *sW = sCf + k * k * C * C;
+    float *win = sW + k * k * C * C;
 
     const int n = blockIdx.x;
     const int tid = threadIdx.x;
-    fold_weights<DIR>(w, C, k, sL, sLinv, sCf);
+    fold_weights<DIR>(w, C, k, sL, sLinv, sCf, sW);
 
     const int ndiag = H + W - 1;
     for (int d = 0; d < ndiag; ++d) {
@@ -167,28 +168,39 @@ __global__ __launch_bounds__(kDwBlock) void k_dw_partial(const float *__restrict
     }
 }
 
-// Pass 2: one wave per kernel entry.  Lane l adds partial rows l, l+64, ... in
-// index order (double accumulator), the 64 lane sums are combined by a fixed
-// butterfly, the result is negated, and masked entries are written as 0.  No
-// atomics anywhere, so dw is bitwise reproducible from run to run.
+// Pass 2: a workgroup takes 64 consecutive kernel entries (lanes, so that every
+// row of `part` is read in 256-byte pieces); its four waves add the rows
+// p = wave, wave+4, ... in index order (double accumulator) and are then
+// combined in wave order.  The result is negated and masked entries are written
+// as 0.  No atomics anywhere, so dw is bitwise reproducible from run to run.
 __global__ __launch_bounds__(256) void k_dw_reduce(const float *__restrict__ part, int nparts,
                                                   float *__restrict__ dw, int C, int k)
 {
+    __shared__ double swave[4][64];
     const int P = C * C * k * k;
-    const int e = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (e >= P)
-        return;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int e = blockIdx.x * 64 + lane;
     double acc = 0.0;
-    for (int p = lane; p < nparts; p += 64)
-        acc += (double)part[(size_t)p * P + e];
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1)
-        acc += __shfl_xor(acc, m, 64);
-    if (lane == 0) {
+    if (e < P) {
+        int p = wave;
+        for (; p + 12 < nparts; p += 16) {
+            const float a0 = part[(size_t)p * P + e], a1 = part[(size_t)(p + 4) * P + e];
+            const float a2 = part[(size_t)(p + 8) * P + e], a3 = part[(size_t)(p + 12) * P + e];
+            acc += (double)a0;
+            acc += (double)a1;
+            acc += (double)a2;
+            acc += (double)a3;
+        }
+        for (; p < nparts; p += 4)
+            acc += (double)part[(size_t)p * P + e];
+    }
+    swave[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && e < P) {
+        const double total = ((swave[0][lane] + swave[1][lane]) + swave[2][lane]) + swave[3][lane];
         const int b = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
         const bool is_masked = (a == k - 1 && b == k - 1 && i > o);
-        dw[e] = is_masked ? 0.0f : (float)(-acc);
+        dw[e] = is_masked ? 0.0f : (float)(-total);
     }
 }
 
@@ -213,7 +225,7 @@ __global__ __launch_bounds__(64) void k_logdet(const float *__restrict__ w, int 
 size_t solve_block_lds_bytes(int C, int H, int k)
 {
     const size_t CP = (size_t)(C | 1), ND = 2 * (size_t)(k - 1) + 1;
-    return sizeof(float) * (2 * (size_t)C * C + (size_t)k * k * C * C + ND * H * CP);
+    return sizeof(float) * (2 * (size_t)C * C + 2 * (size_t)k * k * C * C + ND * H * CP);
 }
 
 template <int DIR>
@@ -284,8 +296,23 @@ DwPlan plan_dw(int B, int C, int H, int W, int k)
     p.nchunks = (H + rt - 1) / rt;
     p.nparts = (size_t)B * p.nchunks;
     p.lds = lds_for(rt);
-    const size_t rows = p.nparts > (size_t)B ? p.nparts : (size_t)B;   // the fused path writes one row per image
-    p.bytes = ((rows * P * sizeof(float)) + 255) / 256 * 256;
+    p.bytes = ((p.nparts * P * sizeof(float)) + 255) / 256 * 256;
+    return p;
+}
+
+// The plan invconv_bwd uses: matrix-core pass 1 when the shape allows it, the generic one otherwise.
+// `bytes` also covers the one-row-per-image partials of the fused backward kernel.
+DwPlan plan_dw_any(int B, int C, int H, int W, int k)
+{
+    DwPlan p = dw_mfma_supported(C, k) ? plan_dw_mfma(B, C, H, W, k) : DwPlan{};
+    if (!p.rt)
+        p = plan_dw(B, C, H, W, k);
+    if (p.rt) {
+        const size_t P = (size_t)C * C * k * k;
+        const size_t per_image = (((size_t)B * P * sizeof(float)) + 255) / 256 * 256;
+        if (p.bytes < per_image)
+            p.bytes = per_image;
+    }
     return p;
 }
 
@@ -302,7 +329,7 @@ int launch_dw(const float *x, const float *v, float *dw, float *part, const DwPl
 int launch_dw_reduce(const float *part, int nparts, float *dw, int C, int k, hipStream_t stream)
 {
     const int P = C * C * k * k;
-    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 3) / 4), dim3(256), 0, stream, part, nparts, dw, C, k);
+    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 63) / 64), dim3(256), 0, stream, part, nparts, dw, C, k);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

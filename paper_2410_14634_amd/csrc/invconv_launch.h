@@ -38,6 +38,11 @@ int launch_dw_reduce(const float *part, int nparts, float *dw, int C, int k, hip
 DwPlan plan_dw(int B, int C, int H, int W, int k);
 int launch_dw(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
               int W, int k, hipStream_t stream);
+bool dw_mfma_supported(int C, int k);
+DwPlan plan_dw_mfma(int B, int C, int H, int W, int k);
+int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
+                   int W, int k, hipStream_t stream);
+DwPlan plan_dw_any(int B, int C, int H, int W, int k);
 int launch_logdet(const float *w, int C, int H, int W, int k, float *out, hipStream_t stream);
 
 }  // namespace invconv
