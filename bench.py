@@ -35,6 +35,10 @@ def parse_args():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--variant", type=int, default=0)
+    ap.add_argument("--variants", action="store_true",
+                    help="also time the forward solve under every launch strategy (reported under 'variant_study')")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run three 64 MiB device copies (reference for the HBM byte counters)")
     return ap.parse_args()
 
 
@@ -164,6 +168,58 @@ def measure_workload(cfg, steps, warmup, variant=0):
     )
 
 
+def variant_study(cfg, reps=200):
+    """Forward solve of one workload under every launch strategy (us per call, HIP events)."""
+    import torch
+    from paper_2410_14634_amd import binding as b
+    names = {b.VARIANT_AUTO: "auto", b.VARIANT_BLOCK: "workgroup per image, LDS window, barrier per diagonal",
+             b.VARIANT_DIAG_LAUNCH: "one launch per diagonal, eager", b.VARIANT_WAVE: "wave per image, registers + DPP",
+             b.VARIANT_BAND: "wave per 16-row band, MFMA 16x16x4",
+             b.VARIANT_PERSISTENT: "persistent cooperative grid, device barrier per diagonal"}
+    out = {}
+    stream = torch.cuda.current_stream().cuda_stream
+    for var, name in names.items():
+        L = Layered(cfg, var)
+        try:
+            L.fwd_layer(0, stream)
+            torch.cuda.synchronize()
+        except AssertionError:
+            continue                     # variant does not cover this shape
+        r = reps if var not in (b.VARIANT_DIAG_LAUNCH, b.VARIANT_PERSISTENT) else max(reps // 10, 5)
+        out[name] = event_time_batch(torch, lambda: L.fwd_layer(0, stream), r, 3) * 1e3
+    # launch-per-diagonal captured once into a HIP graph and replayed
+    L = Layered(cfg, b.VARIANT_DIAG_LAUNCH)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        L.fwd_layer(0, side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        L.fwd_layer(0, torch.cuda.current_stream().cuda_stream)
+    out["one launch per diagonal, HIP graph replay"] = event_time_batch(torch, graph.replay, max(reps // 4, 5), 3) * 1e3
+    # cost of one dependent step under each ordering mechanism, no arithmetic (us per step)
+    lib = b.lib()
+    steps = 200
+    probe = {}
+    for mode, name in ((0, "kernel launch per step, eager"), (1, "device-wide barrier in a cooperative grid"),
+                       (2, "workgroup barrier + LDS exchange")):
+        for wgs in (16, 256):
+            def run(mode=mode, wgs=wgs):
+                assert lib.invconv_probe_step_sync(mode, steps, wgs, stream) == 0
+            probe[f"{name}, {wgs} workgroups"] = event_time_batch(torch, run, 10, 2) * 1e3 / steps
+    graph2 = torch.cuda.CUDAGraph()
+    assert lib.invconv_probe_step_sync(0, steps, 16, stream) == 0
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph2):
+        assert lib.invconv_probe_step_sync(0, steps, 16, torch.cuda.current_stream().cuda_stream) == 0
+    probe["kernel launch per step, HIP graph replay, 16 workgroups"] = \
+        event_time_batch(torch, graph2.replay, 10, 2) * 1e3 / steps
+    out["empty step cost, us per step"] = probe
+    return out
+
+
 def cpu_baseline(cfg, seconds):
     """The CPU oracle, as it stands, on the same workload (bounded sample), all host cores."""
     import oracle
@@ -212,6 +268,14 @@ def main():
         sys.exit(2)
     b.lib()   # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
+    if args.calibration_copy:
+        # a plain device copy of known size: what the HBM byte counters read for it scales the
+        # counter readings of the kernels (64 MiB read + 64 MiB written)
+        src = torch.zeros(64 * 1024 * 1024 // 4, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     cfg = args.workload
     L, res = measure_workload(cfg, args.steps, args.warmup, args.variant)
 
@@ -254,6 +318,9 @@ def main():
             others[str(c)] = r
             print(f"[bench] workload {c}: {json.dumps(r)}", file=sys.stderr, flush=True)
         out["workloads"] = others
+    if args.variants:
+        out["variant_study_us_per_fwd_call"] = variant_study(cfg)
+        print(f"[bench] variants: {json.dumps(out['variant_study_us_per_fwd_call'])}", file=sys.stderr, flush=True)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds)
     else:

@@ -53,7 +53,8 @@ enum {
     INVCONV_VARIANT_BLOCK = 1,    /* one workgroup per image, LDS window, one barrier per anti-diagonal */
     INVCONV_VARIANT_DIAG_LAUNCH = 2, /* one kernel launch per anti-diagonal (capture it in a hipGraph) */
     INVCONV_VARIANT_WAVE = 3,     /* one wave per image, lane = row, register/DPP systolic solve (C <= 4, H <= 64) */
-    INVCONV_VARIANT_BAND = 4      /* one wave per 16-row band, 16x16x4 MFMA systolic solve (C = 8, 12, 16; k = 3; H <= 128) */
+    INVCONV_VARIANT_BAND = 4,     /* one wave per 16-row band, 16x16x4 MFMA systolic solve (C = 8, 12, 16; k = 3; H <= 128) */
+    INVCONV_VARIANT_PERSISTENT = 5 /* one cooperative launch, persistent grid, device-wide barrier per anti-diagonal */
 };
 
 /*
@@ -103,6 +104,16 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
                               float *dLdy, float *dLdw,
                               int B, int C, int H, int W, int k,
                               void *workspace, size_t workspace_bytes, void *stream, int variant);
+
+/*
+ * Measurement aid (Section 3.3 orders anti-diagonals with a synchronisation after
+ * each): runs `steps` dependent, empty steps ordered by
+ *   mode 0: one kernel launch per step (`workgroups` workgroups of 256 threads each),
+ *   mode 1: one cooperative launch with a device-wide barrier per step,
+ *   mode 2: one launch with a workgroup barrier and an LDS exchange per step.
+ * No data is touched.  steps in 1..100000, workgroups in 1..256.
+ */
+invconv_status invconv_probe_step_sync(int mode, int steps, int workgroups, void *stream);
 
 /* Static, human-readable name of a status code. */
 const char *invconv_status_string(invconv_status status);

@@ -17,11 +17,12 @@ LIB_PATH = os.path.join(_PKG, "libinvconv.so")
 
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_ALIAS, ERR_LAUNCH, ERR_VARIANT = range(-1, -8, -1)
-VARIANT_AUTO, VARIANT_BLOCK, VARIANT_DIAG_LAUNCH, VARIANT_WAVE, VARIANT_BAND = 0, 1, 2, 3, 4
+VARIANT_AUTO, VARIANT_BLOCK, VARIANT_DIAG_LAUNCH, VARIANT_WAVE, VARIANT_BAND, VARIANT_PERSISTENT = 0, 1, 2, 3, 4, 5
 
 EXPORTS = (
     "invconv_fwd", "invconv_bwd", "invconv_bwd_workspace_bytes", "invconv_logdet",
     "invconv_fwd_ex", "invconv_bwd_ex", "invconv_status_string", "invconv_version",
+    "invconv_probe_step_sync",
 )
 
 _lib = None
@@ -50,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.invconv_bwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
         L.invconv_bwd_workspace_bytes.restype = sz
         L.invconv_logdet.argtypes = [vp, ci, ci, ci, ci, vp, vp]
+        L.invconv_probe_step_sync.argtypes = [ci, ci, ci, vp]
+        L.invconv_probe_step_sync.restype = ci
         L.invconv_status_string.argtypes = [ci]
         L.invconv_status_string.restype = ctypes.c_char_p
         L.invconv_version.restype = ci

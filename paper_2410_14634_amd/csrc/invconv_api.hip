@@ -38,6 +38,8 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
         return launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_BAND:
         return launch_solve_band(dir, in, w, out, B, C, H, W, k, stream);
+    case INVCONV_VARIANT_PERSISTENT:
+        return launch_solve_persistent(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_DIAG_LAUNCH:
         return launch_solve_diag(dir, in, w, out, B, C, H, W, k, stream);
     default:
@@ -58,7 +60,7 @@ invconv_status invconv_fwd_ex(const float *y, const float *w, float *x, int B, i
         return s;
     if (x == y || (const float *)x == w)
         return INVCONV_ERR_ALIAS;
-    if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_BAND)
+    if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_PERSISTENT)
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_WAVE && !wave_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
@@ -96,7 +98,7 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
     if (dLdy == dLdx || dLdy == x || (const float *)dLdy == w || dLdw == dLdy || (const float *)dLdw == w ||
         (const float *)dLdw == x || (const float *)dLdw == dLdx)
         return INVCONV_ERR_ALIAS;
-    if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_BAND)
+    if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_PERSISTENT)
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_WAVE && !wave_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
@@ -138,6 +140,15 @@ invconv_status invconv_logdet(const float *w, int C, int H, int W, int k, float 
     if (int s = check_shape(1, C, H, W, k))
         return s;
     return launch_logdet(w, C, H, W, k, out, (hipStream_t)stream);
+}
+
+invconv_status invconv_probe_step_sync(int mode, int steps, int workgroups, void *stream)
+{
+    if (mode < 0 || mode > 2)
+        return INVCONV_ERR_VARIANT;
+    if (steps < 1 || steps > 100000 || workgroups < 1 || workgroups > 256)
+        return INVCONV_ERR_SHAPE;
+    return launch_probe(mode, steps, workgroups, (hipStream_t)stream);
 }
 
 const char *invconv_status_string(invconv_status status)

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in
             yb[u][jj] = ld(jj, off);
     }
 
-    fold_weights<DIR>(w, C, K, sL, sLinv, sCf, sW);
+    fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sW);
     for (int idx = tid; idx < NB * kRing * K * 64; idx += blockDim.x)
         sMsg[idx] = 0.0f;
 

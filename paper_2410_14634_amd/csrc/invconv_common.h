@@ -46,7 +46,9 @@ __device__ __forceinline__ float weff(const float *__restrict__ w, int C, int k,
 // zero filled).  sL is C*C floats of scratch and sW k*k*C*C floats of scratch
 // (the oriented, masked kernel as [tp][o][i], read from global memory once).
 // Ends with a barrier.
-template <int DIR>
+// CT = C when it is known at compile time (loops then have fixed trip counts and
+// their LDS reads pipeline), 0 otherwise.
+template <int DIR, int CT = 0>
 __device__ void fold_weights(const float *__restrict__ w, int C, int k,
                              float *sL, float *sLinv, float *sCf, float *sW)
 {
@@ -79,8 +81,15 @@ __device__ void fold_weights(const float *__restrict__ w, int C, int k,
         if (tp != 0) {
             const float *li = sLinv + o * C;
             const float *wt = sW + tp * C * C + i;
-            for (int j = 0; j <= o; ++j)
-                s += li[j] * wt[j * C];
+            if (CT > 0) {
+                // entries of Linv above the diagonal are zero, so the full row may be used
+#pragma unroll
+                for (int j = 0; j < CT; ++j)
+                    s += li[j] * wt[j * CT];
+            } else {
+                for (int j = 0; j <= o; ++j)
+                    s += li[j] * wt[j * C];
+            }
         }
         sCf[idx] = s;
     }

@@ -2,6 +2,8 @@
 // wavefront solve (both orientations), the weight-gradient correlation with
 // its fixed-order reduction, the log-determinant, and the one-launch-per-
 // anti-diagonal comparison variant.  gfx950 only.
+#include <hip/hip_cooperative_groups.h>
+
 #include "invconv_common.h"
 #include "invconv_launch.h"
 
@@ -97,6 +99,98 @@ __global__ __launch_bounds__(256) void k_solve_one_diagonal(const float *__restr
             acc -= weff<DIR>(w, C, k, o, i, k - 1, k - 1) * out[gidx<DIR>(n, i, r, c, C, H, W)];
         out[gidx<DIR>(n, o, r, c, C, H, W)] = acc / weff<DIR>(w, C, k, o, o, k - 1, k - 1);
     }
+}
+
+// ---------------------------------------------------------------------------
+// Comparison variant: ONE cooperative launch of a persistent grid that walks
+// the anti-diagonals itself and separates them with a device-wide barrier
+// (cooperative-groups grid sync).  Same per-pixel work as the launch-per-
+// diagonal variant; every (image, pixel) of a diagonal is one work item and
+// the grid strides over them, so an image may be spread over many compute units.
+// ---------------------------------------------------------------------------
+template <int DIR>
+__global__ __launch_bounds__(256) void k_solve_persistent(const float *__restrict__ in,
+                                                         const float *__restrict__ w, float *out, int B,
+                                                         int C, int H, int W, int k)
+{
+    namespace cg = cooperative_groups;
+    cg::grid_group grid = cg::this_grid();
+    const int ndiag = H + W - 1;
+    const int nthreads = gridDim.x * blockDim.x;
+    const int t0 = blockIdx.x * blockDim.x + threadIdx.x;
+    for (int d = 0; d < ndiag; ++d) {
+        const int rlo = d - (W - 1) > 0 ? d - (W - 1) : 0;
+        const int rhi = d < H - 1 ? d : H - 1;
+        const int npx = rhi - rlo + 1;
+        for (int t = t0; t < B * npx; t += nthreads) {
+            const int n = t / npx, r = rlo + t % npx, c = d - r;
+            for (int o = 0; o < C; ++o) {
+                float acc = in[gidx<DIR>(n, o, r, c, C, H, W)];
+                for (int da = 0; da < k && da <= r; ++da)
+                    for (int db = (da == 0) ? 1 : 0; db < k && db <= c; ++db)
+                        for (int i = 0; i < C; ++i)
+                            acc -= weff<DIR>(w, C, k, o, i, k - 1 - da, k - 1 - db) *
+                                   out[gidx<DIR>(n, i, r - da, c - db, C, H, W)];
+                for (int i = 0; i < o; ++i)
+                    acc -= weff<DIR>(w, C, k, o, i, k - 1, k - 1) * out[gidx<DIR>(n, i, r, c, C, H, W)];
+                out[gidx<DIR>(n, o, r, c, C, H, W)] = acc / weff<DIR>(w, C, k, o, o, k - 1, k - 1);
+            }
+        }
+        grid.sync();    // every thread of the grid reaches this once per diagonal
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Step-synchronisation probes: the cost of one dependent step under each of the
+// three ways of ordering anti-diagonals, with no arithmetic in between.
+// ---------------------------------------------------------------------------
+__global__ void k_probe_empty(int *sink)
+{
+    if (sink && threadIdx.x == 1000000)
+        sink[0] = 0;
+}
+
+__global__ __launch_bounds__(256) void k_probe_grid_sync(int steps, int *sink)
+{
+    namespace cg = cooperative_groups;
+    cg::grid_group grid = cg::this_grid();
+    for (int s = 0; s < steps; ++s)
+        grid.sync();
+    if (sink && threadIdx.x == 1000000)
+        sink[0] = 0;
+}
+
+__global__ __launch_bounds__(256) void k_probe_block_sync(int steps, int *sink)
+{
+    __shared__ float buf[256];
+    float v = threadIdx.x;
+    for (int s = 0; s < steps; ++s) {
+        buf[threadIdx.x] = v;
+        __syncthreads();
+        v += buf[(threadIdx.x + 64) & 255];
+        __syncthreads();
+    }
+    if (sink && v == -1.0f)
+        sink[0] = 0;
+}
+
+int launch_probe(int mode, int steps, int blocks, hipStream_t stream)
+{
+    int *sink = nullptr;
+    if (mode == 0) {
+        for (int s = 0; s < steps; ++s)
+            hipLaunchKernelGGL(k_probe_empty, dim3(blocks), dim3(256), 0, stream, sink);
+    } else if (mode == 1) {
+        void *args[] = {(void *)&steps, (void *)&sink};
+        if (hipLaunchCooperativeKernel(reinterpret_cast<void *>(k_probe_grid_sync), dim3(blocks), dim3(256), args, 0,
+                                       stream) != hipSuccess) {
+            (void)hipGetLastError();
+            return INVCONV_ERR_LAUNCH;
+        }
+    } else {
+        hipLaunchKernelGGL(k_probe_block_sync, dim3(blocks), dim3(256), 0, stream, steps, sink);
+    }
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
 // ---------------------------------------------------------------------------
@@ -272,6 +366,39 @@ int launch_solve_diag(int dir, const float *in, const float *w, float *out, int 
             return INVCONV_ERR_LAUNCH;
     }
     return INVCONV_OK;
+}
+
+template <int DIR>
+static int launch_persistent_dir(const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                                 hipStream_t stream)
+{
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_solve_persistent<DIR>, 256, 0) != hipSuccess ||
+        cus < 1 || per_cu < 1) {
+        (void)hipGetLastError();
+        return INVCONV_ERR_LAUNCH;
+    }
+    const int longest = H < W ? H : W;
+    long long want = ((long long)B * longest + 255) / 256;      // enough threads for the longest diagonal
+    const long long cap = (long long)cus * per_cu;              // what can be resident at once
+    if (want > cap) want = cap;
+    if (want < 1) want = 1;
+    void *args[] = {(void *)&in, (void *)&w, (void *)&out, (void *)&B, (void *)&C, (void *)&H, (void *)&W, (void *)&k};
+    if (hipLaunchCooperativeKernel(reinterpret_cast<void *>(k_solve_persistent<DIR>), dim3((unsigned)want), dim3(256),
+                                   args, 0, stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return INVCONV_ERR_LAUNCH;
+    }
+    return INVCONV_OK;
+}
+
+int launch_solve_persistent(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W,
+                            int k, hipStream_t stream)
+{
+    return dir ? launch_persistent_dir<1>(in, w, out, B, C, H, W, k, stream)
+               : launch_persistent_dir<0>(in, w, out, B, C, H, W, k, stream);
 }
 
 DwPlan plan_dw(int B, int C, int H, int W, int k)

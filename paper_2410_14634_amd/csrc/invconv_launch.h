@@ -35,6 +35,9 @@ bool bwd_wave_supported(int C, int H, int W, int k);
 int launch_bwd_wave(const float *x, const float *w, const float *g, float *v, float *part, int B, int C, int H,
                     int W, int k, hipStream_t stream);
 int launch_dw_reduce(const float *part, int nparts, float *dw, int C, int k, hipStream_t stream);
+int launch_solve_persistent(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W,
+                            int k, hipStream_t stream);
+int launch_probe(int mode, int steps, int blocks, hipStream_t stream);
 DwPlan plan_dw(int B, int C, int H, int W, int k);
 int launch_dw(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
               int W, int k, hipStream_t stream);

@@ -10,7 +10,8 @@ from tests.util import THREADS, TOL_ACT, TOL_DW, dev, elementwise_ok, host, rel_
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [b.VARIANT_AUTO, b.VARIANT_BLOCK, b.VARIANT_DIAG_LAUNCH, b.VARIANT_WAVE, b.VARIANT_BAND]
+VARIANTS = [b.VARIANT_AUTO, b.VARIANT_BLOCK, b.VARIANT_DIAG_LAUNCH, b.VARIANT_WAVE, b.VARIANT_BAND,
+            b.VARIANT_PERSISTENT]
 WAVE_OK = {0, 1, 3}     # workloads the wave-per-image variant covers (C <= 4, H <= 64)
 BAND_OK = {2, 4}        # workloads the 16-row-band variant covers (C = 8, 12, 16; k = 3; H <= 128)
 
@@ -66,7 +67,7 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
 
 
 @pytest.mark.parametrize("shape", EDGE_SHAPES)
-@pytest.mark.parametrize("variant", [b.VARIANT_AUTO, b.VARIANT_DIAG_LAUNCH])
+@pytest.mark.parametrize("variant", [b.VARIANT_AUTO, b.VARIANT_DIAG_LAUNCH, b.VARIANT_PERSISTENT])
 def test_edge_shapes(shape, variant):
     B, C, H, W, k = shape
     print(f"edge {shape} variant {variant}", flush=True)
