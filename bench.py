@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 
+# HBM bytes per launch of the forward solve kernel, from rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE
+# (KiB per dispatch), each scaled by what the same counter reads for a 64 MiB device copy
+# (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00); the runs are summarised under profiles/.
+MEASURED_TRAFFIC_BYTES = {1: int((2.00 * 181.0 + 1.00 * 192.0) * 1024)}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -288,7 +293,8 @@ def main():
     kernel_ms = k_batch
     achieved = kernel_bytes / (kernel_ms * 1e-3) / 1e9
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                    traffic=None, kernel="k_solve_block<0> (wavefront solve, forward orientation)",
+                    traffic=MEASURED_TRAFFIC_BYTES.get(cfg),
+                    kernel="forward wavefront solve (the one kernel invconv_fwd launches)",
                     kernel_ms_back_to_back=k_batch, kernel_ms_event_pair_median=k_med,
                     kernel_ms_event_pair_min=k_min, algorithmic_bytes_per_launch=kernel_bytes,
                     dependent_steps=L.H + L.W - 1,
