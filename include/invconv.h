@@ -106,6 +106,33 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
                               void *workspace, size_t workspace_bytes, void *stream, int variant);
 
 /*
+ * A stack of L inverse-convolution layers (Section 4.1 repeats the flow step K times), layer l with
+ * its own kernel w[l]:  x[0] = invconv(y; w[0]),  x[l] = invconv(x[l-1]; w[l]).
+ * `w` and `x` are HOST arrays of L device pointers (read during the call only); every x[l] is a
+ * distinct B*C*H*W buffer (all are kept: the backward pass needs them).  Results are those of L
+ * calls of invconv_fwd; where the shape allows it the layers run as one pipelined launch in which
+ * layer l+1 trails layer l by a few anti-diagonals.  L in 1..16.
+ *   workspace: at least invconv_chain_workspace_bytes() bytes of device memory, 256-byte aligned.
+ */
+invconv_status invconv_chain_fwd(const float *y, const float *const *w, float *const *x, int L,
+                                 int B, int C, int H, int W, int k,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward pass through the same stack: given x[l] (outputs of invconv_chain_fwd), the kernels and
+ * dLdx_last = dL/dx[L-1], writes dLdy_first = dL/d(y of layer 0) and dLdw[l] for every layer
+ * (Eq. 2 and Eq. 4 per layer; the input gradient of layer l is the output gradient of layer l-1).
+ * `x`, `w`, `dLdw` are HOST arrays of L device pointers.  Intermediate gradients live in the workspace.
+ */
+invconv_status invconv_chain_bwd(const float *const *x, const float *const *w, const float *dLdx_last,
+                                 float *dLdy_first, float *const *dLdw, int L,
+                                 int B, int C, int H, int W, int k,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of scratch the two chain calls need (0 if the shape is invalid or unsupported). */
+size_t invconv_chain_workspace_bytes(int L, int B, int C, int H, int W, int k);
+
+/*
  * Measurement aid (Section 3.3 orders anti-diagonals with a synchronisation after
  * each): runs `steps` dependent, empty steps ordered by
  *   mode 0: one kernel launch per step (`workgroups` workgroups of 256 threads each),

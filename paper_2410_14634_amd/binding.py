@@ -22,7 +22,7 @@ VARIANT_AUTO, VARIANT_BLOCK, VARIANT_DIAG_LAUNCH, VARIANT_WAVE, VARIANT_BAND, VA
 EXPORTS = (
     "invconv_fwd", "invconv_bwd", "invconv_bwd_workspace_bytes", "invconv_logdet",
     "invconv_fwd_ex", "invconv_bwd_ex", "invconv_status_string", "invconv_version",
-    "invconv_probe_step_sync",
+    "invconv_probe_step_sync", "invconv_chain_fwd", "invconv_chain_bwd", "invconv_chain_workspace_bytes",
 )
 
 _lib = None
@@ -53,6 +53,12 @@ def lib() -> ctypes.CDLL:
         L.invconv_logdet.argtypes = [vp, ci, ci, ci, ci, vp, vp]
         L.invconv_probe_step_sync.argtypes = [ci, ci, ci, vp]
         L.invconv_probe_step_sync.restype = ci
+        L.invconv_chain_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+        L.invconv_chain_workspace_bytes.restype = sz
+        L.invconv_chain_fwd.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, sz, vp]
+        L.invconv_chain_fwd.restype = ci
+        L.invconv_chain_bwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, sz, vp]
+        L.invconv_chain_bwd.restype = ci
         L.invconv_status_string.argtypes = [ci]
         L.invconv_status_string.restype = ctypes.c_char_p
         L.invconv_version.restype = ci
@@ -138,3 +144,49 @@ def invconv_logdet(w: torch.Tensor, H: int, W: int, out: torch.Tensor | None = N
     if st != OK:
         raise InvconvError(st, "invconv_logdet")
     return res
+
+
+def _ptr_array(tensors):
+    return (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+
+
+def chain_workspace_bytes(L: int, B: int, C: int, H: int, W: int, k: int) -> int:
+    return int(lib().invconv_chain_workspace_bytes(L, B, C, H, W, k))
+
+
+def invconv_chain_fwd(y: torch.Tensor, ws: list, out: list | None = None, workspace: torch.Tensor | None = None):
+    """x[0] = invconv(y; ws[0]), x[l] = invconv(x[l-1]; ws[l]); returns the list of all x[l]."""
+    _check(y, "y")
+    for i, w in enumerate(ws):
+        _check(w, f"ws[{i}]", ws[0].shape)
+    B, C, H, W, k = _dims(y, ws[0])
+    L = len(ws)
+    xs = [torch.empty_like(y) for _ in range(L)] if out is None else [_check(t, "out", y.shape) for t in out]
+    need = chain_workspace_bytes(L, B, C, H, W, k)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=y.device)
+    st = lib().invconv_chain_fwd(y.data_ptr(), _ptr_array(ws), _ptr_array(xs), L, B, C, H, W, k,
+                                 workspace.data_ptr(), workspace.numel(), _stream())
+    if st != OK:
+        raise InvconvError(st, "invconv_chain_fwd")
+    return xs
+
+
+def invconv_chain_bwd(xs: list, ws: list, dLdx_last: torch.Tensor, workspace: torch.Tensor | None = None):
+    """(dL/dy of layer 0, [dL/dw of every layer]) for the stack evaluated by invconv_chain_fwd."""
+    _check(dLdx_last, "dLdx_last")
+    for i, (x, w) in enumerate(zip(xs, ws)):
+        _check(x, f"xs[{i}]", dLdx_last.shape), _check(w, f"ws[{i}]", ws[0].shape)
+    B, C, H, W, k = _dims(dLdx_last, ws[0])
+    L = len(ws)
+    dy = torch.empty_like(dLdx_last)
+    dws = [torch.empty_like(w) for w in ws]
+    need = chain_workspace_bytes(L, B, C, H, W, k)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dy.device)
+    st = lib().invconv_chain_bwd(_ptr_array(xs), _ptr_array(ws), dLdx_last.data_ptr(), dy.data_ptr(),
+                                 _ptr_array(dws), L, B, C, H, W, k, workspace.data_ptr(), workspace.numel(),
+                                 _stream())
+    if st != OK:
+        raise InvconvError(st, "invconv_chain_bwd")
+    return dy, dws

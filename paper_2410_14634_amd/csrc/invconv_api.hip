@@ -142,6 +142,140 @@ invconv_status invconv_logdet(const float *w, int C, int H, int W, int k, float 
     return launch_logdet(w, C, H, W, k, out, (hipStream_t)stream);
 }
 
+namespace {
+
+struct ChainLayout {
+    size_t flags_bytes, grad_bytes, dw_bytes, total;
+};
+
+bool chain_layout(int L, int B, int C, int H, int W, int k, ChainLayout *lay)
+{
+    if (L < 1 || L > kChainMaxLayers || check_shape(B, C, H, W, k) != INVCONV_OK)
+        return false;
+    const DwPlan p = plan_dw_any(B, C, H, W, k);
+    if (!p.rt)
+        return false;
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    lay->flags_bytes = up(chain_flag_ints(L, B) * sizeof(int));
+    lay->grad_bytes = up((size_t)B * C * H * W * sizeof(float));
+    lay->dw_bytes = up(p.bytes);
+    lay->total = lay->flags_bytes + (size_t)(L > 1 ? L - 1 : 0) * lay->grad_bytes + lay->dw_bytes;
+    return true;
+}
+
+}  // namespace
+
+size_t invconv_chain_workspace_bytes(int L, int B, int C, int H, int W, int k)
+{
+    ChainLayout lay;
+    return chain_layout(L, B, C, H, W, k, &lay) ? lay.total : 0;
+}
+
+invconv_status invconv_chain_fwd(const float *y, const float *const *w, float *const *x, int L, int B, int C, int H,
+                                 int W, int k, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!y || !w || !x)
+        return INVCONV_ERR_NULL;
+    if (L < 1 || L > kChainMaxLayers)
+        return INVCONV_ERR_SHAPE;
+    if (int s = check_shape(B, C, H, W, k))
+        return s;
+    for (int l = 0; l < L; ++l) {
+        if (!w[l] || !x[l])
+            return INVCONV_ERR_NULL;
+        if (x[l] == y)
+            return INVCONV_ERR_ALIAS;
+        for (int m = 0; m < l; ++m)
+            if (x[m] == x[l])
+                return INVCONV_ERR_ALIAS;
+    }
+    ChainLayout lay;
+    if (!chain_layout(L, B, C, H, W, k, &lay))
+        return INVCONV_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < lay.total)
+        return INVCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (chain_supported(L, C, H, k)) {
+        ChainArgs a{};
+        a.in0 = y;
+        for (int l = 0; l < L; ++l) {
+            a.w[l] = w[l];
+            a.out[l] = x[l];
+        }
+        a.flags = (int *)workspace;
+        a.stages = L;
+        a.B = B;
+        a.H = H;
+        a.W = W;
+        return launch_chain(0, a, C, k, st);
+    }
+    for (int l = 0; l < L; ++l)
+        if (int s = invconv_fwd(l == 0 ? y : x[l - 1], w[l], x[l], B, C, H, W, k, stream))
+            return s;
+    return INVCONV_OK;
+}
+
+invconv_status invconv_chain_bwd(const float *const *x, const float *const *w, const float *dLdx_last,
+                                 float *dLdy_first, float *const *dLdw, int L, int B, int C, int H, int W, int k,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || !w || !dLdx_last || !dLdy_first || !dLdw)
+        return INVCONV_ERR_NULL;
+    if (L < 1 || L > kChainMaxLayers)
+        return INVCONV_ERR_SHAPE;
+    if (int s = check_shape(B, C, H, W, k))
+        return s;
+    for (int l = 0; l < L; ++l) {
+        if (!w[l] || !x[l] || !dLdw[l])
+            return INVCONV_ERR_NULL;
+        if (x[l] == dLdy_first)
+            return INVCONV_ERR_ALIAS;
+    }
+    if (dLdy_first == dLdx_last)
+        return INVCONV_ERR_ALIAS;
+    ChainLayout lay;
+    if (!chain_layout(L, B, C, H, W, k, &lay))
+        return INVCONV_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < lay.total)
+        return INVCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    // v[l] = dL/dy of layer l: v[0] is the caller's output, the others live in the workspace
+    float *v[kChainMaxLayers];
+    v[0] = dLdy_first;
+    for (int l = 1; l < L; ++l)
+        v[l] = (float *)(ws + lay.flags_bytes + (size_t)(l - 1) * lay.grad_bytes);
+    float *part = (float *)(ws + lay.flags_bytes + (size_t)(L > 1 ? L - 1 : 0) * lay.grad_bytes);
+    if (chain_supported(L, C, H, k)) {
+        ChainArgs a{};
+        a.in0 = dLdx_last;
+        for (int s = 0; s < L; ++s) {       // stage s solves layer L-1-s
+            a.w[s] = w[L - 1 - s];
+            a.out[s] = v[L - 1 - s];
+        }
+        a.flags = (int *)workspace;
+        a.stages = L;
+        a.B = B;
+        a.H = H;
+        a.W = W;
+        if (int s = launch_chain(1, a, C, k, st))
+            return s;
+    } else {
+        for (int l = L - 1; l >= 0; --l)
+            if (int s = solve(1, l == L - 1 ? dLdx_last : v[l + 1], w[l], v[l], B, C, H, W, k, st, INVCONV_VARIANT_AUTO))
+                return s;
+    }
+    const DwPlan p = plan_dw_any(B, C, H, W, k);
+    const bool mfma = dw_mfma_supported(C, k) && plan_dw_mfma(B, C, H, W, k).rt;
+    for (int l = 0; l < L; ++l) {
+        const int s = mfma ? launch_dw_mfma(x[l], v[l], dLdw[l], part, p, B, C, H, W, k, st)
+                           : launch_dw(x[l], v[l], dLdw[l], part, p, B, C, H, W, k, st);
+        if (s)
+            return s;
+    }
+    return INVCONV_OK;
+}
+
 invconv_status invconv_probe_step_sync(int mode, int steps, int workgroups, void *stream)
 {
     if (mode < 0 || mode > 2)

@@ -46,6 +46,18 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k);
 int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
                    int W, int k, hipStream_t stream);
 DwPlan plan_dw_any(int B, int C, int H, int W, int k);
+constexpr int kChainMaxLayers = 16;
+struct ChainArgs {
+    const float *in0;                    // input of stage 0
+    const float *w[kChainMaxLayers];     // kernel of stage s
+    float *out[kChainMaxLayers];         // output of stage s = input of stage s+1
+    int *flags;                          // progress counters + error word (chain_flag_ints() ints)
+    int *err;                            // set by launch_chain
+    int stages, B, H, W, NB;
+};
+bool chain_supported(int stages, int C, int H, int k);
+size_t chain_flag_ints(int stages, int B);
+int launch_chain(int dir, ChainArgs args, int C, int k, hipStream_t stream);
 int launch_logdet(const float *w, int C, int H, int W, int k, float *out, hipStream_t stream);
 
 }  // namespace invconv

@@ -145,3 +145,69 @@ def test_chain_workload_parity():
         assert rel_err(host(dws[l]), dwr) <= TOL_DW
         assert float(host(lds[l])[0]) == pytest.approx(oracle.invconv_logdet(wl["w"][l], H, W), rel=1e-5)
     assert rel_err(host(g), gr) <= TOL_ACT
+
+
+CHAIN_SHAPES = [  # (L, B, C, H, W, k)
+    (1, 2, 12, 16, 16, 3), (3, 2, 12, 16, 20, 3), (2, 3, 12, 40, 9, 3), (4, 1, 8, 33, 31, 3),
+    (2, 2, 16, 128, 12, 3), (3, 2, 12, 7, 5, 3),
+    (2, 2, 3, 10, 10, 3),          # not covered by the pipelined kernel: falls back to per-layer launches
+]
+
+
+def oracle_chain(y, ws, g_last):
+    xs = [np.asarray(y, dtype=np.float64)]
+    for w in ws:
+        xs.append(oracle.invconv_fwd(xs[-1], w, THREADS))
+    return xs[1:]
+
+
+@pytest.mark.parametrize("shape", CHAIN_SHAPES)
+def test_chain_calls_match_oracle(shape):
+    import torch
+    L, B, C, H, W, k = shape
+    print(f"chain {shape}", flush=True)
+    cases = [inputs.make_case(B, C, H, W, k, seed=100 + l, tap_std=0.03) for l in range(L)]
+    ws = [cs["w"][0] for cs in cases]
+    y, g_last = cases[0]["y"], cases[0]["g"]
+    wd = [dev(w) for w in ws]
+    xs = b.invconv_chain_fwd(dev(y), wd)
+    dy, dws = b.invconv_chain_bwd(xs, wd, dev(g_last))
+    torch.cuda.synchronize()
+    xr = oracle_chain(y, ws, g_last)
+    for l in range(L):
+        assert rel_err(host(xs[l]), xr[l]) <= TOL_ACT, f"x of layer {l}"
+    # backward oracle on the GPU's own activations
+    gr = g_last.astype(np.float64)
+    for l in reversed(range(L)):
+        gr, dwr = oracle.invconv_bwd(host(xs[l]), ws[l], gr, THREADS)
+        assert rel_err(host(dws[l]), dwr) <= TOL_DW, f"dw of layer {l}"
+    assert rel_err(host(dy), gr) <= TOL_ACT
+
+
+def test_chain_workload4_matches_per_layer_calls_and_oracle():
+    import torch
+    wl = inputs.make_workload(4)
+    H, W = wl["H"], wl["W"]
+    wd = [dev(w) for w in wl["w"]]
+    yd = dev(wl["y"])
+    xs = b.invconv_chain_fwd(yd, wd)
+    dy, dws = b.invconv_chain_bwd(xs, wd, xs[-1])
+    torch.cuda.synchronize()
+    # per-layer calls of the plain API
+    acts = [yd]
+    for w in wd:
+        acts.append(b.invconv_fwd(acts[-1], w))
+    g = acts[-1]
+    dws2 = [None] * len(wd)
+    for l in reversed(range(len(wd))):
+        g, dws2[l] = b.invconv_bwd(acts[l + 1], wd[l], g)
+    torch.cuda.synchronize()
+    for l in range(len(wd)):
+        assert rel_err(host(xs[l]), host(acts[l + 1])) <= 1e-5
+        assert rel_err(host(dws[l]), host(dws2[l])) <= 1e-4
+    assert rel_err(host(dy), host(g)) <= 1e-5
+    # and the oracle for the forward chain (the backward chain is covered by test_chain_workload_parity)
+    xr = wl["y"].astype(np.float64)
+    for l, w in enumerate(wl["w"]):
+        xr = oracle.invconv_fwd(xr, w, THREADS)
+        assert rel_err(host(xs[l]), xr) <= TOL_ACT
