@@ -74,6 +74,13 @@ class Layered:
         self.need = need
         self.lib = b.lib()
         self.n_elems = self.B * self.C * self.H * self.W
+        if self.L > 1:
+            # stacked layers go through the chain entry points (host arrays of device pointers)
+            import ctypes
+            arr = lambda ts: (ctypes.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+            self.p_w, self.p_x, self.p_dw = arr(self.ws_d), arr(self.acts[1:]), arr(self.dws)
+            self.cneed = b.chain_workspace_bytes(self.L, self.B, self.C, self.H, self.W, self.k)
+            self.cws = torch.empty(max(self.cneed, 256), dtype=torch.uint8, device="cuda")
 
     # raw C-ABI calls: pointers and sizes only
     def fwd_layer(self, l, stream):
@@ -93,11 +100,22 @@ class Layered:
         assert st == 0, self.b.status_string(st)
 
     def fwd_all(self, stream):
+        if self.L > 1 and self.variant == 0:
+            st = self.lib.invconv_chain_fwd(self.acts[0].data_ptr(), self.p_w, self.p_x, self.L, self.B, self.C,
+                                            self.H, self.W, self.k, self.cws.data_ptr(), self.cneed, stream)
+            assert st == 0, self.b.status_string(st)
+            return
         for l in range(self.L):
             self.fwd_layer(l, stream)
 
     def bwd_all(self, stream):
         # single layer: upstream gradient is the seeded dL/dx; chain: dL/dx_L = x_L (loss 0.5*sum x^2)
+        if self.L > 1 and self.variant == 0:
+            st = self.lib.invconv_chain_bwd(self.p_x, self.p_w, self.acts[self.L].data_ptr(), self.grads[0].data_ptr(),
+                                            self.p_dw, self.L, self.B, self.C, self.H, self.W, self.k,
+                                            self.cws.data_ptr(), self.cneed, stream)
+            assert st == 0, self.b.status_string(st)
+            return
         gin = self.g0 if self.L == 1 else self.acts[self.L]
         for i, l in enumerate(reversed(range(self.L))):
             gout = self.grads[i % 2]

@@ -158,7 +158,7 @@ bool chain_layout(int L, int B, int C, int H, int W, int k, ChainLayout *lay)
     auto up = [](size_t v) { return (v + 255) / 256 * 256; };
     lay->flags_bytes = up(chain_flag_ints(L, B) * sizeof(int));
     lay->grad_bytes = up((size_t)B * C * H * W * sizeof(float));
-    lay->dw_bytes = up(p.bytes);
+    lay->dw_bytes = up(p.bytes) * (size_t)L;      // pass 1 of all layers runs as one launch
     lay->total = lay->flags_bytes + (size_t)(L > 1 ? L - 1 : 0) * lay->grad_bytes + lay->dw_bytes;
     return true;
 }
@@ -267,6 +267,8 @@ invconv_status invconv_chain_bwd(const float *const *x, const float *const *w, c
     }
     const DwPlan p = plan_dw_any(B, C, H, W, k);
     const bool mfma = dw_mfma_supported(C, k) && plan_dw_mfma(B, C, H, W, k).rt;
+    if (mfma)
+        return launch_dw_mfma_layers(x, v, dLdw, L, part, p, B, C, H, W, k, st);
     for (int l = 0; l < L; ++l) {
         const int s = mfma ? launch_dw_mfma(x[l], v[l], dLdw[l], part, p, B, C, H, W, k, st)
                            : launch_dw(x[l], v[l], dLdw[l], part, p, B, C, H, W, k, st);

@@ -19,8 +19,11 @@
 //                   into the ring, after waiting for the producer stage's
 //                   progress counter;
 //   2 storer waves  drain finished results from the ring to global memory in
-//                   the same blocks, then publish the stage's progress
-//                   (release fence + counter store, agent scope).
+//                   the same blocks, then publish the stage's progress.
+// Data that crosses workgroups is written and read with agent-scope (device-
+// coherent) stores and loads, so publishing needs no cache write-back or
+// invalidate: the storer waits until all its stores are acknowledged and then
+// advances the counter; the loader reads the counter and only then issues loads.
 // The ring is indexed by the global step t (slot t mod 16) and is skew-free:
 // at step t every row of a band touches slot t, whatever its column, so its
 // length covers only the load lead and the store lag, not the 16-column skew of
@@ -137,6 +140,8 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
     constexpr int kStep = DIR ? -4 : 4;
     int seen = (stage == 0 || a.flags == nullptr) ? kCDone : 0;   // producer progress known so far
     const int *pflag = (stage > 0 && a.flags) ? a.flags + ((size_t)(stage - 1) * a.B + n_img) * 2 + iox : nullptr;
+    const bool coherent = stage > 0;
+    int pending = -1;                                          // storer: progress value not yet published
     int *myflag = a.flags ? a.flags + ((size_t)stage * a.B + n_img) * 2 + iox : nullptr;
 
     const int t_last = (NB - 1) * (16 + kCDelay) + span;       // one past the last active step of any band
@@ -213,6 +218,19 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][db][jj], xh[jj][db], acc, 0, 0, 0);
                 own = acc;
             }
+        } else if (io >= 2 && (t & (kCBlk - 1)) == 2) {
+            // ---- storer, two steps after a drain: the stores have had time to complete, so the
+            // wait below does not hold up the workgroup's barrier for long
+            if (myflag && pending >= 0) {
+                // every store of the block was an agent-scope (device-coherent) store: once all of
+                // them have been acknowledged the counter may be advanced
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0);
+                asm volatile("" ::: "memory");
+                if (lane == 0)
+                    __hip_atomic_store(myflag, pending, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                pending = -1;
+            }
         } else if ((t & (kCBlk - 1)) == 0) {
             if (io < 2) {
                 // ---- loader: write the block fetched one round ago, then fetch the next one
@@ -247,7 +265,7 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
                             v = kCDone;
                         }
                         seen = v;
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                        asm volatile("" ::: "memory");   // the loads below are issued after the counter was read
                     }
 #pragma unroll
                     for (int bi = 0; bi < kMaxIoBands; ++bi) {
@@ -264,14 +282,17 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
                                 for (int ch = 0; ch < C; ++ch) {
                                     const char *base = reinterpret_cast<const char *>(
                                         in + img + (size_t)(DIR ? C - 1 - ch : ch) * H * W);
-                                    lreg[bi][ch] = *reinterpret_cast<const float *>(base + off);
+                                    const float *src = reinterpret_cast<const float *>(base + off);
+                                    // what another workgroup of this launch wrote is read device-coherently
+                                    lreg[bi][ch] = coherent ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                                            : *src;
                                 }
                             }
                         }
                     }
                 }
             } else {
-                // ---- storer: drain block [t-4, t) and publish progress
+                // ---- storer: drain block [t-4, t); its progress is published two steps later
                 const int us = t - kCBlk;
                 if (us >= 0) {
 #pragma unroll
@@ -294,23 +315,29 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
                                     for (int ch = 0; ch < C; ++ch) {
                                         char *base = reinterpret_cast<char *>(
                                             out + img + (size_t)(DIR ? C - 1 - ch : ch) * H * W);
-                                        *reinterpret_cast<float *>(base + off) = val[ch];
+                                        float *dst = reinterpret_cast<float *>(base + off);
+                                        if (myflag)     // another workgroup of this launch will read it
+                                            __hip_atomic_store(dst, val[ch], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                        else
+                                            *dst = val[ch];
                                     }
                                 }
                             }
                         }
                     }
-                    if (myflag) {
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-                        if (lane == 0)
-                            __hip_atomic_store(myflag, (t >= t_last) ? kCDone : t, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT);
-                    }
+                    pending = (t >= t_last) ? kCDone : t;
                 }
             }
         }
         (void)kStep;
         __syncthreads();
+    }
+    if (!is_compute && io >= 2 && myflag && pending >= 0) {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0);
+        asm volatile("" ::: "memory");
+        if (lane == 0)
+            __hip_atomic_store(myflag, pending, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 

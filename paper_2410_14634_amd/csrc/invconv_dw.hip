@@ -18,35 +18,30 @@ namespace invconv {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Pointers of up to kChainMaxLayers independent (x, v) pairs handled by one launch.
+struct DwBatch {
+    const float *x[kChainMaxLayers];
+    const float *v[kChainMaxLayers];
+};
+
+constexpr int kDwHalo = 4;      // left halo of the x tile, in columns (>= k-1, keeps rows 16-byte aligned)
+
 template <int NS>
-__global__ __launch_bounds__(256) void k_dw_partial_mfma(const float *__restrict__ x, const float *__restrict__ v,
-                                                        float *__restrict__ part, int C, int H, int W, int k,
-                                                        int RT, int nchunks)
+__global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *__restrict__ part, int B, int C,
+                                                        int H, int W, int k, int RT, int nchunks, int G, int vec)
 {
     extern __shared__ float smem[];
-    const int n = blockIdx.x / nchunks, chunk = blockIdx.x % nchunks;
-    const int r0 = chunk * RT;
-    const int rows = (H - r0 < RT) ? H - r0 : RT;
-    const int XR = RT + k - 1, XW = W + k - 1;
+    // blockIdx = ((layer * B + n) * G + cg); this workgroup takes chunks cg, cg+G, ... of image n
+    const int cg = blockIdx.x % G, n = (blockIdx.x / G) % B, layer = blockIdx.x / (G * B);
+    const float *__restrict__ x = batch.x[layer];
+    const float *__restrict__ v = batch.v[layer];
+    const int XR = RT + k - 1, XW = W + kDwHalo;
     const int NCOL = C * k * k;
     const int P = C * NCOL;
     float *sv = smem;                 // [C][RT][W]
-    float *sx = sv + C * RT * W;      // [C][XR][XW], origin at (r0-(k-1), -(k-1))
+    float *sx = sv + C * RT * W;      // [C][XR][XW], origin at (r0-(k-1), -kDwHalo)
     float *sred = smem;               // [4 waves][64 lanes][NS*4], reuses the tiles afterwards
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-
-    for (int idx = tid; idx < C * rows * W; idx += 256) {
-        const int c = idx % W, r = (idx / W) % rows, ch = idx / (W * rows);
-        sv[(ch * RT + r) * W + c] = v[(((size_t)n * C + ch) * H + r0 + r) * W + c];
-    }
-    const int xrows = rows + k - 1;
-    for (int idx = tid; idx < C * xrows * XW; idx += 256) {
-        const int cc = idx % XW, rr = (idx / XW) % xrows, ch = idx / (XW * xrows);
-        const int gr = r0 - (k - 1) + rr, gc = cc - (k - 1);
-        sx[(ch * XR + rr) * XW + cc] =
-            (gr >= 0 && gc >= 0) ? x[(((size_t)n * C + ch) * H + gr) * W + gc] : 0.0f;
-    }
-    __syncthreads();
 
     const int nn = lane & 15, kk = lane >> 4;
     const int aoff = (nn < C ? nn : 0) * RT * W;            // A row m = nn -> v[o = m]
@@ -55,25 +50,64 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(const float *__restrict
     for (int s = 0; s < NS; ++s) {
         const int col = (16 * s + nn < NCOL) ? 16 * s + nn : 0;
         const int i = col / (k * k), a = (col / k) % k, b = col % k;
-        boff[s] = (i * XR + a) * XW + b;
+        boff[s] = (i * XR + a) * XW + b + kDwHalo - (k - 1);
     }
     f32x4 acc[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s)
         acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int npix = rows * W;
-    const int ngroups = (npix + 3) / 4;
-    for (int q = wave; q < ngroups; q += 4) {
-        const int p = 4 * q + kk;
-        const bool pv = p < npix;
-        const int pr = pv ? p / W : 0, pc = pv ? p - pr * W : 0;
-        const float avl = sv[aoff + pr * W + pc];
-        const float av = pv ? avl : 0.0f;       // pixels past the end contribute nothing
-        const float *bp = sx + pr * XW + pc;
+    for (int chunk = cg; chunk < nchunks; chunk += G) {
+        const int r0 = chunk * RT;
+        const int rows = (H - r0 < RT) ? H - r0 : RT;
+        const int xrows = rows + k - 1;
+        __syncthreads();        // previous chunk's products are done with the tiles
+        if (vec) {
+            const int W4 = W / 4;
+            for (int idx = tid; idx < C * rows * W4; idx += 256) {
+                const int c4 = idx % W4, rr = idx / W4;         // rr = ch*rows + r
+                const int ch = rr / rows, r = rr - ch * rows;
+                const float4 val = *reinterpret_cast<const float4 *>(
+                    v + (((size_t)n * C + ch) * H + r0 + r) * W + 4 * c4);
+                *reinterpret_cast<float4 *>(sv + (ch * RT + r) * W + 4 * c4) = val;
+            }
+            const int X4 = XW / 4;                              // first float4 of a row is the halo
+            for (int idx = tid; idx < C * xrows * X4; idx += 256) {
+                const int c4 = idx % X4, rr = idx / X4;
+                const int ch = rr / xrows, r = rr - ch * xrows;
+                const int gr = r0 - (k - 1) + r;
+                float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (gr >= 0 && c4 > 0)
+                    val = *reinterpret_cast<const float4 *>(x + (((size_t)n * C + ch) * H + gr) * W + 4 * (c4 - 1));
+                *reinterpret_cast<float4 *>(sx + (ch * XR + r) * XW + 4 * c4) = val;
+            }
+        } else {
+            for (int idx = tid; idx < C * rows * W; idx += 256) {
+                const int c = idx % W, r = (idx / W) % rows, ch = idx / (W * rows);
+                sv[(ch * RT + r) * W + c] = v[(((size_t)n * C + ch) * H + r0 + r) * W + c];
+            }
+            for (int idx = tid; idx < C * xrows * XW; idx += 256) {
+                const int cc = idx % XW, rr = (idx / XW) % xrows, ch = idx / (XW * xrows);
+                const int gr = r0 - (k - 1) + rr, gc = cc - kDwHalo;
+                sx[(ch * XR + rr) * XW + cc] =
+                    (gr >= 0 && gc >= 0) ? x[(((size_t)n * C + ch) * H + gr) * W + gc] : 0.0f;
+            }
+        }
+        __syncthreads();
+
+        const int npix = rows * W;
+        const int ngroups = (npix + 3) / 4;
+        for (int q = wave; q < ngroups; q += 4) {
+            const int p = 4 * q + kk;
+            const bool pv = p < npix;
+            const int pr = pv ? p / W : 0, pc = pv ? p - pr * W : 0;
+            const float avl = sv[aoff + pr * W + pc];
+            const float av = pv ? avl : 0.0f;       // pixels past the end contribute nothing
+            const float *bp = sx + pr * XW + pc;
 #pragma unroll
-        for (int s = 0; s < NS; ++s)
-            acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bp[boff[s]], acc[s], 0, 0, 0);
+            for (int s = 0; s < NS; ++s)
+                acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bp[boff[s]], acc[s], 0, 0, 0);
+        }
     }
     __syncthreads();        // tiles no longer needed
     // lane (nn, g = kk) register (s, j) holds entry (o = 4g + j, col = 16s + nn)
@@ -100,63 +134,101 @@ bool dw_mfma_supported(int C, int k)
 }
 
 // Row chunking of pass 1: tiles (or the reduction buffer that reuses them) must fit the LDS budget.
+// p.nparts = B * G partial rows per layer, G workgroups per image each looping over chunks.
 DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
 {
     DwPlan p{};
-    if (!dw_mfma_supported(C, k))
+    if (!dw_mfma_supported(C, k) || k - 1 > kDwHalo)
         return p;
     const size_t P = (size_t)C * C * k * k;
     const size_t NS = ((size_t)C * k * k + 15) / 16;
     const size_t red = 256 * NS * 4;
+    const size_t XW = (size_t)W + kDwHalo;
     auto lds_for = [&](int rt) {
-        const size_t tiles = (size_t)C * rt * W + (size_t)C * (rt + k - 1) * (W + k - 1);
+        const size_t tiles = (size_t)C * rt * W + (size_t)C * (rt + k - 1) * XW;
         return sizeof(float) * (tiles > red ? tiles : red);
     };
     if (lds_for(1) > kDwLdsBudget)
         return p;
-    int want = (int)((2048 + B - 1) / B);          // aim for a few workgroups per compute unit
-    if (want < 1) want = 1;
-    int rt = (H + want - 1) / want;
-    if (rt < 1) rt = 1;
+    int rt = H < 8 ? H : 8;
     while (rt > 1 && lds_for(rt) > kDwLdsBudget)
         --rt;
     p.rt = rt;
     p.nchunks = (H + rt - 1) / rt;
-    p.nparts = (size_t)B * p.nchunks;
+    int g = (1024 + B - 1) / B;                     // about a thousand workgroups per layer at most
+    if (g > p.nchunks) g = p.nchunks;
+    if (g < 1) g = 1;
+    p.groups = g;
+    p.nparts = (size_t)B * g;
     p.lds = lds_for(rt);
     p.bytes = ((p.nparts * P * sizeof(float)) + 255) / 256 * 256;
     return p;
 }
 
 template <int NS>
-static void launch_ns(const float *x, const float *v, float *part, const DwPlan &p, int C, int H, int W, int k,
-                      hipStream_t stream)
+static void launch_ns(const DwBatch &batch, int layers, float *part, const DwPlan &p, int B, int C, int H, int W,
+                      int k, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_dw_partial_mfma<NS>, dim3((unsigned)p.nparts), dim3(256), p.lds, stream, x, v, part, C, H,
-                       W, k, p.rt, p.nchunks);
+    // 16-byte tile loads need rows that start on 16-byte boundaries
+    int vec = (W % 4) == 0;
+    for (int l = 0; l < layers; ++l)
+        if (((size_t)batch.x[l] | (size_t)batch.v[l]) & 15)
+            vec = 0;
+    hipLaunchKernelGGL(k_dw_partial_mfma<NS>, dim3((unsigned)(p.nparts * layers)), dim3(256), p.lds, stream, batch,
+                       part, B, C, H, W, k, p.rt, p.nchunks, p.groups, vec);
+}
+
+// Pass 1 for `layers` independent (x, v) pairs in one launch; part holds layers * p.nparts rows.
+static int launch_dw_partial_batch(const DwBatch &batch, int layers, float *part, const DwPlan &p, int B, int C,
+                                   int H, int W, int k, hipStream_t stream)
+{
+    const int ns = (C * k * k + 15) / 16;
+    switch (ns) {
+    case 1: launch_ns<1>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 2: launch_ns<2>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 3: launch_ns<3>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 4: launch_ns<4>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 5: launch_ns<5>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 6: launch_ns<6>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 7: launch_ns<7>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 8: launch_ns<8>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 9: launch_ns<9>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 10: launch_ns<10>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    default: return INVCONV_ERR_UNSUPPORTED;
+    }
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
 int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
                    int W, int k, hipStream_t stream)
 {
-    (void)B;
-    const int ns = (C * k * k + 15) / 16;
-    switch (ns) {
-    case 1: launch_ns<1>(x, v, part, p, C, H, W, k, stream); break;
-    case 2: launch_ns<2>(x, v, part, p, C, H, W, k, stream); break;
-    case 3: launch_ns<3>(x, v, part, p, C, H, W, k, stream); break;
-    case 4: launch_ns<4>(x, v, part, p, C, H, W, k, stream); break;
-    case 5: launch_ns<5>(x, v, part, p, C, H, W, k, stream); break;
-    case 6: launch_ns<6>(x, v, part, p, C, H, W, k, stream); break;
-    case 7: launch_ns<7>(x, v, part, p, C, H, W, k, stream); break;
-    case 8: launch_ns<8>(x, v, part, p, C, H, W, k, stream); break;
-    case 9: launch_ns<9>(x, v, part, p, C, H, W, k, stream); break;
-    case 10: launch_ns<10>(x, v, part, p, C, H, W, k, stream); break;
-    default: return INVCONV_ERR_UNSUPPORTED;
-    }
-    if (hipGetLastError() != hipSuccess)
-        return INVCONV_ERR_LAUNCH;
+    DwBatch batch{};
+    batch.x[0] = x;
+    batch.v[0] = v;
+    if (int s = launch_dw_partial_batch(batch, 1, part, p, B, C, H, W, k, stream))
+        return s;
     return launch_dw_reduce(part, (int)p.nparts, dw, C, k, stream);
+}
+
+// dL/dw of `layers` layers: one pass-1 launch over all of them, then one pass 2 per layer.
+// part must hold layers * p.bytes bytes.
+int launch_dw_mfma_layers(const float *const *x, const float *const *v, float *const *dw, int layers, float *part,
+                          const DwPlan &p, int B, int C, int H, int W, int k, hipStream_t stream)
+{
+    if (layers < 1 || layers > kChainMaxLayers)
+        return INVCONV_ERR_SHAPE;
+    DwBatch batch{};
+    for (int l = 0; l < layers; ++l) {
+        batch.x[l] = x[l];
+        batch.v[l] = v[l];
+    }
+    if (int s = launch_dw_partial_batch(batch, layers, part, p, B, C, H, W, k, stream))
+        return s;
+    const size_t P = (size_t)C * C * k * k;
+    for (int l = 0; l < layers; ++l)
+        if (int s = launch_dw_reduce(part + (size_t)l * p.nparts * P, (int)p.nparts, dw[l], C, k, stream))
+            return s;
+    return INVCONV_OK;
 }
 
 }  // namespace invconv

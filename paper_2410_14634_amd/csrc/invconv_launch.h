@@ -11,10 +11,12 @@ constexpr int kSolveBlock = 256;
 constexpr int kDwBlock = 256;
 constexpr size_t kMaxLdsBytes = 160 * 1024;   // LDS per workgroup on gfx950
 constexpr size_t kDwLdsBudget = 64 * 1024;
+constexpr int kChainMaxLayers = 16;
 
 struct DwPlan {
     int rt;          // rows per chunk (0 = shape unsupported)
     int nchunks;     // chunks per image
+    int groups;      // matrix-core pass 1: workgroups per image, each looping over chunks
     size_t nparts;   // workgroups of pass 1 = rows of the partial-sum matrix
     size_t lds;      // dynamic LDS bytes of pass 1
     size_t bytes;    // workspace bytes
@@ -45,8 +47,9 @@ bool dw_mfma_supported(int C, int k);
 DwPlan plan_dw_mfma(int B, int C, int H, int W, int k);
 int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
                    int W, int k, hipStream_t stream);
+int launch_dw_mfma_layers(const float *const *x, const float *const *v, float *const *dw, int layers, float *part,
+                          const DwPlan &p, int B, int C, int H, int W, int k, hipStream_t stream);
 DwPlan plan_dw_any(int B, int C, int H, int W, int k);
-constexpr int kChainMaxLayers = 16;
 struct ChainArgs {
     const float *in0;                    // input of stage 0
     const float *w[kChainMaxLayers];     // kernel of stage s
