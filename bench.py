@@ -123,6 +123,11 @@ class Layered:
             gin = gout
 
     def logdet_all(self, stream):
+        if self.L > 1 and self.variant == 0:
+            st = self.lib.invconv_chain_logdet(self.p_w, self.L, self.C, self.H, self.W, self.k,
+                                               self.lds.data_ptr(), stream)
+            assert st == 0, self.b.status_string(st)
+            return
         for l in range(self.L):
             self.logdet_layer(l, stream)
 

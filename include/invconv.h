@@ -129,6 +129,10 @@ invconv_status invconv_chain_bwd(const float *const *x, const float *const *w, c
                                  int B, int C, int H, int W, int k,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
+/* invconv_logdet for every layer of a stack in one launch: out[l] = log|det| of layer l (L device floats). */
+invconv_status invconv_chain_logdet(const float *const *w, int L, int C, int H, int W, int k,
+                                    float *out, void *stream);
+
 /* Bytes of scratch the two chain calls need (0 if the shape is invalid or unsupported). */
 size_t invconv_chain_workspace_bytes(int L, int B, int C, int H, int W, int k);
 

@@ -22,7 +22,7 @@ VARIANT_AUTO, VARIANT_BLOCK, VARIANT_DIAG_LAUNCH, VARIANT_WAVE, VARIANT_BAND, VA
 EXPORTS = (
     "invconv_fwd", "invconv_bwd", "invconv_bwd_workspace_bytes", "invconv_logdet",
     "invconv_fwd_ex", "invconv_bwd_ex", "invconv_status_string", "invconv_version",
-    "invconv_probe_step_sync", "invconv_chain_fwd", "invconv_chain_bwd", "invconv_chain_workspace_bytes",
+    "invconv_probe_step_sync", "invconv_chain_fwd", "invconv_chain_bwd", "invconv_chain_workspace_bytes", "invconv_chain_logdet",
 )
 
 _lib = None
@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.invconv_chain_fwd.restype = ci
         L.invconv_chain_bwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, sz, vp]
         L.invconv_chain_bwd.restype = ci
+        L.invconv_chain_logdet.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
+        L.invconv_chain_logdet.restype = ci
         L.invconv_status_string.argtypes = [ci]
         L.invconv_status_string.restype = ctypes.c_char_p
         L.invconv_version.restype = ci
@@ -190,3 +192,15 @@ def invconv_chain_bwd(xs: list, ws: list, dLdx_last: torch.Tensor, workspace: to
     if st != OK:
         raise InvconvError(st, "invconv_chain_bwd")
     return dy, dws
+
+
+def invconv_chain_logdet(ws: list, H: int, W: int) -> torch.Tensor:
+    """log|det dx/dy| of every layer of a stack (tensor of len(ws) floats)."""
+    for i, w in enumerate(ws):
+        _check(w, f"ws[{i}]", ws[0].shape)
+    res = torch.empty(len(ws), dtype=torch.float32, device=ws[0].device)
+    st = lib().invconv_chain_logdet(_ptr_array(ws), len(ws), ws[0].shape[0], H, W, ws[0].shape[2],
+                                    res.data_ptr(), _stream())
+    if st != OK:
+        raise InvconvError(st, "invconv_chain_logdet")
+    return res

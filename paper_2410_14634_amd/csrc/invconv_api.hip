@@ -287,6 +287,21 @@ invconv_status invconv_probe_step_sync(int mode, int steps, int workgroups, void
     return launch_probe(mode, steps, workgroups, (hipStream_t)stream);
 }
 
+invconv_status invconv_chain_logdet(const float *const *w, int L, int C, int H, int W, int k, float *out,
+                                    void *stream)
+{
+    if (!w || !out)
+        return INVCONV_ERR_NULL;
+    if (L < 1 || L > kChainMaxLayers)
+        return INVCONV_ERR_SHAPE;
+    if (int s = check_shape(1, C, H, W, k))
+        return s;
+    for (int l = 0; l < L; ++l)
+        if (!w[l])
+            return INVCONV_ERR_NULL;
+    return launch_logdet_layers(w, L, C, H, W, k, out, (hipStream_t)stream);
+}
+
 const char *invconv_status_string(invconv_status status)
 {
     switch (status) {

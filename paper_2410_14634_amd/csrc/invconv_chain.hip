@@ -17,7 +17,7 @@
 //   2 loader waves  fetch the input in blocks of 4 steps (16 rows x 4 columns
 //                   per instruction, so a row contributes 16 contiguous bytes)
 //                   into the ring, after waiting for the producer stage's
-//                   progress counter;
+//                   progress counter; each handles one of its bands per step;
 //   2 storer waves  drain finished results from the ring to global memory in
 //                   the same blocks, then publish the stage's progress.
 // Data that crosses workgroups is written and read with agent-scope (device-
@@ -141,12 +141,11 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
     int seen = (stage == 0 || a.flags == nullptr) ? kCDone : 0;   // producer progress known so far
     const int *pflag = (stage > 0 && a.flags) ? a.flags + ((size_t)(stage - 1) * a.B + n_img) * 2 + iox : nullptr;
     const bool coherent = stage > 0;
-    int pending = -1;                                          // storer: progress value not yet published
     int *myflag = a.flags ? a.flags + ((size_t)stage * a.B + n_img) * 2 + iox : nullptr;
 
     const int t_last = (NB - 1) * (16 + kCDelay) + span;       // one past the last active step of any band
-    const int t_end = (t_last + kCBlk - 1) / kCBlk * kCBlk + 1; // storers flush block [t-4,t) at step t
-    for (int t = -kCLead; t < t_end; ++t) {
+    const int t_end = t_last + kCBlk;                          // a band's last steps are drained up to 4 steps later
+    for (int t = -(kCLead + kCBlk); t < t_end; ++t) {
         if (is_compute) {
             const int tau = t - tf_c;
             const int c = tau - nrow;
@@ -218,126 +217,111 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][db][jj], xh[jj][db], acc, 0, 0, 0);
                 own = acc;
             }
-        } else if (io >= 2 && (t & (kCBlk - 1)) == 2) {
-            // ---- storer, two steps after a drain: the stores have had time to complete, so the
-            // wait below does not hold up the workgroup's barrier for long
-            if (myflag && pending >= 0) {
-                // every store of the block was an agent-scope (device-coherent) store: once all of
-                // them have been acknowledged the counter may be advanced
+        } else if (io < 2) {
+            // ---- loader: the band whose turn it is (one band per step, so the work is spread
+            // evenly): write the block fetched four steps ago, then fetch the next one
+            const int uw = t + kCLead - kCBlk;          // first step of the block to write
+            const int ul = t + kCLead;                  // first step of the block to fetch
+#pragma unroll
+            for (int bi = 0; bi < kMaxIoBands; ++bi) {
+                const int b = iox + 2 * bi;
+                if (bi == (t & (kMaxIoBands - 1)) && b < NB) {
+                    const int tf = b * (16 + kCDelay);
+                    if (uw + kCBlk > tf && uw < tf + span) {
+                        const int slot = (uw + jblk) & (kCRing - 1);
+#pragma unroll
+                        for (int ch = 0; ch < C; ++ch)
+                            ring[((b * C + ch) * kCRing + slot) * 16 + nrow] = lreg[bi][ch];
+                    }
+                    if (ul + kCBlk > tf && ul < tf + span) {
+                        if (seen < ul + kCBlk) {
+                            // wait until the producer stage has stored every step below ul + kCBlk
+                            int spins = 0, v = 0;
+                            do {
+                                v = __hip_atomic_load(pflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                if (v >= ul + kCBlk)
+                                    break;
+                                __builtin_amdgcn_s_sleep(8);
+                            } while (++spins < kCSpinLimit);
+                            if (v < ul + kCBlk) {
+                                if (a.err)
+                                    a.err[0] = 1;       // bounded wait ran out: carry on, results are invalid
+                                v = kCDone;
+                            }
+                            seen = v;
+                            asm volatile("" ::: "memory");   // the loads below are issued after the counter was read
+                        }
+                        int row = b * 16 + nrow;
+                        row = row < H ? row : H - 1;
+                        int cc = (ul + jblk - tf) - nrow;
+                        cc = cc < 0 ? 0 : (cc > W - 1 ? W - 1 : cc);
+                        const unsigned off = 4u * (unsigned)(DIR ? (H - 1 - row) * W + (W - 1 - cc) : row * W + cc);
+#pragma unroll
+                        for (int ch = 0; ch < C; ++ch) {
+                            const char *base = reinterpret_cast<const char *>(
+                                in + img + (size_t)(DIR ? C - 1 - ch : ch) * H * W);
+                            const float *src = reinterpret_cast<const float *>(base + off);
+                            // what another workgroup of this launch wrote is read device-coherently
+                            lreg[bi][ch] = coherent ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                                    : *src;
+                        }
+                    }
+                }
+            }
+        } else {
+            // ---- storer.  First publish: the stores issued in earlier steps were agent-scope
+            // (device-coherent) stores and have had at least a step to complete; once they are all
+            // acknowledged, every band of this wave has drained all steps below t - 4.
+            if (myflag && t - kCBlk > 0) {
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_s_waitcnt(0);
                 asm volatile("" ::: "memory");
                 if (lane == 0)
-                    __hip_atomic_store(myflag, pending, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                pending = -1;
+                    __hip_atomic_store(myflag, t - kCBlk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-        } else if ((t & (kCBlk - 1)) == 0) {
-            if (io < 2) {
-                // ---- loader: write the block fetched one round ago, then fetch the next one
-                const int uw = t + kCLead - kCBlk;          // first step of the block to write
-                const int ul = t + kCLead;                  // first step of the block to fetch
+            // then drain block [t-4, t) of the band whose turn it is
+            const int us = t - kCBlk;
 #pragma unroll
-                for (int bi = 0; bi < kMaxIoBands; ++bi) {
-                    const int b = iox + 2 * bi;
-                    if (b < NB) {
-                        const int tf = b * (16 + kCDelay);
-                        if (uw + kCBlk > tf && uw < tf + span) {
-                            const int slot = (uw + jblk) & (kCRing - 1);
+            for (int bi = 0; bi < kMaxIoBands; ++bi) {
+                const int b = iox + 2 * bi;
+                if (bi == (t & (kMaxIoBands - 1)) && b < NB) {
+                    const int tf = b * (16 + kCDelay);
+                    if (us + kCBlk > tf && us < tf + span) {
+                        const int row = b * 16 + nrow;
+                        const int cc = (us + jblk - tf) - nrow;
+                        const int slot = (us + jblk) & (kCRing - 1);
+                        float val[C];
 #pragma unroll
-                            for (int ch = 0; ch < C; ++ch)
-                                ring[((b * C + ch) * kCRing + slot) * 16 + nrow] = lreg[bi][ch];
-                        }
-                    }
-                }
-                if (ul < t_last) {
-                    if (seen < ul + kCBlk) {
-                        // wait until the producer stage has stored every step below ul + kCBlk
-                        int spins = 0, v = 0;
-                        do {
-                            v = __hip_atomic_load(pflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            if (v >= ul + kCBlk)
-                                break;
-                            __builtin_amdgcn_s_sleep(8);
-                        } while (++spins < kCSpinLimit);
-                        if (v < ul + kCBlk) {
-                            if (a.err)
-                                a.err[0] = 1;       // bounded wait ran out: carry on, results are invalid
-                            v = kCDone;
-                        }
-                        seen = v;
-                        asm volatile("" ::: "memory");   // the loads below are issued after the counter was read
-                    }
+                        for (int ch = 0; ch < C; ++ch)
+                            val[ch] = ring[((b * C + ch) * kCRing + slot) * 16 + nrow];
+                        if (row < H && (unsigned)cc < (unsigned)W) {
+                            const unsigned off =
+                                4u * (unsigned)(DIR ? (H - 1 - row) * W + (W - 1 - cc) : row * W + cc);
 #pragma unroll
-                    for (int bi = 0; bi < kMaxIoBands; ++bi) {
-                        const int b = iox + 2 * bi;
-                        if (b < NB) {
-                            const int tf = b * (16 + kCDelay);
-                            if (ul + kCBlk > tf && ul < tf + span) {
-                                int row = b * 16 + nrow;
-                                row = row < H ? row : H - 1;
-                                int cc = (ul + jblk - tf) - nrow;
-                                cc = cc < 0 ? 0 : (cc > W - 1 ? W - 1 : cc);
-                                const unsigned off = 4u * (unsigned)(DIR ? (H - 1 - row) * W + (W - 1 - cc) : row * W + cc);
-#pragma unroll
-                                for (int ch = 0; ch < C; ++ch) {
-                                    const char *base = reinterpret_cast<const char *>(
-                                        in + img + (size_t)(DIR ? C - 1 - ch : ch) * H * W);
-                                    const float *src = reinterpret_cast<const float *>(base + off);
-                                    // what another workgroup of this launch wrote is read device-coherently
-                                    lreg[bi][ch] = coherent ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                                            : *src;
-                                }
+                            for (int ch = 0; ch < C; ++ch) {
+                                char *base = reinterpret_cast<char *>(
+                                    out + img + (size_t)(DIR ? C - 1 - ch : ch) * H * W);
+                                float *dst = reinterpret_cast<float *>(base + off);
+                                if (myflag)     // another workgroup of this launch will read it
+                                    __hip_atomic_store(dst, val[ch], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                else
+                                    *dst = val[ch];
                             }
                         }
                     }
-                }
-            } else {
-                // ---- storer: drain block [t-4, t); its progress is published two steps later
-                const int us = t - kCBlk;
-                if (us >= 0) {
-#pragma unroll
-                    for (int bi = 0; bi < kMaxIoBands; ++bi) {
-                        const int b = iox + 2 * bi;
-                        if (b < NB) {
-                            const int tf = b * (16 + kCDelay);
-                            if (us + kCBlk > tf && us < tf + span) {
-                                const int row = b * 16 + nrow;
-                                const int cc = (us + jblk - tf) - nrow;
-                                const int slot = (us + jblk) & (kCRing - 1);
-                                float val[C];
-#pragma unroll
-                                for (int ch = 0; ch < C; ++ch)
-                                    val[ch] = ring[((b * C + ch) * kCRing + slot) * 16 + nrow];
-                                if (row < H && (unsigned)cc < (unsigned)W) {
-                                    const unsigned off =
-                                        4u * (unsigned)(DIR ? (H - 1 - row) * W + (W - 1 - cc) : row * W + cc);
-#pragma unroll
-                                    for (int ch = 0; ch < C; ++ch) {
-                                        char *base = reinterpret_cast<char *>(
-                                            out + img + (size_t)(DIR ? C - 1 - ch : ch) * H * W);
-                                        float *dst = reinterpret_cast<float *>(base + off);
-                                        if (myflag)     // another workgroup of this launch will read it
-                                            __hip_atomic_store(dst, val[ch], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                        else
-                                            *dst = val[ch];
-                                    }
-                                }
-                            }
-                        }
-                    }
-                    pending = (t >= t_last) ? kCDone : t;
                 }
             }
         }
         (void)kStep;
         __syncthreads();
     }
-    if (!is_compute && io >= 2 && myflag && pending >= 0) {
+    if (!is_compute && io >= 2 && myflag) {
+        // everything is drained: tell the consumer stage it never has to wait again
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(0);
         asm volatile("" ::: "memory");
         if (lane == 0)
-            __hip_atomic_store(myflag, pending, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(myflag, kCDone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 

@@ -224,11 +224,7 @@ int launch_dw_mfma_layers(const float *const *x, const float *const *v, float *c
     }
     if (int s = launch_dw_partial_batch(batch, layers, part, p, B, C, H, W, k, stream))
         return s;
-    const size_t P = (size_t)C * C * k * k;
-    for (int l = 0; l < layers; ++l)
-        if (int s = launch_dw_reduce(part + (size_t)l * p.nparts * P, (int)p.nparts, dw[l], C, k, stream))
-            return s;
-    return INVCONV_OK;
+    return launch_dw_reduce_layers(part, (int)p.nparts, dw, layers, C, k, stream);
 }
 
 }  // namespace invconv

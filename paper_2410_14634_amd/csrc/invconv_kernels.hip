@@ -267,23 +267,28 @@ __global__ __launch_bounds__(kDwBlock) void k_dw_partial(const float *__restrict
 // p = wave, wave+4, ... in index order (double accumulator) and are then
 // combined in wave order.  The result is negated and masked entries are written
 // as 0.  No atomics anywhere, so dw is bitwise reproducible from run to run.
-__global__ __launch_bounds__(256) void k_dw_reduce(const float *__restrict__ part, int nparts,
-                                                  float *__restrict__ dw, int C, int k)
+// blockIdx.y selects the layer when several layers are reduced by one launch
+// (layer l's rows start at part + l*nparts*P, its result goes to out.p[l]).
+__global__ __launch_bounds__(256) void k_dw_reduce(const float *__restrict__ part_all, int nparts, PtrList out,
+                                                  int C, int k)
 {
     __shared__ double swave[4][64];
     const int P = C * C * k * k;
+    const float *__restrict__ part = part_all + (size_t)blockIdx.y * nparts * P;
+    float *__restrict__ dw = out.p[blockIdx.y];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int e = blockIdx.x * 64 + lane;
     double acc = 0.0;
     if (e < P) {
         int p = wave;
-        for (; p + 12 < nparts; p += 16) {
-            const float a0 = part[(size_t)p * P + e], a1 = part[(size_t)(p + 4) * P + e];
-            const float a2 = part[(size_t)(p + 8) * P + e], a3 = part[(size_t)(p + 12) * P + e];
-            acc += (double)a0;
-            acc += (double)a1;
-            acc += (double)a2;
-            acc += (double)a3;
+        for (; p + 28 < nparts; p += 32) {
+            float a[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                a[u] = part[(size_t)(p + 4 * u) * P + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                acc += (double)a[u];
         }
         for (; p < nparts; p += 4)
             acc += (double)part[(size_t)p * P + e];
@@ -300,9 +305,12 @@ __global__ __launch_bounds__(256) void k_dw_reduce(const float *__restrict__ par
 
 // log|det dx/dy| for one image (Section 4): -H*W*sum_c log|w[c][c][k-1][k-1]|.
 // One wave; lane l takes channels l, l+64, ...; fixed butterfly across lanes.
-__global__ __launch_bounds__(64) void k_logdet(const float *__restrict__ w, int C, int H, int W, int k,
-                                              float *__restrict__ out)
+// blockIdx.x selects the layer: kernel ws.p[l], result out[l].
+__global__ __launch_bounds__(64) void k_logdet(ConstPtrList ws, int C, int H, int W, int k,
+                                              float *__restrict__ out_all)
 {
+    const float *__restrict__ w = ws.p[blockIdx.x];
+    float *__restrict__ out = out_all + blockIdx.x;
     double s = 0.0;
     for (int c = threadIdx.x; c < C; c += 64)
         s += log(fabs((double)w[((c * C + c) * k + (k - 1)) * k + (k - 1)]));
@@ -455,14 +463,37 @@ int launch_dw(const float *x, const float *v, float *dw, float *part, const DwPl
 
 int launch_dw_reduce(const float *part, int nparts, float *dw, int C, int k, hipStream_t stream)
 {
+    return launch_dw_reduce_layers(part, nparts, &dw, 1, C, k, stream);
+}
+
+// Second pass for `layers` layers in one launch (rows of layer l start at part + l*nparts*P).
+int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int layers, int C, int k,
+                            hipStream_t stream)
+{
+    if (layers < 1 || layers > kChainMaxLayers)
+        return INVCONV_ERR_SHAPE;
     const int P = C * C * k * k;
-    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 63) / 64), dim3(256), 0, stream, part, nparts, dw, C, k);
+    PtrList out{};
+    for (int l = 0; l < layers; ++l)
+        out.p[l] = dw[l];
+    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 63) / 64, layers), dim3(256), 0, stream, part, nparts, out, C, k);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
 int launch_logdet(const float *w, int C, int H, int W, int k, float *out, hipStream_t stream)
 {
-    hipLaunchKernelGGL(k_logdet, dim3(1), dim3(64), 0, stream, w, C, H, W, k, out);
+    return launch_logdet_layers(&w, 1, C, H, W, k, out, stream);
+}
+
+int launch_logdet_layers(const float *const *w, int layers, int C, int H, int W, int k, float *out,
+                         hipStream_t stream)
+{
+    if (layers < 1 || layers > kChainMaxLayers)
+        return INVCONV_ERR_SHAPE;
+    ConstPtrList ws{};
+    for (int l = 0; l < layers; ++l)
+        ws.p[l] = w[l];
+    hipLaunchKernelGGL(k_logdet, dim3(layers), dim3(64), 0, stream, ws, C, H, W, k, out);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

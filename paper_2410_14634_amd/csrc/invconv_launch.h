@@ -50,6 +50,12 @@ int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const
 int launch_dw_mfma_layers(const float *const *x, const float *const *v, float *const *dw, int layers, float *part,
                           const DwPlan &p, int B, int C, int H, int W, int k, hipStream_t stream);
 DwPlan plan_dw_any(int B, int C, int H, int W, int k);
+struct PtrList { float *p[kChainMaxLayers]; };
+struct ConstPtrList { const float *p[kChainMaxLayers]; };
+int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int layers, int C, int k,
+                            hipStream_t stream);
+int launch_logdet_layers(const float *const *w, int layers, int C, int H, int W, int k, float *out,
+                         hipStream_t stream);
 struct ChainArgs {
     const float *in0;                    // input of stage 0
     const float *w[kChainMaxLayers];     // kernel of stage s

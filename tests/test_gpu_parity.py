@@ -174,8 +174,10 @@ def test_chain_calls_match_oracle(shape):
     dy, dws = b.invconv_chain_bwd(xs, wd, dev(g_last))
     torch.cuda.synchronize()
     xr = oracle_chain(y, ws, g_last)
+    lds = host(b.invconv_chain_logdet(wd, H, W))
     for l in range(L):
         assert rel_err(host(xs[l]), xr[l]) <= TOL_ACT, f"x of layer {l}"
+        assert float(lds[l]) == pytest.approx(oracle.invconv_logdet(ws[l], H, W), rel=1e-5, abs=1e-5)
     # backward oracle on the GPU's own activations
     gr = g_last.astype(np.float64)
     for l in reversed(range(L)):
