@@ -36,7 +36,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", type=int, default=1, help="workload id 0..4 (1 = headline)")
-    ap.add_argument("--all", action="store_true", help="also time workloads 0..4 (reported under 'workloads')")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="time only the selected workload (default: also workloads 0..4, reported under 'workloads')")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--variant", type=int, default=0)
@@ -335,7 +336,7 @@ def main():
         hbm_frac_whole_step=res["hbm_frac"],
         roofline=roofline,
     )
-    if args.all:
+    if not args.headline_only:
         others = {}
         for c in range(5):
             if c == cfg:

@@ -200,7 +200,7 @@ __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in
                     }
                 }
 #pragma unroll
-                for (int db = 0; db < K; ++db)
+                for (int db = K - 1; db >= 0; --db)     // oldest column first: only db = 0 waits for this step\'s result
 #pragma unroll
                     for (int jj = 0; jj < CG; ++jj)
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[a][db][jj], xh[jj][db], acc, 0, 0, 0);
@@ -228,7 +228,7 @@ __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in
                 for (int jj = 0; jj < CG; ++jj)
                     acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wLi[jj], in_row ? yb[s][jj] : 0.0f, acc, 0, 0, 0);
 #pragma unroll
-                for (int db = 1; db < K; ++db)
+                for (int db = K - 1; db >= 1; --db)
 #pragma unroll
                     for (int jj = 0; jj < CG; ++jj)
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][db][jj], xh[jj][db], acc, 0, 0, 0);

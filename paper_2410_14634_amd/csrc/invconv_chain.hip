@@ -181,7 +181,7 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
                         }
                     }
 #pragma unroll
-                    for (int db = 0; db < K; ++db)
+                    for (int db = K - 1; db >= 0; --db)     // oldest column first: only db = 0 waits for this step\'s result
 #pragma unroll
                         for (int jj = 0; jj < CG; ++jj)
                             acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[aa][db][jj], xh[jj][db], acc, 0, 0, 0);
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
                     acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wLi[jj], in_row ? yv : 0.0f, acc, 0, 0, 0);
                 }
 #pragma unroll
-                for (int db = 1; db < K; ++db)
+                for (int db = K - 1; db >= 1; --db)
 #pragma unroll
                     for (int jj = 0; jj < CG; ++jj)
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][db][jj], xh[jj][db], acc, 0, 0, 0);

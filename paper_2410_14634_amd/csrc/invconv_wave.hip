@@ -214,7 +214,7 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
                         acc[o] = from_lane_above(T[a + 1][o]);
                 }
 #pragma unroll
-                for (int db = 0; db < K; ++db)
+                for (int db = K - 1; db >= 0; --db)     // oldest column first: only db = 0 waits for this step's result
 #pragma unroll
                     for (int i = 0; i < C; ++i)
                         acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[a][db][i], xh[i][db], acc, 0, 0, 0);
@@ -235,7 +235,7 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
                 for (int j = 0; j < C; ++j)
                     acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wLi[j], in_row ? yb[s][j] : 0.0f, acc, 0, 0, 0);
 #pragma unroll
-                for (int db = 1; db < K; ++db)
+                for (int db = K - 1; db >= 1; --db)
 #pragma unroll
                     for (int i = 0; i < C; ++i)
                         acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[0][db][i], xh[i][db], acc, 0, 0, 0);
@@ -336,15 +336,21 @@ __global__ __launch_bounds__(256) void k_bwd_wave(const float *__restrict__ x, c
         for (int o = 0; o < 4; ++o)
             sred[tid * (NS * 4) + s * 4 + o] = acc[s][o];
     __syncthreads();
-    for (int e = tid; e < P; e += 256) {
+    // fixed-order sum in two levels: the 16 blocks of each wave, then the four waves
+    float *swave = sred + 256 * NS * 4;     // [4][P]
+    for (int idx = tid; idx < 4 * P; idx += 256) {
+        const int e = idx % P, wv = idx / P;
         const int o = e / NCOL, col = e % NCOL;
         const int s = col >> 2, jj = col & 3;
         float sum = 0.0f;
-        for (int wv = 0; wv < 4; ++wv)
-            for (int bb = 0; bb < 16; ++bb)
-                sum += sred[(wv * 64 + bb * 4 + jj) * (NS * 4) + s * 4 + o];
-        part[(size_t)n * P + e] = sum;
+#pragma unroll
+        for (int bb = 0; bb < 16; ++bb)
+            sum += sred[(wv * 64 + bb * 4 + jj) * (NS * 4) + s * 4 + o];
+        swave[wv * P + e] = sum;
     }
+    __syncthreads();
+    for (int e = tid; e < P; e += 256)
+        part[(size_t)n * P + e] = ((swave[e] + swave[P + e]) + swave[2 * P + e]) + swave[3 * P + e];
 }
 
 template <int C, int K>
@@ -361,7 +367,7 @@ static int launch_wave_ck(int dir, const float *in, const float *w, float *out, 
 size_t bwd_wave_lds_bytes(int C, int H, int W, int k)
 {
     const size_t tiles = (size_t)C * H * W + (size_t)C * (H + k - 1) * (W + k - 1);
-    const size_t red = 256 * (size_t)((C * k * k + 3) / 4) * 4;
+    const size_t red = 256 * (size_t)((C * k * k + 3) / 4) * 4 + 4 * (size_t)C * C * k * k;
     return sizeof(float) * (tiles > red ? tiles : red);
 }
 
