@@ -116,6 +116,8 @@ __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in
         wLi[jj] = m_ok ? lv : 0.0f;
     }
     __syncthreads();        // ring zeroed, weights read
+    if (band >= NB)
+        return;             // helper waves of a single-band launch: they only speed up the weight preparation
 
     float xh[CG][K];
     f32x4 T[K];
@@ -266,10 +268,12 @@ static int launch_band_ck(int dir, const float *in, const float *w, float *out, 
 {
     const int NB = (H + 15) / 16;
     const size_t lds = solve_band_lds_bytes(4 * CG, K, NB);
+    // a single band gets three helper waves for the weight preparation (its loop has no barriers)
+    const int threads = NB == 1 ? 256 : 64 * NB;
     if (dir)
-        hipLaunchKernelGGL((k_solve_band<CG, K, 1>), dim3(B), dim3(64 * NB), lds, stream, in, w, out, H, W, NB);
+        hipLaunchKernelGGL((k_solve_band<CG, K, 1>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB);
     else
-        hipLaunchKernelGGL((k_solve_band<CG, K, 0>), dim3(B), dim3(64 * NB), lds, stream, in, w, out, H, W, NB);
+        hipLaunchKernelGGL((k_solve_band<CG, K, 0>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

@@ -62,7 +62,24 @@ __device__ void fold_weights(const float *__restrict__ w, int C, int k,
             sL[o * C + i] = val;
     }
     __syncthreads();
-    if (tid < C) {
+    if (CT > 0) {
+        // column j of Linv by forward substitution, kept in registers (all loops unrolled,
+        // entries above the diagonal stay zero so the inner sum needs no lower bound)
+        if (tid < CT) {
+            const int j = tid;
+            float lv[CT > 0 ? CT : 1];
+#pragma unroll
+            for (int o = 0; o < CT; ++o) {
+                float s = 0.0f;
+#pragma unroll
+                for (int m = 0; m < o; ++m)
+                    s += sL[o * CT + m] * lv[m];
+                const float d = sL[o * CT + o];
+                lv[o] = (o == j) ? 1.0f / d : (o > j ? -s / d : 0.0f);
+                sLinv[o * CT + j] = lv[o];
+            }
+        }
+    } else if (tid < C) {
         const int j = tid;
         for (int o = 0; o < j; ++o)
             sLinv[o * C + j] = 0.0f;
