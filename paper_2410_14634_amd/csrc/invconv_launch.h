@@ -10,7 +10,7 @@ namespace invconv {
 constexpr int kSolveBlock = 256;
 constexpr int kDwBlock = 256;
 constexpr size_t kMaxLdsBytes = 160 * 1024;   // LDS per workgroup on gfx950
-constexpr size_t kDwLdsBudget = 64 * 1024;
+constexpr size_t kDwLdsBudget = 40 * 1024;
 constexpr int kChainMaxLayers = 16;
 
 struct DwPlan {
