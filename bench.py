@@ -187,6 +187,8 @@ def measure_workload(cfg, steps, warmup, variant=0):
     ms_fwd = event_time_batch(torch, lambda: L.fwd_all(stream), max(steps // 4, 5), 3)
     ms_bwd = event_time_batch(torch, lambda: L.bwd_all(stream), max(steps // 4, 5), 3)
     bytes_step = 20.0 * L.n_elems * L.L
+    macs_per_elt = L.C * (L.k * L.k - 1) + (L.C - 1) / 2.0          # one solve; the weight gradient costs as much again
+    flops_step = 6.0 * macs_per_elt * L.n_elems * L.L               # fwd solve 2x, bwd solve 2x, dL/dw 2x (x2 flop/MAC)
     return L, dict(
         workload=cfg, B=L.B, C=L.C, H=L.H, W=L.W, k=L.k, layers=L.L,
         ms_per_step=ms_step, ms_fwd=ms_fwd, ms_bwd=ms_bwd,
@@ -194,6 +196,8 @@ def measure_workload(cfg, steps, warmup, variant=0):
         us_per_diagonal=(ms_fwd + ms_bwd) * 1e3 / (2 * L.L * (L.H + L.W - 1)),
         algorithmic_gbs=bytes_step / (ms_step * 1e-3) / 1e9,
         hbm_frac=bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        fp32_tflops=flops_step / (ms_step * 1e-3) / 1e12,
+        fp32_frac=flops_step / (ms_step * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
     )
 
 
@@ -330,7 +334,9 @@ def main():
         ms_per_step=res["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None,
         dtype="f32", data="synthetic",
         config=dict(workload=f"workload {cfg}: B={L.B} C={L.C} H=W={L.H} k={L.k} layers={L.L}, "
-                             "step = invconv_fwd + invconv_bwd + invconv_logdet, eager launches on one stream",
+                             + ("step = invconv_fwd + invconv_bwd + invconv_logdet" if L.L == 1 else
+                                "step = invconv_chain_fwd + invconv_chain_bwd + invconv_chain_logdet")
+                             + ", eager launches on one stream",
                     variant=args.variant),
         ms_fwd=res["ms_fwd"], ms_bwd=res["ms_bwd"], algorithmic_gbs=res["algorithmic_gbs"],
         hbm_frac_whole_step=res["hbm_frac"],
