@@ -213,3 +213,54 @@ def test_chain_workload4_matches_per_layer_calls_and_oracle():
     for l, w in enumerate(wl["w"]):
         xr = oracle.invconv_fwd(xr, w, THREADS)
         assert rel_err(host(xs[l]), xr) <= TOL_ACT
+
+
+def test_hip_graph_replays_match_eager():
+    """A captured step (fwd + bwd + logdet) replayed several times, with eager work in between,
+    gives the eager results every time (the library records kernel nodes only)."""
+    import torch
+    wl = inputs.make_workload(1)
+    y, w, g = dev(wl["y"]), dev(wl["w"][0]), dev(wl["g"])
+    x, v, dw = torch.empty_like(y), torch.empty_like(y), torch.empty_like(w)
+    ld = torch.empty(1, device="cuda")
+    wsp = torch.empty(b.bwd_workspace_bytes(16, 3, 32, 32, 3), dtype=torch.uint8, device="cuda")
+
+    def step():
+        b.invconv_fwd(y, w, out=x)
+        b.invconv_bwd(x, w, g, out=(v, dw), workspace=wsp)
+        b.invconv_logdet(w, 32, 32, out=ld)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (x, v, dw, ld)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        for t in (x, v, dw, ld):
+            t.fill_(float("nan"))             # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, r in zip((x, v, dw, ld), ref):
+            assert torch.equal(t, r), f"replay {rep}"
+
+
+def test_chain_error_word_stays_clear():
+    """The pipelined chain launch never runs out of its bounded waits in normal operation."""
+    import torch
+    L, B, C, H, W, k = 4, 3, 12, 48, 40, 3
+    cases = [inputs.make_case(B, C, H, W, k, seed=200 + l, tap_std=0.03) for l in range(L)]
+    wd = [dev(cs["w"][0]) for cs in cases]
+    need = b.chain_workspace_bytes(L, B, C, H, W, k)
+    wsp = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    b.invconv_chain_fwd(dev(cases[0]["y"]), wd, workspace=wsp)
+    torch.cuda.synchronize()
+    flags = wsp[: (L * B * 2 + 1) * 4].view(torch.int32).cpu().numpy()
+    assert flags[L * B * 2] == 0                       # error word
+    assert np.all(flags[: L * B * 2] == 1 << 30)       # every stage published "finished"
