@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--variants", action="store_true",
                     help="also time the forward solve under every launch strategy (reported under 'variant_study')")
+    ap.add_argument("--conv-only", action="store_true",
+                    help="only time the sampling-direction convolution (invconv_conv_fwd) and print its table")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three 64 MiB device copies (reference for the HBM byte counters)")
     return ap.parse_args()
@@ -288,6 +290,40 @@ def cpu_baseline(cfg, seconds):
                 sample=f"{sample}; {n} passes in {el:.1f} s")
 
 
+CONV_SHAPES = {  # the sampling-direction operator y = conv_w(x); streaming sizes besides the workload shapes
+    "workload1": (16, 3, 32, 32, 3), "workload2": (64, 12, 16, 16, 3), "workload3": (32, 3, 64, 64, 5),
+    "workload4_layer": (32, 12, 128, 128, 3),
+    "stream_c3": (256, 3, 256, 256, 3), "stream_c12": (256, 12, 128, 128, 3),
+}
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def measure_conv(reps=100):
+    """invconv_conv_fwd on device-resident tensors: us per call, algorithmic GB/s (read x + write y), TFLOP/s."""
+    import torch
+    from paper_2410_14634_amd import binding as b
+    lib = b.lib()
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {}
+    for name, (B, C, H, W, k) in CONV_SHAPES.items():
+        g = torch.Generator(device="cpu").manual_seed(7)
+        x = torch.randn(B, C, H, W, generator=g).cuda()
+        w = (torch.randn(C, C, k, k, generator=g) * 0.05).cuda()
+        y = torch.empty_like(x)
+
+        def call():
+            st = lib.invconv_conv_fwd(x.data_ptr(), w.data_ptr(), y.data_ptr(), B, C, H, W, k, stream)
+            if st != 0:
+                raise RuntimeError(f"invconv_conv_fwd failed with status {st}")
+        ms = event_time_batch(torch, call, reps, 5)
+        byts = 8.0 * x.numel()
+        flops = 2.0 * x.numel() * (C * k * k - (C - 1) / 2.0)
+        out[name] = dict(B=B, C=C, H=H, W=W, k=k, us_per_call=ms * 1e3, algorithmic_gbs=byts / ms / 1e6,
+                         hbm_frac=byts / ms / 1e6 / HBM_PEAK_GBS, fp32_tflops=flops / ms / 1e9,
+                         mfma_fp32_frac=flops / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS)
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -309,6 +345,9 @@ def main():
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
+    if args.conv_only:
+        print(json.dumps(dict(sampling_conv=measure_conv())), flush=True)
+        return
     cfg = args.workload
     L, res = measure_workload(cfg, args.steps, args.warmup, args.variant)
 
@@ -354,6 +393,8 @@ def main():
             others[str(c)] = r
             print(f"[bench] workload {c}: {json.dumps(r)}", file=sys.stderr, flush=True)
         out["workloads"] = others
+        out["sampling_conv"] = measure_conv()
+        print(f"[bench] sampling conv: {json.dumps(out['sampling_conv'])}", file=sys.stderr, flush=True)
     if args.variants:
         out["variant_study_us_per_fwd_call"] = variant_study(cfg)
         print(f"[bench] variants: {json.dumps(out['variant_study_us_per_fwd_call'])}", file=sys.stderr, flush=True)

@@ -69,6 +69,14 @@ invconv_status invconv_fwd(const float *y, const float *w, float *x,
                            int B, int C, int H, int W, int k, void *stream);
 
 /*
+ * The masked causal convolution itself, y = conv_w(x) (Eq. 1): the inverse of invconv_fwd and the
+ * only operator the sampling direction needs (Section 4.3).  Same layouts and masking conventions.
+ *   x [in]  B*C*H*W     w [in]  C*C*k*k     y [out] B*C*H*W, must not alias x.
+ */
+invconv_status invconv_conv_fwd(const float *x, const float *w, float *y,
+                                int B, int C, int H, int W, int k, void *stream);
+
+/*
  * Backward pass (Section 3.1-3.3, Eq. 2 and Eq. 4, Theorems 1 and 2).
  *   dLdy = M^{-T} dLdx, M being the matrix of conv_w: the transposed system is
  *          solved by back-substitution over anti-diagonals in decreasing order.

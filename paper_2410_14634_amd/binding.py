@@ -22,7 +22,7 @@ VARIANT_AUTO, VARIANT_BLOCK, VARIANT_DIAG_LAUNCH, VARIANT_WAVE, VARIANT_BAND, VA
 EXPORTS = (
     "invconv_fwd", "invconv_bwd", "invconv_bwd_workspace_bytes", "invconv_logdet",
     "invconv_fwd_ex", "invconv_bwd_ex", "invconv_status_string", "invconv_version",
-    "invconv_probe_step_sync", "invconv_chain_fwd", "invconv_chain_bwd", "invconv_chain_workspace_bytes", "invconv_chain_logdet",
+    "invconv_probe_step_sync", "invconv_chain_fwd", "invconv_chain_bwd", "invconv_chain_workspace_bytes", "invconv_chain_logdet", "invconv_conv_fwd",
 )
 
 _lib = None
@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.invconv_chain_bwd.restype = ci
         L.invconv_chain_logdet.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
         L.invconv_chain_logdet.restype = ci
+        L.invconv_conv_fwd.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.invconv_conv_fwd.restype = ci
         L.invconv_status_string.argtypes = [ci]
         L.invconv_status_string.restype = ctypes.c_char_p
         L.invconv_version.restype = ci
@@ -204,3 +206,14 @@ def invconv_chain_logdet(ws: list, H: int, W: int) -> torch.Tensor:
     if st != OK:
         raise InvconvError(st, "invconv_chain_logdet")
     return res
+
+
+def invconv_conv_fwd(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """y = conv_w(x): the masked causal convolution (the inverse of invconv_fwd)."""
+    _check(x, "x"), _check(w, "w")
+    B, C, H, W, k = _dims(x, w)
+    y = torch.empty_like(x) if out is None else _check(out, "out", x.shape)
+    st = lib().invconv_conv_fwd(x.data_ptr(), w.data_ptr(), y.data_ptr(), B, C, H, W, k, _stream())
+    if st != OK:
+        raise InvconvError(st, "invconv_conv_fwd")
+    return y

@@ -79,6 +79,18 @@ invconv_status invconv_fwd(const float *y, const float *w, float *x, int B, int 
     return invconv_fwd_ex(y, w, x, B, C, H, W, k, stream, INVCONV_VARIANT_AUTO);
 }
 
+invconv_status invconv_conv_fwd(const float *x, const float *w, float *y, int B, int C, int H, int W, int k,
+                                void *stream)
+{
+    if (!x || !w || !y)
+        return INVCONV_ERR_NULL;
+    if (int s = check_shape(B, C, H, W, k))
+        return s;
+    if (y == x || (const float *)y == w)
+        return INVCONV_ERR_ALIAS;
+    return launch_conv(x, w, y, B, C, H, W, k, (hipStream_t)stream);
+}
+
 size_t invconv_bwd_workspace_bytes(int B, int C, int H, int W, int k)
 {
     if (check_shape(B, C, H, W, k) != INVCONV_OK)

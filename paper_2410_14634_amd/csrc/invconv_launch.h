@@ -67,6 +67,7 @@ struct ChainArgs {
 bool chain_supported(int stages, int C, int H, int k);
 size_t chain_flag_ints(int stages, int B);
 int launch_chain(int dir, ChainArgs args, int C, int k, hipStream_t stream);
+int launch_conv(const float *x, const float *w, float *y, int B, int C, int H, int W, int k, hipStream_t stream);
 int launch_logdet(const float *w, int C, int H, int W, int k, float *out, hipStream_t stream);
 
 }  // namespace invconv
