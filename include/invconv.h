@@ -39,7 +39,7 @@ typedef int invconv_status;
 enum {
     INVCONV_OK = 0,
     INVCONV_ERR_NULL = -1,        /* a required pointer is NULL */
-    INVCONV_ERR_SHAPE = -2,       /* B, C, H, W or k < 1, or a size overflows int */
+    INVCONV_ERR_SHAPE = -2,       /* B, C, H, W or k < 1, B*C*H*W > 2^31 - 1, or one image C*H*W >= 2^29 elements (2 GiB) */
     INVCONV_ERR_UNSUPPORTED = -3, /* shape beyond what the kernels' on-chip buffers hold */
     INVCONV_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than invconv_bwd_workspace_bytes() */
     INVCONV_ERR_ALIAS = -5,       /* an output pointer equals an input pointer */

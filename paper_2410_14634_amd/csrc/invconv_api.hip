@@ -14,6 +14,9 @@ int check_shape(int B, int C, int H, int W, int k)
     const long long lim = 0x7fffffffLL;
     if ((long long)B * C * H * W > lim || (long long)C * C * k * k > lim || (long long)H + W > lim)
         return INVCONV_ERR_SHAPE;
+    // the kernels address inside one image with 32-bit byte offsets
+    if ((long long)C * H * W >= (1LL << 29))
+        return INVCONV_ERR_SHAPE;
     return INVCONV_OK;
 }
 

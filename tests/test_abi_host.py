@@ -39,12 +39,23 @@ def test_fwd_rejects_bad_arguments():
     assert L.invconv_fwd(y, None, x, 1, 1, 4, 4, 3, None) == b.ERR_NULL
     assert L.invconv_fwd(y, w, None, 1, 1, 4, 4, 3, None) == b.ERR_NULL
     for bad in [(0, 1, 4, 4, 3), (1, 0, 4, 4, 3), (1, 1, 0, 4, 3), (1, 1, 4, 0, 3), (1, 1, 4, 4, 0),
-                (-1, 1, 4, 4, 3), (2 ** 20, 64, 64, 64, 3)]:
+                (-1, 1, 4, 4, 3), (2 ** 20, 64, 64, 64, 3),
+                (1, 1, 32768, 16384, 3)]:      # one image of 2^29 elements: past the 32-bit byte offsets
         assert L.invconv_fwd(y, w, x, *bad, None) == b.ERR_SHAPE
     assert L.invconv_fwd(y, w, y, 1, 1, 4, 4, 3, None) == b.ERR_ALIAS
     assert L.invconv_fwd_ex(y, w, x, 1, 1, 4, 4, 3, None, 99) == b.ERR_VARIANT
     # on-chip buffers too small for this shape
-    assert L.invconv_fwd(y, w, x, 1, 64, 4096, 4096, 11, None) == b.ERR_UNSUPPORTED
+    assert L.invconv_fwd(y, w, x, 1, 64, 2048, 1024, 11, None) == b.ERR_UNSUPPORTED
+
+
+def test_conv_rejects_bad_arguments():
+    L = b.lib()
+    x, w, y = FAKE[:3]
+    assert L.invconv_conv_fwd(None, w, y, 1, 1, 4, 4, 3, None) == b.ERR_NULL
+    assert L.invconv_conv_fwd(x, None, y, 1, 1, 4, 4, 3, None) == b.ERR_NULL
+    assert L.invconv_conv_fwd(x, w, None, 1, 1, 4, 4, 3, None) == b.ERR_NULL
+    assert L.invconv_conv_fwd(x, w, y, 1, 1, 0, 4, 3, None) == b.ERR_SHAPE
+    assert L.invconv_conv_fwd(x, w, x, 1, 1, 4, 4, 3, None) == b.ERR_ALIAS
 
 
 def test_bwd_rejects_bad_arguments():
