@@ -36,11 +36,13 @@ def _load():
         lib.oracle_invconv_fwd.argtypes = [dp, dp, dp, ci, ci, ci, ci, ci, ci]
         lib.oracle_invconv_bwd_dy.argtypes = [dp, dp, dp, ci, ci, ci, ci, ci, ci]
         lib.oracle_invconv_bwd_dw.argtypes = [dp, dp, dp, ci, ci, ci, ci, ci, ci]
+        lib.oracle_conv_bwd_dx.argtypes = [dp, dp, dp, ci, ci, ci, ci, ci, ci]
+        lib.oracle_conv_bwd_dw.argtypes = [dp, dp, dp, ci, ci, ci, ci, ci, ci]
         lib.oracle_invconv_logdet.argtypes = [dp, ci, ci, ci, ci]
         lib.oracle_invconv_logdet.restype = ctypes.c_double
         lib.oracle_max_threads.restype = ci
         for f in (lib.oracle_conv, lib.oracle_invconv_fwd, lib.oracle_invconv_bwd_dy,
-                  lib.oracle_invconv_bwd_dw):
+                  lib.oracle_invconv_bwd_dw, lib.oracle_conv_bwd_dx, lib.oracle_conv_bwd_dw):
             f.restype = None
         _lib = lib
     return _lib
@@ -74,6 +76,30 @@ def conv(x, w, threads: int = 1) -> np.ndarray:
     y = np.empty_like(x)
     _load().oracle_conv(_p(x), _p(w), _p(y), B, C, H, W, k, threads)
     return y
+
+
+def conv_bwd_dx(g, w, threads: int = 1) -> np.ndarray:
+    """dL/dx = M^T dL/dy of y = conv_w(x)."""
+    g, w = _d(g), _d(w)
+    B, C, H, W, k = _dims(g, w)
+    dx = np.empty_like(g)
+    _load().oracle_conv_bwd_dx(_p(g), _p(w), _p(dx), B, C, H, W, k, threads)
+    return dx
+
+
+def conv_bwd_dw(x, g, k: int, threads: int = 1) -> np.ndarray:
+    """dL/dw of y = conv_w(x): correlation of dL/dy with shifted x, summed over batch and pixels."""
+    x, g = _d(x), _d(g)
+    B, C, H, W = x.shape
+    dw = np.empty((C, C, k, k), dtype=np.float64)
+    _load().oracle_conv_bwd_dw(_p(x), _p(g), _p(dw), B, C, H, W, k, threads)
+    return dw
+
+
+def conv_bwd(x, w, g, threads: int = 1):
+    """(dL/dx, dL/dw) of y = conv_w(x) given dL/dy."""
+    w = _d(w)
+    return conv_bwd_dx(g, w, threads), conv_bwd_dw(x, g, w.shape[2], threads)
 
 
 def invconv_fwd(y, w, threads: int = 1) -> np.ndarray:

@@ -65,6 +65,60 @@ void oracle_conv(const double *x, const double *w, double *y,
 }
 
 /*
+ * Gradients of the convolution itself (the sampling direction only needs plain
+ * convolutions, Section 4.3).  y = M x is linear in x and in w, so with g = dL/dy
+ *   dL/dx = M^T g:  dL/dx[n][i][r][c] = sum_{o,a,b} w[o][i][a][b] g[n][o][r+(k-1)-a][c+(k-1)-b]
+ * over the output pixels inside the image that read input pixel (r, c) through tap
+ * (a, b), and
+ *   dL/dw[o][i][a][b] = sum_{n,r,c} g[n][o][r][c] x[n][i][r-(k-1)+a][c-(k-1)+b],
+ * masked entries 0.
+ */
+void oracle_conv_bwd_dx(const double *g, const double *w, double *dx,
+                        int B, int C, int H, int W, int k, int threads)
+{
+    (void)threads;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (int n = 0; n < B; ++n)
+        for (int i = 0; i < C; ++i)
+            for (int r = 0; r < H; ++r)
+                for (int c = 0; c < W; ++c) {
+                    double acc = 0.0;
+                    for (int o = 0; o < C; ++o)
+                        for (int a = 0; a < k; ++a)
+                            for (int b = 0; b < k; ++b) {
+                                int rr = r + (k - 1) - a, cc = c + (k - 1) - b;
+                                if (rr >= H || cc >= W)
+                                    continue;
+                                acc += eff(w, C, k, o, i, a, b) * g[at(C, H, W, n, o, rr, cc)];
+                            }
+                    dx[at(C, H, W, n, i, r, c)] = acc;
+                }
+}
+
+void oracle_conv_bwd_dw(const double *x, const double *g, double *dw,
+                        int B, int C, int H, int W, int k, int threads)
+{
+    (void)threads;
+    int P = C * C * k * k;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (int e = 0; e < P; ++e) {
+        int b = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
+        double acc = 0.0;
+        if (!(a == k - 1 && b == k - 1 && i > o)) {
+            for (int n = 0; n < B; ++n)
+                for (int r = 0; r < H; ++r)
+                    for (int c = 0; c < W; ++c) {
+                        int rr = r - (k - 1) + a, cc = c - (k - 1) + b;
+                        if (rr < 0 || cc < 0)
+                            continue;
+                        acc += g[at(C, H, W, n, o, r, c)] * x[at(C, H, W, n, i, rr, cc)];
+                    }
+        }
+        dw[e] = acc;
+    }
+}
+
+/*
  * Inverse convolution: solve conv_w(x) = y for x by forward substitution,
  *   x_q = ( y_q - sum_{r in Delta(q)} W_{(k,k)-q+r} x_r ) / W_{k,k}
  * (the rearranged Eq. 1 used in the proofs of Theorems 1 and 2), extended to

@@ -398,3 +398,54 @@ def test_hand_worked_2x2_example():
     v, dw = oracle.invconv_bwd(x, vals["W"], vals["g"])
     np.testing.assert_allclose(v, vals["v"], rtol=0, atol=1e-15)
     np.testing.assert_allclose(dw, vals["dW"], rtol=0, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------- gradients of the convolution itself
+@pytest.mark.parametrize("shape", TINY)
+def test_conv_bwd_matches_dense_transpose_and_torch_autograd(shape):
+    cs = tiny_case(shape, seed=21)
+    B, C, H, W, k = shape
+    x, g, w = cs["y"].astype(np.float64), cs["g"].astype(np.float64), cs["w"][0]
+    dx, dw = oracle.conv_bwd(x, w, g)
+    M = dr.dense_M(w, H, W)
+    for n in range(B):
+        np.testing.assert_allclose(dr.to_vec(dx[n]), M.T @ dr.to_vec(g[n]), rtol=0, atol=1e-13)
+    # library autograd through pad + conv2d with the masked kernel (mask applied outside the graph, so
+    # the masked entries get whatever conv2d gives them; compare the unmasked ones and require 0 elsewhere)
+    xt = torch.from_numpy(x).requires_grad_(True)
+    wt = torch.from_numpy(dr.masked(w)).requires_grad_(True)
+    F.conv2d(F.pad(xt, (k - 1, 0, k - 1, 0)), wt).backward(torch.from_numpy(g))
+    np.testing.assert_allclose(dx, xt.grad.numpy(), rtol=0, atol=1e-12)
+    for o, i, a, b in np.ndindex(C, C, k, k):
+        if a == k - 1 and b == k - 1 and i > o:
+            assert dw[o, i, a, b] == 0.0
+        else:
+            assert dw[o, i, a, b] == pytest.approx(wt.grad[o, i, a, b].item(), rel=1e-11, abs=1e-12)
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+def test_conv_bwd_adjoint_and_directional_derivative_at_workload_shapes(cfg):
+    wl = inputs.make_workload(cfg)
+    x, g, w = wl["y"].astype(np.float64), wl["g"].astype(np.float64), wl["w"][0]
+    dx, dw = oracle.conv_bwd(x, w, g, THREADS)
+    # <conv(x), g> = <x, M^T g>
+    lhs = float(np.vdot(oracle.conv(x, w, THREADS), g))
+    assert float(np.vdot(x, dx)) == pytest.approx(lhs, rel=1e-10)
+    # conv is linear in w: L(w + t d) - L(w) = t <dw, d> exactly (up to rounding), d kept off the masked entries
+    rng = np.random.default_rng(5)
+    d = dr.masked(rng.standard_normal(w.shape))
+    k = w.shape[2]
+    for c in range(w.shape[0]):
+        d[c, c, k - 1, k - 1] = rng.standard_normal()
+    diff = float(np.vdot(oracle.conv(x, w + d, THREADS), g)) - lhs
+    assert float(np.vdot(dw, d)) == pytest.approx(diff, rel=1e-9)
+
+
+def test_inverse_gradients_follow_from_the_convolution_gradients():
+    # x = M^{-1} y: dL/dy = M^{-T} g and dL/dw = -(dL/dw of the convolution evaluated with dL/dy in place of g)
+    cs = inputs.make_case(2, 3, 6, 5, 3, seed=23, tap_std=0.2)
+    y, g, w = cs["y"].astype(np.float64), cs["g"].astype(np.float64), cs["w"][0]
+    x = oracle.invconv_fwd(y, w)
+    v, dw_inv = oracle.invconv_bwd(x, w, g)
+    np.testing.assert_allclose(oracle.conv_bwd_dx(v, w), g, rtol=0, atol=1e-12)     # M^T v = g
+    np.testing.assert_allclose(dw_inv, -oracle.conv_bwd_dw(x, v, 3), rtol=1e-13, atol=1e-14)
