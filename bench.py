@@ -299,7 +299,8 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
 def measure_conv(reps=100):
-    """invconv_conv_fwd on device-resident tensors: us per call, algorithmic GB/s (read x + write y), TFLOP/s."""
+    """invconv_conv_fwd / invconv_conv_bwd on device-resident tensors: us per call, algorithmic GB/s
+    (fwd: read x, write y; bwd: read x and dL/dy, write dL/dx), TFLOP/s."""
     import torch
     from paper_2410_14634_amd import binding as b
     lib = b.lib()
@@ -315,12 +316,25 @@ def measure_conv(reps=100):
             st = lib.invconv_conv_fwd(x.data_ptr(), w.data_ptr(), y.data_ptr(), B, C, H, W, k, stream)
             if st != 0:
                 raise RuntimeError(f"invconv_conv_fwd failed with status {st}")
+        g_ = torch.randn(B, C, H, W, generator=g).cuda()
+        dx, dw = torch.empty_like(x), torch.empty_like(w)
+        need = lib.invconv_bwd_workspace_bytes(B, C, H, W, k)
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+
+        def call_bwd():
+            st = lib.invconv_conv_bwd(x.data_ptr(), w.data_ptr(), g_.data_ptr(), dx.data_ptr(), dw.data_ptr(),
+                                      B, C, H, W, k, ws.data_ptr(), need, stream)
+            if st != 0:
+                raise RuntimeError(f"invconv_conv_bwd failed with status {st}")
         ms = event_time_batch(torch, call, reps, 5)
+        ms_bwd = event_time_batch(torch, call_bwd, max(reps // 2, 5), 3)
         byts = 8.0 * x.numel()
         flops = 2.0 * x.numel() * (C * k * k - (C - 1) / 2.0)
         out[name] = dict(B=B, C=C, H=H, W=W, k=k, us_per_call=ms * 1e3, algorithmic_gbs=byts / ms / 1e6,
                          hbm_frac=byts / ms / 1e6 / HBM_PEAK_GBS, fp32_tflops=flops / ms / 1e9,
-                         mfma_fp32_frac=flops / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS)
+                         mfma_fp32_frac=flops / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS,
+                         bwd_us_per_call=ms_bwd * 1e3, bwd_algorithmic_gbs=12.0 * x.numel() / ms_bwd / 1e6,
+                         bwd_fp32_tflops=2.0 * flops / ms_bwd / 1e9)
     return out
 
 

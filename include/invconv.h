@@ -77,6 +77,17 @@ invconv_status invconv_conv_fwd(const float *x, const float *w, float *y,
                                 int B, int C, int H, int W, int k, void *stream);
 
 /*
+ * Gradients of that convolution (y = M x is linear in x and in w; Eq. 1): with dLdy given,
+ *   dLdx = M^T dLdy                                  (B*C*H*W, must not alias x or dLdy)
+ *   dLdw[o][i][a][b] = sum over batch and pixels of dLdy[n][o][r][c] * x[n][i][r-(k-1)+a][c-(k-1)+b]
+ *                                                    (C*C*k*k, masked entries 0, deterministic two-pass sum)
+ * workspace: device scratch of invconv_bwd_workspace_bytes(B, C, H, W, k) bytes, contents undefined on return.
+ */
+invconv_status invconv_conv_bwd(const float *x, const float *w, const float *dLdy, float *dLdx, float *dLdw,
+                                int B, int C, int H, int W, int k,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Backward pass (Section 3.1-3.3, Eq. 2 and Eq. 4, Theorems 1 and 2).
  *   dLdy = M^{-T} dLdx, M being the matrix of conv_w: the transposed system is
  *          solved by back-substitution over anti-diagonals in decreasing order.

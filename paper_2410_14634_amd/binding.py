@@ -22,7 +22,7 @@ VARIANT_AUTO, VARIANT_BLOCK, VARIANT_DIAG_LAUNCH, VARIANT_WAVE, VARIANT_BAND, VA
 EXPORTS = (
     "invconv_fwd", "invconv_bwd", "invconv_bwd_workspace_bytes", "invconv_logdet",
     "invconv_fwd_ex", "invconv_bwd_ex", "invconv_status_string", "invconv_version",
-    "invconv_probe_step_sync", "invconv_chain_fwd", "invconv_chain_bwd", "invconv_chain_workspace_bytes", "invconv_chain_logdet", "invconv_conv_fwd",
+    "invconv_probe_step_sync", "invconv_chain_fwd", "invconv_chain_bwd", "invconv_chain_workspace_bytes", "invconv_chain_logdet", "invconv_conv_fwd", "invconv_conv_bwd",
 )
 
 _lib = None
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.invconv_chain_logdet.restype = ci
         L.invconv_conv_fwd.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
         L.invconv_conv_fwd.restype = ci
+        L.invconv_conv_bwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, ctypes.c_size_t, vp]
+        L.invconv_conv_bwd.restype = ci
         L.invconv_status_string.argtypes = [ci]
         L.invconv_status_string.restype = ctypes.c_char_p
         L.invconv_version.restype = ci
@@ -217,3 +219,24 @@ def invconv_conv_fwd(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None 
     if st != OK:
         raise InvconvError(st, "invconv_conv_fwd")
     return y
+
+
+def invconv_conv_bwd(x: torch.Tensor, w: torch.Tensor, dLdy: torch.Tensor,
+                     out: tuple[torch.Tensor, torch.Tensor] | None = None,
+                     workspace: torch.Tensor | None = None):
+    """(dL/dx, dL/dw) of y = conv_w(x) given dL/dy."""
+    _check(x, "x"), _check(w, "w"), _check(dLdy, "dLdy", x.shape)
+    B, C, H, W, k = _dims(x, w)
+    if out is None:
+        dLdx, dLdw = torch.empty_like(x), torch.empty_like(w)
+    else:
+        dLdx, dLdw = _check(out[0], "out[0]", x.shape), _check(out[1], "out[1]", w.shape)
+    need = bwd_workspace_bytes(B, C, H, W, k)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    st = lib().invconv_conv_bwd(x.data_ptr(), w.data_ptr(), dLdy.data_ptr(), dLdx.data_ptr(), dLdw.data_ptr(),
+                                B, C, H, W, k, workspace.data_ptr(), ws_bytes, _stream())
+    if st != OK:
+        raise InvconvError(st, "invconv_conv_bwd")
+    return dLdx, dLdw

@@ -91,7 +91,30 @@ invconv_status invconv_conv_fwd(const float *x, const float *w, float *y, int B,
         return s;
     if (y == x || (const float *)y == w)
         return INVCONV_ERR_ALIAS;
-    return launch_conv(x, w, y, B, C, H, W, k, (hipStream_t)stream);
+    return launch_conv(0, x, w, y, B, C, H, W, k, (hipStream_t)stream);
+}
+
+invconv_status invconv_conv_bwd(const float *x, const float *w, const float *dLdy, float *dLdx, float *dLdw, int B,
+                                int C, int H, int W, int k, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || !w || !dLdy || !dLdx || !dLdw)
+        return INVCONV_ERR_NULL;
+    if (int s = check_shape(B, C, H, W, k))
+        return s;
+    if (dLdx == dLdy || dLdx == x || (const float *)dLdx == w || dLdw == dLdx || (const float *)dLdw == w ||
+        (const float *)dLdw == x || (const float *)dLdw == dLdy)
+        return INVCONV_ERR_ALIAS;
+    const DwPlan p = plan_dw_any(B, C, H, W, k);
+    if (!p.rt)
+        return INVCONV_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < p.bytes)
+        return INVCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (int s = launch_conv(1, dLdy, w, dLdx, B, C, H, W, k, st))
+        return s;
+    if (dw_mfma_supported(C, k) && plan_dw_mfma(B, C, H, W, k).rt)
+        return launch_dw_mfma(x, dLdy, dLdw, (float *)workspace, p, B, C, H, W, k, st, 1.0f);
+    return launch_dw(x, dLdy, dLdw, (float *)workspace, p, B, C, H, W, k, st, 1.0f);
 }
 
 size_t invconv_bwd_workspace_bytes(int B, int C, int H, int W, int k)
@@ -285,9 +308,7 @@ invconv_status invconv_chain_bwd(const float *const *x, const float *const *w, c
     if (mfma)
         return launch_dw_mfma_layers(x, v, dLdw, L, part, p, B, C, H, W, k, st);
     for (int l = 0; l < L; ++l) {
-        const int s = mfma ? launch_dw_mfma(x[l], v[l], dLdw[l], part, p, B, C, H, W, k, st)
-                           : launch_dw(x[l], v[l], dLdw[l], part, p, B, C, H, W, k, st);
-        if (s)
+        if (int s = launch_dw(x[l], v[l], dLdw[l], part, p, B, C, H, W, k, st))
             return s;
     }
     return INVCONV_OK;

@@ -50,7 +50,10 @@ struct TileGeom {
 
 // One element: where it comes from (clamped into the image), where it goes in LDS (-1: nowhere) and
 // whether it lies inside the image.
-template <bool vec>
+// With DIR = 1 the tile lives in mirrored coordinates (rows, columns and channels reversed), which
+// turns the transposed operator M^T into a causal convolution again; four consecutive mirrored
+// columns are four consecutive image columns in reverse order.
+template <bool vec, int DIR>
 __device__ __forceinline__ void tile_elem(const TileGeom &g, unsigned raw, unsigned total, unsigned line, unsigned m_line,
                                           unsigned m_rows, unsigned &src, int &dst, bool &keep)
 {
@@ -62,13 +65,16 @@ __device__ __forceinline__ void tile_elem(const TileGeom &g, unsigned raw, unsig
     keep = gr >= 0 && gr < g.H && gc >= 0 && gc < g.W;
     const int grc = gr < 0 ? 0 : (gr >= g.H ? g.H - 1 : gr);
     const int gcc = gc < 0 ? 0 : (gc >= g.W ? g.W - step : gc);
-    src = (ch * g.H + grc) * g.W + gcc;
+    if (DIR)
+        src = ((g.C - 1 - ch) * g.H + (g.H - 1 - grc)) * g.W + (g.W - step - gcc);
+    else
+        src = (ch * g.H + grc) * g.W + gcc;
     dst = raw < total ? (int)((ch * g.XR + r) * g.XW + step * cq) : -1;
 }
 
 // Tile loader: kConvLoadBatch loads at a time with clamped addresses (no branch around a
 // load); out-of-image elements are zeroed when the batch is written to LDS.
-template <bool vec>
+template <bool vec, int DIR>
 __device__ __forceinline__ void conv_load_tile(const TileGeom &g, float *sx)
 {
     const unsigned line = vec ? g.XW >> 2 : g.XW;       // elements (16 or 4 bytes) per tile row
@@ -81,7 +87,7 @@ __device__ __forceinline__ void conv_load_tile(const TileGeom &g, float *sx)
 #pragma unroll
         for (int j = 0; j < kConvLoadBatch; ++j) {
             unsigned src;
-            tile_elem<vec>(g, base + j * 256, total, line, m_line, m_rows, src, dst[j], keep[j]);
+            tile_elem<vec, DIR>(g, base + j * 256, total, line, m_line, m_rows, src, dst[j], keep[j]);
             if (vec)
                 val[j] = *reinterpret_cast<const float4 *>(g.xi + src);
             else
@@ -91,7 +97,10 @@ __device__ __forceinline__ void conv_load_tile(const TileGeom &g, float *sx)
         for (int j = 0; j < kConvLoadBatch; ++j)
             if (dst[j] >= 0) {
                 const bool kp = keep[j];
-                if (vec)
+                if (vec && DIR)
+                    *reinterpret_cast<float4 *>(sx + dst[j]) = make_float4(kp ? val[j].w : 0.f, kp ? val[j].z : 0.f,
+                                                                            kp ? val[j].y : 0.f, kp ? val[j].x : 0.f);
+                else if (vec)
                     *reinterpret_cast<float4 *>(sx + dst[j]) = make_float4(kp ? val[j].x : 0.f, kp ? val[j].y : 0.f,
                                                                             kp ? val[j].z : 0.f, kp ? val[j].w : 0.f);
                 else
@@ -104,7 +113,7 @@ __device__ __forceinline__ void conv_load_tile(const TileGeom &g, float *sx)
 // Tile of kConvRows x TW pixels (TW = 32, 64 or 128), LDS tile [C][kConvRows + K - 1][TW + 4].
 // A wave works on two batches of 64 pixels at a time (two independent accumulators); all LDS
 // offsets of the taps are compile-time constants.
-template <int C, int K, int TW, bool VEC>
+template <int C, int K, int TW, bool VEC, int DIR>
 __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x, const float *__restrict__ w,
                                                    float *__restrict__ y, int H, int W, int tiles_r, int tiles_c,
                                                    unsigned ntiles)
@@ -133,7 +142,8 @@ __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x,
 #pragma unroll
             for (int b = 0; b < K; ++b) {
                 const bool masked = (a == K - 1 && b == K - 1 && i > o_lane) || o_lane >= C;
-                const float v = w[((oc * C + i) * K + a) * K + b];
+                const int oo = DIR ? C - 1 - i : oc, ii = DIR ? C - 1 - oc : i;     // mirrored: transposed, reversed
+                const float v = w[((oo * C + ii) * K + a) * K + b];
                 wA[i][a][b] = masked ? 0.0f : v;
             }
 
@@ -153,7 +163,7 @@ __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x,
     const int lr = lane / LW, lc = lane % LW;
     for (unsigned t = t0; t < t1; t += tstep) {
         const TileGeom g = geom(t, n, r0, c0, rows);
-        conv_load_tile<VEC>(g, sx);
+        conv_load_tile<VEC, DIR>(g, sx);
         __syncthreads();
         float *__restrict__ yi = y + n * C * H * W;
         for (int bi = 2 * wave; bi < NBATCH; bi += 8) {
@@ -188,16 +198,16 @@ __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x,
                 acc1 = __builtin_amdgcn_mfma_f32_4x4x1f32(wv, bv[s % (kAhead + 1)][1], acc1, 0, 0, 0);
             }
             if (pr0 < rows && c0 + pc0 < W) {
-                const unsigned off = (r0 + pr0) * W + c0 + pc0;
+                const unsigned off = DIR ? (H - 1 - r0 - pr0) * W + (W - 1 - c0 - pc0) : (r0 + pr0) * W + c0 + pc0;
 #pragma unroll
                 for (int o = 0; o < C; ++o)
-                    yi[off + o * H * W] = acc0[o];
+                    yi[off + (DIR ? C - 1 - o : o) * H * W] = acc0[o];
             }
             if (pr1 < rows && c0 + pc1 < W) {
-                const unsigned off = (r0 + pr1) * W + c0 + pc1;
+                const unsigned off = DIR ? (H - 1 - r0 - pr1) * W + (W - 1 - c0 - pc1) : (r0 + pr1) * W + c0 + pc1;
 #pragma unroll
                 for (int o = 0; o < C; ++o)
-                    yi[off + o * H * W] = acc1[o];
+                    yi[off + (DIR ? C - 1 - o : o) * H * W] = acc1[o];
             }
         }
         __syncthreads();        // the tile is overwritten next
@@ -210,7 +220,7 @@ __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x,
 // so a lane ends up with four consecutive pixels of one output channel and stores them as 16 bytes.  The A operands and the LDS offsets of the pairs are tabulated in LDS once per
 // workgroup and held in registers NSC instructions at a time; a wave forms the four 16-pixel groups
 // of one tile row together (four independent accumulators).
-template <int NSC, bool VEC>
+template <int NSC, bool VEC, int DIR>
 __global__ __launch_bounds__(256, 2) void k_conv_mfma16(const float *__restrict__ x, const float *__restrict__ w,
                                                     float *__restrict__ y, int C, int H, int W, int k, int halo,
                                                     int TR, int tiles_r, int tiles_c, int nck, unsigned ntiles)
@@ -256,7 +266,8 @@ __global__ __launch_bounds__(256, 2) void k_conv_mfma16(const float *__restrict_
                     const unsigned kc = kk < (unsigned)NK ? kk : 0;    // padding pairs: zero weights, any valid offset
                     const unsigned i = fastdiv(kc, kk2, m_kk), t = kc - i * kk2;
                     const unsigned a = fastdiv(t, k, m_k), b = t - a * k;
-                    val[j] = w[(oc * C + i) * kk2 + t];
+                    const unsigned oo = DIR ? C - 1 - i : oc, ii = DIR ? C - 1 - oc : i;    // mirrored: transposed, reversed
+                    val[j] = w[(oo * C + ii) * kk2 + t];
                     keep[j] = kk < (unsigned)NK && o < (unsigned)C && !(t == kk2 - 1 && i > o);
                     if (ob == 0 && (l & 15) == 0 && s0 + 4 * j < NS)
                         sOff[kk] = (i * XR + a) * XW + b + halo - (k - 1);
@@ -274,7 +285,7 @@ __global__ __launch_bounds__(256, 2) void k_conv_mfma16(const float *__restrict_
     int boff[NSC];
     for (unsigned t = t0; t < t1; t += tstep) {
         const TileGeom g = geom(t, n, r0, c0, rows);
-        conv_load_tile<VEC>(g, sx);
+        conv_load_tile<VEC, DIR>(g, sx);
         __syncthreads();        // also orders the tables before their first use
         float *__restrict__ yi = y + n * C * H * W;
         for (int ob = 0; ob < OB; ++ob) {
@@ -323,18 +334,25 @@ __global__ __launch_bounds__(256, 2) void k_conv_mfma16(const float *__restrict_
                 // lane (nn, g4) register j holds output channel 16 ob + nn of pixel 16u + 4 g4 + j
                 const int o = 16 * ob + nn;
                 if (o < C) {
-                    float *yo = yi + (o * H + r0 + pr) * W + c0 + 4 * g4;
+                    // mirrored: pixel (row, c .. c+3) is image pixel (H-1-row, W-1-c-3 .. W-1-c) of channel C-1-o
+                    const int row = r0 + pr;
+                    float *yo = DIR ? yi + ((C - 1 - o) * H + (H - 1 - row)) * W : yi + (o * H + row) * W;
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         const int c = c0 + 16 * u + 4 * g4;
                         if (VEC) {
-                            if (c < W)
-                                *reinterpret_cast<float4 *>(yo + 16 * u) = make_float4(acc[u][0], acc[u][1], acc[u][2], acc[u][3]);
+                            if (c < W) {
+                                if (DIR)
+                                    *reinterpret_cast<float4 *>(yo + W - 4 - c) =
+                                        make_float4(acc[u][3], acc[u][2], acc[u][1], acc[u][0]);
+                                else
+                                    *reinterpret_cast<float4 *>(yo + c) = make_float4(acc[u][0], acc[u][1], acc[u][2], acc[u][3]);
+                            }
                         } else {
 #pragma unroll
                             for (int j = 0; j < 4; ++j)
                                 if (c + j < W)
-                                    yo[16 * u + j] = acc[u][j];
+                                    yo[DIR ? W - 1 - c - j : c + j] = acc[u][j];
                         }
                     }
                 }
@@ -345,6 +363,7 @@ __global__ __launch_bounds__(256, 2) void k_conv_mfma16(const float *__restrict_
 }
 
 // ---- any shape: one thread per output element ---------------------------------------------------
+template <int DIR>
 __global__ __launch_bounds__(256) void k_conv_generic(const float *__restrict__ x, const float *__restrict__ w,
                                                      float *__restrict__ y, int B, int C, int H, int W, int k)
 {
@@ -361,10 +380,10 @@ __global__ __launch_bounds__(256) void k_conv_generic(const float *__restrict__ 
                 for (int b = 0; b < k; ++b) {
                     const int cc = c - (k - 1) + b;
                     if (cc >= 0)
-                        acc += weff<0>(w, C, k, o, i, a, b) * x[((n * C + i) * H + rr) * W + cc];
+                        acc += weff<DIR>(w, C, k, o, i, a, b) * x[gidx<DIR>((int)n, i, rr, cc, C, H, W)];
                 }
             }
-        y[idx] = acc;
+        y[gidx<DIR>((int)n, o, r, c, C, H, W)] = acc;
     }
 }
 
@@ -373,7 +392,7 @@ static unsigned conv_grid(size_t ntiles)
     return ntiles < (size_t)kConvMaxGrid ? (unsigned)ntiles : (unsigned)kConvMaxGrid;
 }
 
-template <int C, int K, int TW>
+template <int C, int K, int TW, int DIR>
 static void launch_small_tw(const float *x, const float *w, float *y, int B, int H, int W, int vec, hipStream_t stream)
 {
     const int tiles_r = (H + kConvRows - 1) / kConvRows, tiles_c = (W + TW - 1) / TW;
@@ -381,22 +400,22 @@ static void launch_small_tw(const float *x, const float *w, float *y, int B, int
     const size_t lds = sizeof(float) * C * (kConvRows + K - 1) * (TW + 4);
     const unsigned grid = conv_grid(ntiles);
     if (vec)
-        hipLaunchKernelGGL((k_conv_small<C, K, TW, true>), dim3(grid), dim3(256), lds, stream, x, w, y, H, W, tiles_r,
-                           tiles_c, (unsigned)ntiles);
+        hipLaunchKernelGGL((k_conv_small<C, K, TW, true, DIR>), dim3(grid), dim3(256), lds, stream, x, w, y, H, W,
+                           tiles_r, tiles_c, (unsigned)ntiles);
     else
-        hipLaunchKernelGGL((k_conv_small<C, K, TW, false>), dim3(grid), dim3(256), lds, stream, x, w, y, H, W, tiles_r,
-                           tiles_c, (unsigned)ntiles);
+        hipLaunchKernelGGL((k_conv_small<C, K, TW, false, DIR>), dim3(grid), dim3(256), lds, stream, x, w, y, H, W,
+                           tiles_r, tiles_c, (unsigned)ntiles);
 }
 
-template <int C, int K>
+template <int C, int K, int DIR>
 static void launch_small(const float *x, const float *w, float *y, int B, int H, int W, int vec, hipStream_t stream)
 {
     if (W <= 32)
-        launch_small_tw<C, K, 32>(x, w, y, B, H, W, vec, stream);
+        launch_small_tw<C, K, 32, DIR>(x, w, y, B, H, W, vec, stream);
     else if (W <= 64)
-        launch_small_tw<C, K, 64>(x, w, y, B, H, W, vec, stream);
+        launch_small_tw<C, K, 64, DIR>(x, w, y, B, H, W, vec, stream);
     else
-        launch_small_tw<C, K, 128>(x, w, y, B, H, W, vec, stream);
+        launch_small_tw<C, K, 128, DIR>(x, w, y, B, H, W, vec, stream);
 }
 
 // Plan of the 16-channel kernel: instructions per register chunk, chunks, halo columns, tile rows,
@@ -426,7 +445,7 @@ static ConvPlan plan_m16(int C, int k)
     return p;
 }
 
-template <int NSC>
+template <int NSC, int DIR>
 static void launch_m16(const float *x, const float *w, float *y, int B, int C, int H, int W, int k, const ConvPlan &p,
                        int vec, hipStream_t stream)
 {
@@ -434,47 +453,55 @@ static void launch_m16(const float *x, const float *w, float *y, int B, int C, i
     const size_t ntiles = (size_t)B * tiles_r * tiles_c;
     const unsigned grid = conv_grid(ntiles);
     if (vec)
-        hipLaunchKernelGGL((k_conv_mfma16<NSC, true>), dim3(grid), dim3(256), p.lds, stream, x, w, y, C, H, W, k, p.halo,
-                           p.tr, tiles_r, tiles_c, p.nck, (unsigned)ntiles);
+        hipLaunchKernelGGL((k_conv_mfma16<NSC, true, DIR>), dim3(grid), dim3(256), p.lds, stream, x, w, y, C, H, W, k,
+                           p.halo, p.tr, tiles_r, tiles_c, p.nck, (unsigned)ntiles);
     else
-        hipLaunchKernelGGL((k_conv_mfma16<NSC, false>), dim3(grid), dim3(256), p.lds, stream, x, w, y, C, H, W, k, p.halo,
-                           p.tr, tiles_r, tiles_c, p.nck, (unsigned)ntiles);
+        hipLaunchKernelGGL((k_conv_mfma16<NSC, false, DIR>), dim3(grid), dim3(256), p.lds, stream, x, w, y, C, H, W, k,
+                           p.halo, p.tr, tiles_r, tiles_c, p.nck, (unsigned)ntiles);
 }
 
-int launch_conv(const float *x, const float *w, float *y, int B, int C, int H, int W, int k, hipStream_t stream)
+// y = M x (DIR = 0) or y = M^T x (DIR = 1, the same kernels in mirrored coordinates).
+template <int DIR>
+static int launch_conv_dir(const float *x, const float *w, float *y, int B, int C, int H, int W, int k,
+                           hipStream_t stream)
 {
-    const int vec = (W % 4) == 0 && (((size_t)x) & 15) == 0;
-    const size_t tiles = (size_t)B * H * ((W + 63) / 64);   // upper bound of the grid size
+    const int vec = (W % 4) == 0 && (((size_t)x | (size_t)y) & 15) == 0;
+    const size_t tiles = (size_t)B * H * ((W + 63) / 64);   // upper bound of the tile count
     bool done = true;
     if (tiles > 0x7fffffffull || (size_t)C * H * W > 0x7fffffffull) done = false;
-    else if (C == 1 && k == 3) launch_small<1, 3>(x, w, y, B, H, W, vec, stream);
-    else if (C == 2 && k == 3) launch_small<2, 3>(x, w, y, B, H, W, vec, stream);
-    else if (C == 3 && k == 3) launch_small<3, 3>(x, w, y, B, H, W, vec, stream);
-    else if (C == 4 && k == 3) launch_small<4, 3>(x, w, y, B, H, W, vec, stream);
-    else if (C == 3 && k == 5) launch_small<3, 5>(x, w, y, B, H, W, vec, stream);
+    else if (C == 1 && k == 3) launch_small<1, 3, DIR>(x, w, y, B, H, W, vec, stream);
+    else if (C == 2 && k == 3) launch_small<2, 3, DIR>(x, w, y, B, H, W, vec, stream);
+    else if (C == 3 && k == 3) launch_small<3, 3, DIR>(x, w, y, B, H, W, vec, stream);
+    else if (C == 4 && k == 3) launch_small<4, 3, DIR>(x, w, y, B, H, W, vec, stream);
+    else if (C == 3 && k == 5) launch_small<3, 5, DIR>(x, w, y, B, H, W, vec, stream);
     else {
         const ConvPlan p = plan_m16(C, k);
         if (p.lds == 0) done = false;
         else switch (p.nsc) {
-            case 4: launch_m16<4>(x, w, y, B, C, H, W, k, p, vec, stream); break;
-            case 8: launch_m16<8>(x, w, y, B, C, H, W, k, p, vec, stream); break;
-            case 12: launch_m16<12>(x, w, y, B, C, H, W, k, p, vec, stream); break;
-            case 16: launch_m16<16>(x, w, y, B, C, H, W, k, p, vec, stream); break;
-            case 20: launch_m16<20>(x, w, y, B, C, H, W, k, p, vec, stream); break;
-            case 24: launch_m16<24>(x, w, y, B, C, H, W, k, p, vec, stream); break;
-            case 28: launch_m16<28>(x, w, y, B, C, H, W, k, p, vec, stream); break;
-            case 32: launch_m16<32>(x, w, y, B, C, H, W, k, p, vec, stream); break;
-            case 36: launch_m16<36>(x, w, y, B, C, H, W, k, p, vec, stream); break;
-            default: launch_m16<40>(x, w, y, B, C, H, W, k, p, vec, stream); break;
+            case 4: launch_m16<4, DIR>(x, w, y, B, C, H, W, k, p, vec, stream); break;
+            case 8: launch_m16<8, DIR>(x, w, y, B, C, H, W, k, p, vec, stream); break;
+            case 12: launch_m16<12, DIR>(x, w, y, B, C, H, W, k, p, vec, stream); break;
+            case 16: launch_m16<16, DIR>(x, w, y, B, C, H, W, k, p, vec, stream); break;
+            case 20: launch_m16<20, DIR>(x, w, y, B, C, H, W, k, p, vec, stream); break;
+            case 24: launch_m16<24, DIR>(x, w, y, B, C, H, W, k, p, vec, stream); break;
+            case 28: launch_m16<28, DIR>(x, w, y, B, C, H, W, k, p, vec, stream); break;
+            case 32: launch_m16<32, DIR>(x, w, y, B, C, H, W, k, p, vec, stream); break;
+            case 36: launch_m16<36, DIR>(x, w, y, B, C, H, W, k, p, vec, stream); break;
+            default: launch_m16<40, DIR>(x, w, y, B, C, H, W, k, p, vec, stream); break;
         }
     }
     if (!done) {
         const size_t total = (size_t)B * C * H * W;
         size_t blocks = (total + 255) / 256;
         if (blocks > 65536) blocks = 65536;
-        hipLaunchKernelGGL(k_conv_generic, dim3((unsigned)blocks), dim3(256), 0, stream, x, w, y, B, C, H, W, k);
+        hipLaunchKernelGGL(k_conv_generic<DIR>, dim3((unsigned)blocks), dim3(256), 0, stream, x, w, y, B, C, H, W, k);
     }
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+int launch_conv(int dir, const float *x, const float *w, float *y, int B, int C, int H, int W, int k, hipStream_t stream)
+{
+    return dir ? launch_conv_dir<1>(x, w, y, B, C, H, W, k, stream) : launch_conv_dir<0>(x, w, y, B, C, H, W, k, stream);
 }
 
 }  // namespace invconv

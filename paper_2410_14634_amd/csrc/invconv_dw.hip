@@ -200,14 +200,14 @@ static int launch_dw_partial_batch(const DwBatch &batch, int layers, float *part
 }
 
 int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
-                   int W, int k, hipStream_t stream)
+                   int W, int k, hipStream_t stream, float sign)
 {
     DwBatch batch{};
     batch.x[0] = x;
     batch.v[0] = v;
     if (int s = launch_dw_partial_batch(batch, 1, part, p, B, C, H, W, k, stream))
         return s;
-    return launch_dw_reduce(part, (int)p.nparts, dw, C, k, stream);
+    return launch_dw_reduce(part, (int)p.nparts, dw, C, k, stream, sign);
 }
 
 // dL/dw of `layers` layers: one pass-1 launch over all of them, then one pass 2 per layer.

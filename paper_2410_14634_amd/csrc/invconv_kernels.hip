@@ -196,8 +196,9 @@ int launch_probe(int mode, int steps, int blocks, hipStream_t stream)
 // ---------------------------------------------------------------------------
 // Weight gradient, pass 1 (Eq. 4 with Theorem 2):
 //   dw[o][i][a][b] = - sum_{n,r,c} v[n][o][r][c] * x[n][i][r-(k-1)+a][c-(k-1)+b].
-// One workgroup per (image, chunk of RT rows) stages v and x (with a zero
-// halo of k-1 rows/columns on the top/left) in LDS and writes the un-negated
+// One workgroup per (image, chunk of RT rows x CW columns) stages v and x (with
+// a halo of k-1 rows/columns on the top/left, zero outside the image) in LDS
+// and writes the un-negated
 // partial sums of all P = C*C*k*k entries to part[workgroup][P].  When P is
 // smaller than the block, G = block/P thread groups split the pixels and are
 // combined in a fixed order through LDS.
@@ -205,28 +206,30 @@ int launch_probe(int mode, int steps, int blocks, hipStream_t stream)
 __global__ __launch_bounds__(kDwBlock) void k_dw_partial(const float *__restrict__ x,
                                                         const float *__restrict__ v,
                                                         float *__restrict__ part,
-                                                        int C, int H, int W, int k, int RT, int nchunks)
+                                                        int C, int H, int W, int k, int RT, int nchunks, int CW, int ncol)
 {
     extern __shared__ float smem[];
-    const int n = blockIdx.x / nchunks, chunk = blockIdx.x % nchunks;
-    const int r0 = chunk * RT;
+    const int per_image = nchunks * ncol;
+    const int n = blockIdx.x / per_image, chunk = (blockIdx.x % per_image) / ncol, cchunk = blockIdx.x % ncol;
+    const int r0 = chunk * RT, c0 = cchunk * CW;
     const int rows = (H - r0 < RT) ? H - r0 : RT;
-    const int XR = RT + k - 1, XW = W + k - 1;
+    const int cols = (W - c0 < CW) ? W - c0 : CW;
+    const int XR = RT + k - 1, XW = CW + k - 1;
     const int P = C * C * k * k;
     const int G = (P < kDwBlock) ? kDwBlock / P : 1;
-    float *sv = smem;                 // [C][RT][W]
-    float *sx = sv + C * RT * W;      // [C][XR][XW], origin at (r0-(k-1), -(k-1))
+    float *sv = smem;                 // [C][RT][CW]
+    float *sx = sv + C * RT * CW;     // [C][XR][XW], origin at (r0-(k-1), c0-(k-1))
     float *sred = sx + C * XR * XW;   // [G][P] when G > 1
     const int tid = threadIdx.x;
 
-    for (int idx = tid; idx < C * rows * W; idx += kDwBlock) {
-        const int c = idx % W, r = (idx / W) % rows, ch = idx / (W * rows);
-        sv[(ch * RT + r) * W + c] = v[(((size_t)n * C + ch) * H + r0 + r) * W + c];
+    for (int idx = tid; idx < C * rows * cols; idx += kDwBlock) {
+        const int c = idx % cols, r = (idx / cols) % rows, ch = idx / (cols * rows);
+        sv[(ch * RT + r) * CW + c] = v[(((size_t)n * C + ch) * H + r0 + r) * W + c0 + c];
     }
-    const int xrows = rows + k - 1;
-    for (int idx = tid; idx < C * xrows * XW; idx += kDwBlock) {
-        const int cc = idx % XW, rr = (idx / XW) % xrows, ch = idx / (XW * xrows);
-        const int gr = r0 - (k - 1) + rr, gc = cc - (k - 1);
+    const int xrows = rows + k - 1, xcols = cols + k - 1;
+    for (int idx = tid; idx < C * xrows * xcols; idx += kDwBlock) {
+        const int cc = idx % xcols, rr = (idx / xcols) % xrows, ch = idx / (xcols * xrows);
+        const int gr = r0 - (k - 1) + rr, gc = c0 - (k - 1) + cc;
         sx[(ch * XR + rr) * XW + cc] =
             (gr >= 0 && gc >= 0) ? x[(((size_t)n * C + ch) * H + gr) * W + gc] : 0.0f;
     }
@@ -234,16 +237,16 @@ __global__ __launch_bounds__(kDwBlock) void k_dw_partial(const float *__restrict
 
     const int lanesE = (G > 1) ? P : kDwBlock;
     const int s = tid / lanesE, e0 = tid % lanesE;
-    const int npix = rows * W;
+    const int npix = rows * cols;
     if (s < G) {
         for (int e = e0; e < P; e += lanesE) {
             const int b = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
-            const float *pv = sv + o * RT * W;
+            const float *pv = sv + o * RT * CW;
             const float *px = sx + (i * XR + a) * XW + b;
             float acc = 0.0f;
             for (int p = s; p < npix; p += G) {
-                const int r = p / W, c = p - r * W;
-                acc += pv[r * W + c] * px[r * XW + c];
+                const int r = p / cols, c = p - r * cols;
+                acc += pv[r * CW + c] * px[r * XW + c];
             }
             if (G > 1)
                 sred[s * P + e] = acc;
@@ -270,7 +273,7 @@ __global__ __launch_bounds__(kDwBlock) void k_dw_partial(const float *__restrict
 // blockIdx.y selects the layer when several layers are reduced by one launch
 // (layer l's rows start at part + l*nparts*P, its result goes to out.p[l]).
 __global__ __launch_bounds__(256) void k_dw_reduce(const float *__restrict__ part_all, int nparts, PtrList out,
-                                                  int C, int k)
+                                                  int C, int k, float sign)
 {
     __shared__ double swave[4][64];
     const int P = C * C * k * k;
@@ -299,7 +302,7 @@ __global__ __launch_bounds__(256) void k_dw_reduce(const float *__restrict__ par
         const double total = ((swave[0][lane] + swave[1][lane]) + swave[2][lane]) + swave[3][lane];
         const int b = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
         const bool is_masked = (a == k - 1 && b == k - 1 && i > o);
-        dw[e] = is_masked ? 0.0f : (float)(-total);
+        dw[e] = is_masked ? 0.0f : (float)(sign < 0.0f ? -total : total);
     }
 }
 
@@ -415,22 +418,28 @@ DwPlan plan_dw(int B, int C, int H, int W, int k)
     const size_t P = (size_t)C * C * k * k;
     const size_t G = P < (size_t)kDwBlock ? kDwBlock / P : 1;
     const size_t red = G > 1 ? G * P : 0;
-    // largest row chunk whose tiles fit the LDS budget
-    auto lds_for = [&](int rt) {
-        return sizeof(float) * ((size_t)C * rt * W + (size_t)C * (rt + k - 1) * (W + k - 1) + red);
+    // largest row chunk whose tiles fit the LDS budget; an image too wide for one row is also cut into
+    // column chunks
+    auto lds_for = [&](int rt, int cw) {
+        return sizeof(float) * ((size_t)C * rt * cw + (size_t)C * (rt + k - 1) * (cw + k - 1) + red);
     };
-    if (lds_for(1) > kDwLdsBudget)
+    int cw = W;
+    while (cw > 1 && lds_for(1, cw) > kDwLdsBudget)
+        cw = (cw + 1) / 2;
+    if (lds_for(1, cw) > kDwLdsBudget)
         return p;   // rt == 0: unsupported
     int want = (int)((1024 + B - 1) / B);          // aim for about a thousand workgroups
     if (want < 1) want = 1;
     int rt = (H + want - 1) / want;
     if (rt < 1) rt = 1;
-    while (rt > 1 && lds_for(rt) > kDwLdsBudget)
+    while (rt > 1 && lds_for(rt, cw) > kDwLdsBudget)
         --rt;
     p.rt = rt;
     p.nchunks = (H + rt - 1) / rt;
-    p.nparts = (size_t)B * p.nchunks;
-    p.lds = lds_for(rt);
+    p.cw = cw;
+    p.ncol = (W + cw - 1) / cw;
+    p.nparts = (size_t)B * p.nchunks * p.ncol;
+    p.lds = lds_for(rt, cw);
     p.bytes = ((p.nparts * P * sizeof(float)) + 255) / 256 * 256;
     return p;
 }
@@ -452,23 +461,23 @@ DwPlan plan_dw_any(int B, int C, int H, int W, int k)
 }
 
 int launch_dw(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
-              int W, int k, hipStream_t stream)
+              int W, int k, hipStream_t stream, float sign)
 {
     hipLaunchKernelGGL(k_dw_partial, dim3((unsigned)p.nparts), dim3(kDwBlock), p.lds, stream, x, v, part, C, H,
-                       W, k, p.rt, p.nchunks);
+                       W, k, p.rt, p.nchunks, p.cw, p.ncol);
     if (hipGetLastError() != hipSuccess)
         return INVCONV_ERR_LAUNCH;
-    return launch_dw_reduce(part, (int)p.nparts, dw, C, k, stream);
+    return launch_dw_reduce(part, (int)p.nparts, dw, C, k, stream, sign);
 }
 
-int launch_dw_reduce(const float *part, int nparts, float *dw, int C, int k, hipStream_t stream)
+int launch_dw_reduce(const float *part, int nparts, float *dw, int C, int k, hipStream_t stream, float sign)
 {
-    return launch_dw_reduce_layers(part, nparts, &dw, 1, C, k, stream);
+    return launch_dw_reduce_layers(part, nparts, &dw, 1, C, k, stream, sign);
 }
 
 // Second pass for `layers` layers in one launch (rows of layer l start at part + l*nparts*P).
 int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int layers, int C, int k,
-                            hipStream_t stream)
+                            hipStream_t stream, float sign)
 {
     if (layers < 1 || layers > kChainMaxLayers)
         return INVCONV_ERR_SHAPE;
@@ -476,7 +485,7 @@ int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int
     PtrList out{};
     for (int l = 0; l < layers; ++l)
         out.p[l] = dw[l];
-    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 63) / 64, layers), dim3(256), 0, stream, part, nparts, out, C, k);
+    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 63) / 64, layers), dim3(256), 0, stream, part, nparts, out, C, k, sign);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

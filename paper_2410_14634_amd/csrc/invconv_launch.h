@@ -15,7 +15,8 @@ constexpr int kChainMaxLayers = 16;
 
 struct DwPlan {
     int rt;          // rows per chunk (0 = shape unsupported)
-    int nchunks;     // chunks per image
+    int nchunks;     // row chunks per image
+    int cw, ncol;    // generic pass 1: columns per chunk, column chunks per row chunk (cw = W, ncol = 1 unless W is too wide for LDS)
     int groups;      // matrix-core pass 1: workgroups per image, each looping over chunks
     size_t nparts;   // workgroups of pass 1 = rows of the partial-sum matrix
     size_t lds;      // dynamic LDS bytes of pass 1
@@ -36,24 +37,25 @@ int launch_solve_band(int dir, const float *in, const float *w, float *out, int 
 bool bwd_wave_supported(int C, int H, int W, int k);
 int launch_bwd_wave(const float *x, const float *w, const float *g, float *v, float *part, int B, int C, int H,
                     int W, int k, hipStream_t stream);
-int launch_dw_reduce(const float *part, int nparts, float *dw, int C, int k, hipStream_t stream);
+// sign: -1 for the inverse convolution's dL/dw (Theorem 2), +1 for the convolution's own
+int launch_dw_reduce(const float *part, int nparts, float *dw, int C, int k, hipStream_t stream, float sign = -1.0f);
 int launch_solve_persistent(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W,
                             int k, hipStream_t stream);
 int launch_probe(int mode, int steps, int blocks, hipStream_t stream);
 DwPlan plan_dw(int B, int C, int H, int W, int k);
 int launch_dw(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
-              int W, int k, hipStream_t stream);
+              int W, int k, hipStream_t stream, float sign = -1.0f);
 bool dw_mfma_supported(int C, int k);
 DwPlan plan_dw_mfma(int B, int C, int H, int W, int k);
 int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
-                   int W, int k, hipStream_t stream);
+                   int W, int k, hipStream_t stream, float sign = -1.0f);
 int launch_dw_mfma_layers(const float *const *x, const float *const *v, float *const *dw, int layers, float *part,
                           const DwPlan &p, int B, int C, int H, int W, int k, hipStream_t stream);
 DwPlan plan_dw_any(int B, int C, int H, int W, int k);
 struct PtrList { float *p[kChainMaxLayers]; };
 struct ConstPtrList { const float *p[kChainMaxLayers]; };
 int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int layers, int C, int k,
-                            hipStream_t stream);
+                            hipStream_t stream, float sign = -1.0f);
 int launch_logdet_layers(const float *const *w, int layers, int C, int H, int W, int k, float *out,
                          hipStream_t stream);
 struct ChainArgs {
@@ -67,7 +69,9 @@ struct ChainArgs {
 bool chain_supported(int stages, int C, int H, int k);
 size_t chain_flag_ints(int stages, int B);
 int launch_chain(int dir, ChainArgs args, int C, int k, hipStream_t stream);
-int launch_conv(const float *x, const float *w, float *y, int B, int C, int H, int W, int k, hipStream_t stream);
+// y = M x (dir 0) or y = M^T x (dir 1) for the masked causal convolution M
+int launch_conv(int dir, const float *x, const float *w, float *y, int B, int C, int H, int W, int k,
+                hipStream_t stream);
 int launch_logdet(const float *w, int C, int H, int W, int k, float *out, hipStream_t stream);
 
 }  // namespace invconv

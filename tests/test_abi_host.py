@@ -58,6 +58,18 @@ def test_conv_rejects_bad_arguments():
     assert L.invconv_conv_fwd(x, w, x, 1, 1, 4, 4, 3, None) == b.ERR_ALIAS
 
 
+def test_conv_bwd_rejects_bad_arguments():
+    L = b.lib()
+    x, w, g, dx, dw, ws = FAKE[:6]
+    need = L.invconv_bwd_workspace_bytes(2, 3, 8, 8, 3)
+    assert L.invconv_conv_bwd(None, w, g, dx, dw, 2, 3, 8, 8, 3, ws, need, None) == b.ERR_NULL
+    assert L.invconv_conv_bwd(x, w, g, None, dw, 2, 3, 8, 8, 3, ws, need, None) == b.ERR_NULL
+    assert L.invconv_conv_bwd(x, w, g, dx, dw, 2, 3, 8, 0, 3, ws, need, None) == b.ERR_SHAPE
+    assert L.invconv_conv_bwd(x, w, g, g, dw, 2, 3, 8, 8, 3, ws, need, None) == b.ERR_ALIAS
+    assert L.invconv_conv_bwd(x, w, g, dx, dw, 2, 3, 8, 8, 3, None, need, None) == b.ERR_WORKSPACE
+    assert L.invconv_conv_bwd(x, w, g, dx, dw, 2, 3, 8, 8, 3, ws, need - 1, None) == b.ERR_WORKSPACE
+
+
 def test_bwd_rejects_bad_arguments():
     L = b.lib()
     x, w, g, v, dw, ws = FAKE[:6]

@@ -5,7 +5,7 @@ import pytest
 import oracle
 from paper_2410_14634_amd import binding as b
 from paper_2410_14634_amd import inputs
-from tests.util import THREADS, TOL_ACT, dev, elementwise_ok, host, rel_err
+from tests.util import THREADS, TOL_ACT, TOL_DW, dev, elementwise_ok, host, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -32,6 +32,62 @@ def check_conv(x, w):
     e = rel_err(y, yr)
     assert e <= TOL_ACT and elementwise_ok(y, yr, TOL_ACT), f"conv rel err {e}"
     return y
+
+
+def check_conv_bwd(x, w, g):
+    import torch
+    dx, dw = b.invconv_conv_bwd(dev(x), dev(w), dev(g))
+    torch.cuda.synchronize()
+    dx, dw = host(dx), host(dw)
+    dxr, dwr = oracle.conv_bwd(x, w, g, THREADS)
+    ex, ew = rel_err(dx, dxr), rel_err(dw, dwr)
+    assert ex <= TOL_ACT and elementwise_ok(dx, dxr, TOL_ACT), f"conv dL/dx rel err {ex}"
+    assert ew <= TOL_DW, f"conv dL/dw rel err {ew}"
+    return dx, dw
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3])
+def test_conv_bwd_workload_parity(cfg):
+    wl = inputs.make_workload(cfg)
+    print(f"conv bwd workload {cfg}", flush=True)
+    check_conv_bwd(wl["y"], wl["w"][0], wl["g"])
+
+
+def test_conv_bwd_workload4_reduced_batch_parity():
+    wl = inputs.make_workload(4, B=4, layers=1)
+    check_conv_bwd(wl["y"], wl["w"][0], wl["g"])
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv_bwd_edge_shapes(shape):
+    B, C, H, W, k = shape
+    print(f"conv bwd edge {shape}", flush=True)
+    cs = inputs.make_case(B, C, H, W, k, seed=sum(shape) + 3, tap_std=0.05)
+    check_conv_bwd(cs["y"], cs["w"][0], cs["g"])
+
+
+def test_conv_bwd_masked_entries_get_zero_gradient_and_are_ignored():
+    cs = inputs.make_case(2, 4, 9, 9, 3, seed=6, tap_std=0.05)
+    w = cs["w"][0].copy()
+    dx0, dw0 = check_conv_bwd(cs["y"], w, cs["g"])
+    for o in range(4):
+        for i in range(o + 1, 4):
+            w[o, i, 2, 2] = 1e6
+            assert dw0[o, i, 2, 2] == 0.0
+    dx1, dw1 = check_conv_bwd(cs["y"], w, cs["g"])
+    assert np.array_equal(dx0, dx1) and np.array_equal(dw0, dw1)
+
+
+def test_conv_bwd_adjoint_identity_on_gpu():
+    import torch
+    wl = inputs.make_workload(1)
+    xd, wd, gd = dev(wl["y"]), dev(wl["w"][0]), dev(wl["g"])
+    y = b.invconv_conv_fwd(xd, wd)
+    dx, _ = b.invconv_conv_bwd(xd, wd, gd)
+    torch.cuda.synchronize()
+    lhs = float((y.double() * gd.double()).sum())
+    rhs = float((xd.double() * dx.double()).sum())
+    assert abs(lhs - rhs) <= 1e-5 * max(abs(lhs), 1.0)
 
 
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3])

@@ -63,6 +63,7 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     (2, 12, 16, 16, 3), (1, 12, 33, 20, 3), (2, 8, 50, 17, 3), (1, 16, 128, 40, 3), (1, 12, 7, 100, 3),
     (3, 12, 1, 1, 3), (1, 8, 17, 2, 3), (1, 12, 129, 8, 3),
     (1, 20, 6, 7, 2), (2, 18, 9, 5, 3),      # more than 16 channels: generic solve and generic dL/dw
+    (1, 3, 17, 1200, 3), (1, 12, 4, 1400, 3),    # wide images: dL/dw row tiles beyond the preferred LDS budget
 ]
 
 
