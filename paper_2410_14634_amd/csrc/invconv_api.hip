@@ -32,12 +32,16 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
     case INVCONV_VARIANT_AUTO:
         if (wave_supported(C, H, k))
             return launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream);
+        if (wave_bands_supported(C, H, W, k))
+            return launch_solve_wave_bands(dir, in, w, out, B, C, H, W, k, stream);
         if (band_supported(C, H, k))
             return launch_solve_band(dir, in, w, out, B, C, H, W, k, stream);
         return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_BLOCK:
         return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_WAVE:
+        if (wave_bands_supported(C, H, W, k))
+            return launch_solve_wave_bands(dir, in, w, out, B, C, H, W, k, stream);
         return launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_BAND:
         return launch_solve_band(dir, in, w, out, B, C, H, W, k, stream);
@@ -65,12 +69,13 @@ invconv_status invconv_fwd_ex(const float *y, const float *w, float *x, int B, i
         return INVCONV_ERR_ALIAS;
     if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_PERSISTENT)
         return INVCONV_ERR_VARIANT;
-    if (variant == INVCONV_VARIANT_WAVE && !wave_supported(C, H, k))
+    if (variant == INVCONV_VARIANT_WAVE && !wave_supported(C, H, k) && !wave_bands_supported(C, H, W, k))
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_BAND && !band_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_BLOCK ||
-        (variant == INVCONV_VARIANT_AUTO && !wave_supported(C, H, k) && !band_supported(C, H, k)))
+        (variant == INVCONV_VARIANT_AUTO && !wave_supported(C, H, k) && !wave_bands_supported(C, H, W, k) &&
+         !band_supported(C, H, k)))
         if (int s = check_supported(C, H, k))
             return s;
     return solve(0, y, w, x, B, C, H, W, k, (hipStream_t)stream, variant);
@@ -138,12 +143,13 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
         return INVCONV_ERR_ALIAS;
     if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_PERSISTENT)
         return INVCONV_ERR_VARIANT;
-    if (variant == INVCONV_VARIANT_WAVE && !wave_supported(C, H, k))
+    if (variant == INVCONV_VARIANT_WAVE && !wave_supported(C, H, k) && !wave_bands_supported(C, H, W, k))
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_BAND && !band_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_BLOCK ||
-        (variant == INVCONV_VARIANT_AUTO && !wave_supported(C, H, k) && !band_supported(C, H, k)))
+        (variant == INVCONV_VARIANT_AUTO && !wave_supported(C, H, k) && !wave_bands_supported(C, H, W, k) &&
+         !band_supported(C, H, k)))
         if (int s = check_supported(C, H, k))
             return s;
     const DwPlan p = plan_dw_any(B, C, H, W, k);

@@ -35,6 +35,9 @@ bool band_supported(int C, int H, int k);
 int launch_solve_band(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                       hipStream_t stream);
 bool bwd_wave_supported(int C, int H, int W, int k);
+bool wave_bands_supported(int C, int H, int W, int k);
+int launch_solve_wave_bands(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                            hipStream_t stream);
 int launch_bwd_wave(const float *x, const float *w, const float *g, float *v, float *part, int B, int C, int H,
                     int W, int k, hipStream_t stream);
 // sign: -1 for the inverse convolution's dL/dw (Theorem 2), +1 for the convolution's own

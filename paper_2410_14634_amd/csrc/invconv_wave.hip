@@ -33,22 +33,52 @@ __device__ __forceinline__ float from_lane_above(float v)
         float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x138 /* wave_shr:1 */, 0xf, 0xf, true));
 }
 
+// value of the lane above; lane 0 keeps `first` (what the row above the wave's first row sent)
+__device__ __forceinline__ float from_lane_above_or(float first, float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, first),
+                                                                 __builtin_bit_cast(int, v), 0x138 /* wave_shr:1 */,
+                                                                 0xf, 0xf, false));
+}
+
 constexpr int kWavePF = 16;   // steps of load prefetch
+
+// Images of more than 64 rows are cut into bands of 64 rows, one wave each, all in one workgroup
+// (BANDS).  A band is the single-wave solve on its own rows and its own clock (local step j,
+// lane l at column j - l); what row 63 of the band above would have handed to lane 0 through the
+// DPP shift arrives through LDS instead: after its local step j' the upper band's lane 63 appends
+// its messages T[1..K-1] to a log, entry j'; the lower band's lane 0 needs entry j + 63 at its step
+// j (its row is 64 rows further down, so the same anti-diagonal is 64 local steps earlier).  The
+// log keeps every step (no slot is reused, so a fast upper band can never overwrite what the
+// lower one has not read), progress is published once per block of kWavePF steps in an LDS
+// counter, and the lower band starts a block only when the counter covers the block's last entry.
+// The upper band never waits for the lower one, so the waits end; they are bounded all the same.
+struct WaveBands {
+    int band;           // this wave's band
+    int nbands;
+    f32x4 *log;         // [nbands - 1][log_steps][K - 1]
+    int *prog;          // [nbands - 1] local steps finished by band b
+    int log_steps;      // entries per band, a multiple of kWavePF
+    f32x4 *scratch;     // [64][K - 1] write-only dump for the lanes that have nothing to send
+};
+constexpr int kBandSpinLimit = 1 << 22;
 
 // Body of the solve for image n, executed by one full wave (lanes 0..63 of the
 // calling workgroup).  With LDS_COPY the result is also written to lds_copy as a
 // [C][H][W] tile in image (not mirrored) coordinates.
-template <int C, int K, int DIR, bool LDS_COPY>
+template <int C, int K, int DIR, bool LDS_COPY, bool BANDS = false>
 __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, const float *__restrict__ w,
-                                                float *__restrict__ out, int H, int W, int n, float *lds_copy)
+                                                float *__restrict__ out, int H, int W, int n, float *lds_copy,
+                                                WaveBands wb = WaveBands{})
 {
     static_assert(C >= 1 && C <= 4, "one 4-row MFMA block per pixel");
     // All 64 lanes stay active to the end: the matrix instruction reads its weight
     // operand from every lane of a 4-lane block, whatever the execution mask says.
     // Lanes past the last row compute on clamped inputs and never store.
-    const int r = threadIdx.x & 63;
-    const bool row_ok = r < H;
-    const int rr = row_ok ? r : H - 1;
+    const int r = threadIdx.x & 63;                   // row inside the band = lane
+    const int grow = BANDS ? 64 * wb.band + r : r;    // image row
+    const bool row_ok = grow < H;
+    const int rr = row_ok ? grow : H - 1;
     const int o_lane = r & 3;
     const unsigned Wst = row_ok ? (unsigned)W : 0u;   // columns this lane may store
 
@@ -186,15 +216,49 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
         ldoff += kStep;
     }
 
-    const int nsteps = H + W - 1;
+    const int band_rows = BANDS ? (H - 64 * wb.band < 64 ? H - 64 * wb.band : 64) : H;
+    const int nsteps = band_rows + W - 1;
+    const bool recv = BANDS && wb.band > 0, send = BANDS && wb.band + 1 < wb.nbands;
+    // (plain offsets from the LDS base, never a null alternative: the accesses stay LDS instructions)
+    const f32x4 *log_in = wb.log + (recv ? wb.band - 1 : 0) * wb.log_steps * (K - 1);
+    f32x4 *log_out = wb.log + (send ? wb.band : 0) * wb.log_steps * (K - 1);
+    f32x4 M[K];          // M[a]: what the band above sent for this step (used by lane 0 only)
+#pragma unroll
+    for (int a = 0; a < K; ++a)
+        M[a] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int t0 = 0; t0 < nsteps; t0 += kWavePF) {
+        if (recv) {
+            // entries t0 + 63 .. t0 + 63 + kWavePF - 1 of the upper band's log are needed
+            int need = t0 + 64 + kWavePF;
+            need = need > wb.log_steps ? wb.log_steps : need;
+            int spins = 0;
+            while (__hip_atomic_load(wb.prog + wb.band - 1, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < need &&
+                   ++spins < kBandSpinLimit)
+                __builtin_amdgcn_s_sleep(1);
+        }
+        // Entry of the first step now, the others one step ahead of their use (volatile: the read is
+        // issued where it is written, well before the value is needed).
+        f32x4 Mn[K];
+        if (recv) {
+            const int e = t0 + 63 < wb.log_steps ? t0 + 63 : wb.log_steps - 1;
+#pragma unroll
+            for (int a = 1; a < K; ++a)
+                M[a] = log_in[e * (K - 1) + a - 1];
+        }
 #pragma unroll
         for (int u = 0; u < kWavePF; ++u) {
+            if (recv && u + 1 < kWavePF) {
+                int e = t0 + u + 64;
+                e = e < wb.log_steps ? e : wb.log_steps - 1;     // past the upper band's last step: unused
+#pragma unroll
+                for (int a = 1; a < K; ++a)
+                    Mn[a] = *(const volatile __attribute__((address_space(3))) f32x4 *)(log_in + e * (K - 1) + a - 1);
+            }
             // x(r,c) = own + (message from the row above, computed there one step ago)
             float xn[C];
 #pragma unroll
             for (int o = 0; o < C; ++o)
-                xn[o] = own[o] + from_lane_above(T[1][o]);
+                xn[o] = own[o] + (BANDS ? from_lane_above_or(M[1][o], T[1][o]) : from_lane_above(T[1][o]));
             if ((unsigned)c < Wst) {
                 const unsigned off = (unsigned)(row0 + kStep * c);
 #pragma unroll
@@ -211,7 +275,7 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
                 if (a + 1 < K) {
 #pragma unroll
                     for (int o = 0; o < C; ++o)
-                        acc[o] = from_lane_above(T[a + 1][o]);
+                        acc[o] = BANDS ? from_lane_above_or(M[a + 1][o], T[a + 1][o]) : from_lane_above(T[a + 1][o]);
                 }
 #pragma unroll
                 for (int db = K - 1; db >= 0; --db)     // oldest column first: only db = 0 waits for this step's result
@@ -219,6 +283,19 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
                     for (int i = 0; i < C; ++i)
                         acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[a][db][i], xh[i][db], acc, 0, 0, 0);
                 T[a] = acc;
+            }
+            if (send) {
+                // lane 63 appends to the log; the other lanes write to a scratch line of their own, so that
+                // no branch surrounds the LDS write (a branch makes the wait counters conservative)
+                f32x4 *dst = r == 63 ? log_out + (t0 + u) * (K - 1) : wb.scratch + r * (K - 1);
+#pragma unroll
+                for (int a = 1; a < K; ++a)
+                    dst[a - 1] = T[a];
+            }
+            if (recv && u + 1 < kWavePF) {
+#pragma unroll
+                for (int a = 1; a < K; ++a)
+                    M[a] = Mn[a];
             }
             // shift the row history and prepare `own` for the next pixel
 #pragma unroll
@@ -248,6 +325,8 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
                 ldoff += kStep;
             }
         }
+        if (send)       // the block's log entries are written (LDS operations of a wave complete in order)
+            __hip_atomic_store(wb.prog + wb.band, t0 + kWavePF, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
 }
 
@@ -256,6 +335,25 @@ __global__ __launch_bounds__(64) void k_solve_wave(const float *__restrict__ in,
                                                   float *__restrict__ out, int H, int W)
 {
     solve_wave_body<C, K, DIR, false>(in, w, out, H, W, blockIdx.x, nullptr);
+}
+
+// Images of 65 .. 512 rows: one workgroup per image, one wave per band of 64 rows.
+template <int C, int K, int DIR>
+__global__ __launch_bounds__(512) void k_solve_wave_bands(const float *__restrict__ in, const float *__restrict__ w,
+                                                         float *__restrict__ out, int H, int W, int log_steps)
+{
+    extern __shared__ float smem[];
+    WaveBands wb;
+    wb.band = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    wb.nbands = blockDim.x >> 6;
+    wb.log = reinterpret_cast<f32x4 *>(smem);
+    wb.scratch = wb.log + (size_t)(wb.nbands - 1) * log_steps * (K - 1);
+    wb.prog = reinterpret_cast<int *>(wb.scratch + 64 * (K - 1));
+    wb.log_steps = log_steps;
+    if (threadIdx.x < wb.nbands - 1)
+        wb.prog[threadIdx.x] = 0;
+    __syncthreads();
+    solve_wave_body<C, K, DIR, false, true>(in, w, out, H, W, blockIdx.x, nullptr, wb);
 }
 
 // ---------------------------------------------------------------------------
@@ -364,6 +462,35 @@ static int launch_wave_ck(int dir, const float *in, const float *w, float *out, 
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
+static int wave_bands_log_steps(int W) { return (64 + W - 1 + kWavePF - 1) / kWavePF * kWavePF; }
+
+static size_t wave_bands_lds_bytes(int H, int W, int k)
+{
+    const size_t nb = (H + 63) / 64;
+    return ((nb - 1) * (size_t)wave_bands_log_steps(W) + 64) * (k - 1) * sizeof(f32x4) + nb * sizeof(int);
+}
+
+template <int C, int K>
+static int launch_wave_bands_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
+                                hipStream_t stream)
+{
+    const int nb = (H + 63) / 64, log_steps = wave_bands_log_steps(W);
+    const size_t lds = wave_bands_lds_bytes(H, W, K);
+    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave_bands<C, K, 1>)
+                         : reinterpret_cast<const void *>(&k_solve_wave_bands<C, K, 0>);
+    if (lds > 48 * 1024 && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+        (void)hipGetLastError();
+        return INVCONV_ERR_UNSUPPORTED;
+    }
+    if (dir)
+        hipLaunchKernelGGL((k_solve_wave_bands<C, K, 1>), dim3(B), dim3(64 * nb), lds, stream, in, w, out, H, W,
+                           log_steps);
+    else
+        hipLaunchKernelGGL((k_solve_wave_bands<C, K, 0>), dim3(B), dim3(64 * nb), lds, stream, in, w, out, H, W,
+                           log_steps);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
 size_t bwd_wave_lds_bytes(int C, int H, int W, int k)
 {
     const size_t tiles = (size_t)C * H * W + (size_t)C * (H + k - 1) * (W + k - 1);
@@ -405,11 +532,30 @@ int launch_bwd_wave(const float *x, const float *w, const float *g, float *v, fl
     return INVCONV_ERR_VARIANT;
 }
 
-bool wave_supported(int C, int H, int k)
+static bool wave_ck(int C, int k)
 {
-    if (H > 64)
-        return false;
     return (C == 3 && (k == 3 || k == 5)) || (C == 1 && k == 3) || (C == 2 && k == 3) || (C == 4 && k == 3);
+}
+
+bool wave_supported(int C, int H, int k) { return H <= 64 && wave_ck(C, k); }
+
+// 65 .. 512 rows, bands of 64 rows; the message log of the band boundaries has to fit LDS
+bool wave_bands_supported(int C, int H, int W, int k)
+{
+    return H > 64 && H <= 512 && wave_ck(C, k) && wave_bands_lds_bytes(H, W, k) <= 128 * 1024;
+}
+
+int launch_solve_wave_bands(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                            hipStream_t stream)
+{
+    if (!wave_bands_supported(C, H, W, k))
+        return INVCONV_ERR_VARIANT;
+    if (C == 3 && k == 3) return launch_wave_bands_ck<3, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 5) return launch_wave_bands_ck<3, 5>(dir, in, w, out, B, H, W, stream);
+    if (C == 1 && k == 3) return launch_wave_bands_ck<1, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 2 && k == 3) return launch_wave_bands_ck<2, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 4 && k == 3) return launch_wave_bands_ck<4, 3>(dir, in, w, out, B, H, W, stream);
+    return INVCONV_ERR_VARIANT;
 }
 
 int launch_solve_wave(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
