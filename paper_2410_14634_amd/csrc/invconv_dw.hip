@@ -25,32 +25,35 @@ struct DwBatch {
 };
 
 constexpr int kDwHalo = 4;      // left halo of the x tile, in columns (>= k-1, keeps rows 16-byte aligned)
+constexpr int kDwUnroll = 4;    // pixel quads per trip of the product loop
 
 template <int NS>
 __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *__restrict__ part, int B, int C,
-                                                        int H, int W, int k, int RT, int nchunks, int G, int vec)
+                                                        int H, int W, int k, int RT, int nchunks, int G, int vec,
+                                                        int XW, int SXC, int SVC)
 {
     extern __shared__ float smem[];
     // blockIdx = ((layer * B + n) * G + cg); this workgroup takes chunks cg, cg+G, ... of image n
     const int cg = blockIdx.x % G, n = (blockIdx.x / G) % B, layer = blockIdx.x / (G * B);
     const float *__restrict__ x = batch.x[layer];
     const float *__restrict__ v = batch.v[layer];
-    const int XR = RT + k - 1, XW = W + kDwHalo;
+    // XW >= W + kDwHalo, SXC >= (RT + k - 1) * XW and SVC >= RT * W: row / channel strides padded by the
+    // host so that the 64 lanes of an operand read fall into different LDS banks
     const int NCOL = C * k * k;
     const int P = C * NCOL;
-    float *sv = smem;                 // [C][RT][W]
-    float *sx = sv + C * RT * W;      // [C][XR][XW], origin at (r0-(k-1), -kDwHalo)
+    float *sv = smem;                 // [C] x SVC, rows of W floats
+    float *sx = sv + C * SVC;         // [C] x SXC, rows of XW floats, origin at (r0-(k-1), -kDwHalo)
     float *sred = smem;               // [4 waves][64 lanes][NS*4], reuses the tiles afterwards
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
     const int nn = lane & 15, kk = lane >> 4;
-    const int aoff = (nn < C ? nn : 0) * RT * W;            // A row m = nn -> v[o = m]
+    const int aoff = (nn < C ? nn : 0) * SVC;               // A row m = nn -> v[o = m]
     int boff[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         const int col = (16 * s + nn < NCOL) ? 16 * s + nn : 0;
         const int i = col / (k * k), a = (col / k) % k, b = col % k;
-        boff[s] = (i * XR + a) * XW + b + kDwHalo - (k - 1);
+        boff[s] = i * SXC + a * XW + b + kDwHalo - (k - 1);
     }
     f32x4 acc[NS];
 #pragma unroll
@@ -69,9 +72,9 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
                 const int ch = rr / rows, r = rr - ch * rows;
                 const float4 val = *reinterpret_cast<const float4 *>(
                     v + (((size_t)n * C + ch) * H + r0 + r) * W + 4 * c4);
-                *reinterpret_cast<float4 *>(sv + (ch * RT + r) * W + 4 * c4) = val;
+                *reinterpret_cast<float4 *>(sv + ch * SVC + r * W + 4 * c4) = val;
             }
-            const int X4 = XW / 4;                              // first float4 of a row is the halo
+            const int X4 = (W + kDwHalo) / 4;                   // first float4 of a row is the halo
             for (int idx = tid; idx < C * xrows * X4; idx += 256) {
                 const int c4 = idx % X4, rr = idx / X4;
                 const int ch = rr / xrows, r = rr - ch * xrows;
@@ -79,34 +82,69 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
                 float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (gr >= 0 && c4 > 0)
                     val = *reinterpret_cast<const float4 *>(x + (((size_t)n * C + ch) * H + gr) * W + 4 * (c4 - 1));
-                *reinterpret_cast<float4 *>(sx + (ch * XR + r) * XW + 4 * c4) = val;
+                *reinterpret_cast<float4 *>(sx + ch * SXC + r * XW + 4 * c4) = val;
             }
         } else {
             for (int idx = tid; idx < C * rows * W; idx += 256) {
                 const int c = idx % W, r = (idx / W) % rows, ch = idx / (W * rows);
-                sv[(ch * RT + r) * W + c] = v[(((size_t)n * C + ch) * H + r0 + r) * W + c];
+                sv[ch * SVC + r * W + c] = v[(((size_t)n * C + ch) * H + r0 + r) * W + c];
             }
-            for (int idx = tid; idx < C * xrows * XW; idx += 256) {
-                const int cc = idx % XW, rr = (idx / XW) % xrows, ch = idx / (XW * xrows);
+            const int xcols = W + kDwHalo;
+            for (int idx = tid; idx < C * xrows * xcols; idx += 256) {
+                const int cc = idx % xcols, rr = (idx / xcols) % xrows, ch = idx / (xcols * xrows);
                 const int gr = r0 - (k - 1) + rr, gc = cc - kDwHalo;
-                sx[(ch * XR + rr) * XW + cc] =
+                sx[ch * SXC + rr * XW + cc] =
                     (gr >= 0 && gc >= 0) ? x[(((size_t)n * C + ch) * H + gr) * W + gc] : 0.0f;
             }
         }
         __syncthreads();
 
-        const int npix = rows * W;
-        const int ngroups = (npix + 3) / 4;
-        for (int q = wave; q < ngroups; q += 4) {
-            const int p = 4 * q + kk;
-            const bool pv = p < npix;
-            const int pr = pv ? p / W : 0, pc = pv ? p - pr * W : 0;
-            const float avl = sv[aoff + pr * W + pc];
-            const float av = pv ? avl : 0.0f;       // pixels past the end contribute nothing
-            const float *bp = sx + pr * XW + pc;
+        if (vec) {
+            // W is a multiple of 4: a wave takes whole rows, four pixels (lanes kk = 0..3) per instruction and
+            // kDwUnroll such quads per trip, so that the tile offsets inside a trip are immediates
+            const int WQ = W >> 2, NBLK = WQ / kDwUnroll;
+            // wide rows: the four waves share every row (blocks wave, wave+4, ...); narrow rows: a wave
+            // takes whole rows
+            const bool share = NBLK >= 4;
+            const int pr_step = share ? 1 : 4, q_first = share ? wave : 0, q_step = share ? 4 : 1;
+            for (int pr = share ? 0 : wave; pr < rows; pr += pr_step) {
+                const float *ap = sv + aoff + pr * W + kk;
+                const float *bp = sx + pr * XW + kk;
+                for (int blk = q_first; blk < NBLK; blk += q_step) {
+                    const int qc = blk * kDwUnroll;
+                    float av[kDwUnroll];
 #pragma unroll
-            for (int s = 0; s < NS; ++s)
-                acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bp[boff[s]], acc[s], 0, 0, 0);
+                    for (int u = 0; u < kDwUnroll; ++u)
+                        av[u] = ap[4 * (qc + u)];
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) {
+                        const float *bs = bp + boff[s] + 4 * qc;
+#pragma unroll
+                        for (int u = 0; u < kDwUnroll; ++u)
+                            acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[u], bs[4 * u], acc[s], 0, 0, 0);
+                    }
+                }
+                for (int qc = NBLK * kDwUnroll + q_first; qc < WQ; qc += q_step) {
+                    const float av = ap[4 * qc];
+#pragma unroll
+                    for (int s = 0; s < NS; ++s)
+                        acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bp[boff[s] + 4 * qc], acc[s], 0, 0, 0);
+                }
+            }
+        } else {
+            const int npix = rows * W;
+            const int ngroups = (npix + 3) / 4;
+            for (int q = wave; q < ngroups; q += 4) {
+                const int p = 4 * q + kk;
+                const bool pv = p < npix;
+                const int pr = pv ? p / W : 0, pc = pv ? p - pr * W : 0;
+                const float avl = sv[aoff + pr * W + pc];
+                const float av = pv ? avl : 0.0f;       // pixels past the end contribute nothing
+                const float *bp = sx + pr * XW + pc;
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+                    acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bp[boff[s]], acc[s], 0, 0, 0);
+            }
         }
     }
     __syncthreads();        // tiles no longer needed
@@ -143,11 +181,17 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
     const size_t P = (size_t)C * C * k * k;
     const size_t NS = ((size_t)C * k * k + 15) / 16;
     const size_t red = 256 * NS * 4;
-    const size_t XW = (size_t)W + kDwHalo;
-    auto lds_for = [&](int rt) {
-        const size_t tiles = (size_t)C * rt * W + (size_t)C * (rt + k - 1) * XW;
+    // strides: v rows stay contiguous, its channel stride is 4 (mod 64) so that the 16 output channels of
+    // an A operand read fall into different banks; the x tile's row and channel pads are searched
+    auto svc_for = [&](int rt) {
+        const int base = rt * W;
+        return base + ((4 - base % 64) + 64) % 64;
+    };
+    auto lds_with = [&](int rt, int xw, int sxc) {
+        const size_t tiles = (size_t)C * svc_for(rt) + (size_t)C * sxc;
         return sizeof(float) * (tiles > red ? tiles : red);
     };
+    auto lds_for = [&](int rt) { return lds_with(rt, W + kDwHalo, (rt + k - 1) * (W + kDwHalo)); };
     if (lds_for(1) > kDwLdsBudget)
         return p;
     int rt = H < 8 ? H : 8;
@@ -155,12 +199,63 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
         --rt;
     p.rt = rt;
     p.nchunks = (H + rt - 1) / rt;
+    p.svc = svc_for(rt);
+    p.xw = W + kDwHalo;
+    p.sxc = (rt + k - 1) * p.xw;
+    {
+        // bank conflicts of the B operand reads: lane (nn, kk) of instruction s reads
+        // i*sxc + a*xw + b + kk for column 16s + nn = (i, a, b); degree = most distinct addresses in one bank.
+        // The search costs about a millisecond of host time, so the last answer is remembered per thread.
+        struct Memo { int C, k, rt, W, xw, sxc; };
+        static thread_local Memo memo = {0, 0, 0, 0, 0, 0};
+        if (memo.C != C || memo.k != k || memo.rt != rt || memo.W != W) {
+            const int ncol = C * k * k;
+            auto cost = [&](int xw, int sxc) {
+                int total = 0;
+                for (int s = 0; s < (int)NS; ++s) {
+                    int addr[64], per_bank[64] = {0};
+                    for (int l = 0; l < 64; ++l) {
+                        const int nn = l & 15, kk = l >> 4;
+                        const int col = 16 * s + nn < ncol ? 16 * s + nn : 0;
+                        addr[l] = (col / (k * k)) * sxc + ((col / k) % k) * xw + col % k + kk;
+                        bool seen = false;
+                        for (int m = 0; m < l; ++m)
+                            seen = seen || addr[m] == addr[l];
+                        if (!seen)
+                            ++per_bank[addr[l] % 64];
+                    }
+                    int worst = 1;
+                    for (int bank = 0; bank < 64; ++bank)
+                        worst = per_bank[bank] > worst ? per_bank[bank] : worst;
+                    total += worst;
+                }
+                return total;
+            };
+            Memo m = {C, k, rt, W, p.xw, p.sxc};
+            int best = cost(p.xw, p.sxc);
+            for (int rp = 0; rp <= 12; rp += 4)
+                for (int cp = 0; cp <= 60; cp += 4) {
+                    const int xw = W + kDwHalo + rp, sxc = (rt + k - 1) * xw + cp;
+                    if (lds_with(rt, xw, sxc) > kDwLdsBudget)       // same number of workgroups per CU as unpadded
+                        continue;
+                    const int c = cost(xw, sxc);
+                    if (c < best) {
+                        best = c;
+                        m.xw = xw;
+                        m.sxc = sxc;
+                    }
+                }
+            memo = m;
+        }
+        p.xw = memo.xw;
+        p.sxc = memo.sxc;
+    }
     int g = (1024 + B - 1) / B;                     // about a thousand workgroups per layer at most
     if (g > p.nchunks) g = p.nchunks;
     if (g < 1) g = 1;
     p.groups = g;
     p.nparts = (size_t)B * g;
-    p.lds = lds_for(rt);
+    p.lds = lds_with(rt, p.xw, p.sxc);
     p.bytes = ((p.nparts * P * sizeof(float)) + 255) / 256 * 256;
     return p;
 }
@@ -175,7 +270,7 @@ static void launch_ns(const DwBatch &batch, int layers, float *part, const DwPla
         if (((size_t)batch.x[l] | (size_t)batch.v[l]) & 15)
             vec = 0;
     hipLaunchKernelGGL(k_dw_partial_mfma<NS>, dim3((unsigned)(p.nparts * layers)), dim3(256), p.lds, stream, batch,
-                       part, B, C, H, W, k, p.rt, p.nchunks, p.groups, vec);
+                       part, B, C, H, W, k, p.rt, p.nchunks, p.groups, vec, p.xw, p.sxc, p.svc);
 }
 
 // Pass 1 for `layers` independent (x, v) pairs in one launch; part holds layers * p.nparts rows.

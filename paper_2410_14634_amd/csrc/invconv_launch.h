@@ -18,6 +18,7 @@ struct DwPlan {
     int nchunks;     // row chunks per image
     int cw, ncol;    // generic pass 1: columns per chunk, column chunks per row chunk (cw = W, ncol = 1 unless W is too wide for LDS)
     int groups;      // matrix-core pass 1: workgroups per image, each looping over chunks
+    int xw, sxc, svc; // matrix-core pass 1: row and channel strides of the x tile, channel stride of the v tile (padded against LDS bank conflicts)
     size_t nparts;   // workgroups of pass 1 = rows of the partial-sum matrix
     size_t lds;      // dynamic LDS bytes of pass 1
     size_t bytes;    // workspace bytes
