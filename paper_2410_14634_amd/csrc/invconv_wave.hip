@@ -455,10 +455,31 @@ template <int C, int K>
 static int launch_wave_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
                           hipStream_t stream)
 {
+    // Large batches: every lane walks its own row 4 bytes at a time, so a wave keeps
+    // rows * C * 2 (input and output) cache lines of 128 bytes live for dozens of steps.  When the
+    // waves resident on the 32 CUs of an XCD need more than about 2.5 MB of its 4 MB L2, lines are
+    // evicted between two touches and the solve becomes several times slower than running the batch
+    // in rounds.  An LDS allocation the kernel never touches caps the waves per CU accordingly.
+    size_t lds = 0;
+    if (B > 512) {
+        const size_t live = (size_t)(H < 64 ? H : 64) * C * 2 * 128;
+        size_t cap = (size_t)(2.5 * 1024 * 1024) / (32 * live);
+        cap = cap < 1 ? 1 : cap;
+        if (cap < 8) {
+            lds = (kMaxLdsBytes / cap) & ~(size_t)255;
+            const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave<C, K, 1>)
+                                 : reinterpret_cast<const void *>(&k_solve_wave<C, K, 0>);
+            if (lds > 48 * 1024 &&
+                hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+                (void)hipGetLastError();
+                lds = 0;
+            }
+        }
+    }
     if (dir)
-        hipLaunchKernelGGL((k_solve_wave<C, K, 1>), dim3(B), dim3(64), 0, stream, in, w, out, H, W);
+        hipLaunchKernelGGL((k_solve_wave<C, K, 1>), dim3(B), dim3(64), lds, stream, in, w, out, H, W);
     else
-        hipLaunchKernelGGL((k_solve_wave<C, K, 0>), dim3(B), dim3(64), 0, stream, in, w, out, H, W);
+        hipLaunchKernelGGL((k_solve_wave<C, K, 0>), dim3(B), dim3(64), lds, stream, in, w, out, H, W);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

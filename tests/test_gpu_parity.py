@@ -67,6 +67,7 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     # few channels, more than 64 rows: bands of 64 rows, one wave each
     (2, 3, 256, 256, 3), (1, 3, 130, 40, 5), (1, 4, 512, 16, 3), (1, 1, 65, 7, 3), (2, 3, 128, 200, 3),
     (1, 2, 191, 3, 3), (1, 3, 320, 70, 5),
+    (600, 3, 8, 8, 3), (520, 1, 64, 4, 3),     # large batches: the forward launch caps its waves per CU
 ]
 
 
