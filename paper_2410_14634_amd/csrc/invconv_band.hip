@@ -252,6 +252,194 @@ __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in
     }
 }
 
+// ---------------------------------------------------------------------------
+// Images of at most 16 rows (one band, k = 3): the 27 matrix instructions of a step are split over
+// the four waves of the workgroup by the age of their input, so that the wave on the chain of
+// dependent steps issues only the 9 that read the pixel just solved.  With x_s the diagonal solved
+// at step s (lane (n, g) as above) and A[a][db] the folded taps,
+//   T1_s = up(T2_{s-1}) + A[1][0] x_s + { A[1][1] x_{s-1} + A[1][2] x_{s-2} }        = T1p_s + F1_s
+//   T2_s =                A[2][0] x_s + { A[2][1] x_{s-1} + A[2][2] x_{s-2} }        = T2p_s + G2_s
+//   own_{s+1} =           A[0][1] x_s + { Linv y_{s+1}    + A[0][2] x_{s-1} }        = ownp_s + O_{s+1}
+//   x_{s+1} = own_{s+1} + up(T1_s)
+// The braces only need x_{s-1}: waves 1, 2 and 3 form F1_s, G2_s and O_{s+1} during step s (x_{s-1}
+// was published through LDS before the barrier that ended step s-1) and wave 0 picks them up at the
+// start of step s+1, after the barrier that ends step s.  Wave 0 forms T1p, T2p and ownp itself.
+// Wave 1 also writes x to global memory, wave 3 reads y.  One barrier per step.
+// ---------------------------------------------------------------------------
+template <int CG, int DIR>
+__global__ __launch_bounds__(256) void k_solve_band_split(const float *__restrict__ in, const float *__restrict__ w,
+                                                          float *__restrict__ out, int H, int W)
+{
+    constexpr int K = 3, C = 4 * CG;
+    extern __shared__ float smem[];
+    float *sL = smem;
+    float *sLinv = sL + C * C;
+    float *sCf = sLinv + C * C;
+    float *sW = sCf + K * K * C * C;
+    float *sX = sW + K * K * C * C;                     // [2][CG][64]  x of the last two steps
+    f32x4 *sM = reinterpret_cast<f32x4 *>(sX + 2 * CG * 64);   // [2][3][64]  F1, G2, O of the last two steps
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const bool row_ok = n < H;
+    const int rr = row_ok ? n : H - 1;
+    const unsigned Wst = row_ok ? (unsigned)W : 0u;
+
+    const size_t img = (size_t)blockIdx.x * C * H * W;
+    const char *chan_src[CG];
+    char *chan_dst[CG];
+#pragma unroll
+    for (int jj = 0; jj < CG; ++jj) {
+        const int ch = CG * g + jj;
+        const size_t cb = img + (size_t)(DIR ? C - 1 - ch : ch) * H * W;
+        chan_src[jj] = reinterpret_cast<const char *>(in + cb);
+        chan_dst[jj] = reinterpret_cast<char *>(out + cb);
+    }
+    constexpr int kStep = DIR ? -4 : 4;
+    const int row0 = 4 * (DIR ? (H - 1 - rr) * W + (W - 1) : rr * W);
+    const int rowlo = DIR ? row0 - 4 * (W - 1) : row0;
+    const int rowhi = DIR ? row0 : row0 + 4 * (W - 1);
+    auto clamp_row = [&](int off) -> unsigned { return (unsigned)(off < rowlo ? rowlo : (off > rowhi ? rowhi : off)); };
+    auto ld = [&](int jj, unsigned off) -> float { return *reinterpret_cast<const float *>(chan_src[jj] + off); };
+    auto st = [&](int jj, unsigned off, float v) { *reinterpret_cast<float *>(chan_dst[jj] + off) = v; };
+
+    // wave 3 reads y: slot u holds the input of the steps congruent to u; first batch = steps 0 .. kBandPF-1
+    float yb[kBandPF][CG];
+#pragma unroll
+    for (int u = 0; u < kBandPF; ++u) {
+        const unsigned off = clamp_row(row0 + kStep * (u - n));
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj)
+            yb[u][jj] = ld(jj, off);
+    }
+
+    fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sW);
+    for (int idx = tid; idx < 2 * CG * 64 + 2 * 3 * 64 * 4; idx += 256)
+        sX[idx] = 0.0f;
+
+    const int m = n;
+    const bool m_ok = (m & 3) < CG;
+    const int om = m_ok ? CG * (m >> 2) + (m & 3) : 0;
+    float wA[K][K][CG], wLi[CG];
+#pragma unroll
+    for (int a = 0; a < K; ++a)
+#pragma unroll
+        for (int db = 0; db < K; ++db)
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj) {
+                const float cf = sCf[((a * K + db) * C + om) * C + CG * g + jj];
+                wA[a][db][jj] = m_ok ? -cf : 0.0f;
+            }
+#pragma unroll
+    for (int jj = 0; jj < CG; ++jj) {
+        const float lv = sLinv[om * C + CG * g + jj];
+        wLi[jj] = m_ok ? lv : 0.0f;
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int u = 0; u < kBandPF; ++u)
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj)
+            asm volatile("" : "+v"(yb[u][jj]));
+
+    // Step s = -1 only lets the helpers prepare O_0 = Linv y_0; the steps after the last diagonal only
+    // let wave 1 store.  Every wave runs its own loop (so that no register state is merged across the
+    // roles) over the same number of steps, one barrier each.
+    const int nsteps = 16 + W - 1;
+    const int total = (nsteps + 2 + kBandPF - 1) / kBandPF * kBandPF;      // steps -1 .. total-2
+    if (wave == 0) {
+        f32x4 T1p = f32x4{0.f, 0.f, 0.f, 0.f}, T2p = T1p, ownp = T1p;
+        for (int s = -1; s < total - 1; ++s) {
+            const int rs = (s - 1) & 1;
+            const f32x4 F1 = sM[(rs * 3 + 0) * 64 + lane], G2 = sM[(rs * 3 + 1) * 64 + lane],
+                        O = sM[(rs * 3 + 2) * 64 + lane];
+            const f32x4 T1 = T1p + F1, T2 = T2p + G2, own = ownp + O;
+            float xn[CG];
+#pragma unroll
+            for (int j = 0; j < CG; ++j) {
+                xn[j] = own[j] + from_row_above16(T1[j]);
+                sX[((s & 1) * CG + j) * 64 + lane] = xn[j];
+            }
+            f32x4 a1 = f32x4{0.f, 0.f, 0.f, 0.f}, a2 = a1, a0 = a1;
+#pragma unroll
+            for (int j = 0; j < CG; ++j)
+                a1[j] = from_row_above16(T2[j]);
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj) {
+                a1 = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[1][0][jj], xn[jj], a1, 0, 0, 0);
+                a2 = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[2][0][jj], xn[jj], a2, 0, 0, 0);
+                a0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][1][jj], xn[jj], a0, 0, 0, 0);
+            }
+            T1p = a1;
+            T2p = a2;
+            ownp = a0;
+            __syncthreads();
+        }
+    } else if (wave == 1 || wave == 2) {
+        // F1 (wave 1, a = 1) or G2 (wave 2, a = 2): A[a][1] x_{s-1} + A[a][2] x_{s-2}; wave 1 also stores x_{s-1}
+        const int a = wave;
+        float x1[CG], x2[CG], w1[CG], w2[CG];
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj) {
+            x1[jj] = x2[jj] = 0.0f;
+            w1[jj] = a == 1 ? wA[1][1][jj] : wA[2][1][jj];
+            w2[jj] = a == 1 ? wA[1][2][jj] : wA[2][2][jj];
+        }
+        const unsigned Wst1 = a == 1 ? Wst : 0u;
+        for (int s = -1; s < total - 1; ++s) {
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj) {
+                x2[jj] = x1[jj];
+                x1[jj] = sX[(((s - 1) & 1) * CG + jj) * 64 + lane];
+            }
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f}, acc2 = acc;
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj) {
+                acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(w2[jj], x2[jj], acc2, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1[jj], x1[jj], acc, 0, 0, 0);
+            }
+            sM[((s & 1) * 3 + (a - 1)) * 64 + lane] = acc + acc2;
+            const int c = s - 1 - n;        // column of x_{s-1} in this lane's row
+            if ((unsigned)c < Wst1) {
+                const unsigned off = (unsigned)(row0 + kStep * c);
+#pragma unroll
+                for (int j = 0; j < CG; ++j)
+                    st(j, off, x1[j]);
+            }
+            __syncthreads();
+        }
+    } else {
+        // O_{s+1} = Linv y_{s+1} + A[0][2] x_{s-1}
+        float x1[CG];
+        int ldoff = row0 + kStep * (kBandPF - n);       // unclamped offset of the next refill
+        for (int s0 = -1; s0 < total - 1; s0 += kBandPF) {
+#pragma unroll
+            for (int u = 0; u < kBandPF; ++u) {
+                const int s = s0 + u;       // step s + 1 is congruent to u: its input is in slot u
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    x1[jj] = sX[(((s - 1) & 1) * CG + jj) * 64 + lane];
+                const bool in_row = (unsigned)(s + 1 - n) < (unsigned)W;
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f}, acc2 = acc;
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj) {
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wLi[jj], in_row ? yb[u][jj] : 0.0f, acc, 0, 0, 0);
+                    acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][2][jj], x1[jj], acc2, 0, 0, 0);
+                }
+                sM[((s & 1) * 3 + 2) * 64 + lane] = acc + acc2;
+                const unsigned off = clamp_row(ldoff);      // refill with the input of step s + 1 + kBandPF
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    yb[u][jj] = ld(jj, off);
+                ldoff += kStep;
+                __syncthreads();
+            }
+        }
+    }
+}
+
 size_t solve_band_lds_bytes(int C, int k, int NB)
 {
     return sizeof(float) * (2 * (size_t)C * C + 2 * (size_t)k * k * C * C + (size_t)NB * kRing * k * 64);
@@ -267,6 +455,15 @@ static int launch_band_ck(int dir, const float *in, const float *w, float *out, 
                           hipStream_t stream)
 {
     const int NB = (H + 15) / 16;
+    if (NB == 1 && K == 3) {
+        const size_t lds1 = sizeof(float) * (2 * (size_t)16 * CG * CG + 2 * (size_t)K * K * 16 * CG * CG +
+                                             2 * CG * 64 + 2 * 3 * 64 * 4);
+        if (dir)
+            hipLaunchKernelGGL((k_solve_band_split<CG, 1>), dim3(B), dim3(256), lds1, stream, in, w, out, H, W);
+        else
+            hipLaunchKernelGGL((k_solve_band_split<CG, 0>), dim3(B), dim3(256), lds1, stream, in, w, out, H, W);
+        return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+    }
     const size_t lds = solve_band_lds_bytes(4 * CG, K, NB);
     // a single band gets three helper waves for the weight preparation (its loop has no barriers)
     const int threads = NB == 1 ? 256 : 64 * NB;
