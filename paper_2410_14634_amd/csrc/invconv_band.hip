@@ -304,14 +304,16 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
     auto ld = [&](int jj, unsigned off) -> float { return *reinterpret_cast<const float *>(chan_src[jj] + off); };
     auto st = [&](int jj, unsigned off, float v) { *reinterpret_cast<float *>(chan_dst[jj] + off) = v; };
 
-    // wave 3 reads y: slot u holds the input of the steps congruent to u; first batch = steps 0 .. kBandPF-1
+    // wave 3 reads y: slot u holds the input of the steps congruent to u; first batch = steps 0 .. kBandPF-1,
+    // issued before the weight preparation so that both latencies overlap.  The other waves run the same
+    // instructions on one common address (no branch around a load, next to no work for the address unit).
     float yb[kBandPF][CG];
 #pragma unroll
     for (int u = 0; u < kBandPF; ++u) {
-        const unsigned off = clamp_row(row0 + kStep * (u - n));
+        const unsigned off = wave == 3 ? clamp_row(row0 + kStep * (u - n)) : 0u;
 #pragma unroll
         for (int jj = 0; jj < CG; ++jj)
-            yb[u][jj] = ld(jj, off);
+            yb[u][jj] = *reinterpret_cast<const float *>((wave == 3 ? chan_src[jj] : chan_src[0]) + off);
     }
 
     fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sW);

@@ -54,29 +54,55 @@ __device__ void fold_weights(const float *__restrict__ w, int C, int k,
 {
     const int tid = threadIdx.x, nt = blockDim.x;
     const int total = k * k * C * C;
-    for (int idx = tid; idx < total; idx += nt) {
-        const int i = idx % C, o = (idx / C) % C, tp = idx / (C * C);
-        const float val = weff<DIR>(w, C, k, o, i, k - 1 - tp / k, k - 1 - tp % k);
-        sW[idx] = val;
-        if (tp == 0)
-            sL[o * C + i] = val;
+    // the kernel is read four entries per thread at a time (addresses clamped, no branch around a load),
+    // so that the whole staging costs about one memory latency
+    for (int base = tid; base < total; base += 4 * nt) {
+        float val[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int raw = base + u * nt;
+            const int idx = raw < total ? raw : total - 1;
+            const int i = idx % C, o = (idx / C) % C, tp = idx / (C * C);
+            const int a = k - 1 - tp / k, b = k - 1 - tp % k;
+            const int oo = DIR ? C - 1 - i : o, ii = DIR ? C - 1 - o : i;
+            const float v = w[((oo * C + ii) * k + a) * k + b];
+            val[u] = (tp == 0 && ii > oo) ? 0.0f : v;       // the current-pixel block's upper triangle reads as zero
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + u * nt;
+            if (idx < total) {
+                sW[idx] = val[u];
+                if (idx < C * C)
+                    sL[idx] = val[u];       // tp == 0: idx = o * C + i
+            }
+        }
     }
     __syncthreads();
     if (CT > 0) {
-        // column j of Linv by forward substitution, kept in registers (all loops unrolled,
-        // entries above the diagonal stay zero so the inner sum needs no lower bound)
+        // column j of Linv by forward substitution in registers: the needed part of L and the reciprocals
+        // of its diagonal are fetched first, so the chain over o is multiply-adds only (entries above the
+        // diagonal stay zero, so the inner sum needs no lower bound)
         if (tid < CT) {
             const int j = tid;
-            float lv[CT > 0 ? CT : 1];
+            constexpr int N = CT > 0 ? CT : 1;
+            float Lr[N][N], rd[N], lv[N];
 #pragma unroll
-            for (int o = 0; o < CT; ++o) {
-                float s = 0.0f;
+            for (int o = 0; o < N; ++o)
+#pragma unroll
+                for (int m = 0; m <= o; ++m)
+                    Lr[o][m] = sL[o * N + m];
+#pragma unroll
+            for (int o = 0; o < N; ++o)
+                rd[o] = 1.0f / Lr[o][o];
+#pragma unroll
+            for (int o = 0; o < N; ++o) {
+                float acc = 0.0f;
 #pragma unroll
                 for (int m = 0; m < o; ++m)
-                    s += sL[o * CT + m] * lv[m];
-                const float d = sL[o * CT + o];
-                lv[o] = (o == j) ? 1.0f / d : (o > j ? -s / d : 0.0f);
-                sLinv[o * CT + j] = lv[o];
+                    acc += Lr[o][m] * lv[m];
+                lv[o] = (o == j) ? rd[o] : (o > j ? -acc * rd[o] : 0.0f);
+                sLinv[o * N + j] = lv[o];
             }
         }
     } else if (tid < C) {
@@ -92,23 +118,37 @@ __device__ void fold_weights(const float *__restrict__ w, int C, int k,
         }
     }
     __syncthreads();
-    for (int idx = tid; idx < total; idx += nt) {
-        const int i = idx % C, o = (idx / C) % C, tp = idx / (C * C);
-        float s = 0.0f;
-        if (tp != 0) {
-            const float *li = sLinv + o * C;
-            const float *wt = sW + tp * C * C + i;
-            if (CT > 0) {
-                // entries of Linv above the diagonal are zero, so the full row may be used
+    if (CT > 0) {
+        // two outputs per trip, so that the LDS reads of one overlap the arithmetic of the other
+        // (entries of Linv above the diagonal are zero, so the full row may be used)
+        for (int idx = tid; idx < total; idx += 2 * nt) {
+            const int idx2 = idx + nt < total ? idx + nt : idx;
+            const int i = idx % CT, o = (idx / CT) % CT, tp = idx / (CT * CT);
+            const int i2 = idx2 % CT, o2 = (idx2 / CT) % CT, tp2 = idx2 / (CT * CT);
+            const float *li = sLinv + o * CT, *wt = sW + tp * CT * CT + i;
+            const float *li2 = sLinv + o2 * CT, *wt2 = sW + tp2 * CT * CT + i2;
+            float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
-                for (int j = 0; j < CT; ++j)
-                    s += li[j] * wt[j * CT];
-            } else {
+            for (int j = 0; j < (CT > 0 ? CT : 1); ++j) {
+                s1 += li[j] * wt[j * CT];
+                s2 += li2[j] * wt2[j * CT];
+            }
+            sCf[idx] = tp != 0 ? s1 : 0.0f;
+            if (idx + nt < total)
+                sCf[idx2] = tp2 != 0 ? s2 : 0.0f;
+        }
+    } else {
+        for (int idx = tid; idx < total; idx += nt) {
+            const int i = idx % C, o = (idx / C) % C, tp = idx / (C * C);
+            float s = 0.0f;
+            if (tp != 0) {
+                const float *li = sLinv + o * C;
+                const float *wt = sW + tp * C * C + i;
                 for (int j = 0; j <= o; ++j)
                     s += li[j] * wt[j * C];
             }
+            sCf[idx] = s;
         }
-        sCf[idx] = s;
     }
     __syncthreads();
 }
