@@ -54,7 +54,8 @@ enum {
     INVCONV_VARIANT_DIAG_LAUNCH = 2, /* one kernel launch per anti-diagonal (capture it in a hipGraph) */
     INVCONV_VARIANT_WAVE = 3,     /* one wave per 64 image rows, lane = row, register/DPP systolic solve (C <= 4, H <= 512; bands of one image hand over through LDS) */
     INVCONV_VARIANT_BAND = 4,     /* one wave per 16-row band, 16x16x4 MFMA systolic solve (C = 8, 12, 16; k = 3; H <= 128) */
-    INVCONV_VARIANT_PERSISTENT = 5 /* one cooperative launch, persistent grid, device-wide barrier per anti-diagonal */
+    INVCONV_VARIANT_PERSISTENT = 5, /* one cooperative launch, persistent grid, device-wide barrier per anti-diagonal */
+    INVCONV_VARIANT_WAVE_SPLIT = 6 /* the wave solve with a step's matrix instructions split over four waves by the age of their input (C <= 4, H <= 64) */
 };
 
 /*

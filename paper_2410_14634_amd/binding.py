@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_PKG, "libinvconv.so")
 
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_ALIAS, ERR_LAUNCH, ERR_VARIANT = range(-1, -8, -1)
-VARIANT_AUTO, VARIANT_BLOCK, VARIANT_DIAG_LAUNCH, VARIANT_WAVE, VARIANT_BAND, VARIANT_PERSISTENT = 0, 1, 2, 3, 4, 5
+VARIANT_AUTO, VARIANT_BLOCK, VARIANT_DIAG_LAUNCH, VARIANT_WAVE, VARIANT_BAND, VARIANT_PERSISTENT, VARIANT_WAVE_SPLIT = \
+    0, 1, 2, 3, 4, 5, 6
 
 EXPORTS = (
     "invconv_fwd", "invconv_bwd", "invconv_bwd_workspace_bytes", "invconv_logdet",

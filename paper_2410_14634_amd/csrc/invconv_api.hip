@@ -31,7 +31,8 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
     switch (variant) {
     case INVCONV_VARIANT_AUTO:
         if (wave_supported(C, H, k))
-            return launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream);
+            return wave_split_preferred(B, k) ? launch_solve_wave_split(dir, in, w, out, B, C, H, W, k, stream)
+                                              : launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream);
         if (wave_bands_supported(C, H, W, k))
             return launch_solve_wave_bands(dir, in, w, out, B, C, H, W, k, stream);
         if (band_supported(C, H, k))
@@ -47,6 +48,8 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
         return launch_solve_band(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_PERSISTENT:
         return launch_solve_persistent(dir, in, w, out, B, C, H, W, k, stream);
+    case INVCONV_VARIANT_WAVE_SPLIT:
+        return launch_solve_wave_split(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_DIAG_LAUNCH:
         return launch_solve_diag(dir, in, w, out, B, C, H, W, k, stream);
     default:
@@ -67,7 +70,9 @@ invconv_status invconv_fwd_ex(const float *y, const float *w, float *x, int B, i
         return s;
     if (x == y || (const float *)x == w)
         return INVCONV_ERR_ALIAS;
-    if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_PERSISTENT)
+    if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_WAVE_SPLIT)
+        return INVCONV_ERR_VARIANT;
+    if (variant == INVCONV_VARIANT_WAVE_SPLIT && !wave_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_WAVE && !wave_supported(C, H, k) && !wave_bands_supported(C, H, W, k))
         return INVCONV_ERR_VARIANT;
@@ -141,7 +146,9 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
     if (dLdy == dLdx || dLdy == x || (const float *)dLdy == w || dLdw == dLdy || (const float *)dLdw == w ||
         (const float *)dLdw == x || (const float *)dLdw == dLdx)
         return INVCONV_ERR_ALIAS;
-    if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_PERSISTENT)
+    if (variant < INVCONV_VARIANT_AUTO || variant > INVCONV_VARIANT_WAVE_SPLIT)
+        return INVCONV_ERR_VARIANT;
+    if (variant == INVCONV_VARIANT_WAVE_SPLIT && !wave_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_WAVE && !wave_supported(C, H, k) && !wave_bands_supported(C, H, W, k))
         return INVCONV_ERR_VARIANT;

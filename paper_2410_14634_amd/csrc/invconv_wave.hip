@@ -43,6 +43,66 @@ __device__ __forceinline__ float from_lane_above_or(float first, float v)
 
 constexpr int kWavePF = 16;   // steps of load prefetch
 
+// Weight preparation in registers, by every lane for itself (the kernel reads w
+// with uniform addresses only): Linv = inverse of the lower-triangular
+// current-pixel block; the lane keeps row o = lane%4 of it (zeros for o >= C) and
+// folds it into every other tap.  MFMA A operands of this lane:
+//   wLi[j] = Linv[o][j],   wA[a][db][i] = -(Linv W_tap)[o][i] for tap (a,db) up/left.
+template <int C, int K, int DIR>
+__device__ __forceinline__ void wave_fold_regs(const float *__restrict__ w, int o_lane, float (&wA)[K][K][C],
+                                               float (&wLi)[C])
+{
+    float Lm[C][C], Li[C][C], rd[C];
+#pragma unroll
+    for (int o = 0; o < C; ++o)
+#pragma unroll
+        for (int i = 0; i < C; ++i)
+            Lm[o][i] = weff<DIR>(w, C, K, o, i, K - 1, K - 1);
+#pragma unroll
+    for (int o = 0; o < C; ++o)
+        rd[o] = 1.0f / Lm[o][o];
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+#pragma unroll
+        for (int o = 0; o < C; ++o) {
+            if (o < j) {
+                Li[o][j] = 0.0f;
+            } else if (o == j) {
+                Li[o][j] = rd[j];
+            } else {
+                float sum = 0.0f;
+#pragma unroll
+                for (int m = j; m < o; ++m)
+                    sum += Lm[o][m] * Li[m][j];
+                Li[o][j] = -sum * rd[o];
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+        float v = 0.0f;
+#pragma unroll
+        for (int o = 0; o < C; ++o)
+            v = (o_lane == o) ? Li[o][j] : v;
+        wLi[j] = v;
+    }
+#pragma unroll
+    for (int a = 0; a < K; ++a)
+#pragma unroll
+        for (int db = 0; db < K; ++db)
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                float sum = 0.0f;
+                if (a != 0 || db != 0) {
+#pragma unroll
+                    for (int j = 0; j < C; ++j)
+                        sum += wLi[j] * weff<DIR>(w, C, K, j, i, K - 1 - a, K - 1 - db);
+                }
+                wA[a][db][i] = -sum;
+            }
+}
+
+
 // Images of more than 64 rows are cut into bands of 64 rows, one wave each, all in one workgroup
 // (BANDS).  A band is the single-wave solve on its own rows and its own clock (local step j,
 // lane l at column j - l); what row 63 of the band above would have handed to lane 0 through the
@@ -122,62 +182,8 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
             yb[u][ch] = ld(ch, off);
     }
 
-    // Weight preparation in registers, by every lane for itself (the kernel reads w
-    // with uniform addresses only): Linv = inverse of the lower-triangular
-    // current-pixel block; the lane keeps row o = lane%4 of it (zeros for o >= C) and
-    // folds it into every other tap.  MFMA A operands of this lane:
-    //   wLi[j] = Linv[o][j],   wA[a][db][i] = -(Linv W_tap)[o][i] for tap (a,db) up/left.
     float wA[K][K][C], wLi[C];
-    {
-        float Lm[C][C], Li[C][C], rd[C];
-#pragma unroll
-        for (int o = 0; o < C; ++o)
-#pragma unroll
-            for (int i = 0; i < C; ++i)
-                Lm[o][i] = weff<DIR>(w, C, K, o, i, K - 1, K - 1);
-#pragma unroll
-        for (int o = 0; o < C; ++o)
-            rd[o] = 1.0f / Lm[o][o];
-#pragma unroll
-        for (int j = 0; j < C; ++j) {
-#pragma unroll
-            for (int o = 0; o < C; ++o) {
-                if (o < j) {
-                    Li[o][j] = 0.0f;
-                } else if (o == j) {
-                    Li[o][j] = rd[j];
-                } else {
-                    float sum = 0.0f;
-#pragma unroll
-                    for (int m = j; m < o; ++m)
-                        sum += Lm[o][m] * Li[m][j];
-                    Li[o][j] = -sum * rd[o];
-                }
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < C; ++j) {
-            float v = 0.0f;
-#pragma unroll
-            for (int o = 0; o < C; ++o)
-                v = (o_lane == o) ? Li[o][j] : v;
-            wLi[j] = v;
-        }
-#pragma unroll
-        for (int a = 0; a < K; ++a)
-#pragma unroll
-            for (int db = 0; db < K; ++db)
-#pragma unroll
-                for (int i = 0; i < C; ++i) {
-                    float sum = 0.0f;
-                    if (a != 0 || db != 0) {
-#pragma unroll
-                        for (int j = 0; j < C; ++j)
-                            sum += wLi[j] * weff<DIR>(w, C, K, j, i, K - 1 - a, K - 1 - db);
-                    }
-                    wA[a][db][i] = -sum;
-                }
-    }
+    wave_fold_regs<C, K, DIR>(w, o_lane, wA, wLi);
 
     float xh[C][K];      // xh[i][db] = x(r, c-db), db >= 1
     f32x4 T[K];          // T[a][o], a >= 1: message for pixel (r+a, c), negated sums
@@ -337,6 +343,221 @@ __global__ __launch_bounds__(64) void k_solve_wave(const float *__restrict__ in,
     solve_wave_body<C, K, DIR, false>(in, w, out, H, W, blockIdx.x, nullptr);
 }
 
+// ---------------------------------------------------------------------------
+// The same solve with the matrix instructions of a step split over the four waves of a workgroup by
+// the age of their input (images of at most 64 rows; pays when a step is long, i.e. k = 5).  With
+// x_s the diagonal solved at step s and A[a][db] the folded taps (lane = row, as above),
+//   T[a]_s    = up(T[a+1]_{s-1}) + A[a][0] x_s + { sum_{db>=1} A[a][db] x_{s-db} }   = Tp[a]_s + F[a]_s
+//   own_{s+1} =                    A[0][1] x_s + { Linv y_{s+1} + sum_{db>=2} A[0][db] x_{s+1-db} }
+//                                                                                    = ownp_s + O_{s+1}
+//   x_{s+1}   = own_{s+1} + up(T[1]_s)
+// The braces need nothing newer than x_{s-1}.  Wave 0, on the chain of dependent steps, publishes x_s
+// through LDS and forms Tp and ownp (K*C instructions); during step s waves 1 and 2 form the F[a]_s,
+// wave 3 forms O_{s+1}, reads y and writes x_{s-1} to global memory; wave 0 picks the results up
+// after the barrier that ends the step.  Every wave runs its own loop over the same number of steps.
+// ---------------------------------------------------------------------------
+struct WaveSplitLds {
+    float *x;       // [2][C][64]   x of the last two steps
+    f32x4 *m;       // [2][K][64]   slot 0: O, slot a: F[a]
+};
+
+template <int C, int K>
+__host__ __device__ constexpr size_t wave_split_lds_floats() { return 2 * C * 64 + 2 * K * 64 * 4; }
+
+template <int C, int K, int DIR, bool LDS_COPY>
+__device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ in, const float *__restrict__ w,
+                                                      float *__restrict__ out, int H, int W, int n, float *lds_copy,
+                                                      WaveSplitLds sl)
+{
+    static_assert(C >= 1 && C <= 4 && K >= 3, "one 4-row MFMA block per pixel");
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane;
+    const bool row_ok = r < H;
+    const int rr = row_ok ? r : H - 1;
+    const int o_lane = r & 3;
+    const unsigned Wst = row_ok ? (unsigned)W : 0u;
+
+    const size_t img = (size_t)n * C * H * W;
+    const char *chan_src[C];
+    char *chan_dst[C];
+    char *chan_lds[C];
+#pragma unroll
+    for (int ch = 0; ch < C; ++ch) {
+        const size_t cb = (size_t)(DIR ? C - 1 - ch : ch) * H * W;
+        chan_src[ch] = reinterpret_cast<const char *>(in + img + cb);
+        chan_dst[ch] = reinterpret_cast<char *>(out + img + cb);
+        chan_lds[ch] = reinterpret_cast<char *>(lds_copy + cb);
+    }
+    constexpr int kStep = DIR ? -4 : 4;
+    const int row0 = 4 * (DIR ? (H - 1 - rr) * W + (W - 1) : rr * W);
+    const int rowlo = DIR ? row0 - 4 * (W - 1) : row0;
+    const int rowhi = DIR ? row0 : row0 + 4 * (W - 1);
+    auto clamp_row = [&](int off) -> unsigned { return (unsigned)(off < rowlo ? rowlo : (off > rowhi ? rowhi : off)); };
+
+    // wave 3 reads y: slot u holds the input of the steps congruent to u.  The other waves run the same
+    // instructions on one common address (no branch around a load, next to no work for the address unit).
+    float yb[kWavePF][C];
+#pragma unroll
+    for (int u = 0; u < kWavePF; ++u) {
+        const unsigned off = wave == 3 ? clamp_row(row0 + kStep * (u - r)) : 0u;
+#pragma unroll
+        for (int ch = 0; ch < C; ++ch)
+            yb[u][ch] = *reinterpret_cast<const float *>((wave == 3 ? chan_src[ch] : chan_src[0]) + off);
+    }
+
+    float wA[K][K][C], wLi[C];
+    wave_fold_regs<C, K, DIR>(w, o_lane, wA, wLi);
+
+    for (int idx = threadIdx.x; idx < (int)wave_split_lds_floats<C, K>(); idx += 256)
+        sl.x[idx] = 0.0f;       // x and message slots are contiguous
+#pragma unroll
+    for (int u = 0; u < kWavePF; ++u)
+#pragma unroll
+        for (int ch = 0; ch < C; ++ch)
+            asm volatile("" : "+v"(yb[u][ch]));
+    __syncthreads();
+
+    // step s = -1 only lets wave 3 prepare O_0 = Linv y_0; the steps after the last diagonal only let it store
+    const int nsteps = H + W - 1;
+    const int total = (nsteps + 2 + kWavePF - 1) / kWavePF * kWavePF;      // steps -1 .. total-2
+    if (wave == 0) {
+        f32x4 Tp[K], ownp = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int a = 0; a < K; ++a)
+            Tp[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int s = -1; s < total - 1; ++s) {
+            const f32x4 *mi = sl.m + ((s - 1) & 1) * K * 64 + lane;
+            f32x4 T[K];
+#pragma unroll
+            for (int a = 1; a < K; ++a)
+                T[a] = Tp[a] + mi[a * 64];
+            const f32x4 own = ownp + mi[0];
+            float xn[C];
+#pragma unroll
+            for (int o = 0; o < C; ++o) {
+                xn[o] = own[o] + from_lane_above(T[1][o]);
+                sl.x[((s & 1) * C + o) * 64 + lane] = xn[o];
+            }
+#pragma unroll
+            for (int a = 1; a < K; ++a) {
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (a + 1 < K) {
+#pragma unroll
+                    for (int o = 0; o < C; ++o)
+                        acc[o] = from_lane_above(T[a + 1][o]);
+                }
+#pragma unroll
+                for (int i = 0; i < C; ++i)
+                    acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[a][0][i], xn[i], acc, 0, 0, 0);
+                Tp[a] = acc;
+            }
+            {
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int i = 0; i < C; ++i)
+                    acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[0][1][i], xn[i], acc, 0, 0, 0);
+                ownp = acc;
+            }
+            __syncthreads();
+        }
+    } else if (wave == 1 || wave == 2) {
+        // F[a]_s = sum_{db>=1} A[a][db] x_{s-db}: wave 1 takes a = 1 .. (K-1)/2, wave 2 the rest
+        constexpr int A_SPLIT = (K - 1) / 2 + 1;
+        float xo[K][C];     // xo[db] = x_{s-db}, db >= 1
+#pragma unroll
+        for (int db = 0; db < K; ++db)
+#pragma unroll
+            for (int i = 0; i < C; ++i)
+                xo[db][i] = 0.0f;
+        for (int s = -1; s < total - 1; ++s) {
+#pragma unroll
+            for (int db = K - 1; db >= 2; --db)
+#pragma unroll
+                for (int i = 0; i < C; ++i)
+                    xo[db][i] = xo[db - 1][i];
+#pragma unroll
+            for (int i = 0; i < C; ++i)
+                xo[1][i] = sl.x[(((s - 1) & 1) * C + i) * 64 + lane];
+            f32x4 *mo = sl.m + (s & 1) * K * 64 + lane;
+#pragma unroll
+            for (int a = 1; a < K; ++a) {
+                if ((a < A_SPLIT) != (wave == 1))
+                    continue;
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int db = K - 1; db >= 1; --db)
+#pragma unroll
+                    for (int i = 0; i < C; ++i)
+                        acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[a][db][i], xo[db][i], acc, 0, 0, 0);
+                mo[a * 64] = acc;
+            }
+            __syncthreads();
+        }
+    } else {
+        // O_{s+1} = Linv y_{s+1} + sum_{db>=2} A[0][db] x_{s+1-db}; also x_{s-1} to global memory
+        float xo[K][C];     // xo[db] = x_{s+1-db}, db >= 2
+#pragma unroll
+        for (int db = 0; db < K; ++db)
+#pragma unroll
+            for (int i = 0; i < C; ++i)
+                xo[db][i] = 0.0f;
+        int ldoff = row0 + kStep * (kWavePF - r);       // unclamped offset of the next refill
+        for (int s0 = -1; s0 < total - 1; s0 += kWavePF) {
+#pragma unroll
+            for (int u = 0; u < kWavePF; ++u) {
+                const int s = s0 + u;       // step s + 1 is congruent to u: its input is in slot u
+#pragma unroll
+                for (int db = K - 1; db >= 3; --db)
+#pragma unroll
+                    for (int i = 0; i < C; ++i)
+                        xo[db][i] = xo[db - 1][i];
+#pragma unroll
+                for (int i = 0; i < C; ++i)
+                    xo[2][i] = sl.x[(((s - 1) & 1) * C + i) * 64 + lane];
+                const bool in_row = (unsigned)(s + 1 - r) < (unsigned)W;
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < C; ++j)
+                    acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wLi[j], in_row ? yb[u][j] : 0.0f, acc, 0, 0, 0);
+#pragma unroll
+                for (int db = K - 1; db >= 2; --db)
+#pragma unroll
+                    for (int i = 0; i < C; ++i)
+                        acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[0][db][i], xo[db][i], acc, 0, 0, 0);
+                sl.m[(s & 1) * K * 64 + lane] = acc;
+                const int c = s - 1 - r;        // column of x_{s-1} = xo[2] in this lane's row
+                if ((unsigned)c < Wst) {
+                    const unsigned off = (unsigned)(row0 + kStep * c);
+#pragma unroll
+                    for (int o = 0; o < C; ++o) {
+                        *reinterpret_cast<float *>(chan_dst[o] + off) = xo[2][o];
+                        if (LDS_COPY)
+                            *reinterpret_cast<float *>(chan_lds[o] + off) = xo[2][o];
+                    }
+                }
+                const unsigned off = clamp_row(ldoff);      // refill with the input of step s + 1 + kWavePF
+#pragma unroll
+                for (int ch = 0; ch < C; ++ch)
+                    yb[u][ch] = *reinterpret_cast<const float *>(chan_src[ch] + off);
+                ldoff += kStep;
+                __syncthreads();
+            }
+        }
+    }
+}
+
+template <int C, int K, int DIR>
+__global__ __launch_bounds__(256) void k_solve_wave_split(const float *__restrict__ in, const float *__restrict__ w,
+                                                         float *__restrict__ out, int H, int W)
+{
+    __shared__ __attribute__((aligned(16))) float smem[wave_split_lds_floats<C, K>()];
+    WaveSplitLds sl;
+    sl.x = smem;
+    sl.m = reinterpret_cast<f32x4 *>(smem + 2 * C * 64);
+    solve_wave_split_body<C, K, DIR, false>(in, w, out, H, W, blockIdx.x, nullptr, sl);
+}
+
 // Images of 65 .. 512 rows: one workgroup per image, one wave per band of 64 rows.
 template <int C, int K, int DIR>
 __global__ __launch_bounds__(512) void k_solve_wave_bands(const float *__restrict__ in, const float *__restrict__ w,
@@ -370,7 +591,9 @@ __global__ __launch_bounds__(512) void k_solve_wave_bands(const float *__restric
 //               accumulators of the four waves are added in a fixed order through LDS.
 // Output: part[n][P] un-negated; a second kernel adds the images in index order.
 // ---------------------------------------------------------------------------
-template <int C, int K>
+// With SPLIT all four waves stage x first and then run the transposed solve with its steps split over
+// the waves (solve_wave_split_body); its exchange buffers sit behind the tiles.
+template <int C, int K, bool SPLIT>
 __global__ __launch_bounds__(256) void k_bwd_wave(const float *__restrict__ x, const float *__restrict__ w,
                                                  const float *__restrict__ g, float *__restrict__ v,
                                                  float *__restrict__ part, int H, int W)
@@ -385,7 +608,33 @@ __global__ __launch_bounds__(256) void k_bwd_wave(const float *__restrict__ x, c
     float *sred = smem;                        // [4*64][NS*4], reuses the tiles after the products
     const int n = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
-    if (wave == 0) {
+    if (SPLIT) {
+        // all waves stage x before the solve: eight loads in flight per thread, addresses clamped (no
+        // branch around a load), halo zeroed when written
+        const float *xi = x + (size_t)n * C * H * W;
+        const int total = C * XR * XW;
+        for (int base = tid; base < total; base += 8 * 256) {
+            float val[8];
+            bool halo[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int raw = base + u * 256;
+                const int idx = raw < total ? raw : total - 1;
+                const int cc = idx % XW, rr = (idx / XW) % XR, ch = idx / (XW * XR);
+                const int gr = rr - (K - 1), gc = cc - (K - 1);
+                halo[u] = gr < 0 || gc < 0;
+                val[u] = xi[(ch * H + (gr < 0 ? 0 : gr)) * W + (gc < 0 ? 0 : gc)];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (base + u * 256 < total)
+                    sx[base + u * 256] = halo[u] ? 0.0f : val[u];
+        }
+        WaveSplitLds sl;
+        sl.x = smem + ((C * H * W + C * XR * XW + 3) & ~3);     // 16-byte aligned behind the tiles
+        sl.m = reinterpret_cast<f32x4 *>(sl.x + 2 * C * 64);
+        solve_wave_split_body<C, K, 1, true>(g, w, v, H, W, n, sv, sl);
+    } else if (wave == 0) {
         solve_wave_body<C, K, 1, true>(g, w, v, H, W, n, sv);
     } else {
         const float *xi = x + (size_t)n * C * H * W;
@@ -512,9 +761,18 @@ static int launch_wave_bands_ck(int dir, const float *in, const float *w, float 
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
+// k = 5: a step is long enough for the four-wave split of the solve to pay (measured: 223 against
+// 365 ns per step); k = 3: the single wave is as fast or faster at the image sizes in use.
+static bool wave_split_pays(int k) { return k >= 5; }
+
+// (large batches fill the CUs with single waves instead)
+bool wave_split_preferred(int B, int k) { return wave_split_pays(k) && B <= 512; }
+
 size_t bwd_wave_lds_bytes(int C, int H, int W, int k)
 {
-    const size_t tiles = (size_t)C * H * W + (size_t)C * (H + k - 1) * (W + k - 1);
+    size_t tiles = (size_t)C * H * W + (size_t)C * (H + k - 1) * (W + k - 1);
+    if (wave_split_pays(k))
+        tiles += 4 + 2 * (size_t)C * 64 + 2 * (size_t)k * 64 * 4;      // exchange buffers of the split solve
     const size_t red = 256 * (size_t)((C * k * k + 3) / 4) * 4 + 4 * (size_t)C * C * k * k;
     return sizeof(float) * (tiles > red ? tiles : red);
 }
@@ -524,13 +782,14 @@ static int launch_bwd_wave_ck(const float *x, const float *w, const float *g, fl
                               int W, hipStream_t stream)
 {
     const size_t lds = bwd_wave_lds_bytes(C, H, W, K);
+    constexpr bool kSplit = K >= 5;
     if (lds > 48 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_wave<C, K>),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_wave<C, K, kSplit>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
         return INVCONV_ERR_UNSUPPORTED;
     }
-    hipLaunchKernelGGL((k_bwd_wave<C, K>), dim3(B), dim3(256), lds, stream, x, w, g, v, part, H, W);
+    hipLaunchKernelGGL((k_bwd_wave<C, K, kSplit>), dim3(B), dim3(256), lds, stream, x, w, g, v, part, H, W);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
@@ -564,6 +823,31 @@ bool wave_supported(int C, int H, int k) { return H <= 64 && wave_ck(C, k); }
 bool wave_bands_supported(int C, int H, int W, int k)
 {
     return H > 64 && H <= 512 && wave_ck(C, k) && wave_bands_lds_bytes(H, W, k) <= 128 * 1024;
+}
+
+template <int C, int K>
+static int launch_wave_split_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
+                                hipStream_t stream)
+{
+    if (dir)
+        hipLaunchKernelGGL((k_solve_wave_split<C, K, 1>), dim3(B), dim3(256), 0, stream, in, w, out, H, W);
+    else
+        hipLaunchKernelGGL((k_solve_wave_split<C, K, 0>), dim3(B), dim3(256), 0, stream, in, w, out, H, W);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+// Same shapes as the single-wave kernel; four waves per image.
+int launch_solve_wave_split(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                            hipStream_t stream)
+{
+    if (!wave_supported(C, H, k))
+        return INVCONV_ERR_VARIANT;
+    if (C == 3 && k == 3) return launch_wave_split_ck<3, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 5) return launch_wave_split_ck<3, 5>(dir, in, w, out, B, H, W, stream);
+    if (C == 1 && k == 3) return launch_wave_split_ck<1, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 2 && k == 3) return launch_wave_split_ck<2, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 4 && k == 3) return launch_wave_split_ck<4, 3>(dir, in, w, out, B, H, W, stream);
+    return INVCONV_ERR_VARIANT;
 }
 
 int launch_solve_wave_bands(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,

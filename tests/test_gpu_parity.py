@@ -11,7 +11,7 @@ from tests.util import THREADS, TOL_ACT, TOL_DW, dev, elementwise_ok, host, rel_
 pytestmark = pytest.mark.gpu
 
 VARIANTS = [b.VARIANT_AUTO, b.VARIANT_BLOCK, b.VARIANT_DIAG_LAUNCH, b.VARIANT_WAVE, b.VARIANT_BAND,
-            b.VARIANT_PERSISTENT]
+            b.VARIANT_PERSISTENT, b.VARIANT_WAVE_SPLIT]
 WAVE_OK = {0, 1, 3}     # workloads the wave-per-image variant covers (C <= 4, H <= 64)
 BAND_OK = {2, 4}        # workloads the 16-row-band variant covers (C = 8, 12, 16; k = 3; H <= 128)
 
@@ -43,7 +43,8 @@ def check_layer(y, w, g, variant=b.VARIANT_AUTO):
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3])
 @pytest.mark.parametrize("variant", VARIANTS)
 def test_workload_parity(cfg, variant):
-    if (variant == b.VARIANT_WAVE and cfg not in WAVE_OK) or (variant == b.VARIANT_BAND and cfg not in BAND_OK):
+    if (variant in (b.VARIANT_WAVE, b.VARIANT_WAVE_SPLIT) and cfg not in WAVE_OK) or \
+            (variant == b.VARIANT_BAND and cfg not in BAND_OK):
         pytest.skip("variant does not cover this shape")
     wl = inputs.make_workload(cfg)
     print(f"cfg {cfg} variant {variant}", flush=True)
@@ -78,6 +79,21 @@ def test_edge_shapes(shape, variant):
     print(f"edge {shape} variant {variant}", flush=True)
     cs = inputs.make_case(B, C, H, W, k, seed=sum(shape), tap_std=0.05)
     check_layer(cs["y"], cs["w"][0], cs["g"], variant)
+
+
+WAVE_SPLIT_SHAPES = [  # (B, C, H, W, k): few channels, at most 64 rows
+    (1, 1, 1, 1, 3), (3, 2, 7, 13, 3), (2, 3, 13, 7, 3), (1, 4, 1, 40, 3), (1, 4, 40, 1, 3), (2, 3, 2, 2, 5),
+    (2, 3, 64, 5, 3), (3, 1, 33, 20, 3), (1, 2, 64, 64, 3), (2, 4, 63, 9, 3), (1, 3, 5, 100, 5), (1, 3, 64, 150, 3),
+    (2, 3, 31, 33, 5), (1, 4, 64, 64, 3),
+]
+
+
+@pytest.mark.parametrize("shape", WAVE_SPLIT_SHAPES)
+def test_wave_split_variant_edge_shapes(shape):
+    B, C, H, W, k = shape
+    print(f"wave split {shape}", flush=True)
+    cs = inputs.make_case(B, C, H, W, k, seed=sum(shape) + 1, tap_std=0.05)
+    check_layer(cs["y"], cs["w"][0], cs["g"], b.VARIANT_WAVE_SPLIT)
 
 
 def test_masked_entries_are_ignored_and_get_zero_gradient():
