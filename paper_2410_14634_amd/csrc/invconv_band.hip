@@ -350,7 +350,7 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
     // let wave 1 store.  Every wave runs its own loop (so that no register state is merged across the
     // roles) over the same number of steps, one barrier each.
     const int nsteps = 16 + W - 1;
-    const int total = (nsteps + 2 + kBandPF - 1) / kBandPF * kBandPF;      // steps -1 .. total-2
+    const int total = nsteps + 2;       // steps -1 .. total-2, the same for every wave
     if (wave == 0) {
         f32x4 T1p = f32x4{0.f, 0.f, 0.f, 0.f}, T2p = T1p, ownp = T1p;
         for (int s = -1; s < total - 1; ++s) {
@@ -416,29 +416,41 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
         // O_{s+1} = Linv y_{s+1} + A[0][2] x_{s-1}
         float x1[CG];
         int ldoff = row0 + kStep * (kBandPF - n);       // unclamped offset of the next refill
-        for (int s0 = -1; s0 < total - 1; s0 += kBandPF) {
+        // one step; u = slot of the input of step s + 1 (s + 1 is congruent to u)
+        auto step = [&](int s, int u, bool refill) {
 #pragma unroll
-            for (int u = 0; u < kBandPF; ++u) {
-                const int s = s0 + u;       // step s + 1 is congruent to u: its input is in slot u
+            for (int jj = 0; jj < CG; ++jj)
+                x1[jj] = sX[(((s - 1) & 1) * CG + jj) * 64 + lane];
+            const bool in_row = (unsigned)(s + 1 - n) < (unsigned)W;
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f}, acc2 = acc;
 #pragma unroll
-                for (int jj = 0; jj < CG; ++jj)
-                    x1[jj] = sX[(((s - 1) & 1) * CG + jj) * 64 + lane];
-                const bool in_row = (unsigned)(s + 1 - n) < (unsigned)W;
-                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f}, acc2 = acc;
-#pragma unroll
-                for (int jj = 0; jj < CG; ++jj) {
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wLi[jj], in_row ? yb[u][jj] : 0.0f, acc, 0, 0, 0);
-                    acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][2][jj], x1[jj], acc2, 0, 0, 0);
-                }
-                sM[((s & 1) * 3 + 2) * 64 + lane] = acc + acc2;
-                const unsigned off = clamp_row(ldoff);      // refill with the input of step s + 1 + kBandPF
+            for (int jj = 0; jj < CG; ++jj) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wLi[jj], in_row ? yb[u][jj] : 0.0f, acc, 0, 0, 0);
+                acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][2][jj], x1[jj], acc2, 0, 0, 0);
+            }
+            sM[((s & 1) * 3 + 2) * 64 + lane] = acc + acc2;
+            if (refill) {       // the input of step s + 1 + kBandPF
+                const unsigned off = clamp_row(ldoff);
 #pragma unroll
                 for (int jj = 0; jj < CG; ++jj)
                     yb[u][jj] = ld(jj, off);
                 ldoff += kStep;
-                __syncthreads();
             }
+            __syncthreads();
+        };
+        // whole blocks of kBandPF steps, then the rest without refills (its inputs are already there)
+        const int nfull = total / kBandPF;
+        int s0 = -1;
+        for (int blk = 0; blk < nfull; ++blk, s0 += kBandPF) {
+#pragma unroll
+            for (int u = 0; u < kBandPF; ++u)
+                step(s0 + u, u, true);
         }
+        const int rest = total - nfull * kBandPF;
+#pragma unroll
+        for (int u = 0; u < kBandPF; ++u)
+            if (u < rest)
+                step(s0 + u, u, false);
     }
 }
 

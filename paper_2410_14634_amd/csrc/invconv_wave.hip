@@ -420,7 +420,7 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
 
     // step s = -1 only lets wave 3 prepare O_0 = Linv y_0; the steps after the last diagonal only let it store
     const int nsteps = H + W - 1;
-    const int total = (nsteps + 2 + kWavePF - 1) / kWavePF * kWavePF;      // steps -1 .. total-2
+    const int total = nsteps + 2;       // steps -1 .. total-2, the same for every wave
     if (wave == 0) {
         f32x4 Tp[K], ownp = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -503,47 +503,59 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
             for (int i = 0; i < C; ++i)
                 xo[db][i] = 0.0f;
         int ldoff = row0 + kStep * (kWavePF - r);       // unclamped offset of the next refill
-        for (int s0 = -1; s0 < total - 1; s0 += kWavePF) {
+        // one step; u = slot of the input of step s + 1 (s + 1 is congruent to u)
+        auto step = [&](int s, int u, bool refill) {
 #pragma unroll
-            for (int u = 0; u < kWavePF; ++u) {
-                const int s = s0 + u;       // step s + 1 is congruent to u: its input is in slot u
-#pragma unroll
-                for (int db = K - 1; db >= 3; --db)
-#pragma unroll
-                    for (int i = 0; i < C; ++i)
-                        xo[db][i] = xo[db - 1][i];
+            for (int db = K - 1; db >= 3; --db)
 #pragma unroll
                 for (int i = 0; i < C; ++i)
-                    xo[2][i] = sl.x[(((s - 1) & 1) * C + i) * 64 + lane];
-                const bool in_row = (unsigned)(s + 1 - r) < (unsigned)W;
-                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                    xo[db][i] = xo[db - 1][i];
 #pragma unroll
-                for (int j = 0; j < C; ++j)
-                    acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wLi[j], in_row ? yb[u][j] : 0.0f, acc, 0, 0, 0);
+            for (int i = 0; i < C; ++i)
+                xo[2][i] = sl.x[(((s - 1) & 1) * C + i) * 64 + lane];
+            const bool in_row = (unsigned)(s + 1 - r) < (unsigned)W;
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int db = K - 1; db >= 2; --db)
+            for (int j = 0; j < C; ++j)
+                acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wLi[j], in_row ? yb[u][j] : 0.0f, acc, 0, 0, 0);
 #pragma unroll
-                    for (int i = 0; i < C; ++i)
-                        acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[0][db][i], xo[db][i], acc, 0, 0, 0);
-                sl.m[(s & 1) * K * 64 + lane] = acc;
-                const int c = s - 1 - r;        // column of x_{s-1} = xo[2] in this lane's row
-                if ((unsigned)c < Wst) {
-                    const unsigned off = (unsigned)(row0 + kStep * c);
+            for (int db = K - 1; db >= 2; --db)
 #pragma unroll
-                    for (int o = 0; o < C; ++o) {
-                        *reinterpret_cast<float *>(chan_dst[o] + off) = xo[2][o];
-                        if (LDS_COPY)
-                            *reinterpret_cast<float *>(chan_lds[o] + off) = xo[2][o];
-                    }
+                for (int i = 0; i < C; ++i)
+                    acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[0][db][i], xo[db][i], acc, 0, 0, 0);
+            sl.m[(s & 1) * K * 64 + lane] = acc;
+            const int c = s - 1 - r;        // column of x_{s-1} = xo[2] in this lane's row
+            if ((unsigned)c < Wst) {
+                const unsigned off = (unsigned)(row0 + kStep * c);
+#pragma unroll
+                for (int o = 0; o < C; ++o) {
+                    *reinterpret_cast<float *>(chan_dst[o] + off) = xo[2][o];
+                    if (LDS_COPY)
+                        *reinterpret_cast<float *>(chan_lds[o] + off) = xo[2][o];
                 }
-                const unsigned off = clamp_row(ldoff);      // refill with the input of step s + 1 + kWavePF
+            }
+            if (refill) {       // the input of step s + 1 + kWavePF
+                const unsigned off = clamp_row(ldoff);
 #pragma unroll
                 for (int ch = 0; ch < C; ++ch)
                     yb[u][ch] = *reinterpret_cast<const float *>(chan_src[ch] + off);
                 ldoff += kStep;
-                __syncthreads();
             }
+            __syncthreads();
+        };
+        // whole blocks of kWavePF steps, then the rest without refills (its inputs are already there)
+        const int nfull = total / kWavePF;
+        int s0 = -1;
+        for (int blk = 0; blk < nfull; ++blk, s0 += kWavePF) {
+#pragma unroll
+            for (int u = 0; u < kWavePF; ++u)
+                step(s0 + u, u, true);
         }
+        const int rest = total - nfull * kWavePF;
+#pragma unroll
+        for (int u = 0; u < kWavePF; ++u)
+            if (u < rest)
+                step(s0 + u, u, false);
     }
 }
 
