@@ -21,6 +21,7 @@
 // four result registers are the pixel's output channels).
 #include "invconv_common.h"
 #include "invconv_launch.h"
+#include <type_traits>
 
 namespace invconv {
 
@@ -622,25 +623,48 @@ __global__ __launch_bounds__(256) void k_bwd_wave(const float *__restrict__ x, c
 
     if (SPLIT) {
         // all waves stage x before the solve: eight loads in flight per thread, addresses clamped (no
-        // branch around a load), halo zeroed when written
+        // branch around a load), halo zeroed when written; 16 bytes per load when the halo is four
+        // columns and the rows are 16-byte aligned
         const float *xi = x + (size_t)n * C * H * W;
-        const int total = C * XR * XW;
-        for (int base = tid; base < total; base += 8 * 256) {
-            float val[8];
-            bool halo[8];
+        if (K == 5 && (W & 3) == 0 && ((size_t)xi & 15) == 0 && ((C * H * W) & 3) == 0) {
+            const int X4 = XW >> 2, total4 = C * XR * X4;
+            for (int base = tid; base < total4; base += 8 * 256) {
+                float4 val[8];
+                bool halo[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int raw = base + u * 256;
-                const int idx = raw < total ? raw : total - 1;
-                const int cc = idx % XW, rr = (idx / XW) % XR, ch = idx / (XW * XR);
-                const int gr = rr - (K - 1), gc = cc - (K - 1);
-                halo[u] = gr < 0 || gc < 0;
-                val[u] = xi[(ch * H + (gr < 0 ? 0 : gr)) * W + (gc < 0 ? 0 : gc)];
+                for (int u = 0; u < 8; ++u) {
+                    const int raw = base + u * 256;
+                    const int idx = raw < total4 ? raw : total4 - 1;
+                    const int c4 = idx % X4, rr = (idx / X4) % XR, ch = idx / (X4 * XR);
+                    const int gr = rr - (K - 1), gc = 4 * c4 - (K - 1);
+                    halo[u] = gr < 0 || gc < 0;
+                    val[u] = *reinterpret_cast<const float4 *>(xi + (ch * H + (gr < 0 ? 0 : gr)) * W + (gc < 0 ? 0 : gc));
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (base + u * 256 < total4)
+                        *reinterpret_cast<float4 *>(sx + 4 * (base + u * 256)) =
+                            halo[u] ? make_float4(0.f, 0.f, 0.f, 0.f) : val[u];
             }
+        } else {
+            const int total = C * XR * XW;
+            for (int base = tid; base < total; base += 8 * 256) {
+                float val[8];
+                bool halo[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (base + u * 256 < total)
-                    sx[base + u * 256] = halo[u] ? 0.0f : val[u];
+                for (int u = 0; u < 8; ++u) {
+                    const int raw = base + u * 256;
+                    const int idx = raw < total ? raw : total - 1;
+                    const int cc = idx % XW, rr = (idx / XW) % XR, ch = idx / (XW * XR);
+                    const int gr = rr - (K - 1), gc = cc - (K - 1);
+                    halo[u] = gr < 0 || gc < 0;
+                    val[u] = xi[(ch * H + (gr < 0 ? 0 : gr)) * W + (gc < 0 ? 0 : gc)];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (base + u * 256 < total)
+                        sx[base + u * 256] = halo[u] ? 0.0f : val[u];
+            }
         }
         WaveSplitLds sl;
         sl.x = smem + ((C * H * W + C * XR * XW + 3) & ~3);     // 16-byte aligned behind the tiles
@@ -674,18 +698,59 @@ __global__ __launch_bounds__(256) void k_bwd_wave(const float *__restrict__ x, c
 #pragma unroll
     for (int s = 0; s < NS; ++s)
         acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int npix = H * W;
-    const int ngroups = (npix + 15) / 16;
-    for (int q = wave; q < ngroups; q += 4) {
-        const int p = q * 16 + b;
-        const bool pv = p < npix;
-        const int pr = pv ? p / W : 0, pc = pv ? p - pr * W : 0;
-        const float avl = sv[aoff + pr * W + pc];
-        const float av = pv ? avl : 0.0f;       // pixels past the end contribute nothing
-        const float *bp = sx + pr * XW + pc;
+    if ((W & 15) == 0) {
+        // rows are whole groups of 16 pixels: a wave takes rows wave, wave+4, ... and walks a row GPT
+        // groups at a time, so that the tile offsets inside a trip are immediates
+        auto rows_of = [&](auto gpt_tag) {
+            constexpr int GPT = decltype(gpt_tag)::value;
+            for (int pr = wave; pr < H; pr += 4) {
+                const float *ap = sv + aoff + pr * W + b;
+                const float *bp = sx + pr * XW + b;
+                for (int pc = 0; pc < W; pc += 16 * GPT) {
+                    float av[GPT];
 #pragma unroll
-        for (int s = 0; s < NS; ++s)
-            acc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(av, bp[boff[s]], acc[s], 0, 0, 0);
+                    for (int u = 0; u < GPT; ++u)
+                        av[u] = ap[pc + 16 * u];
+                    // group u+1's columns are read while group u's products run (NS independent accumulators)
+                    float bv[2][NS];
+#pragma unroll
+                    for (int s = 0; s < NS; ++s)
+                        bv[0][s] = bp[boff[s] + pc];
+#pragma unroll
+                    for (int u = 0; u < GPT; ++u) {
+                        if (u + 1 < GPT) {
+#pragma unroll
+                            for (int s = 0; s < NS; ++s)
+                                bv[(u + 1) & 1][s] = bp[boff[s] + pc + 16 * (u + 1)];
+                        }
+                        __builtin_amdgcn_sched_barrier(0);      // keep the reads ahead of the products below
+#pragma unroll
+                        for (int s = 0; s < NS; ++s)
+                            acc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(av[u], bv[u & 1][s], acc[s], 0, 0, 0);
+                    }
+                }
+            }
+        };
+        if ((W & 63) == 0)
+            rows_of(std::integral_constant<int, 4>());
+        else if ((W & 31) == 0)
+            rows_of(std::integral_constant<int, 2>());
+        else
+            rows_of(std::integral_constant<int, 1>());
+    } else {
+        const int npix = H * W;
+        const int ngroups = (npix + 15) / 16;
+        for (int q = wave; q < ngroups; q += 4) {
+            const int p = q * 16 + b;
+            const bool pv = p < npix;
+            const int pr = pv ? p / W : 0, pc = pv ? p - pr * W : 0;
+            const float avl = sv[aoff + pr * W + pc];
+            const float av = pv ? avl : 0.0f;       // pixels past the end contribute nothing
+            const float *bp = sx + pr * XW + pc;
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                acc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(av, bp[boff[s]], acc[s], 0, 0, 0);
+        }
     }
     __syncthreads();        // tiles no longer needed: reuse them for the reduction
     // lane (b, j) register (s, o) holds block b's partial of entry (o, col = 4s + j)
