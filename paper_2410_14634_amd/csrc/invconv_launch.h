@@ -38,7 +38,7 @@ int launch_solve_band(int dir, const float *in, const float *w, float *out, int 
 bool bwd_wave_supported(int C, int H, int W, int k);
 int launch_solve_wave_split(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                             hipStream_t stream);
-bool wave_split_preferred(int B, int k);
+bool wave_split_preferred(int B, int H, int W, int k);
 bool wave_bands_supported(int C, int H, int W, int k);
 int launch_solve_wave_bands(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                             hipStream_t stream);

@@ -838,12 +838,14 @@ static int launch_wave_bands_ck(int dir, const float *in, const float *w, float 
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
-// k = 5: a step is long enough for the four-wave split of the solve to pay (measured: 223 against
-// 365 ns per step); k = 3: the single wave is as fast or faster at the image sizes in use.
+// The four-wave split of the solve costs about a microsecond more before its first step and saves
+// 20 ns (k = 3) to 140 ns (k = 5) per step at up to 32 rows, less at 64.  The forward launch uses it
+// unless the image is tiny or the batch large enough to fill the CUs with single waves.  Inside the
+// fused backward kernel it pays for k = 5 only: there the single wave leaves the other three free to
+// stage x meanwhile, which the split has to do before it starts (measured at k = 3: 2.6 us slower).
 static bool wave_split_pays(int k) { return k >= 5; }
 
-// (large batches fill the CUs with single waves instead)
-bool wave_split_preferred(int B, int k) { return wave_split_pays(k) && B <= 512; }
+bool wave_split_preferred(int B, int H, int W, int k) { return (k >= 5 || H + W >= 48) && B <= 512; }
 
 size_t bwd_wave_lds_bytes(int C, int H, int W, int k)
 {
