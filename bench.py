@@ -27,7 +27,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the forward solve kernel, from rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE
 # (KiB per dispatch), each scaled by what the same counter reads for a 64 MiB device copy
 # (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00); the runs are summarised under profiles/.
-MEASURED_TRAFFIC_BYTES = {1: int((2.00 * 181.0 + 1.00 * 192.0) * 1024)}
+MEASURED_TRAFFIC_BYTES = {1: int((2.00 * 173.5 + 1.00 * 192.0) * 1024)}
 
 
 def parse_args():
