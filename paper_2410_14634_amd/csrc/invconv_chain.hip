@@ -14,12 +14,19 @@
 //   waves 0..NB-1   compute: the band-systolic solve on 16x16x4 MFMA of the
 //                   single-layer kernel, one wave per 16-row band, but all
 //                   operands come from / go to an LDS ring, never global memory;
-//   2 loader waves  fetch the input in blocks of 4 steps (16 rows x 4 columns
+//   4 loader waves  fetch the input in blocks of 4 steps (16 rows x 4 columns
 //                   per instruction, so a row contributes 16 contiguous bytes)
 //                   into the ring, after waiting for the producer stage's
-//                   progress counter; each handles one of its bands per step;
-//   2 storer waves  drain finished results from the ring to global memory in
+//                   progress counter;
+//   4 storer waves  drain finished results from the ring to global memory in
 //                   the same blocks, then publish the stage's progress.
+// Loader and storer wave q serve bands q and q+4, and only at steps congruent
+// to q modulo 4: what a loader fetched is written into the ring four steps
+// later, and a storer publishes a block four steps after storing it.  The wave
+// issues no other memory operation in between, so "wait for everything
+// outstanding" is exact and a memory round trip has four steps to finish instead
+// of lying on every step's path.  Every role runs a loop of its own (same number
+// of barriers), so its registers are its own.
 // Data that crosses workgroups is written and read with agent-scope (device-
 // coherent) stores and loads, so publishing needs no cache write-back or
 // invalidate: the storer waits until all its stores are acknowledged and then
@@ -47,11 +54,13 @@ constexpr int kCBlk = 4;          // steps per load/store block
 constexpr int kCMsg = 4;          // depth of the band-to-band message ring
 constexpr int kCDelay = 1;        // extra steps a band lags behind the band above
 constexpr int kCLead = 8;         // a block is loaded this many steps before its first step
+constexpr int kCIo = 4;           // loader waves = storer waves = flags per (stage, image)
+constexpr int kCIoBands = 2;      // bands per loader / storer wave (NB <= 8)
 constexpr int kCSpinLimit = 1 << 21;
 constexpr int kCDone = 1 << 30;   // progress value published when a stage has finished
 
 template <int CG, int K, int DIR>
-__global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
+__global__ __launch_bounds__(1024) void k_chain_band(ChainArgs a)
 {
     constexpr int C = 4 * CG;
     extern __shared__ float smem[];
@@ -68,85 +77,68 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
     float *sL = ring;                                // folding scratch, dead before the ring is used
     float *sW = ring + C * C;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sW);
 
-    // ---- per-role set-up -------------------------------------------------------------------
-    const bool is_compute = wave < NB;
-    const int io = wave - NB;                        // 0,1 loaders; 2,3 storers
-    const int nrow = lane & 15, g = lane >> 4;       // compute: row of the band, channel group
-    const int band = is_compute ? wave : 0;
-
-    float wA[K][K][CG], wLi[CG];
-    {
-        const int m = nrow;
-        const bool m_ok = (m & 3) < CG;
-        const int om = m_ok ? CG * (m >> 2) + (m & 3) : 0;
-#pragma unroll
-        for (int aa = 0; aa < K; ++aa)
-#pragma unroll
-            for (int db = 0; db < K; ++db)
-#pragma unroll
-                for (int jj = 0; jj < CG; ++jj) {
-                    const float cf = sCf[((aa * K + db) * C + om) * C + CG * g + jj];
-                    wA[aa][db][jj] = m_ok ? -cf : 0.0f;
-                }
-#pragma unroll
-        for (int jj = 0; jj < CG; ++jj) {
-            const float lv = sLinv[om * C + CG * g + jj];
-            wLi[jj] = m_ok ? lv : 0.0f;
-        }
-    }
-    __syncthreads();        // everyone is done with sCf/sLinv reads and the folding scratch
-    for (int idx = tid; idx < NB * kCMsg * K * 64 + NB * C * kCRing * 16; idx += blockDim.x)
-        sMsg[idx] = 0.0f;   // message ring and data ring are contiguous
-    __syncthreads();
-
-    // compute state
-    float xh[CG][K];
-    f32x4 T[K];
-    f32x4 own = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int jj = 0; jj < CG; ++jj)
-#pragma unroll
-        for (int db = 0; db < K; ++db)
-            xh[jj][db] = 0.0f;
-#pragma unroll
-    for (int aa = 0; aa < K; ++aa)
-        T[aa] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int nrow = lane & 15, g = lane >> 4;       // compute: row of the band, channel group; i/o: row, step of the block
     const int span = 16 + W - 1;                               // active steps of a band
-    const int tf_c = band * (16 + kCDelay);                    // first step of this compute wave's band
-    const bool first_row = (nrow == 0) && (band > 0);
-    const bool last_row = (nrow == 15) && (band + 1 < NB);
-    const float *msg_in = sMsg + (size_t)(band > 0 ? band - 1 : 0) * kCMsg * K * 64 + g * 4;
-    float *msg_out = sMsg + (size_t)band * kCMsg * K * 64 + g * 4;
-    // ring address of this compute lane for channel jj at slot s: cbase[jj] + s*16
-    int cbase[CG];
-#pragma unroll
-    for (int jj = 0; jj < CG; ++jj)
-        cbase[jj] = ((band * C + CG * g + jj) * kCRing) * 16 + nrow;
-
-    // loader / storer state: lane = (row nrow, step j of the block)
-    const int jblk = lane >> 4;
-    const int iox = io & 1;                                    // handles bands iox, iox+2, ...
-    constexpr int kMaxIoBands = 4;                             // NB <= 8
-    float lreg[kMaxIoBands][C];
-#pragma unroll
-    for (int bi = 0; bi < kMaxIoBands; ++bi)
-#pragma unroll
-        for (int ch = 0; ch < C; ++ch)
-            lreg[bi][ch] = 0.0f;
-    const size_t img = (size_t)n_img * C * H * W;
-    constexpr int kStep = DIR ? -4 : 4;
-    int seen = (stage == 0 || a.flags == nullptr) ? kCDone : 0;   // producer progress known so far
-    const int *pflag = (stage > 0 && a.flags) ? a.flags + ((size_t)(stage - 1) * a.B + n_img) * 2 + iox : nullptr;
-    const bool coherent = stage > 0;
-    int *myflag = a.flags ? a.flags + ((size_t)stage * a.B + n_img) * 2 + iox : nullptr;
-
     const int t_last = (NB - 1) * (16 + kCDelay) + span;       // one past the last active step of any band
     const int t_end = t_last + kCBlk;                          // a band's last steps are drained up to 4 steps later
-    for (int t = -(kCLead + kCBlk); t < t_end; ++t) {
-        if (is_compute) {
+    const int t_begin = -(kCLead + kCBlk);
+    const size_t img = (size_t)n_img * C * H * W;
+
+    if (wave < NB) {
+        // ================= compute =================
+        const int band = wave;
+        float wA[K][K][CG], wLi[CG];
+        {
+            const int m = nrow;
+            const bool m_ok = (m & 3) < CG;
+            const int om = m_ok ? CG * (m >> 2) + (m & 3) : 0;
+#pragma unroll
+            for (int aa = 0; aa < K; ++aa)
+#pragma unroll
+                for (int db = 0; db < K; ++db)
+#pragma unroll
+                    for (int jj = 0; jj < CG; ++jj) {
+                        const float cf = sCf[((aa * K + db) * C + om) * C + CG * g + jj];
+                        wA[aa][db][jj] = m_ok ? -cf : 0.0f;
+                    }
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj) {
+                const float lv = sLinv[om * C + CG * g + jj];
+                wLi[jj] = m_ok ? lv : 0.0f;
+            }
+        }
+        __syncthreads();        // everyone is done with sCf/sLinv reads and the folding scratch
+        for (int idx = tid; idx < NB * kCMsg * K * 64 + NB * C * kCRing * 16; idx += blockDim.x)
+            sMsg[idx] = 0.0f;   // message ring and data ring are contiguous
+        __syncthreads();
+
+        float xh[CG][K];
+        f32x4 T[K];
+        f32x4 own = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj)
+#pragma unroll
+            for (int db = 0; db < K; ++db)
+                xh[jj][db] = 0.0f;
+#pragma unroll
+        for (int aa = 0; aa < K; ++aa)
+            T[aa] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const int tf_c = band * (16 + kCDelay);                    // first step of this band
+        const bool first_row = (nrow == 0) && (band > 0);
+        const bool last_row = (nrow == 15) && (band + 1 < NB);
+        const float *msg_in = sMsg + (size_t)(band > 0 ? band - 1 : 0) * kCMsg * K * 64 + g * 4;
+        float *msg_out = sMsg + (size_t)band * kCMsg * K * 64 + g * 4;
+        // ring address of this lane for channel jj at slot s: cbase[jj] + s*16
+        int cbase[CG];
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj)
+            cbase[jj] = ((band * C + CG * g + jj) * kCRing) * 16 + nrow;
+
+        for (int t = t_begin; t < t_end; ++t) {
             const int tau = t - tf_c;
             const int c = tau - nrow;
             if (tau >= 0 && tau < span) {
@@ -181,7 +173,7 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
                         }
                     }
 #pragma unroll
-                    for (int db = K - 1; db >= 0; --db)     // oldest column first: only db = 0 waits for this step\'s result
+                    for (int db = K - 1; db >= 0; --db)     // oldest column first: only db = 0 waits for this step's result
 #pragma unroll
                         for (int jj = 0; jj < CG; ++jj)
                             acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[aa][db][jj], xh[jj][db], acc, 0, 0, 0);
@@ -217,23 +209,54 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
                         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][db][jj], xh[jj][db], acc, 0, 0, 0);
                 own = acc;
             }
-        } else if (io < 2) {
-            // ---- loader: the band whose turn it is (one band per step, so the work is spread
-            // evenly): write the block fetched four steps ago, then fetch the next one
-            const int uw = t + kCLead - kCBlk;          // first step of the block to write
-            const int ul = t + kCLead;                  // first step of the block to fetch
+            __syncthreads();
+        }
+        return;
+    }
+
+    // ================= loaders and storers =================
+    __syncthreads();
+    for (int idx = tid; idx < NB * kCMsg * K * 64 + NB * C * kCRing * 16; idx += blockDim.x)
+        sMsg[idx] = 0.0f;
+    __syncthreads();
+    const int io = wave - NB;                        // 0..3 loaders; 4..7 storers
+    const int q = io & (kCIo - 1);                   // serves bands q, q + 4 at steps = q (mod 4)
+    const int jblk = lane >> 4;                      // lane = (row nrow, step jblk of the block)
+
+    if (io < kCIo) {
+        float lreg[kCIoBands][C];
+        bool have[kCIoBands];
 #pragma unroll
-            for (int bi = 0; bi < kMaxIoBands; ++bi) {
-                const int b = iox + 2 * bi;
-                if (bi == (t & (kMaxIoBands - 1)) && b < NB) {
-                    const int tf = b * (16 + kCDelay);
-                    if (uw + kCBlk > tf && uw < tf + span) {
+        for (int bi = 0; bi < kCIoBands; ++bi) {
+            have[bi] = false;
+#pragma unroll
+            for (int ch = 0; ch < C; ++ch)
+                lreg[bi][ch] = 0.0f;
+        }
+        int seen = (stage == 0 || a.flags == nullptr) ? kCDone : 0;   // producer progress known so far
+        const int *pflag =
+            (stage > 0 && a.flags) ? a.flags + ((size_t)(stage - 1) * a.B + n_img) * kCIo + q : nullptr;
+        const bool coherent = stage > 0;
+        for (int t = t_begin; t < t_end; ++t) {
+            if ((t & (kCIo - 1)) == q) {
+                const int uw = t + kCLead - kCBlk;          // first step of the block to write (fetched 4 steps ago)
+                const int ul = t + kCLead;                  // first step of the block to fetch
+#pragma unroll
+                for (int bi = 0; bi < kCIoBands; ++bi) {
+                    const int b = q + kCIo * bi;
+                    if (have[bi]) {
                         const int slot = (uw + jblk) & (kCRing - 1);
 #pragma unroll
                         for (int ch = 0; ch < C; ++ch)
                             ring[((b * C + ch) * kCRing + slot) * 16 + nrow] = lreg[bi][ch];
                     }
-                    if (ul + kCBlk > tf && ul < tf + span) {
+                }
+#pragma unroll
+                for (int bi = 0; bi < kCIoBands; ++bi) {
+                    const int b = q + kCIo * bi;
+                    const int tf = b * (16 + kCDelay);
+                    have[bi] = b < NB && ul + kCBlk > tf && ul < tf + span;
+                    if (have[bi]) {
                         if (seen < ul + kCBlk) {
                             // wait until the producer stage has stored every step below ul + kCBlk
                             int spins = 0, v = 0;
@@ -268,10 +291,18 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
                     }
                 }
             }
-        } else {
-            // ---- storer.  First publish: the stores issued in earlier steps were agent-scope
-            // (device-coherent) stores and have had at least a step to complete; once they are all
-            // acknowledged, every band of this wave has drained all steps below t - 4.
+            __syncthreads();
+        }
+        return;
+    }
+
+    // ---- storer
+    int *myflag = a.flags ? a.flags + ((size_t)stage * a.B + n_img) * kCIo + q : nullptr;
+    for (int t = t_begin; t < t_end; ++t) {
+        if ((t & (kCIo - 1)) == q) {
+            // First publish: this wave's last stores were issued four steps ago, as agent-scope
+            // (device-coherent) stores; once they are all acknowledged, its bands have drained every
+            // step below t - 4.
             if (myflag && t - kCBlk > 0) {
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_s_waitcnt(0);
@@ -279,43 +310,38 @@ __global__ __launch_bounds__(768) void k_chain_band(ChainArgs a)
                 if (lane == 0)
                     __hip_atomic_store(myflag, t - kCBlk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            // then drain block [t-4, t) of the band whose turn it is
+            // then drain block [t-4, t) of both bands
             const int us = t - kCBlk;
 #pragma unroll
-            for (int bi = 0; bi < kMaxIoBands; ++bi) {
-                const int b = iox + 2 * bi;
-                if (bi == (t & (kMaxIoBands - 1)) && b < NB) {
-                    const int tf = b * (16 + kCDelay);
-                    if (us + kCBlk > tf && us < tf + span) {
-                        const int row = b * 16 + nrow;
-                        const int cc = (us + jblk - tf) - nrow;
-                        const int slot = (us + jblk) & (kCRing - 1);
-                        float val[C];
+            for (int bi = 0; bi < kCIoBands; ++bi) {
+                const int b = q + kCIo * bi;
+                const int tf = b * (16 + kCDelay);
+                if (b < NB && us + kCBlk > tf && us < tf + span) {
+                    const int row = b * 16 + nrow;
+                    const int cc = (us + jblk - tf) - nrow;
+                    const int slot = (us + jblk) & (kCRing - 1);
+                    float val[C];
 #pragma unroll
-                        for (int ch = 0; ch < C; ++ch)
-                            val[ch] = ring[((b * C + ch) * kCRing + slot) * 16 + nrow];
-                        if (row < H && (unsigned)cc < (unsigned)W) {
-                            const unsigned off =
-                                4u * (unsigned)(DIR ? (H - 1 - row) * W + (W - 1 - cc) : row * W + cc);
+                    for (int ch = 0; ch < C; ++ch)
+                        val[ch] = ring[((b * C + ch) * kCRing + slot) * 16 + nrow];
+                    if (row < H && (unsigned)cc < (unsigned)W) {
+                        const unsigned off = 4u * (unsigned)(DIR ? (H - 1 - row) * W + (W - 1 - cc) : row * W + cc);
 #pragma unroll
-                            for (int ch = 0; ch < C; ++ch) {
-                                char *base = reinterpret_cast<char *>(
-                                    out + img + (size_t)(DIR ? C - 1 - ch : ch) * H * W);
-                                float *dst = reinterpret_cast<float *>(base + off);
-                                if (myflag)     // another workgroup of this launch will read it
-                                    __hip_atomic_store(dst, val[ch], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                else
-                                    *dst = val[ch];
-                            }
+                        for (int ch = 0; ch < C; ++ch) {
+                            char *base = reinterpret_cast<char *>(out + img + (size_t)(DIR ? C - 1 - ch : ch) * H * W);
+                            float *dst = reinterpret_cast<float *>(base + off);
+                            if (myflag)     // another workgroup of this launch will read it
+                                __hip_atomic_store(dst, val[ch], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            else
+                                *dst = val[ch];
                         }
                     }
                 }
             }
         }
-        (void)kStep;
         __syncthreads();
     }
-    if (!is_compute && io >= 2 && myflag) {
+    if (myflag) {
         // everything is drained: tell the consumer stage it never has to wait again
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_waitcnt(0);
@@ -346,7 +372,7 @@ bool chain_supported(int stages, int C, int H, int k)
            chain_lds_bytes(C, k, (H + 15) / 16) <= kMaxLdsBytes;
 }
 
-size_t chain_flag_ints(int stages, int B) { return (size_t)stages * B * 2 + 64; }
+size_t chain_flag_ints(int stages, int B) { return (size_t)stages * B * kCIo + 64; }
 
 template <int CG, int K>
 static int launch_chain_ck(int dir, const ChainArgs &args, int C, hipStream_t stream)
@@ -359,7 +385,7 @@ static int launch_chain_ck(int dir, const ChainArgs &args, int C, hipStream_t st
         (void)hipGetLastError();
         return INVCONV_ERR_UNSUPPORTED;
     }
-    const dim3 grid((unsigned)(args.stages * args.B)), block((unsigned)(64 * (args.NB + 4)));
+    const dim3 grid((unsigned)(args.stages * args.B)), block((unsigned)(64 * (args.NB + 2 * kCIo)));
     if (dir)
         hipLaunchKernelGGL((k_chain_band<CG, K, 1>), grid, block, lds, stream, args);
     else
@@ -375,7 +401,7 @@ int launch_chain(int dir, ChainArgs args, int C, int k, hipStream_t stream)
         return INVCONV_ERR_VARIANT;
     args.NB = (args.H + 15) / 16;
     if (args.flags) {
-        const int nflags = args.stages * args.B * 2;
+        const int nflags = args.stages * args.B * kCIo;
         args.err = args.flags + nflags;
         hipLaunchKernelGGL(k_chain_clear, dim3((nflags + 255) / 256), dim3(256), 0, stream, args.flags, nflags,
                            args.err);
