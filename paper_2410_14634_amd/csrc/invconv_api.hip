@@ -246,7 +246,7 @@ invconv_status invconv_chain_fwd(const float *y, const float *const *w, float *c
     if (!workspace || workspace_bytes < lay.total)
         return INVCONV_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    if (chain_supported(L, C, H, k)) {
+    if (chain_supported(L, C, H, W, k)) {
         ChainArgs a{};
         a.in0 = y;
         for (int l = 0; l < L; ++l) {
@@ -297,7 +297,7 @@ invconv_status invconv_chain_bwd(const float *const *x, const float *const *w, c
     for (int l = 1; l < L; ++l)
         v[l] = (float *)(ws + lay.flags_bytes + (size_t)(l - 1) * lay.grad_bytes);
     float *part = (float *)(ws + lay.flags_bytes + (size_t)(L > 1 ? L - 1 : 0) * lay.grad_bytes);
-    if (chain_supported(L, C, H, k)) {
+    if (chain_supported(L, C, H, W, k)) {
         ChainArgs a{};
         a.in0 = dLdx_last;
         for (int s = 0; s < L; ++s) {       // stage s solves layer L-1-s

@@ -20,18 +20,22 @@
 //                   progress counter;
 //   4 storer waves  drain finished results from the ring to global memory in
 //                   the same blocks, then publish the stage's progress.
-// Loader and storer wave q serve bands q and q+4, and only at steps congruent
-// to q modulo 4: what a loader fetched is written into the ring four steps
-// later, and a storer publishes a block four steps after storing it.  The wave
-// issues no other memory operation in between, so "wait for everything
-// outstanding" is exact and a memory round trip has four steps to finish instead
-// of lying on every step's path.  Every role runs a loop of its own (same number
-// of barriers), so its registers are its own.
+// Global memory is touched 64 bytes of a row at a time: a group of 16 steps of a
+// band is 16 rows x 16 columns per channel, lane (row, quarter) moves 16 bytes,
+// the four lanes of a row 64 contiguous bytes.  A group lives in the registers of
+// its loader (storer) wave and passes to (from) the ring a quarter, 4 steps, at a
+// time, every fourth step.  Each such wave serves two bands whose groups are 6
+// and 10 steps out of phase: what it fetched is first used four steps later, a
+// storer publishes a group four steps after storing it, and the wave's other
+// memory operations are at least six steps old by then, so "wait for everything
+// outstanding" costs nothing extra and a memory round trip has four steps to
+// finish instead of lying on every step's path.  Every role runs a loop of its
+// own (same number of barriers), so its registers are its own.
 // Data that crosses workgroups is written and read with agent-scope (device-
 // coherent) stores and loads, so publishing needs no cache write-back or
 // invalidate: the storer waits until all its stores are acknowledged and then
 // advances the counter; the loader reads the counter and only then issues loads.
-// The ring is indexed by the global step t (slot t mod 16) and is skew-free:
+// The ring is indexed by the global step t (16 slots per row) and is skew-free:
 // at step t every row of a band touches slot t, whatever its column, so its
 // length covers only the load lead and the store lag, not the 16-column skew of
 // a band.  A slot first holds the input y of its step and is then overwritten
@@ -42,6 +46,24 @@
 namespace invconv {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes at any 4-byte boundary of one image (a raw buffer of `bytes` bytes), read or written
+// device-coherently (sc1): no cache of this or another XCD answers with a stale line.  `lane_off`
+// is the lane's byte offset, `plane_off` a wave-uniform one.
+constexpr int kCoherent = 16;     // cache policy bit of the buffer instructions that sets sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t chain_image_buffer(const float *p, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ f32x4 chain_load16(__amdgpu_buffer_rsrc_t r, unsigned lane_off, unsigned plane_off)
+{
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)plane_off, kCoherent));
+}
+__device__ __forceinline__ void chain_store16(__amdgpu_buffer_rsrc_t r, unsigned lane_off, unsigned plane_off, f32x4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)lane_off, (int)plane_off, kCoherent);
+}
 
 __device__ __forceinline__ float chain_from_row_above(float v)
 {
@@ -50,19 +72,26 @@ __device__ __forceinline__ float chain_from_row_above(float v)
 }
 
 constexpr int kCRing = 16;        // ring slots (steps) per band
-constexpr int kCBlk = 4;          // steps per load/store block
+constexpr int kCRow = 18;         // floats per (channel, row) of the ring: 16 slots + 2, so that the 16 rows of a
+                                  // band fall into 16 different banks and a quarter (4 slots) is two 8-byte words
+constexpr int kCBlk = 4;          // steps per ring transfer (a quarter of a group)
+constexpr int kCGroup = 16;       // steps per global-memory transfer: 16 columns = 64 bytes of a row
 constexpr int kCMsg = 4;          // depth of the band-to-band message ring
 constexpr int kCDelay = 1;        // extra steps a band lags behind the band above
 constexpr int kCLead = 8;         // a block is loaded this many steps before its first step
-constexpr int kCIo = 4;           // loader waves = storer waves = flags per (stage, image)
-constexpr int kCIoBands = 2;      // bands per loader / storer wave (NB <= 8)
+constexpr int kCIo = 4;           // loader waves = storer waves
+constexpr int kCFlags = 8;        // progress counters per (stage, image): one per band
 constexpr int kCSpinLimit = 1 << 21;
 constexpr int kCDone = 1 << 30;   // progress value published when a stage has finished
 
+// 16 channels: a loader or storer wave has registers for one band only, so at most 4 bands (64 rows)
+__host__ __device__ constexpr int chain_io_bands(int C) { return C <= 12 ? 2 : 1; }
+
 template <int CG, int K, int DIR>
-__global__ __launch_bounds__(1024) void k_chain_band(ChainArgs a)
+__global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) void k_chain_band(ChainArgs a)
 {
     constexpr int C = 4 * CG;
+    constexpr int kCIoBands = chain_io_bands(C);     // bands per loader / storer wave
     extern __shared__ float smem[];
     const int H = a.H, W = a.W, NB = a.NB;
     const int stage = blockIdx.x / a.B, n_img = blockIdx.x % a.B;
@@ -73,7 +102,7 @@ __global__ __launch_bounds__(1024) void k_chain_band(ChainArgs a)
     float *sLinv = smem;
     float *sCf = sLinv + C * C;
     float *sMsg = sCf + K * K * C * C;               // [NB][kCMsg][K][64]
-    float *ring = sMsg + NB * kCMsg * K * 64;        // [NB][C][kCRing][16]
+    float *ring = sMsg + NB * kCMsg * K * 64;        // [NB][C][16 rows][kCRow]; step t of band b is slot (t - b) & 15 of its row
     float *sL = ring;                                // folding scratch, dead before the ring is used
     float *sW = ring + C * C;
 
@@ -84,8 +113,8 @@ __global__ __launch_bounds__(1024) void k_chain_band(ChainArgs a)
     const int nrow = lane & 15, g = lane >> 4;       // compute: row of the band, channel group; i/o: row, step of the block
     const int span = 16 + W - 1;                               // active steps of a band
     const int t_last = (NB - 1) * (16 + kCDelay) + span;       // one past the last active step of any band
-    const int t_end = t_last + kCBlk;                          // a band's last steps are drained up to 4 steps later
-    const int t_begin = -(kCLead + kCBlk);
+    const int t_end = t_last + kCGroup;                        // a band's last group is stored up to 16 steps later
+    const int t_begin = -(kCLead + kCGroup);                   // the group that holds step 0 is fetched up to 24 steps before
     const size_t img = (size_t)n_img * C * H * W;
 
     if (wave < NB) {
@@ -112,7 +141,7 @@ __global__ __launch_bounds__(1024) void k_chain_band(ChainArgs a)
             }
         }
         __syncthreads();        // everyone is done with sCf/sLinv reads and the folding scratch
-        for (int idx = tid; idx < NB * kCMsg * K * 64 + NB * C * kCRing * 16; idx += blockDim.x)
+        for (int idx = tid; idx < NB * kCMsg * K * 64 + NB * C * 16 * kCRow; idx += blockDim.x)
             sMsg[idx] = 0.0f;   // message ring and data ring are contiguous
         __syncthreads();
 
@@ -132,11 +161,11 @@ __global__ __launch_bounds__(1024) void k_chain_band(ChainArgs a)
         const bool last_row = (nrow == 15) && (band + 1 < NB);
         const float *msg_in = sMsg + (size_t)(band > 0 ? band - 1 : 0) * kCMsg * K * 64 + g * 4;
         float *msg_out = sMsg + (size_t)band * kCMsg * K * 64 + g * 4;
-        // ring address of this lane for channel jj at slot s: cbase[jj] + s*16
+        // ring address of this lane for channel jj at step t: cbase[jj] + ((t - band) & 15)
         int cbase[CG];
 #pragma unroll
         for (int jj = 0; jj < CG; ++jj)
-            cbase[jj] = ((band * C + CG * g + jj) * kCRing) * 16 + nrow;
+            cbase[jj] = ((band * C + CG * g + jj) * 16 + nrow) * kCRow;
 
         for (int t = t_begin; t < t_end; ++t) {
             const int tau = t - tf_c;
@@ -158,7 +187,7 @@ __global__ __launch_bounds__(1024) void k_chain_band(ChainArgs a)
                 // result replaces the input in the ring slot of this step (the storers skip invalid pixels)
 #pragma unroll
                 for (int j = 0; j < CG; ++j)
-                    ring[cbase[j] + (t & (kCRing - 1)) * 16] = xn[j];
+                    ring[cbase[j] + ((t - band) & (kCRing - 1))] = xn[j];
 #pragma unroll
                 for (int jj = 0; jj < CG; ++jj)
                     xh[jj][0] = xn[jj];
@@ -199,7 +228,7 @@ __global__ __launch_bounds__(1024) void k_chain_band(ChainArgs a)
                 f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int jj = 0; jj < CG; ++jj) {
-                    const float yv = ring[cbase[jj] + ((t + 1) & (kCRing - 1)) * 16];
+                    const float yv = ring[cbase[jj] + ((t + 1 - band) & (kCRing - 1))];
                     acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wLi[jj], in_row ? yv : 0.0f, acc, 0, 0, 0);
                 }
 #pragma unroll
@@ -216,77 +245,130 @@ __global__ __launch_bounds__(1024) void k_chain_band(ChainArgs a)
 
     // ================= loaders and storers =================
     __syncthreads();
-    for (int idx = tid; idx < NB * kCMsg * K * 64 + NB * C * kCRing * 16; idx += blockDim.x)
+    for (int idx = tid; idx < NB * kCMsg * K * 64 + NB * C * 16 * kCRow; idx += blockDim.x)
         sMsg[idx] = 0.0f;
     __syncthreads();
     const int io = wave - NB;                        // 0..3 loaders; 4..7 storers
-    const int q = io & (kCIo - 1);                   // serves bands q, q + 4 at steps = q (mod 4)
-    const int jblk = lane >> 4;                      // lane = (row nrow, step jblk of the block)
+    const int jq = lane >> 4;                        // lane = (row nrow, quarter jq of a 16-step group)
+    // A lane moves 16 bytes: columns c0 .. c0+3 of its row, c0 = U + 4*jq - tf - nrow for the group
+    // that starts at step U.  The four lanes of a row cover 64 contiguous bytes.
+    // Wave q of either kind serves band A in 0..3 and band A' = 4 + ((A + 2) & 3); groups of band A
+    // start at steps = A (mod 16), those of A' at steps = A + 10 (mod 16); a band is served at the
+    // steps congruent to it modulo 4.  Loader q has A = q, storer q has A = q - 1 (another SIMD).
+    const int q = io & (kCIo - 1);
+    const int bandA = io < kCIo ? q : ((q + 3) & 3);
+    const int rowW = W;
+    const unsigned plane_bytes = 4u * (unsigned)(H * W);
+    const __amdgpu_buffer_rsrc_t rin = chain_image_buffer(in + img, plane_bytes * C);
+    const __amdgpu_buffer_rsrc_t rout = chain_image_buffer(out + img, plane_bytes * C);
+    int bnd[kCIoBands], gph[kCIoBands], tfb[kCIoBands];
+#pragma unroll
+    for (int bi = 0; bi < kCIoBands; ++bi) {
+        bnd[bi] = bi == 0 ? bandA : 4 + ((bandA + 2) & 3);
+        gph[bi] = bi == 0 ? bandA : bandA + 10;
+        tfb[bi] = bnd[bi] * (16 + kCDelay);
+    }
 
     if (io < kCIo) {
-        float lreg[kCIoBands][C];
-        bool have[kCIoBands];
+        f32x4 lr[kCIoBands][C];
+        bool have[kCIoBands], edge[kCIoBands];
+        int dsh[kCIoBands];
 #pragma unroll
         for (int bi = 0; bi < kCIoBands; ++bi) {
             have[bi] = false;
+            edge[bi] = false;
+            dsh[bi] = 0;
 #pragma unroll
             for (int ch = 0; ch < C; ++ch)
-                lreg[bi][ch] = 0.0f;
+                lr[bi][ch] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
-        int seen = (stage == 0 || a.flags == nullptr) ? kCDone : 0;   // producer progress known so far
-        const int *pflag =
-            (stage > 0 && a.flags) ? a.flags + ((size_t)(stage - 1) * a.B + n_img) * kCIo + q : nullptr;
-        const bool coherent = stage > 0;
+        int seen[kCIoBands];                             // producer progress known so far
+        const int *pflag[kCIoBands];
+#pragma unroll
+        for (int bi = 0; bi < kCIoBands; ++bi) {
+            seen[bi] = (stage == 0 || a.flags == nullptr) ? kCDone : 0;
+            pflag[bi] = (stage > 0 && a.flags) ? a.flags + ((size_t)(stage - 1) * a.B + n_img) * kCFlags + bnd[bi]
+                                                : nullptr;
+        }
         for (int t = t_begin; t < t_end; ++t) {
-            if ((t & (kCIo - 1)) == q) {
-                const int uw = t + kCLead - kCBlk;          // first step of the block to write (fetched 4 steps ago)
-                const int ul = t + kCLead;                  // first step of the block to fetch
 #pragma unroll
-                for (int bi = 0; bi < kCIoBands; ++bi) {
-                    const int b = q + kCIo * bi;
-                    if (have[bi]) {
-                        const int slot = (uw + jblk) & (kCRing - 1);
+            for (int bi = 0; bi < kCIoBands; ++bi) {
+                if (((t - gph[bi]) & 3) == 0) {
+                    const int b = bnd[bi], tf = tfb[bi];
+                    const int uw = t + kCBlk;                       // first step of the quarter written now
+                    const int i = ((uw - gph[bi]) >> 2) & 3;        // its position in the group held in registers
+                    if (have[bi] && jq == i) {
+                        float *dst = ring + ((b * C) * 16 + nrow) * kCRow + ((uw - b) & (kCRing - 1));
+                        // lr holds memory order: column cv + m is component m, mirrored 3 - m
+                        if (!edge[bi]) {
 #pragma unroll
-                        for (int ch = 0; ch < C; ++ch)
-                            ring[((b * C + ch) * kCRing + slot) * 16 + nrow] = lreg[bi][ch];
-                    }
-                }
-#pragma unroll
-                for (int bi = 0; bi < kCIoBands; ++bi) {
-                    const int b = q + kCIo * bi;
-                    const int tf = b * (16 + kCDelay);
-                    have[bi] = b < NB && ul + kCBlk > tf && ul < tf + span;
-                    if (have[bi]) {
-                        if (seen < ul + kCBlk) {
-                            // wait until the producer stage has stored every step below ul + kCBlk
-                            int spins = 0, v = 0;
-                            do {
-                                v = __hip_atomic_load(pflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                if (v >= ul + kCBlk)
-                                    break;
-                                __builtin_amdgcn_s_sleep(8);
-                            } while (++spins < kCSpinLimit);
-                            if (v < ul + kCBlk) {
-                                if (a.err)
-                                    a.err[0] = 1;       // bounded wait ran out: carry on, results are invalid
-                                v = kCDone;
+                            for (int ch = 0; ch < C; ++ch) {
+                                const f32x4 v = lr[bi][ch];
+                                float *d = dst + ch * 16 * kCRow;
+                                if (DIR) {
+                                    d[0] = v[3];
+                                    d[1] = v[2];
+                                    d[2] = v[1];
+                                    d[3] = v[0];
+                                } else {
+                                    float2 *d2 = reinterpret_cast<float2 *>(d);
+                                    d2[0] = float2{v[0], v[1]};
+                                    d2[1] = float2{v[2], v[3]};
+                                }
                             }
-                            seen = v;
-                            asm volatile("" ::: "memory");   // the loads below are issued after the counter was read
-                        }
-                        int row = b * 16 + nrow;
-                        row = row < H ? row : H - 1;
-                        int cc = (ul + jblk - tf) - nrow;
-                        cc = cc < 0 ? 0 : (cc > W - 1 ? W - 1 : cc);
-                        const unsigned off = 4u * (unsigned)(DIR ? (H - 1 - row) * W + (W - 1 - cc) : row * W + cc);
+                        } else {
+                            // a group that reaches over an end of the row: the lane's four columns were
+                            // fetched from the nearest position inside the row, dsh columns away, so
+                            // component m belongs to slot m - dsh of the quarter, if that is one of its four
+                            float *de = dst - dsh[bi];
 #pragma unroll
-                        for (int ch = 0; ch < C; ++ch) {
-                            const char *base = reinterpret_cast<const char *>(
-                                in + img + (size_t)(DIR ? C - 1 - ch : ch) * H * W);
-                            const float *src = reinterpret_cast<const float *>(base + off);
-                            // what another workgroup of this launch wrote is read device-coherently
-                            lreg[bi][ch] = coherent ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                                    : *src;
+                            for (int m = 0; m < 4; ++m) {
+                                if ((unsigned)(m - dsh[bi]) < 4u) {
+#pragma unroll
+                                    for (int ch = 0; ch < C; ++ch)
+                                        de[ch * 16 * kCRow + m] = lr[bi][ch][DIR ? 3 - m : m];
+                                }
+                            }
+                        }
+                    }
+                    if (i == 3) {
+                        const int U = t + kCLead;                   // the next group: its first quarter is written in 4 steps
+                        // Nothing fetched is still unused here except the other band's group, issued six or
+                        // more steps ago; waiting now keeps the compiler from waiting between the loads below
+                        // for registers it reuses.
+                        __builtin_amdgcn_s_waitcnt(0);
+                        have[bi] = b < NB && U + kCGroup > tf && U < tf + span;
+                        if (have[bi]) {
+                            if (seen[bi] < U + kCGroup) {
+                                // wait until the producer stage has stored every step of this band below U + 16
+                                int spins = 0, v = 0;
+                                do {
+                                    v = __hip_atomic_load(pflag[bi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                    if (v >= U + kCGroup)
+                                        break;
+                                    __builtin_amdgcn_s_sleep(8);
+                                } while (++spins < kCSpinLimit);
+                                if (v < U + kCGroup) {
+                                    if (a.err)
+                                        a.err[0] = 1;       // bounded wait ran out: carry on, results are invalid
+                                    v = kCDone;
+                                }
+                                seen[bi] = v;
+                                asm volatile("" ::: "memory");   // the loads below are issued after the counter was read
+                            }
+                            int row = b * 16 + nrow;
+                            row = row < H ? row : H - 1;
+                            const int c0 = (U + 4 * jq - tf) - nrow;
+                            const int cv = c0 < 0 ? 0 : (c0 > rowW - 4 ? rowW - 4 : c0);
+                            dsh[bi] = c0 - cv;
+                            edge[bi] = __builtin_amdgcn_ballot_w64(c0 != cv) != 0;
+                            const unsigned off =
+                                4u * (unsigned)(DIR ? (H - 1 - row) * rowW + (rowW - 4 - cv) : row * rowW + cv);
+#pragma unroll
+                            for (int ch = 0; ch < C; ++ch) {
+                                // device-coherent: another workgroup of this launch may have written it
+                                lr[bi][ch] = chain_load16(rin, off, plane_bytes * (unsigned)(DIR ? C - 1 - ch : ch));
+                            }
                         }
                     }
                 }
@@ -297,58 +379,94 @@ __global__ __launch_bounds__(1024) void k_chain_band(ChainArgs a)
     }
 
     // ---- storer
-    int *myflag = a.flags ? a.flags + ((size_t)stage * a.B + n_img) * kCIo + q : nullptr;
+    int *myflag[kCIoBands];
+    f32x4 sr[kCIoBands][C];
+    int publish[kCIoBands];                          // progress to publish once the band's stores are acknowledged
+#pragma unroll
+    for (int bi = 0; bi < kCIoBands; ++bi) {
+        myflag[bi] = a.flags ? a.flags + ((size_t)stage * a.B + n_img) * kCFlags + bnd[bi] : nullptr;
+        publish[bi] = 0;
+#pragma unroll
+        for (int ch = 0; ch < C; ++ch)
+            sr[bi][ch] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
     for (int t = t_begin; t < t_end; ++t) {
-        if ((t & (kCIo - 1)) == q) {
-            // First publish: this wave's last stores were issued four steps ago, as agent-scope
-            // (device-coherent) stores; once they are all acknowledged, its bands have drained every
-            // step below t - 4.
-            if (myflag && t - kCBlk > 0) {
-                asm volatile("" ::: "memory");
-                __builtin_amdgcn_s_waitcnt(0);
-                asm volatile("" ::: "memory");
-                if (lane == 0)
-                    __hip_atomic_store(myflag, t - kCBlk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            // then drain block [t-4, t) of both bands
-            const int us = t - kCBlk;
 #pragma unroll
-            for (int bi = 0; bi < kCIoBands; ++bi) {
-                const int b = q + kCIo * bi;
-                const int tf = b * (16 + kCDelay);
-                if (b < NB && us + kCBlk > tf && us < tf + span) {
-                    const int row = b * 16 + nrow;
-                    const int cc = (us + jblk - tf) - nrow;
-                    const int slot = (us + jblk) & (kCRing - 1);
-                    float val[C];
+        for (int bi = 0; bi < kCIoBands; ++bi) {
+            if (((t - gph[bi]) & 3) == 0) {
+                const int b = bnd[bi], tf = tfb[bi];
+                // The band's last stores were issued at least four steps ago (the other band's six), as
+                // device-coherent stores; once all are acknowledged, every step below `publish` is in memory.
+                if (myflag[bi] && publish[bi] > 0) {
+                    asm volatile("" ::: "memory");
+                    __builtin_amdgcn_s_waitcnt(0);
+                    asm volatile("" ::: "memory");
+                    if (lane == 0)
+                        __hip_atomic_store(myflag[bi], publish[bi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    publish[bi] = 0;
+                }
+                // collect the quarter [t-4, t); after the fourth quarter store the group
+                const int us = t - kCBlk;
+                const int i = ((us - gph[bi]) >> 2) & 3;
+                if (b < NB && us + kCBlk > tf && us < tf + span && jq == i) {
+                    const float *src = ring + ((b * C) * 16 + nrow) * kCRow + ((us - b) & (kCRing - 1));
 #pragma unroll
-                    for (int ch = 0; ch < C; ++ch)
-                        val[ch] = ring[((b * C + ch) * kCRing + slot) * 16 + nrow];
-                    if (row < H && (unsigned)cc < (unsigned)W) {
-                        const unsigned off = 4u * (unsigned)(DIR ? (H - 1 - row) * W + (W - 1 - cc) : row * W + cc);
-#pragma unroll
-                        for (int ch = 0; ch < C; ++ch) {
-                            char *base = reinterpret_cast<char *>(out + img + (size_t)(DIR ? C - 1 - ch : ch) * H * W);
-                            float *dst = reinterpret_cast<float *>(base + off);
-                            if (myflag)     // another workgroup of this launch will read it
-                                __hip_atomic_store(dst, val[ch], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            else
-                                *dst = val[ch];
+                    for (int ch = 0; ch < C; ++ch) {
+                        // kept in memory order (mirrored: columns descending), so that the store needs no shuffle
+                        const float *sc = src + ch * 16 * kCRow;
+                        if (DIR) {
+                            sr[bi][ch] = f32x4{sc[3], sc[2], sc[1], sc[0]};
+                        } else {
+                            const float2 *s2 = reinterpret_cast<const float2 *>(sc);
+                            const float2 lo = s2[0], hi = s2[1];
+                            sr[bi][ch] = f32x4{lo.x, lo.y, hi.x, hi.y};
                         }
                     }
+                }
+                if (i == 3) {
+                    const int U = us - 3 * kCBlk;
+                    if (b < NB && U + kCGroup > tf && U < tf + span) {
+                        const int row = b * 16 + nrow;
+                        const int c0 = (U + 4 * jq - tf) - nrow;
+                        if (row < H && c0 >= 0 && c0 + 3 <= rowW - 1) {
+                            const unsigned off =
+                                4u * (unsigned)(DIR ? (H - 1 - row) * rowW + (rowW - 4 - c0) : row * rowW + c0);
+#pragma unroll
+                            for (int ch = 0; ch < C; ++ch)
+                                chain_store16(rout, off, plane_bytes * (unsigned)(DIR ? C - 1 - ch : ch), sr[bi][ch]);
+                        } else if (row < H) {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const int cj = c0 + j;
+                                if ((unsigned)cj < (unsigned)rowW) {
+                                    const unsigned offj = 4u * (unsigned)(DIR ? (H - 1 - row) * rowW + (rowW - 1 - cj)
+                                                                              : row * rowW + cj);
+#pragma unroll
+                                    for (int ch = 0; ch < C; ++ch) {
+                                        char *base = reinterpret_cast<char *>(
+                                            out + img + (size_t)(DIR ? C - 1 - ch : ch) * H * rowW);
+                                        __hip_atomic_store(reinterpret_cast<float *>(base + offj),
+                                                           sr[bi][ch][DIR ? 3 - j : j], __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT);
+                                    }
+                                }
+                            }
+                        }
+                    }
+                    publish[bi] = t;                    // = U + 16: everything below it has now been issued
                 }
             }
         }
         __syncthreads();
     }
-    if (myflag) {
-        // everything is drained: tell the consumer stage it never has to wait again
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_waitcnt(0);
-        asm volatile("" ::: "memory");
-        if (lane == 0)
-            __hip_atomic_store(myflag, kCDone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    // everything is drained: tell the consumer stage it never has to wait again
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0);
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int bi = 0; bi < kCIoBands; ++bi)
+        if (myflag[bi] && lane == 0)
+            __hip_atomic_store(myflag[bi], kCDone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ void k_chain_clear(int *flags, int nflags, int *err)
@@ -363,16 +481,18 @@ __global__ void k_chain_clear(int *flags, int nflags, int *err)
 size_t chain_lds_bytes(int C, int k, int NB)
 {
     return sizeof(float) * ((size_t)C * C + (size_t)k * k * C * C + (size_t)NB * kCMsg * k * 64 +
-                            (size_t)NB * C * kCRing * 16);
+                            (size_t)NB * C * 16 * kCRow);
 }
 
-bool chain_supported(int stages, int C, int H, int k)
+bool chain_supported(int stages, int C, int H, int W, int k)
 {
-    return stages >= 1 && stages <= kChainMaxLayers && (C == 8 || C == 12 || C == 16) && k == 3 && H <= 128 &&
+    // W >= 4: a lane moves four columns of a row at a time
+    return stages >= 1 && stages <= kChainMaxLayers && (C == 8 || C == 12 || C == 16) && k == 3 && W >= 4 &&
+           (H + 15) / 16 <= kCIo * chain_io_bands(C) &&
            chain_lds_bytes(C, k, (H + 15) / 16) <= kMaxLdsBytes;
 }
 
-size_t chain_flag_ints(int stages, int B) { return (size_t)stages * B * kCIo + 64; }
+size_t chain_flag_ints(int stages, int B) { return (size_t)stages * B * kCFlags + 64; }
 
 template <int CG, int K>
 static int launch_chain_ck(int dir, const ChainArgs &args, int C, hipStream_t stream)
@@ -397,11 +517,11 @@ static int launch_chain_ck(int dir, const ChainArgs &args, int C, hipStream_t st
 // error word) is cleared first; it may be null only when stages == 1.
 int launch_chain(int dir, ChainArgs args, int C, int k, hipStream_t stream)
 {
-    if (!chain_supported(args.stages, C, args.H, k) || (args.stages > 1 && !args.flags))
+    if (!chain_supported(args.stages, C, args.H, args.W, k) || (args.stages > 1 && !args.flags))
         return INVCONV_ERR_VARIANT;
     args.NB = (args.H + 15) / 16;
     if (args.flags) {
-        const int nflags = args.stages * args.B * kCIo;
+        const int nflags = args.stages * args.B * kCFlags;
         args.err = args.flags + nflags;
         hipLaunchKernelGGL(k_chain_clear, dim3((nflags + 255) / 256), dim3(256), 0, stream, args.flags, nflags,
                            args.err);

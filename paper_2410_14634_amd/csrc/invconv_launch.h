@@ -73,7 +73,7 @@ struct ChainArgs {
     int *err;                            // set by launch_chain
     int stages, B, H, W, NB;
 };
-bool chain_supported(int stages, int C, int H, int k);
+bool chain_supported(int stages, int C, int H, int W, int k);
 size_t chain_flag_ints(int stages, int B);
 int launch_chain(int dir, ChainArgs args, int C, int k, hipStream_t stream);
 // y = M x (dir 0) or y = M^T x (dir 1) for the masked causal convolution M

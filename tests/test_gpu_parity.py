@@ -282,7 +282,7 @@ def test_chain_error_word_stays_clear():
     wsp = torch.zeros(need, dtype=torch.uint8, device="cuda")
     b.invconv_chain_fwd(dev(cases[0]["y"]), wd, workspace=wsp)
     torch.cuda.synchronize()
-    nflags = L * B * 4                                 # one progress counter per storer wave, 4 per (layer, image)
+    nflags = L * B * 8                                 # one progress counter per band, 8 per (layer, image)
     flags = wsp[: (nflags + 1) * 4].view(torch.int32).cpu().numpy()
     assert flags[nflags] == 0                          # error word
     assert np.all(flags[:nflags] == 1 << 30)           # every stage published "finished"
