@@ -78,7 +78,9 @@ constexpr int kCBlk = 4;          // steps per ring transfer (a quarter of a gro
 constexpr int kCGroup = 16;       // steps per global-memory transfer: 16 columns = 64 bytes of a row
 constexpr int kCMsg = 4;          // depth of the band-to-band message ring
 constexpr int kCDelay = 1;        // extra steps a band lags behind the band above
-constexpr int kCLead = 8;         // a block is loaded this many steps before its first step
+constexpr int kCAhead = 2;        // a quarter enters the ring this many steps before its first step is solved
+constexpr int kCLead = kCAhead + 4;  // a group is fetched this many steps before its first step: four for the round trip
+constexpr int kCPubLag = 2;       // a storer publishes a group this many steps after storing it
 constexpr int kCIo = 4;           // loader waves = storer waves
 constexpr int kCFlags = 8;        // progress counters per (stage, image): one per band
 constexpr int kCSpinLimit = 1 << 21;
@@ -167,10 +169,18 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
         for (int jj = 0; jj < CG; ++jj)
             cbase[jj] = ((band * C + CG * g + jj) * 16 + nrow) * kCRow;
 
+        // A step in this order: the terms that need nothing newer than the previous pixel of the row
+        // go to the matrix cores first (18 of the 27 products), so that the LDS reads of this step
+        // complete behind them; then the pixel itself, then the 9 products that contain it.
         for (int t = t_begin; t < t_end; ++t) {
             const int tau = t - tf_c;
             const int c = tau - nrow;
-            if (tau >= 0 && tau < span) {
+            // tau = -1 only prepares pixel 0; doing the rest of the step on the all-zero state is harmless
+            if (tau >= -1 && tau < span) {
+                float yv[CG];
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    yv[jj] = ring[cbase[jj] + ((t + 1 - band) & (kCRing - 1))];
                 const float *mi = msg_in + ((t - 1 - kCDelay) & (kCMsg - 1)) * K * 64;
                 float mrow[K][CG];
 #pragma unroll
@@ -178,6 +188,37 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
 #pragma unroll
                     for (int j = 0; j < CG; ++j)
                         mrow[aa][j] = mi[aa * 64 + j];
+                const bool in_row = (unsigned)(c + 1) < (unsigned)W;
+                // xh[.][db] = x at column c - db (db >= 1); xh[.][0] is filled below
+                f32x4 accT[K];
+#pragma unroll
+                for (int aa = K - 1; aa >= 1; --aa) {      // the last one first: it takes nothing from the row above
+                    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (aa + 1 < K) {
+#pragma unroll
+                        for (int j = 0; j < CG; ++j) {
+                            const float up = chain_from_row_above(T[aa + 1][j]);
+                            acc[j] = first_row ? mrow[aa + 1][j] : up;
+                        }
+                    }
+#pragma unroll
+                    for (int db = K - 1; db >= 1; --db)
+#pragma unroll
+                        for (int jj = 0; jj < CG; ++jj)
+                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[aa][db][jj], xh[jj][db], acc, 0, 0, 0);
+                    accT[aa] = acc;
+                }
+                // the part of the next pixel that does not depend on this one
+                f32x4 accO = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int db = K - 1; db >= 2; --db)
+#pragma unroll
+                    for (int jj = 0; jj < CG; ++jj)
+                        accO = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][db][jj], xh[jj][db - 1], accO, 0, 0, 0);
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    accO = __builtin_amdgcn_mfma_f32_16x16x4f32(wLi[jj], in_row ? yv[jj] : 0.0f, accO, 0, 0, 0);
+                // this pixel
                 float xn[CG];
 #pragma unroll
                 for (int j = 0; j < CG; ++j) {
@@ -189,25 +230,17 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                 for (int j = 0; j < CG; ++j)
                     ring[cbase[j] + ((t - band) & (kCRing - 1))] = xn[j];
 #pragma unroll
-                for (int jj = 0; jj < CG; ++jj)
-                    xh[jj][0] = xn[jj];
-#pragma unroll
                 for (int aa = 1; aa < K; ++aa) {
-                    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-                    if (aa + 1 < K) {
+                    f32x4 acc = accT[aa];
 #pragma unroll
-                        for (int j = 0; j < CG; ++j) {
-                            const float up = chain_from_row_above(T[aa + 1][j]);
-                            acc[j] = first_row ? mrow[aa + 1][j] : up;
-                        }
-                    }
-#pragma unroll
-                    for (int db = K - 1; db >= 0; --db)     // oldest column first: only db = 0 waits for this step's result
-#pragma unroll
-                        for (int jj = 0; jj < CG; ++jj)
-                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[aa][db][jj], xh[jj][db], acc, 0, 0, 0);
+                    for (int jj = 0; jj < CG; ++jj)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[aa][0][jj], xn[jj], acc, 0, 0, 0);
                     T[aa] = acc;
                 }
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    accO = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][1][jj], xn[jj], accO, 0, 0, 0);
+                own = accO;
                 if (last_row) {
                     float *mo = msg_out + (t & (kCMsg - 1)) * K * 64;
 #pragma unroll
@@ -217,26 +250,12 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                             mo[aa * 64 + j] = T[aa][j];
                 }
 #pragma unroll
-                for (int jj = 0; jj < CG; ++jj)
-#pragma unroll
-                    for (int db = K - 1; db >= 1; --db)
-                        xh[jj][db] = xh[jj][db - 1];
-            }
-            if (tau + 1 >= 0 && tau + 1 < span) {
-                // prepare the part of the next pixel that does not depend on the rows above
-                const bool in_row = (unsigned)(c + 1) < (unsigned)W;
-                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
                 for (int jj = 0; jj < CG; ++jj) {
-                    const float yv = ring[cbase[jj] + ((t + 1 - band) & (kCRing - 1))];
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wLi[jj], in_row ? yv : 0.0f, acc, 0, 0, 0);
+#pragma unroll
+                    for (int db = K - 1; db >= 2; --db)
+                        xh[jj][db] = xh[jj][db - 1];
+                    xh[jj][1] = xn[jj];
                 }
-#pragma unroll
-                for (int db = K - 1; db >= 1; --db)
-#pragma unroll
-                    for (int jj = 0; jj < CG; ++jj)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][db][jj], xh[jj][db], acc, 0, 0, 0);
-                own = acc;
             }
             __syncthreads();
         }
@@ -293,9 +312,9 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
         for (int t = t_begin; t < t_end; ++t) {
 #pragma unroll
             for (int bi = 0; bi < kCIoBands; ++bi) {
-                if (((t - gph[bi]) & 3) == 0) {
+                if (((t + kCAhead - gph[bi]) & 3) == 0) {
                     const int b = bnd[bi], tf = tfb[bi];
-                    const int uw = t + kCBlk;                       // first step of the quarter written now
+                    const int uw = t + kCAhead;                     // first step of the quarter written now
                     const int i = ((uw - gph[bi]) >> 2) & 3;        // its position in the group held in registers
                     if (have[bi] && jq == i) {
                         float *dst = ring + ((b * C) * 16 + nrow) * kCRow + ((uw - b) & (kCRing - 1));
@@ -381,11 +400,12 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
     // ---- storer
     int *myflag[kCIoBands];
     f32x4 sr[kCIoBands][C];
-    int publish[kCIoBands];                          // progress to publish once the band's stores are acknowledged
+    int publish[kCIoBands], pubat[kCIoBands];        // progress to publish once the band's stores are acknowledged, and when
 #pragma unroll
     for (int bi = 0; bi < kCIoBands; ++bi) {
         myflag[bi] = a.flags ? a.flags + ((size_t)stage * a.B + n_img) * kCFlags + bnd[bi] : nullptr;
         publish[bi] = 0;
+        pubat[bi] = 0;
 #pragma unroll
         for (int ch = 0; ch < C; ++ch)
             sr[bi][ch] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -393,18 +413,18 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
     for (int t = t_begin; t < t_end; ++t) {
 #pragma unroll
         for (int bi = 0; bi < kCIoBands; ++bi) {
+            // The band's last stores were issued kCPubLag steps ago (the other band's four or more), as
+            // device-coherent stores; once all are acknowledged, every step below `publish` is in memory.
+            if (myflag[bi] && publish[bi] > 0 && t >= pubat[bi]) {
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0);
+                asm volatile("" ::: "memory");
+                if (lane == 0)
+                    __hip_atomic_store(myflag[bi], publish[bi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                publish[bi] = 0;
+            }
             if (((t - gph[bi]) & 3) == 0) {
                 const int b = bnd[bi], tf = tfb[bi];
-                // The band's last stores were issued at least four steps ago (the other band's six), as
-                // device-coherent stores; once all are acknowledged, every step below `publish` is in memory.
-                if (myflag[bi] && publish[bi] > 0) {
-                    asm volatile("" ::: "memory");
-                    __builtin_amdgcn_s_waitcnt(0);
-                    asm volatile("" ::: "memory");
-                    if (lane == 0)
-                        __hip_atomic_store(myflag[bi], publish[bi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    publish[bi] = 0;
-                }
                 // collect the quarter [t-4, t); after the fourth quarter store the group
                 const int us = t - kCBlk;
                 const int i = ((us - gph[bi]) >> 2) & 3;
@@ -454,6 +474,7 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                         }
                     }
                     publish[bi] = t;                    // = U + 16: everything below it has now been issued
+                    pubat[bi] = t + kCPubLag;
                 }
             }
         }
