@@ -621,7 +621,7 @@ __global__ __launch_bounds__(256) void k_bwd_wave(const float *__restrict__ x, c
     float *sred = smem;                        // [4*64][NS*4], reuses the tiles after the products
     const int n = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
-    if (SPLIT) {
+    if constexpr (SPLIT) {
         // all waves stage x before the solve: eight loads in flight per thread, addresses clamped (no
         // branch around a load), halo zeroed when written; 16 bytes per load when the halo is four
         // columns and the rows are 16-byte aligned
@@ -845,7 +845,7 @@ static int launch_wave_bands_ck(int dir, const float *in, const float *w, float 
 // stage x meanwhile, which the split has to do before it starts (measured at k = 3: 2.6 us slower).
 static bool wave_split_pays(int k) { return k >= 5; }
 
-bool wave_split_preferred(int B, int H, int W, int k) { return (k >= 5 || H + W >= 48) && B <= 512; }
+bool wave_split_preferred(int B, int H, int W, int k) { return k >= 3 && (k >= 5 || H + W >= 48) && B <= 512; }
 
 size_t bwd_wave_lds_bytes(int C, int H, int W, int k)
 {
@@ -874,7 +874,7 @@ static int launch_bwd_wave_ck(const float *x, const float *w, const float *g, fl
 
 bool bwd_wave_supported(int C, int H, int W, int k)
 {
-    return wave_supported(C, H, k) && bwd_wave_lds_bytes(C, H, W, k) <= kMaxLdsBytes;
+    return wave_supported(C, H, k) && k <= 7 && bwd_wave_lds_bytes(C, H, W, k) <= kMaxLdsBytes;
 }
 
 // dL/dy and the per-image partial sums of dL/dw (part[B][C*C*k*k], un-negated) in one launch.
@@ -884,16 +884,22 @@ int launch_bwd_wave(const float *x, const float *w, const float *g, float *v, fl
     if (!bwd_wave_supported(C, H, W, k))
         return INVCONV_ERR_VARIANT;
     if (C == 3 && k == 3) return launch_bwd_wave_ck<3, 3>(x, w, g, v, part, B, H, W, stream);
+    if (C == 3 && k == 2) return launch_bwd_wave_ck<3, 2>(x, w, g, v, part, B, H, W, stream);
     if (C == 3 && k == 5) return launch_bwd_wave_ck<3, 5>(x, w, g, v, part, B, H, W, stream);
+    if (C == 3 && k == 7) return launch_bwd_wave_ck<3, 7>(x, w, g, v, part, B, H, W, stream);
     if (C == 1 && k == 3) return launch_bwd_wave_ck<1, 3>(x, w, g, v, part, B, H, W, stream);
     if (C == 2 && k == 3) return launch_bwd_wave_ck<2, 3>(x, w, g, v, part, B, H, W, stream);
     if (C == 4 && k == 3) return launch_bwd_wave_ck<4, 3>(x, w, g, v, part, B, H, W, stream);
     return INVCONV_ERR_VARIANT;
 }
 
+// Kernel sizes of the paper's kernel-size ablation (2, 3, 5, 7, 9, 11) for three channels.  Registers hold
+// every folded tap, so the larger kernels exist for the solve only: the fused backward kernel stops at
+// k = 7 and the banded one at k = 5 (beyond that they would spill to scratch memory).
 static bool wave_ck(int C, int k)
 {
-    return (C == 3 && (k == 3 || k == 5)) || (C == 1 && k == 3) || (C == 2 && k == 3) || (C == 4 && k == 3);
+    return (C == 3 && (k == 2 || k == 3 || k == 5 || k == 7 || k == 9 || k == 11)) || (C == 1 && k == 3) ||
+           (C == 2 && k == 3) || (C == 4 && k == 3);
 }
 
 bool wave_supported(int C, int H, int k) { return H <= 64 && wave_ck(C, k); }
@@ -901,7 +907,7 @@ bool wave_supported(int C, int H, int k) { return H <= 64 && wave_ck(C, k); }
 // 65 .. 512 rows, bands of 64 rows; the message log of the band boundaries has to fit LDS
 bool wave_bands_supported(int C, int H, int W, int k)
 {
-    return H > 64 && H <= 512 && wave_ck(C, k) && wave_bands_lds_bytes(H, W, k) <= 128 * 1024;
+    return H > 64 && H <= 512 && wave_ck(C, k) && k <= 5 && wave_bands_lds_bytes(H, W, k) <= 128 * 1024;
 }
 
 template <int C, int K>
@@ -923,6 +929,9 @@ int launch_solve_wave_split(int dir, const float *in, const float *w, float *out
         return INVCONV_ERR_VARIANT;
     if (C == 3 && k == 3) return launch_wave_split_ck<3, 3>(dir, in, w, out, B, H, W, stream);
     if (C == 3 && k == 5) return launch_wave_split_ck<3, 5>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 7) return launch_wave_split_ck<3, 7>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 9) return launch_wave_split_ck<3, 9>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 11) return launch_wave_split_ck<3, 11>(dir, in, w, out, B, H, W, stream);
     if (C == 1 && k == 3) return launch_wave_split_ck<1, 3>(dir, in, w, out, B, H, W, stream);
     if (C == 2 && k == 3) return launch_wave_split_ck<2, 3>(dir, in, w, out, B, H, W, stream);
     if (C == 4 && k == 3) return launch_wave_split_ck<4, 3>(dir, in, w, out, B, H, W, stream);
@@ -935,6 +944,7 @@ int launch_solve_wave_bands(int dir, const float *in, const float *w, float *out
     if (!wave_bands_supported(C, H, W, k))
         return INVCONV_ERR_VARIANT;
     if (C == 3 && k == 3) return launch_wave_bands_ck<3, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 2) return launch_wave_bands_ck<3, 2>(dir, in, w, out, B, H, W, stream);
     if (C == 3 && k == 5) return launch_wave_bands_ck<3, 5>(dir, in, w, out, B, H, W, stream);
     if (C == 1 && k == 3) return launch_wave_bands_ck<1, 3>(dir, in, w, out, B, H, W, stream);
     if (C == 2 && k == 3) return launch_wave_bands_ck<2, 3>(dir, in, w, out, B, H, W, stream);
@@ -948,7 +958,11 @@ int launch_solve_wave(int dir, const float *in, const float *w, float *out, int 
     if (!wave_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
     if (C == 3 && k == 3) return launch_wave_ck<3, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 2) return launch_wave_ck<3, 2>(dir, in, w, out, B, H, W, stream);
     if (C == 3 && k == 5) return launch_wave_ck<3, 5>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 7) return launch_wave_ck<3, 7>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 9) return launch_wave_ck<3, 9>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 11) return launch_wave_ck<3, 11>(dir, in, w, out, B, H, W, stream);
     if (C == 1 && k == 3) return launch_wave_ck<1, 3>(dir, in, w, out, B, H, W, stream);
     if (C == 2 && k == 3) return launch_wave_ck<2, 3>(dir, in, w, out, B, H, W, stream);
     if (C == 4 && k == 3) return launch_wave_ck<4, 3>(dir, in, w, out, B, H, W, stream);

@@ -96,6 +96,25 @@ def test_wave_split_variant_edge_shapes(shape):
     check_layer(cs["y"], cs["w"][0], cs["g"], b.VARIANT_WAVE_SPLIT)
 
 
+LARGE_K_SHAPES = [  # (B, C, H, W, k): the kernel sizes of the paper's kernel-size ablation, three channels
+    (2, 3, 32, 32, 2), (2, 3, 32, 32, 7), (2, 3, 28, 28, 9), (1, 3, 32, 32, 11), (2, 3, 64, 40, 7), (2, 3, 20, 9, 11),
+    (1, 3, 5, 50, 9), (3, 3, 64, 64, 11), (1, 3, 100, 20, 7), (2, 3, 7, 7, 2),
+]
+
+
+@pytest.mark.parametrize("shape", LARGE_K_SHAPES)
+@pytest.mark.parametrize("variant", [b.VARIANT_AUTO, b.VARIANT_WAVE, b.VARIANT_WAVE_SPLIT])
+def test_kernel_size_ablation_shapes(shape, variant):
+    B, C, H, W, k = shape
+    if variant == b.VARIANT_WAVE_SPLIT and (k < 3 or H > 64):
+        pytest.skip("the four-wave split needs k >= 3 and at most 64 rows")
+    if variant == b.VARIANT_WAVE and H > 64 and k > 5:
+        pytest.skip("bands of 64 rows exist up to k = 5")
+    print(f"kernel size {shape} variant {variant}", flush=True)
+    cs = inputs.make_case(B, C, H, W, k, seed=sum(shape) + 2, tap_std=0.15 / k)
+    check_layer(cs["y"], cs["w"][0], cs["g"], variant)
+
+
 def test_masked_entries_are_ignored_and_get_zero_gradient():
     cs = inputs.make_case(2, 4, 9, 8, 3, seed=3)
     y, w, g = cs["y"], cs["w"][0].copy(), cs["g"]
