@@ -10,6 +10,10 @@
 // columns >= C*k*k are padding: they read valid data and are never written out.
 // The four waves take pixel groups round robin and are added in wave order
 // through LDS; the un-negated partial sums go to part[workgroup][P].
+// A workgroup takes a contiguous range of row chunks.  In the streaming mode (16-byte aligned rows,
+// RT >= k-1) it reads every element of x and v once: the halo rows of a chunk are the last rows of
+// the chunk before, kept in registers, and the next chunk is fetched into registers while the
+// matrix cores work on the current one.
 // Pass 2 (k_dw_reduce in the generic file) adds the rows of `part` in a fixed order.
 #include "invconv_common.h"
 #include "invconv_launch.h"
@@ -26,6 +30,7 @@ struct DwBatch {
 
 constexpr int kDwHalo = 4;      // left halo of the x tile, in columns (>= k-1, keeps rows 16-byte aligned)
 constexpr int kDwUnroll = 4;    // pixel quads per trip of the product loop
+constexpr int kDwPre = 6;       // streaming mode: 16-byte pieces of each tile a thread holds in registers
 
 template <int NS>
 __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *__restrict__ part, int B, int C,
@@ -60,12 +65,64 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
     for (int s = 0; s < NS; ++s)
         acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int chunk = cg; chunk < nchunks; chunk += G) {
+    const int cpw = (nchunks + G - 1) / G;          // chunks cg*cpw .. of image n, contiguous
+    const int c_begin = cg * cpw, c_end = (c_begin + cpw < nchunks) ? c_begin + cpw : nchunks;
+    const size_t img = (size_t)n * C * H * W;
+
+    // streaming mode: this thread's pieces of a chunk (loop invariant): piece i is float4 c4 of row r of channel ch
+    float4 pv[kDwPre], px[kDwPre], ph[kDwPre];
+    int p_go[kDwPre], p_vl[kDwPre], p_xl[kDwPre], p_r[kDwPre];
+    if (vec == 2) {
+        const int W4 = W / 4;
+#pragma unroll
+        for (int i = 0; i < kDwPre; ++i) {
+            const int idx = tid + 256 * i;
+            const bool ok = idx < C * RT * W4;
+            const int c4 = idx % W4, rr = idx / W4;
+            const int ch = ok ? rr / RT : 0, r = ok ? rr - ch * RT : 0;
+            p_r[i] = ok ? r : -1;
+            p_go[i] = (ch * H + r) * W + 4 * c4;
+            p_vl[i] = ch * SVC + r * W + 4 * c4;
+            p_xl[i] = ch * SXC + (r + k - 1) * XW + 4 * (c4 + 1);
+            pv[i] = px[i] = ph[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        // the halo columns stay zero for the whole launch
+        for (int idx = tid; idx < C * (RT + k - 1); idx += 256) {
+            const int ch = idx / (RT + k - 1), r = idx - ch * (RT + k - 1);
+            *reinterpret_cast<float4 *>(sx + ch * SXC + r * XW) = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        // rows above the first chunk, as if left by a chunk before it; then the first chunk itself
+        const int rb = c_begin * RT;
+#pragma unroll
+        for (int i = 0; i < kDwPre; ++i) {
+            const int r = p_r[i];
+            if (r >= RT - (k - 1) && rb - RT + r >= 0 && c_begin < c_end)
+                ph[i] = *reinterpret_cast<const float4 *>(x + img + p_go[i] + (ptrdiff_t)(rb - RT) * W);
+            if (r >= 0 && rb + r < H && c_begin < c_end) {
+                pv[i] = *reinterpret_cast<const float4 *>(v + img + p_go[i] + (size_t)rb * W);
+                px[i] = *reinterpret_cast<const float4 *>(x + img + p_go[i] + (size_t)rb * W);
+            }
+        }
+    }
+
+    for (int chunk = c_begin; chunk < c_end; ++chunk) {
         const int r0 = chunk * RT;
         const int rows = (H - r0 < RT) ? H - r0 : RT;
         const int xrows = rows + k - 1;
         __syncthreads();        // previous chunk's products are done with the tiles
-        if (vec) {
+        if (vec == 2) {
+#pragma unroll
+            for (int i = 0; i < kDwPre; ++i) {
+                const int r = p_r[i];
+                if (r >= 0) {
+                    *reinterpret_cast<float4 *>(sv + p_vl[i]) = pv[i];
+                    *reinterpret_cast<float4 *>(sx + p_xl[i]) = px[i];
+                    if (r >= RT - (k - 1))      // last rows of the chunk before: rows 0 .. k-2 of the tile
+                        *reinterpret_cast<float4 *>(sx + p_xl[i] - RT * XW) = ph[i];
+                    ph[i] = px[i];
+                }
+            }
+        } else if (vec) {
             const int W4 = W / 4;
             for (int idx = tid; idx < C * rows * W4; idx += 256) {
                 const int c4 = idx % W4, rr = idx / W4;         // rr = ch*rows + r
@@ -98,6 +155,19 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
             }
         }
         __syncthreads();
+        if (vec == 2 && chunk + 1 < c_end) {
+            // the next chunk travels while the matrix cores work on this one
+            const int rn = r0 + RT;
+#pragma unroll
+            for (int i = 0; i < kDwPre; ++i) {
+                const bool in = p_r[i] >= 0 && rn + p_r[i] < H;
+                const size_t go = img + p_go[i] + (size_t)(in ? rn : 0) * W;
+                const float4 a4 = *reinterpret_cast<const float4 *>(v + go);
+                const float4 b4 = *reinterpret_cast<const float4 *>(x + go);
+                pv[i] = a4;
+                px[i] = in ? b4 : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
 
         if (vec) {
             // W is a multiple of 4: a wave takes whole rows, four pixels (lanes kk = 0..3) per instruction and
@@ -250,9 +320,13 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
         p.xw = memo.xw;
         p.sxc = memo.sxc;
     }
-    int g = (1024 + B - 1) / B;                     // about a thousand workgroups per layer at most
+    // Workgroups per image: a workgroup streams through a contiguous range of chunks and re-reads only the
+    // k-1 halo rows at the start of its range, so few long ranges are better than many short ones, as long
+    // as every compute unit gets a workgroup or two per layer.
+    int g = (320 + B - 1) / B;
     if (g > p.nchunks) g = p.nchunks;
     if (g < 1) g = 1;
+    g = (p.nchunks + (p.nchunks + g - 1) / g - 1) / ((p.nchunks + g - 1) / g);      // no empty workgroups
     p.groups = g;
     p.nparts = (size_t)B * g;
     p.lds = lds_with(rt, p.xw, p.sxc);
@@ -269,6 +343,9 @@ static void launch_ns(const DwBatch &batch, int layers, float *part, const DwPla
     for (int l = 0; l < layers; ++l)
         if (((size_t)batch.x[l] | (size_t)batch.v[l]) & 15)
             vec = 0;
+    // streaming mode: the halo rows come from one chunk before, and a thread's share of a tile fits its registers
+    if (vec && p.rt >= k - 1 && C * p.rt * (W / 4) <= 256 * kDwPre)
+        vec = 2;
     hipLaunchKernelGGL(k_dw_partial_mfma<NS>, dim3((unsigned)(p.nparts * layers)), dim3(256), p.lds, stream, batch,
                        part, B, C, H, W, k, p.rt, p.nchunks, p.groups, vec, p.xw, p.sxc, p.svc);
 }
