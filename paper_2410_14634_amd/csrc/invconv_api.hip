@@ -35,8 +35,20 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
                                               : launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream);
         if (wave_bands_supported(C, H, W, k))
             return launch_solve_wave_bands(dir, in, w, out, B, C, H, W, k, stream);
-        if (band_supported(C, H, k))
+        if (band_supported(C, H, k)) {
+            if (chain_supported(1, C, H, W, k) && chain_single_preferred(B, C, H)) {
+                ChainArgs a{};          // the pipelined kernel with one stage: no counters, no workspace
+                a.in0 = in;
+                a.w[0] = w;
+                a.out[0] = out;
+                a.stages = 1;
+                a.B = B;
+                a.H = H;
+                a.W = W;
+                return launch_chain(dir, a, C, k, stream);
+            }
             return launch_solve_band(dir, in, w, out, B, C, H, W, k, stream);
+        }
         return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_BLOCK:
         return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);

@@ -513,6 +513,18 @@ bool chain_supported(int stages, int C, int H, int W, int k)
            chain_lds_bytes(C, k, (H + 15) / 16) <= kMaxLdsBytes;
 }
 
+// One layer: the band kernel (one wave per band, every lane walking its own row four bytes at a time)
+// keeps B*H*C*2 cache lines of 128 bytes live; beyond about 2 MB per XCD (an eighth of them on each)
+// its lines are evicted between two touches and it collapses (B = 256, 12 x 128 x 128: 1.3 ms against
+// 0.3 ms), while this kernel moves whole 64-byte pieces and does not care.  Below that the band kernel
+// wins on small images (this kernel runs 38 steps more), this one on tall ones (measured: 253 against
+// 293 us at B = 32, 12 x 128 x 128).
+bool chain_single_preferred(int B, int C, int H)
+{
+    const double live_per_xcd = (double)B * H * C * 256.0 / 8.0;
+    return live_per_xcd > 2.0e6 || (H > 80 && B >= 24);
+}
+
 size_t chain_flag_ints(int stages, int B) { return (size_t)stages * B * kCFlags + 64; }
 
 template <int CG, int K>

@@ -74,6 +74,7 @@ struct ChainArgs {
     int stages, B, H, W, NB;
 };
 bool chain_supported(int stages, int C, int H, int W, int k);
+bool chain_single_preferred(int B, int C, int H);
 size_t chain_flag_ints(int stages, int B);
 int launch_chain(int dir, ChainArgs args, int C, int k, hipStream_t stream);
 // y = M x (dir 0) or y = M^T x (dir 1) for the masked causal convolution M
