@@ -52,10 +52,10 @@ enum {
     INVCONV_VARIANT_AUTO = 0,
     INVCONV_VARIANT_BLOCK = 1,    /* one workgroup per image, LDS window, one barrier per anti-diagonal */
     INVCONV_VARIANT_DIAG_LAUNCH = 2, /* one kernel launch per anti-diagonal (capture it in a hipGraph) */
-    INVCONV_VARIANT_WAVE = 3,     /* one wave per 64 image rows, lane = row, register/DPP systolic solve (C <= 4, H <= 512; bands of one image hand over through LDS) */
+    INVCONV_VARIANT_WAVE = 3,     /* one wave per 64 image rows, lane = row, register/DPP systolic solve (C <= 4 with k = 3, C = 3 also k = 2, 5, 7, 9, 11; H <= 512, k <= 5 beyond 64 rows; bands of one image hand over through LDS) */
     INVCONV_VARIANT_BAND = 4,     /* one wave per 16-row band, 16x16x4 MFMA systolic solve (C = 8, 12, 16; k = 3; H <= 128) */
     INVCONV_VARIANT_PERSISTENT = 5, /* one cooperative launch, persistent grid, device-wide barrier per anti-diagonal */
-    INVCONV_VARIANT_WAVE_SPLIT = 6 /* the wave solve with a step's matrix instructions split over four waves by the age of their input (C <= 4, H <= 64) */
+    INVCONV_VARIANT_WAVE_SPLIT = 6 /* the wave solve with a step's matrix instructions split over four waves by the age of their input (same shapes, k >= 3, H <= 64) */
 };
 
 /*
@@ -131,7 +131,7 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
  * `w` and `x` are HOST arrays of L device pointers (read during the call only); every x[l] is a
  * distinct B*C*H*W buffer (all are kept: the backward pass needs them).  Results are those of L
  * calls of invconv_fwd; where the shape allows it the layers run as one pipelined launch in which
- * layer l+1 trails layer l by a few anti-diagonals.  L in 1..16.
+ * layer l+1 trails layer l by a few dozen anti-diagonals.  L in 1..16.
  *   workspace: at least invconv_chain_workspace_bytes() bytes of device memory, 256-byte aligned.
  */
 invconv_status invconv_chain_fwd(const float *y, const float *const *w, float *const *x, int L,
