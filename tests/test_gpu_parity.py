@@ -191,7 +191,7 @@ def test_chain_workload_parity():
 
 CHAIN_SHAPES = [  # (L, B, C, H, W, k)
     (1, 2, 12, 16, 16, 3), (3, 2, 12, 16, 20, 3), (2, 3, 12, 40, 9, 3), (4, 1, 8, 33, 31, 3),
-    (2, 2, 16, 128, 12, 3), (3, 2, 12, 7, 5, 3),
+    (2, 2, 16, 128, 12, 3), (3, 2, 12, 7, 5, 3), (2, 2, 12, 20, 3, 3), (2, 2, 16, 64, 16, 3), (3, 1, 8, 128, 4, 3),
     (2, 2, 3, 10, 10, 3),          # not covered by the pipelined kernel: falls back to per-layer launches
 ]
 
