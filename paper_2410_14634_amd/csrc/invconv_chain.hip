@@ -94,6 +94,9 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
 {
     constexpr int C = 4 * CG;
     constexpr int kCIoBands = chain_io_bands(C);     // bands per loader / storer wave
+    // Mirrored direction: the four slots of a quarter hold their steps in descending order, which is the
+    // ascending memory order, so that loaders and storers move a lane's 16 bytes without reordering them.
+    constexpr int kSlotFlip = DIR ? 3 : 0;
     extern __shared__ float smem[];
     const int H = a.H, W = a.W, NB = a.NB;
     const int stage = blockIdx.x / a.B, n_img = blockIdx.x % a.B;
@@ -180,7 +183,7 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                 float yv[CG];
 #pragma unroll
                 for (int jj = 0; jj < CG; ++jj)
-                    yv[jj] = ring[cbase[jj] + ((t + 1 - band) & (kCRing - 1))];
+                    yv[jj] = ring[cbase[jj] + (((t + 1 - band) & (kCRing - 1)) ^ kSlotFlip)];
                 const float *mi = msg_in + ((t - 1 - kCDelay) & (kCMsg - 1)) * K * 64;
                 float mrow[K][CG];
 #pragma unroll
@@ -228,7 +231,7 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                 // result replaces the input in the ring slot of this step (the storers skip invalid pixels)
 #pragma unroll
                 for (int j = 0; j < CG; ++j)
-                    ring[cbase[j] + ((t - band) & (kCRing - 1))] = xn[j];
+                    ring[cbase[j] + (((t - band) & (kCRing - 1)) ^ kSlotFlip)] = xn[j];
 #pragma unroll
                 for (int aa = 1; aa < K; ++aa) {
                     f32x4 acc = accT[aa];
@@ -318,34 +321,27 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                     const int i = ((uw - gph[bi]) >> 2) & 3;        // its position in the group held in registers
                     if (have[bi] && jq == i) {
                         float *dst = ring + ((b * C) * 16 + nrow) * kCRow + ((uw - b) & (kCRing - 1));
-                        // lr holds memory order: column cv + m is component m, mirrored 3 - m
+                        // lr holds memory order, which is also the slot order of the quarter
                         if (!edge[bi]) {
 #pragma unroll
                             for (int ch = 0; ch < C; ++ch) {
                                 const f32x4 v = lr[bi][ch];
-                                float *d = dst + ch * 16 * kCRow;
-                                if (DIR) {
-                                    d[0] = v[3];
-                                    d[1] = v[2];
-                                    d[2] = v[1];
-                                    d[3] = v[0];
-                                } else {
-                                    float2 *d2 = reinterpret_cast<float2 *>(d);
-                                    d2[0] = float2{v[0], v[1]};
-                                    d2[1] = float2{v[2], v[3]};
-                                }
+                                float2 *d2 = reinterpret_cast<float2 *>(dst + ch * 16 * kCRow);
+                                d2[0] = float2{v[0], v[1]};
+                                d2[1] = float2{v[2], v[3]};
                             }
                         } else {
                             // a group that reaches over an end of the row: the lane's four columns were
                             // fetched from the nearest position inside the row, dsh columns away, so
-                            // component m belongs to slot m - dsh of the quarter, if that is one of its four
-                            float *de = dst - dsh[bi];
+                            // component m belongs dsh slots further (mirrored) or back, if that is in the quarter
+                            const int sh = DIR ? dsh[bi] : -dsh[bi];
+                            float *de = dst + sh;
 #pragma unroll
                             for (int m = 0; m < 4; ++m) {
-                                if ((unsigned)(m - dsh[bi]) < 4u) {
+                                if ((unsigned)(m + sh) < 4u) {
 #pragma unroll
                                     for (int ch = 0; ch < C; ++ch)
-                                        de[ch * 16 * kCRow + m] = lr[bi][ch][DIR ? 3 - m : m];
+                                        de[ch * 16 * kCRow + m] = lr[bi][ch][m];
                                 }
                             }
                         }
@@ -432,15 +428,10 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                     const float *src = ring + ((b * C) * 16 + nrow) * kCRow + ((us - b) & (kCRing - 1));
 #pragma unroll
                     for (int ch = 0; ch < C; ++ch) {
-                        // kept in memory order (mirrored: columns descending), so that the store needs no shuffle
-                        const float *sc = src + ch * 16 * kCRow;
-                        if (DIR) {
-                            sr[bi][ch] = f32x4{sc[3], sc[2], sc[1], sc[0]};
-                        } else {
-                            const float2 *s2 = reinterpret_cast<const float2 *>(sc);
-                            const float2 lo = s2[0], hi = s2[1];
-                            sr[bi][ch] = f32x4{lo.x, lo.y, hi.x, hi.y};
-                        }
+                        // memory order (mirrored: columns descending) = slot order: the store needs no shuffle
+                        const float2 *s2 = reinterpret_cast<const float2 *>(src + ch * 16 * kCRow);
+                        const float2 lo = s2[0], hi = s2[1];
+                        sr[bi][ch] = f32x4{lo.x, lo.y, hi.x, hi.y};
                     }
                 }
                 if (i == 3) {
