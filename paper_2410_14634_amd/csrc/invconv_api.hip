@@ -331,7 +331,7 @@ invconv_status invconv_chain_bwd(const float *const *x, const float *const *w, c
     const DwPlan p = plan_dw_any(B, C, H, W, k);
     const bool mfma = dw_mfma_supported(C, k) && plan_dw_mfma(B, C, H, W, k).rt;
     if (mfma)
-        return launch_dw_mfma_layers(x, v, dLdw, L, part, p, B, C, H, W, k, st);
+        return launch_dw_mfma_layers(x, v, dLdw, L, part, plan_dw_mfma_layers(L, B, C, H, W, k), B, C, H, W, k, st);
     for (int l = 0; l < L; ++l) {
         if (int s = launch_dw(x[l], v[l], dLdw[l], part, p, B, C, H, W, k, st))
             return s;

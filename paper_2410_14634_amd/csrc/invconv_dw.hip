@@ -334,6 +334,24 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
     return p;
 }
 
+// The same plan for one launch over `layers` layers: fewer, longer chunk ranges per image, about two
+// workgroups per compute unit in all (a workgroup's set-up and its final reduction cost about as much as
+// two chunks).  Never more partial rows than plan_dw_mfma's, so the same workspace serves.
+DwPlan plan_dw_mfma_layers(int layers, int B, int C, int H, int W, int k)
+{
+    DwPlan p = plan_dw_mfma(B, C, H, W, k);
+    if (!p.rt || layers <= 1)
+        return p;
+    const long per_round = 512;
+    int g = (int)((per_round + (long)B * layers - 1) / ((long)B * layers));
+    if (g > p.groups) g = p.groups;
+    if (g < 1) g = 1;
+    g = (p.nchunks + (p.nchunks + g - 1) / g - 1) / ((p.nchunks + g - 1) / g);      // no empty workgroups
+    p.groups = g;
+    p.nparts = (size_t)B * g;
+    return p;
+}
+
 template <int NS>
 static void launch_ns(const DwBatch &batch, int layers, float *part, const DwPlan &p, int B, int C, int H, int W,
                       int k, hipStream_t stream)

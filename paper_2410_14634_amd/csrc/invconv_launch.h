@@ -54,6 +54,7 @@ int launch_dw(const float *x, const float *v, float *dw, float *part, const DwPl
               int W, int k, hipStream_t stream, float sign = -1.0f);
 bool dw_mfma_supported(int C, int k);
 DwPlan plan_dw_mfma(int B, int C, int H, int W, int k);
+DwPlan plan_dw_mfma_layers(int layers, int B, int C, int H, int W, int k);
 int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
                    int W, int k, hipStream_t stream, float sign = -1.0f);
 int launch_dw_mfma_layers(const float *const *x, const float *const *v, float *const *dw, int layers, float *part,
