@@ -31,6 +31,7 @@ struct DwBatch {
 constexpr int kDwHalo = 4;      // left halo of the x tile, in columns (>= k-1, keeps rows 16-byte aligned)
 constexpr int kDwUnroll = 4;    // pixel quads per trip of the product loop
 constexpr int kDwPre = 6;       // streaming mode: 16-byte pieces of each tile a thread holds in registers
+constexpr size_t kDwStreamLdsBudget = 72 * 1024;   // streaming mode: two workgroups per compute unit
 
 template <int NS>
 __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *__restrict__ part, int B, int C,
@@ -262,10 +263,15 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
         return sizeof(float) * (tiles > red ? tiles : red);
     };
     auto lds_for = [&](int rt) { return lds_with(rt, W + kDwHalo, (rt + k - 1) * (W + kDwHalo)); };
-    if (lds_for(1) > kDwLdsBudget)
+    // Rows of 16-byte pieces take the streaming mode (if the pointers are aligned too): registers limit it
+    // to two workgroups per compute unit, so its tiles may be larger, as long as a thread's share of a
+    // tile still fits its kDwPre registers.
+    const bool stream_shape = (W % 4) == 0;
+    const size_t budget = stream_shape ? kDwStreamLdsBudget : kDwLdsBudget;
+    if (lds_for(1) > budget)
         return p;
     int rt = H < 8 ? H : 8;
-    while (rt > 1 && lds_for(rt) > kDwLdsBudget)
+    while (rt > 1 && (lds_for(rt) > budget || (stream_shape && rt > k - 1 && C * rt * (W / 4) > 256 * kDwPre)))
         --rt;
     p.rt = rt;
     p.nchunks = (H + rt - 1) / rt;
@@ -306,7 +312,7 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
             for (int rp = 0; rp <= 12; rp += 4)
                 for (int cp = 0; cp <= 60; cp += 4) {
                     const int xw = W + kDwHalo + rp, sxc = (rt + k - 1) * xw + cp;
-                    if (lds_with(rt, xw, sxc) > kDwLdsBudget)       // same number of workgroups per CU as unpadded
+                    if (lds_with(rt, xw, sxc) > budget)             // same number of workgroups per CU as unpadded
                         continue;
                     const int c = cost(xw, sxc);
                     if (c < best) {
@@ -364,6 +370,10 @@ static void launch_ns(const DwBatch &batch, int layers, float *part, const DwPla
     // streaming mode: the halo rows come from one chunk before, and a thread's share of a tile fits its registers
     if (vec && p.rt >= k - 1 && C * p.rt * (W / 4) <= 256 * kDwPre)
         vec = 2;
+    if (p.lds > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_dw_partial_mfma<NS>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds) != hipSuccess)
+        return;     // the launch below then fails and reports it
     hipLaunchKernelGGL(k_dw_partial_mfma<NS>, dim3((unsigned)(p.nparts * layers)), dim3(256), p.lds, stream, batch,
                        part, B, C, H, W, k, p.rt, p.nchunks, p.groups, vec, p.xw, p.sxc, p.svc);
 }
