@@ -117,8 +117,10 @@ __device__ __forceinline__ void wave_fold_regs(const float *__restrict__ w, int 
 struct WaveBands {
     int band;           // this wave's band
     int nbands;
-    f32x4 *log;         // [nbands - 1][log_steps][K - 1]
-    int *prog;          // [nbands - 1] local steps finished by band b
+    const f32x4 *log_in;    // [log_steps][K - 1]: what the band above sent (valid offset also for band 0)
+    f32x4 *log_out;         // [log_steps][K - 1]: what this band sends (valid offset also for the last band)
+    const int *prog_in;     // local steps of the band above whose entries are in log_in
+    int *prog_out;          // local steps of this band whose entries are in log_out
     int log_steps;      // entries per band, a multiple of kWavePF
     f32x4 *scratch;     // [64][K - 1] write-only dump for the lanes that have nothing to send
 };
@@ -227,8 +229,8 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
     const int nsteps = band_rows + W - 1;
     const bool recv = BANDS && wb.band > 0, send = BANDS && wb.band + 1 < wb.nbands;
     // (plain offsets from the LDS base, never a null alternative: the accesses stay LDS instructions)
-    const f32x4 *log_in = wb.log + (recv ? wb.band - 1 : 0) * wb.log_steps * (K - 1);
-    f32x4 *log_out = wb.log + (send ? wb.band : 0) * wb.log_steps * (K - 1);
+    const f32x4 *log_in = wb.log_in;
+    f32x4 *log_out = wb.log_out;
     f32x4 M[K];          // M[a]: what the band above sent for this step (used by lane 0 only)
 #pragma unroll
     for (int a = 0; a < K; ++a)
@@ -239,7 +241,7 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
             int need = t0 + 64 + kWavePF;
             need = need > wb.log_steps ? wb.log_steps : need;
             int spins = 0;
-            while (__hip_atomic_load(wb.prog + wb.band - 1, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < need &&
+            while (__hip_atomic_load(wb.prog_in, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < need &&
                    ++spins < kBandSpinLimit)
                 __builtin_amdgcn_s_sleep(1);
         }
@@ -333,7 +335,7 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
             }
         }
         if (send)       // the block's log entries are written (LDS operations of a wave complete in order)
-            __hip_atomic_store(wb.prog + wb.band, t0 + kWavePF, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_store(wb.prog_out, t0 + kWavePF, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
 }
 
@@ -580,14 +582,129 @@ __global__ __launch_bounds__(512) void k_solve_wave_bands(const float *__restric
     WaveBands wb;
     wb.band = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     wb.nbands = blockDim.x >> 6;
-    wb.log = reinterpret_cast<f32x4 *>(smem);
-    wb.scratch = wb.log + (size_t)(wb.nbands - 1) * log_steps * (K - 1);
-    wb.prog = reinterpret_cast<int *>(wb.scratch + 64 * (K - 1));
+    f32x4 *log = reinterpret_cast<f32x4 *>(smem);        // [nbands - 1][log_steps][K - 1]
+    wb.scratch = log + (size_t)(wb.nbands - 1) * log_steps * (K - 1);
+    int *prog = reinterpret_cast<int *>(wb.scratch + 64 * (K - 1));     // [nbands - 1]
+    // (plain offsets from the LDS base, never a null alternative: the accesses stay LDS instructions)
+    wb.log_in = log + (size_t)(wb.band > 0 ? wb.band - 1 : 0) * log_steps * (K - 1);
+    wb.log_out = log + (size_t)(wb.band + 1 < wb.nbands ? wb.band : 0) * log_steps * (K - 1);
+    wb.prog_in = prog + (wb.band > 0 ? wb.band - 1 : 0);
+    wb.prog_out = prog + (wb.band + 1 < wb.nbands ? wb.band : 0);
     wb.log_steps = log_steps;
     if (threadIdx.x < wb.nbands - 1)
-        wb.prog[threadIdx.x] = 0;
+        prog[threadIdx.x] = 0;
     __syncthreads();
     solve_wave_body<C, K, DIR, false, true>(in, w, out, H, W, blockIdx.x, nullptr, wb);
+}
+
+// The same bands on different compute units: one workgroup per (band, image), two waves each.  Wave 0 is
+// the band's solve exactly as above, with its two logs in the workgroup's own LDS.  Wave 1 carries the
+// logs between workgroups through global memory, a block of kWavePF entries at a time: it sends what its
+// own band has appended (device-coherent stores, then a counter once they are acknowledged - it has no
+// other memory operations in flight, so that wait is exact) and fetches what the band above has published
+// into the local log, then advances the local counter the solve waits on.  A workgroup waits only for the
+// one of the band above, which has a lower block index; every wait is bounded.
+constexpr int kCourierSpinLimit = 1 << 22;
+template <int C, int K, int DIR>
+__global__ __launch_bounds__(128) void k_solve_wave_bands_multi(const float *__restrict__ in,
+                                                               const float *__restrict__ w, float *__restrict__ out,
+                                                               int B, int H, int W, int log_steps, int *gcount,
+                                                               f32x4 *glog)
+{
+    extern __shared__ float smem[];
+    const int nb = (H + 63) >> 6;
+    const int band = blockIdx.x / B, n = blockIdx.x % B;
+    const size_t seg = (size_t)log_steps * (K - 1);
+    f32x4 *log = reinterpret_cast<f32x4 *>(smem);        // [2][log_steps][K - 1]: received, sent
+    f32x4 *scratch = log + 2 * seg;
+    int *prog = reinterpret_cast<int *>(scratch + 64 * (K - 1));        // [2]: received, sent
+    if (threadIdx.x < 2)
+        prog[threadIdx.x] = 0;
+    __syncthreads();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (wave == 0) {
+        WaveBands wb;
+        wb.band = band;
+        wb.nbands = nb;
+        wb.log_in = log;
+        wb.log_out = log + seg;
+        wb.prog_in = prog;
+        wb.prog_out = prog + 1;
+        wb.log_steps = log_steps;
+        wb.scratch = scratch;
+        solve_wave_body<C, K, DIR, false, true>(in, w, out, H, W, n, nullptr, wb);
+        return;
+    }
+    // ---- courier
+    const int lane = threadIdx.x & 63;
+    const int per_blk = kWavePF * (K - 1);               // 16-byte entries per block (at most 64: K <= 5)
+    const int send_total = band + 1 < nb ? log_steps : 0, recv_total = band > 0 ? log_steps : 0;
+    int *cnt_out = gcount + (size_t)n * (nb - 1) + (band + 1 < nb ? band : 0);
+    const int *cnt_in = gcount + (size_t)n * (nb - 1) + (band > 0 ? band - 1 : 0);
+    f32x4 *g_out = glog + ((size_t)n * (nb - 1) + (band + 1 < nb ? band : 0)) * seg;
+    const f32x4 *g_in = glog + ((size_t)n * (nb - 1) + (band > 0 ? band - 1 : 0)) * seg;
+    const unsigned seg_bytes = (unsigned)(seg * sizeof(f32x4));
+    const __amdgpu_buffer_rsrc_t r_out =
+        __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(g_out), 0, (int)seg_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_in = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(reinterpret_cast<const void *>(g_in)), 0, (int)seg_bytes, 0x00020000);
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    int sent = 0, got = 0, spins = 0;
+    while ((sent < send_total || got < recv_total) && spins < kCourierSpinLimit) {
+        bool moved = false;
+        if (sent < send_total) {
+            int have = __hip_atomic_load(prog + 1, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            have = have < send_total ? have : send_total;
+            if (sent < have) {
+                while (sent < have) {
+                    if (lane < per_blk) {
+                        const f32x4 e = log[seg + (size_t)sent * (K - 1) + lane];
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, e), r_out,
+                                                               (sent * (K - 1) + lane) * 16, 0, 16 /* sc1 */);
+                    }
+                    sent += kWavePF;
+                }
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0);          // every store above is acknowledged
+                asm volatile("" ::: "memory");
+                if (lane == 0)
+                    __hip_atomic_store(cnt_out, sent, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                moved = true;
+            }
+        }
+        if (got < recv_total) {
+            int avail = __hip_atomic_load(cnt_in, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            avail = avail < recv_total ? avail : recv_total;
+            asm volatile("" ::: "memory");              // the loads below are issued after the counter was read
+            if (got < avail) {
+                while (got < avail) {
+                    if (lane < per_blk) {
+                        const u32x4 e = __builtin_amdgcn_raw_buffer_load_b128(r_in, (got * (K - 1) + lane) * 16, 0,
+                                                                              16 /* sc1 */);
+                        log[(size_t)got * (K - 1) + lane] = __builtin_bit_cast(f32x4, e);
+                    }
+                    got += kWavePF;
+                }
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0);          // the entries are in LDS
+                asm volatile("" ::: "memory");
+                if (lane == 0)
+                    __hip_atomic_store(prog, got, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+                moved = true;
+            }
+        }
+        if (!moved) {
+            __builtin_amdgcn_s_sleep(2);
+            ++spins;
+        }
+    }
+}
+
+__global__ void k_wave_bands_clear(int *gcount, int count)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count)
+        gcount[i] = 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -823,6 +940,8 @@ static int launch_wave_bands_ck(int dir, const float *in, const float *w, float 
 {
     const int nb = (H + 63) / 64, log_steps = wave_bands_log_steps(W);
     const size_t lds = wave_bands_lds_bytes(H, W, K);
+    if (lds > 128 * 1024)       // reached only as the fall-back of the multi-workgroup launch
+        return launch_solve_block(dir, in, w, out, B, C, H, W, K, stream);
     const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave_bands<C, K, 1>)
                          : reinterpret_cast<const void *>(&k_solve_wave_bands<C, K, 0>);
     if (lds > 48 * 1024 && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
@@ -836,6 +955,77 @@ static int launch_wave_bands_ck(int dir, const float *in, const float *w, float 
         hipLaunchKernelGGL((k_solve_wave_bands<C, K, 0>), dim3(B), dim3(64 * nb), lds, stream, in, w, out, H, W,
                            log_steps);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+// Bands on different compute units (k_solve_wave_bands_multi).  The logs between workgroups live in
+// device memory that this launch takes from, and returns to, the stream's memory pool (no call
+// synchronises); a stream that is being captured, or a pool that refuses, gets the one-workgroup kernel.
+template <int C, int K>
+static int launch_wave_bands_multi_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
+                                      hipStream_t stream)
+{
+    const int nb = (H + 63) / 64, log_steps = wave_bands_log_steps(W);
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
+        (void)hipGetLastError();
+        return launch_wave_bands_ck<C, K>(dir, in, w, out, B, H, W, stream);
+    }
+    const size_t seg = (size_t)log_steps * (K - 1);
+    const size_t ncnt = (size_t)B * (nb - 1);
+    const size_t cnt_bytes = (ncnt * sizeof(int) + 255) / 256 * 256;
+    const size_t bytes = cnt_bytes + ncnt * seg * sizeof(f32x4);
+    void *scratch = nullptr;
+    if (hipMallocAsync(&scratch, bytes, stream) != hipSuccess || !scratch) {
+        (void)hipGetLastError();
+        return launch_wave_bands_ck<C, K>(dir, in, w, out, B, H, W, stream);
+    }
+    int *gcount = static_cast<int *>(scratch);
+    f32x4 *glog = reinterpret_cast<f32x4 *>(static_cast<char *>(scratch) + cnt_bytes);
+    const size_t lds = (2 * seg + 64 * (K - 1)) * sizeof(f32x4) + 2 * sizeof(int);
+    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave_bands_multi<C, K, 1>)
+                         : reinterpret_cast<const void *>(&k_solve_wave_bands_multi<C, K, 0>);
+    int status = INVCONV_OK;
+    if (lds > 48 * 1024 && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+        (void)hipGetLastError();
+        status = INVCONV_ERR_UNSUPPORTED;
+    } else {
+        hipLaunchKernelGGL(k_wave_bands_clear, dim3((unsigned)((ncnt + 255) / 256)), dim3(256), 0, stream, gcount,
+                           (int)ncnt);
+        const dim3 grid((unsigned)(B * nb));       // band-major: a band's workgroups come after those it waits for
+        if (dir)
+            hipLaunchKernelGGL((k_solve_wave_bands_multi<C, K, 1>), grid, dim3(128), lds, stream, in, w, out, B, H, W,
+                               log_steps, gcount, glog);
+        else
+            hipLaunchKernelGGL((k_solve_wave_bands_multi<C, K, 0>), grid, dim3(128), lds, stream, in, w, out, B, H, W,
+                               log_steps, gcount, glog);
+        status = hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+    }
+    if (hipFreeAsync(scratch, stream) != hipSuccess) {
+        (void)hipGetLastError();
+        status = status == INVCONV_OK ? INVCONV_ERR_LAUNCH : status;
+    }
+    return status;
+}
+
+// Several compute units per image pay while there are compute units to spare and an image has at least
+// three bands of some width: the bands of an image are then limited by the address unit of the one compute
+// unit they share (0.49 us per step at 3x256x256 against 0.31 us here), while the hand-over through global
+// memory makes a band trail the one above by about 105 steps instead of 80 (measured, 3x256x256 forward:
+// B = 1 275 -> 198 us, B = 128 400 -> 339 us; two bands or narrow images are faster in one workgroup).
+// Images whose logs do not fit one workgroup's LDS (3x512x512) have only this way.
+static size_t wave_bands_multi_lds_bytes(int W, int k)
+{
+    return (2 * (size_t)wave_bands_log_steps(W) + 64) * (k - 1) * sizeof(f32x4) + 2 * sizeof(int);
+}
+static bool wave_bands_single_fits(int H, int W, int k) { return wave_bands_lds_bytes(H, W, k) <= 128 * 1024; }
+static bool wave_bands_multi_preferred(int B, int H, int W, int k)
+{
+    if (wave_bands_multi_lds_bytes(W, k) > kMaxLdsBytes)
+        return false;
+    if (!wave_bands_single_fits(H, W, k))
+        return true;
+    const int nb = (H + 63) / 64;
+    return nb >= 3 && W >= 128 && (long)B * nb <= 512;
 }
 
 // The four-wave split of the solve costs about a microsecond more before its first step and saves
@@ -907,7 +1097,9 @@ bool wave_supported(int C, int H, int k) { return H <= 64 && wave_ck(C, k); }
 // 65 .. 512 rows, bands of 64 rows; the message log of the band boundaries has to fit LDS
 bool wave_bands_supported(int C, int H, int W, int k)
 {
-    return H > 64 && H <= 512 && wave_ck(C, k) && k <= 5 && wave_bands_lds_bytes(H, W, k) <= 128 * 1024;
+    return H > 64 && H <= 512 && wave_ck(C, k) && k <= 5 &&
+           (wave_bands_lds_bytes(H, W, k) <= 128 * 1024 ||
+            (2 * (size_t)wave_bands_log_steps(W) + 64) * (k - 1) * sizeof(f32x4) + 2 * sizeof(int) <= kMaxLdsBytes);
 }
 
 template <int C, int K>
@@ -943,12 +1135,19 @@ int launch_solve_wave_bands(int dir, const float *in, const float *w, float *out
 {
     if (!wave_bands_supported(C, H, W, k))
         return INVCONV_ERR_VARIANT;
-    if (C == 3 && k == 3) return launch_wave_bands_ck<3, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 2) return launch_wave_bands_ck<3, 2>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 5) return launch_wave_bands_ck<3, 5>(dir, in, w, out, B, H, W, stream);
-    if (C == 1 && k == 3) return launch_wave_bands_ck<1, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 2 && k == 3) return launch_wave_bands_ck<2, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 4 && k == 3) return launch_wave_bands_ck<4, 3>(dir, in, w, out, B, H, W, stream);
+    const bool multi = wave_bands_multi_preferred(B, H, W, k);
+    if (C == 3 && k == 3) return multi ? launch_wave_bands_multi_ck<3, 3>(dir, in, w, out, B, H, W, stream)
+                                  : launch_wave_bands_ck<3, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 2) return multi ? launch_wave_bands_multi_ck<3, 2>(dir, in, w, out, B, H, W, stream)
+                                  : launch_wave_bands_ck<3, 2>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 5) return multi ? launch_wave_bands_multi_ck<3, 5>(dir, in, w, out, B, H, W, stream)
+                                  : launch_wave_bands_ck<3, 5>(dir, in, w, out, B, H, W, stream);
+    if (C == 1 && k == 3) return multi ? launch_wave_bands_multi_ck<1, 3>(dir, in, w, out, B, H, W, stream)
+                                  : launch_wave_bands_ck<1, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 2 && k == 3) return multi ? launch_wave_bands_multi_ck<2, 3>(dir, in, w, out, B, H, W, stream)
+                                  : launch_wave_bands_ck<2, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 4 && k == 3) return multi ? launch_wave_bands_multi_ck<4, 3>(dir, in, w, out, B, H, W, stream)
+                                  : launch_wave_bands_ck<4, 3>(dir, in, w, out, B, H, W, stream);
     return INVCONV_ERR_VARIANT;
 }
 

@@ -68,6 +68,8 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     # few channels, more than 64 rows: bands of 64 rows, one wave each
     (2, 3, 256, 256, 3), (1, 3, 130, 40, 5), (1, 4, 512, 16, 3), (1, 1, 65, 7, 3), (2, 3, 128, 200, 3),
     (1, 2, 191, 3, 3), (1, 3, 320, 70, 5),
+    # three or more bands of wide images: one workgroup per band, logs handed over through global memory
+    (1, 3, 512, 512, 3), (2, 3, 200, 130, 5), (3, 1, 300, 128, 3), (2, 4, 193, 160, 3), (5, 2, 257, 129, 3),
     (600, 3, 8, 8, 3), (520, 1, 64, 4, 3),     # large batches: the forward launch caps its waves per CU
     # 8 / 12 channels, large batches or tall images: single-layer solves through the pipelined kernel
     (130, 12, 64, 64, 3), (26, 12, 100, 36, 3), (300, 8, 40, 24, 3), (40, 8, 128, 8, 3),
