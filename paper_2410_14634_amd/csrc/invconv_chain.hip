@@ -4,7 +4,7 @@
 //
 // The solve of layer s+1 at pixel p needs the output of layer s only at pixels
 // <= p (same partial order as inside a layer, Section 3), so layer s+1 can trail
-// layer s by a few anti-diagonals instead of waiting for it to finish.  One
+// layer s by a few dozen anti-diagonals instead of waiting for it to finish.  One
 // workgroup per (stage s, image n); workgroups of later stages have higher block
 // indices than the ones they wait for.  The same holds for the backward chain in
 // mirrored coordinates (the transposed solve of layer l consumes dL/dy of layer
@@ -14,20 +14,18 @@
 //   waves 0..NB-1   compute: the band-systolic solve on 16x16x4 MFMA of the
 //                   single-layer kernel, one wave per 16-row band, but all
 //                   operands come from / go to an LDS ring, never global memory;
-//   4 loader waves  fetch the input in blocks of 4 steps (16 rows x 4 columns
-//                   per instruction, so a row contributes 16 contiguous bytes)
-//                   into the ring, after waiting for the producer stage's
-//                   progress counter;
-//   4 storer waves  drain finished results from the ring to global memory in
-//                   the same blocks, then publish the stage's progress.
+//   4 loader waves  fetch the input into the ring, after waiting for the producer
+//                   stage's progress counter;
+//   4 storer waves  drain finished results from the ring to global memory, then
+//                   publish the stage's progress.
 // Global memory is touched 64 bytes of a row at a time: a group of 16 steps of a
 // band is 16 rows x 16 columns per channel, lane (row, quarter) moves 16 bytes,
 // the four lanes of a row 64 contiguous bytes.  A group lives in the registers of
 // its loader (storer) wave and passes to (from) the ring a quarter, 4 steps, at a
 // time, every fourth step.  Each such wave serves two bands whose groups are 6
 // and 10 steps out of phase: what it fetched is first used four steps later, a
-// storer publishes a group four steps after storing it, and the wave's other
-// memory operations are at least six steps old by then, so "wait for everything
+// storer publishes a group two steps after storing it, and the wave's other
+// memory operations are at least four steps old by then, so "wait for everything
 // outstanding" costs nothing extra and a memory round trip has four steps to
 // finish instead of lying on every step's path.  Every role runs a loop of its
 // own (same number of barriers), so its registers are its own.
@@ -115,11 +113,11 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sW);
 
-    const int nrow = lane & 15, g = lane >> 4;       // compute: row of the band, channel group; i/o: row, step of the block
+    const int nrow = lane & 15, g = lane >> 4;       // compute: row of the band, channel group; i/o: row, quarter
     const int span = 16 + W - 1;                               // active steps of a band
     const int t_last = (NB - 1) * (16 + kCDelay) + span;       // one past the last active step of any band
     const int t_end = t_last + kCGroup;                        // a band's last group is stored up to 16 steps later
-    const int t_begin = -(kCLead + kCGroup);                   // the group that holds step 0 is fetched up to 24 steps before
+    const int t_begin = -(kCLead + kCGroup);                   // the group that holds step 0 is fetched up to 22 steps before
     const size_t img = (size_t)n_img * C * H * W;
 
     if (wave < NB) {
