@@ -203,6 +203,36 @@ def measure_workload(cfg, steps, warmup, variant=0):
     )
 
 
+def device_info(torch):
+    """What the runtime reports for the GPU, and a measured streaming copy (read + write) to hold beside the
+    published HBM peak."""
+    p = torch.cuda.get_device_properties(0)
+    info = dict(name=p.name, compute_units=p.multi_processor_count,
+                clock_mhz=(p.clock_rate / 1e3 if getattr(p, "clock_rate", 0) else None),   # None: not reported here
+                published_clock_mhz=2400, memory_gib=p.total_memory / 2**30)
+    n = 512 * 1024 * 1024 // 4
+    src = torch.zeros(n, device="cuda")
+    dst = torch.empty_like(src)
+    ms = event_time_batch(torch, lambda: dst.copy_(src), 20, 3)
+    info["measured_copy_gbs"] = 2.0 * n * 4 / (ms * 1e-3) / 1e9
+    info["measured_copy_note"] = "512 MiB device-to-device copy, bytes read + bytes written over the mean of 20 copies"
+    return info
+
+
+def graph_replay_ms(torch, L, reps):
+    """The same step captured once into a HIP graph and replayed: what is left when the host's launch work
+    is taken out (reported beside ms_per_step, never instead of it)."""
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        L.step(side.cuda_stream)                  # warm up on the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            L.step(side.cuda_stream)
+    torch.cuda.synchronize()
+    return event_time_batch(torch, graph.replay, reps, 5)
+
+
 def variant_study(cfg, reps=200):
     """Forward solve of one workload under every launch strategy (us per call, HIP events)."""
     import torch
@@ -396,6 +426,11 @@ def main():
         roofline=roofline,
     )
     if not args.headline_only:
+        dev = device_info(torch)
+        out["device"] = dev
+        roofline["frac_of_measured_copy"] = achieved / dev["measured_copy_gbs"]
+        if L.L == 1 and cfg in (0, 1):
+            out["ms_per_step_graph_replay"] = graph_replay_ms(torch, L, max(min(args.steps, 500), 20))
         others = {}
         for c in range(5):
             if c == cfg:
@@ -403,9 +438,13 @@ def main():
                 continue
             st = {0: args.steps, 1: args.steps, 2: max(args.steps // 2, 10), 3: max(args.steps // 4, 10),
                   4: max(args.steps // 100, 5)}[c]
-            _, r = measure_workload(c, st, max(st // 10, 2), args.variant)
+            Lc, r = measure_workload(c, st, max(st // 10, 2), args.variant)
+            if c in (0, 1):
+                r["ms_per_step_graph_replay"] = graph_replay_ms(torch, Lc, max(min(st, 500), 20))
             others[str(c)] = r
             print(f"[bench] workload {c}: {json.dumps(r)}", file=sys.stderr, flush=True)
+        for r in others.values():
+            r["hbm_frac_of_measured_copy"] = r["algorithmic_gbs"] / dev["measured_copy_gbs"]
         out["workloads"] = others
         out["sampling_conv"] = measure_conv()
         print(f"[bench] sampling conv: {json.dumps(out['sampling_conv'])}", file=sys.stderr, flush=True)
