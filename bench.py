@@ -316,8 +316,26 @@ def cpu_baseline(cfg, seconds):
         el = time.perf_counter() - t0
         if el >= seconds or (cfg == 4 and n >= 1):
             break
-    return dict(value=B * n / el, unit="images/s", cores=threads, kind="oracle",
-                sample=f"{sample}; {n} passes in {el:.1f} s")
+    out = dict(value=B * n / el, unit="images/s", cores=threads, kind="oracle",
+               sample=f"{sample}; {n} passes in {el:.1f} s")
+    # the same oracle on one thread (a short sample), and the host it ran on
+    if cfg != 4:
+        all_threads, threads = threads, 1
+        one_pass()
+        n1, t1 = 0, time.perf_counter()
+        while time.perf_counter() - t1 < min(2.0, seconds):
+            one_pass()
+            n1 += 1
+        out["value_single_thread"] = B * n1 / (time.perf_counter() - t1)
+        threads = all_threads
+    try:
+        with open("/proc/cpuinfo") as f:
+            models = [ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")]
+        out["cpu_model"] = models[0] if models else None
+        out["host_logical_cpus"] = len(models) or os.cpu_count()
+    except OSError:
+        out["cpu_model"] = None
+    return out
 
 
 CONV_SHAPES = {  # the sampling-direction operator y = conv_w(x); streaming sizes besides the workload shapes
