@@ -31,8 +31,9 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
     switch (variant) {
     case INVCONV_VARIANT_AUTO:
         if (wave_supported(C, H, k))
-            return wave_split_preferred(B, H, W, k) ? launch_solve_wave_split(dir, in, w, out, B, C, H, W, k, stream)
-                                              : launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream);
+            return wave_split_preferred(B, H, W, k) && !wave_tile_preferred(B, C, H, W)
+                       ? launch_solve_wave_split(dir, in, w, out, B, C, H, W, k, stream)
+                       : launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream);
         if (wave_bands_supported(C, H, W, k))
             return launch_solve_wave_bands(dir, in, w, out, B, C, H, W, k, stream);
         if (band_supported(C, H, k)) {

@@ -39,6 +39,7 @@ bool bwd_wave_supported(int C, int H, int W, int k);
 int launch_solve_wave_split(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                             hipStream_t stream);
 bool wave_split_preferred(int B, int H, int W, int k);
+bool wave_tile_preferred(int B, int C, int H, int W);
 bool wave_bands_supported(int C, int H, int W, int k);
 int launch_solve_wave_bands(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                             hipStream_t stream);
