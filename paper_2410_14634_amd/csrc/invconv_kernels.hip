@@ -272,34 +272,38 @@ __global__ __launch_bounds__(kDwBlock) void k_dw_partial(const float *__restrict
 // as 0.  No atomics anywhere, so dw is bitwise reproducible from run to run.
 // blockIdx.y selects the layer when several layers are reduced by one launch
 // (layer l's rows start at part + l*nparts*P, its result goes to out.p[l]).
-__global__ __launch_bounds__(256) void k_dw_reduce(const float *__restrict__ part_all, int nparts, PtrList out,
-                                                  int C, int k, float sign)
+__global__ __launch_bounds__(1024) void k_dw_reduce(const float *__restrict__ part_all, int nparts, PtrList out,
+                                                   int C, int k, float sign)
 {
-    __shared__ double swave[4][64];
+    // 4 waves, or 16 for many rows (the launch decides from nparts alone, so the order of the additions is
+    // a function of the shape): wave v adds rows v, v + NW, ... in order, then the waves are added in order
+    __shared__ double swave[16][64];
     const int P = C * C * k * k;
     const float *__restrict__ part = part_all + (size_t)blockIdx.y * nparts * P;
     float *__restrict__ dw = out.p[blockIdx.y];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, NW = blockDim.x >> 6;
     const int e = blockIdx.x * 64 + lane;
     double acc = 0.0;
     if (e < P) {
         int p = wave;
-        for (; p + 28 < nparts; p += 32) {
+        for (; p + 7 * NW < nparts; p += 8 * NW) {
             float a[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                a[u] = part[(size_t)(p + 4 * u) * P + e];
+                a[u] = part[(size_t)(p + NW * u) * P + e];
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 acc += (double)a[u];
         }
-        for (; p < nparts; p += 4)
+        for (; p < nparts; p += NW)
             acc += (double)part[(size_t)p * P + e];
     }
     swave[wave][lane] = acc;
     __syncthreads();
     if (wave == 0 && e < P) {
-        const double total = ((swave[0][lane] + swave[1][lane]) + swave[2][lane]) + swave[3][lane];
+        double total = swave[0][lane];
+        for (int v = 1; v < NW; ++v)
+            total += swave[v][lane];
         const int b = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
         const bool is_masked = (a == k - 1 && b == k - 1 && i > o);
         dw[e] = is_masked ? 0.0f : (float)(sign < 0.0f ? -total : total);
@@ -485,7 +489,8 @@ int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int
     PtrList out{};
     for (int l = 0; l < layers; ++l)
         out.p[l] = dw[l];
-    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 63) / 64, layers), dim3(256), 0, stream, part, nparts, out, C, k, sign);
+    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 63) / 64, layers), dim3(nparts >= 512 ? 1024 : 256), 0, stream, part,
+                       nparts, out, C, k, sign);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
