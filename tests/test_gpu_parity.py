@@ -121,6 +121,23 @@ def test_kernel_size_ablation_shapes(shape, variant):
     check_layer(cs["y"], cs["w"][0], cs["g"], variant)
 
 
+def test_bands_on_many_compute_units_at_full_occupancy():
+    """512 band workgroups at once (128 images of 3 x 256 x 256): sampled images against the oracle."""
+    import torch
+    B, C, H, W, k = 128, 3, 256, 256, 3
+    cs = inputs.make_case(B, C, H, W, k, seed=77, tap_std=0.05)
+    y, w, g = cs["y"], cs["w"][0], cs["g"]
+    x = b.invconv_fwd(dev(y), dev(w))
+    v, _ = b.invconv_bwd(x, dev(w), dev(g))
+    torch.cuda.synchronize()
+    xh, vh = host(x), host(v)
+    for n in (0, 63, 127):
+        xr = oracle.invconv_fwd(y[n:n + 1], w, THREADS)
+        assert rel_err(xh[n:n + 1], xr) <= TOL_ACT, f"x of image {n}"
+        vr, _ = oracle.invconv_bwd(xh[n:n + 1], w, g[n:n + 1], THREADS)
+        assert rel_err(vh[n:n + 1], vr) <= TOL_ACT, f"dL/dy of image {n}"
+
+
 def test_masked_entries_are_ignored_and_get_zero_gradient():
     cs = inputs.make_case(2, 4, 9, 8, 3, seed=3)
     y, w, g = cs["y"], cs["w"][0].copy(), cs["g"]
