@@ -272,16 +272,17 @@ __global__ __launch_bounds__(kDwBlock) void k_dw_partial(const float *__restrict
 // as 0.  No atomics anywhere, so dw is bitwise reproducible from run to run.
 // blockIdx.y selects the layer when several layers are reduced by one launch
 // (layer l's rows start at part + l*nparts*P, its result goes to out.p[l]).
-__global__ __launch_bounds__(1024) void k_dw_reduce(const float *__restrict__ part_all, int nparts, PtrList out,
-                                                   int C, int k, float sign)
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void k_dw_reduce(const float *__restrict__ part_all, int nparts, PtrList out,
+                                                      int C, int k, float sign)
 {
-    // 4 waves, or 16 for many rows (the launch decides from nparts alone, so the order of the additions is
-    // a function of the shape): wave v adds rows v, v + NW, ... in order, then the waves are added in order
-    __shared__ double swave[16][64];
+    // NW = 4 waves, or 16 for many rows (the launch decides from nparts alone, so the order of the additions
+    // is a function of the shape): wave v adds rows v, v + NW, ... in order, then the waves are added in order
+    __shared__ double swave[NW][64];
     const int P = C * C * k * k;
     const float *__restrict__ part = part_all + (size_t)blockIdx.y * nparts * P;
     float *__restrict__ dw = out.p[blockIdx.y];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, NW = blockDim.x >> 6;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int e = blockIdx.x * 64 + lane;
     double acc = 0.0;
     if (e < P) {
@@ -302,6 +303,7 @@ __global__ __launch_bounds__(1024) void k_dw_reduce(const float *__restrict__ pa
     __syncthreads();
     if (wave == 0 && e < P) {
         double total = swave[0][lane];
+#pragma unroll
         for (int v = 1; v < NW; ++v)
             total += swave[v][lane];
         const int b = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
@@ -489,8 +491,12 @@ int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int
     PtrList out{};
     for (int l = 0; l < layers; ++l)
         out.p[l] = dw[l];
-    hipLaunchKernelGGL(k_dw_reduce, dim3((P + 63) / 64, layers), dim3(nparts >= 512 ? 1024 : 256), 0, stream, part,
-                       nparts, out, C, k, sign);
+    if (nparts >= 512)
+        hipLaunchKernelGGL(k_dw_reduce<16>, dim3((P + 63) / 64, layers), dim3(1024), 0, stream, part, nparts, out, C, k,
+                           sign);
+    else
+        hipLaunchKernelGGL(k_dw_reduce<4>, dim3((P + 63) / 64, layers), dim3(256), 0, stream, part, nparts, out, C, k,
+                           sign);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
