@@ -1120,11 +1120,147 @@ static bool wave_split_pays(int k) { return k >= 5; }
 
 bool wave_split_preferred(int B, int H, int W, int k) { return k >= 3 && (k >= 5 || H + W >= 48) && B <= 512; }
 
+// ---------------------------------------------------------------------------
+// The backward pass of one image on eight waves (W a multiple of 16, at most 64): waves 0..3 run the
+// transposed solve with its steps split over them (solve_wave_split_body, which also keeps dL/dy in an
+// LDS tile), waves 4..7 meanwhile stage x and then form the weight-gradient products behind the
+// wavefront: mirrored row r of dL/dy is complete in LDS once step r + W has ended, a row goes to helper
+// wave r mod 4, and a helper takes one group of 16 pixels per step, so it keeps up with the solve.  The
+// helpers pass through the same barriers as the solving waves (one after the set-up, one per step),
+// doing a slice of their work in between.  What is left after the last step (the rows of
+// the last few steps) is finished by the helpers before the common reduction.
+// ---------------------------------------------------------------------------
+template <int C, int K>
+__global__ __launch_bounds__(512) void k_bwd_wave8(const float *__restrict__ x, const float *__restrict__ w,
+                                                  const float *__restrict__ g, float *__restrict__ v,
+                                                  float *__restrict__ part, int H, int W)
+{
+    extern __shared__ float smem[];
+    constexpr int NCOL = C * K * K;            // shifted-x columns (i, a, b)
+    constexpr int NS = (NCOL + 3) / 4;         // groups of four columns
+    constexpr int P = C * NCOL;
+    const int XR = H + K - 1, XW = W + K - 1;
+    float *sv = smem;                          // [C][H][W]
+    float *sx = sv + C * H * W;                // [C][XR][XW], origin at (-(K-1), -(K-1))
+    float *sred = smem;                        // [4*64][NS*4], reuses the tiles after the products
+    const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    if (wave < 4) {
+        __builtin_amdgcn_s_setprio(2);      // the dependent chain goes first; the helpers fill the gaps
+        WaveSplitLds sl;
+        sl.x = smem + ((C * H * W + C * XR * XW + 3) & ~3);     // 16-byte aligned behind the tiles
+        sl.m = reinterpret_cast<f32x4 *>(sl.x + 2 * C * 64);
+        solve_wave_split_body<C, K, 1, true>(g, w, v, H, W, n, sv, sl);
+        __syncthreads();        // the helpers have finished the products
+    } else {
+        const int ht = tid - 256, hw = wave - 4;
+        const float *xi = x + (size_t)n * C * H * W;
+        for (int base = ht; base < C * XR * XW; base += 8 * 256) {
+            float val[8];
+            bool halo[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int raw = base + u * 256;
+                const int idx = raw < C * XR * XW ? raw : C * XR * XW - 1;
+                const int cc = idx % XW, rr = (idx / XW) % XR, ch = idx / (XW * XR);
+                const int gr = rr - (K - 1), gc = cc - (K - 1);
+                halo[u] = gr < 0 || gc < 0;
+                val[u] = xi[(ch * H + (gr < 0 ? 0 : gr)) * W + (gc < 0 ? 0 : gc)];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (base + u * 256 < C * XR * XW)
+                    sx[base + u * 256] = halo[u] ? 0.0f : val[u];
+        }
+        // lane = (block b, j): A row o = j, B column 4s + j (padding rows / columns read valid data, unused)
+        const int j = lane & 3, b = lane >> 2;
+        const int aoff = (j < C) ? j * H * W : 0;
+        int boff[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const int col = (4 * s + j < NCOL) ? 4 * s + j : 0;
+            const int i = col / (K * K), a = (col / K) % K, bb = col % K;
+            boff[s] = (i * XR + a) * XW + bb;
+        }
+        f32x4 acc[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // one group: 16 pixels pc .. pc+15 of image row pr
+        auto group = [&](int pr, int pc) {
+            const float av = sv[aoff + pr * W + b + pc];
+            const float *bp = sx + pr * XW + b + pc;
+            float bv[NS];
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                bv[s] = bp[boff[s]];
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                acc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(av, bv[s], acc[s], 0, 0, 0);
+        };
+        const int ngrp = W >> 4;
+        int row = hw, grp = 0;                  // next group of this helper: mirrored row `row`, group `grp`
+        __syncthreads();        // the solving waves' set-up barrier; x is staged for all helpers
+        const int total = H + W - 1 + 2;
+        for (int s = -1; s < total - 1; ++s) {
+            // mirrored row r is complete once step r + W has ended, i.e. from step r + W + 1 on
+            if (row < H && row + W + 1 <= s) {
+                group(H - 1 - row, 16 * grp);
+                if (++grp == ngrp) {
+                    grp = 0;
+                    row += 4;
+                }
+            }
+            __syncthreads();
+        }
+        // (the last step's barrier has passed: every row is complete)
+        while (row < H) {
+            group(H - 1 - row, 16 * grp);
+            if (++grp == ngrp) {
+                grp = 0;
+                row += 4;
+            }
+        }
+        __syncthreads();        // products finished: the tiles can be reused
+        // lane (b, j) register (s, o) holds block b's partial of entry (o, col = 4s + j)
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int o = 0; o < 4; ++o)
+                sred[ht * (NS * 4) + s * 4 + o] = acc[s][o];
+    }
+    __syncthreads();
+    // fixed-order sum in two levels: the 16 blocks of each helper wave, then the four helper waves
+    float *swave = sred + 256 * NS * 4;     // [4][P]
+    for (int idx = tid; idx < 4 * P; idx += 512) {
+        const int e = idx % P, wv = idx / P;
+        const int o = e / NCOL, col = e % NCOL;
+        const int s = col >> 2, jj = col & 3;
+        float sum = 0.0f;
+#pragma unroll
+        for (int bb = 0; bb < 16; ++bb)
+            sum += sred[(wv * 64 + bb * 4 + jj) * (NS * 4) + s * 4 + o];
+        swave[wv * P + e] = sum;
+    }
+    __syncthreads();
+    for (int e = tid; e < P; e += 512)
+        part[(size_t)n * P + e] = ((swave[e] + swave[P + e]) + swave[2 * P + e]) + swave[3 * P + e];
+}
+
 size_t bwd_wave_lds_bytes(int C, int H, int W, int k)
 {
     size_t tiles = (size_t)C * H * W + (size_t)C * (H + k - 1) * (W + k - 1);
     if (wave_split_pays(k))
         tiles += 4 + 2 * (size_t)C * 64 + 2 * (size_t)k * 64 * 4;      // exchange buffers of the split solve
+    const size_t red = 256 * (size_t)((C * k * k + 3) / 4) * 4 + 4 * (size_t)C * C * k * k;
+    return sizeof(float) * (tiles > red ? tiles : red);
+}
+
+static size_t bwd_wave8_lds_bytes(int C, int H, int W, int k)
+{
+    const size_t tiles = (size_t)C * H * W + (size_t)C * (H + k - 1) * (W + k - 1) + 4 + 2 * (size_t)C * 64 +
+                         2 * (size_t)k * 64 * 4;
     const size_t red = 256 * (size_t)((C * k * k + 3) / 4) * 4 + 4 * (size_t)C * C * k * k;
     return sizeof(float) * (tiles > red ? tiles : red);
 }
@@ -1150,6 +1286,22 @@ static int launch_bwd_wave_ck(const float *x, const float *w, const float *g, fl
         }
         hipLaunchKernelGGL((k_bwd_wave<C, K, false, true>), dim3(B), dim3(256), lds, stream, x, w, g, v, part, H, W);
         return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+    }
+    if constexpr (K == 3) {
+        // eight waves while every image still gets a compute unit's worth of waves (k = 3: headline backward
+        // 20.4 -> 19.7 us; at k = 5 the same arrangement measured 3.5 us slower than four waves): the products run behind the solve instead of after it (rows of whole 16-pixel groups,
+        // at most four per row, so that a helper wave keeps up with one group per step)
+        const size_t lds8 = bwd_wave8_lds_bytes(C, H, W, K);
+        if (B <= 256 && (W & 15) == 0 && W <= 64 && lds8 <= kMaxLdsBytes) {
+            if (lds8 > 48 * 1024 &&
+                hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_wave8<C, K>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds8) != hipSuccess) {
+                (void)hipGetLastError();
+                return INVCONV_ERR_UNSUPPORTED;
+            }
+            hipLaunchKernelGGL((k_bwd_wave8<C, K>), dim3(B), dim3(512), lds8, stream, x, w, g, v, part, H, W);
+            return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+        }
     }
     hipLaunchKernelGGL((k_bwd_wave<C, K, kSplit>), dim3(B), dim3(256), lds, stream, x, w, g, v, part, H, W);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
