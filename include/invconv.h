@@ -10,9 +10,14 @@
  *
  * Conventions shared by every entry point
  *   - Every pointer except `stream` is a DEVICE pointer to contiguous fp32.
- *     The caller owns all buffers; the library never allocates, frees or keeps
- *     them.  `stream` is a hipStream_t (NULL = the default stream).  Calls are
- *     asynchronous on `stream`: no host synchronisation, no host read-back.
+ *     The caller owns all buffers; the library never frees or keeps them.
+ *     Scratch comes in as `workspace` arguments, with one exception: a solve of
+ *     few-channel images (C <= 4) of more than 128 rows may take a few KB per
+ *     image from the stream's memory pool and return them in stream order
+ *     (hipMallocAsync / hipFreeAsync; on a capturing stream, or where the pool
+ *     refuses, another kernel that needs none is used).  `stream` is a
+ *     hipStream_t (NULL = the default stream).  Calls are asynchronous on
+ *     `stream`: no host synchronisation, no host read-back.
  *   - Activations (y, x, dLdx, dLdy) are [B][C][H][W].
  *   - Kernels (w, dLdw) are [C_out = C][C_in = C][k][k] (Algorithm 1's
  *     K[c, k_c, ., .]).  Tap (a,b) multiplies x[., r-(k-1)+a, c-(k-1)+b].
