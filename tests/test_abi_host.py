@@ -99,3 +99,15 @@ def test_binding_refuses_cpu_tensors():
     import torch
     with pytest.raises(TypeError):
         b.invconv_fwd(torch.zeros(1, 1, 4, 4), torch.zeros(1, 1, 3, 3))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py --gpus N with N > 1 exits with a message that says so."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr or "one GPU" in r.stderr
+    assert r.stdout.strip() == ""
