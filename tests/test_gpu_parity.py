@@ -314,6 +314,33 @@ def test_hip_graph_replays_match_eager():
             assert torch.equal(t, r), f"replay {rep}"
 
 
+def test_hip_graph_of_a_tall_image_solve_matches_eager():
+    """Tall few-channel images: the eager launch spreads the bands over workgroups and takes its logs from
+    the stream's memory pool; under capture the one-workgroup kernel is recorded instead.  Same results."""
+    import torch
+    cs = inputs.make_case(2, 3, 256, 160, 3, seed=31, tap_std=0.05)
+    y, w = dev(cs["y"]), dev(cs["w"][0])
+    x = torch.empty_like(y)
+    b.invconv_fwd(y, w, out=x)
+    torch.cuda.synchronize()
+    ref = x.clone()
+    assert rel_err(host(ref), oracle.invconv_fwd(cs["y"], cs["w"][0], THREADS)) <= TOL_ACT
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        b.invconv_fwd(y, w, out=x)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        b.invconv_fwd(y, w, out=x)
+    for rep in range(3):
+        x.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(x, ref), f"replay {rep}"
+
+
 def test_chain_error_word_stays_clear():
     """The pipelined chain launch never runs out of its bounded waits in normal operation."""
     import torch
