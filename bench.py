@@ -45,6 +45,8 @@ def parse_args():
                     help="also time the forward solve under every launch strategy (reported under 'variant_study')")
     ap.add_argument("--conv-only", action="store_true",
                     help="only time the sampling-direction convolution (invconv_conv_fwd) and print its table")
+    ap.add_argument("--scale-study", action="store_true",
+                    help="only the shapes of the paper's ablations (tall images, large batches, kernel sizes 2..11)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three 64 MiB device copies (reference for the HBM byte counters)")
     return ap.parse_args()
@@ -386,6 +388,41 @@ def measure_conv(reps=100):
     return out
 
 
+SCALE_SHAPES = {  # (B, C, H, W, k): the paper's image-size / batch-size / kernel-size ablations, synthetic inputs
+    "tall_b1": (1, 3, 256, 256, 3), "tall_b16": (16, 3, 256, 256, 3), "tall_b128": (128, 3, 256, 256, 3),
+    "tall_512": (1, 3, 512, 512, 3),
+    "batch_256": (256, 3, 32, 32, 3), "batch_1024": (1024, 3, 32, 32, 3), "batch_4096": (4096, 3, 32, 32, 3),
+    "k2": (16, 3, 32, 32, 2), "k5": (16, 3, 32, 32, 5), "k7": (16, 3, 32, 32, 7), "k9": (16, 3, 32, 32, 9),
+    "k11": (16, 3, 32, 32, 11), "mnist_like": (128, 1, 28, 28, 3),
+}
+
+
+def scale_study(reps=30):
+    """invconv_fwd / invconv_bwd at the shapes of the paper's ablations: us per call, images/s of forward + backward,
+    algorithmic GB/s (20 bytes per element).  Not part of the default run."""
+    import torch
+    from paper_2410_14634_amd import binding as b
+    from paper_2410_14634_amd import inputs
+    out = {}
+    for name, (B, C, H, W, k) in SCALE_SHAPES.items():
+        cs = inputs.make_case(B, C, H, W, k, seed=5, tap_std=0.15 / k)
+        y, w, g = (torch.from_numpy(cs[n]).cuda() for n in ("y", "g", "y"))
+        w = torch.from_numpy(cs["w"][0]).cuda()
+        g = torch.from_numpy(cs["g"]).cuda()
+        x = torch.empty_like(y)
+        v, dw = torch.empty_like(y), torch.empty_like(w)
+        wsp = torch.empty(max(b.bwd_workspace_bytes(B, C, H, W, k), 256), dtype=torch.uint8, device="cuda")
+        b.invconv_fwd(y, w, out=x)
+        ms_f = event_time_batch(torch, lambda: b.invconv_fwd(y, w, out=x), reps, 3)
+        ms_b = event_time_batch(torch, lambda: b.invconv_bwd(x, w, g, out=(v, dw), workspace=wsp), reps, 3)
+        n = B * C * H * W
+        out[name] = dict(B=B, C=C, H=H, W=W, k=k, fwd_us=ms_f * 1e3, bwd_us=ms_b * 1e3,
+                         images_per_s=B / ((ms_f + ms_b) * 1e-3),
+                         algorithmic_gbs=20.0 * n / ((ms_f + ms_b) * 1e-3) / 1e9,
+                         us_per_diagonal=(ms_f + ms_b) * 1e3 / (2 * (H + W - 1)))
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -409,6 +446,9 @@ def main():
         torch.cuda.synchronize()
     if args.conv_only:
         print(json.dumps(dict(sampling_conv=measure_conv())), flush=True)
+        return
+    if args.scale_study:
+        print(json.dumps(dict(scale_study=scale_study())), flush=True)
         return
     cfg = args.workload
     L, res = measure_workload(cfg, args.steps, args.warmup, args.variant)
