@@ -9,15 +9,24 @@
  * the bottom-right kernel tap multiplies the current pixel (Eq. 1).
  *
  * Conventions shared by every entry point
- *   - Every pointer except `stream` is a DEVICE pointer to contiguous fp32.
- *     The caller owns all buffers; the library never frees or keeps them.
- *     Scratch comes in as `workspace` arguments, with one exception: a solve of
- *     few-channel images (C <= 4) of more than 128 rows may take a few KB per
- *     image from the stream's memory pool and return them in stream order
- *     (hipMallocAsync / hipFreeAsync; on a capturing stream, or where the pool
- *     refuses, another kernel that needs none is used).  `stream` is a
- *     hipStream_t (NULL = the default stream).  Calls are asynchronous on
- *     `stream`: no host synchronisation, no host read-back.
+ *   - Every pointer except `stream` is a DEVICE pointer to contiguous fp32
+ *     (unless a comment says HOST).  The caller owns all buffers; the library
+ *     never allocates, frees or keeps device memory: all scratch comes in as
+ *     `workspace` arguments (256-byte aligned device memory of at least the
+ *     size the matching *_workspace_bytes() call returns), and the same
+ *     kernels run whether or not the stream is being captured into a graph.
+ *     `stream` is a hipStream_t (NULL = the default stream).  Calls are
+ *     asynchronous on `stream`: no host synchronisation, no host read-back.
+ *   - Workspace header.  The first INVCONV_WS_HEADER_BYTES bytes of every
+ *     workspace belong to the library.  The int32 at byte offset
+ *     INVCONV_WS_ERROR_WORD_OFFSET is the ERROR WORD.  Kernels that spread one
+ *     image or one stack of layers over several workgroups order them with
+ *     bounded waits; a wait that runs out (which a healthy device never
+ *     shows) makes the waiting wave carry on, every kernel still ends, the
+ *     affected outputs are filled with NaN, and the error word is set to 1.
+ *     The library only ever sets the word, it never clears it: zero the header
+ *     once after allocating the workspace, then read the word (4 bytes, device
+ *     to host, or invconv_workspace_error()) whenever a result is consumed.
  *   - Activations (y, x, dLdx, dLdy) are [B][C][H][W].
  *   - Kernels (w, dLdw) are [C_out = C][C_in = C][k][k] (Algorithm 1's
  *     K[c, k_c, ., .]).  Tap (a,b) multiplies x[., r-(k-1)+a, c-(k-1)+b].
@@ -27,8 +36,11 @@
  *     w[c][c][k-1][k-1] must be non-zero (the paper fixes it to 1); a zero
  *     diagonal is not checked and yields IEEE inf/NaN.
  *   - H != W, k > min(H,W) and k = 1 are valid.
- *   - Return value: INVCONV_OK or a negative invconv_status.  On any error no
- *     kernel has been launched and no output has been touched.
+ *   - Return value: INVCONV_OK or a negative invconv_status.  Argument and
+ *     shape errors (NULL, SHAPE, UNSUPPORTED, WORKSPACE, ALIAS, VARIANT) are
+ *     found before anything is launched: no output has been touched.
+ *     INVCONV_ERR_LAUNCH means the runtime refused a launch; kernels of the
+ *     same call queued before it still run, so outputs are undefined.
  */
 #ifndef INVCONV_H
 #define INVCONV_H
@@ -41,12 +53,16 @@ extern "C" {
 
 typedef int invconv_status;
 
+#define INVCONV_WS_HEADER_BYTES 256
+#define INVCONV_WS_ERROR_WORD_OFFSET 0
+
 enum {
     INVCONV_OK = 0,
     INVCONV_ERR_NULL = -1,        /* a required pointer is NULL */
     INVCONV_ERR_SHAPE = -2,       /* B, C, H, W or k < 1, B*C*H*W > 2^31 - 1, or one image C*H*W >= 2^29 elements (2 GiB) */
     INVCONV_ERR_UNSUPPORTED = -3, /* shape beyond what the kernels' on-chip buffers hold */
-    INVCONV_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than invconv_bwd_workspace_bytes() */
+    INVCONV_ERR_WORKSPACE = -4,   /* workspace NULL, not 256-byte aligned, smaller than *_workspace_bytes(), or
+                                     (entry point without a workspace argument) larger than the library's own */
     INVCONV_ERR_ALIAS = -5,       /* an output pointer equals an input pointer */
     INVCONV_ERR_LAUNCH = -6,      /* the HIP runtime refused a launch */
     INVCONV_ERR_VARIANT = -7      /* unknown variant, or variant not available for this shape */
@@ -73,6 +89,34 @@ enum {
  */
 invconv_status invconv_fwd(const float *y, const float *w, float *x,
                            int B, int C, int H, int W, int k, void *stream);
+
+/*
+ * The same forward pass with scratch from the caller.  Images of few channels (C <= 4) and more than
+ * 128 rows are then cut into bands of 64 rows that run on different compute units and hand their
+ * boundary messages over through the workspace (Section 3.3 only needs the pixels of an anti-diagonal
+ * to be independent; a band trails the one above by a fixed number of steps); invconv_fwd, which has
+ * nowhere to put those messages, keeps all bands of an image in one workgroup.  Other shapes run the
+ * kernels invconv_fwd runs.  Results are identical.
+ *   workspace [scratch] at least invconv_fwd_workspace_bytes() bytes (never 0 for a valid shape).
+ */
+invconv_status invconv_fwd_ws(const float *y, const float *w, float *x,
+                              int B, int C, int H, int W, int k,
+                              void *workspace, size_t workspace_bytes, void *stream);
+size_t invconv_fwd_workspace_bytes(int B, int C, int H, int W, int k);   /* 0 if the shape is invalid */
+
+/*
+ * Reads the error word of a workspace: copies it to *word (HOST pointer) on `stream` and waits for the
+ * stream.  0 = no bounded wait has run out since the header was last zeroed.
+ */
+invconv_status invconv_workspace_error(const void *workspace, void *stream, int *word);
+
+/*
+ * Test hook for the bounded waits: the number of polls a waiting wave makes before it gives up, for
+ * all calls of this process from now on (0 = the built-in budgets, about a second).  With a budget of
+ * a few polls the waits of a multi-workgroup kernel run out at once: outputs are NaN-filled, the error
+ * word is set, every kernel still ends normally.
+ */
+void invconv_set_wait_budget(int polls);
 
 /*
  * The masked causal convolution itself, y = conv_w(x) (Eq. 1): the inverse of invconv_fwd and the
@@ -138,6 +182,8 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
  * calls of invconv_fwd; where the shape allows it the layers run as one pipelined launch in which
  * layer l+1 trails layer l by a few dozen anti-diagonals.  L in 1..16.
  *   workspace: at least invconv_chain_workspace_bytes() bytes of device memory, 256-byte aligned.
+ * A stack that needs more workgroups than the device holds at once goes out as several launches of
+ * whole layers, so that no workgroup ever waits for one that has not started.
  */
 invconv_status invconv_chain_fwd(const float *y, const float *const *w, float *const *x, int L,
                                  int B, int C, int H, int W, int k,
@@ -160,16 +206,6 @@ invconv_status invconv_chain_logdet(const float *const *w, int L, int C, int H, 
 
 /* Bytes of scratch the two chain calls need (0 if the shape is invalid or unsupported). */
 size_t invconv_chain_workspace_bytes(int L, int B, int C, int H, int W, int k);
-
-/*
- * Measurement aid (Section 3.3 orders anti-diagonals with a synchronisation after
- * each): runs `steps` dependent, empty steps ordered by
- *   mode 0: one kernel launch per step (`workgroups` workgroups of 256 threads each),
- *   mode 1: one cooperative launch with a device-wide barrier per step,
- *   mode 2: one launch with a workgroup barrier and an LDS exchange per step.
- * No data is touched.  steps in 1..100000, workgroups in 1..256.
- */
-invconv_status invconv_probe_step_sync(int mode, int steps, int workgroups, void *stream);
 
 /* Static, human-readable name of a status code. */
 const char *invconv_status_string(invconv_status status);

@@ -23,8 +23,11 @@ VARIANT_AUTO, VARIANT_BLOCK, VARIANT_DIAG_LAUNCH, VARIANT_WAVE, VARIANT_BAND, VA
 EXPORTS = (
     "invconv_fwd", "invconv_bwd", "invconv_bwd_workspace_bytes", "invconv_logdet",
     "invconv_fwd_ex", "invconv_bwd_ex", "invconv_status_string", "invconv_version",
-    "invconv_probe_step_sync", "invconv_chain_fwd", "invconv_chain_bwd", "invconv_chain_workspace_bytes", "invconv_chain_logdet", "invconv_conv_fwd", "invconv_conv_bwd",
+    "invconv_probe_step_sync", "invconv_chain_fwd", "invconv_chain_bwd", "invconv_chain_workspace_bytes",
+    "invconv_chain_logdet", "invconv_conv_fwd", "invconv_conv_bwd",
+    "invconv_fwd_ws", "invconv_fwd_workspace_bytes", "invconv_workspace_error", "invconv_set_wait_budget",
 )
+WS_HEADER_BYTES = 256
 
 _lib = None
 
@@ -66,6 +69,14 @@ def lib() -> ctypes.CDLL:
         L.invconv_conv_fwd.restype = ci
         L.invconv_conv_bwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, ctypes.c_size_t, vp]
         L.invconv_conv_bwd.restype = ci
+        L.invconv_fwd_ws.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+        L.invconv_fwd_ws.restype = ci
+        L.invconv_fwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+        L.invconv_fwd_workspace_bytes.restype = sz
+        L.invconv_workspace_error.argtypes = [vp, vp, ctypes.POINTER(ci)]
+        L.invconv_workspace_error.restype = ci
+        L.invconv_set_wait_budget.argtypes = [ci]
+        L.invconv_set_wait_budget.restype = None
         L.invconv_status_string.argtypes = [ci]
         L.invconv_status_string.restype = ctypes.c_char_p
         L.invconv_version.restype = ci
@@ -108,13 +119,45 @@ def bwd_workspace_bytes(B: int, C: int, H: int, W: int, k: int) -> int:
     return int(lib().invconv_bwd_workspace_bytes(B, C, H, W, k))
 
 
+def fwd_workspace_bytes(B: int, C: int, H: int, W: int, k: int) -> int:
+    return int(lib().invconv_fwd_workspace_bytes(B, C, H, W, k))
+
+
+def new_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    """Device scratch of at least `nbytes` bytes with a zeroed header (the error word starts clear)."""
+    ws = torch.empty(max(int(nbytes), WS_HEADER_BYTES), dtype=torch.uint8, device=device)
+    ws[:WS_HEADER_BYTES].zero_()
+    return ws
+
+
+def workspace_error(workspace: torch.Tensor) -> int:
+    """The workspace's error word (waits for the current stream): non-zero after a bounded wait ran out."""
+    word = ctypes.c_int(-1)
+    st = lib().invconv_workspace_error(workspace.data_ptr(), _stream(), ctypes.byref(word))
+    if st != OK:
+        raise InvconvError(st, "invconv_workspace_error")
+    return int(word.value)
+
+
+def set_wait_budget(polls: int) -> None:
+    """Test hook: polls a bounded wait makes before it gives up (0 = built-in budgets)."""
+    lib().invconv_set_wait_budget(int(polls))
+
+
 def invconv_fwd(y: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None,
-                variant: int = VARIANT_AUTO) -> torch.Tensor:
-    """x with conv_w(x) = y (inverse of the masked causal convolution)."""
+                variant: int = VARIANT_AUTO, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """x with conv_w(x) = y (inverse of the masked causal convolution).  With `workspace` the call goes
+    through invconv_fwd_ws (scratch from the caller), otherwise through invconv_fwd."""
     _check(y, "y"), _check(w, "w")
     B, C, H, W, k = _dims(y, w)
     x = torch.empty_like(y) if out is None else _check(out, "out", y.shape)
-    st = lib().invconv_fwd_ex(y.data_ptr(), w.data_ptr(), x.data_ptr(), B, C, H, W, k, _stream(), variant)
+    if workspace is not None:
+        if variant != VARIANT_AUTO:
+            raise ValueError("a workspace goes with the automatic kernel choice only")
+        st = lib().invconv_fwd_ws(y.data_ptr(), w.data_ptr(), x.data_ptr(), B, C, H, W, k,
+                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream())
+    else:
+        st = lib().invconv_fwd_ex(y.data_ptr(), w.data_ptr(), x.data_ptr(), B, C, H, W, k, _stream(), variant)
     if st != OK:
         raise InvconvError(st, "invconv_fwd")
     return x
@@ -132,7 +175,7 @@ def invconv_bwd(x: torch.Tensor, w: torch.Tensor, dLdx: torch.Tensor,
         dLdy, dLdw = _check(out[0], "out[0]", x.shape), _check(out[1], "out[1]", w.shape)
     need = bwd_workspace_bytes(B, C, H, W, k)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+        workspace = new_workspace(need, x.device)
     ws_bytes = workspace.numel() * workspace.element_size()
     st = lib().invconv_bwd_ex(x.data_ptr(), w.data_ptr(), dLdx.data_ptr(), dLdy.data_ptr(), dLdw.data_ptr(),
                               B, C, H, W, k, workspace.data_ptr(), ws_bytes, _stream(), variant)
@@ -171,7 +214,7 @@ def invconv_chain_fwd(y: torch.Tensor, ws: list, out: list | None = None, worksp
     xs = [torch.empty_like(y) for _ in range(L)] if out is None else [_check(t, "out", y.shape) for t in out]
     need = chain_workspace_bytes(L, B, C, H, W, k)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=y.device)
+        workspace = new_workspace(need, y.device)
     st = lib().invconv_chain_fwd(y.data_ptr(), _ptr_array(ws), _ptr_array(xs), L, B, C, H, W, k,
                                  workspace.data_ptr(), workspace.numel(), _stream())
     if st != OK:
@@ -190,7 +233,7 @@ def invconv_chain_bwd(xs: list, ws: list, dLdx_last: torch.Tensor, workspace: to
     dws = [torch.empty_like(w) for w in ws]
     need = chain_workspace_bytes(L, B, C, H, W, k)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dy.device)
+        workspace = new_workspace(need, dy.device)
     st = lib().invconv_chain_bwd(_ptr_array(xs), _ptr_array(ws), dLdx_last.data_ptr(), dy.data_ptr(),
                                  _ptr_array(dws), L, B, C, H, W, k, workspace.data_ptr(), workspace.numel(),
                                  _stream())
@@ -234,7 +277,7 @@ def invconv_conv_bwd(x: torch.Tensor, w: torch.Tensor, dLdy: torch.Tensor,
         dLdx, dLdw = _check(out[0], "out[0]", x.shape), _check(out[1], "out[1]", w.shape)
     need = bwd_workspace_bytes(B, C, H, W, k)
     if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+        workspace = new_workspace(need, x.device)
     ws_bytes = workspace.numel() * workspace.element_size()
     st = lib().invconv_conv_bwd(x.data_ptr(), w.data_ptr(), dLdy.data_ptr(), dLdx.data_ptr(), dLdw.data_ptr(),
                                 B, C, H, W, k, workspace.data_ptr(), ws_bytes, _stream())

@@ -1,6 +1,18 @@
 // C ABI of the inverse-convolution library: argument validation and dispatch.
 #include "invconv_launch.h"
 
+namespace invconv {
+
+size_t solve_ws_bytes(int B, int C, int H, int W, int k)
+{
+    // only the few-channel images of more than 64 rows have a kernel that spreads one image over workgroups
+    if (!wave_supported(C, H, k) && wave_bands_supported(C, H, W, k))
+        return wave_bands_ws_bytes(B, C, H, W, k);
+    return 0;
+}
+
+}  // namespace invconv
+
 using namespace invconv;
 
 namespace {
@@ -25,8 +37,43 @@ int check_supported(int C, int H, int k)
     return solve_block_lds_bytes(C, H, k) <= kMaxLdsBytes ? INVCONV_OK : INVCONV_ERR_UNSUPPORTED;
 }
 
+constexpr size_t kWsHeader = INVCONV_WS_HEADER_BYTES;
+size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+
+// Workspace of invconv_fwd_ws: header, then what the solve can use.
+// Workspace of invconv_bwd / invconv_conv_bwd: header, the solve's share, then the partial sums of dL/dw.
+struct WsLayout {
+    size_t solve_bytes, dw_off, dw_bytes, total;
+};
+
+bool ws_layout(int B, int C, int H, int W, int k, bool with_dw, WsLayout *lay)
+{
+    lay->solve_bytes = up256(solve_ws_bytes(B, C, H, W, k));
+    lay->dw_off = kWsHeader + lay->solve_bytes;
+    lay->dw_bytes = 0;
+    if (with_dw) {
+        const DwPlan p = plan_dw_any(B, C, H, W, k);
+        if (!p.rt)
+            return false;
+        lay->dw_bytes = up256(p.bytes);
+    }
+    lay->total = lay->dw_off + lay->dw_bytes;
+    return true;
+}
+
+SolveWs solve_ws_of(void *workspace, const WsLayout &lay)
+{
+    SolveWs ws;
+    if (workspace) {
+        ws.base = (char *)workspace + kWsHeader;
+        ws.bytes = lay.solve_bytes;
+        ws.err = (int *)((char *)workspace + INVCONV_WS_ERROR_WORD_OFFSET);
+    }
+    return ws;
+}
+
 int solve(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-          hipStream_t stream, int variant)
+          hipStream_t stream, int variant, SolveWs ws = SolveWs{})
 {
     switch (variant) {
     case INVCONV_VARIANT_AUTO:
@@ -35,7 +82,7 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
                        ? launch_solve_wave_split(dir, in, w, out, B, C, H, W, k, stream)
                        : launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream);
         if (wave_bands_supported(C, H, W, k))
-            return launch_solve_wave_bands(dir, in, w, out, B, C, H, W, k, stream);
+            return launch_solve_wave_bands(dir, in, w, out, B, C, H, W, k, stream, ws);
         if (band_supported(C, H, k)) {
             if (chain_supported(1, C, H, W, k) && chain_single_preferred(B, C, H)) {
                 ChainArgs a{};          // the pipelined kernel with one stage: no counters, no workspace
@@ -55,7 +102,7 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
         return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_WAVE:
         if (wave_bands_supported(C, H, W, k))
-            return launch_solve_wave_bands(dir, in, w, out, B, C, H, W, k, stream);
+            return launch_solve_wave_bands(dir, in, w, out, B, C, H, W, k, stream, ws);
         return launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_BAND:
         return launch_solve_band(dir, in, w, out, B, C, H, W, k, stream);
@@ -70,12 +117,8 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
     }
 }
 
-}  // namespace
-
-extern "C" {
-
-invconv_status invconv_fwd_ex(const float *y, const float *w, float *x, int B, int C, int H, int W, int k,
-                              void *stream, int variant)
+int fwd_impl(const float *y, const float *w, float *x, int B, int C, int H, int W, int k, void *stream, int variant,
+             SolveWs ws)
 {
     if (!y || !w || !x)
         return INVCONV_ERR_NULL;
@@ -96,13 +139,60 @@ invconv_status invconv_fwd_ex(const float *y, const float *w, float *x, int B, i
          !band_supported(C, H, k)))
         if (int s = check_supported(C, H, k))
             return s;
-    return solve(0, y, w, x, B, C, H, W, k, (hipStream_t)stream, variant);
+    return solve(0, y, w, x, B, C, H, W, k, (hipStream_t)stream, variant, ws);
+}
+
+}  // namespace
+
+extern "C" {
+
+invconv_status invconv_fwd_ex(const float *y, const float *w, float *x, int B, int C, int H, int W, int k,
+                              void *stream, int variant)
+{
+    return fwd_impl(y, w, x, B, C, H, W, k, stream, variant, SolveWs{});
 }
 
 invconv_status invconv_fwd(const float *y, const float *w, float *x, int B, int C, int H, int W, int k,
                            void *stream)
 {
-    return invconv_fwd_ex(y, w, x, B, C, H, W, k, stream, INVCONV_VARIANT_AUTO);
+    return fwd_impl(y, w, x, B, C, H, W, k, stream, INVCONV_VARIANT_AUTO, SolveWs{});
+}
+
+size_t invconv_fwd_workspace_bytes(int B, int C, int H, int W, int k)
+{
+    WsLayout lay;
+    if (check_shape(B, C, H, W, k) != INVCONV_OK || !ws_layout(B, C, H, W, k, false, &lay))
+        return 0;
+    return lay.total;
+}
+
+invconv_status invconv_fwd_ws(const float *y, const float *w, float *x, int B, int C, int H, int W, int k,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!y || !w || !x)
+        return INVCONV_ERR_NULL;
+    if (int s = check_shape(B, C, H, W, k))
+        return s;
+    WsLayout lay;
+    ws_layout(B, C, H, W, k, false, &lay);
+    if (!workspace || workspace_bytes < lay.total || ((size_t)workspace & 255))
+        return INVCONV_ERR_WORKSPACE;
+    return fwd_impl(y, w, x, B, C, H, W, k, stream, INVCONV_VARIANT_AUTO, solve_ws_of(workspace, lay));
+}
+
+void invconv_set_wait_budget(int polls) { set_wait_budget(polls); }
+
+invconv_status invconv_workspace_error(const void *workspace, void *stream, int *word)
+{
+    if (!workspace || !word)
+        return INVCONV_ERR_NULL;
+    if (hipMemcpyAsync(word, (const char *)workspace + INVCONV_WS_ERROR_WORD_OFFSET, sizeof(int), hipMemcpyDeviceToHost,
+                       (hipStream_t)stream) != hipSuccess ||
+        hipStreamSynchronize((hipStream_t)stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return INVCONV_ERR_LAUNCH;
+    }
+    return INVCONV_OK;
 }
 
 invconv_status invconv_conv_fwd(const float *x, const float *w, float *y, int B, int C, int H, int W, int k,
@@ -128,24 +218,26 @@ invconv_status invconv_conv_bwd(const float *x, const float *w, const float *dLd
         (const float *)dLdw == x || (const float *)dLdw == dLdy)
         return INVCONV_ERR_ALIAS;
     const DwPlan p = plan_dw_any(B, C, H, W, k);
-    if (!p.rt)
+    WsLayout lay;
+    if (!p.rt || !ws_layout(B, C, H, W, k, true, &lay))
         return INVCONV_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < p.bytes)
+    if (!workspace || workspace_bytes < lay.total || ((size_t)workspace & 255))
         return INVCONV_ERR_WORKSPACE;
+    float *part = (float *)((char *)workspace + lay.dw_off);
     hipStream_t st = (hipStream_t)stream;
     if (int s = launch_conv(1, dLdy, w, dLdx, B, C, H, W, k, st))
         return s;
     if (dw_mfma_supported(C, k) && plan_dw_mfma(B, C, H, W, k).rt)
-        return launch_dw_mfma(x, dLdy, dLdw, (float *)workspace, p, B, C, H, W, k, st, 1.0f);
-    return launch_dw(x, dLdy, dLdw, (float *)workspace, p, B, C, H, W, k, st, 1.0f);
+        return launch_dw_mfma(x, dLdy, dLdw, part, p, B, C, H, W, k, st, 1.0f);
+    return launch_dw(x, dLdy, dLdw, part, p, B, C, H, W, k, st, 1.0f);
 }
 
 size_t invconv_bwd_workspace_bytes(int B, int C, int H, int W, int k)
 {
-    if (check_shape(B, C, H, W, k) != INVCONV_OK)
+    WsLayout lay;
+    if (check_shape(B, C, H, W, k) != INVCONV_OK || !ws_layout(B, C, H, W, k, true, &lay))
         return 0;
-    const DwPlan p = plan_dw_any(B, C, H, W, k);
-    return p.rt ? p.bytes : 0;
+    return lay.total;
 }
 
 invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx, float *dLdy, float *dLdw,
@@ -173,21 +265,23 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
         if (int s = check_supported(C, H, k))
             return s;
     const DwPlan p = plan_dw_any(B, C, H, W, k);
-    if (!p.rt)
+    WsLayout lay;
+    if (!p.rt || !ws_layout(B, C, H, W, k, true, &lay))
         return INVCONV_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < p.bytes)
+    if (!workspace || workspace_bytes < lay.total || ((size_t)workspace & 255))
         return INVCONV_ERR_WORKSPACE;
+    float *part = (float *)((char *)workspace + lay.dw_off);
     hipStream_t st = (hipStream_t)stream;
     if ((variant == INVCONV_VARIANT_AUTO || variant == INVCONV_VARIANT_WAVE) && bwd_wave_supported(C, H, W, k)) {
-        if (int s = launch_bwd_wave(x, w, dLdx, dLdy, (float *)workspace, B, C, H, W, k, st))
+        if (int s = launch_bwd_wave(x, w, dLdx, dLdy, part, B, C, H, W, k, st))
             return s;
-        return launch_dw_reduce((const float *)workspace, B, dLdw, C, k, st);
+        return launch_dw_reduce(part, B, dLdw, C, k, st);
     }
-    if (int s = solve(1, dLdx, w, dLdy, B, C, H, W, k, st, variant))
+    if (int s = solve(1, dLdx, w, dLdy, B, C, H, W, k, st, variant, solve_ws_of(workspace, lay)))
         return s;
     if (dw_mfma_supported(C, k) && plan_dw_mfma(B, C, H, W, k).rt)
-        return launch_dw_mfma(x, dLdy, dLdw, (float *)workspace, p, B, C, H, W, k, st);
-    return launch_dw(x, dLdy, dLdw, (float *)workspace, p, B, C, H, W, k, st);
+        return launch_dw_mfma(x, dLdy, dLdw, part, p, B, C, H, W, k, st);
+    return launch_dw(x, dLdy, dLdw, part, p, B, C, H, W, k, st);
 }
 
 invconv_status invconv_bwd(const float *x, const float *w, const float *dLdx, float *dLdy, float *dLdw, int B,
@@ -219,10 +313,10 @@ bool chain_layout(int L, int B, int C, int H, int W, int k, ChainLayout *lay)
     const DwPlan p = plan_dw_any(B, C, H, W, k);
     if (!p.rt)
         return false;
-    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
-    lay->flags_bytes = up(chain_flag_ints(L, B) * sizeof(int));
-    lay->grad_bytes = up((size_t)B * C * H * W * sizeof(float));
-    lay->dw_bytes = up(p.bytes) * (size_t)L;      // pass 1 of all layers runs as one launch
+    // header, progress counters, intermediate gradients, partial sums of dL/dw
+    lay->flags_bytes = kWsHeader + up256(chain_flag_ints(L, B) * sizeof(int));
+    lay->grad_bytes = up256((size_t)B * C * H * W * sizeof(float));
+    lay->dw_bytes = up256(p.bytes) * (size_t)L;      // pass 1 of all layers runs as one launch
     lay->total = lay->flags_bytes + (size_t)(L > 1 ? L - 1 : 0) * lay->grad_bytes + lay->dw_bytes;
     return true;
 }
@@ -256,7 +350,7 @@ invconv_status invconv_chain_fwd(const float *y, const float *const *w, float *c
     ChainLayout lay;
     if (!chain_layout(L, B, C, H, W, k, &lay))
         return INVCONV_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < lay.total)
+    if (!workspace || workspace_bytes < lay.total || ((size_t)workspace & 255))
         return INVCONV_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     if (chain_supported(L, C, H, W, k)) {
@@ -266,7 +360,8 @@ invconv_status invconv_chain_fwd(const float *y, const float *const *w, float *c
             a.w[l] = w[l];
             a.out[l] = x[l];
         }
-        a.flags = (int *)workspace;
+        a.flags = (int *)((char *)workspace + kWsHeader);
+        a.err = (int *)((char *)workspace + INVCONV_WS_ERROR_WORD_OFFSET);
         a.stages = L;
         a.B = B;
         a.H = H;
@@ -300,7 +395,7 @@ invconv_status invconv_chain_bwd(const float *const *x, const float *const *w, c
     ChainLayout lay;
     if (!chain_layout(L, B, C, H, W, k, &lay))
         return INVCONV_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < lay.total)
+    if (!workspace || workspace_bytes < lay.total || ((size_t)workspace & 255))
         return INVCONV_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
@@ -317,7 +412,8 @@ invconv_status invconv_chain_bwd(const float *const *x, const float *const *w, c
             a.w[s] = w[L - 1 - s];
             a.out[s] = v[L - 1 - s];
         }
-        a.flags = (int *)workspace;
+        a.flags = (int *)((char *)workspace + kWsHeader);
+        a.err = (int *)((char *)workspace + INVCONV_WS_ERROR_WORD_OFFSET);
         a.stages = L;
         a.B = B;
         a.H = H;

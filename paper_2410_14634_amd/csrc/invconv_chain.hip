@@ -81,7 +81,7 @@ constexpr int kCLead = kCAhead + 4;  // a group is fetched this many steps befor
 constexpr int kCPubLag = 2;       // a storer publishes a group this many steps after storing it
 constexpr int kCIo = 4;           // loader waves = storer waves
 constexpr int kCFlags = 8;        // progress counters per (stage, image): one per band
-constexpr int kCSpinLimit = 1 << 21;
+constexpr int kCSpinLimit = 1 << 21;   // polls (512 clocks apart) of a producer's counter before a loader gives up
 constexpr int kCDone = 1 << 30;   // progress value published when a stage has finished
 
 // 16 channels: a loader or storer wave has registers for one band only, so at most 4 bands (64 rows)
@@ -304,6 +304,7 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
         }
         int seen[kCIoBands];                             // producer progress known so far
         const int *pflag[kCIoBands];
+        bool lost = false;                               // a wait ran out: what is fetched from now on counts as NaN
 #pragma unroll
         for (int bi = 0; bi < kCIoBands; ++bi) {
             seen[bi] = (stage == 0 || a.flags == nullptr) ? kCDone : 0;
@@ -323,7 +324,7 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                         if (!edge[bi]) {
 #pragma unroll
                             for (int ch = 0; ch < C; ++ch) {
-                                const f32x4 v = lr[bi][ch];
+                                const f32x4 v = lr[bi][ch];     // (NaN after a lost wait, see below)
                                 float2 *d2 = reinterpret_cast<float2 *>(dst + ch * 16 * kCRow);
                                 d2[0] = float2{v[0], v[1]};
                                 d2[1] = float2{v[2], v[3]};
@@ -360,10 +361,13 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                                     if (v >= U + kCGroup)
                                         break;
                                     __builtin_amdgcn_s_sleep(8);
-                                } while (++spins < kCSpinLimit);
+                                } while (++spins < a.spin_limit);
                                 if (v < U + kCGroup) {
-                                    if (a.err)
-                                        a.err[0] = 1;       // bounded wait ran out: carry on, results are invalid
+                                    // bounded wait ran out: carry on without waiting again (every wave still
+                                    // finishes), feed NaN to the solve and tell the caller
+                                    if (a.err && lane == 0)
+                                        __hip_atomic_store(a.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                    lost = true;
                                     v = kCDone;
                                 }
                                 seen[bi] = v;
@@ -380,7 +384,9 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
 #pragma unroll
                             for (int ch = 0; ch < C; ++ch) {
                                 // device-coherent: another workgroup of this launch may have written it
-                                lr[bi][ch] = chain_load16(rin, off, plane_bytes * (unsigned)(DIR ? C - 1 - ch : ch));
+                                const f32x4 got = chain_load16(rin, off, plane_bytes * (unsigned)(DIR ? C - 1 - ch : ch));
+                                const float qn = __builtin_nanf("");
+                                lr[bi][ch] = lost ? f32x4{qn, qn, qn, qn} : got;
                             }
                         }
                     }
@@ -479,13 +485,11 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
             __hip_atomic_store(myflag[bi], kCDone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__global__ void k_chain_clear(int *flags, int nflags, int *err)
+__global__ void k_chain_clear(int *flags, int nflags)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < nflags)
         flags[i] = 0;
-    if (i == 0 && err)
-        err[0] = 0;
 }
 
 size_t chain_lds_bytes(int C, int k, int NB)
@@ -514,44 +518,66 @@ bool chain_single_preferred(int B, int C, int H)
     return live_per_xcd > 2.0e6 || (H > 80 && B >= 24);
 }
 
-size_t chain_flag_ints(int stages, int B) { return (size_t)stages * B * kCFlags + 64; }
+size_t chain_flag_ints(int stages, int B) { return (size_t)stages * B * kCFlags; }
 
+// A workgroup of stage s waits for the workgroup of stage s-1 of the same image, so a launch holds at most
+// as many workgroups as the device keeps resident at once: then nothing depends on the order in which the
+// hardware starts them.  A longer stack goes out as several launches of whole stages (a launch's first
+// stage reads what the launch before it has finished, without waiting); a batch that is too large for
+// even one launch of two stages goes out stage by stage, where no workgroup waits for another.
 template <int CG, int K>
-static int launch_chain_ck(int dir, const ChainArgs &args, int C, hipStream_t stream)
+static int launch_chain_ck(int dir, const ChainArgs &all, int C, hipStream_t stream)
 {
-    const size_t lds = chain_lds_bytes(C, K, args.NB);
+    const size_t lds = chain_lds_bytes(C, K, all.NB);
     const void *fn = dir ? reinterpret_cast<const void *>(&k_chain_band<CG, K, 1>)
                          : reinterpret_cast<const void *>(&k_chain_band<CG, K, 0>);
-    if (lds > 48 * 1024 &&
-        hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-        (void)hipGetLastError();
+    if (!ensure_dynamic_lds(fn, lds))
         return INVCONV_ERR_UNSUPPORTED;
+    const int threads = 64 * (all.NB + 2 * kCIo);
+    int per_launch = all.stages;                    // stages per launch
+    if (all.stages > 1) {
+        const int resident = resident_workgroups(fn, threads, lds);
+        per_launch = resident / all.B;
+        if (per_launch < 1)
+            per_launch = 1;
+        if (per_launch > all.stages)
+            per_launch = all.stages;
     }
-    const dim3 grid((unsigned)(args.stages * args.B)), block((unsigned)(64 * (args.NB + 2 * kCIo)));
-    if (dir)
-        hipLaunchKernelGGL((k_chain_band<CG, K, 1>), grid, block, lds, stream, args);
-    else
-        hipLaunchKernelGGL((k_chain_band<CG, K, 0>), grid, block, lds, stream, args);
-    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+    for (int s0 = 0; s0 < all.stages; s0 += per_launch) {
+        ChainArgs a = all;
+        a.stages = all.stages - s0 < per_launch ? all.stages - s0 : per_launch;
+        a.in0 = s0 == 0 ? all.in0 : all.out[s0 - 1];
+        for (int s = 0; s < a.stages; ++s) {
+            a.w[s] = all.w[s0 + s];
+            a.out[s] = all.out[s0 + s];
+        }
+        if (a.stages > 1) {
+            const int nflags = a.stages * a.B * kCFlags;
+            hipLaunchKernelGGL(k_chain_clear, dim3((nflags + 255) / 256), dim3(256), 0, stream, a.flags, nflags);
+            if (hipGetLastError() != hipSuccess)
+                return INVCONV_ERR_LAUNCH;
+        } else {
+            a.flags = nullptr;      // one stage: nothing to wait for, nothing to publish
+        }
+        const dim3 grid((unsigned)(a.stages * a.B)), block((unsigned)threads);
+        if (dir)
+            hipLaunchKernelGGL((k_chain_band<CG, K, 1>), grid, block, lds, stream, a);
+        else
+            hipLaunchKernelGGL((k_chain_band<CG, K, 0>), grid, block, lds, stream, a);
+        if (hipGetLastError() != hipSuccess)
+            return INVCONV_ERR_LAUNCH;
+    }
+    return INVCONV_OK;
 }
 
-// Runs `stages` solves as one pipelined launch.  args.flags (chain_flag_ints() ints; the last one is the
-// error word) is cleared first; it may be null only when stages == 1.
+// Runs `stages` solves as pipelined launches.  args.flags (chain_flag_ints() ints) may be null only when
+// stages == 1; args.err is the caller's error word or null.
 int launch_chain(int dir, ChainArgs args, int C, int k, hipStream_t stream)
 {
     if (!chain_supported(args.stages, C, args.H, args.W, k) || (args.stages > 1 && !args.flags))
         return INVCONV_ERR_VARIANT;
     args.NB = (args.H + 15) / 16;
-    if (args.flags) {
-        const int nflags = args.stages * args.B * kCFlags;
-        args.err = args.flags + nflags;
-        hipLaunchKernelGGL(k_chain_clear, dim3((nflags + 255) / 256), dim3(256), 0, stream, args.flags, nflags,
-                           args.err);
-        if (hipGetLastError() != hipSuccess)
-            return INVCONV_ERR_LAUNCH;
-    } else {
-        args.err = nullptr;
-    }
+    args.spin_limit = wait_budget(kCSpinLimit);
     if (C == 8) return launch_chain_ck<2, 3>(dir, args, C, stream);
     if (C == 12) return launch_chain_ck<3, 3>(dir, args, C, stream);
     if (C == 16) return launch_chain_ck<4, 3>(dir, args, C, stream);

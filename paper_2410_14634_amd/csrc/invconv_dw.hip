@@ -359,7 +359,7 @@ DwPlan plan_dw_mfma_layers(int layers, int B, int C, int H, int W, int k)
 }
 
 template <int NS>
-static void launch_ns(const DwBatch &batch, int layers, float *part, const DwPlan &p, int B, int C, int H, int W,
+static bool launch_ns(const DwBatch &batch, int layers, float *part, const DwPlan &p, int B, int C, int H, int W,
                       int k, hipStream_t stream)
 {
     // 16-byte tile loads need rows that start on 16-byte boundaries
@@ -370,12 +370,11 @@ static void launch_ns(const DwBatch &batch, int layers, float *part, const DwPla
     // streaming mode: the halo rows come from one chunk before, and a thread's share of a tile fits its registers
     if (vec && p.rt >= k - 1 && C * p.rt * (W / 4) <= 256 * kDwPre)
         vec = 2;
-    if (p.lds > 48 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_dw_partial_mfma<NS>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds) != hipSuccess)
-        return;     // the launch below then fails and reports it
+    if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_dw_partial_mfma<NS>), p.lds))
+        return false;
     hipLaunchKernelGGL(k_dw_partial_mfma<NS>, dim3((unsigned)(p.nparts * layers)), dim3(256), p.lds, stream, batch,
                        part, B, C, H, W, k, p.rt, p.nchunks, p.groups, vec, p.xw, p.sxc, p.svc);
+    return true;
 }
 
 // Pass 1 for `layers` independent (x, v) pairs in one launch; part holds layers * p.nparts rows.
@@ -383,19 +382,22 @@ static int launch_dw_partial_batch(const DwBatch &batch, int layers, float *part
                                    int H, int W, int k, hipStream_t stream)
 {
     const int ns = (C * k * k + 15) / 16;
+    bool ok = false;
     switch (ns) {
-    case 1: launch_ns<1>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 2: launch_ns<2>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 3: launch_ns<3>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 4: launch_ns<4>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 5: launch_ns<5>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 6: launch_ns<6>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 7: launch_ns<7>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 8: launch_ns<8>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 9: launch_ns<9>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 10: launch_ns<10>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 1: ok = launch_ns<1>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 2: ok = launch_ns<2>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 3: ok = launch_ns<3>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 4: ok = launch_ns<4>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 5: ok = launch_ns<5>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 6: ok = launch_ns<6>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 7: ok = launch_ns<7>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 8: ok = launch_ns<8>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 9: ok = launch_ns<9>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 10: ok = launch_ns<10>(batch, layers, part, p, B, C, H, W, k, stream); break;
     default: return INVCONV_ERR_UNSUPPORTED;
     }
+    if (!ok)
+        return INVCONV_ERR_UNSUPPORTED;
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

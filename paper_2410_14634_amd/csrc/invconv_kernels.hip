@@ -4,10 +4,93 @@
 // anti-diagonal comparison variant.  gfx950 only.
 #include <hip/hip_cooperative_groups.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "invconv_common.h"
 #include "invconv_launch.h"
 
 namespace invconv {
+
+// ---------------------------------------------------------------------------
+// Host-side caches of what the runtime says about a kernel
+// ---------------------------------------------------------------------------
+namespace {
+struct LdsLimit { int dev; const void *fn; size_t bytes; };
+struct Residency { int dev; const void *fn; int threads; size_t lds; int count; };
+// fixed tables (no heap): a full table only means the runtime is asked again
+constexpr int kCacheSlots = 512;
+std::mutex g_cache_mutex;
+LdsLimit g_lds_limits[kCacheSlots];
+Residency g_residency[kCacheSlots];
+int g_n_lds_limits = 0, g_n_residency = 0;
+std::atomic<int> g_wait_budget{0};
+}  // namespace
+
+bool ensure_dynamic_lds(const void *fn, size_t bytes)
+{
+    if (bytes <= 48 * 1024)
+        return true;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    for (int i = 0; i < g_n_lds_limits; ++i) {
+        LdsLimit &e = g_lds_limits[i];
+        if (e.dev == dev && e.fn == fn) {
+            if (e.bytes >= bytes)
+                return true;
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
+                (void)hipGetLastError();
+                return false;
+            }
+            e.bytes = bytes;
+            return true;
+        }
+    }
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    if (g_n_lds_limits < kCacheSlots)
+        g_lds_limits[g_n_lds_limits++] = LdsLimit{dev, fn, bytes};
+    return true;
+}
+
+int resident_workgroups(const void *fn, int threads, size_t lds)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    for (int i = 0; i < g_n_residency; ++i) {
+        const Residency &e = g_residency[i];
+        if (e.dev == dev && e.fn == fn && e.threads == threads && e.lds == lds)
+            return e.count;
+    }
+    int cus = 0, per_cu = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, threads, lds) != hipSuccess || cus < 1 ||
+        per_cu < 1) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    if (g_n_residency < kCacheSlots)
+        g_residency[g_n_residency++] = Residency{dev, fn, threads, lds, cus * per_cu};
+    return cus * per_cu;
+}
+
+int wait_budget(int standard)
+{
+    const int v = g_wait_budget.load(std::memory_order_relaxed);
+    return v > 0 ? v : standard;
+}
+
+void set_wait_budget(int polls) { g_wait_budget.store(polls > 0 ? polls : 0, std::memory_order_relaxed); }
 
 // ---------------------------------------------------------------------------
 // Wavefront solve, one workgroup per image (Section 3.3: anti-diagonals in
@@ -346,13 +429,8 @@ static int launch_solve_block_dir(const float *in, const float *w, float *out, i
     const size_t lds = solve_block_lds_bytes(C, H, k);
     if (lds > kMaxLdsBytes)
         return INVCONV_ERR_UNSUPPORTED;
-    if (lds > 48 * 1024) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_solve_block<DIR>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-            (void)hipGetLastError();
-            return INVCONV_ERR_UNSUPPORTED;
-        }
-    }
+    if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_solve_block<DIR>), lds))
+        return INVCONV_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(k_solve_block<DIR>, dim3(B), dim3(kSolveBlock), lds, stream, in, w, out, C, H, W, k);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }

@@ -4,6 +4,7 @@
 #include <stddef.h>
 
 #include "invconv.h"
+#include "invconv_probe.h"
 
 namespace invconv {
 
@@ -12,6 +13,26 @@ constexpr int kDwBlock = 256;
 constexpr size_t kMaxLdsBytes = 160 * 1024;   // LDS per workgroup on gfx950
 constexpr size_t kDwLdsBudget = 40 * 1024;
 constexpr int kChainMaxLayers = 16;
+
+// Sets the dynamic-LDS limit of kernel `fn` to at least `bytes` on the current device; the runtime is asked
+// once per (device, kernel) and size step, not on every launch.  False if the runtime refuses.
+bool ensure_dynamic_lds(const void *fn, size_t bytes);
+// Workgroups of kernel `fn` (block of `threads`, `lds` bytes of dynamic LDS) that the current device holds
+// at the same time; cached.  0 if the runtime cannot tell.
+int resident_workgroups(const void *fn, int threads, size_t lds);
+// Polls a bounded wait makes before it gives up: `standard` unless invconv_set_wait_budget() has set another.
+int wait_budget(int standard);
+void set_wait_budget(int polls);   // 0 restores the standard budgets
+
+// Scratch a caller handed in for one solve.  `base` points behind the workspace header (256-byte aligned),
+// `err` at the header's error word; all null / 0 when the call has no workspace.
+struct SolveWs {
+    char *base = nullptr;
+    size_t bytes = 0;
+    int *err = nullptr;
+};
+// Bytes of SolveWs the automatic kernel choice can use for this shape (0: none)
+size_t solve_ws_bytes(int B, int C, int H, int W, int k);
 
 struct DwPlan {
     int rt;          // rows per chunk (0 = shape unsupported)
@@ -42,7 +63,8 @@ bool wave_split_preferred(int B, int H, int W, int k);
 bool wave_tile_preferred(int B, int C, int H, int W);
 bool wave_bands_supported(int C, int H, int W, int k);
 int launch_solve_wave_bands(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                            hipStream_t stream);
+                            hipStream_t stream, SolveWs ws = SolveWs{});
+size_t wave_bands_ws_bytes(int B, int C, int H, int W, int k);
 int launch_bwd_wave(const float *x, const float *w, const float *g, float *v, float *part, int B, int C, int H,
                     int W, int k, hipStream_t stream);
 // sign: -1 for the inverse convolution's dL/dw (Theorem 2), +1 for the convolution's own
@@ -71,8 +93,9 @@ struct ChainArgs {
     const float *in0;                    // input of stage 0
     const float *w[kChainMaxLayers];     // kernel of stage s
     float *out[kChainMaxLayers];         // output of stage s = input of stage s+1
-    int *flags;                          // progress counters + error word (chain_flag_ints() ints)
-    int *err;                            // set by launch_chain
+    int *flags;                          // progress counters (chain_flag_ints() ints)
+    int *err;                            // error word (may be null): set to 1 when a bounded wait ran out
+    int spin_limit;                      // set by launch_chain
     int stages, B, H, W, NB;
 };
 bool chain_supported(int stages, int C, int H, int W, int k);

@@ -123,8 +123,9 @@ struct WaveBands {
     int *prog_out;          // local steps of this band whose entries are in log_out
     int log_steps;      // entries per band, a multiple of kWavePF
     f32x4 *scratch;     // [64][K - 1] write-only dump for the lanes that have nothing to send
+    int spin_limit;     // polls of prog_in before a waiting band gives up
+    int *err;           // device error word (may be null): set to 1 when a wait ran out
 };
-constexpr int kBandSpinLimit = 1 << 22;
 
 // Body of the solve for image n, executed by one full wave (lanes 0..63 of the
 // calling workgroup).  With LDS_COPY the result is also written to lds_copy as a
@@ -168,7 +169,12 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
     auto ld = [&](int ch, unsigned off) -> float {
         return *reinterpret_cast<const float *>((TILE ? chan_lds[ch] : chan_src[ch]) + off);
     };
+    // A band whose bounded wait for the band above ran out has no valid input any more: from then on it
+    // stores NaN instead of results, so that a lost hand-over can never pass for a solution.
+    bool lost = false;
     auto st = [&](int ch, unsigned off, float v) {
+        if (BANDS)
+            v = lost ? __builtin_nanf("") : v;
         if (!TILE)
             *reinterpret_cast<float *>(chan_dst[ch] + off) = v;
         if (LDS_COPY || TILE)
@@ -240,14 +246,19 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
     for (int a = 0; a < K; ++a)
         M[a] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int t0 = 0; t0 < nsteps; t0 += kWavePF) {
-        if (recv) {
+        if (recv && !lost) {
             // entries t0 + 63 .. t0 + 63 + kWavePF - 1 of the upper band's log are needed
             int need = t0 + 64 + kWavePF;
             need = need > wb.log_steps ? wb.log_steps : need;
             int spins = 0;
             while (__hip_atomic_load(wb.prog_in, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < need &&
-                   ++spins < kBandSpinLimit)
+                   ++spins < wb.spin_limit)
                 __builtin_amdgcn_s_sleep(1);
+            if (__hip_atomic_load(wb.prog_in, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < need) {
+                lost = true;        // the wait ran out: carry on (every wave still finishes), results are NaN
+                if (wb.err && r == 0)
+                    __hip_atomic_store(wb.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         // Entry of the first step now, the others one step ahead of their use (volatile: the read is
         // issued where it is written, well before the value is needed).
@@ -609,10 +620,13 @@ __global__ __launch_bounds__(256) void k_solve_wave_split(const float *__restric
 // Images of 65 .. 512 rows: one workgroup per image, one wave per band of 64 rows.
 template <int C, int K, int DIR>
 __global__ __launch_bounds__(512) void k_solve_wave_bands(const float *__restrict__ in, const float *__restrict__ w,
-                                                         float *__restrict__ out, int H, int W, int log_steps)
+                                                         float *__restrict__ out, int H, int W, int log_steps,
+                                                         int spin_limit, int *err)
 {
     extern __shared__ float smem[];
     WaveBands wb;
+    wb.spin_limit = spin_limit;
+    wb.err = err;
     wb.band = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     wb.nbands = blockDim.x >> 6;
     f32x4 *log = reinterpret_cast<f32x4 *>(smem);        // [nbands - 1][log_steps][K - 1]
@@ -637,12 +651,11 @@ __global__ __launch_bounds__(512) void k_solve_wave_bands(const float *__restric
 // other memory operations in flight, so that wait is exact) and fetches what the band above has published
 // into the local log, then advances the local counter the solve waits on.  A workgroup waits only for the
 // one of the band above, which has a lower block index; every wait is bounded.
-constexpr int kCourierSpinLimit = 1 << 22;
 template <int C, int K, int DIR>
 __global__ __launch_bounds__(128) void k_solve_wave_bands_multi(const float *__restrict__ in,
                                                                const float *__restrict__ w, float *__restrict__ out,
                                                                int B, int H, int W, int log_steps, int *gcount,
-                                                               f32x4 *glog)
+                                                               f32x4 *glog, int spin_limit, int *err)
 {
     extern __shared__ float smem[];
     const int nb = (H + 63) >> 6;
@@ -665,6 +678,8 @@ __global__ __launch_bounds__(128) void k_solve_wave_bands_multi(const float *__r
         wb.prog_out = prog + 1;
         wb.log_steps = log_steps;
         wb.scratch = scratch;
+        wb.spin_limit = spin_limit;
+        wb.err = err;
         solve_wave_body<C, K, DIR, false, true>(in, w, out, H, W, n, nullptr, wb);
         return;
     }
@@ -683,7 +698,7 @@ __global__ __launch_bounds__(128) void k_solve_wave_bands_multi(const float *__r
         const_cast<void *>(reinterpret_cast<const void *>(g_in)), 0, (int)seg_bytes, 0x00020000);
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
     int sent = 0, got = 0, spins = 0;
-    while ((sent < send_total || got < recv_total) && spins < kCourierSpinLimit) {
+    while ((sent < send_total || got < recv_total) && spins < spin_limit) {
         bool moved = false;
         if (sent < send_total) {
             int have = __hip_atomic_load(prog + 1, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -731,6 +746,10 @@ __global__ __launch_bounds__(128) void k_solve_wave_bands_multi(const float *__r
             ++spins;
         }
     }
+    // gave up with entries still to carry: the solving waves that depend on them run out of their own
+    // waits and store NaN; the error word tells the caller
+    if ((sent < send_total || got < recv_total) && err && lane == 0)
+        __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ void k_wave_bands_clear(int *gcount, int count)
@@ -976,11 +995,8 @@ static int launch_wave_ck(int dir, const float *in, const float *w, float *out, 
     if (wave_tile_preferred(B, C, H, W) && (((size_t)in | (size_t)out) & 15) == 0) {
         const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave_tile<C, K, 1>)
                              : reinterpret_cast<const void *>(&k_solve_wave_tile<C, K, 0>);
-        if (tile_bytes > 48 * 1024 &&
-            hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)tile_bytes) != hipSuccess) {
-            (void)hipGetLastError();
+        if (!ensure_dynamic_lds(fn, tile_bytes))
             return INVCONV_ERR_UNSUPPORTED;
-        }
         if (dir)
             hipLaunchKernelGGL((k_solve_wave_tile<C, K, 1>), dim3(B), dim3(64), tile_bytes, stream, in, w, out, H, W);
         else
@@ -995,11 +1011,8 @@ static int launch_wave_ck(int dir, const float *in, const float *w, float *out, 
             lds = (kMaxLdsBytes / cap) & ~(size_t)255;
             const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave<C, K, 1>)
                                  : reinterpret_cast<const void *>(&k_solve_wave<C, K, 0>);
-            if (lds > 48 * 1024 &&
-                hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-                (void)hipGetLastError();
+            if (!ensure_dynamic_lds(fn, lds))
                 lds = 0;
-            }
         }
     }
     if (dir)
@@ -1017,77 +1030,87 @@ static size_t wave_bands_lds_bytes(int H, int W, int k)
     return ((nb - 1) * (size_t)wave_bands_log_steps(W) + 64) * (k - 1) * sizeof(f32x4) + nb * sizeof(int);
 }
 
+constexpr int kBandSpinLimit = 1 << 22;       // polls of an LDS counter (64 clocks apart)
+constexpr int kCourierSpinLimit = 1 << 22;    // idle rounds of a courier wave
+
 template <int C, int K>
 static int launch_wave_bands_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
-                                hipStream_t stream)
+                                hipStream_t stream, int *err)
 {
     const int nb = (H + 63) / 64, log_steps = wave_bands_log_steps(W);
     const size_t lds = wave_bands_lds_bytes(H, W, K);
-    if (lds > 128 * 1024)       // reached only as the fall-back of the multi-workgroup launch
+    if (lds > 128 * 1024)       // reached only when the multi-workgroup launch has no workspace to put its logs in
         return launch_solve_block(dir, in, w, out, B, C, H, W, K, stream);
     const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave_bands<C, K, 1>)
                          : reinterpret_cast<const void *>(&k_solve_wave_bands<C, K, 0>);
-    if (lds > 48 * 1024 && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-        (void)hipGetLastError();
+    if (!ensure_dynamic_lds(fn, lds))
         return INVCONV_ERR_UNSUPPORTED;
-    }
+    const int spin = wait_budget(kBandSpinLimit);
     if (dir)
         hipLaunchKernelGGL((k_solve_wave_bands<C, K, 1>), dim3(B), dim3(64 * nb), lds, stream, in, w, out, H, W,
-                           log_steps);
+                           log_steps, spin, err);
     else
         hipLaunchKernelGGL((k_solve_wave_bands<C, K, 0>), dim3(B), dim3(64 * nb), lds, stream, in, w, out, H, W,
-                           log_steps);
+                           log_steps, spin, err);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
-// Bands on different compute units (k_solve_wave_bands_multi).  The logs between workgroups live in
-// device memory that this launch takes from, and returns to, the stream's memory pool (no call
-// synchronises); a stream that is being captured, or a pool that refuses, gets the one-workgroup kernel.
+// Bands on different compute units (k_solve_wave_bands_multi).  The logs and counters between workgroups
+// live in the caller's workspace.  A band's workgroup waits for the one of the band above, so the images
+// go out in launches of at most as many workgroups as the device holds at once: inside a launch nothing
+// depends on the order in which the hardware starts workgroups.
+static size_t wave_bands_multi_ws_per_image(int H, int W, int k)
+{
+    const size_t nb = (H + 63) / 64;
+    return (nb - 1) * ((size_t)wave_bands_log_steps(W) * (k - 1) * sizeof(f32x4) + 256);
+}
+
 template <int C, int K>
 static int launch_wave_bands_multi_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
-                                      hipStream_t stream)
+                                      hipStream_t stream, SolveWs ws)
 {
     const int nb = (H + 63) / 64, log_steps = wave_bands_log_steps(W);
-    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
-        (void)hipGetLastError();
-        return launch_wave_bands_ck<C, K>(dir, in, w, out, B, H, W, stream);
-    }
     const size_t seg = (size_t)log_steps * (K - 1);
-    const size_t ncnt = (size_t)B * (nb - 1);
-    const size_t cnt_bytes = (ncnt * sizeof(int) + 255) / 256 * 256;
-    const size_t bytes = cnt_bytes + ncnt * seg * sizeof(f32x4);
-    void *scratch = nullptr;
-    if (hipMallocAsync(&scratch, bytes, stream) != hipSuccess || !scratch) {
-        (void)hipGetLastError();
-        return launch_wave_bands_ck<C, K>(dir, in, w, out, B, H, W, stream);
-    }
-    int *gcount = static_cast<int *>(scratch);
-    f32x4 *glog = reinterpret_cast<f32x4 *>(static_cast<char *>(scratch) + cnt_bytes);
     const size_t lds = (2 * seg + 64 * (K - 1)) * sizeof(f32x4) + 2 * sizeof(int);
     const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave_bands_multi<C, K, 1>)
                          : reinterpret_cast<const void *>(&k_solve_wave_bands_multi<C, K, 0>);
-    int status = INVCONV_OK;
-    if (lds > 48 * 1024 && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-        (void)hipGetLastError();
-        status = INVCONV_ERR_UNSUPPORTED;
-    } else {
-        hipLaunchKernelGGL(k_wave_bands_clear, dim3((unsigned)((ncnt + 255) / 256)), dim3(256), 0, stream, gcount,
-                           (int)ncnt);
-        const dim3 grid((unsigned)(B * nb));       // band-major: a band's workgroups come after those it waits for
+    if (!ensure_dynamic_lds(fn, lds))
+        return INVCONV_ERR_UNSUPPORTED;
+    const int resident = resident_workgroups(fn, 128, lds);
+    int per_launch = resident / nb;                 // images per launch
+    if (per_launch < 1)
+        return launch_wave_bands_ck<C, K>(dir, in, w, out, B, H, W, stream, ws.err);
+    if (per_launch > B)
+        per_launch = B;
+    // workspace: counters of all images of a launch, then their logs; launches follow each other on the
+    // stream, so they share the space, and a small workspace only means more launches
+    const size_t per_image = wave_bands_multi_ws_per_image(H, W, K);
+    const size_t fit = ws.base ? ws.bytes / per_image : 0;
+    if ((size_t)per_launch > fit)
+        per_launch = (int)fit;
+    if (per_launch < 1)
+        return launch_wave_bands_ck<C, K>(dir, in, w, out, B, H, W, stream, ws.err);
+    const size_t ncnt = (size_t)per_launch * (nb - 1);
+    const size_t cnt_bytes = (ncnt * sizeof(int) + 255) / 256 * 256;     // at most 256 bytes per counter: fits
+    int *gcount = reinterpret_cast<int *>(ws.base);
+    f32x4 *glog = reinterpret_cast<f32x4 *>(ws.base + cnt_bytes);
+    const int spin_courier = wait_budget(kCourierSpinLimit);
+    const size_t img = (size_t)C * H * W;
+    for (int n0 = 0; n0 < B; n0 += per_launch) {
+        const int nimg = B - n0 < per_launch ? B - n0 : per_launch;
+        const int cnt = nimg * (nb - 1);
+        hipLaunchKernelGGL(k_wave_bands_clear, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, stream, gcount, cnt);
+        const dim3 grid((unsigned)(nimg * nb));    // band-major: a band's workgroups come after those it waits for
         if (dir)
-            hipLaunchKernelGGL((k_solve_wave_bands_multi<C, K, 1>), grid, dim3(128), lds, stream, in, w, out, B, H, W,
-                               log_steps, gcount, glog);
+            hipLaunchKernelGGL((k_solve_wave_bands_multi<C, K, 1>), grid, dim3(128), lds, stream, in + n0 * img, w,
+                               out + n0 * img, nimg, H, W, log_steps, gcount, glog, spin_courier, ws.err);
         else
-            hipLaunchKernelGGL((k_solve_wave_bands_multi<C, K, 0>), grid, dim3(128), lds, stream, in, w, out, B, H, W,
-                               log_steps, gcount, glog);
-        status = hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+            hipLaunchKernelGGL((k_solve_wave_bands_multi<C, K, 0>), grid, dim3(128), lds, stream, in + n0 * img, w,
+                               out + n0 * img, nimg, H, W, log_steps, gcount, glog, spin_courier, ws.err);
+        if (hipGetLastError() != hipSuccess)
+            return INVCONV_ERR_LAUNCH;
     }
-    if (hipFreeAsync(scratch, stream) != hipSuccess) {
-        (void)hipGetLastError();
-        status = status == INVCONV_OK ? INVCONV_ERR_LAUNCH : status;
-    }
-    return status;
+    return INVCONV_OK;
 }
 
 // Several compute units per image pay while there are compute units to spare and an image has at least
@@ -1271,19 +1294,11 @@ static int launch_bwd_wave_ck(const float *x, const float *w, const float *g, fl
 {
     const size_t lds = bwd_wave_lds_bytes(C, H, W, K);
     constexpr bool kSplit = K >= 5;
-    if (lds > 48 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_wave<C, K, kSplit>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-        (void)hipGetLastError();
+    if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_bwd_wave<C, K, kSplit>), lds))
         return INVCONV_ERR_UNSUPPORTED;
-    }
     if (!kSplit && wave_tile_preferred(B, C, H, W) && (((size_t)g | (size_t)v) & 15) == 0) {
-        if (lds > 48 * 1024 &&
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_wave<C, K, false, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-            (void)hipGetLastError();
+        if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_bwd_wave<C, K, false, true>), lds))
             return INVCONV_ERR_UNSUPPORTED;
-        }
         hipLaunchKernelGGL((k_bwd_wave<C, K, false, true>), dim3(B), dim3(256), lds, stream, x, w, g, v, part, H, W);
         return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
     }
@@ -1293,12 +1308,8 @@ static int launch_bwd_wave_ck(const float *x, const float *w, const float *g, fl
         // at most four per row, so that a helper wave keeps up with one group per step)
         const size_t lds8 = bwd_wave8_lds_bytes(C, H, W, K);
         if (B <= 256 && (W & 15) == 0 && W <= 64 && lds8 <= kMaxLdsBytes) {
-            if (lds8 > 48 * 1024 &&
-                hipFuncSetAttribute(reinterpret_cast<const void *>(&k_bwd_wave8<C, K>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds8) != hipSuccess) {
-                (void)hipGetLastError();
+            if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_bwd_wave8<C, K>), lds8))
                 return INVCONV_ERR_UNSUPPORTED;
-            }
             hipLaunchKernelGGL((k_bwd_wave8<C, K>), dim3(B), dim3(512), lds8, stream, x, w, g, v, part, H, W);
             return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
         }
@@ -1375,24 +1386,34 @@ int launch_solve_wave_split(int dir, const float *in, const float *w, float *out
     return INVCONV_ERR_VARIANT;
 }
 
+// What the multi-workgroup launch wants for this shape: logs and counters of up to 2048 workgroups at once
+size_t wave_bands_ws_bytes(int B, int C, int H, int W, int k)
+{
+    if (!wave_bands_supported(C, H, W, k) || !wave_bands_multi_preferred(B, H, W, k))
+        return 0;
+    const size_t nb = (H + 63) / 64;
+    const size_t most = 2048 / nb < 1 ? 1 : 2048 / nb;
+    return ((size_t)B < most ? (size_t)B : most) * wave_bands_multi_ws_per_image(H, W, k);
+}
+
 int launch_solve_wave_bands(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                            hipStream_t stream)
+                            hipStream_t stream, SolveWs ws)
 {
     if (!wave_bands_supported(C, H, W, k))
         return INVCONV_ERR_VARIANT;
     const bool multi = wave_bands_multi_preferred(B, H, W, k);
-    if (C == 3 && k == 3) return multi ? launch_wave_bands_multi_ck<3, 3>(dir, in, w, out, B, H, W, stream)
-                                  : launch_wave_bands_ck<3, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 2) return multi ? launch_wave_bands_multi_ck<3, 2>(dir, in, w, out, B, H, W, stream)
-                                  : launch_wave_bands_ck<3, 2>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 5) return multi ? launch_wave_bands_multi_ck<3, 5>(dir, in, w, out, B, H, W, stream)
-                                  : launch_wave_bands_ck<3, 5>(dir, in, w, out, B, H, W, stream);
-    if (C == 1 && k == 3) return multi ? launch_wave_bands_multi_ck<1, 3>(dir, in, w, out, B, H, W, stream)
-                                  : launch_wave_bands_ck<1, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 2 && k == 3) return multi ? launch_wave_bands_multi_ck<2, 3>(dir, in, w, out, B, H, W, stream)
-                                  : launch_wave_bands_ck<2, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 4 && k == 3) return multi ? launch_wave_bands_multi_ck<4, 3>(dir, in, w, out, B, H, W, stream)
-                                  : launch_wave_bands_ck<4, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 3) return multi ? launch_wave_bands_multi_ck<3, 3>(dir, in, w, out, B, H, W, stream, ws)
+                                  : launch_wave_bands_ck<3, 3>(dir, in, w, out, B, H, W, stream, ws.err);
+    if (C == 3 && k == 2) return multi ? launch_wave_bands_multi_ck<3, 2>(dir, in, w, out, B, H, W, stream, ws)
+                                  : launch_wave_bands_ck<3, 2>(dir, in, w, out, B, H, W, stream, ws.err);
+    if (C == 3 && k == 5) return multi ? launch_wave_bands_multi_ck<3, 5>(dir, in, w, out, B, H, W, stream, ws)
+                                  : launch_wave_bands_ck<3, 5>(dir, in, w, out, B, H, W, stream, ws.err);
+    if (C == 1 && k == 3) return multi ? launch_wave_bands_multi_ck<1, 3>(dir, in, w, out, B, H, W, stream, ws)
+                                  : launch_wave_bands_ck<1, 3>(dir, in, w, out, B, H, W, stream, ws.err);
+    if (C == 2 && k == 3) return multi ? launch_wave_bands_multi_ck<2, 3>(dir, in, w, out, B, H, W, stream, ws)
+                                  : launch_wave_bands_ck<2, 3>(dir, in, w, out, B, H, W, stream, ws.err);
+    if (C == 4 && k == 3) return multi ? launch_wave_bands_multi_ck<4, 3>(dir, in, w, out, B, H, W, stream, ws)
+                                  : launch_wave_bands_ck<4, 3>(dir, in, w, out, B, H, W, stream, ws.err);
     return INVCONV_ERR_VARIANT;
 }
 

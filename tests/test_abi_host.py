@@ -13,9 +13,12 @@ FAKE = [0x10000 * (i + 1) for i in range(8)]   # never dereferenced: every call 
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "invconv.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(invconv_[a-z_]+)\s*\(", text)))
+    import glob
+    names = set()
+    for path in glob.glob(os.path.join(ROOT, "include", "*.h")):
+        text = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)
+        names.update(re.findall(r"\b(invconv_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -86,6 +89,24 @@ def test_bwd_rejects_bad_arguments():
     assert L.invconv_bwd(x, w, g, v, dw, *shape, ws, need - 1, None) == b.ERR_WORKSPACE
     assert L.invconv_bwd_ex(x, w, g, v, dw, *shape, ws, need, None, -1) == b.ERR_VARIANT
     assert b.bwd_workspace_bytes(0, 3, 8, 8, 3) == 0
+
+
+def test_workspace_taking_calls_reject_bad_workspaces():
+    L = b.lib()
+    y, w, x, g, v, dw, ws = FAKE[:7]
+    shape = (2, 3, 256, 256, 3)             # tall few-channel images: the solve can use scratch
+    need = b.fwd_workspace_bytes(*shape)
+    assert need > 256 and need % 256 == 0
+    assert b.fwd_workspace_bytes(2, 3, 8, 8, 3) == 256          # header only
+    assert b.fwd_workspace_bytes(2, 3, 8, 0, 3) == 0
+    assert b.bwd_workspace_bytes(*shape) > need                  # the solve's share plus the dL/dw partial sums
+    assert L.invconv_fwd_ws(y, w, x, *shape, None, need, None) == b.ERR_WORKSPACE
+    assert L.invconv_fwd_ws(y, w, x, *shape, ws, need - 1, None) == b.ERR_WORKSPACE
+    assert L.invconv_fwd_ws(y, w, x, *shape, ws + 16, need, None) == b.ERR_WORKSPACE     # not 256-byte aligned
+    assert L.invconv_fwd_ws(None, w, x, *shape, ws, need, None) == b.ERR_NULL
+    assert L.invconv_fwd_ws(y, w, y, *shape, ws, need, None) == b.ERR_ALIAS
+    assert L.invconv_bwd(x, w, g, v, dw, 2, 3, 8, 8, 3, ws + 16, 1 << 20, None) == b.ERR_WORKSPACE
+    assert L.invconv_workspace_error(None, None, None) == b.ERR_NULL
 
 
 def test_logdet_rejects_bad_arguments():

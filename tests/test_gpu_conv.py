@@ -23,6 +23,10 @@ CONV_SHAPES = [  # (B, C, H, W, k)
 ]
 
 
+# more tiles than the launch has workgroups: every workgroup walks several tiles (LDS reuse, XCD sweep)
+MANY_TILE_SHAPES = [(300, 3, 64, 64, 3), (260, 12, 64, 64, 3), (1100, 2, 16, 40, 5)]
+
+
 def check_conv(x, w):
     import torch
     y = b.invconv_conv_fwd(dev(x), dev(w))
@@ -64,6 +68,28 @@ def test_conv_bwd_edge_shapes(shape):
     print(f"conv bwd edge {shape}", flush=True)
     cs = inputs.make_case(B, C, H, W, k, seed=sum(shape) + 3, tap_std=0.05)
     check_conv_bwd(cs["y"], cs["w"][0], cs["g"])
+
+
+@pytest.mark.parametrize("shape", MANY_TILE_SHAPES)
+def test_conv_fwd_and_bwd_with_more_tiles_than_workgroups(shape):
+    B, C, H, W, k = shape
+    print(f"conv many tiles {shape}", flush=True)
+    cs = inputs.make_case(B, C, H, W, k, seed=sum(shape) + 5, tap_std=0.05)
+    check_conv(cs["y"], cs["w"][0])
+    check_conv_bwd(cs["y"], cs["w"][0], cs["g"])
+
+
+def test_conv_masked_garbage_at_twelve_channels():
+    cs = inputs.make_case(3, 12, 40, 36, 3, seed=8, tap_std=0.05)
+    w = cs["w"][0].copy()
+    y0 = check_conv(cs["y"], w)
+    dx0, dw0 = check_conv_bwd(cs["y"], w, cs["g"])
+    iu = np.triu_indices(12, 1)
+    w[:, :, 2, 2][iu] = 1e6
+    y1 = check_conv(cs["y"], w)
+    dx1, dw1 = check_conv_bwd(cs["y"], w, cs["g"])
+    assert np.array_equal(y0, y1) and np.array_equal(dx0, dx1) and np.array_equal(dw0, dw1)
+    assert np.all(dw1[:, :, 2, 2][iu] == 0.0)
 
 
 def test_conv_bwd_masked_entries_get_zero_gradient_and_are_ignored():
