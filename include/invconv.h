@@ -158,6 +158,23 @@ invconv_status invconv_bwd(const float *x, const float *w, const float *dLdx,
 size_t invconv_bwd_workspace_bytes(int B, int C, int H, int W, int k);
 
 /*
+ * invconv_bwd for callers that cannot allocate device memory and have no workspace to pass: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same results;
+ * the scratch is an array of INVCONV_STATIC_SCRATCH_BYTES bytes that the library holds in the memory of
+ * every device it is loaded on until the process ends.  The call allocates and frees nothing.
+ *   - Shapes whose invconv_bwd_workspace_bytes() exceeds INVCONV_STATIC_SCRATCH_BYTES are refused with
+ *     INVCONV_ERR_WORKSPACE before anything is launched.
+ *   - All calls on one device share that device's array: calls that overlap in time on one device (two
+ *     streams, two threads) RACE on it and give undefined dLdw.  Calls that follow each other on one
+ *     stream are fine: nothing is expected to survive from one call to the next.
+ *   - The array's header (its error word) starts as 0 and is only ever set, as for any workspace.
+ */
+#define INVCONV_STATIC_SCRATCH_BYTES (8u << 20)
+invconv_status invconv_bwd_static(const float *x, const float *w, const float *dLdx,
+                                  float *dLdy, float *dLdw,
+                                  int B, int C, int H, int W, int k, void *stream);
+
+/*
  * log |det dx/dy| of the inverse convolution for ONE H x W image (Section 4):
  * the Jacobian is triangular, so this is -H*W*sum_c log|w[c][c][k-1][k-1]|,
  * exactly 0 for the paper's unit diagonal.  Independent of the data and of B.

@@ -26,6 +26,7 @@ EXPORTS = (
     "invconv_probe_step_sync", "invconv_chain_fwd", "invconv_chain_bwd", "invconv_chain_workspace_bytes",
     "invconv_chain_logdet", "invconv_conv_fwd", "invconv_conv_bwd",
     "invconv_fwd_ws", "invconv_fwd_workspace_bytes", "invconv_workspace_error", "invconv_set_wait_budget",
+    "invconv_bwd_static",
 )
 WS_HEADER_BYTES = 256
 
@@ -77,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.invconv_workspace_error.restype = ci
         L.invconv_set_wait_budget.argtypes = [ci]
         L.invconv_set_wait_budget.restype = None
+        L.invconv_bwd_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.invconv_bwd_static.restype = ci
         L.invconv_status_string.argtypes = [ci]
         L.invconv_status_string.restype = ctypes.c_char_p
         L.invconv_version.restype = ci
@@ -161,6 +164,19 @@ def invconv_fwd(y: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = Non
     if st != OK:
         raise InvconvError(st, "invconv_fwd")
     return x
+
+
+def invconv_bwd_static(x: torch.Tensor, w: torch.Tensor, dLdx: torch.Tensor,
+                       out: tuple[torch.Tensor, torch.Tensor]):
+    """invconv_bwd on the library's own scratch: allocates nothing (outputs must be passed in)."""
+    _check(x, "x"), _check(w, "w"), _check(dLdx, "dLdx", x.shape)
+    B, C, H, W, k = _dims(x, w)
+    dLdy, dLdw = _check(out[0], "out[0]", x.shape), _check(out[1], "out[1]", w.shape)
+    st = lib().invconv_bwd_static(x.data_ptr(), w.data_ptr(), dLdx.data_ptr(), dLdy.data_ptr(), dLdw.data_ptr(),
+                                  B, C, H, W, k, _stream())
+    if st != OK:
+        raise InvconvError(st, "invconv_bwd_static")
+    return dLdy, dLdw
 
 
 def invconv_bwd(x: torch.Tensor, w: torch.Tensor, dLdx: torch.Tensor,

@@ -1,4 +1,6 @@
 // C ABI of the inverse-convolution library: argument validation and dispatch.
+#include <mutex>
+
 #include "invconv_launch.h"
 
 namespace invconv {
@@ -289,6 +291,64 @@ invconv_status invconv_bwd(const float *x, const float *w, const float *dLdx, fl
 {
     return invconv_bwd_ex(x, w, dLdx, dLdy, dLdw, B, C, H, W, k, workspace, workspace_bytes, stream,
                           INVCONV_VARIANT_AUTO);
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------
+// Scratch of the entry point that takes no workspace (for callers that cannot allocate): one array in
+// every device's memory for as long as the library is loaded.  In host code its name only stands for
+// the symbol; the address in a device's memory comes from hipGetSymbolAddress, asked once per device
+// with that device current, and only that address is ever handed to a kernel.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[INVCONV_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];       // [device] address of that device's copy of `scratch`
+std::mutex g_scratch_mutex;
+
+int static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return INVCONV_ERR_LAUNCH;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return INVCONV_ERR_LAUNCH;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return INVCONV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+invconv_status invconv_bwd_static(const float *x, const float *w, const float *dLdx, float *dLdy, float *dLdw, int B,
+                                  int C, int H, int W, int k, void *stream)
+{
+    if (!x || !w || !dLdx || !dLdy || !dLdw)
+        return INVCONV_ERR_NULL;
+    if (int s = check_shape(B, C, H, W, k))
+        return s;
+    const size_t need = invconv_bwd_workspace_bytes(B, C, H, W, k);
+    if (!need)
+        return INVCONV_ERR_UNSUPPORTED;
+    if (need > (size_t)INVCONV_STATIC_SCRATCH_BYTES)
+        return INVCONV_ERR_WORKSPACE;       // this shape needs more scratch than the library holds
+    void *ws = nullptr;
+    if (int s = static_scratch(&ws))
+        return s;
+    return invconv_bwd(x, w, dLdx, dLdy, dLdw, B, C, H, W, k, ws, INVCONV_STATIC_SCRATCH_BYTES, stream);
 }
 
 invconv_status invconv_logdet(const float *w, int C, int H, int W, int k, float *out, void *stream)

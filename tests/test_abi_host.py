@@ -109,6 +109,16 @@ def test_workspace_taking_calls_reject_bad_workspaces():
     assert L.invconv_workspace_error(None, None, None) == b.ERR_NULL
 
 
+def test_static_scratch_call_rejects_bad_arguments_and_oversized_shapes():
+    L = b.lib()
+    x, w, g, v, dw = FAKE[:5]
+    assert L.invconv_bwd_static(None, w, g, v, dw, 2, 3, 8, 8, 3, None) == b.ERR_NULL
+    assert L.invconv_bwd_static(x, w, g, v, dw, 2, 3, 8, 0, 3, None) == b.ERR_SHAPE
+    big = (4096, 12, 128, 128, 3)
+    assert b.bwd_workspace_bytes(*big) > 8 << 20
+    assert L.invconv_bwd_static(x, w, g, v, dw, *big, None) == b.ERR_WORKSPACE
+
+
 def test_logdet_rejects_bad_arguments():
     L = b.lib()
     assert L.invconv_logdet(None, 3, 8, 8, 3, FAKE[0], None) == b.ERR_NULL
