@@ -1,11 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the inverse-convolution hot path on one MI355X.
 
-One "step" = invconv_fwd + invconv_bwd + invconv_logdet over one batch of the
-headline workload (B=16, C=3, 32x32, k=3, fp32), inputs resident in HBM.
-Prints ONE JSON line with images/s, the roofline figures of the dominant
-kernel (timed live with HIP events on the launch stream) and the CPU oracle
-timed on the host cores as a baseline.
+One "step" = forward solve + log-determinant (invconv_fwd_logdet) and backward
+pass (invconv_bwd) over one batch of the headline workload (B=16, C=3, 32x32,
+k=3, fp32), inputs resident in HBM.  Prints ONE JSON line with images/s, the
+roofline figures of the kernel that takes most of a step (the fused backward
+kernel; the forward solve in a second block), both timed live with HIP events
+on the launch stream, the cost of an empty dependent step as a floor, and the
+CPU oracle timed on the host cores as a baseline.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1] [--all]
 """
@@ -24,10 +26,38 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 
-# HBM bytes per launch of the forward solve kernel, from rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE
-# (KiB per dispatch), each scaled by what the same counter reads for a 64 MiB device copy
-# (FETCH_SIZE x 2.00, WRITE_SIZE x 1.00); the runs are summarised under profiles/.
-MEASURED_TRAFFIC_BYTES = {1: int((2.00 * 173.5 + 1.00 * 192.0) * 1024)}
+PROFILES = os.path.join(ROOT, "profiles")
+CALIBRATION_COPY_KIB = 65536.0   # the --calibration-copy run moves 64 MiB each way
+
+
+def counter_traffic_bytes(summary: str, kernel: str, column: str = "median_KiB"):
+    """HBM bytes per launch of `kernel` from a committed rocprofv3 --pmc summary under profiles/
+    (sections '## FETCH_SIZE' and '## WRITE_SIZE', KiB per dispatch), each counter scaled by what it read for
+    the 64 MiB device copy of the same run.  None if the file or the kernel is not there."""
+    path = os.path.join(PROFILES, summary)
+    if not os.path.exists(path):
+        return None
+    sect, rows = None, {"FETCH_SIZE": {}, "WRITE_SIZE": {}}
+    col = 1 if column == "median_KiB" else 2
+    with open(path) as f:
+        for line in f:
+            if line.startswith("## "):
+                sect = line[3:].strip()
+                continue
+            parts = line.rsplit(None, 3)
+            if sect in rows and len(parts) == 4 and not line.startswith(("#", "kernel")):
+                try:
+                    rows[sect][parts[0].strip()] = (float(parts[2]), float(parts[3]))
+                except ValueError:
+                    pass
+    out = 0.0
+    for sect in ("FETCH_SIZE", "WRITE_SIZE"):
+        cal = [v[1] for k, v in rows[sect].items() if "copyBuffer" in k]
+        hit = [v[col - 1] for k, v in rows[sect].items() if kernel in k]
+        if not cal or not hit or cal[0] <= 0:
+            return None
+        out += hit[0] * CALIBRATION_COPY_KIB / cal[0] * 1024.0
+    return int(out)
 
 
 def parse_args():
@@ -75,7 +105,7 @@ class Layered:
         self.dws = [torch.empty_like(w) for w in self.ws_d]
         self.lds = torch.empty(self.L, device="cuda")
         need = b.bwd_workspace_bytes(self.B, self.C, self.H, self.W, self.k)
-        self.wsp = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        self.wsp = b.new_workspace(need)            # header zeroed once, as the interface asks
         self.need = need
         self.lib = b.lib()
         self.n_elems = self.B * self.C * self.H * self.W
@@ -85,7 +115,7 @@ class Layered:
             arr = lambda ts: (ctypes.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
             self.p_w, self.p_x, self.p_dw = arr(self.ws_d), arr(self.acts[1:]), arr(self.dws)
             self.cneed = b.chain_workspace_bytes(self.L, self.B, self.C, self.H, self.W, self.k)
-            self.cws = torch.empty(max(self.cneed, 256), dtype=torch.uint8, device="cuda")
+            self.cws = b.new_workspace(self.cneed)
 
     # raw C-ABI calls: pointers and sizes only
     def fwd_layer(self, l, stream):
@@ -97,6 +127,11 @@ class Layered:
         st = self.lib.invconv_bwd_ex(self.acts[l + 1].data_ptr(), self.ws_d[l].data_ptr(), gin.data_ptr(),
                                      gout.data_ptr(), self.dws[l].data_ptr(), self.B, self.C, self.H, self.W,
                                      self.k, self.wsp.data_ptr(), self.need, stream, self.variant)
+        assert st == 0, self.b.status_string(st)
+
+    def fwd_logdet_layer(self, l, stream):
+        st = self.lib.invconv_fwd_logdet(self.acts[l].data_ptr(), self.ws_d[l].data_ptr(), self.acts[l + 1].data_ptr(),
+                                         self.lds[l:l + 1].data_ptr(), self.B, self.C, self.H, self.W, self.k, stream)
         assert st == 0, self.b.status_string(st)
 
     def logdet_layer(self, l, stream):
@@ -137,6 +172,11 @@ class Layered:
             self.logdet_layer(l, stream)
 
     def step(self, stream):
+        if self.L == 1 and self.variant == 0:
+            # forward solve and log-determinant in one call, then the backward pass
+            self.fwd_logdet_layer(0, stream)
+            self.bwd_all(stream)
+            return
         self.fwd_all(stream)
         self.bwd_all(stream)
         self.logdet_all(stream)
@@ -203,6 +243,25 @@ def measure_workload(cfg, steps, warmup, variant=0):
         fp32_tflops=flops_step / (ms_step * 1e-3) / 1e12,
         fp32_frac=flops_step / (ms_step * 1e-3) / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
     )
+
+
+def chain_roofline(torch, L, stream, reps):
+    """Workload 4: the pipelined chain launch (all layers of one direction in one launch).  At 12 channels the
+    arithmetic intensity (about 30 flop/byte) is past the ridge of the fp32 roofs, so the matrix/vector fp32
+    peak is the bound that binds; the HBM fraction and the counter-measured traffic are reported beside it."""
+    ms_f = event_time_batch(torch, lambda: L.fwd_all(stream), reps, 2)
+    n = L.n_elems * L.L
+    macs = L.C * (L.k * L.k - 1) + (L.C - 1) / 2.0
+    flops = 2.0 * macs * n
+    alg_bytes = 8.0 * n
+    traffic = counter_traffic_bytes("hbm_counters_workload4_chain.txt", "k_chain_band<3, 3, 0>", "max_KiB")
+    tf = flops / (ms_f * 1e-3) / 1e12
+    gbs = alg_bytes / (ms_f * 1e-3) / 1e9
+    return dict(bound="mfma", achieved=tf, peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s", frac=tf / FP32_VECTOR_PEAK_TFLOPS,
+                traffic=traffic, kernel="pipelined chain launch, forward direction (all layers, one launch)",
+                kernel_ms_back_to_back=ms_f, algorithmic_bytes_per_launch=alg_bytes, flops_per_launch=flops,
+                hbm=dict(achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS),
+                traffic_over_algorithmic=(traffic / alg_bytes if traffic else None))
 
 
 def device_info(torch):
@@ -369,7 +428,7 @@ def measure_conv(reps=100):
         g_ = torch.randn(B, C, H, W, generator=g).cuda()
         dx, dw = torch.empty_like(x), torch.empty_like(w)
         need = lib.invconv_bwd_workspace_bytes(B, C, H, W, k)
-        ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        ws = b.new_workspace(need)
 
         def call_bwd():
             st = lib.invconv_conv_bwd(x.data_ptr(), w.data_ptr(), g_.data_ptr(), dx.data_ptr(), dw.data_ptr(),
@@ -411,9 +470,10 @@ def scale_study(reps=30):
         g = torch.from_numpy(cs["g"]).cuda()
         x = torch.empty_like(y)
         v, dw = torch.empty_like(y), torch.empty_like(w)
-        wsp = torch.empty(max(b.bwd_workspace_bytes(B, C, H, W, k), 256), dtype=torch.uint8, device="cuda")
-        b.invconv_fwd(y, w, out=x)
-        ms_f = event_time_batch(torch, lambda: b.invconv_fwd(y, w, out=x), reps, 3)
+        wsp = b.new_workspace(b.bwd_workspace_bytes(B, C, H, W, k))
+        wsf = b.new_workspace(b.fwd_workspace_bytes(B, C, H, W, k))
+        b.invconv_fwd(y, w, out=x, workspace=wsf)
+        ms_f = event_time_batch(torch, lambda: b.invconv_fwd(y, w, out=x, workspace=wsf), reps, 3)
         ms_b = event_time_batch(torch, lambda: b.invconv_bwd(x, w, g, out=(v, dw), workspace=wsp), reps, 3)
         n = B * C * H * W
         out[name] = dict(B=B, C=C, H=H, W=W, k=k, fwd_us=ms_f * 1e3, bwd_us=ms_b * 1e3,
@@ -453,21 +513,46 @@ def main():
     cfg = args.workload
     L, res = measure_workload(cfg, args.steps, args.warmup, args.variant)
 
-    # dominant kernel: the wavefront solve (forward orientation), one launch per call of invconv_fwd
     stream = torch.cuda.current_stream().cuda_stream
     reps = max(min(args.steps, 500), 20)
-    k_med, k_mean, k_min = event_time(torch, lambda: L.fwd_layer(0, stream), reps, 20)
-    k_batch = event_time_batch(torch, lambda: L.fwd_layer(0, stream), reps, 20)
-    kernel_bytes = 8.0 * L.n_elems                       # read y, write x
-    kernel_ms = k_batch
-    achieved = kernel_bytes / (kernel_ms * 1e-3) / 1e9
-    roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                    traffic=MEASURED_TRAFFIC_BYTES.get(cfg),
-                    kernel="forward wavefront solve (the one kernel invconv_fwd launches)",
-                    kernel_ms_back_to_back=k_batch, kernel_ms_event_pair_median=k_med,
+    nsteps = L.H + L.W - 1
+
+    def kernel_block(name, fn, bytes_per_elt, traffic):
+        """HIP-event timing of one call that is one kernel launch; algorithmic bytes over its mean duration."""
+        k_med, k_mean, k_min = event_time(torch, fn, reps, 20)
+        k_batch = event_time_batch(torch, fn, reps, 20)
+        kernel_bytes = bytes_per_elt * L.n_elems
+        achieved = kernel_bytes / (k_batch * 1e-3) / 1e9
+        return dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
+                    traffic=traffic, kernel=name, kernel_ms_back_to_back=k_batch, kernel_ms_event_pair_median=k_med,
                     kernel_ms_event_pair_min=k_min, algorithmic_bytes_per_launch=kernel_bytes,
-                    dependent_steps=L.H + L.W - 1,
-                    us_per_dependent_step=kernel_ms * 1e3 / (L.H + L.W - 1))
+                    traffic_over_algorithmic=(traffic / kernel_bytes if traffic else None),
+                    dependent_steps=nsteps, us_per_dependent_step=k_batch * 1e3 / nsteps)
+
+    if L.L == 1:
+        gin, gout = L.g0, L.grads[0]
+        summary = f"hbm_counters_workload{cfg}_headline.txt" if cfg == 1 else f"hbm_counters_workload{cfg}.txt"
+        # the kernel with the most time per step: the fused backward (transposed solve + dL/dw), 12 B per element
+        roofline = kernel_block("backward: transposed solve + weight gradient (the launch invconv_bwd makes"
+                                + (")" if L.C <= 4 and L.H <= 64 and L.k <= 7 else "; first of several)"),
+                                lambda: L.bwd_layer(0, gin, gout, stream), 12.0,
+                                counter_traffic_bytes(summary, "k_bwd_wave"))
+        roofline_fwd = kernel_block("forward wavefront solve + log-determinant (the launch invconv_fwd_logdet makes)",
+                                    lambda: L.fwd_logdet_layer(0, stream), 8.0,
+                                    counter_traffic_bytes(summary, "k_solve_wave"))
+    else:
+        roofline = chain_roofline(torch, L, stream, reps=max(args.steps // 20, 5))
+        roofline_fwd = None
+    # floor: an empty dependent step ordered by a workgroup barrier + LDS exchange (no arithmetic, no memory)
+    lib = b.lib()
+    probe_steps = 2000
+    def probe():
+        assert lib.invconv_probe_step_sync(2, probe_steps, max(min(L.B, 256), 1), stream) == 0
+    floor_us = event_time_batch(torch, probe, 20, 3) * 1e3 / probe_steps
+    for r in (roofline, roofline_fwd):
+        if r and "us_per_dependent_step" in r:
+            r["empty_step_floor_us"] = floor_us
+            r["step_over_floor"] = r["us_per_dependent_step"] / floor_us
 
     out = dict(
         metric="inverse-conv fwd+bwd images/sec at m=32,C=3,k=3; achieved HBM GB/s fraction",
@@ -475,18 +560,19 @@ def main():
         ms_per_step=res["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None,
         dtype="f32", data="synthetic",
         config=dict(workload=f"workload {cfg}: B={L.B} C={L.C} H=W={L.H} k={L.k} layers={L.L}, "
-                             + ("step = invconv_fwd + invconv_bwd + invconv_logdet" if L.L == 1 else
+                             + ("step = invconv_fwd_logdet + invconv_bwd" if L.L == 1 else
                                 "step = invconv_chain_fwd + invconv_chain_bwd + invconv_chain_logdet")
                              + ", eager launches on one stream",
                     variant=args.variant),
         ms_fwd=res["ms_fwd"], ms_bwd=res["ms_bwd"], algorithmic_gbs=res["algorithmic_gbs"],
         hbm_frac_whole_step=res["hbm_frac"],
-        roofline=roofline,
+        roofline=roofline, roofline_forward=roofline_fwd,
     )
     if not args.headline_only:
         dev = device_info(torch)
         out["device"] = dev
-        roofline["frac_of_measured_copy"] = achieved / dev["measured_copy_gbs"]
+        if roofline.get("unit") == "GB/s":
+            roofline["frac_of_measured_copy"] = roofline["achieved"] / dev["measured_copy_gbs"]
         if L.L == 1 and cfg in (0, 1):
             out["ms_per_step_graph_replay"] = graph_replay_ms(torch, L, max(min(args.steps, 500), 20))
         others = {}
@@ -495,10 +581,13 @@ def main():
                 others[str(c)] = res
                 continue
             st = {0: args.steps, 1: args.steps, 2: max(args.steps // 2, 10), 3: max(args.steps // 4, 10),
-                  4: max(args.steps // 100, 5)}[c]
-            Lc, r = measure_workload(c, st, max(st // 10, 2), args.variant)
+                  4: max(args.steps // 50, 10)}[c]
+            # (the chain's heavy launches need a few more warm-up steps than the rest: the clocks ramp up)
+            Lc, r = measure_workload(c, st, max(st // 10, 8 if c == 4 else 2), args.variant)
             if c in (0, 1):
                 r["ms_per_step_graph_replay"] = graph_replay_ms(torch, Lc, max(min(st, 500), 20))
+            if c == 4:
+                r["roofline"] = chain_roofline(torch, Lc, torch.cuda.current_stream().cuda_stream, reps=5)
             others[str(c)] = r
             print(f"[bench] workload {c}: {json.dumps(r)}", file=sys.stderr, flush=True)
         for r in others.values():

@@ -91,6 +91,15 @@ invconv_status invconv_fwd(const float *y, const float *w, float *x,
                            int B, int C, int H, int W, int k, void *stream);
 
 /*
+ * Forward pass and log-determinant in one call: what the forward pass of a flow step needs
+ * (Section 4: the likelihood takes x and log|det dx/dy|).  x as invconv_fwd, *logdet as invconv_logdet;
+ * for few-channel images (C <= 4, H <= 64) both come out of one kernel launch.
+ *   logdet [out] one device float.
+ */
+invconv_status invconv_fwd_logdet(const float *y, const float *w, float *x, float *logdet,
+                                  int B, int C, int H, int W, int k, void *stream);
+
+/*
  * The same forward pass with scratch from the caller.  Images of few channels (C <= 4) and more than
  * 128 rows are then cut into bands of 64 rows that run on different compute units and hand their
  * boundary messages over through the workspace (Section 3.3 only needs the pixels of an anti-diagonal

@@ -25,7 +25,7 @@ EXPORTS = (
     "invconv_fwd_ex", "invconv_bwd_ex", "invconv_status_string", "invconv_version",
     "invconv_probe_step_sync", "invconv_chain_fwd", "invconv_chain_bwd", "invconv_chain_workspace_bytes",
     "invconv_chain_logdet", "invconv_conv_fwd", "invconv_conv_bwd",
-    "invconv_fwd_ws", "invconv_fwd_workspace_bytes", "invconv_workspace_error", "invconv_set_wait_budget",
+    "invconv_fwd_logdet", "invconv_fwd_ws", "invconv_fwd_workspace_bytes", "invconv_workspace_error", "invconv_set_wait_budget",
     "invconv_bwd_static",
 )
 WS_HEADER_BYTES = 256
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.invconv_conv_fwd.restype = ci
         L.invconv_conv_bwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, ctypes.c_size_t, vp]
         L.invconv_conv_bwd.restype = ci
+        L.invconv_fwd_logdet.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.invconv_fwd_logdet.restype = ci
         L.invconv_fwd_ws.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
         L.invconv_fwd_ws.restype = ci
         L.invconv_fwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
@@ -164,6 +166,20 @@ def invconv_fwd(y: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = Non
     if st != OK:
         raise InvconvError(st, "invconv_fwd")
     return x
+
+
+def invconv_fwd_logdet(y: torch.Tensor, w: torch.Tensor, out: tuple[torch.Tensor, torch.Tensor] | None = None):
+    """(x, log|det dx/dy| of one image): forward pass and log-determinant in one call."""
+    _check(y, "y"), _check(w, "w")
+    B, C, H, W, k = _dims(y, w)
+    if out is None:
+        x, ld = torch.empty_like(y), torch.empty(1, dtype=torch.float32, device=y.device)
+    else:
+        x, ld = _check(out[0], "out[0]", y.shape), _check(out[1], "out[1]", (1,))
+    st = lib().invconv_fwd_logdet(y.data_ptr(), w.data_ptr(), x.data_ptr(), ld.data_ptr(), B, C, H, W, k, _stream())
+    if st != OK:
+        raise InvconvError(st, "invconv_fwd_logdet")
+    return x, ld
 
 
 def invconv_bwd_static(x: torch.Tensor, w: torch.Tensor, dLdx: torch.Tensor,

@@ -74,8 +74,25 @@ SolveWs solve_ws_of(void *workspace, const WsLayout &lay)
     return ws;
 }
 
+int solve_variant(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                  hipStream_t stream, int variant, SolveWs ws);
+
+// `logdet` (forward direction only, may be null): where log|det dx/dy| of one image goes; the few-channel
+// kernels write it on the side, every other kernel is followed by the small launch invconv_logdet makes.
 int solve(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-          hipStream_t stream, int variant, SolveWs ws = SolveWs{})
+          hipStream_t stream, int variant, SolveWs ws = SolveWs{}, float *logdet = nullptr)
+{
+    if (variant == INVCONV_VARIANT_AUTO && wave_supported(C, H, k))
+        return wave_split_preferred(B, H, W, k) && !wave_tile_preferred(B, C, H, W)
+                   ? launch_solve_wave_split(dir, in, w, out, B, C, H, W, k, stream, logdet)
+                   : launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream, logdet);
+    if (int s = solve_variant(dir, in, w, out, B, C, H, W, k, stream, variant, ws))
+        return s;
+    return logdet ? launch_logdet(w, C, H, W, k, logdet, stream) : INVCONV_OK;
+}
+
+int solve_variant(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                  hipStream_t stream, int variant, SolveWs ws)
 {
     switch (variant) {
     case INVCONV_VARIANT_AUTO:
@@ -120,7 +137,7 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
 }
 
 int fwd_impl(const float *y, const float *w, float *x, int B, int C, int H, int W, int k, void *stream, int variant,
-             SolveWs ws)
+             SolveWs ws, float *logdet = nullptr)
 {
     if (!y || !w || !x)
         return INVCONV_ERR_NULL;
@@ -141,7 +158,7 @@ int fwd_impl(const float *y, const float *w, float *x, int B, int C, int H, int 
          !band_supported(C, H, k)))
         if (int s = check_supported(C, H, k))
             return s;
-    return solve(0, y, w, x, B, C, H, W, k, (hipStream_t)stream, variant, ws);
+    return solve(0, y, w, x, B, C, H, W, k, (hipStream_t)stream, variant, ws, logdet);
 }
 
 }  // namespace
@@ -158,6 +175,16 @@ invconv_status invconv_fwd(const float *y, const float *w, float *x, int B, int 
                            void *stream)
 {
     return fwd_impl(y, w, x, B, C, H, W, k, stream, INVCONV_VARIANT_AUTO, SolveWs{});
+}
+
+invconv_status invconv_fwd_logdet(const float *y, const float *w, float *x, float *logdet, int B, int C, int H, int W,
+                                  int k, void *stream)
+{
+    if (!logdet)
+        return INVCONV_ERR_NULL;
+    if ((const float *)logdet == y || (const float *)logdet == w || logdet == x)
+        return INVCONV_ERR_ALIAS;
+    return fwd_impl(y, w, x, B, C, H, W, k, stream, INVCONV_VARIANT_AUTO, SolveWs{}, logdet);
 }
 
 size_t invconv_fwd_workspace_bytes(int B, int C, int H, int W, int k)

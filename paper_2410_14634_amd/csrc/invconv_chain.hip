@@ -324,7 +324,10 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                         if (!edge[bi]) {
 #pragma unroll
                             for (int ch = 0; ch < C; ++ch) {
-                                const f32x4 v = lr[bi][ch];     // (NaN after a lost wait, see below)
+                                const float qn = __builtin_nanf("");
+                                // (selected here, where the value is used: a select right behind the load
+                                // would make the wave wait for it at once)
+                                const f32x4 v = lost ? f32x4{qn, qn, qn, qn} : lr[bi][ch];
                                 float2 *d2 = reinterpret_cast<float2 *>(dst + ch * 16 * kCRow);
                                 d2[0] = float2{v[0], v[1]};
                                 d2[1] = float2{v[2], v[3]};
@@ -340,7 +343,7 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                                 if ((unsigned)(m + sh) < 4u) {
 #pragma unroll
                                     for (int ch = 0; ch < C; ++ch)
-                                        de[ch * 16 * kCRow + m] = lr[bi][ch][m];
+                                        de[ch * 16 * kCRow + m] = lost ? __builtin_nanf("") : lr[bi][ch][m];
                                 }
                             }
                         }
@@ -384,9 +387,7 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
 #pragma unroll
                             for (int ch = 0; ch < C; ++ch) {
                                 // device-coherent: another workgroup of this launch may have written it
-                                const f32x4 got = chain_load16(rin, off, plane_bytes * (unsigned)(DIR ? C - 1 - ch : ch));
-                                const float qn = __builtin_nanf("");
-                                lr[bi][ch] = lost ? f32x4{qn, qn, qn, qn} : got;
+                                lr[bi][ch] = chain_load16(rin, off, plane_bytes * (unsigned)(DIR ? C - 1 - ch : ch));
                             }
                         }
                     }

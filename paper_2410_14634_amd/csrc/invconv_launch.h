@@ -51,14 +51,15 @@ int launch_solve_block(int dir, const float *in, const float *w, float *out, int
 int launch_solve_diag(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W,
                       int k, hipStream_t stream);
 bool wave_supported(int C, int H, int k);
+// `logdet` (may be null): one device float that receives log|det dx/dy| of one image on the side
 int launch_solve_wave(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                      hipStream_t stream);
+                      hipStream_t stream, float *logdet = nullptr);
 bool band_supported(int C, int H, int k);
 int launch_solve_band(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                       hipStream_t stream);
 bool bwd_wave_supported(int C, int H, int W, int k);
 int launch_solve_wave_split(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                            hipStream_t stream);
+                            hipStream_t stream, float *logdet = nullptr);
 bool wave_split_preferred(int B, int H, int W, int k);
 bool wave_tile_preferred(int B, int C, int H, int W);
 bool wave_bands_supported(int C, int H, int W, int k);

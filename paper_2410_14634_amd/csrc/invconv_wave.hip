@@ -354,10 +354,26 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
     }
 }
 
+// log|det dx/dy| of one image (Section 4), -H*W*sum_c log|w[c][c][K-1][K-1]|, by the calling wave: the
+// forward kernels of few-channel images write it on the side (first workgroup only), so that a training
+// step needs no launch of its own for it.  Every lane computes the same value from uniform loads.
+template <int C, int K>
+__device__ __forceinline__ void wave_logdet(const float *__restrict__ w, int H, int W, float *__restrict__ out)
+{
+    double s = 0.0;
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+        s += log(fabs((double)w[((c * C + c) * K + (K - 1)) * K + (K - 1)]));
+    if ((threadIdx.x & 63) == 0)
+        out[0] = (float)(-(double)H * (double)W * s);
+}
+
 template <int C, int K, int DIR>
 __global__ __launch_bounds__(64) void k_solve_wave(const float *__restrict__ in, const float *__restrict__ w,
-                                                  float *__restrict__ out, int H, int W)
+                                                  float *__restrict__ out, int H, int W, float *logdet)
 {
+    if (logdet && blockIdx.x == 0)
+        wave_logdet<C, K>(w, H, W, logdet);
     solve_wave_body<C, K, DIR, false>(in, w, out, H, W, blockIdx.x, nullptr);
 }
 
@@ -368,9 +384,11 @@ __global__ __launch_bounds__(64) void k_solve_wave(const float *__restrict__ in,
 // aligned tensors.
 template <int C, int K, int DIR>
 __global__ __launch_bounds__(64) void k_solve_wave_tile(const float *__restrict__ in, const float *__restrict__ w,
-                                                       float *__restrict__ out, int H, int W)
+                                                       float *__restrict__ out, int H, int W, float *logdet)
 {
     extern __shared__ float smem[];
+    if (logdet && blockIdx.x == 0)
+        wave_logdet<C, K>(w, H, W, logdet);
     const int n4 = C * H * W / 4, lane = threadIdx.x;
     const float4 *src = reinterpret_cast<const float4 *>(in + (size_t)blockIdx.x * C * H * W);
     float4 *dst = reinterpret_cast<float4 *>(out + (size_t)blockIdx.x * C * H * W);
@@ -608,9 +626,11 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
 
 template <int C, int K, int DIR>
 __global__ __launch_bounds__(256) void k_solve_wave_split(const float *__restrict__ in, const float *__restrict__ w,
-                                                         float *__restrict__ out, int H, int W)
+                                                         float *__restrict__ out, int H, int W, float *logdet)
 {
     __shared__ __attribute__((aligned(16))) float smem[wave_split_lds_floats<C, K>()];
+    if (logdet && blockIdx.x == 0 && (threadIdx.x >> 6) == 1)      // wave 1 has the least to set up
+        wave_logdet<C, K>(w, H, W, logdet);
     WaveSplitLds sl;
     sl.x = smem;
     sl.m = reinterpret_cast<f32x4 *>(smem + 2 * C * 64);
@@ -983,7 +1003,7 @@ bool wave_tile_preferred(int B, int C, int H, int W)
 
 template <int C, int K>
 static int launch_wave_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
-                          hipStream_t stream)
+                          hipStream_t stream, float *logdet)
 {
     // Large batches: every lane walks its own row 4 bytes at a time, so a wave keeps
     // rows * C * 2 (input and output) cache lines of 128 bytes live for dozens of steps.  When the
@@ -998,9 +1018,11 @@ static int launch_wave_ck(int dir, const float *in, const float *w, float *out, 
         if (!ensure_dynamic_lds(fn, tile_bytes))
             return INVCONV_ERR_UNSUPPORTED;
         if (dir)
-            hipLaunchKernelGGL((k_solve_wave_tile<C, K, 1>), dim3(B), dim3(64), tile_bytes, stream, in, w, out, H, W);
+            hipLaunchKernelGGL((k_solve_wave_tile<C, K, 1>), dim3(B), dim3(64), tile_bytes, stream, in, w, out, H, W,
+                               logdet);
         else
-            hipLaunchKernelGGL((k_solve_wave_tile<C, K, 0>), dim3(B), dim3(64), tile_bytes, stream, in, w, out, H, W);
+            hipLaunchKernelGGL((k_solve_wave_tile<C, K, 0>), dim3(B), dim3(64), tile_bytes, stream, in, w, out, H, W,
+                               logdet);
         return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
     }
     if (B > 512) {
@@ -1016,9 +1038,9 @@ static int launch_wave_ck(int dir, const float *in, const float *w, float *out, 
         }
     }
     if (dir)
-        hipLaunchKernelGGL((k_solve_wave<C, K, 1>), dim3(B), dim3(64), lds, stream, in, w, out, H, W);
+        hipLaunchKernelGGL((k_solve_wave<C, K, 1>), dim3(B), dim3(64), lds, stream, in, w, out, H, W, logdet);
     else
-        hipLaunchKernelGGL((k_solve_wave<C, K, 0>), dim3(B), dim3(64), lds, stream, in, w, out, H, W);
+        hipLaunchKernelGGL((k_solve_wave<C, K, 0>), dim3(B), dim3(64), lds, stream, in, w, out, H, W, logdet);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
@@ -1360,29 +1382,29 @@ bool wave_bands_supported(int C, int H, int W, int k)
 
 template <int C, int K>
 static int launch_wave_split_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
-                                hipStream_t stream)
+                                hipStream_t stream, float *logdet)
 {
     if (dir)
-        hipLaunchKernelGGL((k_solve_wave_split<C, K, 1>), dim3(B), dim3(256), 0, stream, in, w, out, H, W);
+        hipLaunchKernelGGL((k_solve_wave_split<C, K, 1>), dim3(B), dim3(256), 0, stream, in, w, out, H, W, logdet);
     else
-        hipLaunchKernelGGL((k_solve_wave_split<C, K, 0>), dim3(B), dim3(256), 0, stream, in, w, out, H, W);
+        hipLaunchKernelGGL((k_solve_wave_split<C, K, 0>), dim3(B), dim3(256), 0, stream, in, w, out, H, W, logdet);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
 // Same shapes as the single-wave kernel; four waves per image.
 int launch_solve_wave_split(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                            hipStream_t stream)
+                            hipStream_t stream, float *logdet)
 {
     if (!wave_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
-    if (C == 3 && k == 3) return launch_wave_split_ck<3, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 5) return launch_wave_split_ck<3, 5>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 7) return launch_wave_split_ck<3, 7>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 9) return launch_wave_split_ck<3, 9>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 11) return launch_wave_split_ck<3, 11>(dir, in, w, out, B, H, W, stream);
-    if (C == 1 && k == 3) return launch_wave_split_ck<1, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 2 && k == 3) return launch_wave_split_ck<2, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 4 && k == 3) return launch_wave_split_ck<4, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 3) return launch_wave_split_ck<3, 3>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 3 && k == 5) return launch_wave_split_ck<3, 5>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 3 && k == 7) return launch_wave_split_ck<3, 7>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 3 && k == 9) return launch_wave_split_ck<3, 9>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 3 && k == 11) return launch_wave_split_ck<3, 11>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 1 && k == 3) return launch_wave_split_ck<1, 3>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 2 && k == 3) return launch_wave_split_ck<2, 3>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 4 && k == 3) return launch_wave_split_ck<4, 3>(dir, in, w, out, B, H, W, stream, logdet);
     return INVCONV_ERR_VARIANT;
 }
 
@@ -1418,19 +1440,19 @@ int launch_solve_wave_bands(int dir, const float *in, const float *w, float *out
 }
 
 int launch_solve_wave(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                      hipStream_t stream)
+                      hipStream_t stream, float *logdet)
 {
     if (!wave_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
-    if (C == 3 && k == 3) return launch_wave_ck<3, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 2) return launch_wave_ck<3, 2>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 5) return launch_wave_ck<3, 5>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 7) return launch_wave_ck<3, 7>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 9) return launch_wave_ck<3, 9>(dir, in, w, out, B, H, W, stream);
-    if (C == 3 && k == 11) return launch_wave_ck<3, 11>(dir, in, w, out, B, H, W, stream);
-    if (C == 1 && k == 3) return launch_wave_ck<1, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 2 && k == 3) return launch_wave_ck<2, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 4 && k == 3) return launch_wave_ck<4, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 3 && k == 3) return launch_wave_ck<3, 3>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 3 && k == 2) return launch_wave_ck<3, 2>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 3 && k == 5) return launch_wave_ck<3, 5>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 3 && k == 7) return launch_wave_ck<3, 7>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 3 && k == 9) return launch_wave_ck<3, 9>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 3 && k == 11) return launch_wave_ck<3, 11>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 1 && k == 3) return launch_wave_ck<1, 3>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 2 && k == 3) return launch_wave_ck<2, 3>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 4 && k == 3) return launch_wave_ck<4, 3>(dir, in, w, out, B, H, W, stream, logdet);
     return INVCONV_ERR_VARIANT;
 }
 

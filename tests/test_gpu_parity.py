@@ -244,6 +244,34 @@ def test_masked_entries_are_ignored_and_get_zero_gradient():
     assert np.all(got[2][:, :, 2, 2][iu] == 0.0)
 
 
+FWD_LOGDET_SHAPES = [(4, 3, 8, 8, 3), (16, 3, 32, 32, 3), (32, 3, 64, 64, 5), (2, 1, 5, 5, 3), (700, 2, 50, 10, 3),
+                     (64, 12, 16, 16, 3), (2, 3, 130, 40, 3), (1, 20, 6, 7, 2)]
+
+
+@pytest.mark.parametrize("shape", FWD_LOGDET_SHAPES)
+def test_fwd_logdet_matches_the_two_separate_calls_and_the_oracle(shape):
+    """invconv_fwd_logdet = invconv_fwd + invconv_logdet (one launch for few-channel images)."""
+    import torch
+    B, C, H, W, k = shape
+    cs = inputs.make_case(B, C, H, W, k, seed=sum(shape) + 13, tap_std=0.05)
+    yd, wd = dev(cs["y"]), dev(cs["w"][0])
+    x, ld = b.invconv_fwd_logdet(yd, wd)
+    x2 = b.invconv_fwd(yd, wd)
+    ld2 = b.invconv_logdet(wd, H, W)
+    torch.cuda.synchronize()
+    assert torch.equal(x, x2)
+    ref = oracle.invconv_logdet(cs["w"][0], H, W)
+    assert abs(float(ld[0]) - ref) <= 1e-5 * max(1.0, abs(ref))
+    assert abs(float(ld[0]) - float(ld2[0])) <= 1e-6 * max(1.0, abs(ref))
+    assert rel_err(host(x), oracle.invconv_fwd(cs["y"], cs["w"][0], THREADS)) <= TOL_ACT
+    # the paper's unit diagonal: exactly 0
+    w1 = cs["w"][0].copy()
+    for c in range(C):
+        w1[c, c, k - 1, k - 1] = 1.0
+    _, ld1 = b.invconv_fwd_logdet(yd, dev(w1))
+    assert float(ld1[0]) == 0.0
+
+
 def test_dw_is_bitwise_reproducible():
     wl = inputs.make_workload(2)
     first = run_layer(wl["y"], wl["w"][0], wl["g"])
@@ -382,7 +410,7 @@ def test_hip_graph_replays_match_eager():
     y, w, g = dev(wl["y"]), dev(wl["w"][0]), dev(wl["g"])
     x, v, dw = torch.empty_like(y), torch.empty_like(y), torch.empty_like(w)
     ld = torch.empty(1, device="cuda")
-    wsp = torch.empty(b.bwd_workspace_bytes(16, 3, 32, 32, 3), dtype=torch.uint8, device="cuda")
+    wsp = b.new_workspace(b.bwd_workspace_bytes(16, 3, 32, 32, 3))
 
     def step():
         b.invconv_fwd(y, w, out=x)
