@@ -125,3 +125,19 @@ def make_case(B: int, C: int, H: int, W: int, k: int, *, seed: int = 0,
                 y=make_act(y_kind, shape, cfg=cfg, tensor=_T_Y),
                 g=make_act("normal", shape, cfg=cfg, tensor=_T_G),
                 w=[make_w(C, k, tap_std, diag_kind, cfg=cfg, layer=0)])
+
+
+_T_S, _T_B, _T_Q = 5, 6, 7
+
+
+def make_flow_params(C: int, seed: int = 0, layer: int = 0) -> dict:
+    """Seeded parameters of the two neighbours of the inverse convolution in a flow step (Section 4.1):
+    Actnorm scale s ~ U(0.5, 1.5) and bias b ~ N(0, 0.5) per channel, and a 1 x 1 convolution Q that is a random
+    rotation (the usual initialisation of that layer) plus N(0, 0.05) noise, so that it stays well conditioned."""
+    cfg = 2000 + seed
+    s = np.random.default_rng([0, cfg, layer, _T_S]).uniform(0.5, 1.5, size=C)
+    b = np.random.default_rng([0, cfg, layer, _T_B]).normal(0.0, 0.5, size=C)
+    rng = np.random.default_rng([0, cfg, layer, _T_Q])
+    rot, _ = np.linalg.qr(rng.normal(size=(C, C)))
+    Q = rot + rng.normal(0.0, 0.05, size=(C, C))
+    return dict(s=s.astype(np.float32), b=b.astype(np.float32), Q=np.ascontiguousarray(Q, dtype=np.float32))
