@@ -77,6 +77,9 @@ def parse_args():
                     help="only time the sampling-direction convolution (invconv_conv_fwd) and print its table")
     ap.add_argument("--scale-study", action="store_true",
                     help="only the shapes of the paper's ablations (tall images, large batches, kernel sizes 2..11)")
+    ap.add_argument("--flow-step", action="store_true",
+                    help="only the flow step (inverse convolution + Actnorm + 1x1 convolution): fused kernels against "
+                         "the same arithmetic as separate passes")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three 64 MiB device copies (reference for the HBM byte counters)")
     return ap.parse_args()
@@ -483,6 +486,48 @@ def scale_study(reps=30):
     return out
 
 
+FLOW_SHAPES = {  # (B, C, H, W, k)
+    "workload1": (16, 3, 32, 32, 3), "workload3": (32, 3, 64, 64, 5),
+    "batch_1024": (1024, 3, 32, 32, 3), "batch_4096": (4096, 3, 32, 32, 3), "batch_1024_64x64": (1024, 3, 64, 64, 3),
+}
+
+
+def flow_step_study(reps=50):
+    """One flow step (Section 4.1: inverse convolution, Actnorm, 1 x 1 convolution) forward + backward: the fused
+    kernels (read y, write z; read z and dL/dz, write dL/dy: 20 bytes per element, what the inverse convolution
+    alone moves) against the same arithmetic as separate passes (60 bytes per element: each neighbour adds a read
+    and a write in the forward pass and two reads and a write in the backward pass)."""
+    import torch
+    from paper_2410_14634_amd import binding as b
+    from paper_2410_14634_amd import inputs
+    out = {}
+    for name, (B, C, H, W, k) in FLOW_SHAPES.items():
+        cs = inputs.make_case(B, C, H, W, k, seed=9, tap_std=0.05)
+        p = inputs.make_flow_params(C, 9)
+        y, w, g = (torch.from_numpy(cs[n] if n != "w" else cs["w"][0]).cuda() for n in ("y", "w", "g"))
+        s, bb, Q = (torch.from_numpy(p[n]).cuda() for n in ("s", "b", "Q"))
+        ws = b.new_workspace(b.flowstep_workspace_bytes(B, C, H, W, k))
+        z = torch.empty_like(y)
+        grads = dict(dy=torch.empty_like(y), dw=torch.empty_like(w), ds=torch.empty_like(s), db=torch.empty_like(bb),
+                     dQ=torch.empty_like(Q))
+        row = dict(B=B, C=C, H=H, W=W, k=k)
+        n = B * C * H * W
+        for form, tag, bytes_per_elt in ((b.FLOW_FUSED, "fused", 20.0), (b.FLOW_SEPARATE, "separate", 60.0)):
+            fwd = lambda: b.invconv_flowstep_fwd(y, w, s, bb, Q, out=z, workspace=ws, form=form)
+            bwd = lambda: b.invconv_flowstep_bwd(z, w, s, bb, Q, g, logdet_weight=-float(B), workspace=ws, form=form,
+                                                 out=grads)
+            fwd()
+            ms_f = event_time_batch(torch, fwd, reps, 3)
+            ms_b = event_time_batch(torch, bwd, reps, 3)
+            row[tag] = dict(fwd_us=ms_f * 1e3, bwd_us=ms_b * 1e3, images_per_s=B / ((ms_f + ms_b) * 1e-3),
+                            hbm_bytes_per_element=bytes_per_elt,
+                            gbs=bytes_per_elt * n / ((ms_f + ms_b) * 1e-3) / 1e9)
+        row["speedup_fused_over_separate"] = (row["separate"]["fwd_us"] + row["separate"]["bwd_us"]) / \
+            (row["fused"]["fwd_us"] + row["fused"]["bwd_us"])
+        out[name] = row
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -509,6 +554,9 @@ def main():
         return
     if args.scale_study:
         print(json.dumps(dict(scale_study=scale_study())), flush=True)
+        return
+    if args.flow_step:
+        print(json.dumps(dict(flow_step=flow_step_study())), flush=True)
         return
     cfg = args.workload
     L, res = measure_workload(cfg, args.steps, args.warmup, args.variant)

@@ -192,6 +192,57 @@ invconv_status invconv_bwd_static(const float *x, const float *w, const float *d
 invconv_status invconv_logdet(const float *w, int C, int H, int W, int k,
                               float *out, void *stream);
 
+/*
+ * One flow step around the inverse convolution (Section 4.1: an Inv-Conv layer, an Actnorm layer - a
+ * per-channel affine map with scale s and bias b - and a 1 x 1 convolution Q, in this order):
+ *     x = invconv_w(y),   a[c] = s[c] x[c] + b[c],   z[o] = sum_i Q[o][i] a[i]   at every pixel.
+ * Only z is written: for few-channel images that fit on chip (C <= 4, H <= 64, W a multiple of 4, k = 3, or
+ * C = 3 with k = 5) and batches of 4 MB or more the three layers run as ONE kernel that reads y and writes z,
+ * i.e. the HBM traffic of the inverse convolution alone; other shapes run the same arithmetic as separate
+ * passes over scratch.
+ *   s, b [in] C floats each;  Q [in] C*C floats, row = output channel; must be invertible (a singular Q
+ *   yields inf/NaN like a zero diagonal of w).
+ *   z [out] B*C*H*W, must not alias an input.
+ *   logdet [out, may be NULL] one device float: log|det dz/dy| of one image (Section 4)
+ *       = -H W sum_c log|w[c][c][k-1][k-1]| + H W sum_c log|s[c]| + H W log|det Q|.
+ *   workspace: at least invconv_flowstep_workspace_bytes() bytes (the same buffer serves both calls).
+ */
+invconv_status invconv_flowstep_fwd(const float *y, const float *w, const float *s, const float *b, const float *Q,
+                                    float *z, float *logdet, int B, int C, int H, int W, int k,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward pass of that step from its OUTPUT z (x is recomputed on chip as diag(1/s) (Q^-1 z - b), so the
+ * forward pass need not keep it).  Chain rule through the three layers (Eq. 2 and Eq. 4 with Theorems 1 and 2
+ * for the inverse convolution; the neighbours are linear maps per pixel):
+ *   dLdy  = M^-T ( s * Q^T dLdz )                                    B*C*H*W
+ *   dLdw  as invconv_bwd, with dL/dx = s * Q^T dLdz                  C*C*k*k, masked entries 0
+ *   dLdQ[o][i] = sum dLdz[o] a[i],  dLds[c] = sum (Q^T dLdz)[c] x[c],  dLdb[c] = sum (Q^T dLdz)[c]
+ *                                                                    sums over batch and pixels, fixed order
+ * plus logdet_weight times the gradient of the step's log-determinant (closed forms, Section 4):
+ *   dLdw[c][c][k-1][k-1] -= logdet_weight H W / w[c][c][k-1][k-1],  dLds[c] += logdet_weight H W / s[c],
+ *   dLdQ += logdet_weight H W Q^-T.   (A loss that contains `weight * logdet` of one image passes that weight;
+ *   0 leaves the data term alone.)
+ */
+invconv_status invconv_flowstep_bwd(const float *z, const float *w, const float *s, const float *b, const float *Q,
+                                    const float *dLdz, float *dLdy, float *dLdw, float *dLds, float *dLdb,
+                                    float *dLdQ, float logdet_weight, int B, int C, int H, int W, int k,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+size_t invconv_flowstep_workspace_bytes(int B, int C, int H, int W, int k);   /* 0 if invalid or unsupported */
+
+/* The same two calls with the form chosen by the caller (for measurement): INVCONV_FLOW_SEPARATE runs the
+ * three layers as separate passes over scratch whatever the shape, INVCONV_FLOW_FUSED the fused kernels
+ * wherever they exist (separate passes elsewhere); INVCONV_FLOW_AUTO fuses where the fused kernels exist and
+ * the batch is large enough for the saved HBM passes to matter. */
+enum { INVCONV_FLOW_AUTO = 0, INVCONV_FLOW_SEPARATE = 1, INVCONV_FLOW_FUSED = 2 };
+invconv_status invconv_flowstep_fwd_ex(const float *y, const float *w, const float *s, const float *b, const float *Q,
+                                       float *z, float *logdet, int B, int C, int H, int W, int k,
+                                       void *workspace, size_t workspace_bytes, void *stream, int form);
+invconv_status invconv_flowstep_bwd_ex(const float *z, const float *w, const float *s, const float *b, const float *Q,
+                                       const float *dLdz, float *dLdy, float *dLdw, float *dLds, float *dLdb,
+                                       float *dLdQ, float logdet_weight, int B, int C, int H, int W, int k,
+                                       void *workspace, size_t workspace_bytes, void *stream, int form);
+
 /* Same operations with an explicit kernel variant (INVCONV_VARIANT_*). */
 invconv_status invconv_fwd_ex(const float *y, const float *w, float *x,
                               int B, int C, int H, int W, int k, void *stream, int variant);

@@ -27,7 +27,10 @@ EXPORTS = (
     "invconv_chain_logdet", "invconv_conv_fwd", "invconv_conv_bwd",
     "invconv_fwd_logdet", "invconv_fwd_ws", "invconv_fwd_workspace_bytes", "invconv_workspace_error", "invconv_set_wait_budget",
     "invconv_bwd_static",
+    "invconv_flowstep_fwd", "invconv_flowstep_bwd", "invconv_flowstep_workspace_bytes",
+    "invconv_flowstep_fwd_ex", "invconv_flowstep_bwd_ex",
 )
+FLOW_AUTO, FLOW_SEPARATE, FLOW_FUSED = 0, 1, 2
 WS_HEADER_BYTES = 256
 
 _lib = None
@@ -82,6 +85,17 @@ def lib() -> ctypes.CDLL:
         L.invconv_set_wait_budget.restype = None
         L.invconv_bwd_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp]
         L.invconv_bwd_static.restype = ci
+        L.invconv_flowstep_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+        L.invconv_flowstep_fwd.restype = ci
+        L.invconv_flowstep_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float,
+                                           ci, ci, ci, ci, ci, vp, sz, vp]
+        L.invconv_flowstep_bwd.restype = ci
+        L.invconv_flowstep_fwd_ex.argtypes = L.invconv_flowstep_fwd.argtypes + [ci]
+        L.invconv_flowstep_fwd_ex.restype = ci
+        L.invconv_flowstep_bwd_ex.argtypes = L.invconv_flowstep_bwd.argtypes + [ci]
+        L.invconv_flowstep_bwd_ex.restype = ci
+        L.invconv_flowstep_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+        L.invconv_flowstep_workspace_bytes.restype = sz
         L.invconv_status_string.argtypes = [ci]
         L.invconv_status_string.restype = ctypes.c_char_p
         L.invconv_version.restype = ci
@@ -316,3 +330,54 @@ def invconv_conv_bwd(x: torch.Tensor, w: torch.Tensor, dLdy: torch.Tensor,
     if st != OK:
         raise InvconvError(st, "invconv_conv_bwd")
     return dLdx, dLdw
+
+
+def flowstep_workspace_bytes(B: int, C: int, H: int, W: int, k: int) -> int:
+    return int(lib().invconv_flowstep_workspace_bytes(B, C, H, W, k))
+
+
+def _flow_params(w, s, b, Q):
+    C = w.shape[0]
+    _check(s, "s", (C,)), _check(b, "b", (C,)), _check(Q, "Q", (C, C))
+
+
+def invconv_flowstep_fwd(y: torch.Tensor, w: torch.Tensor, s: torch.Tensor, b: torch.Tensor, Q: torch.Tensor,
+                         out: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                         form: int = FLOW_AUTO):
+    """(z, logdet) of one flow step: z = Q (s * invconv_w(y) + b); logdet = log|det dz/dy| of one image."""
+    _check(y, "y"), _check(w, "w")
+    B, C, H, W, k = _dims(y, w)
+    _flow_params(w, s, b, Q)
+    z = torch.empty_like(y) if out is None else _check(out, "out", y.shape)
+    ld = torch.empty(1, dtype=torch.float32, device=y.device)
+    if workspace is None:
+        workspace = new_workspace(flowstep_workspace_bytes(B, C, H, W, k), y.device)
+    st = lib().invconv_flowstep_fwd_ex(y.data_ptr(), w.data_ptr(), s.data_ptr(), b.data_ptr(), Q.data_ptr(),
+                                       z.data_ptr(), ld.data_ptr(), B, C, H, W, k, workspace.data_ptr(),
+                                       workspace.numel(), _stream(), form)
+    if st != OK:
+        raise InvconvError(st, "invconv_flowstep_fwd")
+    return z, ld
+
+
+def invconv_flowstep_bwd(z: torch.Tensor, w: torch.Tensor, s: torch.Tensor, b: torch.Tensor, Q: torch.Tensor,
+                         dLdz: torch.Tensor, logdet_weight: float = 0.0, workspace: torch.Tensor | None = None,
+                         form: int = FLOW_AUTO, out: dict | None = None):
+    """dict(dy, dw, ds, db, dQ) of one flow step from its output z and dL/dz."""
+    _check(z, "z"), _check(w, "w"), _check(dLdz, "dLdz", z.shape)
+    B, C, H, W, k = _dims(z, w)
+    _flow_params(w, s, b, Q)
+    if out is None:
+        dy, dw = torch.empty_like(z), torch.empty_like(w)
+        ds, db, dQ = torch.empty_like(s), torch.empty_like(b), torch.empty_like(Q)
+    else:
+        dy, dw, ds, db, dQ = (out[n] for n in ("dy", "dw", "ds", "db", "dQ"))
+    if workspace is None:
+        workspace = new_workspace(flowstep_workspace_bytes(B, C, H, W, k), z.device)
+    st = lib().invconv_flowstep_bwd_ex(z.data_ptr(), w.data_ptr(), s.data_ptr(), b.data_ptr(), Q.data_ptr(),
+                                       dLdz.data_ptr(), dy.data_ptr(), dw.data_ptr(), ds.data_ptr(), db.data_ptr(),
+                                       dQ.data_ptr(), float(logdet_weight), B, C, H, W, k, workspace.data_ptr(),
+                                       workspace.numel(), _stream(), form)
+    if st != OK:
+        raise InvconvError(st, "invconv_flowstep_bwd")
+    return dict(dy=dy, dw=dw, ds=ds, db=db, dQ=dQ)

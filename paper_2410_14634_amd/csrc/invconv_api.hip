@@ -389,6 +389,160 @@ invconv_status invconv_logdet(const float *w, int C, int H, int W, int k, float 
 
 namespace {
 
+// Workspace of the flow-step calls: the workspace of invconv_bwd for the same shape first (so that the
+// separate-pass form can hand its start to the backward pass of the inverse convolution, sharing the header),
+// then the step's small matrices, the summed rows, the partial rows, and two activation-sized buffers for the
+// separate-pass form (x recomputed from z, and A^T dL/dz).
+struct FlowLayout {
+    size_t bwd_bytes, mats_off, sums_off, rows_off, tmp_off, tmp_bytes, total;
+};
+
+bool flow_layout(int B, int C, int H, int W, int k, FlowLayout *lay)
+{
+    WsLayout bl;
+    if (check_shape(B, C, H, W, k) != INVCONV_OK || !ws_layout(B, C, H, W, k, true, &bl))
+        return false;
+    const size_t P = (size_t)C * C * k * k, E2 = (size_t)C * C + C;
+    lay->bwd_bytes = bl.total;
+    lay->mats_off = bl.total;
+    lay->sums_off = lay->mats_off + up256(flow_mats_floats(C) * sizeof(float));
+    lay->rows_off = lay->sums_off + up256((P + E2) * sizeof(float));
+    const size_t rows_fused = (size_t)B * (P + E2), rows_sep = flow_stat_rows(B, H * W) * E2;
+    lay->tmp_off = lay->rows_off + up256((rows_fused > rows_sep ? rows_fused : rows_sep) * sizeof(float));
+    lay->tmp_bytes = up256((size_t)B * C * H * W * sizeof(float));
+    lay->total = lay->tmp_off + 2 * lay->tmp_bytes;
+    return true;
+}
+
+bool aligned16(const void *a, const void *b, const void *c = nullptr, const void *d = nullptr)
+{
+    return (((size_t)a | (size_t)b | (size_t)c | (size_t)d) & 15) == 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t invconv_flowstep_workspace_bytes(int B, int C, int H, int W, int k)
+{
+    FlowLayout lay;
+    return flow_layout(B, C, H, W, k, &lay) ? lay.total : 0;
+}
+
+invconv_status invconv_flowstep_fwd(const float *y, const float *w, const float *s, const float *b, const float *Q,
+                                    float *z, float *logdet, int B, int C, int H, int W, int k, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    return invconv_flowstep_fwd_ex(y, w, s, b, Q, z, logdet, B, C, H, W, k, workspace, workspace_bytes, stream,
+                                   INVCONV_FLOW_AUTO);
+}
+
+invconv_status invconv_flowstep_fwd_ex(const float *y, const float *w, const float *s, const float *b, const float *Q,
+                                       float *z, float *logdet, int B, int C, int H, int W, int k, void *workspace,
+                                       size_t workspace_bytes, void *stream, int form)
+{
+    if (form < INVCONV_FLOW_AUTO || form > INVCONV_FLOW_FUSED)
+        return INVCONV_ERR_VARIANT;
+    if (!y || !w || !s || !b || !Q || !z)
+        return INVCONV_ERR_NULL;
+    if (int st = check_shape(B, C, H, W, k))
+        return st;
+    if (z == y || (const float *)z == w || (const float *)z == s || (const float *)z == b || (const float *)z == Q ||
+        (logdet && (logdet == z || (const float *)logdet == y)))
+        return INVCONV_ERR_ALIAS;
+    FlowLayout lay;
+    if (!flow_layout(B, C, H, W, k, &lay))
+        return INVCONV_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < lay.total || ((size_t)workspace & 255))
+        return INVCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    float *mats = (float *)(ws + lay.mats_off);
+    if (int rc = launch_flow_prep(w, s, b, Q, mats, logdet, C, H, W, k, st))
+        return rc;
+    if (form != INVCONV_FLOW_SEPARATE && flow_fused_supported(C, H, W, k) && aligned16(y, z) &&
+        (form == INVCONV_FLOW_FUSED || flow_fused_preferred(B, C, H, W)))
+        return launch_flow_fwd_tile(y, w, mats, z, B, C, H, W, k, st);
+    // separate passes: the solve into scratch, then the affine channel map
+    float *x = (float *)(ws + lay.tmp_off);
+    WsLayout bl;
+    ws_layout(B, C, H, W, k, true, &bl);
+    if (int rc = fwd_impl(y, w, x, B, C, H, W, k, stream, INVCONV_VARIANT_AUTO, solve_ws_of(workspace, bl)))
+        return rc;
+    return launch_flow_affine(false, x, mats, mats + (size_t)C * C, z, B, C, H * W, st);
+}
+
+invconv_status invconv_flowstep_bwd(const float *z, const float *w, const float *s, const float *b, const float *Q,
+                                    const float *dLdz, float *dLdy, float *dLdw, float *dLds, float *dLdb,
+                                    float *dLdQ, float logdet_weight, int B, int C, int H, int W, int k,
+                                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    return invconv_flowstep_bwd_ex(z, w, s, b, Q, dLdz, dLdy, dLdw, dLds, dLdb, dLdQ, logdet_weight, B, C, H, W, k,
+                                   workspace, workspace_bytes, stream, INVCONV_FLOW_AUTO);
+}
+
+invconv_status invconv_flowstep_bwd_ex(const float *z, const float *w, const float *s, const float *b, const float *Q,
+                                       const float *dLdz, float *dLdy, float *dLdw, float *dLds, float *dLdb,
+                                       float *dLdQ, float logdet_weight, int B, int C, int H, int W, int k,
+                                       void *workspace, size_t workspace_bytes, void *stream, int form)
+{
+    if (form < INVCONV_FLOW_AUTO || form > INVCONV_FLOW_FUSED)
+        return INVCONV_ERR_VARIANT;
+    if (!z || !w || !s || !b || !Q || !dLdz || !dLdy || !dLdw || !dLds || !dLdb || !dLdQ)
+        return INVCONV_ERR_NULL;
+    if (int st = check_shape(B, C, H, W, k))
+        return st;
+    const float *ins[] = {z, w, s, b, Q, dLdz};
+    float *outs[] = {dLdy, dLdw, dLds, dLdb, dLdQ};
+    for (float *o : outs) {
+        for (const float *i : ins)
+            if ((const float *)o == i)
+                return INVCONV_ERR_ALIAS;
+    }
+    for (int a = 0; a < 5; ++a)
+        for (int c = a + 1; c < 5; ++c)
+            if (outs[a] == outs[c])
+                return INVCONV_ERR_ALIAS;
+    FlowLayout lay;
+    if (!flow_layout(B, C, H, W, k, &lay))
+        return INVCONV_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < lay.total || ((size_t)workspace & 255))
+        return INVCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    float *mats = (float *)(ws + lay.mats_off), *sums = (float *)(ws + lay.sums_off), *rows = (float *)(ws + lay.rows_off);
+    const int P = C * C * k * k, E2 = C * C + C;
+    if (int rc = launch_flow_prep(w, s, b, Q, mats, nullptr, C, H, W, k, st))
+        return rc;
+    if (form != INVCONV_FLOW_SEPARATE && flow_fused_supported(C, H, W, k) && aligned16(z, dLdz, dLdy) &&
+        (form == INVCONV_FLOW_FUSED || flow_fused_preferred(B, C, H, W))) {
+        if (int rc = launch_flow_bwd_tile(z, w, dLdz, mats, dLdy, rows, B, C, H, W, k, st))
+            return rc;
+        if (int rc = launch_rows_sum(rows, B, P + E2, P + E2, sums, st))
+            return rc;
+        return launch_flow_finish(sums, 1, w, s, b, Q, mats, dLdw, dLds, dLdb, dLdQ, logdet_weight, C, H, W, k, st);
+    }
+    // separate passes: x = A^-1 z + e and g = A^T dL/dz into scratch, the backward pass of the inverse
+    // convolution on them, the two sums of the neighbours' gradients, and the common last kernel
+    float *x = (float *)(ws + lay.tmp_off), *g = (float *)(ws + lay.tmp_off + lay.tmp_bytes);
+    const size_t CC = (size_t)C * C;
+    if (int rc = launch_flow_affine(false, z, mats + CC + C, mats + 2 * CC + C, x, B, C, H * W, st))
+        return rc;
+    if (int rc = launch_flow_affine(true, dLdz, mats, nullptr, g, B, C, H * W, st))
+        return rc;
+    if (int rc = invconv_bwd(x, w, g, dLdy, dLdw, B, C, H, W, k, workspace, lay.bwd_bytes, stream))
+        return rc;
+    if (int rc = launch_flow_stats(dLdz, x, rows, B, C, H * W, st))
+        return rc;
+    if (int rc = launch_rows_sum(rows, (int)flow_stat_rows(B, H * W), E2, E2, sums, st))
+        return rc;
+    return launch_flow_finish(sums, 0, w, s, b, Q, mats, dLdw, dLds, dLdb, dLdQ, logdet_weight, C, H, W, k, st);
+}
+
+}  // extern "C"
+
+namespace {
+
 struct ChainLayout {
     size_t flags_bytes, grad_bytes, dw_bytes, total;
 };

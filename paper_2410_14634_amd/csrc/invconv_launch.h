@@ -108,4 +108,24 @@ int launch_conv(int dir, const float *x, const float *w, float *y, int B, int C,
                 hipStream_t stream);
 int launch_logdet(const float *w, int C, int H, int W, int k, float *out, hipStream_t stream);
 
+// One flow step (inverse convolution, per-channel affine map, 1 x 1 convolution): invconv_flow.hip
+size_t flow_mats_floats(int C);
+bool flow_fused_supported(int C, int H, int W, int k);
+bool flow_fused_preferred(int B, int C, int H, int W);
+size_t flow_stat_rows(int B, int HW);
+int launch_flow_prep(const float *w, const float *s, const float *b, const float *Q, float *mats, float *logdet, int C,
+                     int H, int W, int k, hipStream_t stream);
+// out[n][o][p] = add[o] + sum_i M[o][i] in[n][i][p] (transposed: M[i][o]); add may be null
+int launch_flow_affine(bool transposed, const float *in, const float *M, const float *add, float *out, int B, int C,
+                       int HW, hipStream_t stream);
+int launch_flow_stats(const float *gz, const float *x, float *rows, int B, int C, int HW, hipStream_t stream);
+int launch_rows_sum(const float *rows, int nrows, int stride, int E, float *out, hipStream_t stream);
+int launch_flow_finish(const float *sums, int have_dw, const float *w, const float *s, const float *b, const float *Q,
+                       const float *mats, float *dLdw, float *dLds, float *dLdb, float *dLdQ, float lw, int C, int H,
+                       int W, int k, hipStream_t stream);
+int launch_flow_fwd_tile(const float *y, const float *w, const float *mats, float *z, int B, int C, int H, int W, int k,
+                         hipStream_t stream);
+int launch_flow_bwd_tile(const float *z, const float *w, const float *gz, const float *mats, float *v, float *part,
+                         int B, int C, int H, int W, int k, hipStream_t stream);
+
 }  // namespace invconv

@@ -21,338 +21,10 @@
 // four result registers are the pixel's output channels).
 #include "invconv_common.h"
 #include "invconv_launch.h"
+#include "invconv_wave_solve.h"
 #include <type_traits>
 
 namespace invconv {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-// value of the lane above (lane 0 receives 0)
-__device__ __forceinline__ float from_lane_above(float v)
-{
-    return __builtin_bit_cast(
-        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x138 /* wave_shr:1 */, 0xf, 0xf, true));
-}
-
-// value of the lane above; lane 0 keeps `first` (what the row above the wave's first row sent)
-__device__ __forceinline__ float from_lane_above_or(float first, float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, first),
-                                                                 __builtin_bit_cast(int, v), 0x138 /* wave_shr:1 */,
-                                                                 0xf, 0xf, false));
-}
-
-constexpr int kWavePF = 16;   // steps of load prefetch
-
-// Weight preparation in registers, by every lane for itself (the kernel reads w
-// with uniform addresses only): Linv = inverse of the lower-triangular
-// current-pixel block; the lane keeps row o = lane%4 of it (zeros for o >= C) and
-// folds it into every other tap.  MFMA A operands of this lane:
-//   wLi[j] = Linv[o][j],   wA[a][db][i] = -(Linv W_tap)[o][i] for tap (a,db) up/left.
-template <int C, int K, int DIR>
-__device__ __forceinline__ void wave_fold_regs(const float *__restrict__ w, int o_lane, float (&wA)[K][K][C],
-                                               float (&wLi)[C])
-{
-    float Lm[C][C], Li[C][C], rd[C];
-#pragma unroll
-    for (int o = 0; o < C; ++o)
-#pragma unroll
-        for (int i = 0; i < C; ++i)
-            Lm[o][i] = weff<DIR>(w, C, K, o, i, K - 1, K - 1);
-#pragma unroll
-    for (int o = 0; o < C; ++o)
-        rd[o] = 1.0f / Lm[o][o];
-#pragma unroll
-    for (int j = 0; j < C; ++j) {
-#pragma unroll
-        for (int o = 0; o < C; ++o) {
-            if (o < j) {
-                Li[o][j] = 0.0f;
-            } else if (o == j) {
-                Li[o][j] = rd[j];
-            } else {
-                float sum = 0.0f;
-#pragma unroll
-                for (int m = j; m < o; ++m)
-                    sum += Lm[o][m] * Li[m][j];
-                Li[o][j] = -sum * rd[o];
-            }
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < C; ++j) {
-        float v = 0.0f;
-#pragma unroll
-        for (int o = 0; o < C; ++o)
-            v = (o_lane == o) ? Li[o][j] : v;
-        wLi[j] = v;
-    }
-#pragma unroll
-    for (int a = 0; a < K; ++a)
-#pragma unroll
-        for (int db = 0; db < K; ++db)
-#pragma unroll
-            for (int i = 0; i < C; ++i) {
-                float sum = 0.0f;
-                if (a != 0 || db != 0) {
-#pragma unroll
-                    for (int j = 0; j < C; ++j)
-                        sum += wLi[j] * weff<DIR>(w, C, K, j, i, K - 1 - a, K - 1 - db);
-                }
-                wA[a][db][i] = -sum;
-            }
-}
-
-
-// Images of more than 64 rows are cut into bands of 64 rows, one wave each, all in one workgroup
-// (BANDS).  A band is the single-wave solve on its own rows and its own clock (local step j,
-// lane l at column j - l); what row 63 of the band above would have handed to lane 0 through the
-// DPP shift arrives through LDS instead: after its local step j' the upper band's lane 63 appends
-// its messages T[1..K-1] to a log, entry j'; the lower band's lane 0 needs entry j + 63 at its step
-// j (its row is 64 rows further down, so the same anti-diagonal is 64 local steps earlier).  The
-// log keeps every step (no slot is reused, so a fast upper band can never overwrite what the
-// lower one has not read), progress is published once per block of kWavePF steps in an LDS
-// counter, and the lower band starts a block only when the counter covers the block's last entry.
-// The upper band never waits for the lower one, so the waits end; they are bounded all the same.
-struct WaveBands {
-    int band;           // this wave's band
-    int nbands;
-    const f32x4 *log_in;    // [log_steps][K - 1]: what the band above sent (valid offset also for band 0)
-    f32x4 *log_out;         // [log_steps][K - 1]: what this band sends (valid offset also for the last band)
-    const int *prog_in;     // local steps of the band above whose entries are in log_in
-    int *prog_out;          // local steps of this band whose entries are in log_out
-    int log_steps;      // entries per band, a multiple of kWavePF
-    f32x4 *scratch;     // [64][K - 1] write-only dump for the lanes that have nothing to send
-    int spin_limit;     // polls of prog_in before a waiting band gives up
-    int *err;           // device error word (may be null): set to 1 when a wait ran out
-};
-
-// Body of the solve for image n, executed by one full wave (lanes 0..63 of the
-// calling workgroup).  With LDS_COPY the result is also written to lds_copy as a
-// [C][H][W] tile in image (not mirrored) coordinates.
-// With TILE the image lives in lds_copy (input on entry, result on return) and global memory is not touched.
-template <int C, int K, int DIR, bool LDS_COPY, bool BANDS = false, bool TILE = false>
-__device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, const float *__restrict__ w,
-                                                float *__restrict__ out, int H, int W, int n, float *lds_copy,
-                                                WaveBands wb = WaveBands{})
-{
-    static_assert(C >= 1 && C <= 4, "one 4-row MFMA block per pixel");
-    // All 64 lanes stay active to the end: the matrix instruction reads its weight
-    // operand from every lane of a 4-lane block, whatever the execution mask says.
-    // Lanes past the last row compute on clamped inputs and never store.
-    const int r = threadIdx.x & 63;                   // row inside the band = lane
-    const int grow = BANDS ? 64 * wb.band + r : r;    // image row
-    const bool row_ok = grow < H;
-    const int rr = row_ok ? grow : H - 1;
-    const int o_lane = r & 3;
-    const unsigned Wst = row_ok ? (unsigned)W : 0u;   // columns this lane may store
-
-    // Element (ch, r, c) of this image, in solve coordinates, sits at
-    // chan[ch] (uniform pointer) + rowoff (per lane) +- 4c bytes: one 32-bit lane
-    // offset serves all channels, the addressing form global loads take directly.
-    const size_t img = (size_t)n * C * H * W;
-    const char *chan_src[C];
-    char *chan_dst[C];
-    char *chan_lds[C];
-#pragma unroll
-    for (int ch = 0; ch < C; ++ch) {
-        const size_t cb = (size_t)(DIR ? C - 1 - ch : ch) * H * W;
-        chan_src[ch] = reinterpret_cast<const char *>(in + img + cb);
-        chan_dst[ch] = reinterpret_cast<char *>(out + img + cb);
-        chan_lds[ch] = reinterpret_cast<char *>(lds_copy + cb);
-    }
-    constexpr int kStep = DIR ? -4 : 4;               // bytes per column in solve order
-    const int row0 = 4 * (DIR ? (H - 1 - rr) * W + (W - 1) : rr * W);   // byte offset of column 0
-    const int rowlo = DIR ? row0 - 4 * (W - 1) : row0;                   // lowest / highest byte offset
-    const int rowhi = DIR ? row0 : row0 + 4 * (W - 1);                   // inside this row
-    auto clamp_row = [&](int off) -> unsigned { return (unsigned)(off < rowlo ? rowlo : (off > rowhi ? rowhi : off)); };
-    auto ld = [&](int ch, unsigned off) -> float {
-        return *reinterpret_cast<const float *>((TILE ? chan_lds[ch] : chan_src[ch]) + off);
-    };
-    // A band whose bounded wait for the band above ran out has no valid input any more: from then on it
-    // stores NaN instead of results, so that a lost hand-over can never pass for a solution.
-    bool lost = false;
-    auto st = [&](int ch, unsigned off, float v) {
-        if (BANDS)
-            v = lost ? __builtin_nanf("") : v;
-        if (!TILE)
-            *reinterpret_cast<float *>(chan_dst[ch] + off) = v;
-        if (LDS_COPY || TILE)
-            *reinterpret_cast<float *>(chan_lds[ch] + off) = v;
-    };
-
-    // Loads are unconditional (offset clamped into the row) so that they stay in
-    // flight for kWavePF steps without the compiler having to assume the worst at
-    // control-flow joins; out-of-range loads are zeroed when consumed.  Slot s holds
-    // the input of the steps congruent to s.  The first batch is issued before the
-    // weight preparation so that both latencies overlap.
-    float yb[kWavePF][C];
-#pragma unroll
-    for (int u = 0; u < kWavePF; ++u) {
-        const unsigned off = clamp_row(row0 + kStep * (u - r));
-#pragma unroll
-        for (int ch = 0; ch < C; ++ch)
-            yb[u][ch] = ld(ch, off);
-    }
-
-    float wA[K][K][C], wLi[C];
-    wave_fold_regs<C, K, DIR>(w, o_lane, wA, wLi);
-
-    float xh[C][K];      // xh[i][db] = x(r, c-db), db >= 1
-    f32x4 T[K];          // T[a][o], a >= 1: message for pixel (r+a, c), negated sums
-#pragma unroll
-    for (int i = 0; i < C; ++i) {
-#pragma unroll
-        for (int db = 0; db < K; ++db)
-            xh[i][db] = 0.0f;
-    }
-#pragma unroll
-    for (int a = 0; a < K; ++a)
-        T[a] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // Have every initial load landed before the loop, so that inside the loop the
-    // compiler's wait counts only need to cover the loads of the loop itself.
-#pragma unroll
-    for (int u = 0; u < kWavePF; ++u)
-#pragma unroll
-        for (int ch = 0; ch < C; ++ch)
-            asm volatile("" : "+v"(yb[u][ch]));
-
-    // own = Linv y - (own-row taps), everything of the coming pixel that does not
-    // depend on the rows above; prepared one step ahead.
-    int c = -r;                                       // column of this lane at the current step
-    int ldoff = row0 + kStep * (kWavePF - r);         // unclamped offset of the next refill
-    f32x4 own = f32x4{0.f, 0.f, 0.f, 0.f};
-    {
-        const bool in_row = (unsigned)c < (unsigned)W;
-#pragma unroll
-        for (int j = 0; j < C; ++j)
-            own = __builtin_amdgcn_mfma_f32_4x4x1f32(wLi[j], in_row ? yb[0][j] : 0.0f, own, 0, 0, 0);
-        const unsigned off = clamp_row(ldoff);
-#pragma unroll
-        for (int ch = 0; ch < C; ++ch)
-            yb[0][ch] = ld(ch, off);
-        ldoff += kStep;
-    }
-
-    const int band_rows = BANDS ? (H - 64 * wb.band < 64 ? H - 64 * wb.band : 64) : H;
-    const int nsteps = band_rows + W - 1;
-    const bool recv = BANDS && wb.band > 0, send = BANDS && wb.band + 1 < wb.nbands;
-    // (plain offsets from the LDS base, never a null alternative: the accesses stay LDS instructions)
-    const f32x4 *log_in = wb.log_in;
-    f32x4 *log_out = wb.log_out;
-    f32x4 M[K];          // M[a]: what the band above sent for this step (used by lane 0 only)
-#pragma unroll
-    for (int a = 0; a < K; ++a)
-        M[a] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int t0 = 0; t0 < nsteps; t0 += kWavePF) {
-        if (recv && !lost) {
-            // entries t0 + 63 .. t0 + 63 + kWavePF - 1 of the upper band's log are needed
-            int need = t0 + 64 + kWavePF;
-            need = need > wb.log_steps ? wb.log_steps : need;
-            int spins = 0;
-            while (__hip_atomic_load(wb.prog_in, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < need &&
-                   ++spins < wb.spin_limit)
-                __builtin_amdgcn_s_sleep(1);
-            if (__hip_atomic_load(wb.prog_in, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < need) {
-                lost = true;        // the wait ran out: carry on (every wave still finishes), results are NaN
-                if (wb.err && r == 0)
-                    __hip_atomic_store(wb.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        // Entry of the first step now, the others one step ahead of their use (volatile: the read is
-        // issued where it is written, well before the value is needed).
-        f32x4 Mn[K];
-        if (recv) {
-            const int e = t0 + 63 < wb.log_steps ? t0 + 63 : wb.log_steps - 1;
-#pragma unroll
-            for (int a = 1; a < K; ++a)
-                M[a] = log_in[e * (K - 1) + a - 1];
-        }
-#pragma unroll
-        for (int u = 0; u < kWavePF; ++u) {
-            if (recv && u + 1 < kWavePF) {
-                int e = t0 + u + 64;
-                e = e < wb.log_steps ? e : wb.log_steps - 1;     // past the upper band's last step: unused
-#pragma unroll
-                for (int a = 1; a < K; ++a)
-                    Mn[a] = *(const volatile __attribute__((address_space(3))) f32x4 *)(log_in + e * (K - 1) + a - 1);
-            }
-            // x(r,c) = own + (message from the row above, computed there one step ago)
-            float xn[C];
-#pragma unroll
-            for (int o = 0; o < C; ++o)
-                xn[o] = own[o] + (BANDS ? from_lane_above_or(M[1][o], T[1][o]) : from_lane_above(T[1][o]));
-            if ((unsigned)c < Wst) {
-                const unsigned off = (unsigned)(row0 + kStep * c);
-#pragma unroll
-                for (int o = 0; o < C; ++o)
-                    st(o, off, xn[o]);
-            }
-#pragma unroll
-            for (int i = 0; i < C; ++i)
-                xh[i][0] = xn[i];
-            // messages for the rows below: T[a] = S[a+1] + this row's taps
-#pragma unroll
-            for (int a = 1; a < K; ++a) {
-                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (a + 1 < K) {
-#pragma unroll
-                    for (int o = 0; o < C; ++o)
-                        acc[o] = BANDS ? from_lane_above_or(M[a + 1][o], T[a + 1][o]) : from_lane_above(T[a + 1][o]);
-                }
-#pragma unroll
-                for (int db = K - 1; db >= 0; --db)     // oldest column first: only db = 0 waits for this step's result
-#pragma unroll
-                    for (int i = 0; i < C; ++i)
-                        acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[a][db][i], xh[i][db], acc, 0, 0, 0);
-                T[a] = acc;
-            }
-            if (send) {
-                // lane 63 appends to the log; the other lanes write to a scratch line of their own, so that
-                // no branch surrounds the LDS write (a branch makes the wait counters conservative)
-                f32x4 *dst = r == 63 ? log_out + (t0 + u) * (K - 1) : wb.scratch + r * (K - 1);
-#pragma unroll
-                for (int a = 1; a < K; ++a)
-                    dst[a - 1] = T[a];
-            }
-            if (recv && u + 1 < kWavePF) {
-#pragma unroll
-                for (int a = 1; a < K; ++a)
-                    M[a] = Mn[a];
-            }
-            // shift the row history and prepare `own` for the next pixel
-#pragma unroll
-            for (int i = 0; i < C; ++i)
-#pragma unroll
-                for (int db = K - 1; db >= 1; --db)
-                    xh[i][db] = xh[i][db - 1];
-            c += 1;
-            {
-                const int s = (u + 1) % kWavePF;     // slot of the next step (static after unrolling)
-                const bool in_row = (unsigned)c < (unsigned)W;
-                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int j = 0; j < C; ++j)
-                    acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wLi[j], in_row ? yb[s][j] : 0.0f, acc, 0, 0, 0);
-#pragma unroll
-                for (int db = K - 1; db >= 1; --db)
-#pragma unroll
-                    for (int i = 0; i < C; ++i)
-                        acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[0][db][i], xh[i][db], acc, 0, 0, 0);
-                own = acc;
-                // refill the slot with the input kWavePF steps later
-                const unsigned off = clamp_row(ldoff);
-#pragma unroll
-                for (int ch = 0; ch < C; ++ch)
-                    yb[s][ch] = ld(ch, off);
-                ldoff += kStep;
-            }
-        }
-        if (send)       // the block's log entries are written (LDS operations of a wave complete in order)
-            __hip_atomic_store(wb.prog_out, t0 + kWavePF, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-    }
-}
 
 // log|det dx/dy| of one image (Section 4), -H*W*sum_c log|w[c][c][K-1][K-1]|, by the calling wave: the
 // forward kernels of few-channel images write it on the side (first workgroup only), so that a training
