@@ -489,6 +489,7 @@ def scale_study(reps=30):
 FLOW_SHAPES = {  # (B, C, H, W, k)
     "workload1": (16, 3, 32, 32, 3), "workload3": (32, 3, 64, 64, 5),
     "batch_1024": (1024, 3, 32, 32, 3), "batch_4096": (4096, 3, 32, 32, 3), "batch_1024_64x64": (1024, 3, 64, 64, 3),
+    "workload4_layer": (32, 12, 128, 128, 3), "batch_256_c12": (256, 12, 64, 64, 3),
 }
 
 
@@ -512,7 +513,11 @@ def flow_step_study(reps=50):
                      dQ=torch.empty_like(Q))
         row = dict(B=B, C=C, H=H, W=W, k=k)
         n = B * C * H * W
-        for form, tag, bytes_per_elt in ((b.FLOW_FUSED, "fused", 20.0), (b.FLOW_SEPARATE, "separate", 60.0)):
+        # 8-16 channels: forward fully fused (8), backward solve fused (8) + x recomputed once (8) + dL/dw (8) + sums (8);
+        # separate passes: 24 forward, 40 backward (few channels: the fused dL/dw kernel saves 4 of them)
+        fused_bytes = 20.0 if C <= 4 else 40.0
+        sep_bytes = 60.0 if C <= 4 else 64.0
+        for form, tag, bytes_per_elt in ((b.FLOW_FUSED, "fused", fused_bytes), (b.FLOW_SEPARATE, "separate", sep_bytes)):
             fwd = lambda: b.invconv_flowstep_fwd(y, w, s, bb, Q, out=z, workspace=ws, form=form)
             bwd = lambda: b.invconv_flowstep_bwd(z, w, s, bb, Q, g, logdet_weight=-float(B), workspace=ws, form=form,
                                                  out=grads)

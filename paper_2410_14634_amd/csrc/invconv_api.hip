@@ -407,11 +407,41 @@ bool flow_layout(int B, int C, int H, int W, int k, FlowLayout *lay)
     lay->mats_off = bl.total;
     lay->sums_off = lay->mats_off + up256(flow_mats_floats(C) * sizeof(float));
     lay->rows_off = lay->sums_off + up256((P + E2) * sizeof(float));
-    const size_t rows_fused = (size_t)B * (P + E2), rows_sep = flow_stat_rows(B, H * W) * E2;
-    lay->tmp_off = lay->rows_off + up256((rows_fused > rows_sep ? rows_fused : rows_sep) * sizeof(float));
+    // partial rows: the fused few-channel kernel's [P | C*C | C] per image, or the generic sums' rows, or
+    // (C <= 16) the partial sums of the matrix-core correlation with k = 1 followed by one value per plane
+    size_t rows_bytes = (size_t)B * (P + E2) * sizeof(float);
+    const size_t rows_sep = flow_stat_rows(B, H * W) * E2 * sizeof(float);
+    rows_bytes = rows_bytes > rows_sep ? rows_bytes : rows_sep;
+    const DwPlan p1 = plan_dw_any(B, C, H, W, 1);
+    if (p1.rt) {
+        const size_t with_planes = up256(p1.bytes) + (size_t)B * C * sizeof(float);
+        rows_bytes = rows_bytes > with_planes ? rows_bytes : with_planes;
+    }
+    lay->tmp_off = lay->rows_off + up256(rows_bytes);
     lay->tmp_bytes = up256((size_t)B * C * H * W * sizeof(float));
     lay->total = lay->tmp_off + 2 * lay->tmp_bytes;
     return true;
+}
+
+// M2[o][i] = sum dLdz[o] x[i] and m1[o] = sum dLdz[o] over batch and pixels into sums = [C*C | C]
+int flow_sums(const float *dLdz, const float *x, float *rows, float *sums, int B, int C, int H, int W, hipStream_t st)
+{
+    const int E2 = C * C + C;
+    const DwPlan p1 = plan_dw_any(B, C, H, W, 1);
+    if (dw_mfma_supported(C, 1) && p1.rt && plan_dw_mfma(B, C, H, W, 1).rt) {
+        // the correlation of Eq. 4 with a 1 x 1 window, neither negated nor masked, is exactly M2
+        if (int rc = launch_dw_mfma_partial(x, dLdz, rows, p1, B, C, H, W, 1, st))
+            return rc;
+        if (int rc = launch_rows_sum(rows, (int)p1.nparts, C * C, C * C, sums, st))
+            return rc;
+        float *planes = (float *)((char *)rows + up256(p1.bytes));
+        if (int rc = launch_flow_plane_sum(dLdz, planes, B * C, H * W, st))
+            return rc;
+        return launch_rows_sum(planes, B, C, C, sums + (size_t)C * C, st);
+    }
+    if (int rc = launch_flow_stats(dLdz, x, rows, B, C, H * W, st))
+        return rc;
+    return launch_rows_sum(rows, (int)flow_stat_rows(B, H * W), E2, E2, sums, st);
 }
 
 bool aligned16(const void *a, const void *b, const void *c = nullptr, const void *d = nullptr)
@@ -463,6 +493,20 @@ invconv_status invconv_flowstep_fwd_ex(const float *y, const float *w, const flo
     if (form != INVCONV_FLOW_SEPARATE && flow_fused_supported(C, H, W, k) && aligned16(y, z) &&
         (form == INVCONV_FLOW_FUSED || flow_fused_preferred(B, C, H, W)))
         return launch_flow_fwd_tile(y, w, mats, z, B, C, H, W, k, st);
+    if (form != INVCONV_FLOW_SEPARATE && chain_supported(1, C, H, W, k) &&
+        (form == INVCONV_FLOW_FUSED || chain_single_preferred(B, C, H))) {
+        // 8-16 channels: the pipelined band kernel with the affine map applied by its storers
+        ChainArgs a{};
+        a.in0 = y;
+        a.w[0] = w;
+        a.out[0] = z;
+        a.map[0] = mats;
+        a.stages = 1;
+        a.B = B;
+        a.H = H;
+        a.W = W;
+        return launch_chain(0, a, C, k, st);
+    }
     // separate passes: the solve into scratch, then the affine channel map
     float *x = (float *)(ws + lay.tmp_off);
     WsLayout bl;
@@ -522,19 +566,48 @@ invconv_status invconv_flowstep_bwd_ex(const float *z, const float *w, const flo
             return rc;
         return launch_flow_finish(sums, 1, w, s, b, Q, mats, dLdw, dLds, dLdb, dLdQ, logdet_weight, C, H, W, k, st);
     }
-    // separate passes: x = A^-1 z + e and g = A^T dL/dz into scratch, the backward pass of the inverse
-    // convolution on them, the two sums of the neighbours' gradients, and the common last kernel
     float *x = (float *)(ws + lay.tmp_off), *g = (float *)(ws + lay.tmp_off + lay.tmp_bytes);
     const size_t CC = (size_t)C * C;
+    if (form != INVCONV_FLOW_SEPARATE && chain_supported(1, C, H, W, k) &&
+        (form == INVCONV_FLOW_FUSED || chain_single_preferred(B, C, H))) {
+        // 8-16 channels: the transposed solve in the pipelined band kernel with A^T folded into its input
+        // weights (dL/dz in, dL/dy out); x is recomputed once into scratch for the two sums over pixels
+        ChainArgs a{};
+        a.in0 = dLdz;
+        a.w[0] = w;
+        a.out[0] = dLdy;
+        a.map[0] = mats;
+        a.stages = 1;
+        a.B = B;
+        a.H = H;
+        a.W = W;
+        if (int rc = launch_chain(1, a, C, k, st))
+            return rc;
+        if (int rc = launch_flow_affine(false, z, mats + CC + C, mats + 2 * CC + C, x, B, C, H * W, st))
+            return rc;
+        WsLayout bl;
+        ws_layout(B, C, H, W, k, true, &bl);
+        const DwPlan p = plan_dw_any(B, C, H, W, k);
+        float *part = (float *)(ws + bl.dw_off);
+        if (dw_mfma_supported(C, k) && plan_dw_mfma(B, C, H, W, k).rt) {
+            if (int rc = launch_dw_mfma(x, dLdy, dLdw, part, p, B, C, H, W, k, st))
+                return rc;
+        } else if (int rc = launch_dw(x, dLdy, dLdw, part, p, B, C, H, W, k, st)) {
+            return rc;
+        }
+        if (int rc = flow_sums(dLdz, x, rows, sums, B, C, H, W, st))
+            return rc;
+        return launch_flow_finish(sums, 0, w, s, b, Q, mats, dLdw, dLds, dLdb, dLdQ, logdet_weight, C, H, W, k, st);
+    }
+    // separate passes: x = A^-1 z + e and g = A^T dL/dz into scratch, the backward pass of the inverse
+    // convolution on them, the two sums of the neighbours' gradients, and the common last kernel
     if (int rc = launch_flow_affine(false, z, mats + CC + C, mats + 2 * CC + C, x, B, C, H * W, st))
         return rc;
     if (int rc = launch_flow_affine(true, dLdz, mats, nullptr, g, B, C, H * W, st))
         return rc;
     if (int rc = invconv_bwd(x, w, g, dLdy, dLdw, B, C, H, W, k, workspace, lay.bwd_bytes, stream))
         return rc;
-    if (int rc = launch_flow_stats(dLdz, x, rows, B, C, H * W, st))
-        return rc;
-    if (int rc = launch_rows_sum(rows, (int)flow_stat_rows(B, H * W), E2, E2, sums, st))
+    if (int rc = flow_sums(dLdz, x, rows, sums, B, C, H, W, st))
         return rc;
     return launch_flow_finish(sums, 0, w, s, b, Q, mats, dLdw, dLds, dLdb, dLdQ, logdet_weight, C, H, W, k, st);
 }

@@ -87,7 +87,14 @@ constexpr int kCDone = 1 << 30;   // progress value published when a stage has f
 // 16 channels: a loader or storer wave has registers for one band only, so at most 4 bands (64 rows)
 __host__ __device__ constexpr int chain_io_bands(int C) { return C <= 12 ? 2 : 1; }
 
-template <int CG, int K, int DIR>
+// MAP: a stage may carry a per-pixel affine channel map of a flow step (a.map[stage] != null; C*C floats A,
+// then C floats d, true channel order).  In the plain orientation it is applied to the RESULT on its way
+// to memory: the compute wave forms A x + d with CG more matrix instructions (the same shape as Linv y: the
+// lane's own value in, the lane's own channels out) and puts that into the ring slot instead of x - the
+// recurrence keeps x in registers, the ring is only the way out.  In the mirrored orientation its transpose
+// is applied to the INPUT, g = A^T (input): the input enters the solve only through Linv y, so the map is
+// folded into Linv once and costs nothing per step.
+template <int CG, int K, int DIR, bool MAP = false>
 __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) void k_chain_band(ChainArgs a)
 {
     constexpr int C = 4 * CG;
@@ -112,6 +119,22 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sW);
+    const float *__restrict__ map = MAP ? a.map[stage] : nullptr;
+    if (MAP && DIR && map) {
+        // solve channel m is true channel C-1-m: the solve's input is y'[m] = sum_j A[C-1-j][C-1-m] in[j],
+        // so Linv <- Linv T with T[m][j] = A[C-1-j][C-1-m]  (scratch: the folding buffers, dead by now)
+        for (int idx = tid; idx < C * C; idx += blockDim.x) {
+            const int o = idx / C, j = idx % C;
+            float acc = 0.0f;
+            for (int m = 0; m < C; ++m)
+                acc += sLinv[o * C + m] * map[(C - 1 - j) * C + (C - 1 - m)];
+            sL[idx] = acc;
+        }
+        __syncthreads();
+        for (int idx = tid; idx < C * C; idx += blockDim.x)
+            sLinv[idx] = sL[idx];
+        __syncthreads();
+    }
 
     const int nrow = lane & 15, g = lane >> 4;       // compute: row of the band, channel group; i/o: row, quarter
     const int span = 16 + W - 1;                               // active steps of a band
@@ -141,6 +164,20 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
             for (int jj = 0; jj < CG; ++jj) {
                 const float lv = sLinv[om * C + CG * g + jj];
                 wLi[jj] = m_ok ? lv : 0.0f;
+            }
+        }
+        // output map of a flow step (plain orientation): weights laid out like wLi, bias per own channel
+        float wAz[CG], dz[CG];
+        const bool mapped = MAP && !DIR && map != nullptr;
+        if (MAP && !DIR) {
+            const int m = nrow;
+            const bool m_ok = (m & 3) < CG;
+            const int om = m_ok ? CG * (m >> 2) + (m & 3) : 0;
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj) {
+                const float av = mapped ? map[om * C + CG * g + jj] : 0.0f;
+                wAz[jj] = m_ok ? av : 0.0f;
+                dz[jj] = mapped ? map[C * C + CG * g + jj] : 0.0f;
             }
         }
         __syncthreads();        // everyone is done with sCf/sLinv reads and the folding scratch
@@ -226,10 +263,13 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                     const float up = chain_from_row_above(T[1][j]);
                     xn[j] = own[j] + (first_row ? mrow[1][j] : up);
                 }
-                // result replaces the input in the ring slot of this step (the storers skip invalid pixels)
+                // result replaces the input in the ring slot of this step (the storers skip invalid pixels);
+                // with an output map that is A x + d, formed behind the products the next step waits for
+                if (!(MAP && !DIR && mapped)) {
 #pragma unroll
-                for (int j = 0; j < CG; ++j)
-                    ring[cbase[j] + (((t - band) & (kCRing - 1)) ^ kSlotFlip)] = xn[j];
+                    for (int j = 0; j < CG; ++j)
+                        ring[cbase[j] + (((t - band) & (kCRing - 1)) ^ kSlotFlip)] = xn[j];
+                }
 #pragma unroll
                 for (int aa = 1; aa < K; ++aa) {
                     f32x4 acc = accT[aa];
@@ -242,6 +282,18 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
                 for (int jj = 0; jj < CG; ++jj)
                     accO = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][1][jj], xn[jj], accO, 0, 0, 0);
                 own = accO;
+                if (MAP && !DIR && mapped) {
+                    f32x4 accZ = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int j = 0; j < CG; ++j)
+                        accZ[j] = dz[j];
+#pragma unroll
+                    for (int jj = 0; jj < CG; ++jj)
+                        accZ = __builtin_amdgcn_mfma_f32_16x16x4f32(wAz[jj], xn[jj], accZ, 0, 0, 0);
+#pragma unroll
+                    for (int j = 0; j < CG; ++j)
+                        ring[cbase[j] + (((t - band) & (kCRing - 1)) ^ kSlotFlip)] = accZ[j];
+                }
                 if (last_row) {
                     float *mo = msg_out + (t & (kCMsg - 1)) * K * 64;
 #pragma unroll
@@ -529,9 +581,14 @@ size_t chain_flag_ints(int stages, int B) { return (size_t)stages * B * kCFlags;
 template <int CG, int K>
 static int launch_chain_ck(int dir, const ChainArgs &all, int C, hipStream_t stream)
 {
+    bool mapped = false;
+    for (int s = 0; s < all.stages; ++s)
+        mapped = mapped || all.map[s] != nullptr;
     const size_t lds = chain_lds_bytes(C, K, all.NB);
-    const void *fn = dir ? reinterpret_cast<const void *>(&k_chain_band<CG, K, 1>)
-                         : reinterpret_cast<const void *>(&k_chain_band<CG, K, 0>);
+    const void *fn = mapped ? (dir ? reinterpret_cast<const void *>(&k_chain_band<CG, K, 1, true>)
+                                   : reinterpret_cast<const void *>(&k_chain_band<CG, K, 0, true>))
+                            : (dir ? reinterpret_cast<const void *>(&k_chain_band<CG, K, 1>)
+                                   : reinterpret_cast<const void *>(&k_chain_band<CG, K, 0>));
     if (!ensure_dynamic_lds(fn, lds))
         return INVCONV_ERR_UNSUPPORTED;
     const int threads = 64 * (all.NB + 2 * kCIo);
@@ -551,6 +608,7 @@ static int launch_chain_ck(int dir, const ChainArgs &all, int C, hipStream_t str
         for (int s = 0; s < a.stages; ++s) {
             a.w[s] = all.w[s0 + s];
             a.out[s] = all.out[s0 + s];
+            a.map[s] = all.map[s0 + s];
         }
         if (a.stages > 1) {
             const int nflags = a.stages * a.B * kCFlags;
@@ -561,7 +619,11 @@ static int launch_chain_ck(int dir, const ChainArgs &all, int C, hipStream_t str
             a.flags = nullptr;      // one stage: nothing to wait for, nothing to publish
         }
         const dim3 grid((unsigned)(a.stages * a.B)), block((unsigned)threads);
-        if (dir)
+        if (mapped && dir)
+            hipLaunchKernelGGL((k_chain_band<CG, K, 1, true>), grid, block, lds, stream, a);
+        else if (mapped)
+            hipLaunchKernelGGL((k_chain_band<CG, K, 0, true>), grid, block, lds, stream, a);
+        else if (dir)
             hipLaunchKernelGGL((k_chain_band<CG, K, 1>), grid, block, lds, stream, a);
         else
             hipLaunchKernelGGL((k_chain_band<CG, K, 0>), grid, block, lds, stream, a);

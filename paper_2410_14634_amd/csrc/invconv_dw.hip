@@ -281,10 +281,18 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
     {
         // bank conflicts of the B operand reads: lane (nn, kk) of instruction s reads
         // i*sxc + a*xw + b + kk for column 16s + nn = (i, a, b); degree = most distinct addresses in one bank.
-        // The search costs about a millisecond of host time, so the last answer is remembered per thread.
+        // The search costs a fraction of a millisecond of host time, so the last few answers are remembered
+        // per thread (a call may plan several kernel sizes of one shape).
         struct Memo { int C, k, rt, W, xw, sxc; };
-        static thread_local Memo memo = {0, 0, 0, 0, 0, 0};
-        if (memo.C != C || memo.k != k || memo.rt != rt || memo.W != W) {
+        constexpr int kMemos = 16;
+        static thread_local Memo memos[kMemos] = {};
+        static thread_local int memo_next = 0;
+        Memo *hit = nullptr;
+        for (int m = 0; m < kMemos; ++m)
+            if (memos[m].C == C && memos[m].k == k && memos[m].rt == rt && memos[m].W == W)
+                hit = &memos[m];
+        Memo memo = hit ? *hit : Memo{0, 0, 0, 0, 0, 0};
+        if (!hit) {
             const int ncol = C * k * k;
             auto cost = [&](int xw, int sxc) {
                 int total = 0;
@@ -322,6 +330,8 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
                     }
                 }
             memo = m;
+            memos[memo_next] = m;
+            memo_next = (memo_next + 1) % kMemos;
         }
         p.xw = memo.xw;
         p.sxc = memo.sxc;
@@ -410,6 +420,16 @@ int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const
     if (int s = launch_dw_partial_batch(batch, 1, part, p, B, C, H, W, k, stream))
         return s;
     return launch_dw_reduce(part, (int)p.nparts, dw, C, k, stream, sign);
+}
+
+// Pass 1 alone: p.nparts rows of C*C*k*k un-negated, unmasked partial sums in `part`
+int launch_dw_mfma_partial(const float *x, const float *v, float *part, const DwPlan &p, int B, int C, int H, int W,
+                           int k, hipStream_t stream)
+{
+    DwBatch batch{};
+    batch.x[0] = x;
+    batch.v[0] = v;
+    return launch_dw_partial_batch(batch, 1, part, p, B, C, H, W, k, stream);
 }
 
 // dL/dw of `layers` layers: one pass-1 launch over all of them, then one pass 2 per layer.

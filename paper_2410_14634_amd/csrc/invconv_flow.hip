@@ -231,6 +231,26 @@ __global__ __launch_bounds__(256) void k_flow_stats(const float *__restrict__ gz
     }
 }
 
+// m1 partial sums: one workgroup per (image, channel) plane adds its H*W values of dL/dz in a fixed order
+// (thread t takes elements t, t + 256, ...; then a fixed tree over the 256 threads).  out[n*C + c].
+__global__ __launch_bounds__(256) void k_flow_plane_sum(const float *__restrict__ gz, float *__restrict__ out, int HW)
+{
+    __shared__ float red[256];
+    const float *p = gz + (size_t)blockIdx.x * HW;
+    float acc = 0.0f;
+    for (int i = threadIdx.x; i < HW; i += 256)
+        acc += p[i];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int half = 128; half >= 1; half >>= 1) {
+        if ((int)threadIdx.x < half)
+            red[threadIdx.x] += red[threadIdx.x + half];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0)
+        out[blockIdx.x] = red[0];
+}
+
 // Sum of `nrows` rows of `E` floats (row stride `stride`) in index order, double accumulator: wave v of a
 // workgroup adds rows v, v + NW, ..., then the waves are added in order.  out[e] = the sum as float.
 template <int NW>
@@ -582,6 +602,12 @@ int launch_flow_stats(const float *gz, const float *x, float *rows, int B, int C
     if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_flow_stats), lds) || lds > kMaxLdsBytes)
         return INVCONV_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(k_flow_stats, dim3((unsigned)(B * chunks)), dim3(256), lds, stream, gz, x, rows, C, HW, chunks);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+int launch_flow_plane_sum(const float *gz, float *out, int planes, int HW, hipStream_t stream)
+{
+    hipLaunchKernelGGL(k_flow_plane_sum, dim3((unsigned)planes), dim3(256), 0, stream, gz, out, HW);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

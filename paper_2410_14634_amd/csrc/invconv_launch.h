@@ -81,6 +81,8 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k);
 DwPlan plan_dw_mfma_layers(int layers, int B, int C, int H, int W, int k);
 int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
                    int W, int k, hipStream_t stream, float sign = -1.0f);
+int launch_dw_mfma_partial(const float *x, const float *v, float *part, const DwPlan &p, int B, int C, int H, int W,
+                           int k, hipStream_t stream);
 int launch_dw_mfma_layers(const float *const *x, const float *const *v, float *const *dw, int layers, float *part,
                           const DwPlan &p, int B, int C, int H, int W, int k, hipStream_t stream);
 DwPlan plan_dw_any(int B, int C, int H, int W, int k);
@@ -94,6 +96,7 @@ struct ChainArgs {
     const float *in0;                    // input of stage 0
     const float *w[kChainMaxLayers];     // kernel of stage s
     float *out[kChainMaxLayers];         // output of stage s = input of stage s+1
+    const float *map[kChainMaxLayers];   // flow step: affine channel map of stage s (C*C floats A, C floats d), or null
     int *flags;                          // progress counters (chain_flag_ints() ints)
     int *err;                            // error word (may be null): set to 1 when a bounded wait ran out
     int spin_limit;                      // set by launch_chain
@@ -120,6 +123,7 @@ int launch_flow_affine(bool transposed, const float *in, const float *M, const f
                        int HW, hipStream_t stream);
 int launch_flow_stats(const float *gz, const float *x, float *rows, int B, int C, int HW, hipStream_t stream);
 int launch_rows_sum(const float *rows, int nrows, int stride, int E, float *out, hipStream_t stream);
+int launch_flow_plane_sum(const float *gz, float *out, int planes, int HW, hipStream_t stream);
 int launch_flow_finish(const float *sums, int have_dw, const float *w, const float *s, const float *b, const float *Q,
                        const float *mats, float *dLdw, float *dLds, float *dLdb, float *dLdQ, float lw, int C, int H,
                        int W, int k, hipStream_t stream);
