@@ -153,4 +153,48 @@ __device__ void fold_weights(const float *__restrict__ w, int C, int k,
     __syncthreads();
 }
 
+// The same preparation for many channels, where a second k*k*C*C staging buffer would not fit LDS: the
+// kernel entries are read from global memory where they are used (every entry C times, from L2).
+// Outputs sL, sLinv (C*C each) and sCf (k*k*C*C) as above.  Ends with a barrier.
+template <int DIR>
+__device__ void fold_weights_lean(const float *__restrict__ w, int C, int k, float *sL, float *sLinv, float *sCf)
+{
+    const int tid = threadIdx.x, nt = blockDim.x;
+    // oriented, masked entry (tp, o, i)
+    auto entry = [&](int tp, int o, int i) -> float {
+        const int a = k - 1 - tp / k, b = k - 1 - tp % k;
+        const int oo = DIR ? C - 1 - i : o, ii = DIR ? C - 1 - o : i;
+        const float v = w[((oo * C + ii) * k + a) * k + b];
+        return (tp == 0 && ii > oo) ? 0.0f : v;
+    };
+    for (int idx = tid; idx < C * C; idx += nt)
+        sL[idx] = entry(0, idx / C, idx % C);
+    __syncthreads();
+    if (tid < C) {
+        const int j = tid;
+        for (int o = 0; o < j; ++o)
+            sLinv[o * C + j] = 0.0f;
+        sLinv[j * C + j] = 1.0f / sL[j * C + j];
+        for (int o = j + 1; o < C; ++o) {
+            float s = 0.0f;
+            for (int m = j; m < o; ++m)
+                s += sL[o * C + m] * sLinv[m * C + j];
+            sLinv[o * C + j] = -s / sL[o * C + o];
+        }
+    }
+    __syncthreads();
+    const int total = k * k * C * C;
+    for (int idx = tid; idx < total; idx += nt) {
+        const int i = idx % C, o = (idx / C) % C, tp = idx / (C * C);
+        float s = 0.0f;
+        if (tp != 0) {
+            const float *li = sLinv + o * C;
+            for (int j = 0; j <= o; ++j)
+                s += li[j] * entry(tp, j, i);
+        }
+        sCf[idx] = s;
+    }
+    __syncthreads();
+}
+
 }  // namespace invconv

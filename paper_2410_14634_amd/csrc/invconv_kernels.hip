@@ -103,7 +103,8 @@ void set_wait_budget(int polls) { g_wait_budget.store(polls > 0 ? polls : 0, std
 // lanes walking down a diagonal hit different banks).  Pixel (r,c) on diagonal
 // d = r+c reads its neighbour (r-da, c-db) from diagonal d-da-db, row r-da.
 // ---------------------------------------------------------------------------
-template <int DIR>
+// LEAN (many channels): no staging copy of the kernel in LDS, see fold_weights_lean.
+template <int DIR, bool LEAN = false>
 __global__ __launch_bounds__(kSolveBlock) void k_solve_block(const float *__restrict__ in,
                                                             const float *__restrict__ w,
                                                             float *__restrict__ out,
@@ -116,11 +117,14 @@ __global__ __launch_bounds__(kSolveBlock) void k_solve_block(const float *__rest
     float *sLinv = sL + C * C;
     float *sCf = sLinv + C * C;
     float *sW = sCf + k * k * C * C;
-    float *win = sW + k * k * C * C;
+    float *win = LEAN ? sW : sW + k * k * C * C;
 
     const int n = blockIdx.x;
     const int tid = threadIdx.x;
-    fold_weights<DIR>(w, C, k, sL, sLinv, sCf, sW);
+    if (LEAN)
+        fold_weights_lean<DIR>(w, C, k, sL, sLinv, sCf);
+    else
+        fold_weights<DIR>(w, C, k, sL, sLinv, sCf, sW);
 
     const int ndiag = H + W - 1;
     for (int d = 0; d < ndiag; ++d) {
@@ -416,10 +420,17 @@ __global__ __launch_bounds__(64) void k_logdet(ConstPtrList ws, int C, int H, in
 // ---------------------------------------------------------------------------
 // Host-side launchers
 // ---------------------------------------------------------------------------
-size_t solve_block_lds_bytes(int C, int H, int k)
+static size_t solve_block_lds_bytes_form(int C, int H, int k, bool lean)
 {
     const size_t CP = (size_t)(C | 1), ND = 2 * (size_t)(k - 1) + 1;
-    return sizeof(float) * (2 * (size_t)C * C + 2 * (size_t)k * k * C * C + ND * H * CP);
+    return sizeof(float) * (2 * (size_t)C * C + (lean ? 1 : 2) * (size_t)k * k * C * C + ND * H * CP);
+}
+
+// What the launch will take: the form with the staging buffer while it fits, the lean one beyond
+size_t solve_block_lds_bytes(int C, int H, int k)
+{
+    const size_t full = solve_block_lds_bytes_form(C, H, k, false);
+    return full <= kMaxLdsBytes ? full : solve_block_lds_bytes_form(C, H, k, true);
 }
 
 template <int DIR>
@@ -429,9 +440,16 @@ static int launch_solve_block_dir(const float *in, const float *w, float *out, i
     const size_t lds = solve_block_lds_bytes(C, H, k);
     if (lds > kMaxLdsBytes)
         return INVCONV_ERR_UNSUPPORTED;
-    if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_solve_block<DIR>), lds))
+    const bool lean = solve_block_lds_bytes_form(C, H, k, false) > kMaxLdsBytes;
+    const void *fn = lean ? reinterpret_cast<const void *>(&k_solve_block<DIR, true>)
+                          : reinterpret_cast<const void *>(&k_solve_block<DIR, false>);
+    if (!ensure_dynamic_lds(fn, lds))
         return INVCONV_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(k_solve_block<DIR>, dim3(B), dim3(kSolveBlock), lds, stream, in, w, out, C, H, W, k);
+    if (lean)
+        hipLaunchKernelGGL((k_solve_block<DIR, true>), dim3(B), dim3(kSolveBlock), lds, stream, in, w, out, C, H, W, k);
+    else
+        hipLaunchKernelGGL((k_solve_block<DIR, false>), dim3(B), dim3(kSolveBlock), lds, stream, in, w, out, C, H, W,
+                           k);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

@@ -64,6 +64,7 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     (2, 12, 16, 16, 3), (1, 12, 33, 20, 3), (2, 8, 50, 17, 3), (1, 16, 128, 40, 3), (1, 12, 7, 100, 3),
     (3, 12, 1, 1, 3), (1, 8, 17, 2, 3), (1, 12, 129, 8, 3),
     (1, 20, 6, 7, 2), (2, 18, 9, 5, 3),      # more than 16 channels: generic solve and generic dL/dw
+    (2, 48, 32, 32, 3), (1, 32, 40, 24, 3), (1, 24, 20, 12, 5), (1, 48, 60, 9, 3), (1, 40, 8, 8, 3),   # after two squeezes
     (1, 3, 17, 1200, 3), (1, 12, 4, 1400, 3),    # wide images: dL/dw row tiles beyond the preferred LDS budget
     # few channels, more than 64 rows: bands of 64 rows, one wave each
     (2, 3, 256, 256, 3), (1, 3, 130, 40, 5), (1, 4, 512, 16, 3), (1, 1, 65, 7, 3), (2, 3, 128, 200, 3),
@@ -105,7 +106,7 @@ def test_wave_split_variant_edge_shapes(shape):
 
 LARGE_K_SHAPES = [  # (B, C, H, W, k): the kernel sizes of the paper's kernel-size ablation, three channels
     (2, 3, 32, 32, 2), (2, 3, 32, 32, 7), (2, 3, 28, 28, 9), (1, 3, 32, 32, 11), (2, 3, 64, 40, 7), (2, 3, 20, 9, 11),
-    (1, 3, 5, 50, 9), (3, 3, 64, 64, 11), (1, 3, 100, 20, 7), (2, 3, 7, 7, 2),
+    (1, 3, 5, 50, 9), (3, 3, 64, 64, 11), (1, 3, 100, 20, 7), (2, 3, 7, 7, 2), (2, 3, 128, 64, 11), (1, 3, 256, 32, 9),
 ]
 
 
