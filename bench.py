@@ -456,6 +456,7 @@ SCALE_SHAPES = {  # (B, C, H, W, k): the paper's image-size / batch-size / kerne
     "batch_256": (256, 3, 32, 32, 3), "batch_1024": (1024, 3, 32, 32, 3), "batch_4096": (4096, 3, 32, 32, 3),
     "k2": (16, 3, 32, 32, 2), "k5": (16, 3, 32, 32, 5), "k7": (16, 3, 32, 32, 7), "k9": (16, 3, 32, 32, 9),
     "k11": (16, 3, 32, 32, 11), "mnist_like": (128, 1, 28, 28, 3),
+    "c48_two_squeezes": (32, 48, 32, 32, 3), "c24": (32, 24, 64, 64, 3), "c32": (64, 32, 32, 32, 3),
 }
 
 

@@ -116,6 +116,8 @@ int solve_variant(int dir, const float *in, const float *w, float *out, int B, i
             }
             return launch_solve_band(dir, in, w, out, B, C, H, W, k, stream);
         }
+        if (wide_supported(C, H, k))
+            return launch_solve_wide(dir, in, w, out, B, C, H, W, k, stream);
         return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_BLOCK:
         return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);
@@ -155,7 +157,7 @@ int fwd_impl(const float *y, const float *w, float *x, int B, int C, int H, int 
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_BLOCK ||
         (variant == INVCONV_VARIANT_AUTO && !wave_supported(C, H, k) && !wave_bands_supported(C, H, W, k) &&
-         !band_supported(C, H, k)))
+         !band_supported(C, H, k) && !wide_supported(C, H, k)))
         if (int s = check_supported(C, H, k))
             return s;
     return solve(0, y, w, x, B, C, H, W, k, (hipStream_t)stream, variant, ws, logdet);
@@ -290,7 +292,7 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_BLOCK ||
         (variant == INVCONV_VARIANT_AUTO && !wave_supported(C, H, k) && !wave_bands_supported(C, H, W, k) &&
-         !band_supported(C, H, k)))
+         !band_supported(C, H, k) && !wide_supported(C, H, k)))
         if (int s = check_supported(C, H, k))
             return s;
     const DwPlan p = plan_dw_any(B, C, H, W, k);
