@@ -430,7 +430,7 @@ int flow_sums(const float *dLdz, const float *x, float *rows, float *sums, int B
 {
     const int E2 = C * C + C;
     const DwPlan p1 = plan_dw_any(B, C, H, W, 1);
-    if (dw_mfma_supported(C, 1) && p1.rt && plan_dw_mfma(B, C, H, W, 1).rt) {
+    if (dw_mfma_supported(C, 1) && p1.rt && !p1.cb && plan_dw_mfma(B, C, H, W, 1).rt) {
         // the correlation of Eq. 4 with a 1 x 1 window, neither negated nor masked, is exactly M2
         if (int rc = launch_dw_mfma_partial(x, dLdz, rows, p1, B, C, H, W, 1, st))
             return rc;
@@ -743,8 +743,14 @@ invconv_status invconv_chain_bwd(const float *const *x, const float *const *w, c
     }
     const DwPlan p = plan_dw_any(B, C, H, W, k);
     const bool mfma = dw_mfma_supported(C, k) && plan_dw_mfma(B, C, H, W, k).rt;
-    if (mfma)
+    if (mfma && !p.cb)
         return launch_dw_mfma_layers(x, v, dLdw, L, part, plan_dw_mfma_layers(L, B, C, H, W, k), B, C, H, W, k, st);
+    if (mfma) {         // more than 16 channels: the blocked form, layer by layer
+        for (int l = 0; l < L; ++l)
+            if (int s = launch_dw_mfma(x[l], v[l], dLdw[l], part, p, B, C, H, W, k, st))
+                return s;
+        return INVCONV_OK;
+    }
     for (int l = 0; l < L; ++l) {
         if (int s = launch_dw(x[l], v[l], dLdw[l], part, p, B, C, H, W, k, st))
             return s;

@@ -33,10 +33,14 @@ constexpr int kDwUnroll = 4;    // pixel quads per trip of the product loop
 constexpr int kDwPre = 6;       // streaming mode: 16-byte pieces of each tile a thread holds in registers
 constexpr size_t kDwStreamLdsBudget = 72 * 1024;   // streaming mode: two workgroups per compute unit
 
+// More than 16 channels: the launcher cuts the C x C k k result into blocks of at most 16 x 16 k k and calls
+// this kernel once per block with the tensors' base pointers moved to the block's first channels: C is then
+// the number of x channels (columns / k k) of the block, Cv the number of v channels (rows), Ctot the
+// channel count of the tensors (image stride).
 template <int NS>
 __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *__restrict__ part, int B, int C,
                                                         int H, int W, int k, int RT, int nchunks, int G, int vec,
-                                                        int XW, int SXC, int SVC)
+                                                        int XW, int SXC, int SVC, int Cv, int Ctot)
 {
     extern __shared__ float smem[];
     // blockIdx = ((layer * B + n) * G + cg); this workgroup takes chunks cg, cg+G, ... of image n
@@ -46,14 +50,15 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
     // XW >= W + kDwHalo, SXC >= (RT + k - 1) * XW and SVC >= RT * W: row / channel strides padded by the
     // host so that the 64 lanes of an operand read fall into different LDS banks
     const int NCOL = C * k * k;
-    const int P = C * NCOL;
-    float *sv = smem;                 // [C] x SVC, rows of W floats
-    float *sx = sv + C * SVC;         // [C] x SXC, rows of XW floats, origin at (r0-(k-1), -kDwHalo)
+    const int P = Cv * NCOL;
+    const int CM = Cv > C ? Cv : C;
+    float *sv = smem;                 // [Cv] x SVC, rows of W floats
+    float *sx = sv + CM * SVC;        // [C] x SXC, rows of XW floats, origin at (r0-(k-1), -kDwHalo)
     float *sred = smem;               // [4 waves][64 lanes][NS*4], reuses the tiles afterwards
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
     const int nn = lane & 15, kk = lane >> 4;
-    const int aoff = (nn < C ? nn : 0) * SVC;               // A row m = nn -> v[o = m]
+    const int aoff = (nn < Cv ? nn : 0) * SVC;              // A row m = nn -> v[o = m]
     int boff[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
@@ -68,19 +73,22 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
 
     const int cpw = (nchunks + G - 1) / G;          // chunks cg*cpw .. of image n, contiguous
     const int c_begin = cg * cpw, c_end = (c_begin + cpw < nchunks) ? c_begin + cpw : nchunks;
-    const size_t img = (size_t)n * C * H * W;
+    const size_t img = (size_t)n * Ctot * H * W;
 
     // streaming mode: this thread's pieces of a chunk (loop invariant): piece i is float4 c4 of row r of channel ch
     float4 pv[kDwPre], px[kDwPre], ph[kDwPre];
     int p_go[kDwPre], p_vl[kDwPre], p_xl[kDwPre], p_r[kDwPre];
+    bool p_hv[kDwPre], p_hx[kDwPre];        // the piece's channel exists in the v / x block
     if (vec == 2) {
         const int W4 = W / 4;
 #pragma unroll
         for (int i = 0; i < kDwPre; ++i) {
             const int idx = tid + 256 * i;
-            const bool ok = idx < C * RT * W4;
+            const bool ok = idx < CM * RT * W4;
             const int c4 = idx % W4, rr = idx / W4;
             const int ch = ok ? rr / RT : 0, r = ok ? rr - ch * RT : 0;
+            p_hv[i] = ok && ch < Cv;
+            p_hx[i] = ok && ch < C;
             p_r[i] = ok ? r : -1;
             p_go[i] = (ch * H + r) * W + 4 * c4;
             p_vl[i] = ch * SVC + r * W + 4 * c4;
@@ -97,11 +105,13 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
 #pragma unroll
         for (int i = 0; i < kDwPre; ++i) {
             const int r = p_r[i];
-            if (r >= RT - (k - 1) && rb - RT + r >= 0 && c_begin < c_end)
+            if (p_hx[i] && r >= RT - (k - 1) && rb - RT + r >= 0 && c_begin < c_end)
                 ph[i] = *reinterpret_cast<const float4 *>(x + img + p_go[i] + (ptrdiff_t)(rb - RT) * W);
             if (r >= 0 && rb + r < H && c_begin < c_end) {
-                pv[i] = *reinterpret_cast<const float4 *>(v + img + p_go[i] + (size_t)rb * W);
-                px[i] = *reinterpret_cast<const float4 *>(x + img + p_go[i] + (size_t)rb * W);
+                if (p_hv[i])
+                    pv[i] = *reinterpret_cast<const float4 *>(v + img + p_go[i] + (size_t)rb * W);
+                if (p_hx[i])
+                    px[i] = *reinterpret_cast<const float4 *>(x + img + p_go[i] + (size_t)rb * W);
             }
         }
     }
@@ -116,20 +126,23 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
             for (int i = 0; i < kDwPre; ++i) {
                 const int r = p_r[i];
                 if (r >= 0) {
-                    *reinterpret_cast<float4 *>(sv + p_vl[i]) = pv[i];
-                    *reinterpret_cast<float4 *>(sx + p_xl[i]) = px[i];
-                    if (r >= RT - (k - 1))      // last rows of the chunk before: rows 0 .. k-2 of the tile
-                        *reinterpret_cast<float4 *>(sx + p_xl[i] - RT * XW) = ph[i];
+                    if (p_hv[i])
+                        *reinterpret_cast<float4 *>(sv + p_vl[i]) = pv[i];
+                    if (p_hx[i]) {
+                        *reinterpret_cast<float4 *>(sx + p_xl[i]) = px[i];
+                        if (r >= RT - (k - 1))      // last rows of the chunk before: rows 0 .. k-2 of the tile
+                            *reinterpret_cast<float4 *>(sx + p_xl[i] - RT * XW) = ph[i];
+                    }
                     ph[i] = px[i];
                 }
             }
         } else if (vec) {
             const int W4 = W / 4;
-            for (int idx = tid; idx < C * rows * W4; idx += 256) {
+            for (int idx = tid; idx < Cv * rows * W4; idx += 256) {
                 const int c4 = idx % W4, rr = idx / W4;         // rr = ch*rows + r
                 const int ch = rr / rows, r = rr - ch * rows;
                 const float4 val = *reinterpret_cast<const float4 *>(
-                    v + (((size_t)n * C + ch) * H + r0 + r) * W + 4 * c4);
+                    v + (((size_t)n * Ctot + ch) * H + r0 + r) * W + 4 * c4);
                 *reinterpret_cast<float4 *>(sv + ch * SVC + r * W + 4 * c4) = val;
             }
             const int X4 = (W + kDwHalo) / 4;                   // first float4 of a row is the halo
@@ -139,20 +152,20 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
                 const int gr = r0 - (k - 1) + r;
                 float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (gr >= 0 && c4 > 0)
-                    val = *reinterpret_cast<const float4 *>(x + (((size_t)n * C + ch) * H + gr) * W + 4 * (c4 - 1));
+                    val = *reinterpret_cast<const float4 *>(x + (((size_t)n * Ctot + ch) * H + gr) * W + 4 * (c4 - 1));
                 *reinterpret_cast<float4 *>(sx + ch * SXC + r * XW + 4 * c4) = val;
             }
         } else {
-            for (int idx = tid; idx < C * rows * W; idx += 256) {
+            for (int idx = tid; idx < Cv * rows * W; idx += 256) {
                 const int c = idx % W, r = (idx / W) % rows, ch = idx / (W * rows);
-                sv[ch * SVC + r * W + c] = v[(((size_t)n * C + ch) * H + r0 + r) * W + c];
+                sv[ch * SVC + r * W + c] = v[(((size_t)n * Ctot + ch) * H + r0 + r) * W + c];
             }
             const int xcols = W + kDwHalo;
             for (int idx = tid; idx < C * xrows * xcols; idx += 256) {
                 const int cc = idx % xcols, rr = (idx / xcols) % xrows, ch = idx / (xcols * xrows);
                 const int gr = r0 - (k - 1) + rr, gc = cc - kDwHalo;
                 sx[ch * SXC + rr * XW + cc] =
-                    (gr >= 0 && gc >= 0) ? x[(((size_t)n * C + ch) * H + gr) * W + gc] : 0.0f;
+                    (gr >= 0 && gc >= 0) ? x[(((size_t)n * Ctot + ch) * H + gr) * W + gc] : 0.0f;
             }
         }
         __syncthreads();
@@ -162,9 +175,10 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
 #pragma unroll
             for (int i = 0; i < kDwPre; ++i) {
                 const bool in = p_r[i] >= 0 && rn + p_r[i] < H;
-                const size_t go = img + p_go[i] + (size_t)(in ? rn : 0) * W;
-                const float4 a4 = *reinterpret_cast<const float4 *>(v + go);
-                const float4 b4 = *reinterpret_cast<const float4 *>(x + go);
+                const size_t go = img + (p_r[i] >= 0 ? p_go[i] : 0) + (size_t)(in ? rn : 0) * W;
+                // (a piece whose channel is missing in one of the blocks reads the block's first channel: unused)
+                const float4 a4 = *reinterpret_cast<const float4 *>(v + (p_hv[i] ? go : img));
+                const float4 b4 = *reinterpret_cast<const float4 *>(x + (p_hx[i] ? go : img));
                 pv[i] = a4;
                 px[i] = in ? b4 : make_float4(0.f, 0.f, 0.f, 0.f);
             }
@@ -236,10 +250,15 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
     }
 }
 
+constexpr int kDwChannelBlock = 16;
+
+// up to 16 channels: one GEMM; up to 64: blocks of 16 x 16 channels (the column count of a block, 16 k k,
+// has to fit the ten accumulators: k <= 3)
 bool dw_mfma_supported(int C, int k)
 {
-    const int ns = (C * k * k + 15) / 16;
-    return C <= 16 && ns >= 1 && ns <= 10;
+    const int cx = C <= kDwChannelBlock ? C : kDwChannelBlock;
+    const int ns = (cx * k * k + 15) / 16;
+    return C <= 64 && ns >= 1 && ns <= 10;
 }
 
 // Row chunking of pass 1: tiles (or the reduction buffer that reuses them) must fit the LDS budget.
@@ -249,6 +268,12 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
     DwPlan p{};
     if (!dw_mfma_supported(C, k) || k - 1 > kDwHalo)
         return p;
+    if (C > kDwChannelBlock) {
+        // the plan of one 16 x 16 block; the launches of the blocks follow each other and share the rows
+        p = plan_dw_mfma(B, kDwChannelBlock, H, W, k);
+        p.cb = p.rt ? kDwChannelBlock : 0;
+        return p;
+    }
     const size_t P = (size_t)C * C * k * k;
     const size_t NS = ((size_t)C * k * k + 15) / 16;
     const size_t red = 256 * NS * 4;
@@ -368,9 +393,10 @@ DwPlan plan_dw_mfma_layers(int layers, int B, int C, int H, int W, int k)
     return p;
 }
 
+// C = x channels of the block (= all channels without blocking), Cv = v channels, Ctot = channels of the tensors
 template <int NS>
 static bool launch_ns(const DwBatch &batch, int layers, float *part, const DwPlan &p, int B, int C, int H, int W,
-                      int k, hipStream_t stream)
+                      int k, hipStream_t stream, int Cv, int Ctot)
 {
     // 16-byte tile loads need rows that start on 16-byte boundaries
     int vec = (W % 4) == 0;
@@ -378,32 +404,34 @@ static bool launch_ns(const DwBatch &batch, int layers, float *part, const DwPla
         if (((size_t)batch.x[l] | (size_t)batch.v[l]) & 15)
             vec = 0;
     // streaming mode: the halo rows come from one chunk before, and a thread's share of a tile fits its registers
-    if (vec && p.rt >= k - 1 && C * p.rt * (W / 4) <= 256 * kDwPre)
+    if (vec && p.rt >= k - 1 && (C > Cv ? C : Cv) * p.rt * (W / 4) <= 256 * kDwPre)
         vec = 2;
     if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_dw_partial_mfma<NS>), p.lds))
         return false;
     hipLaunchKernelGGL(k_dw_partial_mfma<NS>, dim3((unsigned)(p.nparts * layers)), dim3(256), p.lds, stream, batch,
-                       part, B, C, H, W, k, p.rt, p.nchunks, p.groups, vec, p.xw, p.sxc, p.svc);
+                       part, B, C, H, W, k, p.rt, p.nchunks, p.groups, vec, p.xw, p.sxc, p.svc, Cv, Ctot);
     return true;
 }
 
 // Pass 1 for `layers` independent (x, v) pairs in one launch; part holds layers * p.nparts rows.
 static int launch_dw_partial_batch(const DwBatch &batch, int layers, float *part, const DwPlan &p, int B, int C,
-                                   int H, int W, int k, hipStream_t stream)
+                                   int H, int W, int k, hipStream_t stream, int Cv = 0, int Ctot = 0)
 {
+    Cv = Cv ? Cv : C;
+    Ctot = Ctot ? Ctot : C;
     const int ns = (C * k * k + 15) / 16;
     bool ok = false;
     switch (ns) {
-    case 1: ok = launch_ns<1>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 2: ok = launch_ns<2>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 3: ok = launch_ns<3>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 4: ok = launch_ns<4>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 5: ok = launch_ns<5>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 6: ok = launch_ns<6>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 7: ok = launch_ns<7>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 8: ok = launch_ns<8>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 9: ok = launch_ns<9>(batch, layers, part, p, B, C, H, W, k, stream); break;
-    case 10: ok = launch_ns<10>(batch, layers, part, p, B, C, H, W, k, stream); break;
+    case 1: ok = launch_ns<1>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
+    case 2: ok = launch_ns<2>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
+    case 3: ok = launch_ns<3>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
+    case 4: ok = launch_ns<4>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
+    case 5: ok = launch_ns<5>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
+    case 6: ok = launch_ns<6>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
+    case 7: ok = launch_ns<7>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
+    case 8: ok = launch_ns<8>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
+    case 9: ok = launch_ns<9>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
+    case 10: ok = launch_ns<10>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
     default: return INVCONV_ERR_UNSUPPORTED;
     }
     if (!ok)
@@ -415,6 +443,21 @@ int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const
                    int W, int k, hipStream_t stream, float sign)
 {
     DwBatch batch{};
+    if (p.cb) {
+        // more than 16 channels: one pass 1 + pass 2 per block of output x input channels
+        const size_t plane = (size_t)H * W;
+        for (int o0 = 0; o0 < C; o0 += p.cb)
+            for (int i0 = 0; i0 < C; i0 += p.cb) {
+                const int Cv = C - o0 < p.cb ? C - o0 : p.cb, Cx = C - i0 < p.cb ? C - i0 : p.cb;
+                batch.x[0] = x + i0 * plane;
+                batch.v[0] = v + o0 * plane;
+                if (int s = launch_dw_partial_batch(batch, 1, part, p, B, Cx, H, W, k, stream, Cv, C))
+                    return s;
+                if (int s = launch_dw_reduce_block(part, (int)p.nparts, dw, Cv, Cx, o0, i0, C, k, stream, sign))
+                    return s;
+            }
+        return INVCONV_OK;
+    }
     batch.x[0] = x;
     batch.v[0] = v;
     if (int s = launch_dw_partial_batch(batch, 1, part, p, B, C, H, W, k, stream))

@@ -359,14 +359,16 @@ __global__ __launch_bounds__(kDwBlock) void k_dw_partial(const float *__restrict
 // as 0.  No atomics anywhere, so dw is bitwise reproducible from run to run.
 // blockIdx.y selects the layer when several layers are reduced by one launch
 // (layer l's rows start at part + l*nparts*P, its result goes to out.p[l]).
+// A launch may also cover one block of a larger result (more than 16 channels): rows hold Cv x Cx k k entries
+// that go to output channels o0 .. and input channels i0 .. of a Ctot-channel kernel gradient.
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void k_dw_reduce(const float *__restrict__ part_all, int nparts, PtrList out,
-                                                      int C, int k, float sign)
+                                                      int C, int k, float sign, int Cv, int o0, int i0, int Ctot)
 {
     // NW = 4 waves, or 16 for many rows (the launch decides from nparts alone, so the order of the additions
     // is a function of the shape): wave v adds rows v, v + NW, ... in order, then the waves are added in order
     __shared__ double swave[NW][64];
-    const int P = C * C * k * k;
+    const int P = Cv * C * k * k;
     const float *__restrict__ part = part_all + (size_t)blockIdx.y * nparts * P;
     float *__restrict__ dw = out.p[blockIdx.y];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -393,9 +395,9 @@ __global__ __launch_bounds__(64 * NW) void k_dw_reduce(const float *__restrict__
 #pragma unroll
         for (int v = 1; v < NW; ++v)
             total += swave[v][lane];
-        const int b = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
+        const int b = e % k, a = (e / k) % k, i = i0 + (e / (k * k)) % C, o = o0 + e / (k * k * C);
         const bool is_masked = (a == k - 1 && b == k - 1 && i > o);
-        dw[e] = is_masked ? 0.0f : (float)(sign < 0.0f ? -total : total);
+        dw[((o * Ctot + i) * k + a) * k + b] = is_masked ? 0.0f : (float)(sign < 0.0f ? -total : total);
     }
 }
 
@@ -589,10 +591,26 @@ int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int
         out.p[l] = dw[l];
     if (nparts >= 512)
         hipLaunchKernelGGL(k_dw_reduce<16>, dim3((P + 63) / 64, layers), dim3(1024), 0, stream, part, nparts, out, C, k,
-                           sign);
+                           sign, C, 0, 0, C);
     else
         hipLaunchKernelGGL(k_dw_reduce<4>, dim3((P + 63) / 64, layers), dim3(256), 0, stream, part, nparts, out, C, k,
-                           sign);
+                           sign, C, 0, 0, C);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+// Second pass for one Cv x Cx block of a Ctot-channel result (rows of Cv*Cx*k*k partial sums)
+int launch_dw_reduce_block(const float *part, int nparts, float *dw, int Cv, int Cx, int o0, int i0, int Ctot, int k,
+                           hipStream_t stream, float sign)
+{
+    const int P = Cv * Cx * k * k;
+    PtrList out{};
+    out.p[0] = dw;
+    if (nparts >= 512)
+        hipLaunchKernelGGL(k_dw_reduce<16>, dim3((P + 63) / 64, 1), dim3(1024), 0, stream, part, nparts, out, Cx, k, sign,
+                           Cv, o0, i0, Ctot);
+    else
+        hipLaunchKernelGGL(k_dw_reduce<4>, dim3((P + 63) / 64, 1), dim3(256), 0, stream, part, nparts, out, Cx, k, sign,
+                           Cv, o0, i0, Ctot);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

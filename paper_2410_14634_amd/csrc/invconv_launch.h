@@ -39,6 +39,7 @@ struct DwPlan {
     int nchunks;     // row chunks per image
     int cw, ncol;    // generic pass 1: columns per chunk, column chunks per row chunk (cw = W, ncol = 1 unless W is too wide for LDS)
     int groups;      // matrix-core pass 1: workgroups per image, each looping over chunks
+    int cb;          // matrix-core pass 1: 0, or (more than 16 channels) the channel block: one launch per cb x cb block of dL/dw
     int xw, sxc, svc; // matrix-core pass 1: row and channel strides of the x tile, channel stride of the v tile (padded against LDS bank conflicts)
     size_t nparts;   // workgroups of pass 1 = rows of the partial-sum matrix
     size_t lds;      // dynamic LDS bytes of pass 1
@@ -94,6 +95,8 @@ struct PtrList { float *p[kChainMaxLayers]; };
 struct ConstPtrList { const float *p[kChainMaxLayers]; };
 int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int layers, int C, int k,
                             hipStream_t stream, float sign = -1.0f);
+int launch_dw_reduce_block(const float *part, int nparts, float *dw, int Cv, int Cx, int o0, int i0, int Ctot, int k,
+                           hipStream_t stream, float sign = -1.0f);
 int launch_logdet_layers(const float *const *w, int layers, int C, int H, int W, int k, float *out,
                          hipStream_t stream);
 struct ChainArgs {
