@@ -58,6 +58,11 @@ bool ws_layout(int B, int C, int H, int W, int k, bool with_dw, WsLayout *lay)
         if (!p.rt)
             return false;
         lay->dw_bytes = up256(p.bytes);
+        // the fused backward of the convolution itself writes one row per workgroup
+        if (conv_bwd_fused_supported(C, H, W, k)) {
+            const size_t rows = up256(conv_bwd_fused_rows() * (size_t)C * C * k * k * sizeof(float));
+            lay->dw_bytes = lay->dw_bytes > rows ? lay->dw_bytes : rows;
+        }
     }
     lay->total = lay->dw_off + lay->dw_bytes;
     return true;
@@ -256,6 +261,12 @@ invconv_status invconv_conv_bwd(const float *x, const float *w, const float *dLd
         return INVCONV_ERR_WORKSPACE;
     float *part = (float *)((char *)workspace + lay.dw_off);
     hipStream_t st = (hipStream_t)stream;
+    if (conv_bwd_fused_supported(C, H, W, k) && ((((size_t)x | (size_t)dLdy | (size_t)dLdx)) & 15) == 0) {
+        unsigned rows = 0;
+        if (int s = launch_conv_bwd_fused(dLdy, w, dLdx, x, part, B, C, H, W, k, st, &rows))
+            return s;
+        return launch_dw_reduce(part, (int)rows, dLdw, C, k, st, 1.0f);
+    }
     if (int s = launch_conv(1, dLdy, w, dLdx, B, C, H, W, k, st))
         return s;
     if (dw_mfma_supported(C, k) && plan_dw_mfma(B, C, H, W, k).rt)

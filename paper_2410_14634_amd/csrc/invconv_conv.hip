@@ -113,11 +113,22 @@ __device__ __forceinline__ void conv_load_tile(const TileGeom &g, float *sx)
 // Tile of kConvRows x TW pixels (TW = 32, 64 or 128), LDS tile [C][kConvRows + K - 1][TW + 4].
 // A wave works on two batches of 64 pixels at a time (two independent accumulators); all LDS
 // offsets of the taps are compile-time constants.
-template <int C, int K, int TW, bool VEC, int DIR>
+// DW (with DIR = 1, the backward pass of the convolution): the same walk over the tiles also forms the
+// convolution's weight gradient, dw[o][i][a][b] = sum_p g[o][p] x2[i][p - d] with d = (K-1-a, K-1-b) (Eq. 1 is
+// linear in w).  Seen from the x2 pixel q = p - d this is sum_q x2[i][q] g[o][q + d], and in the mirrored
+// coordinates of this tile q + d lies up / left of q: exactly the halo the tile of g already has.  So only a
+// halo-free tile of x2 is staged besides, and every 16 pixels cost ceil(C K K / 4) outer products
+// (v_mfma_f32_4x4x1: rows = channels of x2, columns = shifted channels of g).  The workgroup keeps its sums
+// over all its tiles in registers and writes one row of part[workgroup][C*C*K*K] at the end (un-negated,
+// unmasked, true index order); x2 and g are read from memory once.
+template <int C, int K, int TW, bool VEC, int DIR, bool DW = false>
 __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x, const float *__restrict__ w,
                                                    float *__restrict__ y, int H, int W, int tiles_r, int tiles_c,
-                                                   unsigned ntiles)
+                                                   unsigned ntiles, const float *__restrict__ x2 = nullptr,
+                                                   float *__restrict__ part = nullptr)
 {
+    static_assert(!DW || DIR == 1, "the weight gradient rides on the transposed convolution");
+    constexpr int NCOL = C * K * K, NSW = (NCOL + 3) / 4, PW = C * NCOL;
     constexpr int HALO = 4;                      // K - 1 <= 4
     constexpr int XR = kConvRows + K - 1, XW = TW + HALO;
     constexpr int LW = TW < 64 ? TW : 64;        // pixels of one row a wave covers per batch
@@ -125,10 +136,27 @@ __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x,
     constexpr int BPR = TW / LW;                 // batches per row
     constexpr int NBATCH = kConvRows * TW / 64;
     extern __shared__ float sx[];
+    float *sx2 = sx + C * XR * XW;               // DW: [C][kConvRows][TW], no halo
     unsigned t0, t1, tstep;
     tile_sweep(ntiles, t0, t1, tstep);
-    if (t0 >= t1)
+    if (t0 >= t1) {
+        if (DW)
+            for (int e = threadIdx.x; e < PW; e += 256)
+                part[(size_t)blockIdx.x * PW + e] = 0.0f;
         return;
+    }
+    f32x4 accw[DW ? NSW : 1];
+    int woff[DW ? NSW : 1];
+    if (DW) {
+        const int j = threadIdx.x & 3;
+#pragma unroll
+        for (int s = 0; s < NSW; ++s) {
+            accw[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const int col = (4 * s + j < NCOL) ? 4 * s + j : 0;       // column (o', da, db) in mirrored indices
+            const int o = col / (K * K), da = (col / K) % K, db = col % K;
+            woff[s] = (o * XR + (K - 1) - da) * XW + HALO - db;
+        }
+    }
 
     // A operands: a lane holds the weights of output channel o = lane % 4 (zero for o >= C and for
     // the masked entries of the current-pixel tap), gathered with one load per (i, tap)
@@ -164,6 +192,10 @@ __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x,
     for (unsigned t = t0; t < t1; t += tstep) {
         const TileGeom g = geom(t, n, r0, c0, rows);
         conv_load_tile<VEC, DIR>(g, sx);
+        if (DW) {
+            const TileGeom g2{x2 + n * C * H * W, C, H, W, r0, c0, rows, kConvRows, TW};
+            conv_load_tile<VEC, DIR>(g2, sx2);
+        }
         __syncthreads();
         float *__restrict__ yi = y + n * C * H * W;
         for (int bi = 2 * wave; bi < NBATCH; bi += 8) {
@@ -210,7 +242,57 @@ __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x,
                     yi[off + (DIR ? C - 1 - o : o) * H * W] = acc1[o];
             }
         }
+        if (DW) {
+            // lane = (block b, j): row i' = j of x2, column 4s + j of the shifted g; block b takes pixel 16 grp + b
+            // of a tile row (pixels outside the image are zeros in the x2 tile and contribute nothing)
+            const int j = lane & 3, b = lane >> 2;
+            const float *ap = sx2 + (j < C ? j : 0) * kConvRows * TW + b;
+            for (int pr = wave; pr < rows; pr += 4) {
+                const float *bp = sx + pr * XW + b;
+#pragma unroll
+                for (int grp = 0; grp < TW / 16; ++grp) {
+                    const float av = ap[pr * TW + 16 * grp];
+                    float bv[NSW];
+#pragma unroll
+                    for (int s = 0; s < NSW; ++s)
+                        bv[s] = bp[woff[s] + 16 * grp];
+#pragma unroll
+                    for (int s = 0; s < NSW; ++s)
+                        accw[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(av, bv[s], accw[s], 0, 0, 0);
+                }
+            }
+        }
         __syncthreads();        // the tile is overwritten next
+    }
+    if (DW) {
+        // fixed-order sum over the 16 blocks of each wave, then over the four waves; lane (b, j) register
+        // (s, i') holds block b's sum of entry (i', column 4s + j)
+        float *sred = sx;                               // [256][NSW*4], then [4][PW]
+        float *swave = sred + 256 * NSW * 4;
+#pragma unroll
+        for (int s = 0; s < NSW; ++s)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                sred[threadIdx.x * (NSW * 4) + s * 4 + i] = accw[s][i];
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < 4 * PW; idx += 256) {
+            const int e = idx % PW, wv = idx / PW;
+            const int ip = e / NCOL, col = e % NCOL;            // mirrored x2 channel i', column (o', da, db)
+            const int s = col >> 2, jj = col & 3;
+            float sum = 0.0f;
+#pragma unroll
+            for (int bb = 0; bb < 16; ++bb)
+                sum += sred[(wv * 64 + bb * 4 + jj) * (NSW * 4) + s * 4 + ip];
+            swave[wv * PW + e] = sum;
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < PW; e += 256) {
+            const int ip = e / NCOL, col = e % NCOL;
+            const int op = col / (K * K), da = (col / K) % K, db = col % K;
+            // mirrored channel c' is true channel C-1-c'; reach (da, db) is tap (K-1-da, K-1-db)
+            const int dst = (((C - 1 - op) * C + (C - 1 - ip)) * K + (K - 1 - da)) * K + (K - 1 - db);
+            part[(size_t)blockIdx.x * PW + dst] = ((swave[e] + swave[PW + e]) + swave[2 * PW + e]) + swave[3 * PW + e];
+        }
     }
 }
 
@@ -407,6 +489,42 @@ static void launch_small_tw(const float *x, const float *w, float *y, int B, int
                            tiles_r, tiles_c, (unsigned)ntiles);
 }
 
+// LDS of the backward form: the tile of g with halo, the tile of x2 without; the final reduction reuses them
+template <int C, int K, int TW>
+static size_t conv_small_dw_lds()
+{
+    constexpr size_t ncol = (size_t)C * K * K, nsw = (ncol + 3) / 4;
+    const size_t tiles = (size_t)C * (kConvRows + K - 1) * (TW + 4) + (size_t)C * kConvRows * TW;
+    const size_t red = 256 * nsw * 4 + 4 * (size_t)C * ncol;
+    return sizeof(float) * (tiles > red ? tiles : red);
+}
+
+template <int C, int K, int TW>
+static unsigned launch_small_dw_tw(const float *g, const float *w, float *dx, const float *x2, float *part, int B, int H,
+                                   int W, hipStream_t stream)
+{
+    const int tiles_r = (H + kConvRows - 1) / kConvRows, tiles_c = (W + TW - 1) / TW;
+    const size_t ntiles = (size_t)B * tiles_r * tiles_c;
+    const size_t lds = conv_small_dw_lds<C, K, TW>();
+    const unsigned grid = conv_grid(ntiles);
+    if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_conv_small<C, K, TW, true, 1, true>), lds))
+        return 0;
+    hipLaunchKernelGGL((k_conv_small<C, K, TW, true, 1, true>), dim3(grid), dim3(256), lds, stream, g, w, dx, H, W,
+                       tiles_r, tiles_c, (unsigned)ntiles, x2, part);
+    return grid;
+}
+
+template <int C, int K>
+static unsigned launch_small_dw(const float *g, const float *w, float *dx, const float *x2, float *part, int B, int H,
+                                int W, hipStream_t stream)
+{
+    if (W <= 32)
+        return launch_small_dw_tw<C, K, 32>(g, w, dx, x2, part, B, H, W, stream);
+    if (W <= 64)
+        return launch_small_dw_tw<C, K, 64>(g, w, dx, x2, part, B, H, W, stream);
+    return launch_small_dw_tw<C, K, 128>(g, w, dx, x2, part, B, H, W, stream);
+}
+
 template <int C, int K, int DIR>
 static void launch_small(const float *x, const float *w, float *y, int B, int H, int W, int vec, hipStream_t stream)
 {
@@ -496,6 +614,31 @@ static int launch_conv_dir(const float *x, const float *w, float *y, int B, int 
         if (blocks > 65536) blocks = 65536;
         hipLaunchKernelGGL(k_conv_generic<DIR>, dim3((unsigned)blocks), dim3(256), 0, stream, x, w, y, B, C, H, W, k);
     }
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+// Few channels, rows of whole 16-byte pieces: dL/dx = M^T g and the partial sums of dL/dw in one pass over g
+// and x.  part needs kConvMaxGrid rows of C*C*k*k floats.
+bool conv_bwd_fused_supported(int C, int H, int W, int k)
+{
+    return ((C >= 1 && C <= 4 && k == 3) || (C == 3 && k == 5)) && (W % 4) == 0 && (size_t)C * H * W <= 0x7fffffffull;
+}
+
+size_t conv_bwd_fused_rows() { return kConvMaxGrid; }
+
+// Returns the number of partial rows written (0: not launched)
+int launch_conv_bwd_fused(const float *g, const float *w, float *dx, const float *x, float *part, int B, int C, int H,
+                          int W, int k, hipStream_t stream, unsigned *rows)
+{
+    unsigned n = 0;
+    if (C == 1 && k == 3) n = launch_small_dw<1, 3>(g, w, dx, x, part, B, H, W, stream);
+    else if (C == 2 && k == 3) n = launch_small_dw<2, 3>(g, w, dx, x, part, B, H, W, stream);
+    else if (C == 3 && k == 3) n = launch_small_dw<3, 3>(g, w, dx, x, part, B, H, W, stream);
+    else if (C == 4 && k == 3) n = launch_small_dw<4, 3>(g, w, dx, x, part, B, H, W, stream);
+    else if (C == 3 && k == 5) n = launch_small_dw<3, 5>(g, w, dx, x, part, B, H, W, stream);
+    *rows = n;
+    if (!n)
+        return INVCONV_ERR_UNSUPPORTED;
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

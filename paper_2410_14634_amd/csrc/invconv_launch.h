@@ -116,6 +116,10 @@ int launch_chain(int dir, ChainArgs args, int C, int k, hipStream_t stream);
 // y = M x (dir 0) or y = M^T x (dir 1) for the masked causal convolution M
 int launch_conv(int dir, const float *x, const float *w, float *y, int B, int C, int H, int W, int k,
                 hipStream_t stream);
+bool conv_bwd_fused_supported(int C, int H, int W, int k);
+size_t conv_bwd_fused_rows();
+int launch_conv_bwd_fused(const float *g, const float *w, float *dx, const float *x, float *part, int B, int C, int H,
+                          int W, int k, hipStream_t stream, unsigned *rows);
 int launch_logdet(const float *w, int C, int H, int W, int k, float *out, hipStream_t stream);
 
 // One flow step (inverse convolution, per-channel affine map, 1 x 1 convolution): invconv_flow.hip
