@@ -480,7 +480,19 @@ def scale_study(reps=30):
         ms_f = event_time_batch(torch, lambda: b.invconv_fwd(y, w, out=x, workspace=wsf), reps, 3)
         ms_b = event_time_batch(torch, lambda: b.invconv_bwd(x, w, g, out=(v, dw), workspace=wsp), reps, 3)
         n = B * C * H * W
-        out[name] = dict(B=B, C=C, H=H, W=W, k=k, fwd_us=ms_f * 1e3, bwd_us=ms_b * 1e3,
+        extra = {}
+        if name.startswith("batch_"):
+            # the bf16-storage variant (half the HBM bytes, fp32 arithmetic) on the bandwidth-bound batches
+            y16, g16 = y.to(torch.bfloat16), g.to(torch.bfloat16)
+            x16, v16 = torch.empty_like(y16), torch.empty_like(y16)
+            ws16 = b.new_workspace(b.bf16_workspace_bytes(B, C, H, W, k))
+            b.invconv_fwd_bf16(y16, w, out=x16, workspace=ws16)
+            ms_f16 = event_time_batch(torch, lambda: b.invconv_fwd_bf16(y16, w, out=x16, workspace=ws16), reps, 3)
+            ms_b16 = event_time_batch(torch, lambda: b.invconv_bwd_bf16(x16, w, g16, out=(v16, dw), workspace=ws16),
+                                      reps, 3)
+            extra = dict(bf16_fwd_us=ms_f16 * 1e3, bf16_bwd_us=ms_b16 * 1e3,
+                         bf16_images_per_s=B / ((ms_f16 + ms_b16) * 1e-3))
+        out[name] = dict(B=B, C=C, H=H, W=W, k=k, fwd_us=ms_f * 1e3, bwd_us=ms_b * 1e3, **extra,
                          images_per_s=B / ((ms_f + ms_b) * 1e-3),
                          algorithmic_gbs=20.0 * n / ((ms_f + ms_b) * 1e-3) / 1e9,
                          us_per_diagonal=(ms_f + ms_b) * 1e3 / (2 * (H + W - 1)))

@@ -243,6 +243,24 @@ invconv_status invconv_flowstep_bwd_ex(const float *z, const float *w, const flo
                                        float *dLdQ, float logdet_weight, int B, int C, int H, int W, int k,
                                        void *workspace, size_t workspace_bytes, void *stream, int form);
 
+/*
+ * bf16-STORAGE VARIANT of invconv_fwd / invconv_bwd: the activations (y, x, dLdx, dLdy) are bf16 in memory
+ * (16-bit words holding the upper half of an IEEE float, round to nearest even on the way out), the kernel w and
+ * its gradient dLdw stay fp32, and all arithmetic is fp32 as in the plain calls.  Half the HBM bytes of the
+ * fp32 calls; what matters where a batch is large enough to be bandwidth-bound.  Few-channel images that fit on
+ * chip (C <= 4, H <= 64) convert on the way into and out of the on-chip tile; other shapes run the fp32 kernels
+ * between conversion passes over scratch.  Results carry bf16's rounding: x and dLdy agree with the fp32 calls
+ * on the same (bf16-exact) inputs to 2^-8 relative per element; dLdw is formed from the unrounded dLdy.
+ *   y, x, dLdx, dLdy: B*C*H*W 16-bit words (8-byte aligned for the on-chip form).
+ *   workspace: at least invconv_bf16_workspace_bytes() bytes.
+ */
+invconv_status invconv_fwd_bf16(const void *y, const float *w, void *x, int B, int C, int H, int W, int k,
+                                void *workspace, size_t workspace_bytes, void *stream);
+invconv_status invconv_bwd_bf16(const void *x, const float *w, const void *dLdx, void *dLdy, float *dLdw,
+                                int B, int C, int H, int W, int k,
+                                void *workspace, size_t workspace_bytes, void *stream);
+size_t invconv_bf16_workspace_bytes(int B, int C, int H, int W, int k);   /* 0 if invalid or unsupported */
+
 /* Same operations with an explicit kernel variant (INVCONV_VARIANT_*). */
 invconv_status invconv_fwd_ex(const float *y, const float *w, float *x,
                               int B, int C, int H, int W, int k, void *stream, int variant);

@@ -29,6 +29,7 @@ EXPORTS = (
     "invconv_bwd_static",
     "invconv_flowstep_fwd", "invconv_flowstep_bwd", "invconv_flowstep_workspace_bytes",
     "invconv_flowstep_fwd_ex", "invconv_flowstep_bwd_ex",
+    "invconv_fwd_bf16", "invconv_bwd_bf16", "invconv_bf16_workspace_bytes",
 )
 FLOW_AUTO, FLOW_SEPARATE, FLOW_FUSED = 0, 1, 2
 WS_HEADER_BYTES = 256
@@ -96,6 +97,12 @@ def lib() -> ctypes.CDLL:
         L.invconv_flowstep_bwd_ex.restype = ci
         L.invconv_flowstep_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
         L.invconv_flowstep_workspace_bytes.restype = sz
+        L.invconv_fwd_bf16.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+        L.invconv_fwd_bf16.restype = ci
+        L.invconv_bwd_bf16.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+        L.invconv_bwd_bf16.restype = ci
+        L.invconv_bf16_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+        L.invconv_bf16_workspace_bytes.restype = sz
         L.invconv_status_string.argtypes = [ci]
         L.invconv_status_string.restype = ctypes.c_char_p
         L.invconv_version.restype = ci
@@ -381,3 +388,48 @@ def invconv_flowstep_bwd(z: torch.Tensor, w: torch.Tensor, s: torch.Tensor, b: t
     if st != OK:
         raise InvconvError(st, "invconv_flowstep_bwd")
     return dict(dy=dy, dw=dw, ds=ds, db=db, dQ=dQ)
+
+
+def _check16(t: torch.Tensor, name: str, shape=None) -> torch.Tensor:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous bfloat16 CUDA tensor")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    return t
+
+
+def bf16_workspace_bytes(B: int, C: int, H: int, W: int, k: int) -> int:
+    return int(lib().invconv_bf16_workspace_bytes(B, C, H, W, k))
+
+
+def invconv_fwd_bf16(y: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None,
+                     workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """invconv_fwd with bf16 activations in memory (fp32 kernel, fp32 arithmetic)."""
+    _check16(y, "y"), _check(w, "w")
+    B, C, H, W, k = _dims(y, w)
+    x = torch.empty_like(y) if out is None else _check16(out, "out", y.shape)
+    if workspace is None:
+        workspace = new_workspace(bf16_workspace_bytes(B, C, H, W, k), y.device)
+    st = lib().invconv_fwd_bf16(y.data_ptr(), w.data_ptr(), x.data_ptr(), B, C, H, W, k, workspace.data_ptr(),
+                                workspace.numel(), _stream())
+    if st != OK:
+        raise InvconvError(st, "invconv_fwd_bf16")
+    return x
+
+
+def invconv_bwd_bf16(x: torch.Tensor, w: torch.Tensor, dLdx: torch.Tensor, workspace: torch.Tensor | None = None,
+                     out: tuple[torch.Tensor, torch.Tensor] | None = None):
+    """(dL/dy as bf16, dL/dw as fp32) with bf16 activations in memory."""
+    _check16(x, "x"), _check(w, "w"), _check16(dLdx, "dLdx", x.shape)
+    B, C, H, W, k = _dims(x, w)
+    if out is None:
+        dLdy, dLdw = torch.empty_like(x), torch.empty_like(w)
+    else:
+        dLdy, dLdw = _check16(out[0], "out[0]", x.shape), _check(out[1], "out[1]", w.shape)
+    if workspace is None:
+        workspace = new_workspace(bf16_workspace_bytes(B, C, H, W, k), x.device)
+    st = lib().invconv_bwd_bf16(x.data_ptr(), w.data_ptr(), dLdx.data_ptr(), dLdy.data_ptr(), dLdw.data_ptr(),
+                                B, C, H, W, k, workspace.data_ptr(), workspace.numel(), _stream())
+    if st != OK:
+        raise InvconvError(st, "invconv_bwd_bf16")
+    return dLdy, dLdw

@@ -321,6 +321,13 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
     }
     if (int s = solve(1, dLdx, w, dLdy, B, C, H, W, k, st, variant, solve_ws_of(workspace, lay)))
         return s;
+    if (conv_bwd_fused_supported(C, H, W, k) && ((((size_t)x | (size_t)dLdy)) & 15) == 0) {
+        // few channels (tall images, large kernels): Theorem 2's sums as 4x4x1 outer products, x and dL/dy read once
+        unsigned rows = 0;
+        if (int s = launch_conv_bwd_fused(dLdy, w, nullptr, x, part, B, C, H, W, k, st, &rows))
+            return s;
+        return launch_dw_reduce(part, (int)rows, dLdw, C, k, st);
+    }
     if (dw_mfma_supported(C, k) && plan_dw_mfma(B, C, H, W, k).rt)
         return launch_dw_mfma(x, dLdy, dLdw, part, p, B, C, H, W, k, st);
     return launch_dw(x, dLdy, dLdw, part, p, B, C, H, W, k, st);
@@ -389,6 +396,77 @@ invconv_status invconv_bwd_static(const float *x, const float *w, const float *d
     if (int s = static_scratch(&ws))
         return s;
     return invconv_bwd(x, w, dLdx, dLdy, dLdw, B, C, H, W, k, ws, INVCONV_STATIC_SCRATCH_BYTES, stream);
+}
+
+// ---- bf16 storage variant: activations as bf16 in memory, fp32 arithmetic ----
+size_t invconv_bf16_workspace_bytes(int B, int C, int H, int W, int k)
+{
+    WsLayout lay;
+    if (check_shape(B, C, H, W, k) != INVCONV_OK || !ws_layout(B, C, H, W, k, true, &lay))
+        return 0;
+    return lay.total + 3 * up256((size_t)B * C * H * W * sizeof(float));     // fp32 copies for shapes without a bf16 kernel
+}
+
+invconv_status invconv_fwd_bf16(const void *y, const float *w, void *x, int B, int C, int H, int W, int k,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!y || !w || !x)
+        return INVCONV_ERR_NULL;
+    if (int s = check_shape(B, C, H, W, k))
+        return s;
+    if (x == y || x == (const void *)w)
+        return INVCONV_ERR_ALIAS;
+    WsLayout lay;
+    if (!ws_layout(B, C, H, W, k, true, &lay))
+        return INVCONV_ERR_UNSUPPORTED;
+    const size_t act = up256((size_t)B * C * H * W * sizeof(float));
+    if (!workspace || workspace_bytes < lay.total + 3 * act || ((size_t)workspace & 255))
+        return INVCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (wave_tile_bf16_supported(C, H, W, k) && ((((size_t)y | (size_t)x)) & 7) == 0)
+        return launch_solve_wave_tile_bf16(0, y, w, x, B, C, H, W, k, st);
+    float *t0 = (float *)((char *)workspace + lay.total), *t1 = (float *)((char *)workspace + lay.total + act);
+    const size_t n = (size_t)B * C * H * W;
+    if (int s = launch_bf16_to_f32(y, t0, n, st))
+        return s;
+    if (int s = fwd_impl(t0, w, t1, B, C, H, W, k, stream, INVCONV_VARIANT_AUTO, solve_ws_of(workspace, lay)))
+        return s;
+    return launch_f32_to_bf16(t1, x, n, st);
+}
+
+invconv_status invconv_bwd_bf16(const void *x, const float *w, const void *dLdx, void *dLdy, float *dLdw, int B, int C,
+                                int H, int W, int k, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x || !w || !dLdx || !dLdy || !dLdw)
+        return INVCONV_ERR_NULL;
+    if (int s = check_shape(B, C, H, W, k))
+        return s;
+    if (dLdy == dLdx || dLdy == x || dLdy == (const void *)w || (const void *)dLdw == dLdy || (const float *)dLdw == w ||
+        (const void *)dLdw == x || (const void *)dLdw == dLdx)
+        return INVCONV_ERR_ALIAS;
+    WsLayout lay;
+    if (!ws_layout(B, C, H, W, k, true, &lay))
+        return INVCONV_ERR_UNSUPPORTED;
+    const size_t act = up256((size_t)B * C * H * W * sizeof(float));
+    if (!workspace || workspace_bytes < lay.total + 3 * act || ((size_t)workspace & 255))
+        return INVCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    if (wave_tile_bf16_supported(C, H, W, k) && ((((size_t)x | (size_t)dLdx | (size_t)dLdy)) & 7) == 0) {
+        float *part = (float *)(ws + lay.dw_off);
+        if (int s = launch_bwd_wave_tile_bf16(x, w, dLdx, dLdy, part, B, C, H, W, k, st))
+            return s;
+        return launch_dw_reduce(part, B, dLdw, C, k, st);
+    }
+    float *t0 = (float *)(ws + lay.total), *t1 = (float *)(ws + lay.total + act), *t2 = (float *)(ws + lay.total + 2 * act);
+    const size_t n = (size_t)B * C * H * W;
+    if (int s = launch_bf16_to_f32(x, t0, n, st))
+        return s;
+    if (int s = launch_bf16_to_f32(dLdx, t1, n, st))
+        return s;
+    if (int s = invconv_bwd(t0, w, t1, t2, dLdw, B, C, H, W, k, workspace, lay.total, stream))
+        return s;
+    return launch_f32_to_bf16(t2, dLdy, n, st);
 }
 
 invconv_status invconv_logdet(const float *w, int C, int H, int W, int k, float *out, void *stream)

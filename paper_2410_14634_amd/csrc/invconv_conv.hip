@@ -121,7 +121,9 @@ __device__ __forceinline__ void conv_load_tile(const TileGeom &g, float *sx)
 // (v_mfma_f32_4x4x1: rows = channels of x2, columns = shifted channels of g).  The workgroup keeps its sums
 // over all its tiles in registers and writes one row of part[workgroup][C*C*K*K] at the end (un-negated,
 // unmasked, true index order); x2 and g are read from memory once.
-template <int C, int K, int TW, bool VEC, int DIR, bool DW = false>
+// CONV = false (with DW): only the weight-gradient sums are formed, y is not touched (the backward pass of the
+// inverse convolution uses it with g = dL/dy and the sign of the second pass flipped, Theorem 2).
+template <int C, int K, int TW, bool VEC, int DIR, bool DW = false, bool CONV = true>
 __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x, const float *__restrict__ w,
                                                    float *__restrict__ y, int H, int W, int tiles_r, int tiles_c,
                                                    unsigned ntiles, const float *__restrict__ x2 = nullptr,
@@ -198,7 +200,7 @@ __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x,
         }
         __syncthreads();
         float *__restrict__ yi = y + n * C * H * W;
-        for (int bi = 2 * wave; bi < NBATCH; bi += 8) {
+        for (int bi = 2 * wave; CONV && bi < NBATCH; bi += 8) {
             // batches bi and bi + 1
             const int pr0 = (bi / BPR) * RPB + lr, pc0 = (bi % BPR) * LW + lc;
             constexpr int D1 = (BPR == 2) ? 64 : RPB * XW;     // LDS distance between the two batches
@@ -507,10 +509,17 @@ static unsigned launch_small_dw_tw(const float *g, const float *w, float *dx, co
     const size_t ntiles = (size_t)B * tiles_r * tiles_c;
     const size_t lds = conv_small_dw_lds<C, K, TW>();
     const unsigned grid = conv_grid(ntiles);
-    if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_conv_small<C, K, TW, true, 1, true>), lds))
-        return 0;
-    hipLaunchKernelGGL((k_conv_small<C, K, TW, true, 1, true>), dim3(grid), dim3(256), lds, stream, g, w, dx, H, W,
-                       tiles_r, tiles_c, (unsigned)ntiles, x2, part);
+    if (dx) {
+        if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_conv_small<C, K, TW, true, 1, true>), lds))
+            return 0;
+        hipLaunchKernelGGL((k_conv_small<C, K, TW, true, 1, true>), dim3(grid), dim3(256), lds, stream, g, w, dx, H, W,
+                           tiles_r, tiles_c, (unsigned)ntiles, x2, part);
+    } else {        // weight-gradient sums only
+        if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_conv_small<C, K, TW, true, 1, true, false>), lds))
+            return 0;
+        hipLaunchKernelGGL((k_conv_small<C, K, TW, true, 1, true, false>), dim3(grid), dim3(256), lds, stream, g, w, dx,
+                           H, W, tiles_r, tiles_c, (unsigned)ntiles, x2, part);
+    }
     return grid;
 }
 
@@ -626,6 +635,7 @@ bool conv_bwd_fused_supported(int C, int H, int W, int k)
 
 size_t conv_bwd_fused_rows() { return kConvMaxGrid; }
 
+// dx may be null: then only the partial sums of the weight gradient are formed (g and x read once).
 // Returns the number of partial rows written (0: not launched)
 int launch_conv_bwd_fused(const float *g, const float *w, float *dx, const float *x, float *part, int B, int C, int H,
                           int W, int k, hipStream_t stream, unsigned *rows)

@@ -272,8 +272,17 @@ __global__ __launch_bounds__(64 * NW) void k_rows_sum(const float *__restrict__ 
             for (int u = 0; u < 8; ++u)
                 acc += (double)a[u];
         }
-        for (; p < nrows; p += NW)
-            acc += (double)rows[(size_t)p * stride + e];
+        if (p < nrows) {        // the last rows, loaded together (clamped addresses, rows past the end count as zero)
+            float a[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = p + NW * u;
+                a[u] = rows[(size_t)(r < nrows ? r : nrows - 1) * stride + e];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                acc += p + NW * u < nrows ? (double)a[u] : 0.0;
+        }
     }
     swave[wave][lane] = acc;
     __syncthreads();

@@ -385,8 +385,19 @@ __global__ __launch_bounds__(64 * NW) void k_dw_reduce(const float *__restrict__
             for (int u = 0; u < 8; ++u)
                 acc += (double)a[u];
         }
-        for (; p < nparts; p += NW)
-            acc += (double)part[(size_t)p * P + e];
+        // the last rows: loaded together as well (addresses clamped, rows past the end count as zero), so that
+        // few rows cost one memory latency, not one per row
+        if (p < nparts) {
+            float a[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = p + NW * u;
+                a[u] = part[(size_t)(r < nparts ? r : nparts - 1) * P + e];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                acc += p + NW * u < nparts ? (double)a[u] : 0.0;
+        }
     }
     swave[wave][lane] = acc;
     __syncthreads();

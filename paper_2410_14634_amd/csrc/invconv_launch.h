@@ -116,6 +116,14 @@ int launch_chain(int dir, ChainArgs args, int C, int k, hipStream_t stream);
 // y = M x (dir 0) or y = M^T x (dir 1) for the masked causal convolution M
 int launch_conv(int dir, const float *x, const float *w, float *y, int B, int C, int H, int W, int k,
                 hipStream_t stream);
+// bf16 storage of the activations (fp32 arithmetic)
+bool wave_tile_bf16_supported(int C, int H, int W, int k);
+int launch_solve_wave_tile_bf16(int dir, const void *in, const float *w, void *out, int B, int C, int H, int W, int k,
+                                hipStream_t stream);
+int launch_bwd_wave_tile_bf16(const void *x, const float *w, const void *g, void *v, float *part, int B, int C, int H,
+                              int W, int k, hipStream_t stream);
+int launch_bf16_to_f32(const void *in, float *out, size_t n, hipStream_t stream);
+int launch_f32_to_bf16(const float *in, void *out, size_t n, hipStream_t stream);
 bool conv_bwd_fused_supported(int C, int H, int W, int k);
 size_t conv_bwd_fused_rows();
 int launch_conv_bwd_fused(const float *g, const float *w, float *dx, const float *x, float *part, int B, int C, int H,

@@ -54,30 +54,68 @@ __global__ __launch_bounds__(64) void k_solve_wave(const float *__restrict__ in,
 // whole cache lines instead of 64 row-strided 4-byte accesses per instruction (for large batches,
 // where those keep more lines live than the L2 holds).  Needs C*H*W a multiple of 4 and 16-byte
 // aligned tensors.
-template <int C, int K, int DIR>
-__global__ __launch_bounds__(64) void k_solve_wave_tile(const float *__restrict__ in, const float *__restrict__ w,
-                                                       float *__restrict__ out, int H, int W, float *logdet)
+// Storage type ST of the activations in memory: float, or bf16 (unsigned short holding the upper half of a
+// float; the arithmetic stays fp32, the tile in LDS is float either way).  Four consecutive elements:
+typedef unsigned short bf16_t;
+__device__ __forceinline__ float bf16_to_float(bf16_t h) { return __builtin_bit_cast(float, (unsigned)h << 16); }
+__device__ __forceinline__ bf16_t float_to_bf16(float f)      // round to nearest even; NaN stays NaN
+{
+    const unsigned u = __builtin_bit_cast(unsigned, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (bf16_t)((u >> 16) | 0x40u);
+    return (bf16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+template <typename ST> __device__ __forceinline__ float4 ld4(const ST *base, int i);
+template <> __device__ __forceinline__ float4 ld4<float>(const float *base, int i)
+{
+    return reinterpret_cast<const float4 *>(base)[i];
+}
+template <> __device__ __forceinline__ float4 ld4<bf16_t>(const bf16_t *base, int i)
+{
+    const uint2 raw = reinterpret_cast<const uint2 *>(base)[i];
+    return make_float4(__builtin_bit_cast(float, raw.x << 16), __builtin_bit_cast(float, raw.x & 0xffff0000u),
+                       __builtin_bit_cast(float, raw.y << 16), __builtin_bit_cast(float, raw.y & 0xffff0000u));
+}
+template <typename ST> __device__ __forceinline__ void st4(ST *base, int i, float4 v);
+template <> __device__ __forceinline__ void st4<float>(float *base, int i, float4 v)
+{
+    reinterpret_cast<float4 *>(base)[i] = v;
+}
+template <> __device__ __forceinline__ void st4<bf16_t>(bf16_t *base, int i, float4 v)
+{
+    uint2 raw;
+    raw.x = (unsigned)float_to_bf16(v.x) | ((unsigned)float_to_bf16(v.y) << 16);
+    raw.y = (unsigned)float_to_bf16(v.z) | ((unsigned)float_to_bf16(v.w) << 16);
+    reinterpret_cast<uint2 *>(base)[i] = raw;
+}
+__device__ __forceinline__ float ld1(const float *p) { return *p; }
+__device__ __forceinline__ float ld1(const bf16_t *p) { return bf16_to_float(*p); }
+
+template <int C, int K, int DIR, typename ST = float>
+__global__ __launch_bounds__(64) void k_solve_wave_tile(const ST *__restrict__ in, const float *__restrict__ w,
+                                                       ST *__restrict__ out, int H, int W, float *logdet)
 {
     extern __shared__ float smem[];
     if (logdet && blockIdx.x == 0)
         wave_logdet<C, K>(w, H, W, logdet);
     const int n4 = C * H * W / 4, lane = threadIdx.x;
-    const float4 *src = reinterpret_cast<const float4 *>(in + (size_t)blockIdx.x * C * H * W);
-    float4 *dst = reinterpret_cast<float4 *>(out + (size_t)blockIdx.x * C * H * W);
+    const ST *src = in + (size_t)blockIdx.x * C * H * W;
+    ST *dst = out + (size_t)blockIdx.x * C * H * W;
     float4 *tile = reinterpret_cast<float4 *>(smem);
     for (int i = lane; i < n4; i += 8 * 64) {
         float4 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            v[u] = src[i + 64 * u < n4 ? i + 64 * u : n4 - 1];
+            v[u] = ld4<ST>(src, i + 64 * u < n4 ? i + 64 * u : n4 - 1);
 #pragma unroll
         for (int u = 0; u < 8; ++u)
             if (i + 64 * u < n4)
                 tile[i + 64 * u] = v[u];
     }
-    solve_wave_body<C, K, DIR, false, false, true>(in, w, out, H, W, blockIdx.x, smem);
+    // (the body works on the LDS tile only; it never touches the global pointers in this mode)
+    solve_wave_body<C, K, DIR, false, false, true>(nullptr, w, nullptr, H, W, blockIdx.x, smem);
     for (int i = lane; i < n4; i += 64)
-        dst[i] = tile[i];
+        st4<ST>(dst, i, tile[i]);
 }
 
 // ---------------------------------------------------------------------------
@@ -469,11 +507,12 @@ __global__ void k_wave_bands_clear(int *gcount, int count)
 // the waves (solve_wave_split_body); its exchange buffers sit behind the tiles.
 // With TILE (large batches, see wave_tile_preferred) all four waves first bring dL/dx and x into LDS with
 // accesses of consecutive lanes, wave 0 solves in place in LDS, and dL/dy leaves the same way afterwards.
-template <int C, int K, bool SPLIT, bool TILE = false>
-__global__ __launch_bounds__(256) void k_bwd_wave(const float *__restrict__ x, const float *__restrict__ w,
-                                                 const float *__restrict__ g, float *__restrict__ v,
+template <int C, int K, bool SPLIT, bool TILE = false, typename ST = float>
+__global__ __launch_bounds__(256) void k_bwd_wave(const ST *__restrict__ x, const float *__restrict__ w,
+                                                 const ST *__restrict__ g, ST *__restrict__ v,
                                                  float *__restrict__ part, int H, int W)
 {
+    static_assert(TILE || std::is_same<ST, float>::value, "other storage types go through the LDS tile");
     extern __shared__ float smem[];
     constexpr int NCOL = C * K * K;            // shifted-x columns (i, a, b)
     constexpr int NS = (NCOL + 3) / 4;         // groups of four columns
@@ -534,20 +573,20 @@ __global__ __launch_bounds__(256) void k_bwd_wave(const float *__restrict__ x, c
         sl.m = reinterpret_cast<f32x4 *>(sl.x + 2 * C * 64);
         solve_wave_split_body<C, K, 1, true>(g, w, v, H, W, n, sv, sl);
     } else if constexpr (TILE) {
-        const float4 *g4 = reinterpret_cast<const float4 *>(g + (size_t)n * C * H * W);
+        const ST *gi = g + (size_t)n * C * H * W;
         float4 *sv4 = reinterpret_cast<float4 *>(sv);
         const int n4 = C * H * W / 4;
         for (int i = tid; i < n4; i += 256)
-            sv4[i] = g4[i];
-        const float *xi = x + (size_t)n * C * H * W;
+            sv4[i] = ld4<ST>(gi, i);
+        const ST *xi = x + (size_t)n * C * H * W;
         for (int idx = tid; idx < C * XR * XW; idx += 256) {
             const int cc = idx % XW, rr = (idx / XW) % XR, ch = idx / (XW * XR);
             const int gr = rr - (K - 1), gc = cc - (K - 1);
-            sx[idx] = (gr >= 0 && gc >= 0) ? xi[(ch * H + gr) * W + gc] : 0.0f;
+            sx[idx] = (gr >= 0 && gc >= 0) ? ld1(xi + (ch * H + gr) * W + gc) : 0.0f;
         }
         __syncthreads();
         if (wave == 0)
-            solve_wave_body<C, K, 1, false, false, true>(g, w, v, H, W, n, sv);
+            solve_wave_body<C, K, 1, false, false, true>(nullptr, w, nullptr, H, W, n, sv);
     } else if (wave == 0) {
         solve_wave_body<C, K, 1, true>(g, w, v, H, W, n, sv);
     } else {
@@ -560,10 +599,10 @@ __global__ __launch_bounds__(256) void k_bwd_wave(const float *__restrict__ x, c
     }
     __syncthreads();
     if constexpr (TILE) {
-        float4 *v4 = reinterpret_cast<float4 *>(v + (size_t)n * C * H * W);
+        ST *vo = v + (size_t)n * C * H * W;
         const float4 *sv4 = reinterpret_cast<const float4 *>(sv);
         for (int i = tid; i < C * H * W / 4; i += 256)
-            v4[i] = sv4[i];
+            st4<ST>(vo, i, sv4[i]);
     }
 
     // lane = (block b, j): A row o = j, B column 4s + j.  Rows o >= C and columns
@@ -1126,6 +1165,105 @@ int launch_solve_wave(int dir, const float *in, const float *w, float *out, int 
     if (C == 2 && k == 3) return launch_wave_ck<2, 3>(dir, in, w, out, B, H, W, stream, logdet);
     if (C == 4 && k == 3) return launch_wave_ck<4, 3>(dir, in, w, out, B, H, W, stream, logdet);
     return INVCONV_ERR_VARIANT;
+}
+
+// ---------------------------------------------------------------------------
+// bf16 storage (activations as bf16 in memory, fp32 arithmetic): the LDS-tile kernels with the conversion
+// on the way in and out.  Few channels, images that fit LDS, C*H*W a multiple of 4, 8-byte aligned tensors.
+// ---------------------------------------------------------------------------
+static bool wave_tile_bf16_ck(int C, int k) { return (C == 3 && (k == 3 || k == 5)) || ((C == 1 || C == 2 || C == 4) && k == 3); }
+
+bool wave_tile_bf16_supported(int C, int H, int W, int k)
+{
+    return wave_tile_bf16_ck(C, k) && wave_supported(C, H, k) && (C * H * W) % 4 == 0 &&
+           (size_t)C * H * W * sizeof(float) <= 64 * 1024 && bwd_wave_lds_bytes(C, H, W, k) <= kMaxLdsBytes;
+}
+
+template <int C, int K>
+static int launch_tile_bf16_ck(int dir, const bf16_t *in, const float *w, bf16_t *out, int B, int H, int W,
+                               hipStream_t stream)
+{
+    const size_t lds = (size_t)C * H * W * sizeof(float);
+    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave_tile<C, K, 1, bf16_t>)
+                         : reinterpret_cast<const void *>(&k_solve_wave_tile<C, K, 0, bf16_t>);
+    if (!ensure_dynamic_lds(fn, lds))
+        return INVCONV_ERR_UNSUPPORTED;
+    if (dir)
+        hipLaunchKernelGGL((k_solve_wave_tile<C, K, 1, bf16_t>), dim3(B), dim3(64), lds, stream, in, w, out, H, W,
+                           (float *)nullptr);
+    else
+        hipLaunchKernelGGL((k_solve_wave_tile<C, K, 0, bf16_t>), dim3(B), dim3(64), lds, stream, in, w, out, H, W,
+                           (float *)nullptr);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+int launch_solve_wave_tile_bf16(int dir, const void *in, const float *w, void *out, int B, int C, int H, int W, int k,
+                                hipStream_t stream)
+{
+    if (!wave_tile_bf16_supported(C, H, W, k))
+        return INVCONV_ERR_VARIANT;
+    const bf16_t *i16 = static_cast<const bf16_t *>(in);
+    bf16_t *o16 = static_cast<bf16_t *>(out);
+    if (C == 3 && k == 3) return launch_tile_bf16_ck<3, 3>(dir, i16, w, o16, B, H, W, stream);
+    if (C == 3 && k == 5) return launch_tile_bf16_ck<3, 5>(dir, i16, w, o16, B, H, W, stream);
+    if (C == 1 && k == 3) return launch_tile_bf16_ck<1, 3>(dir, i16, w, o16, B, H, W, stream);
+    if (C == 2 && k == 3) return launch_tile_bf16_ck<2, 3>(dir, i16, w, o16, B, H, W, stream);
+    if (C == 4 && k == 3) return launch_tile_bf16_ck<4, 3>(dir, i16, w, o16, B, H, W, stream);
+    return INVCONV_ERR_VARIANT;
+}
+
+template <int C, int K>
+static int launch_bwd_tile_bf16_ck(const bf16_t *x, const float *w, const bf16_t *g, bf16_t *v, float *part, int B,
+                                   int H, int W, hipStream_t stream)
+{
+    const size_t lds = bwd_wave_lds_bytes(C, H, W, K);
+    if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_bwd_wave<C, K, false, true, bf16_t>), lds))
+        return INVCONV_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_bwd_wave<C, K, false, true, bf16_t>), dim3(B), dim3(256), lds, stream, x, w, g, v, part, H, W);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+// dL/dy (bf16) and the per-image partial sums of dL/dw (fp32, from the unrounded dL/dy) in one launch
+int launch_bwd_wave_tile_bf16(const void *x, const float *w, const void *g, void *v, float *part, int B, int C, int H,
+                              int W, int k, hipStream_t stream)
+{
+    if (!wave_tile_bf16_supported(C, H, W, k))
+        return INVCONV_ERR_VARIANT;
+    const bf16_t *x16 = static_cast<const bf16_t *>(x), *g16 = static_cast<const bf16_t *>(g);
+    bf16_t *v16 = static_cast<bf16_t *>(v);
+    if (C == 3 && k == 3) return launch_bwd_tile_bf16_ck<3, 3>(x16, w, g16, v16, part, B, H, W, stream);
+    if (C == 3 && k == 5) return launch_bwd_tile_bf16_ck<3, 5>(x16, w, g16, v16, part, B, H, W, stream);
+    if (C == 1 && k == 3) return launch_bwd_tile_bf16_ck<1, 3>(x16, w, g16, v16, part, B, H, W, stream);
+    if (C == 2 && k == 3) return launch_bwd_tile_bf16_ck<2, 3>(x16, w, g16, v16, part, B, H, W, stream);
+    if (C == 4 && k == 3) return launch_bwd_tile_bf16_ck<4, 3>(x16, w, g16, v16, part, B, H, W, stream);
+    return INVCONV_ERR_VARIANT;
+}
+
+// Conversion passes for the shapes the tile kernels do not take
+__global__ void k_bf16_to_f32(const bf16_t *__restrict__ in, float *__restrict__ out, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        out[i] = bf16_to_float(in[i]);
+}
+
+__global__ void k_f32_to_bf16(const float *__restrict__ in, bf16_t *__restrict__ out, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        out[i] = float_to_bf16(in[i]);
+}
+
+int launch_bf16_to_f32(const void *in, float *out, size_t n, hipStream_t stream)
+{
+    const unsigned grid = (unsigned)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
+    hipLaunchKernelGGL(k_bf16_to_f32, dim3(grid), dim3(256), 0, stream, static_cast<const bf16_t *>(in), out, n);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+int launch_f32_to_bf16(const float *in, void *out, size_t n, hipStream_t stream)
+{
+    const unsigned grid = (unsigned)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
+    hipLaunchKernelGGL(k_f32_to_bf16, dim3(grid), dim3(256), 0, stream, in, static_cast<bf16_t *>(out), n);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
 }  // namespace invconv

@@ -17,7 +17,7 @@ def declared_functions():
     names = set()
     for path in glob.glob(os.path.join(ROOT, "include", "*.h")):
         text = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)
-        names.update(re.findall(r"\b(invconv_[a-z_]+)\s*\(", text))
+        names.update(re.findall(r"\b(invconv_[a-z0-9_]+)\s*\(", text))
     return sorted(names)
 
 
