@@ -80,6 +80,8 @@ def parse_args():
     ap.add_argument("--flow-step", action="store_true",
                     help="only the flow step (inverse convolution + Actnorm + 1x1 convolution): fused kernels against "
                          "the same arithmetic as separate passes")
+    ap.add_argument("--flow-shape", default=None, help="with --flow-step: only this named shape (for profiling)")
+    ap.add_argument("--reps", type=int, default=None, help="with --flow-step: timed repetitions per form")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three 64 MiB device copies (reference for the HBM byte counters)")
     return ap.parse_args()
@@ -506,7 +508,7 @@ FLOW_SHAPES = {  # (B, C, H, W, k)
 }
 
 
-def flow_step_study(reps=50):
+def flow_step_study(reps=50, only=None):
     """One flow step (Section 4.1: inverse convolution, Actnorm, 1 x 1 convolution) forward + backward: the fused
     kernels (read y, write z; read z and dL/dz, write dL/dy: 20 bytes per element, what the inverse convolution
     alone moves) against the same arithmetic as separate passes (60 bytes per element: each neighbour adds a read
@@ -516,6 +518,8 @@ def flow_step_study(reps=50):
     from paper_2410_14634_amd import inputs
     out = {}
     for name, (B, C, H, W, k) in FLOW_SHAPES.items():
+        if only and name != only:
+            continue
         cs = inputs.make_case(B, C, H, W, k, seed=9, tap_std=0.05)
         p = inputs.make_flow_params(C, 9)
         y, w, g = (torch.from_numpy(cs[n] if n != "w" else cs["w"][0]).cuda() for n in ("y", "w", "g"))
@@ -574,7 +578,7 @@ def main():
         print(json.dumps(dict(scale_study=scale_study())), flush=True)
         return
     if args.flow_step:
-        print(json.dumps(dict(flow_step=flow_step_study())), flush=True)
+        print(json.dumps(dict(flow_step=flow_step_study(reps=args.reps or 50, only=args.flow_shape))), flush=True)
         return
     cfg = args.workload
     L, res = measure_workload(cfg, args.steps, args.warmup, args.variant)
