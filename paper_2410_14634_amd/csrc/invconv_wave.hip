@@ -374,46 +374,12 @@ __global__ __launch_bounds__(512) void k_solve_wave_bands(const float *__restric
     solve_wave_body<C, K, DIR, false, true>(in, w, out, H, W, blockIdx.x, nullptr, wb);
 }
 
-// The same bands on different compute units: one workgroup per (band, image), two waves each.  Wave 0 is
-// the band's solve exactly as above, with its two logs in the workgroup's own LDS.  Wave 1 carries the
-// logs between workgroups through global memory, a block of kWavePF entries at a time: it sends what its
-// own band has appended (device-coherent stores, then a counter once they are acknowledged - it has no
-// other memory operations in flight, so that wait is exact) and fetches what the band above has published
-// into the local log, then advances the local counter the solve waits on.  A workgroup waits only for the
-// one of the band above, which has a lower block index; every wait is bounded.
-template <int C, int K, int DIR>
-__global__ __launch_bounds__(128) void k_solve_wave_bands_multi(const float *__restrict__ in,
-                                                               const float *__restrict__ w, float *__restrict__ out,
-                                                               int B, int H, int W, int log_steps, int *gcount,
-                                                               f32x4 *glog, int spin_limit, int *err)
+// The courier of a band's workgroup (one wave): carries the two logs between the workgroup's LDS and the
+// logs in global memory, a block of kWavePF entries at a time.
+template <int K>
+__device__ __forceinline__ void bands_courier(f32x4 *log, int *prog, size_t seg, int band, int nb, int n,
+                                              int log_steps, int *gcount, f32x4 *glog, int spin_limit, int *err)
 {
-    extern __shared__ float smem[];
-    const int nb = (H + 63) >> 6;
-    const int band = blockIdx.x / B, n = blockIdx.x % B;
-    const size_t seg = (size_t)log_steps * (K - 1);
-    f32x4 *log = reinterpret_cast<f32x4 *>(smem);        // [2][log_steps][K - 1]: received, sent
-    f32x4 *scratch = log + 2 * seg;
-    int *prog = reinterpret_cast<int *>(scratch + 64 * (K - 1));        // [2]: received, sent
-    if (threadIdx.x < 2)
-        prog[threadIdx.x] = 0;
-    __syncthreads();
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (wave == 0) {
-        WaveBands wb;
-        wb.band = band;
-        wb.nbands = nb;
-        wb.log_in = log;
-        wb.log_out = log + seg;
-        wb.prog_in = prog;
-        wb.prog_out = prog + 1;
-        wb.log_steps = log_steps;
-        wb.scratch = scratch;
-        wb.spin_limit = spin_limit;
-        wb.err = err;
-        solve_wave_body<C, K, DIR, false, true>(in, w, out, H, W, n, nullptr, wb);
-        return;
-    }
-    // ---- courier
     const int lane = threadIdx.x & 63;
     const int per_blk = kWavePF * (K - 1);               // 16-byte entries per block (at most 64: K <= 5)
     const int send_total = band + 1 < nb ? log_steps : 0, recv_total = band > 0 ? log_steps : 0;
@@ -482,11 +448,243 @@ __global__ __launch_bounds__(128) void k_solve_wave_bands_multi(const float *__r
         __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// The same bands on different compute units: one workgroup per (band, image), two waves each.  Wave 0 is
+// the band's solve exactly as above, with its two logs in the workgroup's own LDS.  Wave 1 carries the
+// logs between workgroups through global memory, a block of kWavePF entries at a time: it sends what its
+// own band has appended (device-coherent stores, then a counter once they are acknowledged - it has no
+// other memory operations in flight, so that wait is exact) and fetches what the band above has published
+// into the local log, then advances the local counter the solve waits on.  A workgroup waits only for the
+// one of the band above, which has a lower block index; every wait is bounded.
+template <int C, int K, int DIR>
+__global__ __launch_bounds__(128) void k_solve_wave_bands_multi(const float *__restrict__ in,
+                                                               const float *__restrict__ w, float *__restrict__ out,
+                                                               int B, int H, int W, int log_steps, int *gcount,
+                                                               f32x4 *glog, int spin_limit, int *err)
+{
+    extern __shared__ float smem[];
+    const int nb = (H + 63) >> 6;
+    const int band = blockIdx.x / B, n = blockIdx.x % B;
+    const size_t seg = (size_t)log_steps * (K - 1);
+    f32x4 *log = reinterpret_cast<f32x4 *>(smem);        // [2][log_steps][K - 1]: received, sent
+    f32x4 *scratch = log + 2 * seg;
+    int *prog = reinterpret_cast<int *>(scratch + 64 * (K - 1));        // [2]: received, sent
+    if (threadIdx.x < 2)
+        prog[threadIdx.x] = 0;
+    __syncthreads();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (wave == 0) {
+        WaveBands wb;
+        wb.band = band;
+        wb.nbands = nb;
+        wb.log_in = log;
+        wb.log_out = log + seg;
+        wb.prog_in = prog;
+        wb.prog_out = prog + 1;
+        wb.log_steps = log_steps;
+        wb.scratch = scratch;
+        wb.spin_limit = spin_limit;
+        wb.err = err;
+        solve_wave_body<C, K, DIR, false, true>(in, w, out, H, W, n, nullptr, wb);
+        return;
+    }
+    bands_courier<K>(log, prog, seg, band, nb, n, log_steps, gcount, glog, spin_limit, err);
+}
+
 __global__ void k_wave_bands_clear(int *gcount, int count)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count)
         gcount[i] = 0;
+}
+
+// ---------------------------------------------------------------------------
+// Bands on different compute units with whole-line memory traffic (W a multiple of 4): four waves per
+// (band, image).  Wave 0 solves as above but reads its input from, and writes its result into, an LDS
+// ring of kRingCols columns per row (in place); wave 1 is the courier of the logs; wave 2 fills the ring
+// and wave 3 drains it, both with 16-byte accesses of which four neighbouring lanes cover 64 contiguous
+// bytes of one row.  The solving wave itself then issues no memory instruction whose lanes touch 64
+// different cache lines, which is what bounds the step of the kernel above.
+//
+// Schedule, in blocks of kWavePF steps and chunks of kWavePF columns (rho(r) = floor((r-1)/16)):
+//   load block m    row r receives chunk m - rho(r), m = -1, 0, ...; the solve starts block j once load blocks
+//                   <= j are in LDS;
+//   solve block j   row r reads chunks j - rho - 1 and j - rho and overwrites columns 16j - r .. 16j+15 - r;
+//   store block m   after solve block m, row r's chunk m - rho - 1 is complete and leaves.
+// A slot is therefore held by chunk q of row r from load block q + rho to store block q + rho + 1, and the
+// chunk q + 4 that takes the same slot is written by load block q + rho + 4, which waits until store block
+// q + rho + 1 has read the slot.  The filling wave keeps the loads of the next two blocks in flight in its
+// registers, so the wait for a slot does not expose memory latency.  Dependencies only point to earlier
+// blocks, every wait is bounded, and a wave that gives up sets the error word and passes NaN on.
+// ---------------------------------------------------------------------------
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bool wait_count(const int *counter, int need, int spin_limit)
+{
+    int spins = 0;
+    while (__hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < need && ++spins < spin_limit)
+        __builtin_amdgcn_s_sleep(1);
+    return __hip_atomic_load(counter, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= need;
+}
+
+// Byte offset of the four columns 16q + 4p .. + 3 (solve coordinates) of band row `row`, channel ch, inside
+// the image, or an offset past the image (the buffer unit then returns zeros / drops the store).
+template <int C, int DIR>
+__device__ __forceinline__ unsigned ring_item_offset(int ch, int row, int q, int p, int band, int band_rows, int H,
+                                                     int W, bool need_row)
+{
+    const int cs0 = 16 * q + 4 * p;
+    const bool ok = q >= 0 && cs0 < W && (!need_row || row < band_rows);
+    const int rc = row < band_rows ? row : band_rows - 1;
+    const int grow = 64 * band + rc;
+    const int mrow = DIR ? H - 1 - grow : grow, mcol = DIR ? W - 4 - cs0 : cs0, mch = DIR ? C - 1 - ch : ch;
+    return ok ? (unsigned)((((size_t)mch * H + mrow) * W + mcol) * sizeof(float)) : 0x80000000u;
+}
+
+template <int C, int K, int DIR>
+__global__ __launch_bounds__(256) void k_solve_wave_bands_io(const float *__restrict__ in, const float *__restrict__ w,
+                                                            float *__restrict__ out, int B, int H, int W,
+                                                            int log_steps, int *gcount, f32x4 *glog, int spin_limit,
+                                                            int spin_courier, int *err)
+{
+    extern __shared__ float smem[];
+    const int nb = (H + 63) >> 6;
+    const int band = blockIdx.x / B, n = blockIdx.x % B;
+    const size_t seg = (size_t)log_steps * (K - 1);
+    f32x4 *log = reinterpret_cast<f32x4 *>(smem);        // [2][log_steps][K - 1]: received, sent
+    f32x4 *scratch = log + 2 * seg;
+    float *ring = reinterpret_cast<float *>(scratch + 64 * (K - 1));    // [C][64][kRingStride]
+    int *prog = reinterpret_cast<int *>(ring + C * 64 * kRingStride);    // received, sent, loaded, done, stored, lost
+    if (threadIdx.x < 6)
+        prog[threadIdx.x] = 0;
+    __syncthreads();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int band_rows = H - 64 * band < 64 ? H - 64 * band : 64;
+    const int nblocks = (band_rows + W - 1 + kWavePF - 1) / kWavePF;     // blocks of the solve
+    int *io_loaded = prog + 2, *io_done = prog + 3, *io_stored = prog + 4, *io_lost = prog + 5;
+    if (wave == 0) {
+        WaveBands wb;
+        wb.band = band;
+        wb.nbands = nb;
+        wb.log_in = log;
+        wb.log_out = log + seg;
+        wb.prog_in = prog;
+        wb.prog_out = prog + 1;
+        wb.log_steps = log_steps;
+        wb.scratch = scratch;
+        wb.spin_limit = spin_limit;
+        wb.err = err;
+        wb.ring = ring;
+        wb.io_loaded = io_loaded;
+        wb.io_done = io_done;
+        wb.io_lost = io_lost;
+        solve_wave_body<C, K, DIR, false, true, false, true>(in, w, out, H, W, n, nullptr, wb);
+        return;
+    }
+    if (wave == 1) {
+        bands_courier<K>(log, prog, seg, band, nb, n, log_steps, gcount, glog, spin_courier, err);
+        return;
+    }
+    const int lane = threadIdx.x & 63, p = lane & 3, rsub = lane >> 2;
+    const size_t img = (size_t)n * C * H * W;
+    const int img_bytes = (int)((size_t)C * H * W * sizeof(float));
+    if (wave == 2) {
+        // ---- fills the ring
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<void *>(reinterpret_cast<const void *>(in + img)), 0, img_bytes, 0x00020000);
+        bool lost = false;
+        u32x4_t s0[4 * C], s1[4 * C], s2[4 * C];
+        auto issue = [&](int m, u32x4_t(&regs)[4 * C]) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = 16 * i + rsub, q = m - ring_rho(row);
+#pragma unroll
+                for (int ch = 0; ch < C; ++ch)
+                    regs[i * C + ch] = __builtin_amdgcn_raw_buffer_load_b128(
+                        rs, ring_item_offset<C, DIR>(ch, row, q, p, band, band_rows, H, W, false), 0, 0);
+            }
+        };
+        auto land = [&](int m, u32x4_t(&regs)[4 * C]) {
+            if (m >= nblocks)
+                return;
+            // the slots of this block were last read by store block m - 3
+            if (!lost && m >= 3 && !wait_count(io_stored, m - 2, spin_limit)) {
+                lost = true;
+                __hip_atomic_store(io_lost, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (err && lane == 0)
+                    __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = 16 * i + rsub, q = m - ring_rho(row), cs0 = 16 * q + 4 * p;
+                if (q >= 0 && cs0 < W) {
+#pragma unroll
+                    for (int ch = 0; ch < C; ++ch) {
+                        f32x4 v = __builtin_bit_cast(f32x4, regs[i * C + ch]);
+                        if (DIR)
+                            v = f32x4{v[3], v[2], v[1], v[0]};
+                        if (lost)
+                            v = f32x4{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), __builtin_nanf("")};
+                        *reinterpret_cast<f32x4 *>(ring + (ch * 64 + row) * kRingStride + (cs0 & (kRingCols - 1))) = v;
+                    }
+                }
+            }
+            __hip_atomic_store(io_loaded, m + 2, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        };
+        // blocks -1 .. nblocks - 1 (block -1 carries the first chunk of row 0, whose rho is -1)
+        issue(-1, s0);
+        issue(0, s1);
+        for (int m = -1; m < nblocks; m += 3) {
+            issue(m + 2, s2);
+            land(m, s0);
+            issue(m + 3, s0);
+            land(m + 1, s1);
+            issue(m + 4, s1);
+            land(m + 2, s2);
+        }
+        return;
+    }
+    // ---- drains the ring
+    const __amdgpu_buffer_rsrc_t rd =
+        __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(out + img), 0, img_bytes, 0x00020000);
+    bool lost = false;
+    const int nstore = (W + 15) / 16 + 4;      // the last chunk of the last row leaves with store block W/16 + 3
+    for (int m = 0; m < nstore; ++m) {
+        const int need = m + 1 < nblocks ? m + 1 : nblocks;
+        if (!lost && !wait_count(io_done, need, spin_limit)) {
+            lost = true;
+            if (err && lane == 0)
+                __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        f32x4 v[4 * C];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = 16 * i + rsub, q = m - ring_rho(row) - 1, cs0 = 16 * q + 4 * p;
+#pragma unroll
+            for (int ch = 0; ch < C; ++ch)
+                v[i * C + ch] =
+                    *reinterpret_cast<const f32x4 *>(ring + (ch * 64 + row) * kRingStride + (cs0 & (kRingCols - 1)));
+        }
+        // a wave that ran on after a lost wait no longer keeps to the schedule of the ring: nothing read from
+        // now on is known to be a result (the flag was set before the counter that let this block through)
+        lost = lost || __hip_atomic_load(io_lost, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != 0;
+        // (the release waits for the reads above to have returned)
+        __hip_atomic_store(io_stored, m + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = 16 * i + rsub, q = m - ring_rho(row) - 1;
+#pragma unroll
+            for (int ch = 0; ch < C; ++ch) {
+                f32x4 e = v[i * C + ch];
+                if (DIR)
+                    e = f32x4{e[3], e[2], e[1], e[0]};
+                if (lost)
+                    e = f32x4{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), __builtin_nanf("")};
+                __builtin_amdgcn_raw_buffer_store_b128(
+                    __builtin_bit_cast(u32x4_t, e), rd,
+                    ring_item_offset<C, DIR>(ch, row, q, p, band, band_rows, H, W, true), 0, 0);
+            }
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -798,18 +996,39 @@ static size_t wave_bands_multi_ws_per_image(int H, int W, int k)
     return (nb - 1) * ((size_t)wave_bands_log_steps(W) * (k - 1) * sizeof(f32x4) + 256);
 }
 
+static bool wave_bands_single_fits(int H, int W, int k) { return wave_bands_lds_bytes(H, W, k) <= 128 * 1024; }
+static bool wave_bands_multi_strided_pays(int B, int H, int W)
+{
+    const int nb = (H + 63) / 64;
+    return nb >= 3 && W >= 128 && (long)B * nb <= 512;
+}
+
+static size_t wave_bands_io_lds_bytes(int C, int W, int k)
+{
+    return (2 * (size_t)wave_bands_log_steps(W) + 64) * (k - 1) * sizeof(f32x4) +
+           (size_t)C * 64 * kRingStride * sizeof(float) + 6 * sizeof(int);
+}
+
 template <int C, int K>
 static int launch_wave_bands_multi_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
                                       hipStream_t stream, SolveWs ws)
 {
     const int nb = (H + 63) / 64, log_steps = wave_bands_log_steps(W);
     const size_t seg = (size_t)log_steps * (K - 1);
-    const size_t lds = (2 * seg + 64 * (K - 1)) * sizeof(f32x4) + 2 * sizeof(int);
-    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave_bands_multi<C, K, 1>)
-                         : reinterpret_cast<const void *>(&k_solve_wave_bands_multi<C, K, 0>);
+    // rows through an LDS ring (whole-line memory traffic) where rows are made of 16-byte pieces
+    const size_t lds_io = wave_bands_io_lds_bytes(C, W, K);
+    const bool io = (W & 3) == 0 && lds_io <= kMaxLdsBytes &&
+                    ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+    if (!io && wave_bands_single_fits(H, W, K) && !wave_bands_multi_strided_pays(B, H, W))
+        return launch_wave_bands_ck<C, K>(dir, in, w, out, B, H, W, stream, ws.err);
+    const size_t lds = io ? lds_io : (2 * seg + 64 * (K - 1)) * sizeof(f32x4) + 2 * sizeof(int);
+    const void *fn = io ? (dir ? reinterpret_cast<const void *>(&k_solve_wave_bands_io<C, K, 1>)
+                               : reinterpret_cast<const void *>(&k_solve_wave_bands_io<C, K, 0>))
+                        : (dir ? reinterpret_cast<const void *>(&k_solve_wave_bands_multi<C, K, 1>)
+                               : reinterpret_cast<const void *>(&k_solve_wave_bands_multi<C, K, 0>));
     if (!ensure_dynamic_lds(fn, lds))
         return INVCONV_ERR_UNSUPPORTED;
-    const int resident = resident_workgroups(fn, 128, lds);
+    const int resident = resident_workgroups(fn, io ? 256 : 128, lds);
     int per_launch = resident / nb;                 // images per launch
     if (per_launch < 1)
         return launch_wave_bands_ck<C, K>(dir, in, w, out, B, H, W, stream, ws.err);
@@ -834,7 +1053,17 @@ static int launch_wave_bands_multi_ck(int dir, const float *in, const float *w, 
         const int cnt = nimg * (nb - 1);
         hipLaunchKernelGGL(k_wave_bands_clear, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, stream, gcount, cnt);
         const dim3 grid((unsigned)(nimg * nb));    // band-major: a band's workgroups come after those it waits for
-        if (dir)
+        if (io) {
+            const int spin_band = wait_budget(kBandSpinLimit);
+            if (dir)
+                hipLaunchKernelGGL((k_solve_wave_bands_io<C, K, 1>), grid, dim3(256), lds, stream, in + n0 * img, w,
+                                   out + n0 * img, nimg, H, W, log_steps, gcount, glog, spin_band, spin_courier,
+                                   ws.err);
+            else
+                hipLaunchKernelGGL((k_solve_wave_bands_io<C, K, 0>), grid, dim3(256), lds, stream, in + n0 * img, w,
+                                   out + n0 * img, nimg, H, W, log_steps, gcount, glog, spin_band, spin_courier,
+                                   ws.err);
+        } else if (dir)
             hipLaunchKernelGGL((k_solve_wave_bands_multi<C, K, 1>), grid, dim3(128), lds, stream, in + n0 * img, w,
                                out + n0 * img, nimg, H, W, log_steps, gcount, glog, spin_courier, ws.err);
         else
@@ -846,25 +1075,29 @@ static int launch_wave_bands_multi_ck(int dir, const float *in, const float *w, 
     return INVCONV_OK;
 }
 
-// Several compute units per image pay while there are compute units to spare and an image has at least
-// three bands of some width: the bands of an image are then limited by the address unit of the one compute
-// unit they share (0.49 us per step at 3x256x256 against 0.31 us here), while the hand-over through global
-// memory makes a band trail the one above by about 105 steps instead of 80 (measured, 3x256x256 forward:
-// B = 1 275 -> 198 us, B = 128 400 -> 339 us; two bands or narrow images are faster in one workgroup).
-// Images whose logs do not fit one workgroup's LDS (3x512x512) have only this way.
+// Several compute units per image.  With the solving wave reading its rows itself (k_solve_wave_bands_multi)
+// this pays while there are compute units to spare and an image has at least three bands of some width: the
+// bands of an image are then limited by the address unit of the one compute unit they share (0.49 us per
+// step at 3x256x256 against 0.31 us), while the hand-over through global memory makes a band trail the one
+// above by about 105 steps instead of 80.  With the rows passing through the LDS ring (k_solve_wave_bands_io,
+// rows of 16-byte pieces) it pays at every batch size from 64 columns on, since the memory instructions no
+// longer touch 64 lines each (measured forward + backward, ring against one workgroup per image:
+// 128 x 3x256x256 448 us against 868, 256 x 3x128x128 228 against 354, 1024 x 3x96x96 695 against 1725,
+// 256 x 3x128x64 179 against 190; 256 x 3x192x32 392 against 217, hence the lower limit on the width).
+// Images whose logs do not fit one workgroup's LDS (3x512x512) have only these two ways.
 static size_t wave_bands_multi_lds_bytes(int W, int k)
 {
     return (2 * (size_t)wave_bands_log_steps(W) + 64) * (k - 1) * sizeof(f32x4) + 2 * sizeof(int);
 }
-static bool wave_bands_single_fits(int H, int W, int k) { return wave_bands_lds_bytes(H, W, k) <= 128 * 1024; }
 static bool wave_bands_multi_preferred(int B, int H, int W, int k)
 {
     if (wave_bands_multi_lds_bytes(W, k) > kMaxLdsBytes)
         return false;
     if (!wave_bands_single_fits(H, W, k))
         return true;
-    const int nb = (H + 63) / 64;
-    return nb >= 3 && W >= 128 && (long)B * nb <= 512;
+    if ((W & 3) == 0 && W >= 64 && wave_bands_io_lds_bytes(4, W, k) <= kMaxLdsBytes)
+        return true;        // rows through the LDS ring (k_solve_wave_bands_io)
+    return wave_bands_multi_strided_pays(B, H, W);
 }
 
 // The four-wave split of the solve costs about a microsecond more before its first step and saves

@@ -106,13 +106,33 @@ struct WaveBands {
     f32x4 *scratch;     // [64][K - 1] write-only dump for the lanes that have nothing to send
     int spin_limit;     // polls of prog_in before a waiting band gives up
     int *err;           // device error word (may be null): set to 1 when a wait ran out
+    // RING only: the band's rows pass through an LDS ring that other waves of the workgroup fill and drain
+    float *ring;            // [C][64 rows][kRingStride], solve coordinates, column c at c % kRingCols
+    const int *io_loaded;   // load blocks in the ring, counted from block -1: block j may start at j + 2
+    int *io_done;           // blocks this wave has finished
+    int *io_lost;           // set when a wave of the workgroup gave up a wait: the draining wave then writes NaN
 };
+
+// Columns of a row the ring holds (four chunks of kWavePF columns), and the distance between rows.  Lane r
+// reads column t - r at step t: bank (r * kRingStride + t - r) % 64 = (3r + t) % 64, distinct over the lanes;
+// the 16-byte accesses of the filling and draining waves (16 rows, same columns) spread over all banks too.
+constexpr int kRingCols = 64;
+constexpr int kRingStride = 68;
+constexpr int kRingPF = 4;    // steps of read-ahead from the ring (an LDS round trip, not a memory one)
+
+// Row r of a band needs, in block j (steps 16j .. 16j+15, and the input of step 16j+16 for the look-ahead
+// of `own`), columns 16j-r .. 16j+16-r.  With rho(r) = floor((r-1)/16) these fall into chunks j-rho-1 and
+// j-rho, so the input of block j is complete once every row has chunk j-rho(r): "load block j".
+__device__ __forceinline__ int ring_rho(int r) { return (r - 1) >> 4; }
 
 // Body of the solve for image n, executed by one full wave (lanes 0..63 of the
 // calling workgroup).  With LDS_COPY the result is also written to lds_copy as a
 // [C][H][W] tile in image (not mirrored) coordinates.
 // With TILE the image lives in lds_copy (input on entry, result on return) and global memory is not touched.
-template <int C, int K, int DIR, bool LDS_COPY, bool BANDS = false, bool TILE = false>
+// With RING (bands only) input and result live in wb.ring: another wave has put the input of block j there
+// before io_loaded reaches j + 2, the result overwrites the input in place, and io_done tells the draining
+// wave which blocks are complete.  Global memory is not touched by this wave.
+template <int C, int K, int DIR, bool LDS_COPY, bool BANDS = false, bool TILE = false, bool RING = false>
 __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, const float *__restrict__ w,
                                                 float *__restrict__ out, int H, int W, int n, float *lds_copy,
                                                 WaveBands wb = WaveBands{})
@@ -140,15 +160,18 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
         const size_t cb = (size_t)(DIR ? C - 1 - ch : ch) * H * W;
         chan_src[ch] = reinterpret_cast<const char *>(in + img + cb);
         chan_dst[ch] = reinterpret_cast<char *>(out + img + cb);
-        chan_lds[ch] = reinterpret_cast<char *>(lds_copy + cb);
+        chan_lds[ch] = RING ? reinterpret_cast<char *>(wb.ring + ch * 64 * kRingStride)
+                            : reinterpret_cast<char *>(lds_copy + cb);
     }
+    constexpr int PF = RING ? kRingPF : kWavePF;      // slots of read-ahead
+    auto ring_off = [&](int step) -> unsigned { return (unsigned)((r * kRingStride + ((step - r) & (kRingCols - 1))) * 4); };
     constexpr int kStep = DIR ? -4 : 4;               // bytes per column in solve order
     const int row0 = 4 * (DIR ? (H - 1 - rr) * W + (W - 1) : rr * W);   // byte offset of column 0
     const int rowlo = DIR ? row0 - 4 * (W - 1) : row0;                   // lowest / highest byte offset
     const int rowhi = DIR ? row0 : row0 + 4 * (W - 1);                   // inside this row
     auto clamp_row = [&](int off) -> unsigned { return (unsigned)(off < rowlo ? rowlo : (off > rowhi ? rowhi : off)); };
     auto ld = [&](int ch, unsigned off) -> float {
-        return *reinterpret_cast<const float *>((TILE ? chan_lds[ch] : chan_src[ch]) + off);
+        return *reinterpret_cast<const float *>((TILE || RING ? chan_lds[ch] : chan_src[ch]) + off);
     };
     // A band whose bounded wait for the band above ran out has no valid input any more: from then on it
     // stores NaN instead of results, so that a lost hand-over can never pass for a solution.
@@ -156,9 +179,9 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
     auto st = [&](int ch, unsigned off, float v) {
         if (BANDS)
             v = lost ? __builtin_nanf("") : v;
-        if (!TILE)
+        if (!TILE && !RING)
             *reinterpret_cast<float *>(chan_dst[ch] + off) = v;
-        if (LDS_COPY || TILE)
+        if (LDS_COPY || TILE || RING)
             *reinterpret_cast<float *>(chan_lds[ch] + off) = v;
     };
 
@@ -167,17 +190,39 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
     // control-flow joins; out-of-range loads are zeroed when consumed.  Slot s holds
     // the input of the steps congruent to s.  The first batch is issued before the
     // weight preparation so that both latencies overlap.
-    float yb[kWavePF][C];
+    float yb[PF][C];
+    auto ring_wait = [&](int blocks) {
+        if (lost)
+            return;
+        int spins = 0;
+        while (__hip_atomic_load(wb.io_loaded, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < blocks &&
+               ++spins < wb.spin_limit)
+            __builtin_amdgcn_s_sleep(1);
+        if (__hip_atomic_load(wb.io_loaded, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < blocks) {
+            lost = true;
+            __hip_atomic_store(wb.io_lost, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (wb.err && r == 0)
+                __hip_atomic_store(wb.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    if (!RING) {
 #pragma unroll
-    for (int u = 0; u < kWavePF; ++u) {
-        const unsigned off = clamp_row(row0 + kStep * (u - r));
+        for (int u = 0; u < PF; ++u) {
+            const unsigned off = clamp_row(row0 + kStep * (u - r));
 #pragma unroll
-        for (int ch = 0; ch < C; ++ch)
-            yb[u][ch] = ld(ch, off);
+            for (int ch = 0; ch < C; ++ch)
+                yb[u][ch] = ld(ch, off);
+        }
     }
 
     float wA[K][K][C], wLi[C];
     wave_fold_regs<C, K, DIR>(w, o_lane, wA, wLi);
+    if (RING) {     // (the weight preparation has overlapped the filling wave's first loads)
+        ring_wait(2);
+#pragma unroll
+        for (int ch = 0; ch < C; ++ch)
+            yb[0][ch] = ld(ch, ring_off(0));
+    }
 
     float xh[C][K];      // xh[i][db] = x(r, c-db), db >= 1
     f32x4 T[K];          // T[a][o], a >= 1: message for pixel (r+a, c), negated sums
@@ -193,11 +238,13 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
 
     // Have every initial load landed before the loop, so that inside the loop the
     // compiler's wait counts only need to cover the loads of the loop itself.
+    if (!RING) {
 #pragma unroll
-    for (int u = 0; u < kWavePF; ++u)
+        for (int u = 0; u < PF; ++u)
 #pragma unroll
-        for (int ch = 0; ch < C; ++ch)
-            asm volatile("" : "+v"(yb[u][ch]));
+            for (int ch = 0; ch < C; ++ch)
+                asm volatile("" : "+v"(yb[u][ch]));
+    }
 
     // own = Linv y - (own-row taps), everything of the coming pixel that does not
     // depend on the rows above; prepared one step ahead.
@@ -209,11 +256,13 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
 #pragma unroll
         for (int j = 0; j < C; ++j)
             own = __builtin_amdgcn_mfma_f32_4x4x1f32(wLi[j], in_row ? yb[0][j] : 0.0f, own, 0, 0, 0);
-        const unsigned off = clamp_row(ldoff);
+        if (!RING) {
+            const unsigned off = clamp_row(ldoff);
 #pragma unroll
-        for (int ch = 0; ch < C; ++ch)
-            yb[0][ch] = ld(ch, off);
-        ldoff += kStep;
+            for (int ch = 0; ch < C; ++ch)
+                yb[0][ch] = ld(ch, off);
+            ldoff += kStep;
+        }
     }
 
     const int band_rows = BANDS ? (H - 64 * wb.band < 64 ? H - 64 * wb.band : 64) : H;
@@ -241,6 +290,19 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
                     __hip_atomic_store(wb.err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
+        if (RING) {
+            // the input of this block is in the ring: fetch that of steps t0+1 .. t0+PF (the read-ahead
+            // never crosses into the next block's input)
+            if (t0 > 0)
+                ring_wait(t0 / kWavePF + 2);
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const unsigned off = ring_off(t0 + 1 + u);
+#pragma unroll
+                for (int ch = 0; ch < C; ++ch)
+                    yb[(1 + u) % PF][ch] = ld(ch, off);
+            }
+        }
         // Entry of the first step now, the others one step ahead of their use (volatile: the read is
         // issued where it is written, well before the value is needed).
         f32x4 Mn[K];
@@ -265,7 +327,7 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
             for (int o = 0; o < C; ++o)
                 xn[o] = own[o] + (BANDS ? from_lane_above_or(M[1][o], T[1][o]) : from_lane_above(T[1][o]));
             if ((unsigned)c < Wst) {
-                const unsigned off = (unsigned)(row0 + kStep * c);
+                const unsigned off = RING ? ring_off(t0 + u) : (unsigned)(row0 + kStep * c);
 #pragma unroll
                 for (int o = 0; o < C; ++o)
                     st(o, off, xn[o]);
@@ -310,7 +372,7 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
                     xh[i][db] = xh[i][db - 1];
             c += 1;
             {
-                const int s = (u + 1) % kWavePF;     // slot of the next step (static after unrolling)
+                const int s = (u + 1) % PF;     // slot of the next step (static after unrolling)
                 const bool in_row = (unsigned)c < (unsigned)W;
                 f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -322,14 +384,23 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
                     for (int i = 0; i < C; ++i)
                         acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[0][db][i], xh[i][db], acc, 0, 0, 0);
                 own = acc;
-                // refill the slot with the input kWavePF steps later
-                const unsigned off = clamp_row(ldoff);
+                // refill the slot with the input PF steps later
+                if (!RING) {
+                    const unsigned off = clamp_row(ldoff);
 #pragma unroll
-                for (int ch = 0; ch < C; ++ch)
-                    yb[s][ch] = ld(ch, off);
-                ldoff += kStep;
+                    for (int ch = 0; ch < C; ++ch)
+                        yb[s][ch] = ld(ch, off);
+                    ldoff += kStep;
+                } else if (u + 1 + PF <= kWavePF) {
+                    const unsigned off = ring_off(t0 + u + 1 + PF);
+#pragma unroll
+                    for (int ch = 0; ch < C; ++ch)
+                        yb[s][ch] = ld(ch, off);
+                }
             }
         }
+        if (RING)       // the block's results are in the ring
+            __hip_atomic_store(wb.io_done, t0 / kWavePF + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
         if (send)       // the block's log entries are written (LDS operations of a wave complete in order)
             __hip_atomic_store(wb.prog_out, t0 + kWavePF, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
     }

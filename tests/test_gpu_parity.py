@@ -151,7 +151,10 @@ def test_bands_on_many_compute_units_at_full_occupancy():
     assert rel_err(host(dw), dwr) <= TOL_DW
 
 
-TALL_SHAPES = [(2, 3, 256, 160, 3), (1, 3, 512, 512, 3), (5, 2, 257, 129, 3), (2, 3, 200, 130, 5), (1, 3, 130, 40, 5)]
+TALL_SHAPES = [(2, 3, 256, 160, 3), (1, 3, 512, 512, 3), (5, 2, 257, 129, 3), (2, 3, 200, 130, 5), (1, 3, 130, 40, 5),
+               # rows through the LDS ring (W a multiple of 4): ragged last chunk, ragged last band, every C, k = 2, 5
+               (3, 3, 200, 132, 3), (2, 1, 193, 140, 3), (1, 4, 256, 128, 3), (2, 3, 192, 144, 5), (2, 2, 130, 128, 2),
+               (1, 3, 129, 256, 3), (70, 3, 256, 128, 3)]
 
 
 @pytest.mark.parametrize("shape", TALL_SHAPES)
@@ -479,29 +482,44 @@ def test_error_word_stays_clear_and_is_set_when_a_wait_gives_up():
     wd = [dev(cs["w"][0]) for cs in cases]
     yd = dev(cases[0]["y"])
     need = b.chain_workspace_bytes(L, B, C, H, W, k)
-    tall = inputs.make_case(2, 3, 256, 160, 3, seed=41, tap_std=0.05)
-    ty, tw = dev(tall["y"]), dev(tall["w"][0])
-    tneed = b.fwd_workspace_bytes(2, 3, 256, 160, 3)
+    # tall images: rows of 158 floats are read by the solving wave itself, rows of 160 pass through the LDS
+    # ring that a second wave fills (so there even the top band has somebody to wait for)
+    talls = []
+    for TW in (158, 160):
+        tall = inputs.make_case(2, 3, 256, TW, 3, seed=41, tap_std=0.05)
+        talls.append((dev(tall["y"]), dev(tall["w"][0]), b.fwd_workspace_bytes(2, 3, 256, TW, 3)))
     # normal operation
-    wsp, tws = b.new_workspace(need), b.new_workspace(tneed)
+    wsp = b.new_workspace(need)
     xs = b.invconv_chain_fwd(yd, wd, workspace=wsp)
-    tx = b.invconv_fwd(ty, tw, workspace=tws)
-    torch.cuda.synchronize()
-    assert b.workspace_error(wsp) == 0 and b.workspace_error(tws) == 0
+    txs = []
+    for ty, tw, tneed in talls:
+        tws = b.new_workspace(tneed)
+        txs.append(b.invconv_fwd(ty, tw, workspace=tws))
+        torch.cuda.synchronize()
+        assert b.workspace_error(tws) == 0
+    assert b.workspace_error(wsp) == 0
     try:
         b.set_wait_budget(1)
-        wsp2, tws2 = b.new_workspace(need), b.new_workspace(tneed)
+        wsp2 = b.new_workspace(need)
         xs2 = b.invconv_chain_fwd(yd, wd, workspace=wsp2)
-        tx2 = b.invconv_fwd(ty, tw, workspace=tws2)
-        tx3 = b.invconv_fwd(ty, tw)                 # no workspace: no error word, but NaN all the same
+        lost = []
+        for ty, tw, tneed in talls:
+            tws2 = b.new_workspace(tneed)
+            tx2 = b.invconv_fwd(ty, tw, workspace=tws2)
+            tx3 = b.invconv_fwd(ty, tw)             # no workspace: no error word, but NaN all the same
+            lost.append((tws2, tx2, tx3))
         torch.cuda.synchronize()
     finally:
         b.set_wait_budget(0)
-    assert b.workspace_error(wsp2) == 1 and b.workspace_error(tws2) == 1
+    assert b.workspace_error(wsp2) == 1
     assert torch.equal(xs2[0], xs[0])               # the first layer waits for nobody
     assert bool(torch.isnan(xs2[-1]).any())
-    assert torch.equal(tx2[:, :, :64], tx[:, :, :64])       # the top band waits for nobody
-    assert bool(torch.isnan(tx2[:, :, 64:]).any()) and bool(torch.isnan(tx3[:, :, 64:]).any())
+    for i, (tws2, tx2, tx3) in enumerate(lost):
+        assert b.workspace_error(tws2) == 1
+        assert bool(torch.isnan(tx2[:, :, 64:]).any()) and bool(torch.isnan(tx3[:, :, 64:]).any())
+        ok = ~torch.isnan(tx2)                      # whatever is not NaN is the right number
+        assert torch.equal(tx2[ok], txs[i][ok])
+    assert torch.equal(lost[0][1][:, :, :64], txs[0][:, :, :64])     # W = 158: the top band waits for nobody
     # the word is sticky until the caller clears the header; a fresh run on a cleared header is clean
     wsp2[:256].zero_()
     xs3 = b.invconv_chain_fwd(yd, wd, workspace=wsp2)
