@@ -555,7 +555,11 @@ __global__ __launch_bounds__(256) void k_solve_wave_bands_io(const float *__rest
     float *ring = reinterpret_cast<float *>(scratch + 64 * (K - 1));    // [C][64][kRingStride]
     int *prog = reinterpret_cast<int *>(ring + C * 64 * kRingStride);    // received, sent, loaded, done, stored, lost
     if (threadIdx.x < 6)
-        prog[threadIdx.x] = 0;
+        prog[threadIdx.x] = (threadIdx.x == 0 && band == 0) ? log_steps : 0;
+    if (band == 0) {    // nothing comes from above the first band: its incoming log is zeros, already complete
+        for (int i = threadIdx.x; i < (int)seg; i += 256)
+            log[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
     __syncthreads();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int band_rows = H - 64 * band < 64 ? H - 64 * band : 64;
@@ -577,7 +581,7 @@ __global__ __launch_bounds__(256) void k_solve_wave_bands_io(const float *__rest
         wb.io_loaded = io_loaded;
         wb.io_done = io_done;
         wb.io_lost = io_lost;
-        solve_wave_body<C, K, DIR, false, true, false, true>(in, w, out, H, W, n, nullptr, wb);
+        solve_wave_ring_body<C, K, DIR>(w, H, W, wb);
         return;
     }
     if (wave == 1) {

@@ -139,7 +139,8 @@ def test_bands_on_many_compute_units_at_full_occupancy():
     x1 = b.invconv_fwd(yd, wd)                   # all bands of an image in one workgroup
     torch.cuda.synchronize()
     assert b.workspace_error(ws_f) == 0 and b.workspace_error(ws_b) == 0
-    assert torch.equal(x, x1)
+    # (the kernel whose rows pass through LDS adds the terms of a pixel in another order: close, not equal)
+    assert rel_err(host(x), host(x1)) <= 1e-5
     xh, vh = host(x), host(v)
     xr = oracle.invconv_fwd(y, w, THREADS)
     print("oracle fwd done", flush=True)
@@ -175,7 +176,10 @@ def test_tall_images_with_and_without_workspace_agree(shape):
     xr = oracle.invconv_fwd(cs["y"], cs["w"][0], THREADS)
     assert rel_err(host(x_ws), xr) <= TOL_ACT and rel_err(host(x_plain), xr) <= TOL_ACT
     if H * W < 512 * 512:
-        assert torch.equal(x_ws, x_plain)
+        if W % 4 == 0 and W >= 64:      # rows through the LDS ring: the terms of a pixel are added in another order
+            assert rel_err(host(x_ws), host(x_plain)) <= 1e-5
+        else:
+            assert torch.equal(x_ws, x_plain)
     # a workspace of the bare header is enough for any shape: it only changes which kernel runs
     tiny = b.new_workspace(0)
     if b.fwd_workspace_bytes(B, C, H, W, k) > 256:
