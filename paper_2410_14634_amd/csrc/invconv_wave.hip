@@ -23,6 +23,7 @@
 #include "invconv_launch.h"
 #include "invconv_wave_solve.h"
 #include <type_traits>
+#include <utility>
 
 namespace invconv {
 
@@ -119,16 +120,17 @@ __global__ __launch_bounds__(64) void k_solve_wave_tile(const ST *__restrict__ i
 }
 
 // ---------------------------------------------------------------------------
-// The same solve with the matrix instructions of a step split over the four waves of a workgroup by
-// the age of their input (images of at most 64 rows; pays when a step is long, i.e. k = 5).  With
+// The same solve with the matrix instructions of a step split over the waves of a workgroup by the age of
+// their input (images of at most 64 rows; pays when a step is long; four waves up to k = 5, k/2 + 2.5 waves
+// beyond).  With
 // x_s the diagonal solved at step s and A[a][db] the folded taps (lane = row, as above),
 //   T[a]_s    = up(T[a+1]_{s-1}) + A[a][0] x_s + { sum_{db>=1} A[a][db] x_{s-db} }   = Tp[a]_s + F[a]_s
 //   own_{s+1} =                    A[0][1] x_s + { Linv y_{s+1} + sum_{db>=2} A[0][db] x_{s+1-db} }
 //                                                                                    = ownp_s + O_{s+1}
 //   x_{s+1}   = own_{s+1} + up(T[1]_s)
 // The braces need nothing newer than x_{s-1}.  Wave 0, on the chain of dependent steps, publishes x_s
-// through LDS and forms Tp and ownp (K*C instructions); during step s waves 1 and 2 form the F[a]_s,
-// wave 3 forms O_{s+1}, reads y and writes x_{s-1} to global memory; wave 0 picks the results up
+// through LDS and forms Tp and ownp (K*C instructions); during step s waves 1 .. NF form the F[a]_s, the
+// last wave forms O_{s+1}, reads y and writes x_{s-1} to global memory; wave 0 picks the results up
 // after the barrier that ends the step.  Every wave runs its own loop over the same number of steps.
 // ---------------------------------------------------------------------------
 struct WaveSplitLds {
@@ -139,7 +141,19 @@ struct WaveSplitLds {
 template <int C, int K>
 __host__ __device__ constexpr size_t wave_split_lds_floats() { return 2 * C * 64 + 2 * K * 64 * 4; }
 
-template <int C, int K, int DIR, bool LDS_COPY>
+// NF waves share the F[a] (wave f = 1 .. NF takes (K-1)/NF consecutive a; two waves for k <= 5, one per two a
+// from k = 7 on, so that no wave has more than 2 (K-1) C matrix instructions in a step); wave NF + 1 forms O.
+// Every role folds the weights for itself after the set-up barrier, so that only the taps it uses stay in
+// registers (all C K K folded taps of k = 11 are more than a wave of a large workgroup may hold).
+__host__ __device__ constexpr int wave_split_nf(int K) { return K >= 7 ? (K - 1) / 2 : 2; }
+
+template <class F, int... Is>
+__device__ __forceinline__ void wave_split_dispatch(int wave, F &&f, std::integer_sequence<int, Is...>)
+{
+    ((wave == Is + 1 ? (f(std::integral_constant<int, Is>{}), 0) : 0), ...);
+}
+
+template <int C, int K, int DIR, bool LDS_COPY, int NF = 2>
 __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ in, const float *__restrict__ w,
                                                       float *__restrict__ out, int H, int W, int n, float *lds_copy,
                                                       WaveSplitLds sl)
@@ -170,21 +184,19 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
     const int rowhi = DIR ? row0 : row0 + 4 * (W - 1);
     auto clamp_row = [&](int off) -> unsigned { return (unsigned)(off < rowlo ? rowlo : (off > rowhi ? rowhi : off)); };
 
-    // wave 3 reads y: slot u holds the input of the steps congruent to u.  The other waves run the same
+    // the last wave reads y: slot u holds the input of the steps congruent to u.  The other waves run the same
     // instructions on one common address (no branch around a load, next to no work for the address unit).
+    constexpr int kOWave = NF + 1;
     float yb[kWavePF][C];
 #pragma unroll
     for (int u = 0; u < kWavePF; ++u) {
-        const unsigned off = wave == 3 ? clamp_row(row0 + kStep * (u - r)) : 0u;
+        const unsigned off = wave == kOWave ? clamp_row(row0 + kStep * (u - r)) : 0u;
 #pragma unroll
         for (int ch = 0; ch < C; ++ch)
-            yb[u][ch] = *reinterpret_cast<const float *>((wave == 3 ? chan_src[ch] : chan_src[0]) + off);
+            yb[u][ch] = *reinterpret_cast<const float *>((wave == kOWave ? chan_src[ch] : chan_src[0]) + off);
     }
 
-    float wA[K][K][C], wLi[C];
-    wave_fold_regs<C, K, DIR>(w, o_lane, wA, wLi);
-
-    for (int idx = threadIdx.x; idx < (int)wave_split_lds_floats<C, K>(); idx += 256)
+    for (int idx = threadIdx.x; idx < (int)wave_split_lds_floats<C, K>(); idx += 64 * (NF + 2))
         sl.x[idx] = 0.0f;       // x and message slots are contiguous
 #pragma unroll
     for (int u = 0; u < kWavePF; ++u)
@@ -193,25 +205,29 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
             asm volatile("" : "+v"(yb[u][ch]));
     __syncthreads();
 
-    // step s = -1 only lets wave 3 prepare O_0 = Linv y_0; the steps after the last diagonal only let it store
+    // step s = -1 only lets the last wave prepare O_0 = Linv y_0; the steps after the last diagonal only let it store
     const int nsteps = H + W - 1;
     const int total = nsteps + 2;       // steps -1 .. total-2, the same for every wave
     if (wave == 0) {
+        float wA[K][K][C], wLi[C];
+        wave_fold_regs<C, K, DIR>(w, o_lane, wA, wLi);
         f32x4 Tp[K], ownp = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int a = 0; a < K; ++a)
             Tp[a] = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int s = -1; s < total - 1; ++s) {
+            // The F[a] arrive already shifted by one lane (their waves have the time for it), so
+            // up(T[a]) = up(Tp[a]) + up(F[a]) is one add whose first operand takes the lane shift along.
             const f32x4 *mi = sl.m + ((s - 1) & 1) * K * 64 + lane;
-            f32x4 T[K];
+            f32x4 Fs[K];
 #pragma unroll
             for (int a = 1; a < K; ++a)
-                T[a] = Tp[a] + mi[a * 64];
+                Fs[a] = mi[a * 64];
             const f32x4 own = ownp + mi[0];
             float xn[C];
 #pragma unroll
             for (int o = 0; o < C; ++o) {
-                xn[o] = own[o] + from_lane_above(T[1][o]);
+                xn[o] = own[o] + (from_lane_above(Tp[1][o]) + Fs[1][o]);
                 sl.x[((s & 1) * C + o) * 64 + lane] = xn[o];
             }
 #pragma unroll
@@ -220,7 +236,7 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
                 if (a + 1 < K) {
 #pragma unroll
                     for (int o = 0; o < C; ++o)
-                        acc[o] = from_lane_above(T[a + 1][o]);
+                        acc[o] = from_lane_above(Tp[a + 1][o]) + Fs[a + 1][o];
                 }
 #pragma unroll
                 for (int i = 0; i < C; ++i)
@@ -236,41 +252,53 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
             }
             __syncthreads();
         }
-    } else if (wave == 1 || wave == 2) {
-        // F[a]_s = sum_{db>=1} A[a][db] x_{s-db}: wave 1 takes a = 1 .. (K-1)/2, wave 2 the rest
-        constexpr int A_SPLIT = (K - 1) / 2 + 1;
-        float xo[K][C];     // xo[db] = x_{s-db}, db >= 1
+    } else if (wave <= NF) {
+        // F[a]_s = sum_{db>=1} A[a][db] x_{s-db} for the wave's own a (fixed at compile time per wave)
+        constexpr int PER = (K - 1 + NF - 1) / NF;
+        auto f_loop = [&](auto tag) {
+            constexpr int A_LO = decltype(tag)::value * PER + 1;
+            float wA[K][K][C], wLi[C];
+            wave_fold_regs<C, K, DIR>(w, o_lane, wA, wLi);
+            float xo[K][C];     // xo[db] = x_{s-db}, db >= 1
 #pragma unroll
-        for (int db = 0; db < K; ++db)
-#pragma unroll
-            for (int i = 0; i < C; ++i)
-                xo[db][i] = 0.0f;
-        for (int s = -1; s < total - 1; ++s) {
-#pragma unroll
-            for (int db = K - 1; db >= 2; --db)
+            for (int db = 0; db < K; ++db)
 #pragma unroll
                 for (int i = 0; i < C; ++i)
-                    xo[db][i] = xo[db - 1][i];
+                    xo[db][i] = 0.0f;
+            for (int s = -1; s < total - 1; ++s) {
 #pragma unroll
-            for (int i = 0; i < C; ++i)
-                xo[1][i] = sl.x[(((s - 1) & 1) * C + i) * 64 + lane];
-            f32x4 *mo = sl.m + (s & 1) * K * 64 + lane;
-#pragma unroll
-            for (int a = 1; a < K; ++a) {
-                if ((a < A_SPLIT) != (wave == 1))
-                    continue;
-                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int db = K - 1; db >= 1; --db)
+                for (int db = K - 1; db >= 2; --db)
 #pragma unroll
                     for (int i = 0; i < C; ++i)
-                        acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[a][db][i], xo[db][i], acc, 0, 0, 0);
-                mo[a * 64] = acc;
+                        xo[db][i] = xo[db - 1][i];
+#pragma unroll
+                for (int i = 0; i < C; ++i)
+                    xo[1][i] = sl.x[(((s - 1) & 1) * C + i) * 64 + lane];
+                f32x4 *mo = sl.m + (s & 1) * K * 64 + lane;
+#pragma unroll
+                for (int a = A_LO; a < A_LO + PER; ++a) {
+                    if (a >= K)
+                        continue;
+                    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int db = K - 1; db >= 1; --db)
+#pragma unroll
+                        for (int i = 0; i < C; ++i)
+                            acc = __builtin_amdgcn_mfma_f32_4x4x1f32(wA[a][db][i], xo[db][i], acc, 0, 0, 0);
+                    f32x4 up = f32x4{0.f, 0.f, 0.f, 0.f};      // what the row below will add: F[a] of the lane above
+#pragma unroll
+                    for (int o = 0; o < C; ++o)
+                        up[o] = from_lane_above(acc[o]);
+                    mo[a * 64] = up;
+                }
+                __syncthreads();
             }
-            __syncthreads();
-        }
+        };
+        wave_split_dispatch(wave, f_loop, std::make_integer_sequence<int, NF>{});
     } else {
         // O_{s+1} = Linv y_{s+1} + sum_{db>=2} A[0][db] x_{s+1-db}; also x_{s-1} to global memory
+        float wA[K][K][C], wLi[C];
+        wave_fold_regs<C, K, DIR>(w, o_lane, wA, wLi);
         float xo[K][C];     // xo[db] = x_{s+1-db}, db >= 2
 #pragma unroll
         for (int db = 0; db < K; ++db)
@@ -335,8 +363,10 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
 }
 
 template <int C, int K, int DIR>
-__global__ __launch_bounds__(256) void k_solve_wave_split(const float *__restrict__ in, const float *__restrict__ w,
-                                                         float *__restrict__ out, int H, int W, float *logdet)
+__global__ __launch_bounds__(64 * (wave_split_nf(K) + 2)) void k_solve_wave_split(const float *__restrict__ in,
+                                                                                  const float *__restrict__ w,
+                                                                                  float *__restrict__ out, int H,
+                                                                                  int W, float *logdet)
 {
     __shared__ __attribute__((aligned(16))) float smem[wave_split_lds_floats<C, K>()];
     if (logdet && blockIdx.x == 0 && (threadIdx.x >> 6) == 1)      // wave 1 has the least to set up
@@ -344,7 +374,7 @@ __global__ __launch_bounds__(256) void k_solve_wave_split(const float *__restric
     WaveSplitLds sl;
     sl.x = smem;
     sl.m = reinterpret_cast<f32x4 *>(smem + 2 * C * 64);
-    solve_wave_split_body<C, K, DIR, false>(in, w, out, H, W, blockIdx.x, nullptr, sl);
+    solve_wave_split_body<C, K, DIR, false, wave_split_nf(K)>(in, w, out, H, W, blockIdx.x, nullptr, sl);
 }
 
 // Images of 65 .. 512 rows: one workgroup per image, one wave per band of 64 rows.
@@ -1332,14 +1362,15 @@ template <int C, int K>
 static int launch_wave_split_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
                                 hipStream_t stream, float *logdet)
 {
+    const dim3 block(64 * (wave_split_nf(K) + 2));
     if (dir)
-        hipLaunchKernelGGL((k_solve_wave_split<C, K, 1>), dim3(B), dim3(256), 0, stream, in, w, out, H, W, logdet);
+        hipLaunchKernelGGL((k_solve_wave_split<C, K, 1>), dim3(B), block, 0, stream, in, w, out, H, W, logdet);
     else
-        hipLaunchKernelGGL((k_solve_wave_split<C, K, 0>), dim3(B), dim3(256), 0, stream, in, w, out, H, W, logdet);
+        hipLaunchKernelGGL((k_solve_wave_split<C, K, 0>), dim3(B), block, 0, stream, in, w, out, H, W, logdet);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
-// Same shapes as the single-wave kernel; four waves per image.
+// Same shapes as the single-wave kernel; four to seven waves per image.
 int launch_solve_wave_split(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                             hipStream_t stream, float *logdet)
 {
