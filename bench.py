@@ -259,7 +259,7 @@ def chain_roofline(torch, L, stream, reps):
     macs = L.C * (L.k * L.k - 1) + (L.C - 1) / 2.0
     flops = 2.0 * macs * n
     alg_bytes = 8.0 * n
-    traffic = counter_traffic_bytes("hbm_counters_workload4_chain.txt", "k_chain_band<3, 3, 0>", "max_KiB")
+    traffic = counter_traffic_bytes("hbm_counters_workload4_chain.txt", "k_chain_band<3, 3, 0", "max_KiB")
     tf = flops / (ms_f * 1e-3) / 1e12
     gbs = alg_bytes / (ms_f * 1e-3) / 1e9
     return dict(bound="mfma", achieved=tf, peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s", frac=tf / FP32_VECTOR_PEAK_TFLOPS,
