@@ -28,6 +28,108 @@ constexpr int kWideRing = 2 * kWideK - 1;
 
 __host__ __device__ constexpr int wide_out_blocks(int C) { return (C + 15) / 16; }
 
+// Weight preparation of a workgroup: sWt[tap][out (padded to whole blocks of 16)][in, row stride C + 1] = Linv for
+// tap 0 and -Linv W_tap for the others, from oriented, masked kernel entries read straight from global memory.
+// scratch: 3 C C floats.  Ends with a barrier.
+template <int CQ, int DIR>
+__device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, float *sWt, float *scratch)
+{
+    constexpr int C = 4 * CQ, K = kWideK, NT = K * K;
+    constexpr int OB = wide_out_blocks(C), OR = 16 * OB, CPAD = C + 1;
+    float *sL = scratch, *sLinv = scratch + C * C, *sTap = scratch + 2 * C * C;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    auto entry = [&](int tp, int o, int i) -> float {
+        const int a = K - 1 - tp / K, b = K - 1 - tp % K;
+        const int oo = DIR ? C - 1 - i : o, ii = DIR ? C - 1 - o : i;
+        const float v = w[((oo * C + ii) * K + a) * K + b];
+        return (tp == 0 && ii > oo) ? 0.0f : v;
+    };
+    for (int idx = tid; idx < C * C; idx += nt)
+        sL[idx] = entry(0, idx / C, idx % C);
+    __syncthreads();
+    // Inverse of the lower-triangular block, column j by thread j, the column in registers: every thread runs
+    // the same fully unrolled substitution (entries above the diagonal are zeros that take part in the sums),
+    // the matrix entries are the same address for all lanes, and no result travels through LDS on the way.
+    if (tid < 64) {
+        const int j = tid < C ? tid : C - 1;
+        float col[C];
+#pragma unroll
+        for (int o = 0; o < C; ++o) {
+            float sum = 0.0f;
+#pragma unroll
+            for (int m = 0; m < o; ++m)
+                sum += sL[o * C + m] * col[m];
+            const float rd = 1.0f / sL[o * C + o];
+            col[o] = o < j ? 0.0f : (o == j ? rd : -sum * rd);
+        }
+        if (tid < C) {
+#pragma unroll
+            for (int o = 0; o < C; ++o)
+                sLinv[o * C + j] = col[o];
+        }
+    }
+    __syncthreads();
+    // The oriented entries of a tap are fetched one tap ahead into registers, so that no global-memory round trip
+    // lies between two taps, and the product Linv W_tap is formed four input channels at a time (one read of
+    // Linv[o][j] and one 16-byte read of W_tap[j][i .. i+3] for four multiply-adds).
+    constexpr int NPT = (C * C + 127) / 128;        // entries per thread: a workgroup has at least two waves
+    float pre[NPT];
+    auto fetch = [&](int tp) {
+#pragma unroll
+        for (int q = 0; q < NPT; ++q) {
+            const int idx = tid + q * nt;
+            pre[q] = idx < C * C ? entry(tp, idx / C, idx % C) : 0.0f;
+        }
+    };
+    fetch(1);
+    for (int tp = 0; tp < NT; ++tp) {
+        if (tp > 0) {
+#pragma unroll
+            for (int q = 0; q < NPT; ++q) {
+                const int idx = tid + q * nt;
+                if (idx < C * C)
+                    sTap[idx] = pre[q];
+            }
+            __syncthreads();
+        }
+        if (tp + 1 < NT)
+            fetch(tp + 1);
+        for (int it = tid; it < OR * CQ; it += nt) {
+            const int o = it / CQ, i0 = 4 * (it % CQ);
+            f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (o < C) {
+                if (tp == 0) {
+                    v = *reinterpret_cast<const f32x4 *>(sLinv + o * C + i0);
+                } else {
+                    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                    // (rows of Linv are zero beyond the diagonal, so whole groups of eight terms can be
+                    // summed: the reads of a group are issued together)
+                    const int jend = (o + 8) & ~7;
+                    for (int j0 = 0; j0 < jend && j0 < C; j0 += 8) {
+                        float l[8];
+                        f32x4 tv[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const int j = j0 + e < C ? j0 + e : C - 1;
+                            l[e] = j0 + e < C ? sLinv[o * C + j] : 0.0f;
+                            tv[e] = *reinterpret_cast<const f32x4 *>(sTap + j * C + i0);
+                        }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            acc += l[e] * tv[e];
+                    }
+                    v = -acc;
+                }
+            }
+            float *dst = sWt + tp * OR * CPAD + o * CPAD + i0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                dst[e] = v[e];
+        }
+        __syncthreads();
+    }
+}
+
 template <int CQ, int DIR>
 __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ in, const float *__restrict__ w,
                                                     float *__restrict__ out, int H, int W, int NB)
@@ -38,59 +140,13 @@ __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ i
     const int HP = 16 * NB + K - 1;
     float *sWt = smem;                          // [NT][OR][CPAD]: tap 0 = Linv, the others = -Linv W_tap
     float *ring = sWt + NT * OR * CPAD;         // [R][HP][CPAD]
-    float *sL = ring, *sLinv = ring + C * C;    // folding scratch, dead before the ring is used
-    float *sTap = ring + 2 * C * C;             // one oriented tap block at a time
+    // (the ring's memory is the folding scratch first)
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int band = wave / OB, ob = wave % OB;
     const int n = lane & 15, g = lane >> 4;
 
-    // ---- weight preparation (oriented, masked kernel entries straight from global memory)
-    auto entry = [&](int tp, int o, int i) -> float {
-        const int a = K - 1 - tp / K, b = K - 1 - tp % K;
-        const int oo = DIR ? C - 1 - i : o, ii = DIR ? C - 1 - o : i;
-        const float v = w[((oo * C + ii) * K + a) * K + b];
-        return (tp == 0 && ii > oo) ? 0.0f : v;
-    };
-    for (int idx = tid; idx < C * C; idx += nt)
-        sL[idx] = entry(0, idx / C, idx % C);
-    __syncthreads();
-    if (tid < C) {
-        const int j = tid;
-        for (int o = 0; o < j; ++o)
-            sLinv[o * C + j] = 0.0f;
-        sLinv[j * C + j] = 1.0f / sL[j * C + j];
-        for (int o = j + 1; o < C; ++o) {
-            float s = 0.0f;
-            for (int m = j; m < o; ++m)
-                s += sL[o * C + m] * sLinv[m * C + j];
-            sLinv[o * C + j] = -s / sL[o * C + o];
-        }
-    }
-    __syncthreads();
-    for (int tp = 0; tp < NT; ++tp) {
-        if (tp > 0) {
-            for (int idx = tid; idx < C * C; idx += nt)
-                sTap[idx] = entry(tp, idx / C, idx % C);
-            __syncthreads();
-        }
-        for (int idx = tid; idx < OR * CPAD; idx += nt) {
-            const int i = idx % CPAD, o = idx / CPAD;
-            float v = 0.0f;
-            if (o < C && i < C) {
-                if (tp == 0) {
-                    v = sLinv[o * C + i];
-                } else {
-                    float s = 0.0f;
-                    for (int j = 0; j <= o; ++j)
-                        s += sLinv[o * C + j] * sTap[j * C + i];
-                    v = -s;
-                }
-            }
-            sWt[tp * OR * CPAD + idx] = v;
-        }
-        __syncthreads();
-    }
+    wide_fold_weights<CQ, DIR>(w, sWt, ring);
     for (int idx = tid; idx < R * HP * CPAD; idx += nt)
         ring[idx] = 0.0f;
     __syncthreads();
@@ -155,6 +211,15 @@ __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ i
             __builtin_amdgcn_sched_barrier(0);
         }
         const f32x4 acc = acc0 + acc1;
+        // The next step's input is taken over BEFORE this step's global stores are issued: vector memory
+        // operations complete in order, so waiting for the loads behind the stores would wait for the stores'
+        // round trip in every step.
+#pragma unroll
+        for (int c4 = 0; c4 < CQ; ++c4) {
+            ycur[c4] = ynext[c4];
+            asm volatile("" : "+v"(ycur[c4]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
         const int c = t - r;
         const bool ok = row_ok && (unsigned)c < (unsigned)W;
         float *rp = ring + tm * HP * CPAD + (r + K - 1) * CPAD + o_first;
@@ -166,16 +231,244 @@ __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ i
                     out[gaddr(o_first + j, r, c)] = acc[j];
             }
         }
-#pragma unroll
-        for (int c4 = 0; c4 < CQ; ++c4)
-            ycur[c4] = ynext[c4];
         tm = tm + 1 == R ? 0 : tm + 1;
-        // workgroup barrier that orders LDS only: the global loads of the next step's input and this step's
-        // global stores stay in flight across it (a full __syncthreads() would wait for them at every step)
+        // workgroup barrier that orders LDS only: this step's global stores stay in flight across it (a full
+        // __syncthreads() would wait for them at every step)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
     }
+}
+
+// ---------------------------------------------------------------------------
+// The same solve for workgroups of at most eight waves (e.g. 48 channels on 32 rows: 2 bands x 3 blocks of
+// output channels), where a wave may hold its whole weight tile - 9 taps x C/4 A operands - in registers:
+//   * no weight is read from LDS inside the step loop (it was half of the LDS traffic);
+//   * the rings keep a pixel's channels permuted, channel 4 c4 + g at position g C/4 + c4, so that the C/4
+//     B operands of lane (n, g) are contiguous and come in with 16-byte (8-byte) LDS reads;
+//   * the input y takes the same route as x: the wave of output block ob fetches only channels 16 ob ..
+//     16 ob + 15 of its rows' pixels of the next step (four 4-byte loads per lane instead of C/4 - the
+//     address unit handles one lane per clock, and every wave of a band used to fetch all C channels) and
+//     puts them into a two-slot LDS buffer, from which all waves of the band take the B operand of Linv y.
+// Same arithmetic in the same order as k_solve_wide.  The LDS first holds the folded weights, then the rings.
+// ---------------------------------------------------------------------------
+template <int CQ>
+__host__ __device__ constexpr int wide_vec() { return CQ % 4 == 0 ? 4 : (CQ % 2 == 0 ? 2 : 1); }
+
+template <int CQ>
+__device__ __forceinline__ void wide_read_operands(const float *p, float (&o)[CQ])
+{
+    constexpr int VW = wide_vec<CQ>();
+    if constexpr (VW == 4) {
+#pragma unroll
+        for (int i = 0; i < CQ / 4; ++i) {
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(p + 4 * i);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                o[4 * i + j] = v[j];
+        }
+    } else if constexpr (VW == 2) {
+#pragma unroll
+        for (int i = 0; i < CQ / 2; ++i) {
+            const float2 v = *reinterpret_cast<const float2 *>(p + 2 * i);
+            o[2 * i] = v.x;
+            o[2 * i + 1] = v.y;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < CQ; ++i)
+            o[i] = p[i];
+    }
+}
+
+template <int CQ, int DIR>
+__global__ __launch_bounds__(512) void k_solve_wide_reg(const float *__restrict__ in, const float *__restrict__ w,
+                                                       float *__restrict__ out, int H, int W, int NB)
+{
+    constexpr int C = 4 * CQ, K = kWideK, NT = K * K, R = kWideRing;
+    constexpr int OB = wide_out_blocks(C), OR = 16 * OB, CPAD = C + 1;
+    constexpr int CP = C + wide_vec<CQ>();      // row of the rings: a multiple of the vector width, odd in vectors
+    extern __shared__ float smem[];
+    const int HP = 16 * NB + K - 1, YR = 16 * NB;
+    float *sWt = smem;                          // set-up: [NT][OR][CPAD], then 3 C C floats of scratch
+    float *ring = smem;                         // run: [R][HP][CP], permuted channels
+    float *ybuf = ring + R * HP * CP;           // run: [2][YR][CP], the input of this and of the next step
+    int *sflag = reinterpret_cast<int *>(ybuf + 2 * YR * CP);      // run: [waves] steps finished
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int band = wave / OB, ob = wave % OB;
+    const int n = lane & 15, g = lane >> 4;
+
+    wide_fold_weights<CQ, DIR>(w, sWt, sWt + NT * OR * CPAD);
+    // this lane's A operands: row m = n -> output channel 16 ob + n, K slot g -> input channel 4 c4 + g
+    float wAr[NT][CQ];
+    {
+        const int a_base = (16 * ob + n) * CPAD + g;
+#pragma unroll
+        for (int tp = 0; tp < NT; ++tp)
+#pragma unroll
+            for (int c4 = 0; c4 < CQ; ++c4)
+                wAr[tp][c4] = sWt[tp * OR * CPAD + a_base + 4 * c4];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < (R * HP + 2 * YR) * CP + 16; idx += nt)
+        ring[idx] = 0.0f;       // (the flags too: zero bits)
+    __syncthreads();
+
+    const int r = 16 * band + n;
+    const bool row_ok = r < H;
+    const size_t img = (size_t)blockIdx.x * C * H * W;
+    const int b_row = (r + K - 1) * CP + g * CQ;                 // + slot * HP * CP - da * CP
+    const int y_row = r * CP + g * CQ;                           // + slot * YR * CP
+    const int o_first = 16 * ob + 4 * g;                         // first of this lane's four output channels
+    auto gaddr = [&](int ch, int rr, int cc) -> size_t {
+        return img + ((size_t)(DIR ? C - 1 - ch : ch) * H + (DIR ? H - 1 - rr : rr)) * W + (DIR ? W - 1 - cc : cc);
+    };
+    // the wave's share of the input of step t: channels 16 ob + 4 q + g, q = 0..3, of pixel (r, t - r)
+    auto load_y = [&](int t, float (&yv)[4]) {
+        const int c = t - r;
+        const bool ok = row_ok && (unsigned)c < (unsigned)W;
+        const int rr = row_ok ? r : 0, cc = ok ? c : 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int ch = 16 * ob + 4 * q + g;
+            const float v = in[gaddr(ch < C ? ch : C - 1, rr, cc)];
+            yv[q] = (ok && ch < C) ? v : 0.0f;
+        }
+    };
+    auto store_y = [&](int slot, const float (&yv)[4]) {
+        float *dst = ybuf + slot * YR * CP + y_row + 4 * ob;    // channel 16 ob + 4 q + g sits at g CQ + 4 ob + q
+        if constexpr (CQ % 4 == 0) {
+            *reinterpret_cast<f32x4 *>(dst) = f32x4{yv[0], yv[1], yv[2], yv[3]};
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (4 * ob + q < CQ)
+                    dst[q] = yv[q];
+        }
+    };
+    float ynext[4];
+    load_y(0, ynext);
+    store_y(0, ynext);
+    __syncthreads();
+
+    // Of the nine taps only three need the step just finished: Linv y (tap 0), (0,1) and (1,0).  The other six
+    // read results at least two steps old, so their 6 C/4 products for step t + 1 are issued during step t,
+    // AFTER this wave has published its result of step t and BEFORE it needs anybody else's: the waves do not
+    // meet at a barrier but raise a flag (step count, one per wave, in LDS) when their result is in the ring
+    // and poll the others' flags only when they come back for the three dependent taps - by then the others
+    // have long arrived.  No wave is ever more than one step ahead of another (it needs every flag of step
+    // t before it starts step t + 1), which is what the five ring slots and the two input slots allow.
+    // The polls are bounded (all waves of a workgroup are resident, so the bound is never reached; a wave
+    // that reached it would write NaN).
+    constexpr int kCrit[3] = {0, 1, 3};
+    constexpr int kPre[6] = {2, 4, 5, 6, 7, 8};
+    const int nw = nt >> 6;
+    bool lost = false;
+    const int nsteps = H + W - 1;
+    int tm = 0;                                                 // t mod R
+    f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};    // the six old taps of step 0: zeros
+    auto read_tap = [&](int tp, int t, int tmod, float (&ob_)[CQ]) {
+        const int da = tp / K, db = tp % K, lag = da + db;
+        int slot = tmod - lag;
+        slot += slot < 0 ? R : 0;
+        const float *bp = tp == 0 ? ybuf + (t & 1) * YR * CP + y_row : ring + slot * HP * CP + b_row - da * CP;
+        wide_read_operands<CQ>(bp, ob_);
+    };
+    for (int t = 0; t < nsteps; ++t) {
+        load_y(t + 1, ynext);                                   // one step ahead (past the last step: zeros)
+        // ---- everybody's result of step t - 1 (and input of step t) is in LDS
+        if (t > 0 && !lost) {
+            int spins = 0;
+            for (;;) {
+                const int v = lane < nw ? __hip_atomic_load(sflag + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : t;
+                if (__builtin_amdgcn_ballot_w64(v < t) == 0)
+                    break;
+                if (++spins > (1 << 24)) {
+                    lost = true;
+                    break;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        }
+        float opb[2][CQ];
+        read_tap(kCrit[0], t, tm, opb[0]);
+#pragma unroll
+        for (int q = 0; q < 3; ++q) {
+            if (q + 1 < 3)
+                read_tap(kCrit[q + 1], t, tm, opb[(q + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);      // keep the reads above ahead of the products below
+#pragma unroll
+            for (int c4 = 0; c4 < CQ; ++c4) {
+                if (c4 & 1)
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(wAr[kCrit[q]][c4], opb[q & 1][c4], acc1, 0, 0, 0);
+                else
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wAr[kCrit[q]][c4], opb[q & 1][c4], acc0, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // (the first operands of the old taps of step t + 1 are fetched while the result is being stored)
+        const int tn = tm + 1 == R ? 0 : tm + 1;
+        read_tap(kPre[0], t + 1, tn, opb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        f32x4 acc = acc0 + acc1;
+        if (lost)
+            acc = f32x4{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), __builtin_nanf("")};
+        // The next step's input goes to LDS BEFORE this step's global stores are issued: vector memory operations
+        // complete in order, so waiting for the loads behind the stores would wait for the stores' round trip
+        // in every step; this way the stores have a whole step to complete.
+        store_y((t + 1) & 1, ynext);
+        __builtin_amdgcn_sched_barrier(0);
+        const int c = t - r;
+        const bool ok = row_ok && (unsigned)c < (unsigned)W;
+        float *rp = ring + tm * HP * CP + (r + K - 1) * CP;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int ch = o_first + j;
+            if (ch < C) {
+                rp[(ch & 3) * CQ + (ch >> 2)] = ok ? acc[j] : 0.0f;     // pixels outside the image count as zeros
+                if (ok)
+                    out[gaddr(ch, r, c)] = acc[j];
+            }
+        }
+        // ---- published: the LDS writes above are complete before the flag moves
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        if (lane == 0)
+            __hip_atomic_store(sflag + wave, t + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        // ---- the six old taps of step t + 1
+        acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < 6; ++q) {
+            if (q + 1 < 6)
+                read_tap(kPre[q + 1], t + 1, tn, opb[(q + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c4 = 0; c4 < CQ; ++c4) {
+                if (c4 & 1)
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(wAr[kPre[q]][c4], opb[q & 1][c4], acc1, 0, 0, 0);
+                else
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wAr[kPre[q]][c4], opb[q & 1][c4], acc0, 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        tm = tn;
+    }
+}
+
+static size_t wide_reg_lds_bytes(int C, int H)
+{
+    const size_t NB = (H + 15) / 16, OR = 16 * (size_t)wide_out_blocks(C), CPAD = C + 1;
+    const size_t CQ = C / 4, CP = C + (CQ % 4 == 0 ? 4 : (CQ % 2 == 0 ? 2 : 1));
+    const size_t setup = (size_t)kWideK * kWideK * OR * CPAD + 3 * (size_t)C * C;
+    const size_t run = ((size_t)kWideRing * (16 * NB + kWideK - 1) + 2 * 16 * NB) * CP + 16;
+    return sizeof(float) * (setup > run ? setup : run);
+}
+
+// at most eight waves: each may then use 256 registers, enough for its weights
+static bool wide_reg_supported(int C, int H)
+{
+    return ((H + 15) / 16) * wide_out_blocks(C) <= 8 && wide_reg_lds_bytes(C, H) <= kMaxLdsBytes;
 }
 
 static size_t wide_lds_bytes(int C, int H)
@@ -196,6 +489,19 @@ static int launch_wide_cq(int dir, const float *in, const float *w, float *out, 
 {
     constexpr int C = 4 * CQ;
     const int NB = (H + 15) / 16;
+    if (wide_reg_supported(C, H)) {
+        const size_t lds = wide_reg_lds_bytes(C, H);
+        const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 1>)
+                             : reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 0>);
+        if (!ensure_dynamic_lds(fn, lds))
+            return INVCONV_ERR_UNSUPPORTED;
+        const dim3 block((unsigned)(64 * NB * wide_out_blocks(C)));
+        if (dir)
+            hipLaunchKernelGGL((k_solve_wide_reg<CQ, 1>), dim3(B), block, lds, stream, in, w, out, H, W, NB);
+        else
+            hipLaunchKernelGGL((k_solve_wide_reg<CQ, 0>), dim3(B), block, lds, stream, in, w, out, H, W, NB);
+        return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+    }
     const size_t lds = wide_lds_bytes(C, H);
     const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide<CQ, 1>)
                          : reinterpret_cast<const void *>(&k_solve_wide<CQ, 0>);
