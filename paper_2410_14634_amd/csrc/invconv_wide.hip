@@ -241,7 +241,7 @@ __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ i
 }
 
 // ---------------------------------------------------------------------------
-// The same solve for workgroups of at most eight waves (e.g. 48 channels on 32 rows: 2 bands x 3 blocks of
+// The same solve for workgroups of at most twelve waves (e.g. 48 channels on 32 rows: 2 bands x 3 blocks of
 // output channels), where a wave may hold its whole weight tile - 9 taps x C/4 A operands - in registers:
 //   * no weight is read from LDS inside the step loop (it was half of the LDS traffic);
 //   * the rings keep a pixel's channels permuted, channel 4 c4 + g at position g C/4 + c4, so that the C/4
@@ -281,8 +281,8 @@ __device__ __forceinline__ void wide_read_operands(const float *p, float (&o)[CQ
     }
 }
 
-template <int CQ, int DIR>
-__global__ __launch_bounds__(512) void k_solve_wide_reg(const float *__restrict__ in, const float *__restrict__ w,
+template <int CQ, int DIR, int MAXW>
+__global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__restrict__ in, const float *__restrict__ w,
                                                        float *__restrict__ out, int H, int W, int NB)
 {
     constexpr int C = 4 * CQ, K = kWideK, NT = K * K, R = kWideRing;
@@ -465,10 +465,29 @@ static size_t wide_reg_lds_bytes(int C, int H)
     return sizeof(float) * (setup > run ? setup : run);
 }
 
-// at most eight waves: each may then use 256 registers, enough for its weights
+// at most eight waves: each may use 256 registers; at most twelve: 168, which the weights of up to 48 channels
+// still fit (48 channels leave three values of the set-up in scratch memory)
 static bool wide_reg_supported(int C, int H)
 {
-    return ((H + 15) / 16) * wide_out_blocks(C) <= 8 && wide_reg_lds_bytes(C, H) <= kMaxLdsBytes;
+    return ((H + 15) / 16) * wide_out_blocks(C) <= 12 && wide_reg_lds_bytes(C, H) <= kMaxLdsBytes;
+}
+
+template <int CQ, int MAXW>
+static int launch_wide_reg(int dir, const float *in, const float *w, float *out, int B, int H, int W, hipStream_t stream)
+{
+    constexpr int C = 4 * CQ;
+    const int NB = (H + 15) / 16;
+    const size_t lds = wide_reg_lds_bytes(C, H);
+    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 1, MAXW>)
+                         : reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 0, MAXW>);
+    if (!ensure_dynamic_lds(fn, lds))
+        return INVCONV_ERR_UNSUPPORTED;
+    const dim3 block((unsigned)(64 * NB * wide_out_blocks(C)));
+    if (dir)
+        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 1, MAXW>), dim3(B), block, lds, stream, in, w, out, H, W, NB);
+    else
+        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 0, MAXW>), dim3(B), block, lds, stream, in, w, out, H, W, NB);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
 static size_t wide_lds_bytes(int C, int H)
@@ -489,19 +508,9 @@ static int launch_wide_cq(int dir, const float *in, const float *w, float *out, 
 {
     constexpr int C = 4 * CQ;
     const int NB = (H + 15) / 16;
-    if (wide_reg_supported(C, H)) {
-        const size_t lds = wide_reg_lds_bytes(C, H);
-        const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 1>)
-                             : reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 0>);
-        if (!ensure_dynamic_lds(fn, lds))
-            return INVCONV_ERR_UNSUPPORTED;
-        const dim3 block((unsigned)(64 * NB * wide_out_blocks(C)));
-        if (dir)
-            hipLaunchKernelGGL((k_solve_wide_reg<CQ, 1>), dim3(B), block, lds, stream, in, w, out, H, W, NB);
-        else
-            hipLaunchKernelGGL((k_solve_wide_reg<CQ, 0>), dim3(B), block, lds, stream, in, w, out, H, W, NB);
-        return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
-    }
+    if (wide_reg_supported(C, H))
+        return NB * wide_out_blocks(C) <= 8 ? launch_wide_reg<CQ, 8>(dir, in, w, out, B, H, W, stream)
+                                            : launch_wide_reg<CQ, 12>(dir, in, w, out, B, H, W, stream);
     const size_t lds = wide_lds_bytes(C, H);
     const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide<CQ, 1>)
                          : reinterpret_cast<const void *>(&k_solve_wide<CQ, 0>);

@@ -66,6 +66,7 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     (1, 20, 6, 7, 2), (2, 18, 9, 5, 3),      # more than 16 channels: generic solve and generic dL/dw
     (2, 48, 32, 32, 3), (1, 32, 40, 24, 3), (1, 24, 20, 12, 5), (1, 48, 60, 9, 3), (1, 40, 8, 8, 3),   # after two squeezes
     (2, 20, 17, 19, 3), (1, 28, 128, 8, 3), (3, 36, 7, 33, 3), (1, 44, 1, 1, 3), (2, 24, 50, 50, 3), (1, 32, 100, 12, 3),
+    (1, 40, 64, 16, 3), (1, 32, 96, 20, 3), (2, 44, 33, 12, 3), (1, 48, 64, 24, 3),     # nine to twelve waves per image
     (1, 3, 17, 1200, 3), (1, 12, 4, 1400, 3),    # wide images: dL/dw row tiles beyond the preferred LDS budget
     # few channels, more than 64 rows: bands of 64 rows, one wave each
     (2, 3, 256, 256, 3), (1, 3, 130, 40, 5), (1, 4, 512, 16, 3), (1, 1, 65, 7, 3), (2, 3, 128, 200, 3),
