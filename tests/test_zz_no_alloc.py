@@ -29,6 +29,10 @@ def _one(shape, seed):
     assert torch.equal(v, v_ref) and torch.equal(dw, dw_ref)
     vr, dwr = oracle.invconv_bwd(host(x), cs["w"][0], cs["g"], THREADS)
     assert rel_err(host(v), vr) <= TOL_ACT and rel_err(host(dw), dwr) <= TOL_DW
+    # the binding's wrapper hands back the tensors it was given
+    v2, dw2 = b.invconv_bwd_static(x, wd, gd, out=(torch.empty_like(x), torch.empty_like(wd)))
+    torch.cuda.synchronize()
+    assert torch.equal(v2, v_ref) and torch.equal(dw2, dw_ref)
 
 
 @pytest.mark.parametrize("first,second", [
