@@ -82,8 +82,8 @@ SolveWs solve_ws_of(void *workspace, const WsLayout &lay)
 int solve_variant(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                   hipStream_t stream, int variant, SolveWs ws);
 
-// `logdet` (forward direction only, may be null): where log|det dx/dy| of one image goes; the few-channel
-// kernels write it on the side, every other kernel is followed by the small launch invconv_logdet makes.
+// `logdet` (forward direction only, may be null): where log|det dx/dy| of one image goes; the few-channel, band and
+// many-channel kernels write it on the side, every other kernel is followed by the small launch invconv_logdet makes.
 int solve(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
           hipStream_t stream, int variant, SolveWs ws = SolveWs{}, float *logdet = nullptr)
 {
@@ -91,6 +91,15 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
         return wave_split_preferred(B, H, W, k) && !wave_tile_preferred(B, C, H, W)
                    ? launch_solve_wave_split(dir, in, w, out, B, C, H, W, k, stream, logdet)
                    : launch_solve_wave(dir, in, w, out, B, C, H, W, k, stream, logdet);
+    // the band and many-channel kernels have a wave to spare for it too
+    if (variant == INVCONV_VARIANT_AUTO && logdet && !wave_bands_supported(C, H, W, k)) {
+        if (band_supported(C, H, k)) {
+            if (!(chain_supported(1, C, H, W, k) && chain_single_preferred(B, C, H)))
+                return launch_solve_band(dir, in, w, out, B, C, H, W, k, stream, logdet);
+        } else if (wide_supported(C, H, k)) {
+            return launch_solve_wide(dir, in, w, out, B, C, H, W, k, stream, logdet);
+        }
+    }
     if (int s = solve_variant(dir, in, w, out, B, C, H, W, k, stream, variant, ws))
         return s;
     return logdet ? launch_logdet(w, C, H, W, k, logdet, stream) : INVCONV_OK;

@@ -41,7 +41,7 @@ constexpr int kRing = 4;        // depth of the band-to-band message ring
 
 template <int CG, int K, int DIR>
 __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in, const float *__restrict__ w,
-                                                    float *__restrict__ out, int H, int W, int NB)
+                                                    float *__restrict__ out, int H, int W, int NB, float *logdet)
 {
     constexpr int C = 4 * CG;
     extern __shared__ float smem[];
@@ -116,8 +116,13 @@ __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in
         wLi[jj] = m_ok ? lv : 0.0f;
     }
     __syncthreads();        // ring zeroed, weights read
-    if (band >= NB)
-        return;             // helper waves of a single-band launch: they only speed up the weight preparation
+    if (band >= NB) {
+        // helper waves of a single-band launch: they only speed up the weight preparation; the last one of the
+        // first workgroup also forms the log-determinant when the caller asked for it
+        if (logdet && blockIdx.x == 0 && band == 3)
+            wave_logdet_any(w, C, K, H, W, logdet);
+        return;
+    }
 
     float xh[CG][K];
     f32x4 T[K];
@@ -249,6 +254,9 @@ __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in
         const int rest = (NB - 1 - band) * (16 + kBandDelay);
         for (int t = 0; t < rest; ++t)
             __syncthreads();
+        // (the first band is through with its barriers when the last band ends: it has time for the log-determinant)
+        if (logdet && blockIdx.x == 0 && band == 0)
+            wave_logdet_any(w, C, K, H, W, logdet);
     }
 }
 
@@ -268,7 +276,7 @@ __global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in
 // ---------------------------------------------------------------------------
 template <int CG, int DIR>
 __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restrict__ in, const float *__restrict__ w,
-                                                          float *__restrict__ out, int H, int W)
+                                                          float *__restrict__ out, int H, int W, float *logdet)
 {
     constexpr int K = 3, C = 4 * CG;
     extern __shared__ float smem[];
@@ -452,6 +460,8 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
             if (u < rest)
                 step(s0 + u, u, false);
     }
+    if (logdet && blockIdx.x == 0 && wave == 2)
+        wave_logdet_any(w, C, K, H, W, logdet);
 }
 
 size_t solve_band_lds_bytes(int C, int k, int NB)
@@ -466,36 +476,36 @@ bool band_supported(int C, int H, int k)
 
 template <int CG, int K>
 static int launch_band_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
-                          hipStream_t stream)
+                          hipStream_t stream, float *logdet)
 {
     const int NB = (H + 15) / 16;
     if (NB == 1 && K == 3) {
         const size_t lds1 = sizeof(float) * (2 * (size_t)16 * CG * CG + 2 * (size_t)K * K * 16 * CG * CG +
                                              2 * CG * 64 + 2 * 3 * 64 * 4);
         if (dir)
-            hipLaunchKernelGGL((k_solve_band_split<CG, 1>), dim3(B), dim3(256), lds1, stream, in, w, out, H, W);
+            hipLaunchKernelGGL((k_solve_band_split<CG, 1>), dim3(B), dim3(256), lds1, stream, in, w, out, H, W, logdet);
         else
-            hipLaunchKernelGGL((k_solve_band_split<CG, 0>), dim3(B), dim3(256), lds1, stream, in, w, out, H, W);
+            hipLaunchKernelGGL((k_solve_band_split<CG, 0>), dim3(B), dim3(256), lds1, stream, in, w, out, H, W, logdet);
         return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
     }
     const size_t lds = solve_band_lds_bytes(4 * CG, K, NB);
     // a single band gets three helper waves for the weight preparation (its loop has no barriers)
     const int threads = NB == 1 ? 256 : 64 * NB;
     if (dir)
-        hipLaunchKernelGGL((k_solve_band<CG, K, 1>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB);
+        hipLaunchKernelGGL((k_solve_band<CG, K, 1>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB, logdet);
     else
-        hipLaunchKernelGGL((k_solve_band<CG, K, 0>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB);
+        hipLaunchKernelGGL((k_solve_band<CG, K, 0>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB, logdet);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
 int launch_solve_band(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                      hipStream_t stream)
+                      hipStream_t stream, float *logdet)
 {
     if (!band_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
-    if (C == 8) return launch_band_ck<2, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 12) return launch_band_ck<3, 3>(dir, in, w, out, B, H, W, stream);
-    if (C == 16) return launch_band_ck<4, 3>(dir, in, w, out, B, H, W, stream);
+    if (C == 8) return launch_band_ck<2, 3>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 12) return launch_band_ck<3, 3>(dir, in, w, out, B, H, W, stream, logdet);
+    if (C == 16) return launch_band_ck<4, 3>(dir, in, w, out, B, H, W, stream, logdet);
     return INVCONV_ERR_VARIANT;
 }
 

@@ -35,6 +35,23 @@ __device__ __forceinline__ float weff(const float *__restrict__ w, int C, int k,
     return w[((oo * C + ii) * k + a) * k + b];
 }
 
+// log|det dx/dy| of one image (Section 4), -H W sum_c log|w[c][c][k-1][k-1]|, by one full wave: lane l takes
+// channels l, l + 64, ..., fixed butterfly across the lanes (the arithmetic of the stand-alone log-determinant
+// kernel, so both give the same bits).  For kernels that have a wave to spare while the others set up.
+__device__ __forceinline__ void wave_logdet_any(const float *__restrict__ w, int C, int k, int H, int W,
+                                                float *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    double s = 0.0;
+    for (int c = lane; c < C; c += 64)
+        s += log(fabs((double)w[((c * C + c) * k + (k - 1)) * k + (k - 1)]));
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1)
+        s += __shfl_xor(s, m, 64);
+    if (lane == 0)
+        out[0] = (float)(-(double)H * (double)W * s);
+}
+
 // Weight preparation, done by every workgroup for itself (C*C*k*k is at most
 // a few thousand entries).  With L the lower-triangular current-pixel block,
 //   x_p = L^{-1} ( y_p - sum_{tap != current} W_tap x_{p-tap} )

@@ -57,11 +57,11 @@ int launch_solve_wave(int dir, const float *in, const float *w, float *out, int 
                       hipStream_t stream, float *logdet = nullptr);
 bool band_supported(int C, int H, int k);
 int launch_solve_band(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                      hipStream_t stream);
+                      hipStream_t stream, float *logdet = nullptr);
 // many channels (20 .. 48, multiple of 4), k = 3: 16x16x4 MFMA per tap, history in an LDS ring
 bool wide_supported(int C, int H, int k);
 int launch_solve_wide(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                      hipStream_t stream);
+                      hipStream_t stream, float *logdet = nullptr);
 bool bwd_wave_supported(int C, int H, int W, int k);
 int launch_solve_wave_split(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                             hipStream_t stream, float *logdet = nullptr);

@@ -132,7 +132,7 @@ __device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, f
 
 template <int CQ, int DIR>
 __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ in, const float *__restrict__ w,
-                                                    float *__restrict__ out, int H, int W, int NB)
+                                                    float *__restrict__ out, int H, int W, int NB, float *logdet)
 {
     constexpr int C = 4 * CQ, K = kWideK, NT = K * K, R = kWideRing;
     constexpr int OB = wide_out_blocks(C), OR = 16 * OB, CPAD = C + 1;
@@ -238,6 +238,8 @@ __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ i
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
     }
+    if (logdet && blockIdx.x == 0 && wave == 0)
+        wave_logdet_any(w, C, K, H, W, logdet);
 }
 
 // ---------------------------------------------------------------------------
@@ -282,8 +284,9 @@ __device__ __forceinline__ void wide_read_operands(const float *p, float (&o)[CQ
 }
 
 template <int CQ, int DIR, int MAXW>
-__global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__restrict__ in, const float *__restrict__ w,
-                                                       float *__restrict__ out, int H, int W, int NB)
+__global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__restrict__ in,
+                                                              const float *__restrict__ w, float *__restrict__ out,
+                                                              int H, int W, int NB, float *logdet)
 {
     constexpr int C = 4 * CQ, K = kWideK, NT = K * K, R = kWideRing;
     constexpr int OB = wide_out_blocks(C), OR = 16 * OB, CPAD = C + 1;
@@ -454,6 +457,8 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
         }
         tm = tn;
     }
+    if (logdet && blockIdx.x == 0 && wave == 0)
+        wave_logdet_any(w, C, K, H, W, logdet);
 }
 
 static size_t wide_reg_lds_bytes(int C, int H)
@@ -473,7 +478,8 @@ static bool wide_reg_supported(int C, int H)
 }
 
 template <int CQ, int MAXW>
-static int launch_wide_reg(int dir, const float *in, const float *w, float *out, int B, int H, int W, hipStream_t stream)
+static int launch_wide_reg(int dir, const float *in, const float *w, float *out, int B, int H, int W, hipStream_t stream,
+                           float *logdet)
 {
     constexpr int C = 4 * CQ;
     const int NB = (H + 15) / 16;
@@ -484,9 +490,9 @@ static int launch_wide_reg(int dir, const float *in, const float *w, float *out,
         return INVCONV_ERR_UNSUPPORTED;
     const dim3 block((unsigned)(64 * NB * wide_out_blocks(C)));
     if (dir)
-        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 1, MAXW>), dim3(B), block, lds, stream, in, w, out, H, W, NB);
+        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 1, MAXW>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet);
     else
-        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 0, MAXW>), dim3(B), block, lds, stream, in, w, out, H, W, NB);
+        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 0, MAXW>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
@@ -504,13 +510,14 @@ bool wide_supported(int C, int H, int k)
 }
 
 template <int CQ>
-static int launch_wide_cq(int dir, const float *in, const float *w, float *out, int B, int H, int W, hipStream_t stream)
+static int launch_wide_cq(int dir, const float *in, const float *w, float *out, int B, int H, int W, hipStream_t stream,
+                         float *logdet)
 {
     constexpr int C = 4 * CQ;
     const int NB = (H + 15) / 16;
     if (wide_reg_supported(C, H))
-        return NB * wide_out_blocks(C) <= 8 ? launch_wide_reg<CQ, 8>(dir, in, w, out, B, H, W, stream)
-                                            : launch_wide_reg<CQ, 12>(dir, in, w, out, B, H, W, stream);
+        return NB * wide_out_blocks(C) <= 8 ? launch_wide_reg<CQ, 8>(dir, in, w, out, B, H, W, stream, logdet)
+                                            : launch_wide_reg<CQ, 12>(dir, in, w, out, B, H, W, stream, logdet);
     const size_t lds = wide_lds_bytes(C, H);
     const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide<CQ, 1>)
                          : reinterpret_cast<const void *>(&k_solve_wide<CQ, 0>);
@@ -518,26 +525,26 @@ static int launch_wide_cq(int dir, const float *in, const float *w, float *out, 
         return INVCONV_ERR_UNSUPPORTED;
     const dim3 block((unsigned)(64 * NB * wide_out_blocks(C)));
     if (dir)
-        hipLaunchKernelGGL((k_solve_wide<CQ, 1>), dim3(B), block, lds, stream, in, w, out, H, W, NB);
+        hipLaunchKernelGGL((k_solve_wide<CQ, 1>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet);
     else
-        hipLaunchKernelGGL((k_solve_wide<CQ, 0>), dim3(B), block, lds, stream, in, w, out, H, W, NB);
+        hipLaunchKernelGGL((k_solve_wide<CQ, 0>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
 int launch_solve_wide(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                      hipStream_t stream)
+                      hipStream_t stream, float *logdet)
 {
     if (!wide_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
     switch (C / 4) {
-    case 5: return launch_wide_cq<5>(dir, in, w, out, B, H, W, stream);
-    case 6: return launch_wide_cq<6>(dir, in, w, out, B, H, W, stream);
-    case 7: return launch_wide_cq<7>(dir, in, w, out, B, H, W, stream);
-    case 8: return launch_wide_cq<8>(dir, in, w, out, B, H, W, stream);
-    case 9: return launch_wide_cq<9>(dir, in, w, out, B, H, W, stream);
-    case 10: return launch_wide_cq<10>(dir, in, w, out, B, H, W, stream);
-    case 11: return launch_wide_cq<11>(dir, in, w, out, B, H, W, stream);
-    case 12: return launch_wide_cq<12>(dir, in, w, out, B, H, W, stream);
+    case 5: return launch_wide_cq<5>(dir, in, w, out, B, H, W, stream, logdet);
+    case 6: return launch_wide_cq<6>(dir, in, w, out, B, H, W, stream, logdet);
+    case 7: return launch_wide_cq<7>(dir, in, w, out, B, H, W, stream, logdet);
+    case 8: return launch_wide_cq<8>(dir, in, w, out, B, H, W, stream, logdet);
+    case 9: return launch_wide_cq<9>(dir, in, w, out, B, H, W, stream, logdet);
+    case 10: return launch_wide_cq<10>(dir, in, w, out, B, H, W, stream, logdet);
+    case 11: return launch_wide_cq<11>(dir, in, w, out, B, H, W, stream, logdet);
+    case 12: return launch_wide_cq<12>(dir, in, w, out, B, H, W, stream, logdet);
     default: return INVCONV_ERR_VARIANT;
     }
 }

@@ -255,7 +255,9 @@ def test_masked_entries_are_ignored_and_get_zero_gradient():
 
 
 FWD_LOGDET_SHAPES = [(4, 3, 8, 8, 3), (16, 3, 32, 32, 3), (32, 3, 64, 64, 5), (2, 1, 5, 5, 3), (700, 2, 50, 10, 3),
-                     (64, 12, 16, 16, 3), (2, 3, 130, 40, 3), (1, 20, 6, 7, 2)]
+                     (64, 12, 16, 16, 3), (2, 3, 130, 40, 3), (1, 20, 6, 7, 2),
+                     # band and many-channel kernels with the log-determinant formed by a spare wave
+                     (2, 12, 40, 24, 3), (3, 8, 128, 8, 3), (2, 48, 32, 32, 3), (1, 28, 128, 8, 3), (1, 16, 16, 5, 3)]
 
 
 @pytest.mark.parametrize("shape", FWD_LOGDET_SHAPES)
