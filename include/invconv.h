@@ -93,7 +93,8 @@ invconv_status invconv_fwd(const float *y, const float *w, float *x,
 /*
  * Forward pass and log-determinant in one call: what the forward pass of a flow step needs
  * (Section 4: the likelihood takes x and log|det dx/dy|).  x as invconv_fwd, *logdet as invconv_logdet;
- * for few-channel images (C <= 4, H <= 64) both come out of one kernel launch.
+ * for few-channel images (C <= 4, H <= 64) and for the band and many-channel kernels (8-48 channels)
+ * both come out of one kernel launch.
  *   logdet [out] one device float.
  */
 invconv_status invconv_fwd_logdet(const float *y, const float *w, float *x, float *logdet,
@@ -101,11 +102,12 @@ invconv_status invconv_fwd_logdet(const float *y, const float *w, float *x, floa
 
 /*
  * The same forward pass with scratch from the caller.  Images of few channels (C <= 4) and more than
- * 128 rows are then cut into bands of 64 rows that run on different compute units and hand their
+ * 64 rows are then cut into bands of 64 rows that run on different compute units and hand their
  * boundary messages over through the workspace (Section 3.3 only needs the pixels of an anti-diagonal
  * to be independent; a band trails the one above by a fixed number of steps); invconv_fwd, which has
  * nowhere to put those messages, keeps all bands of an image in one workgroup.  Other shapes run the
- * kernels invconv_fwd runs.  Results are identical.
+ * kernels invconv_fwd runs.  Results agree to rounding (the banded kernels add a pixel's terms in
+ * different orders).
  *   workspace [scratch] at least invconv_fwd_workspace_bytes() bytes (never 0 for a valid shape).
  */
 invconv_status invconv_fwd_ws(const float *y, const float *w, float *x,
