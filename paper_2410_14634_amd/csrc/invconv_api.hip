@@ -323,7 +323,10 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
         return INVCONV_ERR_WORKSPACE;
     float *part = (float *)((char *)workspace + lay.dw_off);
     hipStream_t st = (hipStream_t)stream;
-    if ((variant == INVCONV_VARIANT_AUTO || variant == INVCONV_VARIANT_WAVE) && bwd_wave_supported(C, H, W, k)) {
+    const bool separate = variant == INVCONV_VARIANT_AUTO && !bwd_wave_fused_pays(B, C, H, W, k) &&
+                          conv_bwd_fused_supported(C, H, W, k) && ((((size_t)x | (size_t)dLdy)) & 15) == 0;
+    if (!separate && (variant == INVCONV_VARIANT_AUTO || variant == INVCONV_VARIANT_WAVE) &&
+        bwd_wave_supported(C, H, W, k)) {
         if (int s = launch_bwd_wave(x, w, dLdx, dLdy, part, B, C, H, W, k, st))
             return s;
         return launch_dw_reduce(part, B, dLdw, C, k, st);

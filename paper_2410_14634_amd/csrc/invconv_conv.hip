@@ -21,6 +21,7 @@ constexpr int kConvRows = 16;                   // tile height
 constexpr int kConvLoadBatch = 8;               // loads in flight per thread while a tile is staged
 constexpr size_t kConvLdsBudget = 72 * 1024;    // tile + tables; two workgroups per CU at the limit
 constexpr int kConvMaxGrid = 1024;              // workgroups of a launch (four per CU)
+constexpr int kConvMaxGridDw = 2048;            // ... of the launch that only forms weight-gradient sums (small tiles)
 
 // n / d for n * d < 2^32 with m = magic(d): one multiply instead of a division sequence.
 __device__ __forceinline__ unsigned magic(unsigned d) { return 0xFFFFFFFFu / d + 1u; }
@@ -72,42 +73,65 @@ __device__ __forceinline__ void tile_elem(const TileGeom &g, unsigned raw, unsig
     dst = raw < total ? (int)((ch * g.XR + r) * g.XW + step * cq) : -1;
 }
 
-// Tile loader: kConvLoadBatch loads at a time with clamped addresses (no branch around a
-// load); out-of-image elements are zeroed when the batch is written to LDS.
-template <bool vec, int DIR>
-__device__ __forceinline__ void conv_load_tile(const TileGeom &g, float *sx)
+// Tile loader: NB loads at a time with clamped addresses (no branch around a load); out-of-image
+// elements are zeroed when the batch is written to LDS.  A batch is issued (conv_tile_issue) and later
+// written (conv_tile_commit), so that the batches of two tiles can be in flight together.
+template <int NB>
+struct TileBatch {
+    float4 val[NB];
+    int dst[NB];
+    bool keep[NB];
+};
+
+template <bool vec, int DIR, int NB>
+__device__ __forceinline__ void conv_tile_issue(const TileGeom &g, unsigned base, TileBatch<NB> &b)
 {
     const unsigned line = vec ? g.XW >> 2 : g.XW;       // elements (16 or 4 bytes) per tile row
     const unsigned total = g.C * g.xrows * line;
     const unsigned m_line = magic(line), m_rows = magic(g.xrows);
-    for (unsigned base = threadIdx.x; base < total; base += kConvLoadBatch * 256) {
-        float4 val[kConvLoadBatch];
-        int dst[kConvLoadBatch];
-        bool keep[kConvLoadBatch];
 #pragma unroll
-        for (int j = 0; j < kConvLoadBatch; ++j) {
-            unsigned src;
-            tile_elem<vec, DIR>(g, base + j * 256, total, line, m_line, m_rows, src, dst[j], keep[j]);
-            if (vec)
-                val[j] = *reinterpret_cast<const float4 *>(g.xi + src);
-            else
-                val[j].x = g.xi[src];
-        }
-#pragma unroll
-        for (int j = 0; j < kConvLoadBatch; ++j)
-            if (dst[j] >= 0) {
-                const bool kp = keep[j];
-                if (vec && DIR)
-                    *reinterpret_cast<float4 *>(sx + dst[j]) = make_float4(kp ? val[j].w : 0.f, kp ? val[j].z : 0.f,
-                                                                            kp ? val[j].y : 0.f, kp ? val[j].x : 0.f);
-                else if (vec)
-                    *reinterpret_cast<float4 *>(sx + dst[j]) = make_float4(kp ? val[j].x : 0.f, kp ? val[j].y : 0.f,
-                                                                            kp ? val[j].z : 0.f, kp ? val[j].w : 0.f);
-                else
-                    sx[dst[j]] = kp ? val[j].x : 0.f;
-            }
+    for (int j = 0; j < NB; ++j) {
+        unsigned src;
+        tile_elem<vec, DIR>(g, base + j * 256, total, line, m_line, m_rows, src, b.dst[j], b.keep[j]);
+        if (vec)
+            b.val[j] = *reinterpret_cast<const float4 *>(g.xi + src);
+        else
+            b.val[j].x = g.xi[src];
     }
 }
+
+template <bool vec, int DIR, int NB>
+__device__ __forceinline__ void conv_tile_commit(float *sx, const TileBatch<NB> &b)
+{
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+        if (b.dst[j] >= 0) {
+            const bool kp = b.keep[j];
+            if (vec && DIR)
+                *reinterpret_cast<float4 *>(sx + b.dst[j]) = make_float4(kp ? b.val[j].w : 0.f, kp ? b.val[j].z : 0.f,
+                                                                          kp ? b.val[j].y : 0.f, kp ? b.val[j].x : 0.f);
+            else if (vec)
+                *reinterpret_cast<float4 *>(sx + b.dst[j]) = make_float4(kp ? b.val[j].x : 0.f, kp ? b.val[j].y : 0.f,
+                                                                          kp ? b.val[j].z : 0.f, kp ? b.val[j].w : 0.f);
+            else
+                sx[b.dst[j]] = kp ? b.val[j].x : 0.f;
+        }
+}
+
+template <bool vec, int DIR, int NB = kConvLoadBatch>
+__device__ __forceinline__ void conv_load_tile(const TileGeom &g, float *sx)
+{
+    const unsigned line = vec ? g.XW >> 2 : g.XW;
+    const unsigned total = g.C * g.xrows * line;
+    for (unsigned base = threadIdx.x; base < total; base += NB * 256) {
+        TileBatch<NB> b;
+        conv_tile_issue<vec, DIR, NB>(g, base, b);
+        conv_tile_commit<vec, DIR, NB>(sx, b);
+    }
+}
+
+// loads in flight per thread for a tile of `elems` elements: all of them when that is fewer than kConvLoadBatch
+constexpr int conv_batch_for(int elems) { return (elems + 255) / 256 < kConvLoadBatch ? (elems + 255) / 256 : kConvLoadBatch; }
 
 // ---- few channels: lane = pixel ---------------------------------------------------------------
 // Tile of kConvRows x TW pixels (TW = 32, 64 or 128), LDS tile [C][kConvRows + K - 1][TW + 4].
@@ -191,12 +215,37 @@ __global__ __launch_bounds__(256) void k_conv_small(const float *__restrict__ x,
     size_t n;
     int r0, c0, rows;
     const int lr = lane / LW, lc = lane % LW;
+    constexpr int E1 = C * XR * (VEC ? XW / 4 : XW), E2 = C * kConvRows * (VEC ? TW / 4 : TW);
+    constexpr int NB1 = conv_batch_for(E1), NB2 = conv_batch_for(E2);
+    // Small tiles with the weight gradient: both tiles are one batch of loads each, issued together, and the
+    // next tile's batches are issued before this tile's products, so that they are in flight meanwhile.
+    constexpr bool kAhead2 = DW && E1 <= 256 * NB1 && E2 <= 256 * NB2 && NB1 + NB2 <= 12;
+    TileBatch<kAhead2 ? NB1 : 1> b1;
+    TileBatch<kAhead2 ? NB2 : 1> b2;
+    auto issue_both = [&](unsigned t) {
+        if constexpr (kAhead2) {
+            size_t nn;
+            int rr0, cc0, rrows;
+            const TileGeom g = geom(t, nn, rr0, cc0, rrows);
+            const TileGeom g2{x2 + nn * C * H * W, C, H, W, rr0, cc0, rrows, kConvRows, TW};
+            conv_tile_issue<VEC, DIR, NB1>(g, threadIdx.x, b1);
+            conv_tile_issue<VEC, DIR, NB2>(g2, threadIdx.x, b2);
+        }
+    };
+    issue_both(t0);
     for (unsigned t = t0; t < t1; t += tstep) {
         const TileGeom g = geom(t, n, r0, c0, rows);
-        conv_load_tile<VEC, DIR>(g, sx);
-        if (DW) {
-            const TileGeom g2{x2 + n * C * H * W, C, H, W, r0, c0, rows, kConvRows, TW};
-            conv_load_tile<VEC, DIR>(g2, sx2);
+        if constexpr (kAhead2) {
+            conv_tile_commit<VEC, DIR, NB1>(sx, b1);
+            conv_tile_commit<VEC, DIR, NB2>(sx2, b2);
+            if (t + tstep < t1)
+                issue_both(t + tstep);
+        } else {
+            conv_load_tile<VEC, DIR, NB1>(g, sx);
+            if (DW) {
+                const TileGeom g2{x2 + n * C * H * W, C, H, W, r0, c0, rows, kConvRows, TW};
+                conv_load_tile<VEC, DIR, NB2>(g2, sx2);
+            }
         }
         __syncthreads();
         float *__restrict__ yi = y + n * C * H * W;
@@ -508,7 +557,8 @@ static unsigned launch_small_dw_tw(const float *g, const float *w, float *dx, co
     const int tiles_r = (H + kConvRows - 1) / kConvRows, tiles_c = (W + TW - 1) / TW;
     const size_t ntiles = (size_t)B * tiles_r * tiles_c;
     const size_t lds = conv_small_dw_lds<C, K, TW>();
-    const unsigned grid = conv_grid(ntiles);
+    const unsigned grid = dx ? conv_grid(ntiles)
+                             : (ntiles < (size_t)kConvMaxGridDw ? (unsigned)ntiles : (unsigned)kConvMaxGridDw);
     if (dx) {
         if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_conv_small<C, K, TW, true, 1, true>), lds))
             return 0;
@@ -627,13 +677,13 @@ static int launch_conv_dir(const float *x, const float *w, float *y, int B, int 
 }
 
 // Few channels, rows of whole 16-byte pieces: dL/dx = M^T g and the partial sums of dL/dw in one pass over g
-// and x.  part needs kConvMaxGrid rows of C*C*k*k floats.
+// and x.  part needs conv_bwd_fused_rows() rows of C*C*k*k floats.
 bool conv_bwd_fused_supported(int C, int H, int W, int k)
 {
     return ((C >= 1 && C <= 4 && k == 3) || (C == 3 && k == 5)) && (W % 4) == 0 && (size_t)C * H * W <= 0x7fffffffull;
 }
 
-size_t conv_bwd_fused_rows() { return kConvMaxGrid; }
+size_t conv_bwd_fused_rows() { return kConvMaxGridDw; }
 
 // dx may be null: then only the partial sums of the weight gradient are formed (g and x read once).
 // Returns the number of partial rows written (0: not launched)

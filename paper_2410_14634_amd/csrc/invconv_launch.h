@@ -63,6 +63,7 @@ bool wide_supported(int C, int H, int k);
 int launch_solve_wide(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                       hipStream_t stream, float *logdet = nullptr);
 bool bwd_wave_supported(int C, int H, int W, int k);
+bool bwd_wave_fused_pays(int B, int C, int H, int W, int k);   // false: solve and weight gradient as separate launches
 int launch_solve_wave_split(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                             hipStream_t stream, float *logdet = nullptr);
 bool wave_split_preferred(int B, int H, int W, int k);

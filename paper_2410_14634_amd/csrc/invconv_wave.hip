@@ -119,6 +119,75 @@ __global__ __launch_bounds__(64) void k_solve_wave_tile(const ST *__restrict__ i
         st4<ST>(dst, i, tile[i]);
 }
 
+// Images of at most 32 rows leave half of the wave's lanes idle, and at large batches the solve is bound by
+// the instructions a SIMD can issue (27 matrix instructions of 8 clocks per step at C = k = 3, whatever
+// the number of rows): here a wave takes two neighbouring images, one per half (solve_wave_body with PACK).
+// The second tile sits kTilePackPad floats behind the end of the first, so that the two halves of a
+// 64-lane LDS access use different banks.
+// LDS holds few such pairs per compute unit, too few waves to hide the copy in and out behind other
+// waves' solves, so a wave hides its own: it walks over pairs (pair = wave index + a multiple of the
+// number of waves launched) and fetches the next pair into registers while it solves the current one; after
+// the solve each 16-byte piece of the result leaves the tile and the next pair's piece takes its place.
+// Pairs of at most 64 * kTile2Pieces pieces (3x32x32 and smaller).  The waves of a workgroup are independent
+// (own tile, no barrier); four of them per workgroup put one wave on every SIMD of a compute unit.
+constexpr int kTilePackPad = 32;
+constexpr int kTile2Pieces = 24;
+template <int C, int K, int DIR>
+__global__ __launch_bounds__(256) void k_solve_wave_tile2(const float *__restrict__ in, const float *__restrict__ w,
+                                                         float *__restrict__ out, int B, int H, int W, float *logdet)
+{
+    extern __shared__ float smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    if (logdet && blockIdx.x == 0 && wave == 0)
+        wave_logdet<C, K>(w, H, W, logdet);
+    const int chw = C * H * W, n4 = chw / 4;
+    float *slot = smem + wave * (2 * chw + kTilePackPad);
+    float4 *tile = reinterpret_cast<float4 *>(slot);
+    const int npairs = (B + 1) >> 1, stride = gridDim.x * nw;
+    auto pieces_of = [&](int q) { return 2 * q + 1 < B ? 2 * n4 : n4; };      // the last pair may be a single image
+    auto at = [&](int i) { return i < n4 ? i : i + kTilePackPad / 4; };
+    int p = blockIdx.x * nw + wave;
+    if (p >= npairs)
+        return;
+    float4 v[kTile2Pieces];
+    auto fetch = [&](int q) {
+        const float *src = in + (size_t)2 * q * chw;
+        const int t4 = pieces_of(q);
+#pragma unroll
+        for (int u = 0; u < kTile2Pieces; ++u)
+            v[u] = ld4<float>(src, lane + 64 * u < t4 ? lane + 64 * u : t4 - 1);
+    };
+    fetch(p);
+    {
+        const int t4 = pieces_of(p);
+#pragma unroll
+        for (int u = 0; u < kTile2Pieces; ++u)
+            if (lane + 64 * u < t4)
+                tile[at(lane + 64 * u)] = v[u];
+    }
+    for (;;) {
+        const int pn = p + stride;
+        const bool more = pn < npairs;
+        if (more)
+            fetch(pn);
+        solve_wave_body<C, K, DIR, false, false, true, true>(nullptr, w, nullptr, H, W, 0, slot, WaveBands{},
+                                                             2 * p + 1 < B, chw + kTilePackPad);
+        float *dst = out + (size_t)2 * p * chw;
+        const int tc = pieces_of(p), tn = more ? pieces_of(pn) : 0;
+#pragma unroll
+        for (int u = 0; u < kTile2Pieces; ++u) {
+            const int i = lane + 64 * u;
+            if (i < tc)
+                st4<float>(dst, i, tile[at(i)]);
+            if (i < tn)
+                tile[at(i)] = v[u];
+        }
+        if (!more)
+            break;
+        p = pn;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // The same solve with the matrix instructions of a step split over the waves of a workgroup by the age of
 // their input (images of at most 64 rows; pays when a step is long; four waves up to k = 5, k/2 + 2.5 waves
@@ -955,6 +1024,33 @@ static int launch_wave_ck(int dir, const float *in, const float *w, float *out, 
     // in rounds.  An LDS allocation the kernel never touches caps the waves per CU accordingly.
     size_t lds = 0;
     const size_t tile_bytes = (size_t)C * H * W * sizeof(float);
+    // (two images per wave up to k = 7: beyond that the registers that hold the next pair would spill)
+    if (K <= 7 && wave_tile_preferred(B, C, H, W) && H <= 32 && tile_bytes <= 16 * 64 * kTile2Pieces / 2 &&
+        (((size_t)in | (size_t)out) & 15) == 0) {
+        constexpr int KP = K <= 7 ? K : 3;      // (never launched for larger k; keeps those kernels out of the library)
+        const size_t pair_bytes = 2 * tile_bytes + kTilePackPad * sizeof(float);
+        const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave_tile2<C, KP, 1>)
+                             : reinterpret_cast<const void *>(&k_solve_wave_tile2<C, KP, 0>);
+        // from four pairs per compute unit on: workgroups of four waves, as many as are resident at once
+        const int npairs = (B + 1) / 2;
+        int nw = 1, grid = npairs;
+        if (4 * pair_bytes <= kMaxLdsBytes && ensure_dynamic_lds(fn, 4 * pair_bytes)) {
+            const int resident = resident_workgroups(fn, 256, 4 * pair_bytes);
+            if (resident > 0 && npairs >= 4 * resident) {
+                nw = 4;
+                grid = resident;
+            }
+        }
+        if (!ensure_dynamic_lds(fn, nw * pair_bytes))
+            return INVCONV_ERR_UNSUPPORTED;
+        if (dir)
+            hipLaunchKernelGGL((k_solve_wave_tile2<C, KP, 1>), dim3(grid), dim3(64 * nw), nw * pair_bytes, stream, in, w,
+                               out, B, H, W, logdet);
+        else
+            hipLaunchKernelGGL((k_solve_wave_tile2<C, KP, 0>), dim3(grid), dim3(64 * nw), nw * pair_bytes, stream, in, w,
+                               out, B, H, W, logdet);
+        return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+    }
     if (wave_tile_preferred(B, C, H, W) && (((size_t)in | (size_t)out) & 15) == 0) {
         const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wave_tile<C, K, 1>)
                              : reinterpret_cast<const void *>(&k_solve_wave_tile<C, K, 0>);
@@ -1316,6 +1412,22 @@ static int launch_bwd_wave_ck(const float *x, const float *w, const float *g, fl
     }
     hipLaunchKernelGGL((k_bwd_wave<C, K, kSplit>), dim3(B), dim3(256), lds, stream, x, w, g, v, part, H, W);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+// The fused kernel gives a whole workgroup to every image while only one of its waves solves, and registers
+// and LDS allow at most three such workgroups per compute unit.  Once a large batch needs more than about
+// 1.3 rounds of them, the transposed solve as a launch of its own (one wave per image, or per two) followed
+// by the streaming weight-gradient kernel is faster: 3x32x32, B = 1400: 53 against 67 us, B = 4096: 91
+// against 159 us; 3x64x64, B = 400: 65 against 122 us; 1x28x28, B = 4096: 49 against 63 us; B = 1024 at
+// 3x32x32 is a tie, 700 still favours the fused kernel (38 against 43 us).
+bool bwd_wave_fused_pays(int B, int C, int H, int W, int k)
+{
+    if (!wave_tile_preferred(B, C, H, W))
+        return true;
+    const size_t lds = bwd_wave_lds_bytes(C, H, W, k);
+    size_t per_cu = lds ? kMaxLdsBytes / lds : 3;
+    per_cu = per_cu > 3 ? 3 : (per_cu < 1 ? 1 : per_cu);
+    return (double)B <= 1.3 * (double)per_cu * 256.0;      // 256 compute units
 }
 
 bool bwd_wave_supported(int C, int H, int W, int k)

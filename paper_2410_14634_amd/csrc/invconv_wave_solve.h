@@ -128,20 +128,32 @@ __device__ __forceinline__ int ring_rho(int r) { return (r - 1) >> 4; }
 // calling workgroup).  With LDS_COPY the result is also written to lds_copy as a
 // [C][H][W] tile in image (not mirrored) coordinates.
 // With TILE the image lives in lds_copy (input on entry, result on return) and global memory is not touched.
-template <int C, int K, int DIR, bool LDS_COPY, bool BANDS = false, bool TILE = false>
+// With PACK (TILE only, H <= 32) the wave solves two images at once, lanes 0..31 the rows of the one at
+// lds_copy and lanes 32..63 the rows of the one pack_stride floats behind it (pack_second: that image
+// exists); lane 32, a first row, takes nothing from lane 31.
+template <int C, int K, int DIR, bool LDS_COPY, bool BANDS = false, bool TILE = false, bool PACK = false>
 __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, const float *__restrict__ w,
                                                 float *__restrict__ out, int H, int W, int n, float *lds_copy,
-                                                WaveBands wb = WaveBands{})
+                                                WaveBands wb = WaveBands{}, bool pack_second = false,
+                                                int pack_stride = 0)
 {
+    static_assert(!PACK || (TILE && !BANDS), "two images per wave only on LDS tiles");
     static_assert(C >= 1 && C <= 4, "one 4-row MFMA block per pixel");
     // All 64 lanes stay active to the end: the matrix instruction reads its weight
     // operand from every lane of a 4-lane block, whatever the execution mask says.
     // Lanes past the last row compute on clamped inputs and never store.
-    const int r = threadIdx.x & 63;                   // row inside the band = lane
+    const int lane = threadIdx.x & 63;
+    const int r = PACK ? lane & 31 : lane;            // row inside the band (lane, or lane within its half)
+    const bool second = PACK && lane >= 32;
+    const bool top = PACK && r == 0;                  // a first row: nothing arrives from the lane above
     const int grow = BANDS ? 64 * wb.band + r : r;    // image row
-    const bool row_ok = grow < H;
-    const int rr = row_ok ? grow : H - 1;
-    const int o_lane = r & 3;
+    const bool row_ok = grow < H && (!second || pack_second);
+    const int rr = grow < H ? grow : H - 1;
+    const int o_lane = lane & 3;
+    auto from_above = [&](float v) -> float {
+        const float m = from_lane_above(v);
+        return PACK ? (top ? 0.0f : m) : m;
+    };
     const unsigned Wst = row_ok ? (unsigned)W : 0u;   // columns this lane may store
 
     // Element (ch, r, c) of this image, in solve coordinates, sits at
@@ -159,9 +171,15 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
         chan_lds[ch] = reinterpret_cast<char *>(lds_copy + cb);
     }
     constexpr int kStep = DIR ? -4 : 4;               // bytes per column in solve order
-    const int row0 = 4 * (DIR ? (H - 1 - rr) * W + (W - 1) : rr * W);   // byte offset of column 0
-    const int rowlo = DIR ? row0 - 4 * (W - 1) : row0;                   // lowest / highest byte offset
-    const int rowhi = DIR ? row0 : row0 + 4 * (W - 1);                   // inside this row
+    const int row0 = 4 * ((DIR ? (H - 1 - rr) * W + (W - 1) : rr * W) + (second ? pack_stride : 0));   // byte offset of column 0
+    // Lowest / highest byte offset a load may use: the ends of the row in global memory.  On an LDS tile
+    // the ends of the channel plane instead: a lane outside its row then reads some other row's element at
+    // row0 + 4 (t - r), an address whose bank differs from lane to lane like those of the lanes inside,
+    // whereas offsets clamped to the row ends (row * W: all in two banks when W is a multiple of 32) made
+    // every read a many-way bank conflict for as long as part of the wave was outside the image.
+    const int plane0 = 4 * (second ? pack_stride : 0);
+    const int rowlo = TILE ? plane0 : (DIR ? row0 - 4 * (W - 1) : row0);
+    const int rowhi = TILE ? plane0 + 4 * (H * W - 1) : (DIR ? row0 : row0 + 4 * (W - 1));
     auto clamp_row = [&](int off) -> unsigned { return (unsigned)(off < rowlo ? rowlo : (off > rowhi ? rowhi : off)); };
     auto ld = [&](int ch, unsigned off) -> float {
         return *reinterpret_cast<const float *>((TILE ? chan_lds[ch] : chan_src[ch]) + off);
@@ -279,7 +297,7 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
             float xn[C];
 #pragma unroll
             for (int o = 0; o < C; ++o)
-                xn[o] = own[o] + (BANDS ? from_lane_above_or(M[1][o], T[1][o]) : from_lane_above(T[1][o]));
+                xn[o] = own[o] + (BANDS ? from_lane_above_or(M[1][o], T[1][o]) : from_above(T[1][o]));
             if (BANDS) {        // after a lost wait NaN also travels on to the rows and bands below
 #pragma unroll
                 for (int o = 0; o < C; ++o)
@@ -301,7 +319,7 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
                 if (a + 1 < K) {
 #pragma unroll
                     for (int o = 0; o < C; ++o)
-                        acc[o] = BANDS ? from_lane_above_or(M[a + 1][o], T[a + 1][o]) : from_lane_above(T[a + 1][o]);
+                        acc[o] = BANDS ? from_lane_above_or(M[a + 1][o], T[a + 1][o]) : from_above(T[a + 1][o]);
                 }
 #pragma unroll
                 for (int db = K - 1; db >= 0; --db)     // oldest column first: only db = 0 waits for this step's result

@@ -77,6 +77,9 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     # large batches of small images: the image goes through LDS (forward and fused backward)
     (1400, 3, 16, 16, 3), (400, 3, 64, 24, 3), (2400, 1, 28, 28, 3), (700, 2, 50, 10, 3), (1500, 3, 15, 15, 3),
     (1200, 4, 16, 16, 3), (350, 3, 64, 32, 5), (3000, 3, 12, 8, 2),
+    (701, 3, 32, 32, 3), (1367, 3, 16, 32, 3), (2401, 1, 28, 28, 3), (685, 3, 32, 20, 5), (1000, 2, 24, 40, 3),   # two images per wave
+    (1401, 3, 32, 32, 3), (700, 3, 64, 32, 3), (1500, 3, 32, 28, 5),   # backward as separate launches (solve, then weight gradient)
+    (4099, 3, 8, 8, 3), (2500, 3, 32, 32, 3), (2302, 1, 28, 28, 3),   # waves that walk over several pairs of images
     # 8 / 12 channels, large batches or tall images: single-layer solves through the pipelined kernel
     (130, 12, 64, 64, 3), (26, 12, 100, 36, 3), (300, 8, 40, 24, 3), (40, 8, 128, 8, 3),
 ]
