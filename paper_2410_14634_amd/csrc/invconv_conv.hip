@@ -557,8 +557,17 @@ static unsigned launch_small_dw_tw(const float *g, const float *w, float *dx, co
     const int tiles_r = (H + kConvRows - 1) / kConvRows, tiles_c = (W + TW - 1) / TW;
     const size_t ntiles = (size_t)B * tiles_r * tiles_c;
     const size_t lds = conv_small_dw_lds<C, K, TW>();
-    const unsigned grid = dx ? conv_grid(ntiles)
-                             : (ntiles < (size_t)kConvMaxGridDw ? (unsigned)ntiles : (unsigned)kConvMaxGridDw);
+    unsigned grid = conv_grid(ntiles);
+    if (!dx) {
+        // as many workgroups as are resident at once (registers and LDS: five per compute unit for 3 channels),
+        // so that no second, partly filled round of workgroups follows the first
+        const void *fn = reinterpret_cast<const void *>(&k_conv_small<C, K, TW, true, 1, true, false>);
+        if (!ensure_dynamic_lds(fn, lds))
+            return 0;
+        const int resident = resident_workgroups(fn, 256, lds);
+        const size_t cap = resident > 0 && resident < kConvMaxGridDw ? (size_t)resident : (size_t)kConvMaxGridDw;
+        grid = ntiles < cap ? (unsigned)ntiles : (unsigned)cap;
+    }
     if (dx) {
         if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_conv_small<C, K, TW, true, 1, true>), lds))
             return 0;
