@@ -305,7 +305,7 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
     p.sxc = (rt + k - 1) * p.xw;
     {
         // bank conflicts of the B operand reads: lane (nn, kk) of instruction s reads
-        // i*sxc + a*xw + b + kk for column 16s + nn = (i, a, b); degree = most distinct addresses in one bank.
+        // i*sxc + a*xw + b + kk for column 16s + nn = (i, a, b); cost = cycles the read takes in the model below.
         // The search costs a fraction of a millisecond of host time, so the last few answers are remembered
         // per thread (a call may plan several kernel sizes of one shape).
         struct Memo { int C, k, rt, W, xw, sxc; };
@@ -319,25 +319,30 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
         Memo memo = hit ? *hit : Memo{0, 0, 0, 0, 0, 0};
         if (!hit) {
             const int ncol = C * k * k;
+            // LDS model (measured with strided 4-byte reads: stride 32 words costs as much as stride 64, and
+            // moving the upper 32 lanes by 64 words costs nothing): 32 banks of 4 bytes, a 64-lane read is
+            // served as two halves of 32 lanes, a half takes as many cycles as its fullest bank has distinct
+            // addresses.
             auto cost = [&](int xw, int sxc) {
                 int total = 0;
-                for (int s = 0; s < (int)NS; ++s) {
-                    int addr[64], per_bank[64] = {0};
-                    for (int l = 0; l < 64; ++l) {
-                        const int nn = l & 15, kk = l >> 4;
-                        const int col = 16 * s + nn < ncol ? 16 * s + nn : 0;
-                        addr[l] = (col / (k * k)) * sxc + ((col / k) % k) * xw + col % k + kk;
-                        bool seen = false;
-                        for (int m = 0; m < l; ++m)
-                            seen = seen || addr[m] == addr[l];
-                        if (!seen)
-                            ++per_bank[addr[l] % 64];
+                for (int s = 0; s < (int)NS; ++s)
+                    for (int half = 0; half < 2; ++half) {
+                        int addr[32], per_bank[32] = {0};
+                        for (int h = 0; h < 32; ++h) {
+                            const int l = 32 * half + h, nn = l & 15, kk = l >> 4;
+                            const int col = 16 * s + nn < ncol ? 16 * s + nn : 0;
+                            addr[h] = (col / (k * k)) * sxc + ((col / k) % k) * xw + col % k + kk;
+                            bool seen = false;
+                            for (int m = 0; m < h; ++m)
+                                seen = seen || addr[m] == addr[h];
+                            if (!seen)
+                                ++per_bank[addr[h] % 32];
+                        }
+                        int worst = 1;
+                        for (int bank = 0; bank < 32; ++bank)
+                            worst = per_bank[bank] > worst ? per_bank[bank] : worst;
+                        total += worst;
                     }
-                    int worst = 1;
-                    for (int bank = 0; bank < 64; ++bank)
-                        worst = per_bank[bank] > worst ? per_bank[bank] : worst;
-                    total += worst;
-                }
                 return total;
             };
             Memo m = {C, k, rt, W, p.xw, p.sxc};

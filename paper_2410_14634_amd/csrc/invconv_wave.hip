@@ -122,8 +122,9 @@ __global__ __launch_bounds__(64) void k_solve_wave_tile(const ST *__restrict__ i
 // Images of at most 32 rows leave half of the wave's lanes idle, and at large batches the solve is bound by
 // the instructions a SIMD can issue (27 matrix instructions of 8 clocks per step at C = k = 3, whatever
 // the number of rows): here a wave takes two neighbouring images, one per half (solve_wave_body with PACK).
-// The second tile sits kTilePackPad floats behind the end of the first, so that the two halves of a
-// 64-lane LDS access use different banks.
+// Lane r of either half reads word r (W - 1) + t of its tile: an odd stride, so the 32 lanes of a half,
+// which LDS serves on their own, fall into 32 different banks.  The second tile sits kTilePackPad floats
+// behind the end of the first.
 // LDS holds few such pairs per compute unit, too few waves to hide the copy in and out behind other
 // waves' solves, so a wave hides its own: it walks over pairs (pair = wave index + a multiple of the
 // number of waves launched) and fetches the next pair into registers while it solves the current one; after

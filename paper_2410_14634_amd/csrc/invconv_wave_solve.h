@@ -114,7 +114,8 @@ struct WaveBands {
 };
 
 // Columns of a row the ring holds (four chunks of kWavePF columns), and the distance between rows.  Lane r
-// reads column t - r at step t: bank (r * kRingStride + t - r) % 64 = (3r + t) % 64, distinct over the lanes;
+// reads column t - r at step t: word r * kRingStride + t - r, bank (3r + t) % 32, distinct over the 32 lanes
+// of either half of the wave (LDS has 32 banks of 4 bytes and serves a 64-lane access as two halves);
 // the 16-byte accesses of the filling and draining waves (16 rows, same columns) spread over all banks too.
 constexpr int kRingCols = 64;
 constexpr int kRingStride = 68;
@@ -175,7 +176,7 @@ __device__ __forceinline__ void solve_wave_body(const float *__restrict__ in, co
     // Lowest / highest byte offset a load may use: the ends of the row in global memory.  On an LDS tile
     // the ends of the channel plane instead: a lane outside its row then reads some other row's element at
     // row0 + 4 (t - r), an address whose bank differs from lane to lane like those of the lanes inside,
-    // whereas offsets clamped to the row ends (row * W: all in two banks when W is a multiple of 32) made
+    // whereas offsets clamped to the row ends (row * W: one bank when W is a multiple of 32) made
     // every read a many-way bank conflict for as long as part of the wave was outside the image.
     const int plane0 = 4 * (second ? pack_stride : 0);
     const int rowlo = TILE ? plane0 : (DIR ? row0 - 4 * (W - 1) : row0);
