@@ -26,6 +26,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 struct DwBatch {
     const float *x[kChainMaxLayers];
     const float *v[kChainMaxLayers];
+    // blocks of a result with more than 16 channels as the "layers" of one launch: channels of the x block and
+    // of the v block of entry l (0: the launch's C and Cv)
+    unsigned char cx[kChainMaxLayers];
+    unsigned char cv[kChainMaxLayers];
 };
 
 constexpr int kDwHalo = 4;      // left halo of the x tile, in columns (>= k-1, keeps rows 16-byte aligned)
@@ -40,11 +44,15 @@ constexpr size_t kDwStreamLdsBudget = 72 * 1024;   // streaming mode: two workgr
 template <int NS>
 __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *__restrict__ part, int B, int C,
                                                         int H, int W, int k, int RT, int nchunks, int G, int vec,
-                                                        int XW, int SXC, int SVC, int Cv, int Ctot)
+                                                        int XW, int SXC, int SVC, int Cv, int Ctot, int pstride)
 {
     extern __shared__ float smem[];
     // blockIdx = ((layer * B + n) * G + cg); this workgroup takes chunks cg, cg+G, ... of image n
     const int cg = blockIdx.x % G, n = (blockIdx.x / G) % B, layer = blockIdx.x / (G * B);
+    if (batch.cx[layer]) {      // a block of a larger result: its own channel counts (tiles are laid out for the launch's)
+        C = batch.cx[layer];
+        Cv = batch.cv[layer];
+    }
     const float *__restrict__ x = batch.x[layer];
     const float *__restrict__ v = batch.v[layer];
     // XW >= W + kDwHalo, SXC >= (RT + k - 1) * XW and SVC >= RT * W: row / channel strides padded by the
@@ -246,7 +254,7 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
         float sum = 0.0f;
         for (int wv = 0; wv < 4; ++wv)
             sum += sred[(wv * 64 + g * 16 + cn) * (NS * 4) + s * 4 + j];
-        part[(size_t)blockIdx.x * P + e] = sum;
+        part[(size_t)blockIdx.x * (pstride ? pstride : P) + e] = sum;
     }
 }
 
@@ -272,6 +280,8 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
         // the plan of one 16 x 16 block; the launches of the blocks follow each other and share the rows
         p = plan_dw_mfma(B, kDwChannelBlock, H, W, k);
         p.cb = p.rt ? kDwChannelBlock : 0;
+        const size_t nb = (size_t)((C + kDwChannelBlock - 1) / kDwChannelBlock);
+        p.bytes *= nb * nb;         // one set of partial rows per block: all blocks share a launch
         return p;
     }
     const size_t P = (size_t)C * C * k * k;
@@ -401,7 +411,7 @@ DwPlan plan_dw_mfma_layers(int layers, int B, int C, int H, int W, int k)
 // C = x channels of the block (= all channels without blocking), Cv = v channels, Ctot = channels of the tensors
 template <int NS>
 static bool launch_ns(const DwBatch &batch, int layers, float *part, const DwPlan &p, int B, int C, int H, int W,
-                      int k, hipStream_t stream, int Cv, int Ctot)
+                      int k, hipStream_t stream, int Cv, int Ctot, int pstride)
 {
     // 16-byte tile loads need rows that start on 16-byte boundaries
     int vec = (W % 4) == 0;
@@ -414,29 +424,30 @@ static bool launch_ns(const DwBatch &batch, int layers, float *part, const DwPla
     if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_dw_partial_mfma<NS>), p.lds))
         return false;
     hipLaunchKernelGGL(k_dw_partial_mfma<NS>, dim3((unsigned)(p.nparts * layers)), dim3(256), p.lds, stream, batch,
-                       part, B, C, H, W, k, p.rt, p.nchunks, p.groups, vec, p.xw, p.sxc, p.svc, Cv, Ctot);
+                       part, B, C, H, W, k, p.rt, p.nchunks, p.groups, vec, p.xw, p.sxc, p.svc, Cv, Ctot, pstride);
     return true;
 }
 
 // Pass 1 for `layers` independent (x, v) pairs in one launch; part holds layers * p.nparts rows.
 static int launch_dw_partial_batch(const DwBatch &batch, int layers, float *part, const DwPlan &p, int B, int C,
-                                   int H, int W, int k, hipStream_t stream, int Cv = 0, int Ctot = 0)
+                                   int H, int W, int k, hipStream_t stream, int Cv = 0, int Ctot = 0,
+                                   int pstride = 0)
 {
     Cv = Cv ? Cv : C;
     Ctot = Ctot ? Ctot : C;
     const int ns = (C * k * k + 15) / 16;
     bool ok = false;
     switch (ns) {
-    case 1: ok = launch_ns<1>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
-    case 2: ok = launch_ns<2>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
-    case 3: ok = launch_ns<3>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
-    case 4: ok = launch_ns<4>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
-    case 5: ok = launch_ns<5>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
-    case 6: ok = launch_ns<6>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
-    case 7: ok = launch_ns<7>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
-    case 8: ok = launch_ns<8>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
-    case 9: ok = launch_ns<9>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
-    case 10: ok = launch_ns<10>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot); break;
+    case 1: ok = launch_ns<1>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot, pstride); break;
+    case 2: ok = launch_ns<2>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot, pstride); break;
+    case 3: ok = launch_ns<3>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot, pstride); break;
+    case 4: ok = launch_ns<4>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot, pstride); break;
+    case 5: ok = launch_ns<5>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot, pstride); break;
+    case 6: ok = launch_ns<6>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot, pstride); break;
+    case 7: ok = launch_ns<7>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot, pstride); break;
+    case 8: ok = launch_ns<8>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot, pstride); break;
+    case 9: ok = launch_ns<9>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot, pstride); break;
+    case 10: ok = launch_ns<10>(batch, layers, part, p, B, C, H, W, k, stream, Cv, Ctot, pstride); break;
     default: return INVCONV_ERR_UNSUPPORTED;
     }
     if (!ok)
@@ -449,19 +460,28 @@ int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const
 {
     DwBatch batch{};
     if (p.cb) {
-        // more than 16 channels: one pass 1 + pass 2 per block of output x input channels
+        // More than 16 channels: the result is cut into blocks of at most 16 output x 16 input channels.  All
+        // blocks (at most 16: C <= 64) are the "layers" of ONE first pass and ONE second pass; a launch pair
+        // per block made the weight gradient of 48 x 8 x 8 images eighteen launches of a few microseconds.
         const size_t plane = (size_t)H * W;
+        DwBlocks blocks{};
+        const int pstride = p.cb * p.cb * k * k;
         for (int o0 = 0; o0 < C; o0 += p.cb)
             for (int i0 = 0; i0 < C; i0 += p.cb) {
                 const int Cv = C - o0 < p.cb ? C - o0 : p.cb, Cx = C - i0 < p.cb ? C - i0 : p.cb;
-                batch.x[0] = x + i0 * plane;
-                batch.v[0] = v + o0 * plane;
-                if (int s = launch_dw_partial_batch(batch, 1, part, p, B, Cx, H, W, k, stream, Cv, C))
-                    return s;
-                if (int s = launch_dw_reduce_block(part, (int)p.nparts, dw, Cv, Cx, o0, i0, C, k, stream, sign))
-                    return s;
+                const int l = blocks.n++;
+                if (l >= kChainMaxLayers)
+                    return INVCONV_ERR_UNSUPPORTED;
+                batch.x[l] = x + i0 * plane;
+                batch.v[l] = v + o0 * plane;
+                batch.cx[l] = blocks.cx[l] = (unsigned char)Cx;
+                batch.cv[l] = blocks.cv[l] = (unsigned char)Cv;
+                blocks.o0[l] = (unsigned char)o0;
+                blocks.i0[l] = (unsigned char)i0;
             }
-        return INVCONV_OK;
+        if (int s = launch_dw_partial_batch(batch, blocks.n, part, p, B, p.cb, H, W, k, stream, p.cb, C, pstride))
+            return s;
+        return launch_dw_reduce_blocks(part, (int)p.nparts, dw, blocks, C, k, pstride, stream, sign);
     }
     batch.x[0] = x;
     batch.v[0] = v;

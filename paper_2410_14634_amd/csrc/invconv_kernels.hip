@@ -412,6 +412,49 @@ __global__ __launch_bounds__(64 * NW) void k_dw_reduce(const float *__restrict__
     }
 }
 
+// The same second pass for the blocks of a result with more than 16 channels, all in one launch: blockIdx.y
+// selects the block (its channel counts and its place in the result come from `blocks`).
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void k_dw_reduce_blocks(const float *__restrict__ part_all, int nparts,
+                                                             float *__restrict__ dw, DwBlocks blocks, int Ctot, int k,
+                                                             int pstride, float sign)
+{
+    __shared__ double swave[NW][64];
+    const int y = blockIdx.y;
+    const int Cv = blocks.cv[y], C = blocks.cx[y], o0 = blocks.o0[y], i0 = blocks.i0[y];
+    const int P = Cv * C * k * k;
+    const float *__restrict__ part = part_all + (size_t)y * nparts * pstride;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int e = blockIdx.x * 64 + lane;
+    double acc = 0.0;
+    if (e < P) {
+        // rows wave, wave + NW, ... in index order, eight loads in flight (addresses clamped, rows past the end
+        // count as zero)
+        for (int p = wave; p < nparts; p += 8 * NW) {
+            float a[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = p + NW * u;
+                a[u] = part[(size_t)(r < nparts ? r : nparts - 1) * pstride + e];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                acc += p + NW * u < nparts ? (double)a[u] : 0.0;
+        }
+    }
+    swave[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && e < P) {
+        double total = swave[0][lane];
+#pragma unroll
+        for (int v = 1; v < NW; ++v)
+            total += swave[v][lane];
+        const int b = e % k, a = (e / k) % k, i = i0 + (e / (k * k)) % C, o = o0 + e / (k * k * C);
+        const bool is_masked = (a == k - 1 && b == k - 1 && i > o);
+        dw[((o * Ctot + i) * k + a) * k + b] = is_masked ? 0.0f : (float)(sign < 0.0f ? -total : total);
+    }
+}
+
 // log|det dx/dy| for one image (Section 4): -H*W*sum_c log|w[c][c][k-1][k-1]|.
 // One wave; lane l takes channels l, l+64, ...; fixed butterfly across lanes.
 // blockIdx.x selects the layer: kernel ws.p[l], result out[l].
@@ -622,6 +665,21 @@ int launch_dw_reduce_block(const float *part, int nparts, float *dw, int Cv, int
     else
         hipLaunchKernelGGL(k_dw_reduce<4>, dim3((P + 63) / 64, 1), dim3(256), 0, stream, part, nparts, out, Cx, k, sign,
                            Cv, o0, i0, Ctot);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+int launch_dw_reduce_blocks(const float *part, int nparts, float *dw, const DwBlocks &blocks, int Ctot, int k,
+                            int pstride, hipStream_t stream, float sign)
+{
+    if (blocks.n < 1 || blocks.n > kChainMaxLayers)
+        return INVCONV_ERR_SHAPE;
+    const dim3 grid((pstride + 63) / 64, blocks.n);
+    if (nparts >= 512)
+        hipLaunchKernelGGL(k_dw_reduce_blocks<16>, grid, dim3(1024), 0, stream, part, nparts, dw, blocks, Ctot, k, pstride,
+                           sign);
+    else
+        hipLaunchKernelGGL(k_dw_reduce_blocks<4>, grid, dim3(256), 0, stream, part, nparts, dw, blocks, Ctot, k, pstride,
+                           sign);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

@@ -98,6 +98,15 @@ int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int
                             hipStream_t stream, float sign = -1.0f);
 int launch_dw_reduce_block(const float *part, int nparts, float *dw, int Cv, int Cx, int o0, int i0, int Ctot, int k,
                            hipStream_t stream, float sign = -1.0f);
+// Blocks of a result with more than 16 channels reduced by one launch: block l holds cv[l] x cx[l] k k entries per row
+// (rows pstride floats apart, block l's rows start at part + l * nparts * pstride) that go to output channels
+// o0[l] .. and input channels i0[l] .. of the Ctot-channel result.
+struct DwBlocks {
+    int n;
+    unsigned char cv[kChainMaxLayers], cx[kChainMaxLayers], o0[kChainMaxLayers], i0[kChainMaxLayers];
+};
+int launch_dw_reduce_blocks(const float *part, int nparts, float *dw, const DwBlocks &blocks, int Ctot, int k,
+                            int pstride, hipStream_t stream, float sign = -1.0f);
 int launch_logdet_layers(const float *const *w, int layers, int C, int H, int W, int k, float *out,
                          hipStream_t stream);
 struct ChainArgs {

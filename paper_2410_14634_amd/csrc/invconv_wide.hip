@@ -30,13 +30,26 @@ __host__ __device__ constexpr int wide_out_blocks(int C) { return (C + 15) / 16;
 
 // Weight preparation of a workgroup: sWt[tap][out (padded to whole blocks of 16)][in, row stride C + 1] = Linv for
 // tap 0 and -Linv W_tap for the others, from oriented, masked kernel entries read straight from global memory.
-// scratch: 3 C C floats.  Ends with a barrier.
+// The eight products Linv W_tap (C^3 multiply-adds each) run on the matrix cores, four taps at a time: a task is
+// one 16 x 16 block of one product, the waves take tasks round robin, and since Linv is lower triangular a
+// block of rows 16 ob .. needs only the first 4 (ob + 1) of the C/4 instructions.  Operands come from LDS with
+// one 4-byte read each: Linv[o][j] with an odd row stride (the 16 rows of an A read in different banks) and
+// W_tap[j][i] with a row stride of 48 (the two k-slots of a half-wave 16 banks apart).
+// scratch: wide_fold_scratch_floats(C) floats.  Ends with a barrier.
+constexpr int kWideTapStride = 48;      // row stride of the staged taps: C <= 48, and 48 mod 32 = 16
+__host__ __device__ constexpr size_t wide_fold_scratch_floats(int C)
+{
+    return (size_t)C * C + (size_t)16 * wide_out_blocks(C) * (C + 1) + (size_t)4 * C * kWideTapStride;
+}
+
 template <int CQ, int DIR>
 __device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, float *sWt, float *scratch)
 {
     constexpr int C = 4 * CQ, K = kWideK, NT = K * K;
     constexpr int OB = wide_out_blocks(C), OR = 16 * OB, CPAD = C + 1;
-    float *sL = scratch, *sLinv = scratch + C * C, *sTap = scratch + 2 * C * C;
+    constexpr int LP = C + 1, TP = kWideTapStride;
+    static_assert(C <= TP && OR <= TP && NT == 9, "tap staging is laid out for at most 48 channels, 3 x 3 taps");
+    float *sL = scratch, *sLinv = sL + C * C, *sTap = sLinv + OR * LP;       // [C][C], [OR][LP], [4][C][TP]
     const int tid = threadIdx.x, nt = blockDim.x;
     auto entry = [&](int tp, int o, int i) -> float {
         const int a = K - 1 - tp / K, b = K - 1 - tp % K;
@@ -44,8 +57,35 @@ __device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, f
         const float v = w[((oo * C + ii) * K + a) * K + b];
         return (tp == 0 && ii > oo) ? 0.0f : v;
     };
+    // four taps into LDS, sixteen loads of a thread in flight; columns C .. TP-1 and the rows of Linv past C are
+    // zeros (they feed padding rows and columns of the blocks)
+    auto stage = [&](int tp0) {
+        for (int base = tid; base < 4 * C * C; base += 16 * nt) {
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int idx = base + u * nt;
+                const int q = idx / (C * C), e = idx % (C * C);
+                v[u] = idx < 4 * C * C ? entry(tp0 + q, e / C, e % C) : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int idx = base + u * nt;
+                const int q = idx / (C * C), e = idx % (C * C);
+                if (idx < 4 * C * C)
+                    sTap[(q * C + e / C) * TP + e % C] = v[u];
+            }
+        }
+    };
     for (int idx = tid; idx < C * C; idx += nt)
         sL[idx] = entry(0, idx / C, idx % C);
+    if constexpr (C < TP) {
+        for (int idx = tid; idx < 4 * C * (TP - C); idx += nt)
+            sTap[(idx / (TP - C)) * TP + C + idx % (TP - C)] = 0.0f;
+    }
+    for (int idx = tid; idx < (OR - C) * LP; idx += nt)
+        sLinv[C * LP + idx] = 0.0f;
+    stage(1);
     __syncthreads();
     // Inverse of the lower-triangular block, column j by thread j, the column in registers: every thread runs
     // the same fully unrolled substitution (entries above the diagonal are zeros that take part in the sums),
@@ -55,76 +95,87 @@ __device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, f
         float col[C];
 #pragma unroll
         for (int o = 0; o < C; ++o) {
-            float sum = 0.0f;
+            // the row in 16-byte pieces, four partial sums (a single chain of dependent multiply-adds took 6 us
+            // at 48 channels)
+            float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            float diag = 1.0f;
 #pragma unroll
-            for (int m = 0; m < o; ++m)
-                sum += sL[o * C + m] * col[m];
-            const float rd = 1.0f / sL[o * C + o];
+            for (int m4 = 0; m4 <= o / 4; ++m4) {
+                const f32x4 row = *reinterpret_cast<const f32x4 *>(sL + o * C + 4 * m4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (4 * m4 + e < o)
+                        part[e] += row[e] * col[4 * m4 + e];
+                    else if (4 * m4 + e == o)
+                        diag = row[e];
+                }
+            }
+            const float sum = (part[0] + part[1]) + (part[2] + part[3]);
+            const float rd = 1.0f / diag;
             col[o] = o < j ? 0.0f : (o == j ? rd : -sum * rd);
         }
         if (tid < C) {
 #pragma unroll
             for (int o = 0; o < C; ++o)
-                sLinv[o * C + j] = col[o];
+                sLinv[o * LP + j] = col[o];
         }
     }
     __syncthreads();
-    // The oriented entries of a tap are fetched one tap ahead into registers, so that no global-memory round trip
-    // lies between two taps, and the product Linv W_tap is formed four input channels at a time (one read of
-    // Linv[o][j] and one 16-byte read of W_tap[j][i .. i+3] for four multiply-adds).
-    constexpr int NPT = (C * C + 127) / 128;        // entries per thread: a workgroup has at least two waves
-    float pre[NPT];
-    auto fetch = [&](int tp) {
+    for (int it = tid; it < OR * C; it += nt) {
+        const int o = it / C, i = it % C;
+        sWt[o * CPAD + i] = sLinv[o * LP + i];      // tap 0 (rows past C: zeros)
+    }
+    const int wave = tid >> 6, lane = tid & 63, nwv = nt >> 6, n = lane & 15, g = lane >> 4;
+    // taps 5 .. 8 travel from memory while the matrix cores work on taps 1 .. 4 (a workgroup has at least OB waves)
+    constexpr int NPRE = (4 * C * C + 64 * OB - 1) / (64 * OB);
+    float pre[NPRE];
 #pragma unroll
-        for (int q = 0; q < NPT; ++q) {
-            const int idx = tid + q * nt;
-            pre[q] = idx < C * C ? entry(tp, idx / C, idx % C) : 0.0f;
-        }
-    };
-    fetch(1);
-    for (int tp = 0; tp < NT; ++tp) {
-        if (tp > 0) {
+    for (int u = 0; u < NPRE; ++u) {
+        const int idx = tid + u * nt;
+        const int q = idx / (C * C), e = idx % (C * C);
+        pre[u] = idx < 4 * C * C ? entry(5 + q, e / C, e % C) : 0.0f;
+    }
+    for (int half = 0; half < 2; ++half) {
+        if (half) {
 #pragma unroll
-            for (int q = 0; q < NPT; ++q) {
-                const int idx = tid + q * nt;
-                if (idx < C * C)
-                    sTap[idx] = pre[q];
+            for (int u = 0; u < NPRE; ++u) {
+                const int idx = tid + u * nt;
+                const int q = idx / (C * C), e = idx % (C * C);
+                if (idx < 4 * C * C)
+                    sTap[(q * C + e / C) * TP + e % C] = pre[u];
             }
             __syncthreads();
         }
-        if (tp + 1 < NT)
-            fetch(tp + 1);
-        for (int it = tid; it < OR * CQ; it += nt) {
-            const int o = it / CQ, i0 = 4 * (it % CQ);
-            f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (o < C) {
-                if (tp == 0) {
-                    v = *reinterpret_cast<const f32x4 *>(sLinv + o * C + i0);
-                } else {
-                    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-                    // (rows of Linv are zero beyond the diagonal, so whole groups of eight terms can be
-                    // summed: the reads of a group are issued together)
-                    const int jend = (o + 8) & ~7;
-                    for (int j0 = 0; j0 < jend && j0 < C; j0 += 8) {
-                        float l[8];
-                        f32x4 tv[8];
+        for (int task = wave; task < 4 * OB * OB; task += nwv) {
+            const int q = task / (OB * OB), ob = (task / OB) % OB, ib = task % OB;
+            const float *ap = sLinv + (16 * ob + n) * LP + g;           // A[m = n][k = g] = Linv[16 ob + n][4 c + g]
+            const float *bp = sTap + (q * C + g) * TP + 16 * ib + n;    // B[k = g][n] = W[4 c + g][16 ib + n]
+            const int nc = 4 * (ob + 1) < CQ ? 4 * (ob + 1) : CQ;
+            f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+            // four instructions' operands are read together, ahead of the instructions (past nc: a valid address,
+            // a zero B operand)
+            for (int c = 0; c < nc; c += 4) {
+                float a[4], b[4];
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            const int j = j0 + e < C ? j0 + e : C - 1;
-                            l[e] = j0 + e < C ? sLinv[o * C + j] : 0.0f;
-                            tv[e] = *reinterpret_cast<const f32x4 *>(sTap + j * C + i0);
-                        }
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            acc += l[e] * tv[e];
-                    }
-                    v = -acc;
+                for (int u = 0; u < 4; ++u) {
+                    const int cc = c + u < nc ? c + u : nc - 1;
+                    a[u] = ap[4 * cc];
+                    const float bv = bp[4 * cc * TP];
+                    b[u] = c + u < nc ? bv : 0.0f;
                 }
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], b[0], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], b[1], acc1, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], b[2], acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], b[3], acc1, 0, 0, 0);
             }
-            float *dst = sWt + tp * OR * CPAD + o * CPAD + i0;
+            const f32x4 acc = acc0 + acc1;
+            // D[m = 4 g + j][n]: rows 16 ob + 4 g + j, column 16 ib + n
+            if (16 * ib + n < C) {
+                float *dst = sWt + ((1 + 4 * half + q) * OR + 16 * ob + 4 * g) * CPAD + 16 * ib + n;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                dst[e] = v[e];
+                for (int j = 0; j < 4; ++j)
+                    dst[j * CPAD] = -acc[j];
+            }
         }
         __syncthreads();
     }
@@ -293,7 +344,7 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
     constexpr int CP = C + wide_vec<CQ>();      // row of the rings: a multiple of the vector width, odd in vectors
     extern __shared__ float smem[];
     const int HP = 16 * NB + K - 1, YR = 16 * NB;
-    float *sWt = smem;                          // set-up: [NT][OR][CPAD], then 3 C C floats of scratch
+    float *sWt = smem;                          // set-up: [NT][OR][CPAD], then the scratch of the weight preparation
     float *ring = smem;                         // run: [R][HP][CP], permuted channels
     float *ybuf = ring + R * HP * CP;           // run: [2][YR][CP], the input of this and of the next step
     int *sflag = reinterpret_cast<int *>(ybuf + 2 * YR * CP);      // run: [waves] steps finished
@@ -350,10 +401,18 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
                     dst[q] = yv[q];
         }
     };
+    // Small images need few waves for the solve (bands x blocks of output channels) but the set-up above is
+    // work for many threads (C^3 multiply-adds per tap), so the launch may bring more waves than the solve
+    // uses: they have helped up to here and leave after this barrier, the last one of the kernel.
+    const int nw = NB * OB;
     float ynext[4];
-    load_y(0, ynext);
-    store_y(0, ynext);
+    if (wave < nw) {
+        load_y(0, ynext);
+        store_y(0, ynext);
+    }
     __syncthreads();
+    if (wave >= nw)
+        return;
 
     // Of the nine taps only three need the step just finished: Linv y (tap 0), (0,1) and (1,0).  The other six
     // read results at least two steps old, so their 6 C/4 products for step t + 1 are issued during step t,
@@ -366,7 +425,6 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
     // that reached it would write NaN).
     constexpr int kCrit[3] = {0, 1, 3};
     constexpr int kPre[6] = {2, 4, 5, 6, 7, 8};
-    const int nw = nt >> 6;
     bool lost = false;
     const int nsteps = H + W - 1;
     int tm = 0;                                                 // t mod R
@@ -465,7 +523,7 @@ static size_t wide_reg_lds_bytes(int C, int H)
 {
     const size_t NB = (H + 15) / 16, OR = 16 * (size_t)wide_out_blocks(C), CPAD = C + 1;
     const size_t CQ = C / 4, CP = C + (CQ % 4 == 0 ? 4 : (CQ % 2 == 0 ? 2 : 1));
-    const size_t setup = (size_t)kWideK * kWideK * OR * CPAD + 3 * (size_t)C * C;
+    const size_t setup = (size_t)kWideK * kWideK * OR * CPAD + wide_fold_scratch_floats(C);
     const size_t run = ((size_t)kWideRing * (16 * NB + kWideK - 1) + 2 * 16 * NB) * CP + 16;
     return sizeof(float) * (setup > run ? setup : run);
 }
@@ -488,7 +546,12 @@ static int launch_wide_reg(int dir, const float *in, const float *w, float *out,
                          : reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 0, MAXW>);
     if (!ensure_dynamic_lds(fn, lds))
         return INVCONV_ERR_UNSUPPORTED;
-    const dim3 block((unsigned)(64 * NB * wide_out_blocks(C)));
+    // up to one workgroup per compute unit: eight waves at least, the ones the solve does not use help with the
+    // set-up (48 x 8 x 8, B = 100: 70 -> 50 us); more workgroups than that are better off with more of them resident
+    int waves = NB * wide_out_blocks(C);
+    if (B <= 256 && waves < 8)
+        waves = 8 < MAXW ? 8 : MAXW;
+    const dim3 block((unsigned)(64 * waves));
     if (dir)
         hipLaunchKernelGGL((k_solve_wide_reg<CQ, 1, MAXW>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet);
     else
@@ -499,7 +562,7 @@ static int launch_wide_reg(int dir, const float *in, const float *w, float *out,
 static size_t wide_lds_bytes(int C, int H)
 {
     const size_t NB = (H + 15) / 16, OR = 16 * (size_t)wide_out_blocks(C), CPAD = C + 1;
-    const size_t ring = (size_t)kWideRing * (16 * NB + kWideK - 1) * CPAD, scratch = 3 * (size_t)C * C;
+    const size_t ring = (size_t)kWideRing * (16 * NB + kWideK - 1) * CPAD, scratch = wide_fold_scratch_floats(C);
     return sizeof(float) * ((size_t)kWideK * kWideK * OR * CPAD + (ring > scratch ? ring : scratch));
 }
 
