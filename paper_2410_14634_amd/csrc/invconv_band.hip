@@ -23,6 +23,7 @@
 // next band through a small LDS ring.
 #include "invconv_common.h"
 #include "invconv_launch.h"
+#include <type_traits>
 
 namespace invconv {
 
@@ -39,8 +40,10 @@ constexpr int kBandPF = 8;      // steps of load prefetch
 constexpr int kBandDelay = 1;   // extra steps a band lags behind the band above
 constexpr int kRing = 4;        // depth of the band-to-band message ring
 
-template <int CG, int K, int DIR>
-__global__ __launch_bounds__(512) void k_solve_band(const float *__restrict__ in, const float *__restrict__ w,
+// MAXT: the most threads a launch may have (512 for k = 3; the folded taps of larger kernels need the registers
+// of a workgroup of at most four waves).
+template <int CG, int K, int DIR, int MAXT = 512>
+__global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ in, const float *__restrict__ w,
                                                     float *__restrict__ out, int H, int W, int NB, float *logdet)
 {
     constexpr int C = 4 * CG;
@@ -469,9 +472,17 @@ size_t solve_band_lds_bytes(int C, int k, int NB)
     return sizeof(float) * (2 * (size_t)C * C + 2 * (size_t)k * k * C * C + (size_t)NB * kRing * k * 64);
 }
 
+// k = 3: at most 8 bands = 512 threads.  Other kernel sizes of the paper's kernel-size ablation (2, 5; 7 up to 12
+// channels) run on the general kernel with at most four bands: a lane then keeps C k^2 / 4 folded taps in registers
+// (147 at 12 channels, k = 7), which k = 9 and 11 do not have.
 bool band_supported(int C, int H, int k)
 {
-    return (C == 8 || C == 12 || C == 16) && k == 3 && H <= 128;   // at most 8 bands = 512 threads
+    if (!(C == 8 || C == 12 || C == 16))
+        return false;
+    if (k == 3)
+        return H <= 128;
+    const bool size_ok = k == 2 || k == 5 || (k == 7 && C <= 12);
+    return size_ok && H <= 64 && solve_band_lds_bytes(C, k, (H + 15) / 16) <= kMaxLdsBytes;
 }
 
 template <int CG, int K>
@@ -489,12 +500,21 @@ static int launch_band_ck(int dir, const float *in, const float *w, float *out, 
         return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
     }
     const size_t lds = solve_band_lds_bytes(4 * CG, K, NB);
+    constexpr int MAXT = K == 3 ? 512 : 256;
     // a single band gets three helper waves for the weight preparation (its loop has no barriers)
     const int threads = NB == 1 ? 256 : 64 * NB;
+    if (threads > MAXT)
+        return INVCONV_ERR_VARIANT;
+    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_band<CG, K, 1, MAXT>)
+                         : reinterpret_cast<const void *>(&k_solve_band<CG, K, 0, MAXT>);
+    if (!ensure_dynamic_lds(fn, lds))
+        return INVCONV_ERR_UNSUPPORTED;
     if (dir)
-        hipLaunchKernelGGL((k_solve_band<CG, K, 1>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB, logdet);
+        hipLaunchKernelGGL((k_solve_band<CG, K, 1, MAXT>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB,
+                           logdet);
     else
-        hipLaunchKernelGGL((k_solve_band<CG, K, 0>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB, logdet);
+        hipLaunchKernelGGL((k_solve_band<CG, K, 0, MAXT>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB,
+                           logdet);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
@@ -503,9 +523,19 @@ int launch_solve_band(int dir, const float *in, const float *w, float *out, int 
 {
     if (!band_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
-    if (C == 8) return launch_band_ck<2, 3>(dir, in, w, out, B, H, W, stream, logdet);
-    if (C == 12) return launch_band_ck<3, 3>(dir, in, w, out, B, H, W, stream, logdet);
-    if (C == 16) return launch_band_ck<4, 3>(dir, in, w, out, B, H, W, stream, logdet);
+    auto by_k = [&](auto cg_tag) -> int {
+        constexpr int CG = decltype(cg_tag)::value;
+        if (k == 3) return launch_band_ck<CG, 3>(dir, in, w, out, B, H, W, stream, logdet);
+        if (k == 2) return launch_band_ck<CG, 2>(dir, in, w, out, B, H, W, stream, logdet);
+        if (k == 5) return launch_band_ck<CG, 5>(dir, in, w, out, B, H, W, stream, logdet);
+        if constexpr (CG <= 3) {
+            if (k == 7) return launch_band_ck<CG, 7>(dir, in, w, out, B, H, W, stream, logdet);
+        }
+        return INVCONV_ERR_VARIANT;
+    };
+    if (C == 8) return by_k(std::integral_constant<int, 2>());
+    if (C == 12) return by_k(std::integral_constant<int, 3>());
+    if (C == 16) return by_k(std::integral_constant<int, 4>());
     return INVCONV_ERR_VARIANT;
 }
 

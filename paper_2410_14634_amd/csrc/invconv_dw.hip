@@ -259,32 +259,31 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
 }
 
 constexpr int kDwChannelBlock = 16;
+constexpr int kDwMaxNs = 10;        // accumulators (blocks of 16 columns) a wave holds
 
-// up to 16 channels: one GEMM; up to 64: blocks of 16 x 16 channels (the column count of a block, 16 k k,
-// has to fit the ten accumulators: k <= 3)
-bool dw_mfma_supported(int C, int k)
+// Input channels of one block of the result: their Cx k k "shifted x" columns have to fit the accumulators
+// (16 channels up to k = 3, 6 at k = 5), and a block has at most 16 of them.
+static int dw_x_block(int C, int k)
 {
-    const int cx = C <= kDwChannelBlock ? C : kDwChannelBlock;
-    const int ns = (cx * k * k + 15) / 16;
-    return C <= 64 && ns >= 1 && ns <= 10;
+    int cx = (16 * kDwMaxNs) / (k * k);
+    cx = cx > kDwChannelBlock ? kDwChannelBlock : cx;
+    return cx > C ? C : cx;
 }
 
-// Row chunking of pass 1: tiles (or the reduction buffer that reuses them) must fit the LDS budget.
-// p.nparts = B * G partial rows per layer, G workgroups per image each looping over chunks.
-DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
+// one GEMM up to 16 channels when the columns fit; otherwise blocks of (at most 16 output) x (dw_x_block input)
+// channels, all blocks in one launch
+bool dw_mfma_supported(int C, int k)
+{
+    return C >= 1 && C <= 64 && k >= 1 && k - 1 <= kDwHalo && dw_x_block(C, k) >= 1;
+}
+
+// Row chunking of pass 1 for one block of Cv output x Cx input channels: tiles (or the reduction buffer that reuses
+// them) must fit the LDS budget.  p.nparts = B * G partial rows per block, G workgroups per image each looping over chunks.
+static DwPlan plan_dw_mfma_block(int B, int Cv, int C, int H, int W, int k)
 {
     DwPlan p{};
-    if (!dw_mfma_supported(C, k) || k - 1 > kDwHalo)
-        return p;
-    if (C > kDwChannelBlock) {
-        // the plan of one 16 x 16 block; the launches of the blocks follow each other and share the rows
-        p = plan_dw_mfma(B, kDwChannelBlock, H, W, k);
-        p.cb = p.rt ? kDwChannelBlock : 0;
-        const size_t nb = (size_t)((C + kDwChannelBlock - 1) / kDwChannelBlock);
-        p.bytes *= nb * nb;         // one set of partial rows per block: all blocks share a launch
-        return p;
-    }
-    const size_t P = (size_t)C * C * k * k;
+    const int CM = Cv > C ? Cv : C;
+    const size_t P = (size_t)Cv * C * k * k;
     const size_t NS = ((size_t)C * k * k + 15) / 16;
     const size_t red = 256 * NS * 4;
     // strides: v rows stay contiguous, its channel stride is 4 (mod 64) so that the 16 output channels of
@@ -294,7 +293,7 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
         return base + ((4 - base % 64) + 64) % 64;
     };
     auto lds_with = [&](int rt, int xw, int sxc) {
-        const size_t tiles = (size_t)C * svc_for(rt) + (size_t)C * sxc;
+        const size_t tiles = (size_t)CM * svc_for(rt) + (size_t)C * sxc;
         return sizeof(float) * (tiles > red ? tiles : red);
     };
     auto lds_for = [&](int rt) { return lds_with(rt, W + kDwHalo, (rt + k - 1) * (W + kDwHalo)); };
@@ -306,7 +305,7 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
     if (lds_for(1) > budget)
         return p;
     int rt = H < 8 ? H : 8;
-    while (rt > 1 && (lds_for(rt) > budget || (stream_shape && rt > k - 1 && C * rt * (W / 4) > 256 * kDwPre)))
+    while (rt > 1 && (lds_for(rt) > budget || (stream_shape && rt > k - 1 && CM * rt * (W / 4) > 256 * kDwPre)))
         --rt;
     p.rt = rt;
     p.nchunks = (H + rt - 1) / rt;
@@ -324,7 +323,7 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
         static thread_local int memo_next = 0;
         Memo *hit = nullptr;
         for (int m = 0; m < kMemos; ++m)
-            if (memos[m].C == C && memos[m].k == k && memos[m].rt == rt && memos[m].W == W)
+            if (memos[m].C == 100 * Cv + C && memos[m].k == k && memos[m].rt == rt && memos[m].W == W)
                 hit = &memos[m];
         Memo memo = hit ? *hit : Memo{0, 0, 0, 0, 0, 0};
         if (!hit) {
@@ -355,7 +354,7 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
                     }
                 return total;
             };
-            Memo m = {C, k, rt, W, p.xw, p.sxc};
+            Memo m = {100 * Cv + C, k, rt, W, p.xw, p.sxc};
             int best = cost(p.xw, p.sxc);
             for (int rp = 0; rp <= 12; rp += 4)
                 for (int cp = 0; cp <= 60; cp += 4) {
@@ -387,6 +386,23 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
     p.nparts = (size_t)B * g;
     p.lds = lds_with(rt, p.xw, p.sxc);
     p.bytes = ((p.nparts * P * sizeof(float)) + 255) / 256 * 256;
+    return p;
+}
+
+DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
+{
+    if (!dw_mfma_supported(C, k))
+        return DwPlan{};
+    const int cbv = C < kDwChannelBlock ? C : kDwChannelBlock, cbx = dw_x_block(C, k);
+    if (cbv == C && cbx == C)
+        return plan_dw_mfma_block(B, C, C, H, W, k);        // one GEMM
+    // blocks of cbv output x cbx input channels: the plan of one block; up to kChainMaxLayers blocks share a
+    // launch, each with its own partial rows
+    DwPlan p = plan_dw_mfma_block(B, cbv, cbx, H, W, k);
+    p.cb = p.rt ? cbv : 0;
+    p.cbx = cbx;
+    const size_t nblocks = (size_t)((C + cbv - 1) / cbv) * ((C + cbx - 1) / cbx);
+    p.bytes *= nblocks < (size_t)kChainMaxLayers ? nblocks : (size_t)kChainMaxLayers;
     return p;
 }
 
@@ -465,23 +481,32 @@ int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const
         // per block made the weight gradient of 48 x 8 x 8 images eighteen launches of a few microseconds.
         const size_t plane = (size_t)H * W;
         DwBlocks blocks{};
-        const int pstride = p.cb * p.cb * k * k;
+        const int pstride = p.cb * p.cbx * k * k;
+        auto flush = [&]() -> int {
+            if (!blocks.n)
+                return INVCONV_OK;
+            if (int s = launch_dw_partial_batch(batch, blocks.n, part, p, B, p.cbx, H, W, k, stream, p.cb, C, pstride))
+                return s;
+            if (int s = launch_dw_reduce_blocks(part, (int)p.nparts, dw, blocks, C, k, pstride, stream, sign))
+                return s;
+            blocks.n = 0;       // (launches of one stream run in order: the next group may reuse the partial rows)
+            return INVCONV_OK;
+        };
         for (int o0 = 0; o0 < C; o0 += p.cb)
-            for (int i0 = 0; i0 < C; i0 += p.cb) {
-                const int Cv = C - o0 < p.cb ? C - o0 : p.cb, Cx = C - i0 < p.cb ? C - i0 : p.cb;
+            for (int i0 = 0; i0 < C; i0 += p.cbx) {
+                const int Cv = C - o0 < p.cb ? C - o0 : p.cb, Cx = C - i0 < p.cbx ? C - i0 : p.cbx;
                 const int l = blocks.n++;
-                if (l >= kChainMaxLayers)
-                    return INVCONV_ERR_UNSUPPORTED;
                 batch.x[l] = x + i0 * plane;
                 batch.v[l] = v + o0 * plane;
                 batch.cx[l] = blocks.cx[l] = (unsigned char)Cx;
                 batch.cv[l] = blocks.cv[l] = (unsigned char)Cv;
                 blocks.o0[l] = (unsigned char)o0;
                 blocks.i0[l] = (unsigned char)i0;
+                if (blocks.n == kChainMaxLayers)
+                    if (int s = flush())
+                        return s;
             }
-        if (int s = launch_dw_partial_batch(batch, blocks.n, part, p, B, p.cb, H, W, k, stream, p.cb, C, pstride))
-            return s;
-        return launch_dw_reduce_blocks(part, (int)p.nparts, dw, blocks, C, k, pstride, stream, sign);
+        return flush();
     }
     batch.x[0] = x;
     batch.v[0] = v;

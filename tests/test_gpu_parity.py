@@ -80,6 +80,9 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     (701, 3, 32, 32, 3), (1367, 3, 16, 32, 3), (2401, 1, 28, 28, 3), (685, 3, 32, 20, 5), (1000, 2, 24, 40, 3),   # two images per wave
     (1401, 3, 32, 32, 3), (700, 3, 64, 32, 3), (1500, 3, 32, 28, 5),   # backward as separate launches (solve, then weight gradient)
     (4099, 3, 8, 8, 3), (2500, 3, 32, 32, 3), (2302, 1, 28, 28, 3),   # waves that walk over several pairs of images
+    # 8 / 12 / 16 channels with the other kernel sizes of the kernel-size ablation (band kernel with k = 2, 5, 7)
+    (2, 12, 16, 16, 5), (3, 8, 40, 24, 2), (2, 16, 33, 20, 5), (2, 12, 64, 24, 7), (1, 8, 16, 16, 7), (2, 16, 16, 16, 2),
+    (2, 12, 20, 12, 2), (1, 16, 64, 9, 5), (3, 12, 7, 50, 5),
     # 8 / 12 channels, large batches or tall images: single-layer solves through the pipelined kernel
     (130, 12, 64, 64, 3), (26, 12, 100, 36, 3), (300, 8, 40, 24, 3), (40, 8, 128, 8, 3),
 ]
