@@ -32,7 +32,8 @@ struct DwBatch {
     unsigned char cv[kChainMaxLayers];
 };
 
-constexpr int kDwHalo = 4;      // left halo of the x tile, in columns (>= k-1, keeps rows 16-byte aligned)
+// left halo of the x tile, in columns: at least k-1, a multiple of 4 (keeps rows 16-byte aligned)
+__host__ __device__ constexpr int dw_halo(int k) { return k <= 5 ? 4 : ((k - 1 + 3) / 4) * 4; }
 constexpr int kDwUnroll = 4;    // pixel quads per trip of the product loop
 constexpr int kDwPre = 6;       // streaming mode: 16-byte pieces of each tile a thread holds in registers
 constexpr size_t kDwStreamLdsBudget = 72 * 1024;   // streaming mode: two workgroups per compute unit
@@ -55,13 +56,14 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
     }
     const float *__restrict__ x = batch.x[layer];
     const float *__restrict__ v = batch.v[layer];
-    // XW >= W + kDwHalo, SXC >= (RT + k - 1) * XW and SVC >= RT * W: row / channel strides padded by the
+    // XW >= W + halo, SXC >= (RT + k - 1) * XW and SVC >= RT * W: row / channel strides padded by the
     // host so that the 64 lanes of an operand read fall into different LDS banks
     const int NCOL = C * k * k;
     const int P = Cv * NCOL;
     const int CM = Cv > C ? Cv : C;
     float *sv = smem;                 // [Cv] x SVC, rows of W floats
-    float *sx = sv + CM * SVC;        // [C] x SXC, rows of XW floats, origin at (r0-(k-1), -kDwHalo)
+    float *sx = sv + CM * SVC;        // [C] x SXC, rows of XW floats, origin at (r0-(k-1), -halo)
+    const int halo = dw_halo(k);
     float *sred = smem;               // [4 waves][64 lanes][NS*4], reuses the tiles afterwards
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
     for (int s = 0; s < NS; ++s) {
         const int col = (16 * s + nn < NCOL) ? 16 * s + nn : 0;
         const int i = col / (k * k), a = (col / k) % k, b = col % k;
-        boff[s] = i * SXC + a * XW + b + kDwHalo - (k - 1);
+        boff[s] = i * SXC + a * XW + b + halo - (k - 1);
     }
     f32x4 acc[NS];
 #pragma unroll
@@ -100,13 +102,15 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
             p_r[i] = ok ? r : -1;
             p_go[i] = (ch * H + r) * W + 4 * c4;
             p_vl[i] = ch * SVC + r * W + 4 * c4;
-            p_xl[i] = ch * SXC + (r + k - 1) * XW + 4 * (c4 + 1);
+            p_xl[i] = ch * SXC + (r + k - 1) * XW + 4 * c4 + halo;
             pv[i] = px[i] = ph[i] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
         // the halo columns stay zero for the whole launch
-        for (int idx = tid; idx < C * (RT + k - 1); idx += 256) {
-            const int ch = idx / (RT + k - 1), r = idx - ch * (RT + k - 1);
-            *reinterpret_cast<float4 *>(sx + ch * SXC + r * XW) = make_float4(0.f, 0.f, 0.f, 0.f);
+        const int H4 = halo / 4;
+        for (int idx = tid; idx < C * (RT + k - 1) * H4; idx += 256) {
+            const int q = idx % H4, rr = idx / H4;
+            const int ch = rr / (RT + k - 1), r = rr - ch * (RT + k - 1);
+            *reinterpret_cast<float4 *>(sx + ch * SXC + r * XW + 4 * q) = make_float4(0.f, 0.f, 0.f, 0.f);
         }
         // rows above the first chunk, as if left by a chunk before it; then the first chunk itself
         const int rb = c_begin * RT;
@@ -153,14 +157,14 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
                     v + (((size_t)n * Ctot + ch) * H + r0 + r) * W + 4 * c4);
                 *reinterpret_cast<float4 *>(sv + ch * SVC + r * W + 4 * c4) = val;
             }
-            const int X4 = (W + kDwHalo) / 4;                   // first float4 of a row is the halo
+            const int X4 = (W + halo) / 4, H4 = halo / 4;      // the first H4 pieces of a row are the halo
             for (int idx = tid; idx < C * xrows * X4; idx += 256) {
                 const int c4 = idx % X4, rr = idx / X4;
                 const int ch = rr / xrows, r = rr - ch * xrows;
                 const int gr = r0 - (k - 1) + r;
                 float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (gr >= 0 && c4 > 0)
-                    val = *reinterpret_cast<const float4 *>(x + (((size_t)n * Ctot + ch) * H + gr) * W + 4 * (c4 - 1));
+                if (gr >= 0 && c4 >= H4)
+                    val = *reinterpret_cast<const float4 *>(x + (((size_t)n * Ctot + ch) * H + gr) * W + 4 * (c4 - H4));
                 *reinterpret_cast<float4 *>(sx + ch * SXC + r * XW + 4 * c4) = val;
             }
         } else {
@@ -168,10 +172,10 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
                 const int c = idx % W, r = (idx / W) % rows, ch = idx / (W * rows);
                 sv[ch * SVC + r * W + c] = v[(((size_t)n * Ctot + ch) * H + r0 + r) * W + c];
             }
-            const int xcols = W + kDwHalo;
+            const int xcols = W + halo;
             for (int idx = tid; idx < C * xrows * xcols; idx += 256) {
                 const int cc = idx % xcols, rr = (idx / xcols) % xrows, ch = idx / (xcols * xrows);
-                const int gr = r0 - (k - 1) + rr, gc = cc - kDwHalo;
+                const int gr = r0 - (k - 1) + rr, gc = cc - halo;
                 sx[ch * SXC + rr * XW + cc] =
                     (gr >= 0 && gc >= 0) ? x[(((size_t)n * Ctot + ch) * H + gr) * W + gc] : 0.0f;
             }
@@ -274,7 +278,7 @@ static int dw_x_block(int C, int k)
 // channels, all blocks in one launch
 bool dw_mfma_supported(int C, int k)
 {
-    return C >= 1 && C <= 64 && k >= 1 && k - 1 <= kDwHalo && dw_x_block(C, k) >= 1;
+    return C >= 1 && C <= 64 && k >= 1 && dw_x_block(C, k) >= 1;
 }
 
 // Row chunking of pass 1 for one block of Cv output x Cx input channels: tiles (or the reduction buffer that reuses
@@ -296,7 +300,8 @@ static DwPlan plan_dw_mfma_block(int B, int Cv, int C, int H, int W, int k)
         const size_t tiles = (size_t)CM * svc_for(rt) + (size_t)C * sxc;
         return sizeof(float) * (tiles > red ? tiles : red);
     };
-    auto lds_for = [&](int rt) { return lds_with(rt, W + kDwHalo, (rt + k - 1) * (W + kDwHalo)); };
+    const int halo = dw_halo(k);
+    auto lds_for = [&](int rt) { return lds_with(rt, W + halo, (rt + k - 1) * (W + halo)); };
     // Rows of 16-byte pieces take the streaming mode (if the pointers are aligned too): registers limit it
     // to two workgroups per compute unit, so its tiles may be larger, as long as a thread's share of a
     // tile still fits its kDwPre registers.
@@ -310,7 +315,7 @@ static DwPlan plan_dw_mfma_block(int B, int Cv, int C, int H, int W, int k)
     p.rt = rt;
     p.nchunks = (H + rt - 1) / rt;
     p.svc = svc_for(rt);
-    p.xw = W + kDwHalo;
+    p.xw = W + halo;
     p.sxc = (rt + k - 1) * p.xw;
     {
         // bank conflicts of the B operand reads: lane (nn, kk) of instruction s reads
@@ -358,7 +363,7 @@ static DwPlan plan_dw_mfma_block(int B, int Cv, int C, int H, int W, int k)
             int best = cost(p.xw, p.sxc);
             for (int rp = 0; rp <= 12; rp += 4)
                 for (int cp = 0; cp <= 60; cp += 4) {
-                    const int xw = W + kDwHalo + rp, sxc = (rt + k - 1) * xw + cp;
+                    const int xw = W + halo + rp, sxc = (rt + k - 1) * xw + cp;
                     if (lds_with(rt, xw, sxc) > budget)             // same number of workgroups per CU as unpadded
                         continue;
                     const int c = cost(xw, sxc);
