@@ -132,7 +132,11 @@ int solve_variant(int dir, const float *in, const float *w, float *out, int B, i
         }
         if (wide_supported(C, H, k))
             return launch_solve_wide(dir, in, w, out, B, C, H, W, k, stream);
-        return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);
+        if (check_supported(C, H, k) == INVCONV_OK)
+            return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);
+        // nothing on chip holds this shape (more than 48 channels, or a window that outgrows LDS): one launch per
+        // anti-diagonal with the kernel read from memory - slow, but nearly every shape has a solve
+        return launch_solve_diag_wave(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_BLOCK:
         return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);
     case INVCONV_VARIANT_WAVE:
@@ -169,9 +173,7 @@ int fwd_impl(const float *y, const float *w, float *x, int B, int C, int H, int 
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_BAND && !band_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
-    if (variant == INVCONV_VARIANT_BLOCK ||
-        (variant == INVCONV_VARIANT_AUTO && !wave_supported(C, H, k) && !wave_bands_supported(C, H, W, k) &&
-         !band_supported(C, H, k) && !wide_supported(C, H, k)))
+    if (variant == INVCONV_VARIANT_BLOCK)
         if (int s = check_supported(C, H, k))
             return s;
     return solve(0, y, w, x, B, C, H, W, k, (hipStream_t)stream, variant, ws, logdet);
@@ -310,9 +312,7 @@ invconv_status invconv_bwd_ex(const float *x, const float *w, const float *dLdx,
         return INVCONV_ERR_VARIANT;
     if (variant == INVCONV_VARIANT_BAND && !band_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
-    if (variant == INVCONV_VARIANT_BLOCK ||
-        (variant == INVCONV_VARIANT_AUTO && !wave_supported(C, H, k) && !wave_bands_supported(C, H, W, k) &&
-         !band_supported(C, H, k) && !wide_supported(C, H, k)))
+    if (variant == INVCONV_VARIANT_BLOCK)
         if (int s = check_supported(C, H, k))
             return s;
     const DwPlan p = plan_dw_any(B, C, H, W, k);

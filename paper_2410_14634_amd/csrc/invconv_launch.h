@@ -51,6 +51,8 @@ int launch_solve_block(int dir, const float *in, const float *w, float *out, int
                        int k, hipStream_t stream);
 int launch_solve_diag(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W,
                       int k, hipStream_t stream);
+int launch_solve_diag_wave(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                           hipStream_t stream);
 bool wave_supported(int C, int H, int k);
 // `logdet` (may be null): one device float that receives log|det dx/dy| of one image on the side
 int launch_solve_wave(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,

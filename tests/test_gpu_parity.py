@@ -83,6 +83,8 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     # 8 / 12 / 16 channels with the other kernel sizes of the kernel-size ablation (band kernel with k = 2, 5, 7)
     (2, 12, 16, 16, 5), (3, 8, 40, 24, 2), (2, 16, 33, 20, 5), (2, 12, 64, 24, 7), (1, 8, 16, 16, 7), (2, 16, 16, 16, 2),
     (2, 12, 20, 12, 2), (1, 16, 64, 9, 5), (3, 12, 7, 50, 5),
+    # shapes no on-chip kernel holds: one launch per anti-diagonal, a wave per pixel
+    (5, 64, 4, 4, 3), (2, 96, 2, 2, 3), (1, 44, 70, 9, 3), (2, 128, 2, 3, 3), (1, 52, 5, 6, 2), (1, 64, 3, 3, 5),
     # 8 / 12 channels, large batches or tall images: single-layer solves through the pipelined kernel
     (130, 12, 64, 64, 3), (26, 12, 100, 36, 3), (300, 8, 40, 24, 3), (40, 8, 128, 8, 3),
 ]
