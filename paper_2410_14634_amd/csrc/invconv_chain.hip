@@ -567,7 +567,15 @@ bool chain_supported(int stages, int C, int H, int W, int k)
 // 293 us at B = 32, 12 x 128 x 128).
 bool chain_single_preferred(int B, int C, int H)
 {
+    // (images of one band, H <= 16, stay on the band kernel whatever the batch: there this kernel would keep one
+    // of its eight solving waves busy - 1024 x 12x16x16: 40 us on the band kernel, 125 us here; 4096: 133 / 492 us)
+    // With two bands (H <= 32) it keeps two of eight, and takes over later: 700 x 12x24x24 94 against 146 us,
+    // 400 x 12x20x20 56 / 93; 1024 x 12x32x32 385 / 215.
     const double live_per_xcd = (double)B * H * C * 256.0 / 8.0;
+    if (H <= 16)
+        return false;
+    if (H <= 32)
+        return live_per_xcd > 8.0e6;
     return live_per_xcd > 2.0e6 || (H > 80 && B >= 24);
 }
 
