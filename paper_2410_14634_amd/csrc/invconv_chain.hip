@@ -574,8 +574,8 @@ bool chain_single_preferred(int B, int C, int H)
     const double live_per_xcd = (double)B * H * C * 256.0 / 8.0;
     if (H <= 16)
         return false;
-    if (H <= 32)
-        return live_per_xcd > 8.0e6;
+    if (H <= 32)      // (16 channels: the band kernel's registers allow fewer waves, it falls behind sooner: 256 x 16x32x32 112 us)
+        return live_per_xcd > (C == 16 ? 3.0e6 : 8.0e6);
     return live_per_xcd > 2.0e6 || (H > 80 && B >= 24);
 }
 

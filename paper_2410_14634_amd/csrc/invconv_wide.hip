@@ -548,8 +548,9 @@ static int launch_wide_reg(int dir, const float *in, const float *w, float *out,
         return INVCONV_ERR_UNSUPPORTED;
     // up to one workgroup per compute unit: eight waves at least, the ones the solve does not use help with the
     // set-up (48 x 8 x 8, B = 100: 70 -> 50 us); more workgroups than that are better off with more of them resident
+    // (48 channels: the set-up's LDS leaves room for one workgroup per compute unit whatever the batch)
     int waves = NB * wide_out_blocks(C);
-    if (B <= 256 && waves < 8)
+    if ((B <= 256 || 2 * lds > kMaxLdsBytes) && waves < 8)
         waves = 8 < MAXW ? 8 : MAXW;
     const dim3 block((unsigned)(64 * waves));
     if (dir)
