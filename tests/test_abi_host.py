@@ -112,6 +112,20 @@ def test_workspace_taking_calls_reject_bad_workspaces():
     assert L.invconv_workspace_error(None, None, None) == b.ERR_NULL
 
 
+def test_backward_workspace_covers_every_block_of_a_blocked_weight_gradient():
+    """More than 16 channels, or more columns C k k than a wave has accumulators: dL/dw is formed in blocks of
+    channels that share one launch, each block with partial rows of its own - the workspace grows with the
+    number of blocks, stays a multiple of 256 bytes, and every shape with a solve has one."""
+    one = b.bwd_workspace_bytes(8, 16, 32, 32, 3)                 # one GEMM
+    nine = b.bwd_workspace_bytes(8, 48, 32, 32, 3)                # 3 x 3 blocks of 16 x 16 channels
+    assert nine % 256 == 0 and nine > 8 * one
+    k3 = b.bwd_workspace_bytes(8, 12, 16, 16, 3)                  # 108 columns: one GEMM
+    k5 = b.bwd_workspace_bytes(8, 12, 16, 16, 5)                  # 300 columns: two blocks of 6 input channels
+    assert k5 % 256 == 0 and k5 > k3
+    for shape in [(2, 64, 4, 4, 3), (1, 96, 2, 2, 3), (3, 12, 16, 16, 7), (2, 3, 32, 32, 11), (1, 44, 95, 20, 3)]:
+        assert b.bwd_workspace_bytes(*shape) > 256, shape         # (the solve of such shapes is the last-resort path)
+
+
 def test_static_scratch_call_rejects_bad_arguments_and_oversized_shapes():
     L = b.lib()
     x, w, g, v, dw = FAKE[:5]
