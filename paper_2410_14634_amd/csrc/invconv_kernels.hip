@@ -455,8 +455,9 @@ __global__ __launch_bounds__(kDwBlock) void k_dw_partial(const float *__restrict
 // as 0.  No atomics anywhere, so dw is bitwise reproducible from run to run.
 // blockIdx.y selects the layer when several layers are reduced by one launch
 // (layer l's rows start at part + l*nparts*P, its result goes to out.p[l]).
-// A launch may also cover one block of a larger result (more than 16 channels): rows hold Cv x Cx k k entries
-// that go to output channels o0 .. and input channels i0 .. of a Ctot-channel kernel gradient.
+// Rows may hold one Cv x C block of a larger result (entries for output channels o0 .. and input channels i0 .. of a
+// Ctot-channel kernel gradient); the launches here pass the whole result, results formed in blocks take
+// k_dw_reduce_blocks below.
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void k_dw_reduce(const float *__restrict__ part_all, int nparts, PtrList out,
                                                       int C, int k, float sign, int Cv, int o0, int i0, int Ctot)
@@ -774,22 +775,6 @@ int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int
     else
         hipLaunchKernelGGL(k_dw_reduce<4>, dim3((P + 63) / 64, layers), dim3(256), 0, stream, part, nparts, out, C, k,
                            sign, C, 0, 0, C);
-    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
-}
-
-// Second pass for one Cv x Cx block of a Ctot-channel result (rows of Cv*Cx*k*k partial sums)
-int launch_dw_reduce_block(const float *part, int nparts, float *dw, int Cv, int Cx, int o0, int i0, int Ctot, int k,
-                           hipStream_t stream, float sign)
-{
-    const int P = Cv * Cx * k * k;
-    PtrList out{};
-    out.p[0] = dw;
-    if (nparts >= 512)
-        hipLaunchKernelGGL(k_dw_reduce<16>, dim3((P + 63) / 64, 1), dim3(1024), 0, stream, part, nparts, out, Cx, k, sign,
-                           Cv, o0, i0, Ctot);
-    else
-        hipLaunchKernelGGL(k_dw_reduce<4>, dim3((P + 63) / 64, 1), dim3(256), 0, stream, part, nparts, out, Cx, k, sign,
-                           Cv, o0, i0, Ctot);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

@@ -98,8 +98,6 @@ struct PtrList { float *p[kChainMaxLayers]; };
 struct ConstPtrList { const float *p[kChainMaxLayers]; };
 int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int layers, int C, int k,
                             hipStream_t stream, float sign = -1.0f);
-int launch_dw_reduce_block(const float *part, int nparts, float *dw, int Cv, int Cx, int o0, int i0, int Ctot, int k,
-                           hipStream_t stream, float sign = -1.0f);
 // Blocks of a result with more than 16 channels reduced by one launch: block l holds cv[l] x cx[l] k k entries per row
 // (rows pstride floats apart, block l's rows start at part + l * nparts * pstride) that go to output channels
 // o0[l] .. and input channels i0[l] .. of the Ctot-channel result.
