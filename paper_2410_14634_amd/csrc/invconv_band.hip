@@ -1,4 +1,4 @@
-// Band-systolic wavefront solve for C = 8, 12 or 16 channels on the matrix
+// Band-systolic wavefront solve for 5 to 16 channels (laid out for C = 8, 12 or 16) on the matrix
 // cores (v_mfma_f32_16x16x4_f32).  gfx950 only.
 //
 // A wave owns a band of 16 image rows.  Lane (n, g) = (lane % 16, lane / 16)
@@ -42,11 +42,16 @@ constexpr int kRing = 4;        // depth of the band-to-band message ring
 
 // MAXT: the most threads a launch may have (512 for k = 3; the folded taps of larger kernels need the registers
 // of a workgroup of at most four waves).
-template <int CG, int K, int DIR, int MAXT = 512>
+// PAD: the image has Cr < 4 CG channels (5-7, 9-11, 13-15).  The lanes' channel slots beyond Cr carry zero weights in
+// both operand roles, read as zero and are never stored, so the solve is that of the Cr real channels; the folded
+// weights are then laid out with row length Cr.
+template <int CG, int K, int DIR, int MAXT = 512, bool PAD = false>
 __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ in, const float *__restrict__ w,
-                                                    float *__restrict__ out, int H, int W, int NB, float *logdet)
+                                                    float *__restrict__ out, int H, int W, int NB, float *logdet,
+                                                    int Cr)
 {
     constexpr int C = 4 * CG;
+    const int Cs = PAD ? Cr : C;        // channels of the image = row length of the folded weights
     extern __shared__ float smem[];
     float *sL = smem;
     float *sLinv = sL + C * C;
@@ -63,13 +68,15 @@ __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ i
     const unsigned Wst = row_ok ? (unsigned)W : 0u;
 
     // addressing: uniform pointer per (channel of this lane's group) + per-lane 32-bit byte offset
-    const size_t img = (size_t)blockIdx.x * C * H * W;
+    const size_t img = (size_t)blockIdx.x * Cs * H * W;
     const char *chan_src[CG];
     char *chan_dst[CG];
+    bool ch_ok[CG];
 #pragma unroll
     for (int jj = 0; jj < CG; ++jj) {
-        const int ch = CG * g + jj;
-        const size_t cb = img + (size_t)(DIR ? C - 1 - ch : ch) * H * W;
+        ch_ok[jj] = !PAD || CG * g + jj < Cs;
+        const int ch = ch_ok[jj] ? CG * g + jj : 0;
+        const size_t cb = img + (size_t)(DIR ? Cs - 1 - ch : ch) * H * W;
         chan_src[jj] = reinterpret_cast<const char *>(in + cb);
         chan_dst[jj] = reinterpret_cast<char *>(out + cb);
     }
@@ -78,8 +85,14 @@ __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ i
     const int rowlo = DIR ? row0 - 4 * (W - 1) : row0;
     const int rowhi = DIR ? row0 : row0 + 4 * (W - 1);
     auto clamp_row = [&](int off) -> unsigned { return (unsigned)(off < rowlo ? rowlo : (off > rowhi ? rowhi : off)); };
-    auto ld = [&](int jj, unsigned off) -> float { return *reinterpret_cast<const float *>(chan_src[jj] + off); };
-    auto st = [&](int jj, unsigned off, float v) { *reinterpret_cast<float *>(chan_dst[jj] + off) = v; };
+    auto ld = [&](int jj, unsigned off) -> float {
+        const float v = *reinterpret_cast<const float *>(chan_src[jj] + off);
+        return ch_ok[jj] ? v : 0.0f;
+    };
+    auto st = [&](int jj, unsigned off, float v) {
+        if (ch_ok[jj])
+            *reinterpret_cast<float *>(chan_dst[jj] + off) = v;
+    };
 
     // Local step tau = t - t_first of this band: lane row n is at column c = tau - n.
     const int t_first = band * (16 + kBandDelay);
@@ -94,14 +107,17 @@ __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ i
             yb[u][jj] = ld(jj, off);
     }
 
-    fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sW);
+    if (PAD)
+        fold_weights<DIR, 0>(w, Cs, K, sL, sLinv, sCf, sW);
+    else
+        fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sW);
     for (int idx = tid; idx < NB * kRing * K * 64; idx += blockDim.x)
         sMsg[idx] = 0.0f;
 
     // A operands of this lane: output row m = lane%16 -> channel o(m) = CG*(m/4) + m%4 (padding if m%4 >= CG),
     // K slot g -> input channel CG*g + jj
     const int m = n;
-    const bool m_ok = (m & 3) < CG;
+    const bool m_ok = (m & 3) < CG && (!PAD || CG * (m >> 2) + (m & 3) < Cs);
     const int om = m_ok ? CG * (m >> 2) + (m & 3) : 0;
     float wA[K][K][CG], wLi[CG];
 #pragma unroll
@@ -110,20 +126,21 @@ __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ i
         for (int db = 0; db < K; ++db)
 #pragma unroll
             for (int jj = 0; jj < CG; ++jj) {
-                const float cf = sCf[((a * K + db) * C + om) * C + CG * g + jj];
-                wA[a][db][jj] = m_ok ? -cf : 0.0f;
+                const int ii = ch_ok[jj] ? CG * g + jj : 0;
+                const float cf = sCf[((a * K + db) * Cs + om) * Cs + ii];
+                wA[a][db][jj] = m_ok && ch_ok[jj] ? -cf : 0.0f;
             }
 #pragma unroll
     for (int jj = 0; jj < CG; ++jj) {
-        const float lv = sLinv[om * C + CG * g + jj];
-        wLi[jj] = m_ok ? lv : 0.0f;
+        const float lv = sLinv[om * Cs + (ch_ok[jj] ? CG * g + jj : 0)];
+        wLi[jj] = m_ok && ch_ok[jj] ? lv : 0.0f;
     }
     __syncthreads();        // ring zeroed, weights read
     if (band >= NB) {
         // helper waves of a single-band launch: they only speed up the weight preparation; the last one of the
         // first workgroup also forms the log-determinant when the caller asked for it
         if (logdet && blockIdx.x == 0 && band == 3)
-            wave_logdet_any(w, C, K, H, W, logdet);
+            wave_logdet_any(w, Cs, K, H, W, logdet);
         return;
     }
 
@@ -259,7 +276,7 @@ __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ i
             __syncthreads();
         // (the first band is through with its barriers when the last band ends: it has time for the log-determinant)
         if (logdet && blockIdx.x == 0 && band == 0)
-            wave_logdet_any(w, C, K, H, W, logdet);
+            wave_logdet_any(w, Cs, K, H, W, logdet);
     }
 }
 
@@ -277,11 +294,12 @@ __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ i
 // start of step s+1, after the barrier that ends step s.  Wave 0 forms T1p, T2p and ownp itself.
 // Wave 1 also writes x to global memory, wave 3 reads y.  One barrier per step.
 // ---------------------------------------------------------------------------
-template <int CG, int DIR>
+template <int CG, int DIR, bool PAD = false>
 __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restrict__ in, const float *__restrict__ w,
-                                                          float *__restrict__ out, int H, int W, float *logdet)
+                                                          float *__restrict__ out, int H, int W, float *logdet, int Cr)
 {
     constexpr int K = 3, C = 4 * CG;
+    const int Cs = PAD ? Cr : C;        // channels of the image (PAD: fewer than the lanes' 4 CG slots, as in k_solve_band)
     extern __shared__ float smem[];
     float *sL = smem;
     float *sLinv = sL + C * C;
@@ -297,13 +315,15 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
     const int rr = row_ok ? n : H - 1;
     const unsigned Wst = row_ok ? (unsigned)W : 0u;
 
-    const size_t img = (size_t)blockIdx.x * C * H * W;
+    const size_t img = (size_t)blockIdx.x * Cs * H * W;
     const char *chan_src[CG];
     char *chan_dst[CG];
+    bool ch_ok[CG];
 #pragma unroll
     for (int jj = 0; jj < CG; ++jj) {
-        const int ch = CG * g + jj;
-        const size_t cb = img + (size_t)(DIR ? C - 1 - ch : ch) * H * W;
+        ch_ok[jj] = !PAD || CG * g + jj < Cs;
+        const int ch = ch_ok[jj] ? CG * g + jj : 0;
+        const size_t cb = img + (size_t)(DIR ? Cs - 1 - ch : ch) * H * W;
         chan_src[jj] = reinterpret_cast<const char *>(in + cb);
         chan_dst[jj] = reinterpret_cast<char *>(out + cb);
     }
@@ -312,8 +332,14 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
     const int rowlo = DIR ? row0 - 4 * (W - 1) : row0;
     const int rowhi = DIR ? row0 : row0 + 4 * (W - 1);
     auto clamp_row = [&](int off) -> unsigned { return (unsigned)(off < rowlo ? rowlo : (off > rowhi ? rowhi : off)); };
-    auto ld = [&](int jj, unsigned off) -> float { return *reinterpret_cast<const float *>(chan_src[jj] + off); };
-    auto st = [&](int jj, unsigned off, float v) { *reinterpret_cast<float *>(chan_dst[jj] + off) = v; };
+    auto ld = [&](int jj, unsigned off) -> float {
+        const float v = *reinterpret_cast<const float *>(chan_src[jj] + off);
+        return ch_ok[jj] ? v : 0.0f;
+    };
+    auto st = [&](int jj, unsigned off, float v) {
+        if (ch_ok[jj])
+            *reinterpret_cast<float *>(chan_dst[jj] + off) = v;
+    };
 
     // wave 3 reads y: slot u holds the input of the steps congruent to u; first batch = steps 0 .. kBandPF-1,
     // issued before the weight preparation so that both latencies overlap.  The other waves run the same
@@ -323,16 +349,21 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
     for (int u = 0; u < kBandPF; ++u) {
         const unsigned off = wave == 3 ? clamp_row(row0 + kStep * (u - n)) : 0u;
 #pragma unroll
-        for (int jj = 0; jj < CG; ++jj)
-            yb[u][jj] = *reinterpret_cast<const float *>((wave == 3 ? chan_src[jj] : chan_src[0]) + off);
+        for (int jj = 0; jj < CG; ++jj) {
+            const float v = *reinterpret_cast<const float *>((wave == 3 ? chan_src[jj] : chan_src[0]) + off);
+            yb[u][jj] = ch_ok[jj] ? v : 0.0f;
+        }
     }
 
-    fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sW);
+    if (PAD)
+        fold_weights<DIR, 0>(w, Cs, K, sL, sLinv, sCf, sW);
+    else
+        fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sW);
     for (int idx = tid; idx < 2 * CG * 64 + 2 * 3 * 64 * 4; idx += 256)
         sX[idx] = 0.0f;
 
     const int m = n;
-    const bool m_ok = (m & 3) < CG;
+    const bool m_ok = (m & 3) < CG && (!PAD || CG * (m >> 2) + (m & 3) < Cs);
     const int om = m_ok ? CG * (m >> 2) + (m & 3) : 0;
     float wA[K][K][CG], wLi[CG];
 #pragma unroll
@@ -341,13 +372,14 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
         for (int db = 0; db < K; ++db)
 #pragma unroll
             for (int jj = 0; jj < CG; ++jj) {
-                const float cf = sCf[((a * K + db) * C + om) * C + CG * g + jj];
-                wA[a][db][jj] = m_ok ? -cf : 0.0f;
+                const int ii = ch_ok[jj] ? CG * g + jj : 0;
+                const float cf = sCf[((a * K + db) * Cs + om) * Cs + ii];
+                wA[a][db][jj] = m_ok && ch_ok[jj] ? -cf : 0.0f;
             }
 #pragma unroll
     for (int jj = 0; jj < CG; ++jj) {
-        const float lv = sLinv[om * C + CG * g + jj];
-        wLi[jj] = m_ok ? lv : 0.0f;
+        const float lv = sLinv[om * Cs + (ch_ok[jj] ? CG * g + jj : 0)];
+        wLi[jj] = m_ok && ch_ok[jj] ? lv : 0.0f;
     }
     __syncthreads();
 
@@ -464,7 +496,7 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
                 step(s0 + u, u, false);
     }
     if (logdet && blockIdx.x == 0 && wave == 2)
-        wave_logdet_any(w, C, K, H, W, logdet);
+        wave_logdet_any(w, Cs, K, H, W, logdet);
 }
 
 size_t solve_band_lds_bytes(int C, int k, int NB)
@@ -475,18 +507,21 @@ size_t solve_band_lds_bytes(int C, int k, int NB)
 // k = 3: at most 8 bands = 512 threads.  Other kernel sizes of the paper's kernel-size ablation (2, 5; 7 up to 12
 // channels) run on the general kernel with at most four bands: a lane then keeps C k^2 / 4 folded taps in registers
 // (147 at 12 channels, k = 7), which k = 9 and 11 do not have.
+// Channel counts between the sizes the lanes are laid out for (5-7, 9-11, 13-15) run the next size up with the
+// surplus channel slots switched off.
 bool band_supported(int C, int H, int k)
 {
-    if (!(C == 8 || C == 12 || C == 16))
+    if (C < 5 || C > 16)
         return false;
     if (k == 3)
         return H <= 128;
-    const bool size_ok = k == 2 || k == 5 || (k == 7 && C <= 12);
-    return size_ok && H <= 64 && solve_band_lds_bytes(C, k, (H + 15) / 16) <= kMaxLdsBytes;
+    const int Cp = (C + 3) / 4 * 4;
+    const bool size_ok = k == 2 || k == 5 || (k == 7 && Cp <= 12);
+    return size_ok && H <= 64 && solve_band_lds_bytes(Cp, k, (H + 15) / 16) <= kMaxLdsBytes;
 }
 
-template <int CG, int K>
-static int launch_band_ck(int dir, const float *in, const float *w, float *out, int B, int H, int W,
+template <int CG, int K, bool PAD>
+static int launch_band_ck(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W,
                           hipStream_t stream, float *logdet)
 {
     const int NB = (H + 15) / 16;
@@ -494,9 +529,11 @@ static int launch_band_ck(int dir, const float *in, const float *w, float *out, 
         const size_t lds1 = sizeof(float) * (2 * (size_t)16 * CG * CG + 2 * (size_t)K * K * 16 * CG * CG +
                                              2 * CG * 64 + 2 * 3 * 64 * 4);
         if (dir)
-            hipLaunchKernelGGL((k_solve_band_split<CG, 1>), dim3(B), dim3(256), lds1, stream, in, w, out, H, W, logdet);
+            hipLaunchKernelGGL((k_solve_band_split<CG, 1, PAD>), dim3(B), dim3(256), lds1, stream, in, w, out, H, W,
+                               logdet, C);
         else
-            hipLaunchKernelGGL((k_solve_band_split<CG, 0>), dim3(B), dim3(256), lds1, stream, in, w, out, H, W, logdet);
+            hipLaunchKernelGGL((k_solve_band_split<CG, 0, PAD>), dim3(B), dim3(256), lds1, stream, in, w, out, H, W,
+                               logdet, C);
         return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
     }
     const size_t lds = solve_band_lds_bytes(4 * CG, K, NB);
@@ -505,16 +542,16 @@ static int launch_band_ck(int dir, const float *in, const float *w, float *out, 
     const int threads = NB == 1 ? 256 : 64 * NB;
     if (threads > MAXT)
         return INVCONV_ERR_VARIANT;
-    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_band<CG, K, 1, MAXT>)
-                         : reinterpret_cast<const void *>(&k_solve_band<CG, K, 0, MAXT>);
+    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_band<CG, K, 1, MAXT, PAD>)
+                         : reinterpret_cast<const void *>(&k_solve_band<CG, K, 0, MAXT, PAD>);
     if (!ensure_dynamic_lds(fn, lds))
         return INVCONV_ERR_UNSUPPORTED;
     if (dir)
-        hipLaunchKernelGGL((k_solve_band<CG, K, 1, MAXT>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB,
-                           logdet);
+        hipLaunchKernelGGL((k_solve_band<CG, K, 1, MAXT, PAD>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W,
+                           NB, logdet, C);
     else
-        hipLaunchKernelGGL((k_solve_band<CG, K, 0, MAXT>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W, NB,
-                           logdet);
+        hipLaunchKernelGGL((k_solve_band<CG, K, 0, MAXT, PAD>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W,
+                           NB, logdet, C);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
@@ -523,20 +560,23 @@ int launch_solve_band(int dir, const float *in, const float *w, float *out, int 
 {
     if (!band_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
-    auto by_k = [&](auto cg_tag) -> int {
+    auto by_k = [&](auto cg_tag, auto pad_tag) -> int {
         constexpr int CG = decltype(cg_tag)::value;
-        if (k == 3) return launch_band_ck<CG, 3>(dir, in, w, out, B, H, W, stream, logdet);
-        if (k == 2) return launch_band_ck<CG, 2>(dir, in, w, out, B, H, W, stream, logdet);
-        if (k == 5) return launch_band_ck<CG, 5>(dir, in, w, out, B, H, W, stream, logdet);
+        constexpr bool PAD = decltype(pad_tag)::value;
+        if (k == 3) return launch_band_ck<CG, 3, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
+        if (k == 2) return launch_band_ck<CG, 2, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
+        if (k == 5) return launch_band_ck<CG, 5, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
         if constexpr (CG <= 3) {
-            if (k == 7) return launch_band_ck<CG, 7>(dir, in, w, out, B, H, W, stream, logdet);
+            if (k == 7) return launch_band_ck<CG, 7, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
         }
         return INVCONV_ERR_VARIANT;
     };
-    if (C == 8) return by_k(std::integral_constant<int, 2>());
-    if (C == 12) return by_k(std::integral_constant<int, 3>());
-    if (C == 16) return by_k(std::integral_constant<int, 4>());
-    return INVCONV_ERR_VARIANT;
+    auto by_cg = [&](auto pad_tag) -> int {
+        if (C <= 8) return by_k(std::integral_constant<int, 2>(), pad_tag);
+        if (C <= 12) return by_k(std::integral_constant<int, 3>(), pad_tag);
+        return by_k(std::integral_constant<int, 4>(), pad_tag);
+    };
+    return C % 4 ? by_cg(std::true_type()) : by_cg(std::false_type());
 }
 
 }  // namespace invconv

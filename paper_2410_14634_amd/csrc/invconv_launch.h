@@ -60,7 +60,7 @@ int launch_solve_wave(int dir, const float *in, const float *w, float *out, int 
 bool band_supported(int C, int H, int k);
 int launch_solve_band(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                       hipStream_t stream, float *logdet = nullptr);
-// many channels (20 .. 48, multiple of 4), k = 3: 16x16x4 MFMA per tap, history in an LDS ring
+// many channels (17 .. 48), k = 3: 16x16x4 MFMA per tap, history in an LDS ring
 bool wide_supported(int C, int H, int k);
 int launch_solve_wide(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                       hipStream_t stream, float *logdet = nullptr);

@@ -1,5 +1,5 @@
-// Wavefront solve for many channels (C = 20 .. 48, a multiple of 4; k = 3): the shapes a flow reaches after
-// two squeezes (Section 4.1).  gfx950 only.
+// Wavefront solve for many channels (C = 17 .. 48, laid out for multiples of 4; k = 3): the shapes a flow reaches
+// after two squeezes (Section 4.1).  gfx950 only.
 //
 // With folded weights (Linv = inverse of the current-pixel block, Cf_tap = Linv W_tap) the channels of a pixel
 // are independent:  x_p = Linv y_p - sum_{tap} Cf_tap x_{p - tap}  (Eq. 1 rearranged), and at this channel
@@ -42,8 +42,10 @@ __host__ __device__ constexpr size_t wide_fold_scratch_floats(int C)
     return (size_t)C * C + (size_t)16 * wide_out_blocks(C) * (C + 1) + (size_t)4 * C * kWideTapStride;
 }
 
+// Cr: the channels the image really has (4 CQ - 3 .. 4 CQ); the surplus ones are given an identity current-pixel
+// block and no other taps, so they solve to their (zero) input and touch nothing else.
 template <int CQ, int DIR>
-__device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, float *sWt, float *scratch)
+__device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, float *sWt, float *scratch, int Cr)
 {
     constexpr int C = 4 * CQ, K = kWideK, NT = K * K;
     constexpr int OB = wide_out_blocks(C), OR = 16 * OB, CPAD = C + 1;
@@ -53,8 +55,12 @@ __device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, f
     const int tid = threadIdx.x, nt = blockDim.x;
     auto entry = [&](int tp, int o, int i) -> float {
         const int a = K - 1 - tp / K, b = K - 1 - tp % K;
-        const int oo = DIR ? C - 1 - i : o, ii = DIR ? C - 1 - o : i;
-        const float v = w[((oo * C + ii) * K + a) * K + b];
+        const bool real = o < Cr && i < Cr;
+        const int oc = real ? o : 0, ic = real ? i : 0;
+        const int oo = DIR ? Cr - 1 - ic : oc, ii = DIR ? Cr - 1 - oc : ic;
+        const float v = w[((oo * Cr + ii) * K + a) * K + b];
+        if (!real)
+            return (tp == 0 && o == i) ? 1.0f : 0.0f;
         return (tp == 0 && ii > oo) ? 0.0f : v;
     };
     // four taps into LDS, sixteen loads of a thread in flight; columns C .. TP-1 and the rows of Linv past C are
@@ -183,7 +189,8 @@ __device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, f
 
 template <int CQ, int DIR>
 __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ in, const float *__restrict__ w,
-                                                    float *__restrict__ out, int H, int W, int NB, float *logdet)
+                                                    float *__restrict__ out, int H, int W, int NB, float *logdet,
+                                                    int Cr)
 {
     constexpr int C = 4 * CQ, K = kWideK, NT = K * K, R = kWideRing;
     constexpr int OB = wide_out_blocks(C), OR = 16 * OB, CPAD = C + 1;
@@ -197,7 +204,7 @@ __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ i
     const int band = wave / OB, ob = wave % OB;
     const int n = lane & 15, g = lane >> 4;
 
-    wide_fold_weights<CQ, DIR>(w, sWt, ring);
+    wide_fold_weights<CQ, DIR>(w, sWt, ring, Cr);
     for (int idx = tid; idx < R * HP * CPAD; idx += nt)
         ring[idx] = 0.0f;
     __syncthreads();
@@ -206,12 +213,12 @@ __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ i
     //      A operand row m = n -> output channel 16 ob + n; results: output channels 16 ob + 4 g + j
     const int r = 16 * band + n;
     const bool row_ok = r < H;
-    const size_t img = (size_t)blockIdx.x * C * H * W;
+    const size_t img = (size_t)blockIdx.x * Cr * H * W;
     const int a_base = (16 * ob + n) * CPAD + g;                 // + tp * OR * CPAD + 4 c4
     const int b_row = (r + K - 1) * CPAD + g;                    // + slot * HP * CPAD - da * CPAD + 4 c4
     const int o_first = 16 * ob + 4 * g;                         // first of this lane's four output channels
-    auto gaddr = [&](int ch, int rr, int cc) -> size_t {
-        return img + ((size_t)(DIR ? C - 1 - ch : ch) * H + (DIR ? H - 1 - rr : rr)) * W + (DIR ? W - 1 - cc : cc);
+    auto gaddr = [&](int ch, int rr, int cc) -> size_t {     // ch < Cr
+        return img + ((size_t)(DIR ? Cr - 1 - ch : ch) * H + (DIR ? H - 1 - rr : rr)) * W + (DIR ? W - 1 - cc : cc);
     };
     auto load_y = [&](int t, float (&yv)[CQ]) {
         const int c = t - r;
@@ -219,8 +226,9 @@ __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ i
         const int rr = row_ok ? r : 0, cc = ok ? c : 0;
 #pragma unroll
         for (int c4 = 0; c4 < CQ; ++c4) {
-            const float v = in[gaddr(4 * c4 + g, rr, cc)];
-            yv[c4] = ok ? v : 0.0f;
+            const int ch = 4 * c4 + g;
+            const float v = in[gaddr(ch < Cr ? ch : 0, rr, cc)];
+            yv[c4] = (ok && ch < Cr) ? v : 0.0f;
         }
     };
     float ycur[CQ], ynext[CQ];
@@ -278,7 +286,7 @@ __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ i
         for (int j = 0; j < 4; ++j) {
             if (o_first + j < C) {
                 rp[j] = ok ? acc[j] : 0.0f;                     // pixels outside the image count as zeros
-                if (ok)
+                if (ok && o_first + j < Cr)
                     out[gaddr(o_first + j, r, c)] = acc[j];
             }
         }
@@ -290,7 +298,7 @@ __global__ __launch_bounds__(1024) void k_solve_wide(const float *__restrict__ i
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
     }
     if (logdet && blockIdx.x == 0 && wave == 0)
-        wave_logdet_any(w, C, K, H, W, logdet);
+        wave_logdet_any(w, Cr, K, H, W, logdet);
 }
 
 // ---------------------------------------------------------------------------
@@ -337,7 +345,7 @@ __device__ __forceinline__ void wide_read_operands(const float *p, float (&o)[CQ
 template <int CQ, int DIR, int MAXW>
 __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__restrict__ in,
                                                               const float *__restrict__ w, float *__restrict__ out,
-                                                              int H, int W, int NB, float *logdet)
+                                                              int H, int W, int NB, float *logdet, int Cr)
 {
     constexpr int C = 4 * CQ, K = kWideK, NT = K * K, R = kWideRing;
     constexpr int OB = wide_out_blocks(C), OR = 16 * OB, CPAD = C + 1;
@@ -353,7 +361,7 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
     const int band = wave / OB, ob = wave % OB;
     const int n = lane & 15, g = lane >> 4;
 
-    wide_fold_weights<CQ, DIR>(w, sWt, sWt + NT * OR * CPAD);
+    wide_fold_weights<CQ, DIR>(w, sWt, sWt + NT * OR * CPAD, Cr);
     // this lane's A operands: row m = n -> output channel 16 ob + n, K slot g -> input channel 4 c4 + g
     float wAr[NT][CQ];
     {
@@ -371,12 +379,12 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
 
     const int r = 16 * band + n;
     const bool row_ok = r < H;
-    const size_t img = (size_t)blockIdx.x * C * H * W;
+    const size_t img = (size_t)blockIdx.x * Cr * H * W;
     const int b_row = (r + K - 1) * CP + g * CQ;                 // + slot * HP * CP - da * CP
     const int y_row = r * CP + g * CQ;                           // + slot * YR * CP
     const int o_first = 16 * ob + 4 * g;                         // first of this lane's four output channels
-    auto gaddr = [&](int ch, int rr, int cc) -> size_t {
-        return img + ((size_t)(DIR ? C - 1 - ch : ch) * H + (DIR ? H - 1 - rr : rr)) * W + (DIR ? W - 1 - cc : cc);
+    auto gaddr = [&](int ch, int rr, int cc) -> size_t {     // ch < Cr
+        return img + ((size_t)(DIR ? Cr - 1 - ch : ch) * H + (DIR ? H - 1 - rr : rr)) * W + (DIR ? W - 1 - cc : cc);
     };
     // the wave's share of the input of step t: channels 16 ob + 4 q + g, q = 0..3, of pixel (r, t - r)
     auto load_y = [&](int t, float (&yv)[4]) {
@@ -386,8 +394,8 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int ch = 16 * ob + 4 * q + g;
-            const float v = in[gaddr(ch < C ? ch : C - 1, rr, cc)];
-            yv[q] = (ok && ch < C) ? v : 0.0f;
+            const float v = in[gaddr(ch < Cr ? ch : Cr - 1, rr, cc)];
+            yv[q] = (ok && ch < Cr) ? v : 0.0f;
         }
     };
     auto store_y = [&](int slot, const float (&yv)[4]) {
@@ -488,7 +496,7 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
             const int ch = o_first + j;
             if (ch < C) {
                 rp[(ch & 3) * CQ + (ch >> 2)] = ok ? acc[j] : 0.0f;     // pixels outside the image count as zeros
-                if (ok)
+                if (ok && ch < Cr)
                     out[gaddr(ch, r, c)] = acc[j];
             }
         }
@@ -516,7 +524,7 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
         tm = tn;
     }
     if (logdet && blockIdx.x == 0 && wave == 0)
-        wave_logdet_any(w, C, K, H, W, logdet);
+        wave_logdet_any(w, Cr, K, H, W, logdet);
 }
 
 static size_t wide_reg_lds_bytes(int C, int H)
@@ -536,8 +544,8 @@ static bool wide_reg_supported(int C, int H)
 }
 
 template <int CQ, int MAXW>
-static int launch_wide_reg(int dir, const float *in, const float *w, float *out, int B, int H, int W, hipStream_t stream,
-                           float *logdet)
+static int launch_wide_reg(int dir, const float *in, const float *w, float *out, int B, int Cr, int H, int W,
+                           hipStream_t stream, float *logdet)
 {
     constexpr int C = 4 * CQ;
     const int NB = (H + 15) / 16;
@@ -554,9 +562,11 @@ static int launch_wide_reg(int dir, const float *in, const float *w, float *out,
         waves = 8 < MAXW ? 8 : MAXW;
     const dim3 block((unsigned)(64 * waves));
     if (dir)
-        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 1, MAXW>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet);
+        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 1, MAXW>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet,
+                           Cr);
     else
-        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 0, MAXW>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet);
+        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 0, MAXW>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet,
+                           Cr);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
@@ -567,21 +577,23 @@ static size_t wide_lds_bytes(int C, int H)
     return sizeof(float) * ((size_t)kWideK * kWideK * OR * CPAD + (ring > scratch ? ring : scratch));
 }
 
+// Channel counts that are no multiple of 4 run the next multiple with the surplus channels switched off.
 bool wide_supported(int C, int H, int k)
 {
-    return k == kWideK && C % 4 == 0 && C >= 20 && C <= 48 && ((H + 15) / 16) * wide_out_blocks(C) <= 16 &&
-           wide_lds_bytes(C, H) <= kMaxLdsBytes;
+    const int Cp = (C + 3) / 4 * 4;
+    return k == kWideK && C >= 17 && C <= 48 && ((H + 15) / 16) * wide_out_blocks(Cp) <= 16 &&
+           wide_lds_bytes(Cp, H) <= kMaxLdsBytes;
 }
 
 template <int CQ>
-static int launch_wide_cq(int dir, const float *in, const float *w, float *out, int B, int H, int W, hipStream_t stream,
-                         float *logdet)
+static int launch_wide_cq(int dir, const float *in, const float *w, float *out, int B, int Cr, int H, int W,
+                          hipStream_t stream, float *logdet)
 {
     constexpr int C = 4 * CQ;
     const int NB = (H + 15) / 16;
     if (wide_reg_supported(C, H))
-        return NB * wide_out_blocks(C) <= 8 ? launch_wide_reg<CQ, 8>(dir, in, w, out, B, H, W, stream, logdet)
-                                            : launch_wide_reg<CQ, 12>(dir, in, w, out, B, H, W, stream, logdet);
+        return NB * wide_out_blocks(C) <= 8 ? launch_wide_reg<CQ, 8>(dir, in, w, out, B, Cr, H, W, stream, logdet)
+                                            : launch_wide_reg<CQ, 12>(dir, in, w, out, B, Cr, H, W, stream, logdet);
     const size_t lds = wide_lds_bytes(C, H);
     const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide<CQ, 1>)
                          : reinterpret_cast<const void *>(&k_solve_wide<CQ, 0>);
@@ -589,9 +601,9 @@ static int launch_wide_cq(int dir, const float *in, const float *w, float *out, 
         return INVCONV_ERR_UNSUPPORTED;
     const dim3 block((unsigned)(64 * NB * wide_out_blocks(C)));
     if (dir)
-        hipLaunchKernelGGL((k_solve_wide<CQ, 1>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet);
+        hipLaunchKernelGGL((k_solve_wide<CQ, 1>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet, Cr);
     else
-        hipLaunchKernelGGL((k_solve_wide<CQ, 0>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet);
+        hipLaunchKernelGGL((k_solve_wide<CQ, 0>), dim3(B), block, lds, stream, in, w, out, H, W, NB, logdet, Cr);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
@@ -600,15 +612,15 @@ int launch_solve_wide(int dir, const float *in, const float *w, float *out, int 
 {
     if (!wide_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
-    switch (C / 4) {
-    case 5: return launch_wide_cq<5>(dir, in, w, out, B, H, W, stream, logdet);
-    case 6: return launch_wide_cq<6>(dir, in, w, out, B, H, W, stream, logdet);
-    case 7: return launch_wide_cq<7>(dir, in, w, out, B, H, W, stream, logdet);
-    case 8: return launch_wide_cq<8>(dir, in, w, out, B, H, W, stream, logdet);
-    case 9: return launch_wide_cq<9>(dir, in, w, out, B, H, W, stream, logdet);
-    case 10: return launch_wide_cq<10>(dir, in, w, out, B, H, W, stream, logdet);
-    case 11: return launch_wide_cq<11>(dir, in, w, out, B, H, W, stream, logdet);
-    case 12: return launch_wide_cq<12>(dir, in, w, out, B, H, W, stream, logdet);
+    switch ((C + 3) / 4) {
+    case 5: return launch_wide_cq<5>(dir, in, w, out, B, C, H, W, stream, logdet);
+    case 6: return launch_wide_cq<6>(dir, in, w, out, B, C, H, W, stream, logdet);
+    case 7: return launch_wide_cq<7>(dir, in, w, out, B, C, H, W, stream, logdet);
+    case 8: return launch_wide_cq<8>(dir, in, w, out, B, C, H, W, stream, logdet);
+    case 9: return launch_wide_cq<9>(dir, in, w, out, B, C, H, W, stream, logdet);
+    case 10: return launch_wide_cq<10>(dir, in, w, out, B, C, H, W, stream, logdet);
+    case 11: return launch_wide_cq<11>(dir, in, w, out, B, C, H, W, stream, logdet);
+    case 12: return launch_wide_cq<12>(dir, in, w, out, B, C, H, W, stream, logdet);
     default: return INVCONV_ERR_VARIANT;
     }
 }

@@ -63,7 +63,7 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     (2, 3, 64, 5, 3), (3, 1, 33, 20, 3), (1, 2, 64, 64, 3), (2, 4, 63, 9, 3), (1, 3, 5, 100, 5),
     (2, 12, 16, 16, 3), (1, 12, 33, 20, 3), (2, 8, 50, 17, 3), (1, 16, 128, 40, 3), (1, 12, 7, 100, 3),
     (3, 12, 1, 1, 3), (1, 8, 17, 2, 3), (1, 12, 129, 8, 3),
-    (1, 20, 6, 7, 2), (2, 18, 9, 5, 3),      # more than 16 channels: generic solve and generic dL/dw
+    (1, 20, 6, 7, 2), (2, 18, 9, 5, 3),      # more than 16 channels (k = 2: the LDS-window solve)
     (2, 48, 32, 32, 3), (1, 32, 40, 24, 3), (1, 24, 20, 12, 5), (1, 48, 60, 9, 3), (1, 40, 8, 8, 3),   # after two squeezes
     (2, 20, 17, 19, 3), (1, 28, 128, 8, 3), (3, 36, 7, 33, 3), (1, 44, 1, 1, 3), (2, 24, 50, 50, 3), (1, 32, 100, 12, 3),
     (1, 40, 64, 16, 3), (1, 32, 96, 20, 3), (2, 44, 33, 12, 3), (1, 48, 64, 24, 3),     # nine to twelve waves per image
@@ -83,6 +83,12 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     # 8 / 12 / 16 channels with the other kernel sizes of the kernel-size ablation (band kernel with k = 2, 5, 7)
     (2, 12, 16, 16, 5), (3, 8, 40, 24, 2), (2, 16, 33, 20, 5), (2, 12, 64, 24, 7), (1, 8, 16, 16, 7), (2, 16, 16, 16, 2),
     (2, 12, 20, 12, 2), (1, 16, 64, 9, 5), (3, 12, 7, 50, 5),
+    # channel counts between the band kernels' sizes (5-7, 9-11, 13-15): the next size up with the surplus slots off
+    (3, 6, 16, 16, 3), (2, 5, 9, 11, 3), (2, 7, 33, 20, 3), (1, 10, 128, 40, 3), (2, 14, 40, 24, 3), (1, 15, 100, 8, 3),
+    (2, 6, 20, 20, 2), (2, 10, 33, 16, 5), (1, 9, 40, 12, 7), (40, 6, 32, 32, 3), (2, 13, 16, 30, 3),
+    # many channels, no multiple of 4 (17-47): the many-channel kernels with the surplus channels switched off
+    (2, 17, 9, 11, 3), (1, 19, 40, 24, 3), (2, 23, 8, 8, 3), (1, 30, 96, 20, 3), (2, 33, 16, 16, 3), (1, 41, 64, 9, 3),
+    (2, 45, 8, 8, 3), (3, 46, 8, 8, 3), (1, 37, 32, 32, 3),
     # shapes no on-chip kernel holds: one launch per anti-diagonal, a wave per pixel
     (5, 64, 4, 4, 3), (2, 96, 2, 2, 3), (1, 44, 70, 9, 3), (2, 128, 2, 3, 3), (1, 52, 5, 6, 2), (1, 64, 3, 3, 5),
     # 8 / 12 channels, large batches or tall images: single-layer solves through the pipelined kernel
@@ -195,6 +201,26 @@ def test_tall_images_with_and_without_workspace_agree(shape):
         with pytest.raises(b.InvconvError) as ei:
             b.invconv_fwd(yd, wd, workspace=tiny)
         assert ei.value.status == b.ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("shape", [(2, 6, 16, 16, 3), (2, 10, 40, 24, 3), (3, 15, 20, 12, 5), (2, 22, 16, 12, 3),
+                                   (1, 45, 8, 8, 3)])
+def test_masked_garbage_with_surplus_channel_slots(shape):
+    """Channel counts that run the band or many-channel kernels with surplus channel slots: entries above the
+    diagonal of the current-pixel block are ignored and get zero gradient, and the surplus slots leak nothing into
+    the results."""
+    B, C, H, W, k = shape
+    iu = np.triu_indices(C, 1)
+    cs = inputs.make_case(B, C, H, W, k, seed=sum(shape) + 5, tap_std=0.1 / k)
+    y, w, g = cs["y"], cs["w"][0].copy(), cs["g"]
+    ref = run_layer(y, w, g)
+    w[:, :, k - 1, k - 1][iu] = 1e6
+    got = run_layer(y, w, g)
+    for a, r in zip(got[:3], ref[:3]):
+        np.testing.assert_array_equal(a, r)
+    assert np.all(got[2][:, :, k - 1, k - 1][iu] == 0.0)
+    xr = oracle.invconv_fwd(y, w, THREADS)
+    assert rel_err(got[0], xr) <= TOL_ACT
 
 
 def test_masked_garbage_at_twelve_channels():
