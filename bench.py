@@ -538,7 +538,9 @@ def flow_step_study(reps=50, only=None):
         # separate passes: 24 forward, 40 backward (few channels: the fused dL/dw kernel saves 4 of them)
         fused_bytes = 20.0 if C <= 4 else 40.0
         sep_bytes = 60.0 if C <= 4 else 64.0
-        for form, tag, bytes_per_elt in ((b.FLOW_FUSED, "fused", fused_bytes), (b.FLOW_SEPARATE, "separate", sep_bytes)):
+        # "auto" is what a caller gets: few images of few channels ride on the split solve kernels (map applied inside)
+        for form, tag, bytes_per_elt in ((b.FLOW_FUSED, "fused", fused_bytes), (b.FLOW_SEPARATE, "separate", sep_bytes),
+                                         (b.FLOW_AUTO, "auto", fused_bytes)):
             fwd = lambda: b.invconv_flowstep_fwd(y, w, s, bb, Q, out=z, workspace=ws, form=form)
             bwd = lambda: b.invconv_flowstep_bwd(z, w, s, bb, Q, g, logdet_weight=-float(B), workspace=ws, form=form,
                                                  out=grads)

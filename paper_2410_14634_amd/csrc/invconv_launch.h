@@ -66,6 +66,10 @@ int launch_solve_wide(int dir, const float *in, const float *w, float *out, int 
                       hipStream_t stream, float *logdet = nullptr);
 bool bwd_wave_supported(int C, int H, int W, int k);
 bool bwd_wave_fused_pays(int B, int C, int H, int W, int k);   // false: solve and weight gradient as separate launches
+// one flow step's forward pass (y in, z out, log-determinant of the step on the side) on the split solve, no set-up launch
+bool flow_split_supported(int B, int C, int H, int W, int k);
+int launch_flow_fwd_split(const float *y, const float *w, const float *s, const float *b, const float *Q, float *z,
+                          int B, int C, int H, int W, int k, hipStream_t stream, float *logdet);
 int launch_solve_wave_split(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                             hipStream_t stream, float *logdet = nullptr);
 bool wave_split_preferred(int B, int H, int W, int k);

@@ -21,6 +21,7 @@
 // four result registers are the pixel's output channels).
 #include "invconv_common.h"
 #include "invconv_launch.h"
+#include "invconv_small_mat.h"
 #include "invconv_wave_solve.h"
 #include <type_traits>
 #include <utility>
@@ -223,12 +224,57 @@ __device__ __forceinline__ void wave_split_dispatch(int wave, F &&f, std::intege
     ((wave == Is + 1 ? (f(std::integral_constant<int, Is>{}), 0) : 0), ...);
 }
 
-template <int C, int K, int DIR, bool LDS_COPY, int NF = 2>
+// The neighbours of the inverse convolution in a flow step (Section 4.1: Actnorm a = s x + b, then the 1 x 1
+// convolution z = Q a) as the kernels of few channels take them: the three parameter tensors in memory; a wave
+// that needs the channel map z = A x + d (A = Q diag(s), d = Q b) forms it in registers.
+struct FlowParams {
+    const float *s, *b, *Q;
+};
+
+template <int C>
+__device__ __forceinline__ void flow_map_regs(FlowParams fp, float (&A)[C][C], float (&d)[C])
+{
+#pragma unroll
+    for (int o = 0; o < C; ++o) {
+        double acc = 0.0;
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+            A[o][i] = fp.Q[o * C + i] * fp.s[i];
+            acc += (double)fp.Q[o * C + i] * (double)fp.b[i];
+        }
+        d[o] = (float)acc;
+    }
+}
+
+// log|det dz/dy| of one image for the whole step, by one wave (every lane the same arithmetic, lane 0 writes):
+//   H W ( sum log|s[c]| + log|det Q| - sum log|w[c][c][k-1][k-1]| )        (Section 4)
+template <int C, int K>
+__device__ __forceinline__ void flow_logdet_small(const float *__restrict__ w, FlowParams fp, int H, int W,
+                                                  float *__restrict__ out)
+{
+    double q[C][C], qi[C][C];
+#pragma unroll
+    for (int o = 0; o < C; ++o)
+#pragma unroll
+        for (int i = 0; i < C; ++i)
+            q[o][i] = (double)fp.Q[o * C + i];
+    double acc = log(fabs(small_det_inv<C>(q, qi)));
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+        acc += log(fabs((double)fp.s[c])) - log(fabs((double)w[((c * C + c) * K + (K - 1)) * K + (K - 1)]));
+    if ((threadIdx.x & 63) == 0)
+        out[0] = (float)((double)H * (double)W * acc);
+}
+
+// MAP (forward direction only): the wave that stores x applies the flow step's channel map on the way out, so what
+// reaches memory is z = A x + d; x stays in the workgroup.
+template <int C, int K, int DIR, bool LDS_COPY, int NF = 2, bool MAP = false>
 __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ in, const float *__restrict__ w,
                                                       float *__restrict__ out, int H, int W, int n, float *lds_copy,
-                                                      WaveSplitLds sl)
+                                                      WaveSplitLds sl, FlowParams fp = FlowParams{})
 {
     static_assert(C >= 1 && C <= 4 && K >= 3, "one 4-row MFMA block per pixel");
+    static_assert(!MAP || (DIR == 0 && !LDS_COPY), "the channel map goes with the plain forward solve");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane;
@@ -369,6 +415,9 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
         // O_{s+1} = Linv y_{s+1} + sum_{db>=2} A[0][db] x_{s+1-db}; also x_{s-1} to global memory
         float wA[K][K][C], wLi[C];
         wave_fold_regs<C, K, DIR>(w, o_lane, wA, wLi);
+        float mA[MAP ? C : 1][MAP ? C : 1], md[MAP ? C : 1];
+        if constexpr (MAP)
+            flow_map_regs<C>(fp, mA, md);
         float xo[K][C];     // xo[db] = x_{s+1-db}, db >= 2
 #pragma unroll
         for (int db = 0; db < K; ++db)
@@ -402,7 +451,14 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
                 const unsigned off = (unsigned)(row0 + kStep * c);
 #pragma unroll
                 for (int o = 0; o < C; ++o) {
-                    *reinterpret_cast<float *>(chan_dst[o] + off) = xo[2][o];
+                    float val = xo[2][o];
+                    if constexpr (MAP) {
+                        val = md[o];
+#pragma unroll
+                        for (int i = 0; i < C; ++i)
+                            val += mA[o][i] * xo[2][i];
+                    }
+                    *reinterpret_cast<float *>(chan_dst[o] + off) = val;
                     if (LDS_COPY)
                         *reinterpret_cast<float *>(chan_lds[o] + off) = xo[2][o];
                 }
@@ -445,6 +501,23 @@ __global__ __launch_bounds__(64 * (wave_split_nf(K) + 2)) void k_solve_wave_spli
     sl.x = smem;
     sl.m = reinterpret_cast<f32x4 *>(smem + 2 * C * 64);
     solve_wave_split_body<C, K, DIR, false, wave_split_nf(K)>(in, w, out, H, W, blockIdx.x, nullptr, sl);
+}
+
+// Forward pass of a whole flow step for few channels and few images: the split solve with the channel map on its
+// way out (y in, z out) and the step's log-determinant on the side; no set-up launch.
+template <int C, int K>
+__global__ __launch_bounds__(64 * (wave_split_nf(K) + 2)) void k_flow_fwd_split(const float *__restrict__ y,
+                                                                                const float *__restrict__ w,
+                                                                                FlowParams fp, float *__restrict__ z,
+                                                                                int H, int W, float *logdet)
+{
+    __shared__ __attribute__((aligned(16))) float smem[wave_split_lds_floats<C, K>()];
+    if (logdet && blockIdx.x == 0 && (threadIdx.x >> 6) == 1)
+        flow_logdet_small<C, K>(w, fp, H, W, logdet);
+    WaveSplitLds sl;
+    sl.x = smem;
+    sl.m = reinterpret_cast<f32x4 *>(smem + 2 * C * 64);
+    solve_wave_split_body<C, K, 0, false, wave_split_nf(K), true>(y, w, z, H, W, blockIdx.x, nullptr, sl, fp);
 }
 
 // Images of 65 .. 512 rows: one workgroup per image, one wave per band of 64 rows.
@@ -1484,6 +1557,37 @@ static int launch_wave_split_ck(int dir, const float *in, const float *w, float 
 }
 
 // Same shapes as the single-wave kernel; four to seven waves per image.
+// The flow step's forward pass on the split solve: the shapes of the fused flow kernels (few channels, k = 3, or
+// three channels and k = 5) while the split solve is the better single-layer kernel (few images).
+bool flow_split_supported(int B, int C, int H, int W, int k)
+{
+    const bool ck = (C == 3 && (k == 3 || k == 5)) || ((C == 1 || C == 2 || C == 4) && k == 3);
+    return ck && wave_supported(C, H, k) && wave_split_preferred(B, H, W, k) && !wave_tile_preferred(B, C, H, W);
+}
+
+template <int C, int K>
+static int launch_flow_fwd_split_ck(const float *y, const float *w, FlowParams fp, float *z, int B, int H, int W,
+                                    hipStream_t stream, float *logdet)
+{
+    hipLaunchKernelGGL((k_flow_fwd_split<C, K>), dim3(B), dim3(64 * (wave_split_nf(K) + 2)), 0, stream, y, w, fp, z, H,
+                       W, logdet);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+int launch_flow_fwd_split(const float *y, const float *w, const float *s, const float *b, const float *Q, float *z,
+                          int B, int C, int H, int W, int k, hipStream_t stream, float *logdet)
+{
+    if (!flow_split_supported(B, C, H, W, k))
+        return INVCONV_ERR_VARIANT;
+    const FlowParams fp{s, b, Q};
+    if (C == 3 && k == 3) return launch_flow_fwd_split_ck<3, 3>(y, w, fp, z, B, H, W, stream, logdet);
+    if (C == 3 && k == 5) return launch_flow_fwd_split_ck<3, 5>(y, w, fp, z, B, H, W, stream, logdet);
+    if (C == 1 && k == 3) return launch_flow_fwd_split_ck<1, 3>(y, w, fp, z, B, H, W, stream, logdet);
+    if (C == 2 && k == 3) return launch_flow_fwd_split_ck<2, 3>(y, w, fp, z, B, H, W, stream, logdet);
+    if (C == 4 && k == 3) return launch_flow_fwd_split_ck<4, 3>(y, w, fp, z, B, H, W, stream, logdet);
+    return INVCONV_ERR_VARIANT;
+}
+
 int launch_solve_wave_split(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                             hipStream_t stream, float *logdet)
 {
