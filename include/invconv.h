@@ -203,8 +203,10 @@ invconv_status invconv_logdet(const float *w, int C, int H, int W, int k,
  *     x = invconv_w(y),   a[c] = s[c] x[c] + b[c],   z[o] = sum_i Q[o][i] a[i]   at every pixel.
  * Only z is written: for few-channel images that fit on chip (C <= 4, H <= 64, W a multiple of 4, k = 3, or
  * C = 3 with k = 5) and batches of 4 MB or more the three layers run as ONE kernel that reads y and writes z,
- * i.e. the HBM traffic of the inverse convolution alone; other shapes run the same arithmetic as separate
- * passes over scratch.
+ * i.e. the HBM traffic of the inverse convolution alone; for a few such images the kernel that solves one image
+ * on several waves applies the two neighbours on its way out (one launch, no set-up launch; the backward pass
+ * of k = 3 likewise, plus one small launch that finishes the parameter gradients); other shapes run the same
+ * arithmetic as separate passes over scratch.
  *   s, b [in] C floats each;  Q [in] C*C floats, row = output channel; must be invertible (a singular Q
  *   yields inf/NaN like a zero diagonal of w).
  *   z [out] B*C*H*W, must not alias an input.

@@ -662,6 +662,13 @@ invconv_status invconv_flowstep_bwd_ex(const float *z, const float *w, const flo
     char *ws = (char *)workspace;
     float *mats = (float *)(ws + lay.mats_off), *sums = (float *)(ws + lay.sums_off), *rows = (float *)(ws + lay.rows_off);
     const int P = C * C * k * k, E2 = C * C + C;
+    // few channels, few images: two launches, the eight-wave backward kernel with the channel maps inside and the
+    // kernel that sums its rows and finishes the parameter gradients
+    if (form == INVCONV_FLOW_AUTO && flow_bwd_split_supported(B, C, H, W, k)) {
+        if (int rc = launch_flow_bwd_split(z, w, dLdz, s, b, Q, dLdy, rows, B, C, H, W, k, st))
+            return rc;
+        return launch_flow_finish_rows(rows, B, w, s, b, Q, dLdw, dLds, dLdb, dLdQ, logdet_weight, C, H, W, k, st);
+    }
     if (int rc = launch_flow_prep(w, s, b, Q, mats, nullptr, C, H, W, k, st))
         return rc;
     if (form != INVCONV_FLOW_SEPARATE && flow_fused_supported(C, H, W, k) && aligned16(z, dLdz, dLdy) &&

@@ -11,6 +11,7 @@
 // shapes run the same arithmetic as separate passes.  gfx950 only.
 #include "invconv_common.h"
 #include "invconv_launch.h"
+#include "invconv_small_mat.h"
 #include "invconv_wave_solve.h"
 
 namespace invconv {
@@ -303,18 +304,18 @@ __global__ __launch_bounds__(64 * NW) void k_rows_sum(const float *__restrict__ 
 // and adds lw times the gradient of the step's log-determinant (Section 4; closed forms):
 //   dLdw[c][c][k-1][k-1] -= lw H W / w[c][c][k-1][k-1],  dLds[c] += lw H W / s[c],  dLdQ += lw H W Q^-T.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_flow_finish(const float *__restrict__ sums, int have_dw,
-                                                    const float *__restrict__ w, const float *__restrict__ s,
-                                                    const float *__restrict__ b, const float *__restrict__ Q,
-                                                    const float *__restrict__ mats, float *__restrict__ dLdw,
-                                                    float *__restrict__ dLds, float *__restrict__ dLdb,
-                                                    float *__restrict__ dLdQ, float lw, int C, int H, int W, int k)
+// (sums and QinvT = Q^-T may live in LDS or in global memory; nt threads)
+__device__ __forceinline__ void flow_finish_body(const float *sums, int have_dw, const float *__restrict__ w,
+                                                 const float *__restrict__ s, const float *__restrict__ b,
+                                                 const float *__restrict__ Q, const float *QinvT,
+                                                 float *__restrict__ dLdw, float *__restrict__ dLds,
+                                                 float *__restrict__ dLdb, float *__restrict__ dLdQ, float lw, int C,
+                                                 int H, int W, int k, int tid, int nt)
 {
-    const int tid = threadIdx.x;
     const int P = C * C * k * k;
     const float hw = (float)H * (float)W;
     const float *M2 = sums + (have_dw ? P : 0), *m1 = M2 + C * C;
-    for (int e = tid; e < P; e += 256) {
+    for (int e = tid; e < P; e += nt) {
         const int bb = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
         const bool centre = a == k - 1 && bb == k - 1;
         float v = have_dw ? ((centre && i > o) ? 0.0f : -sums[e]) : dLdw[e];
@@ -323,14 +324,14 @@ __global__ __launch_bounds__(256) void k_flow_finish(const float *__restrict__ s
         if (have_dw || (centre && i == o && lw != 0.0f))
             dLdw[e] = v;
     }
-    for (int e = tid; e < C * C; e += 256) {
+    for (int e = tid; e < C * C; e += nt) {
         const int o = e / C, i = e % C;
         float v = s[i] * M2[e] + b[i] * m1[o];
         if (lw != 0.0f)
-            v += lw * hw * mats[flow_off_QinvT(C) + e];
+            v += lw * hw * QinvT[e];
         dLdQ[e] = v;
     }
-    for (int i = tid; i < C; i += 256) {
+    for (int i = tid; i < C; i += nt) {
         float vs = 0.0f, vb = 0.0f;
         for (int o = 0; o < C; ++o) {
             vs += Q[o * C + i] * M2[o * C + i];
@@ -341,6 +342,80 @@ __global__ __launch_bounds__(256) void k_flow_finish(const float *__restrict__ s
         dLds[i] = vs;
         dLdb[i] = vb;
     }
+}
+
+__global__ __launch_bounds__(256) void k_flow_finish(const float *__restrict__ sums, int have_dw,
+                                                    const float *__restrict__ w, const float *__restrict__ s,
+                                                    const float *__restrict__ b, const float *__restrict__ Q,
+                                                    const float *__restrict__ mats, float *__restrict__ dLdw,
+                                                    float *__restrict__ dLds, float *__restrict__ dLdb,
+                                                    float *__restrict__ dLdQ, float lw, int C, int H, int W, int k)
+{
+    flow_finish_body(sums, have_dw, w, s, b, Q, mats + flow_off_QinvT(C), dLdw, dLds, dLdb, dLdQ, lw, C, H, W, k,
+                     threadIdx.x, 256);
+}
+
+// The same last step for few channels and at most a few hundred images, straight from the per-image rows
+// [P | C*C | C] of the fused backward kernel: sixteen waves add the rows in a fixed order (wave v rows v, v + 16,
+// ..., double accumulators, then the waves in order), Q^-T comes from cofactors, no other launch is needed.
+template <int C>
+__global__ __launch_bounds__(1024) void k_flow_finish_rows(const float *__restrict__ rows, int nrows,
+                                                          const float *__restrict__ w, const float *__restrict__ s,
+                                                          const float *__restrict__ b, const float *__restrict__ Q,
+                                                          float *__restrict__ dLdw, float *__restrict__ dLds,
+                                                          float *__restrict__ dLdb, float *__restrict__ dLdQ, float lw,
+                                                          int H, int W, int k)
+{
+    constexpr int NW = 16, EMAX = C * C * 3 * 3 + C * C + C, NCH = (EMAX + 63) / 64;
+    __shared__ double swave[NW][NCH * 64];
+    __shared__ float ssum[NCH * 64];
+    __shared__ float sQinvT[C * C];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int E = C * C * k * k + C * C + C;       // k = 3: E = EMAX
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        const int e = ch * 64 + lane;
+        double acc = 0.0;
+        if (e < E) {
+            for (int p = wave; p < nrows; p += 8 * NW) {        // eight rows in flight (clamped addresses)
+                float a[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int r = p + NW * u;
+                    a[u] = rows[(size_t)(r < nrows ? r : nrows - 1) * E + e];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    acc += p + NW * u < nrows ? (double)a[u] : 0.0;
+            }
+        }
+        swave[wave][e] = acc;
+    }
+    if (tid < C * C) {
+        double q[C][C], qi[C][C];
+#pragma unroll
+        for (int o = 0; o < C; ++o)
+#pragma unroll
+            for (int i = 0; i < C; ++i)
+                q[o][i] = (double)Q[o * C + i];
+        small_det_inv<C>(q, qi);
+#pragma unroll
+        for (int o = 0; o < C; ++o)
+#pragma unroll
+            for (int i = 0; i < C; ++i)
+                if (tid == o * C + i)
+                    sQinvT[tid] = (float)qi[i][o];
+    }
+    __syncthreads();
+    for (int e = tid; e < E; e += 1024) {
+        double total = swave[0][e];
+#pragma unroll
+        for (int v = 1; v < NW; ++v)
+            total += swave[v][e];
+        ssum[e] = (float)total;
+    }
+    __syncthreads();
+    flow_finish_body(ssum, 1, w, s, b, Q, sQinvT, dLdw, dLds, dLdb, dLdQ, lw, C, H, W, k, tid, 1024);
 }
 
 // ---------------------------------------------------------------------------
@@ -635,6 +710,21 @@ int launch_flow_finish(const float *sums, int have_dw, const float *w, const flo
 {
     hipLaunchKernelGGL(k_flow_finish, dim3(1), dim3(256), 0, stream, sums, have_dw, w, s, b, Q, mats, dLdw, dLds, dLdb,
                        dLdQ, lw, C, H, W, k);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+int launch_flow_finish_rows(const float *rows, int nrows, const float *w, const float *s, const float *b,
+                            const float *Q, float *dLdw, float *dLds, float *dLdb, float *dLdQ, float lw, int C, int H,
+                            int W, int k, hipStream_t stream)
+{
+    if (C < 1 || C > 4 || k != 3 || nrows < 1)
+        return INVCONV_ERR_VARIANT;
+    switch (C) {
+    case 1: hipLaunchKernelGGL((k_flow_finish_rows<1>), dim3(1), dim3(1024), 0, stream, rows, nrows, w, s, b, Q, dLdw, dLds, dLdb, dLdQ, lw, H, W, k); break;
+    case 2: hipLaunchKernelGGL((k_flow_finish_rows<2>), dim3(1), dim3(1024), 0, stream, rows, nrows, w, s, b, Q, dLdw, dLds, dLdb, dLdQ, lw, H, W, k); break;
+    case 3: hipLaunchKernelGGL((k_flow_finish_rows<3>), dim3(1), dim3(1024), 0, stream, rows, nrows, w, s, b, Q, dLdw, dLds, dLdb, dLdQ, lw, H, W, k); break;
+    default: hipLaunchKernelGGL((k_flow_finish_rows<4>), dim3(1), dim3(1024), 0, stream, rows, nrows, w, s, b, Q, dLdw, dLds, dLdb, dLdQ, lw, H, W, k); break;
+    }
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

@@ -70,6 +70,14 @@ bool bwd_wave_fused_pays(int B, int C, int H, int W, int k);   // false: solve a
 bool flow_split_supported(int B, int C, int H, int W, int k);
 int launch_flow_fwd_split(const float *y, const float *w, const float *s, const float *b, const float *Q, float *z,
                           int B, int C, int H, int W, int k, hipStream_t stream, float *logdet);
+// the step's backward pass on eight waves per image (z and dL/dz in; dL/dy and one row [C*C*k*k | C*C | C] per image
+// out), and the last kernel that turns those rows into the parameter gradients
+bool flow_bwd_split_supported(int B, int C, int H, int W, int k);
+int launch_flow_bwd_split(const float *z, const float *w, const float *gz, const float *s, const float *b,
+                          const float *Q, float *v, float *part, int B, int C, int H, int W, int k, hipStream_t stream);
+int launch_flow_finish_rows(const float *rows, int nrows, const float *w, const float *s, const float *b,
+                            const float *Q, float *dLdw, float *dLds, float *dLdb, float *dLdQ, float lw, int C, int H,
+                            int W, int k, hipStream_t stream);
 int launch_solve_wave_split(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                             hipStream_t stream, float *logdet = nullptr);
 bool wave_split_preferred(int B, int H, int W, int k);

@@ -266,15 +266,17 @@ __device__ __forceinline__ void flow_logdet_small(const float *__restrict__ w, F
         out[0] = (float)((double)H * (double)W * acc);
 }
 
-// MAP (forward direction only): the wave that stores x applies the flow step's channel map on the way out, so what
-// reaches memory is z = A x + d; x stays in the workgroup.
+// MAP, forward direction: the wave that stores x applies the flow step's channel map on the way out, so what
+// reaches memory is z = A x + d; x stays in the workgroup.  MAP, transposed direction: the input is dL/dz and the
+// solve wants A^T dL/dz; the input enters only through Linv y, so A^T is folded into Linv once (in mirrored channel
+// order, like everything else in that direction).
 template <int C, int K, int DIR, bool LDS_COPY, int NF = 2, bool MAP = false>
 __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ in, const float *__restrict__ w,
                                                       float *__restrict__ out, int H, int W, int n, float *lds_copy,
                                                       WaveSplitLds sl, FlowParams fp = FlowParams{})
 {
     static_assert(C >= 1 && C <= 4 && K >= 3, "one 4-row MFMA block per pixel");
-    static_assert(!MAP || (DIR == 0 && !LDS_COPY), "the channel map goes with the plain forward solve");
+    static_assert(!MAP || DIR == 1 || !LDS_COPY, "the outgoing channel map goes with the plain forward solve");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane;
@@ -416,8 +418,22 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
         float wA[K][K][C], wLi[C];
         wave_fold_regs<C, K, DIR>(w, o_lane, wA, wLi);
         float mA[MAP ? C : 1][MAP ? C : 1], md[MAP ? C : 1];
-        if constexpr (MAP)
+        if constexpr (MAP) {
             flow_map_regs<C>(fp, mA, md);
+            if constexpr (DIR == 1) {
+                float folded[C];
+#pragma unroll
+                for (int j = 0; j < C; ++j) {
+                    folded[j] = 0.0f;
+#pragma unroll
+                    for (int m = 0; m < C; ++m)
+                        folded[j] += wLi[m] * mA[C - 1 - j][C - 1 - m];     // (A^T in mirrored order)[m][j]
+                }
+#pragma unroll
+                for (int j = 0; j < C; ++j)
+                    wLi[j] = folded[j];
+            }
+        }
         float xo[K][C];     // xo[db] = x_{s+1-db}, db >= 2
 #pragma unroll
         for (int db = 0; db < K; ++db)
@@ -452,7 +468,7 @@ __device__ __forceinline__ void solve_wave_split_body(const float *__restrict__ 
 #pragma unroll
                 for (int o = 0; o < C; ++o) {
                     float val = xo[2][o];
-                    if constexpr (MAP) {
+                    if constexpr (MAP && DIR == 0) {
                         val = md[o];
 #pragma unroll
                         for (int i = 0; i < C; ++i)
@@ -1439,6 +1455,240 @@ __global__ __launch_bounds__(512) void k_bwd_wave8(const float *__restrict__ x, 
     __syncthreads();
     for (int e = tid; e < P; e += 512)
         part[(size_t)n * P + e] = ((swave[e] + swave[P + e]) + swave[2 * P + e]) + swave[3 * P + e];
+}
+
+// ---------------------------------------------------------------------------
+// Backward pass of a whole flow step for few channels and few images, on the same eight waves: the inputs are z
+// and dL/dz.  Waves 0..3 run the transposed solve on dL/dz with A^T folded into its input weights; waves 4..7
+// stage x = A^-1 z - b/s (zero halo) and dL/dz in LDS and form, behind the wavefront, the outer products of the
+// weight gradient and, with dL/dz as the first operand, M2[o][i] = sum dL/dz[o] x[i] and m1[o] = sum dL/dz[o].
+// One row [P | C*C | C] per image, fixed-order sums; no set-up launch (the waves form the small matrices
+// themselves).
+// ---------------------------------------------------------------------------
+template <int C, int K>
+__global__ __launch_bounds__(512) void k_flow_bwd_wave8(const float *__restrict__ z, const float *__restrict__ w,
+                                                       const float *__restrict__ gz, FlowParams fp,
+                                                       float *__restrict__ v, float *__restrict__ part, int H, int W)
+{
+    extern __shared__ float smem[];
+    constexpr int NCOL = C * K * K, NS = (NCOL + 3) / 4, P = C * NCOL;
+    constexpr int NC2 = C + 1, NS2 = (NC2 + 3) / 4, P2 = C * NC2;       // second operand: x[i] of the pixel, and 1
+    constexpr int NST = NS + NS2, PT = P + P2;
+    const int XR = H + K - 1, XW = W + K - 1, HW = H * W;
+    float *sv = smem;                          // [C][H][W]   dL/dy as the solve completes it
+    float *sx = sv + C * HW;                   // [C][XR][XW] x, origin at (-(K-1), -(K-1))
+    float *sg = sx + C * XR * XW;              // [C][H][W]   dL/dz
+    float *sred = smem;                        // [4*64][NST*4], reuses the tiles after the products
+    const int n = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    if (wave < 4) {
+        __builtin_amdgcn_s_setprio(2);      // the dependent chain goes first; the helpers fill the gaps
+        WaveSplitLds sl;
+        sl.x = smem + ((2 * C * HW + C * XR * XW + 3) & ~3);    // 16-byte aligned behind the tiles
+        sl.m = reinterpret_cast<f32x4 *>(sl.x + 2 * C * 64);
+        solve_wave_split_body<C, K, 1, true, 2, true>(gz, w, v, H, W, n, sv, sl, fp);
+        __syncthreads();        // the helpers have finished the products
+    } else {
+        const int ht = tid - 256, hw = wave - 4;
+        // A^-1 = diag(1/s) Q^-1 and e = -b/s
+        float Ai[C][C], ev[C];
+        {
+            double q[C][C], qi[C][C];
+#pragma unroll
+            for (int o = 0; o < C; ++o)
+#pragma unroll
+                for (int i = 0; i < C; ++i)
+                    q[o][i] = (double)fp.Q[o * C + i];
+            small_det_inv<C>(q, qi);
+#pragma unroll
+            for (int i = 0; i < C; ++i) {
+                ev[i] = -fp.b[i] / fp.s[i];
+#pragma unroll
+                for (int o = 0; o < C; ++o)
+                    Ai[i][o] = (float)(qi[i][o] / (double)fp.s[i]);
+            }
+        }
+        const float *zi = z + (size_t)n * C * HW, *gi = gz + (size_t)n * C * HW;
+        // a thread takes positions of the padded x tile, four at a time: all channels of z and dL/dz of the pixel
+        for (int base = ht; base < XR * XW; base += 4 * 256) {
+            float zv[4][C], gv[4][C];
+            bool halo[4];
+            int gpix[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int raw = base + u * 256;
+                const int idx = raw < XR * XW ? raw : XR * XW - 1;
+                const int cc = idx % XW, rr = idx / XW;
+                const int gr = rr - (K - 1), gc = cc - (K - 1);
+                halo[u] = gr < 0 || gc < 0;
+                gpix[u] = (gr < 0 ? 0 : gr) * W + (gc < 0 ? 0 : gc);
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    zv[u][c] = zi[c * HW + gpix[u]];
+                    gv[u][c] = gi[c * HW + gpix[u]];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int raw = base + u * 256;
+                if (raw < XR * XW) {
+#pragma unroll
+                    for (int i = 0; i < C; ++i) {
+                        float xi = ev[i];
+#pragma unroll
+                        for (int o = 0; o < C; ++o)
+                            xi += Ai[i][o] * zv[u][o];
+                        sx[i * XR * XW + raw] = halo[u] ? 0.0f : xi;
+                        if (!halo[u])
+                            sg[i * HW + gpix[u]] = gv[u][i];
+                    }
+                }
+            }
+        }
+        // lane = (block b, j): first operand row o = j (of dL/dy, or of dL/dz), second operand column 4s + j
+        // (padding rows / columns read valid data, unused)
+        const int j = lane & 3, b = lane >> 2;
+        const int aoff = (j < C) ? j * HW : 0;
+        int boff[NST];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const int col = (4 * s + j < NCOL) ? 4 * s + j : 0;
+            const int i = col / (K * K), a = (col / K) % K, bb = col % K;
+            boff[s] = (i * XR + a) * XW + bb;
+        }
+        bool one[NS2];
+#pragma unroll
+        for (int s = 0; s < NS2; ++s) {
+            const int col = 4 * s + j;
+            one[s] = col == C;
+            boff[NS + s] = ((col < C ? col : 0) * XR + (K - 1)) * XW + (K - 1);
+        }
+        f32x4 acc[NST];
+#pragma unroll
+        for (int s = 0; s < NST; ++s)
+            acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // one group: 16 pixels pc .. pc+15 of image row pr
+        auto group = [&](int pr, int pc) {
+            const float av = sv[aoff + pr * W + b + pc], ag = sg[aoff + pr * W + b + pc];
+            const float *bp = sx + pr * XW + b + pc;
+            float bv[NST];
+#pragma unroll
+            for (int s = 0; s < NST; ++s)
+                bv[s] = bp[boff[s]];
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                acc[s] = __builtin_amdgcn_mfma_f32_4x4x1f32(av, bv[s], acc[s], 0, 0, 0);
+#pragma unroll
+            for (int s = 0; s < NS2; ++s)
+                acc[NS + s] = __builtin_amdgcn_mfma_f32_4x4x1f32(ag, one[s] ? 1.0f : bv[NS + s], acc[NS + s], 0, 0, 0);
+        };
+        const int ngrp = W >> 4;
+        int row = hw, grp = 0;                  // next group of this helper: mirrored row `row`, group `grp`
+        __syncthreads();        // the solving waves' set-up barrier; x and dL/dz are staged for all helpers
+        const int total = H + W - 1 + 2;
+        for (int s = -1; s < total - 1; ++s) {
+            // mirrored row r is complete once step r + W has ended, i.e. from step r + W + 1 on
+            if (row < H && row + W + 1 <= s) {
+                group(H - 1 - row, 16 * grp);
+                if (++grp == ngrp) {
+                    grp = 0;
+                    row += 4;
+                }
+            }
+            __syncthreads();
+        }
+        // (the last step's barrier has passed: every row is complete)
+        while (row < H) {
+            group(H - 1 - row, 16 * grp);
+            if (++grp == ngrp) {
+                grp = 0;
+                row += 4;
+            }
+        }
+        __syncthreads();        // products finished: the tiles can be reused
+#pragma unroll
+        for (int s = 0; s < NST; ++s)
+#pragma unroll
+            for (int o = 0; o < 4; ++o)
+                sred[ht * (NST * 4) + s * 4 + o] = acc[s][o];
+    }
+    __syncthreads();
+    // fixed-order sum in two levels: the 16 blocks of each helper wave, then the four helper waves
+    float *swave = sred + 256 * NST * 4;     // [4][PT]
+    for (int idx = tid; idx < 4 * PT; idx += 512) {
+        const int e = idx % PT, wv = idx / PT;
+        int o, s, jj;
+        if (e < P) {
+            o = e / NCOL;
+            const int col = e % NCOL;
+            s = col >> 2;
+            jj = col & 3;
+        } else {
+            o = (e - P) / NC2;
+            const int col = (e - P) % NC2;
+            s = NS + (col >> 2);
+            jj = col & 3;
+        }
+        float sum = 0.0f;
+#pragma unroll
+        for (int bb = 0; bb < 16; ++bb)
+            sum += sred[(wv * 64 + bb * 4 + jj) * (NST * 4) + s * 4 + o];
+        swave[wv * PT + e] = sum;
+    }
+    __syncthreads();
+    // row layout: [P] dL/dw sums, [C*C] M2[o][i], [C] m1[o]
+    for (int e = tid; e < PT; e += 512) {
+        const float val = ((swave[e] + swave[PT + e]) + swave[2 * PT + e]) + swave[3 * PT + e];
+        int dst = e;
+        if (e >= P) {
+            const int o = (e - P) / NC2, col = (e - P) % NC2;
+            dst = col < C ? P + o * C + col : P + C * C + o;
+        }
+        part[(size_t)n * PT + dst] = val;
+    }
+}
+
+static size_t flow_bwd_wave8_lds_bytes(int C, int H, int W, int k)
+{
+    const size_t tiles = 2 * (size_t)C * H * W + (size_t)C * (H + k - 1) * (W + k - 1) + 4 + 2 * (size_t)C * 64 +
+                         2 * (size_t)k * 64 * 4;
+    const size_t nst = (size_t)(C * k * k + 3) / 4 + (size_t)(C + 1 + 3) / 4;
+    const size_t red = 256 * nst * 4 + 4 * ((size_t)C * C * k * k + (size_t)C * (C + 1));
+    return sizeof(float) * (tiles > red ? tiles : red);
+}
+
+// few channels, k = 3, few images of rows made of whole 16-pixel groups: the shapes of k_bwd_wave8
+bool flow_bwd_split_supported(int B, int C, int H, int W, int k)
+{
+    return C >= 1 && C <= 4 && k == 3 && wave_supported(C, H, k) && B <= 256 && (W & 15) == 0 && W <= 64 &&
+           !wave_tile_preferred(B, C, H, W) && flow_bwd_wave8_lds_bytes(C, H, W, k) <= kMaxLdsBytes;
+}
+
+template <int C>
+static int launch_flow_bwd_split_c(const float *z, const float *w, const float *gz, FlowParams fp, float *v,
+                                   float *part, int B, int H, int W, hipStream_t stream)
+{
+    const size_t lds = flow_bwd_wave8_lds_bytes(C, H, W, 3);
+    if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_flow_bwd_wave8<C, 3>), lds))
+        return INVCONV_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((k_flow_bwd_wave8<C, 3>), dim3(B), dim3(512), lds, stream, z, w, gz, fp, v, part, H, W);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+// dL/dy and one row [C*C*k*k | C*C | C] per image (un-negated dL/dw sums, M2, m1) in one launch
+int launch_flow_bwd_split(const float *z, const float *w, const float *gz, const float *s, const float *b,
+                          const float *Q, float *v, float *part, int B, int C, int H, int W, int k, hipStream_t stream)
+{
+    if (!flow_bwd_split_supported(B, C, H, W, k))
+        return INVCONV_ERR_VARIANT;
+    const FlowParams fp{s, b, Q};
+    switch (C) {
+    case 1: return launch_flow_bwd_split_c<1>(z, w, gz, fp, v, part, B, H, W, stream);
+    case 2: return launch_flow_bwd_split_c<2>(z, w, gz, fp, v, part, B, H, W, stream);
+    case 3: return launch_flow_bwd_split_c<3>(z, w, gz, fp, v, part, B, H, W, stream);
+    default: return launch_flow_bwd_split_c<4>(z, w, gz, fp, v, part, B, H, W, stream);
+    }
 }
 
 size_t bwd_wave_lds_bytes(int C, int H, int W, int k)

@@ -14,6 +14,10 @@ FLOW_SHAPES = [  # (B, C, H, W, k)
     # fused: few channels, image in LDS, rows of whole 16-byte pieces
     (4, 3, 8, 8, 3), (16, 3, 32, 32, 3), (32, 3, 64, 64, 5), (3, 1, 28, 28, 3), (5, 2, 33, 20, 3), (2, 4, 64, 64, 3),
     (300, 3, 16, 16, 3), (2, 3, 1, 4, 3), (2, 3, 7, 12, 5),
+    # few images of few channels: the split solve applies the map (forward); eight waves per image (backward, rows of
+    # whole 16-pixel groups)
+    (5, 1, 16, 48, 3), (7, 2, 24, 16, 3), (3, 4, 32, 32, 3), (9, 3, 20, 64, 3), (2, 3, 64, 32, 3), (200, 3, 16, 16, 3),
+    (2, 3, 40, 36, 5),
     # separate passes: rows not a multiple of 4, tall or many-channel images, other kernel sizes
     (3, 3, 13, 7, 3), (2, 3, 130, 40, 3), (64, 12, 16, 16, 3), (2, 12, 128, 128, 3), (2, 8, 50, 17, 3),
     (1, 5, 9, 11, 4), (1, 20, 6, 7, 2), (2, 3, 32, 32, 7), (2, 16, 20, 24, 3), (1, 1, 1, 1, 1),
