@@ -542,6 +542,15 @@ int flow_sums(const float *dLdz, const float *x, float *rows, float *sums, int B
             return rc;
         return launch_rows_sum(planes, B, C, C, sums + (size_t)C * C, st);
     }
+    if (dw_mfma_supported(C, 1) && p1.rt && p1.cb && plan_dw_mfma(B, C, H, W, 1).rt) {
+        // more than 16 channels: the same correlation in blocks of channels, both passes, unmasked and un-negated
+        if (int rc = launch_dw_mfma(x, dLdz, sums, rows, p1, B, C, H, W, 1, st, 1.0f, false))
+            return rc;
+        float *planes = (float *)((char *)rows + up256(p1.bytes));
+        if (int rc = launch_flow_plane_sum(dLdz, planes, B * C, H * W, st))
+            return rc;
+        return launch_rows_sum(planes, B, C, C, sums + (size_t)C * C, st);
+    }
     if (int rc = launch_flow_stats(dLdz, x, rows, B, C, H * W, st))
         return rc;
     return launch_rows_sum(rows, (int)flow_stat_rows(B, H * W), E2, E2, sums, st);

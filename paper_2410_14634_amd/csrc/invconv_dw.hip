@@ -477,8 +477,10 @@ static int launch_dw_partial_batch(const DwBatch &batch, int layers, float *part
 }
 
 int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
-                   int W, int k, hipStream_t stream, float sign)
+                   int W, int k, hipStream_t stream, float sign, bool masked)
 {
+    if (!masked && !p.cb)
+        return INVCONV_ERR_VARIANT;     // (one block: pass 1 alone gives the unmasked rows)
     DwBatch batch{};
     if (p.cb) {
         // More than 16 channels: the result is cut into blocks of at most 16 output x 16 input channels.  All
@@ -492,7 +494,7 @@ int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const
                 return INVCONV_OK;
             if (int s = launch_dw_partial_batch(batch, blocks.n, part, p, B, p.cbx, H, W, k, stream, p.cb, C, pstride))
                 return s;
-            if (int s = launch_dw_reduce_blocks(part, (int)p.nparts, dw, blocks, C, k, pstride, stream, sign))
+            if (int s = launch_dw_reduce_blocks(part, (int)p.nparts, dw, blocks, C, k, pstride, stream, sign, masked))
                 return s;
             blocks.n = 0;       // (launches of one stream run in order: the next group may reuse the partial rows)
             return INVCONV_OK;

@@ -19,7 +19,7 @@ namespace invconv {
 // ---------------------------------------------------------------------------
 // Small matrices of a step, prepared once per call by one workgroup (double arithmetic):
 //   A[o][i] = Q[o][i] s[i],  d[o] = sum_i Q[o][i] b[i],  Ainv = A^-1 = diag(1/s) Q^-1 (Gauss-Jordan with
-//   partial pivoting),  e = -Ainv d = -b/s,  QinvT = Q^-T (for the log-determinant's gradient), and
+//   partial pivoting, by one wave),  e = -Ainv d = -b/s,  QinvT = Q^-T (for the log-determinant's gradient), and
 //   logdet = -H W sum log|w[c][c][k-1][k-1]| + H W sum log|s[c]| + H W log|det Q|   (one image).
 // Layout (floats): A, d, Ainv, e, QinvT, logdet.  A singular Q gives inf / NaN, as a zero diagonal does.
 // ---------------------------------------------------------------------------
@@ -30,62 +30,220 @@ __host__ __device__ constexpr int flow_off_QinvT(int C) { return 2 * C * C + 2 *
 __host__ __device__ constexpr int flow_off_logdet(int C) { return 3 * C * C + 2 * C; }
 size_t flow_mats_floats(int C) { return (size_t)3 * C * C + 2 * C + 1; }
 
-__global__ __launch_bounds__(256) void k_flow_prep(const float *__restrict__ w, const float *__restrict__ s,
+// Q^-1 and log|det Q| by ONE wave: in-place Gauss-Jordan with partial pivoting, no barrier anywhere.  Rows never
+// move: the pivot of column `col` is the largest entry of that column among the rows that have not been a pivot
+// row yet, and own[col] remembers which row that was.  That is plain in-place elimination on the row-permuted
+// matrix, so at the end row own[i] holds row i of the inverse with its columns in the same permutation:
+//   Qinv[i][own[j]] = a[own[i]][j].
+// Both forms write qinv[C][C] (LDS, doubles) and return sum log|pivot| in every lane.
+__device__ __forceinline__ double readlane_f64(double v, int lane /* uniform */)
+{
+    const unsigned long long bits = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)bits, lane);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(bits >> 32), lane);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+
+// Pivot search: the candidates |entry| (or -1 for rows that may not be chosen) carry their row in the lowest seven
+// bits of the mantissa, so one max over doubles finds value and row together (positive doubles order like their bit
+// patterns; the seven bits only blur which of two nearly equal candidates wins).  Max over a row of 16 lanes by four
+// DPP shifts, over the wave by two row broadcasts; ROWS16: all candidates sit in lanes 0 .. 15.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_mov_f64(double v)
+{
+    const unsigned long long bits = __builtin_bit_cast(unsigned long long, v);
+    const int lo = (int)(unsigned)bits, hi = (int)(unsigned)(bits >> 32);
+    const unsigned rlo = (unsigned)__builtin_amdgcn_update_dpp(lo, lo, CTRL, ROW_MASK, 0xf, false);
+    const unsigned rhi = (unsigned)__builtin_amdgcn_update_dpp(hi, hi, CTRL, ROW_MASK, 0xf, false);
+    return __builtin_bit_cast(double, ((unsigned long long)rhi << 32) | rlo);
+}
+
+template <bool ROWS16>
+__device__ __forceinline__ int wave_pivot_row(double cand, int row)
+{
+    double key = cand;
+    if (cand >= 0.0) {
+        const unsigned long long bits = __builtin_bit_cast(unsigned long long, cand);
+        key = __builtin_bit_cast(double, (bits & ~0x7full) | (unsigned long long)(127 - (row & 127)));
+    }
+    key = fmax(key, dpp_mov_f64<0x111, 0xf>(key));      // row_shr:1 (lanes without a source keep their own value)
+    key = fmax(key, dpp_mov_f64<0x112, 0xf>(key));      // row_shr:2
+    key = fmax(key, dpp_mov_f64<0x114, 0xf>(key));      // row_shr:4
+    key = fmax(key, dpp_mov_f64<0x118, 0xf>(key));      // row_shr:8: lane 15 of a row holds the row's maximum
+    if (!ROWS16) {
+        key = fmax(key, dpp_mov_f64<0x142, 0xa>(key));  // row_bcast:15 into rows 1 and 3
+        key = fmax(key, dpp_mov_f64<0x143, 0xc>(key));  // row_bcast:31 into rows 2 and 3: lane 63 holds the maximum
+    }
+    const double top = readlane_f64(key, ROWS16 ? 15 : 63);
+    return 127 - (int)(__builtin_bit_cast(unsigned long long, top) & 0x7full);
+}
+
+// C <= 16: lane r holds row r in registers; every index below is a compile-time constant.
+__device__ __forceinline__ double flow_invert_regs(const float *__restrict__ Q, int C, double *qinv)
+{
+    constexpr int N = 16;
+    const int lane = threadIdx.x & 63;
+    const bool mine = lane < C;
+    double row[N], pivs[N];
+#pragma unroll
+    for (int c = 0; c < N; ++c)
+        row[c] = (mine && c < C) ? (double)Q[lane * C + c] : 0.0;
+    int own[N];
+    bool used = !mine;
+    int mycol = 0;
+#pragma unroll
+    for (int col = 0; col < N; ++col) {
+        pivs[col] = 1.0;
+        own[col] = 0;
+        if (col < C) {
+            const int p = wave_pivot_row<true>(used ? -1.0 : fabs(row[col]), lane);
+            own[col] = p;
+            double prow[N];
+#pragma unroll
+            for (int c = 0; c < N; ++c)
+                prow[c] = readlane_f64(row[c], p);
+            const double piv = prow[col], inv = 1.0 / piv;
+            pivs[col] = piv;
+#pragma unroll
+            for (int c = 0; c < N; ++c)
+                prow[c] = c == col ? inv : prow[c] * inv;
+            const double f = row[col];
+            if (lane == p) {
+                used = true;
+                mycol = col;
+            }
+#pragma unroll
+            for (int c = 0; c < N; ++c) {
+                const double upd = c == col ? -f * inv : row[c] - f * prow[c];
+                row[c] = lane == p ? prow[c] : upd;
+            }
+        }
+    }
+    if (mine) {
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            if (j < C)
+                qinv[mycol * C + own[j]] = row[j];
+    }
+    // the logarithms of the pivots, one per lane, at the end (a double logarithm is a long routine)
+    double pv = 1.0;
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+        pv = lane == j ? pivs[j] : pv;
+    double la = log(fabs(pv));
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1)
+        la += __shfl_xor(la, m, 64);
+    return la;
+}
+
+// Up to 128 channels, all waves of the workgroup: the matrix lives in `a` (row stride C + 1 doubles).  The first
+// wave finds the pivot row of a column (lane l looks at rows l and l + 64), keeps a copy of the column (the
+// factors) and scales the pivot row; after a barrier every wave eliminates its share of the COLUMNS from all rows
+// (lane = row; a row's entries are consecutive addresses, four at a time); a second barrier ends the step.
+__device__ __forceinline__ double flow_invert_lds(const float *__restrict__ Q, int C, double *a, double *fcol,
+                                                  double *pivs, int *own, double *qinv)
+{
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nw = nt >> 6, LD = C + 1;
+    for (int e = tid; e < C * C; e += nt)
+        a[(e / C) * LD + e % C] = (double)Q[e];
+    __syncthreads();
+    const int cw = ((C + nw - 1) / nw + 3) & ~3;        // columns per wave, whole groups of four
+    const int c_lo = wave * cw, c_hi = c_lo + cw < C ? c_lo + cw : C;
+    unsigned used = 0;          // (first wave) bit t: row lane + 64 t has been a pivot row
+    for (int col = 0; col < C; ++col) {
+        if (wave == 0) {
+            double best = -1.0;
+            int br = lane;
+            for (int r = lane, t = 0; r < C; r += 64, ++t) {
+                const double v = a[r * LD + col];
+                fcol[r] = v;
+                const double cand = (used >> t) & 1 ? -1.0 : fabs(v);
+                if (cand > best) {
+                    best = cand;
+                    br = r;
+                }
+            }
+            const int p = wave_pivot_row<false>(best, br);
+            if ((p & 63) == lane)
+                used |= 1u << (p >> 6);
+            const double piv = a[p * LD + col], inv = 1.0 / piv;
+            if (lane == 0) {
+                own[col] = p;
+                pivs[col] = piv;
+            }
+            for (int c = lane; c < C; c += 64)
+                a[p * LD + c] = c == col ? inv : a[p * LD + c] * inv;
+        }
+        __syncthreads();
+        const int p = own[col];
+        const double inv = a[p * LD + col];
+        const double *ap = a + p * LD;
+        for (int r = lane; r < C; r += 64) {
+            if (r == p)
+                continue;
+            double *ar = a + r * LD;
+            const double f = fcol[r];
+            for (int c0 = c_lo; c0 < c_hi; c0 += 4) {       // (the pad entry ar[C] is scratch for the columns past the end)
+                double pv[4], rv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + u < c_hi ? c0 + u : C;
+                    pv[u] = ap[c];
+                    rv[u] = ar[c];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + u < c_hi ? c0 + u : C;
+                    ar[c] = c == col ? -f * inv : rv[u] - f * pv[u];
+                }
+            }
+        }
+        __syncthreads();
+    }
+    for (int e = tid; e < C * C; e += nt) {
+        const int i = e / C, j = e % C;
+        qinv[i * C + own[j]] = a[own[i] * LD + j];
+    }
+    double la = 0.0;            // the pivots' logarithms at the end, one column per lane and trip (first wave)
+    if (wave == 0) {
+        for (int c = lane; c < C; c += 64)
+            la += log(fabs(pivs[c]));
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1)
+            la += __shfl_xor(la, m, 64);
+    }
+    return la;
+}
+
+// (WIDE: more than 16 channels, sixteen waves share the elimination)
+template <bool WIDE>
+__global__ __launch_bounds__(WIDE ? 1024 : 256) void k_flow_prep(const float *__restrict__ w, const float *__restrict__ s,
                                                   const float *__restrict__ b, const float *__restrict__ Q,
                                                   float *__restrict__ mats, float *__restrict__ logdet_out, int C,
                                                   int H, int W, int k)
 {
     extern __shared__ double sm[];
-    double *aug = sm;                       // [C][2C]: Q | I, becomes I | Q^-1
-    double *piv_row = sm + 2 * C * C;       // [2C] the scaled pivot row
-    double *fac = piv_row + 2 * C;          // [C]  column `col` before the update
+    double *qinv = sm;                      // [C][C]
+    double *work = sm + C * C;              // [C][C + 1] (more than 16 channels)
+    double *fcol = work + C * (C + 1);      // [C]
+    double *pivs = fcol + C;                // [C]
+    int *own = reinterpret_cast<int *>(pivs + C);       // [C]
     __shared__ double s_logabs;
-    __shared__ int s_piv;
-    const int tid = threadIdx.x, nt = blockDim.x, C2 = 2 * C;
-    for (int e = tid; e < C * C; e += nt) {
-        const int o = e / C, i = e % C;
-        aug[o * C2 + i] = (double)Q[e];
-        aug[o * C2 + C + i] = o == i ? 1.0 : 0.0;
-    }
+    const int tid = threadIdx.x, nt = blockDim.x;
+    double la = 0.0;
+    if constexpr (WIDE)
+        la = flow_invert_lds(Q, C, work, fcol, pivs, own, qinv);
+    else if (tid < 64)
+        la = flow_invert_regs(Q, C, qinv);
     if (tid == 0)
-        s_logabs = 0.0;
+        s_logabs = la;
     __syncthreads();
-    for (int col = 0; col < C; ++col) {
-        if (tid == 0) {
-            int p = col;
-            for (int r = col + 1; r < C; ++r)
-                if (fabs(aug[r * C2 + col]) > fabs(aug[p * C2 + col]))
-                    p = r;
-            s_piv = p;
-            s_logabs += log(fabs(aug[p * C2 + col]));
-        }
-        __syncthreads();
-        const int p = s_piv;
-        if (p != col)
-            for (int c = tid; c < C2; c += nt) {
-                const double t = aug[col * C2 + c];
-                aug[col * C2 + c] = aug[p * C2 + c];
-                aug[p * C2 + c] = t;
-            }
-        __syncthreads();
-        const double inv = 1.0 / aug[col * C2 + col];
-        for (int c = tid; c < C2; c += nt)
-            piv_row[c] = aug[col * C2 + c] * inv;
-        for (int r = tid; r < C; r += nt)
-            fac[r] = aug[r * C2 + col];
-        __syncthreads();
-        for (int e = tid; e < C * C2; e += nt) {
-            const int r = e / C2, c = e % C2;
-            aug[e] = r == col ? piv_row[c] : aug[e] - fac[r] * piv_row[c];
-        }
-        __syncthreads();
-    }
-    // aug[i][C + o] = Qinv[i][o]
     for (int e = tid; e < C * C; e += nt) {
         const int o = e / C, i = e % C;
         mats[e] = Q[e] * s[i];                                                          // A[o][i]
-        mats[flow_off_Ainv(C) + e] = (float)(aug[o * C2 + C + i] / (double)s[o]);       // Ainv[o][i] (row o of Q^-1 over s[o])
-        mats[flow_off_QinvT(C) + e] = (float)aug[i * C2 + C + o];                       // QinvT[o][i] = Qinv[i][o]
+        mats[flow_off_Ainv(C) + e] = (float)(qinv[o * C + i] / (double)s[o]);           // Ainv[o][i] (row o of Q^-1 over s[o])
+        mats[flow_off_QinvT(C) + e] = (float)qinv[i * C + o];                           // QinvT[o][i] = Qinv[i][o]
     }
     for (int o = tid; o < C; o += nt) {
         double acc = 0.0;
@@ -94,21 +252,26 @@ __global__ __launch_bounds__(256) void k_flow_prep(const float *__restrict__ w, 
         mats[flow_off_d(C) + o] = (float)acc;
         mats[flow_off_e(C) + o] = -b[o] / s[o];
     }
-    if (tid == 0) {
-        double acc = s_logabs;
-        for (int c = 0; c < C; ++c)
+    if (tid < 64) {     // one channel per lane and trip: the logarithms are the long part
+        double acc = 0.0;
+        for (int c = tid; c < C; c += 64)
             acc += log(fabs((double)s[c])) - log(fabs((double)w[((c * C + c) * k + (k - 1)) * k + (k - 1)]));
-        const float ld = (float)((double)H * (double)W * acc);
-        mats[flow_off_logdet(C)] = ld;
-        if (logdet_out)
-            logdet_out[0] = ld;
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1)
+            acc += __shfl_xor(acc, m, 64);
+        if (tid == 0) {
+            const float ld = (float)((double)H * (double)W * (acc + s_logabs));
+            mats[flow_off_logdet(C)] = ld;
+            if (logdet_out)
+                logdet_out[0] = ld;
+        }
     }
 }
 
 // ---------------------------------------------------------------------------
 // Separate pass: out[n][o][p] = add[o] + sum_i M[o][i] in[n][i][p]  (TR: M[i][o] instead), one thread per
 // four consecutive pixels when the planes allow 16-byte accesses, else per pixel.  `out` may be `in`: a
-// thread reads all its inputs before it writes.  CT = C when C <= 16 (inputs stay in registers), else 0.
+// thread reads all its inputs before it writes.  CT = C (1-4, 8, 12, 16: the inputs stay in registers).
 // ---------------------------------------------------------------------------
 template <int CT, int VEC, bool TR>
 __global__ __launch_bounds__(256) void k_flow_affine(const float *in, const float *__restrict__ M,
@@ -124,7 +287,8 @@ __global__ __launch_bounds__(256) void k_flow_affine(const float *in, const floa
     const int q = (int)(t % per);
     const vec_t *src = reinterpret_cast<const vec_t *>(in + (size_t)n * C * HW) + q;
     vec_t *dst = reinterpret_cast<vec_t *>(out + (size_t)n * C * HW) + q;
-    if constexpr (CT > 0) {
+    static_assert(CT > 0, "channel counts without a register-resident form take k_flow_affine_blocked");
+    {
         vec_t xin[CT];
 #pragma unroll
         for (int i = 0; i < CT; ++i)
@@ -141,19 +305,57 @@ __global__ __launch_bounds__(256) void k_flow_affine(const float *in, const floa
                 acc += (TR ? M[i * CT + o] : M[o * CT + i]) * xin[i];
             dst[(size_t)o * per] = acc;
         }
-    } else {
-        // many channels: out must not alias in here (the launcher sees to it)
-        for (int o = 0; o < C; ++o) {
-            const float a0 = add ? add[o] : 0.0f;
-            vec_t acc;
+    }
+}
+
+// Other channel counts (5-7, 9-11, 13-15 and everything above 16): a thread forms OT = 8 output channels of its
+// pixels (blockIdx.y selects which eight), reading every input channel once; the matrix entries are the same
+// address for all lanes.  A read is repeated by the C / 8 threads of a pixel (cache hits); `out` must not alias
+// `in`.
+template <int VEC, bool TR>
+__global__ __launch_bounds__(256) void k_flow_affine_blocked(const float *__restrict__ in, const float *__restrict__ M,
+                                                            const float *__restrict__ add, float *__restrict__ out,
+                                                            int C, int HW, long long total /* B * HW / VEC */)
+{
+    constexpr int OT = 8;
+    typedef float vec_t __attribute__((ext_vector_type(VEC)));
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total)
+        return;
+    const int per = HW / VEC;
+    const long long n = t / per;
+    const int q = (int)(t % per);
+    const int o0 = blockIdx.y * OT;
+    const vec_t *src = reinterpret_cast<const vec_t *>(in + (size_t)n * C * HW) + q;
+    vec_t *dst = reinterpret_cast<vec_t *>(out + (size_t)n * C * HW) + q;
+    vec_t acc[OT];
+    int orow[OT];       // clamped output channel: rows past the end repeat the last one and are not stored
 #pragma unroll
-            for (int u = 0; u < VEC; ++u)
-                acc[u] = a0;
-            for (int i = 0; i < C; ++i)
-                acc += (TR ? M[i * C + o] : M[o * C + i]) * src[(size_t)i * per];
-            dst[(size_t)o * per] = acc;
+    for (int u = 0; u < OT; ++u) {
+        orow[u] = o0 + u < C ? o0 + u : C - 1;
+        const float a0 = add ? add[orow[u]] : 0.0f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            acc[u][e] = a0;
+    }
+    for (int i0 = 0; i0 < C; i0 += 4) {       // four input channels in flight
+        vec_t xin[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            xin[j] = src[(size_t)(i0 + j < C ? i0 + j : C - 1) * per];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (i0 + j < C) {
+#pragma unroll
+                for (int u = 0; u < OT; ++u)
+                    acc[u] += (TR ? M[(i0 + j) * C + orow[u]] : M[orow[u] * C + i0 + j]) * xin[j];
+            }
         }
     }
+#pragma unroll
+    for (int u = 0; u < OT; ++u)
+        if (o0 + u < C)
+            dst[(size_t)(o0 + u) * per] = acc[u];
 }
 
 template <int CT, bool TR>
@@ -163,10 +365,17 @@ static void launch_affine_ct(const float *in, const float *M, const float *add, 
     const bool vec = (HW % 4) == 0 && ((((size_t)in) | ((size_t)out)) & 15) == 0;
     const long long total = (long long)B * HW / (vec ? 4 : 1);
     const unsigned grid = (unsigned)((total + 255) / 256);
-    if (vec)
+    if constexpr (CT == 0) {
+        const dim3 g2(grid, (unsigned)((C + 7) / 8));
+        if (vec)
+            hipLaunchKernelGGL((k_flow_affine_blocked<4, TR>), g2, dim3(256), 0, stream, in, M, add, out, C, HW, total);
+        else
+            hipLaunchKernelGGL((k_flow_affine_blocked<1, TR>), g2, dim3(256), 0, stream, in, M, add, out, C, HW, total);
+    } else if (vec) {
         hipLaunchKernelGGL((k_flow_affine<CT, 4, TR>), dim3(grid), dim3(256), 0, stream, in, M, add, out, C, HW, total);
-    else
+    } else {
         hipLaunchKernelGGL((k_flow_affine<CT, 1, TR>), dim3(grid), dim3(256), 0, stream, in, M, add, out, C, HW, total);
+    }
 }
 
 template <bool TR>
@@ -315,14 +524,21 @@ __device__ __forceinline__ void flow_finish_body(const float *sums, int have_dw,
     const int P = C * C * k * k;
     const float hw = (float)H * (float)W;
     const float *M2 = sums + (have_dw ? P : 0), *m1 = M2 + C * C;
-    for (int e = tid; e < P; e += nt) {
-        const int bb = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
-        const bool centre = a == k - 1 && bb == k - 1;
-        float v = have_dw ? ((centre && i > o) ? 0.0f : -sums[e]) : dLdw[e];
-        if (centre && i == o && lw != 0.0f)
-            v -= lw * hw / w[e];
-        if (have_dw || (centre && i == o && lw != 0.0f))
+    if (have_dw) {
+        for (int e = tid; e < P; e += nt) {
+            const int bb = e % k, a = (e / k) % k, i = (e / (k * k)) % C, o = e / (k * k * C);
+            const bool centre = a == k - 1 && bb == k - 1;
+            float v = (centre && i > o) ? 0.0f : -sums[e];
+            if (centre && i == o && lw != 0.0f)
+                v -= lw * hw / w[e];
             dLdw[e] = v;
+        }
+    } else if (lw != 0.0f) {
+        // dL/dw is already there: only the C diagonal entries of the current-pixel block take the log-determinant's term
+        for (int c = tid; c < C; c += nt) {
+            const int e = ((c * C + c) * k + (k - 1)) * k + (k - 1);
+            dLdw[e] -= lw * hw / w[e];
+        }
     }
     for (int e = tid; e < C * C; e += nt) {
         const int o = e / C, i = e % C;
@@ -665,10 +881,16 @@ size_t flow_stat_rows(int B, int HW) { return (size_t)B * ((HW + kFlowStatPix - 
 int launch_flow_prep(const float *w, const float *s, const float *b, const float *Q, float *mats, float *logdet, int C,
                      int H, int W, int k, hipStream_t stream)
 {
-    const size_t lds = sizeof(double) * ((size_t)2 * C * C + 3 * C);
-    if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_flow_prep), lds) || lds > kMaxLdsBytes)
-        return INVCONV_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(k_flow_prep, dim3(1), dim3(256), lds, stream, w, s, b, Q, mats, logdet, C, H, W, k);
+    const size_t lds = sizeof(double) * ((size_t)2 * C * C + 3 * C) + sizeof(int) * (size_t)C;
+    if (C > 16) {
+        if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_flow_prep<true>), lds) || lds > kMaxLdsBytes)
+            return INVCONV_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(k_flow_prep<true>, dim3(1), dim3(1024), lds, stream, w, s, b, Q, mats, logdet, C, H, W, k);
+    } else {
+        if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_flow_prep<false>), lds) || lds > kMaxLdsBytes)
+            return INVCONV_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(k_flow_prep<false>, dim3(1), dim3(256), lds, stream, w, s, b, Q, mats, logdet, C, H, W, k);
+    }
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

@@ -514,7 +514,7 @@ __global__ __launch_bounds__(64 * NW) void k_dw_reduce(const float *__restrict__
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void k_dw_reduce_blocks(const float *__restrict__ part_all, int nparts,
                                                              float *__restrict__ dw, DwBlocks blocks, int Ctot, int k,
-                                                             int pstride, float sign)
+                                                             int pstride, float sign, int masked)
 {
     __shared__ double swave[NW][64];
     const int y = blockIdx.y;
@@ -547,7 +547,7 @@ __global__ __launch_bounds__(64 * NW) void k_dw_reduce_blocks(const float *__res
         for (int v = 1; v < NW; ++v)
             total += swave[v][lane];
         const int b = e % k, a = (e / k) % k, i = i0 + (e / (k * k)) % C, o = o0 + e / (k * k * C);
-        const bool is_masked = (a == k - 1 && b == k - 1 && i > o);
+        const bool is_masked = masked && (a == k - 1 && b == k - 1 && i > o);
         dw[((o * Ctot + i) * k + a) * k + b] = is_masked ? 0.0f : (float)(sign < 0.0f ? -total : total);
     }
 }
@@ -779,17 +779,17 @@ int launch_dw_reduce_layers(const float *part, int nparts, float *const *dw, int
 }
 
 int launch_dw_reduce_blocks(const float *part, int nparts, float *dw, const DwBlocks &blocks, int Ctot, int k,
-                            int pstride, hipStream_t stream, float sign)
+                            int pstride, hipStream_t stream, float sign, bool masked)
 {
     if (blocks.n < 1 || blocks.n > kChainMaxLayers)
         return INVCONV_ERR_SHAPE;
     const dim3 grid((pstride + 63) / 64, blocks.n);
     if (nparts >= 512)
         hipLaunchKernelGGL(k_dw_reduce_blocks<16>, grid, dim3(1024), 0, stream, part, nparts, dw, blocks, Ctot, k, pstride,
-                           sign);
+                           sign, masked ? 1 : 0);
     else
         hipLaunchKernelGGL(k_dw_reduce_blocks<4>, grid, dim3(256), 0, stream, part, nparts, dw, blocks, Ctot, k, pstride,
-                           sign);
+                           sign, masked ? 1 : 0);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

@@ -100,7 +100,7 @@ bool dw_mfma_supported(int C, int k);
 DwPlan plan_dw_mfma(int B, int C, int H, int W, int k);
 DwPlan plan_dw_mfma_layers(int layers, int B, int C, int H, int W, int k);
 int launch_dw_mfma(const float *x, const float *v, float *dw, float *part, const DwPlan &p, int B, int C, int H,
-                   int W, int k, hipStream_t stream, float sign = -1.0f);
+                   int W, int k, hipStream_t stream, float sign = -1.0f, bool masked = true);
 int launch_dw_mfma_partial(const float *x, const float *v, float *part, const DwPlan &p, int B, int C, int H, int W,
                            int k, hipStream_t stream);
 int launch_dw_mfma_layers(const float *const *x, const float *const *v, float *const *dw, int layers, float *part,
@@ -117,8 +117,9 @@ struct DwBlocks {
     int n;
     unsigned char cv[kChainMaxLayers], cx[kChainMaxLayers], o0[kChainMaxLayers], i0[kChainMaxLayers];
 };
+// (masked = false: every entry is kept, for plain correlations such as the flow step's sums over pixels)
 int launch_dw_reduce_blocks(const float *part, int nparts, float *dw, const DwBlocks &blocks, int Ctot, int k,
-                            int pstride, hipStream_t stream, float sign = -1.0f);
+                            int pstride, hipStream_t stream, float sign = -1.0f, bool masked = true);
 int launch_logdet_layers(const float *const *w, int layers, int C, int H, int W, int k, float *out,
                          hipStream_t stream);
 struct ChainArgs {
