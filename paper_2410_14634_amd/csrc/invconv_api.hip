@@ -603,6 +603,9 @@ invconv_status invconv_flowstep_fwd_ex(const float *y, const float *w, const flo
     // few channels, few images: one launch, the split solve with the channel map on its way out
     if (form == INVCONV_FLOW_AUTO && flow_split_supported(B, C, H, W, k))
         return launch_flow_fwd_split(y, w, s, b, Q, z, B, C, H, W, k, st, logdet);
+    // 5-16 channels on images of one band: the same on the one-band kernel
+    if (form == INVCONV_FLOW_AUTO && flow_band_supported(C, H, k))
+        return launch_flow_fwd_band(y, w, s, b, Q, z, B, C, H, W, k, st, logdet);
     if (int rc = launch_flow_prep(w, s, b, Q, mats, logdet, C, H, W, k, st))
         return rc;
     if (form != INVCONV_FLOW_SEPARATE && flow_fused_supported(C, H, W, k) && aligned16(y, z) &&

@@ -23,6 +23,7 @@
 // next band through a small LDS ring.
 #include "invconv_common.h"
 #include "invconv_launch.h"
+#include "invconv_wave_inverse.h"
 #include <type_traits>
 
 namespace invconv {
@@ -294,13 +295,40 @@ __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ i
 // start of step s+1, after the barrier that ends step s.  Wave 0 forms T1p, T2p and ownp itself.
 // Wave 1 also writes x to global memory, wave 3 reads y.  One barrier per step.
 // ---------------------------------------------------------------------------
-template <int CG, int DIR, bool PAD = false>
+// MAP (forward direction): the kernel is the forward pass of a whole flow step (Section 4.1: then Actnorm a = s x + b
+// and the 1 x 1 convolution z = Q a).  The wave that stores applies z = A x + d (A = Q diag(s), d = Q b) to the
+// diagonal it is about to store with CG more matrix instructions - the shape of Linv y: own values in, own channels
+// out - so x never leaves the workgroup; one extra workgroup (the last) only forms the step's log-determinant,
+// with Q eliminated by one wave, while the others solve.
+struct BandFlowParams {
+    const float *s, *b, *Q;
+};
+
+template <int CG, int DIR, bool PAD = false, bool MAP = false>
 __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restrict__ in, const float *__restrict__ w,
-                                                          float *__restrict__ out, int H, int W, float *logdet, int Cr)
+                                                          float *__restrict__ out, int H, int W, float *logdet, int Cr,
+                                                          BandFlowParams fp = BandFlowParams{})
 {
+    static_assert(!MAP || DIR == 0, "the channel map goes with the forward solve");
     constexpr int K = 3, C = 4 * CG;
     const int Cs = PAD ? Cr : C;        // channels of the image (PAD: fewer than the lanes' 4 CG slots, as in k_solve_band)
     extern __shared__ float smem[];
+    if (MAP && blockIdx.x == gridDim.x - 1) {
+        // log|det dz/dy| of one image = H W (sum log|s| + log|det Q| - sum log|w[c][c][K-1][K-1]|)    (Section 4)
+        if (logdet && threadIdx.x < 64) {
+            double la = flow_invert_regs(fp.Q, Cs, reinterpret_cast<double *>(smem));
+            double acc = 0.0;
+            const int c = threadIdx.x;
+            if (c < Cs)
+                acc = log(fabs((double)fp.s[c])) - log(fabs((double)w[((c * Cs + c) * K + (K - 1)) * K + (K - 1)]));
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1)
+                acc += __shfl_xor(acc, m, 64);
+            if (c == 0)
+                logdet[0] = (float)((double)H * (double)W * (acc + la));
+        }
+        return;
+    }
     float *sL = smem;
     float *sLinv = sL + C * C;
     float *sCf = sLinv + C * C;
@@ -381,6 +409,20 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
         const float lv = sLinv[om * Cs + (ch_ok[jj] ? CG * g + jj : 0)];
         wLi[jj] = m_ok && ch_ok[jj] ? lv : 0.0f;
     }
+    // the map's operands, laid out like wLi (row om, input channel CG g + jj), and its offset per own channel
+    float wAz[MAP ? CG : 1], dz[MAP ? CG : 1];
+    if (MAP && wave == 1) {     // (the storing wave)
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj) {
+            const int ic = ch_ok[jj] ? CG * g + jj : 0;
+            const float av = fp.Q[om * Cs + ic] * fp.s[ic];
+            wAz[jj] = m_ok && ch_ok[jj] ? av : 0.0f;
+            double acc = 0.0;
+            for (int i = 0; i < Cs; ++i)
+                acc += (double)fp.Q[ic * Cs + i] * (double)fp.b[i];
+            dz[jj] = (float)acc;
+        }
+    }
     __syncthreads();
 
 #pragma unroll
@@ -447,7 +489,20 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
             }
             sM[((s & 1) * 3 + (a - 1)) * 64 + lane] = acc + acc2;
             const int c = s - 1 - n;        // column of x_{s-1} in this lane's row
-            if ((unsigned)c < Wst1) {
+            if constexpr (MAP) {
+                f32x4 zacc = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (a == 1) {
+#pragma unroll
+                    for (int jj = 0; jj < CG; ++jj)
+                        zacc = __builtin_amdgcn_mfma_f32_16x16x4f32(wAz[jj], x1[jj], zacc, 0, 0, 0);
+                }
+                if ((unsigned)c < Wst1) {
+                    const unsigned off = (unsigned)(row0 + kStep * c);
+#pragma unroll
+                    for (int j = 0; j < CG; ++j)
+                        st(j, off, zacc[j] + dz[j]);
+                }
+            } else if ((unsigned)c < Wst1) {
                 const unsigned off = (unsigned)(row0 + kStep * c);
 #pragma unroll
                 for (int j = 0; j < CG; ++j)
@@ -495,7 +550,7 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
             if (u < rest)
                 step(s0 + u, u, false);
     }
-    if (logdet && blockIdx.x == 0 && wave == 2)
+    if (!MAP && logdet && blockIdx.x == 0 && wave == 2)
         wave_logdet_any(w, Cs, K, H, W, logdet);
 }
 
@@ -553,6 +608,36 @@ static int launch_band_ck(int dir, const float *in, const float *w, float *out, 
         hipLaunchKernelGGL((k_solve_band<CG, K, 0, MAXT, PAD>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W,
                            NB, logdet, C);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+// Forward pass of a whole flow step on the one-band kernel: 5-16 channels, k = 3, images of at most 16 rows.
+bool flow_band_supported(int C, int H, int k) { return k == 3 && H <= 16 && band_supported(C, H, k); }
+
+template <int CG, bool PAD>
+static int launch_flow_band_cg(const float *y, const float *w, BandFlowParams fp, float *z, int B, int C, int H, int W,
+                               hipStream_t stream, float *logdet)
+{
+    constexpr int K = 3;
+    const size_t lds1 = sizeof(float) * (2 * (size_t)16 * CG * CG + 2 * (size_t)K * K * 16 * CG * CG +
+                                         2 * CG * 64 + 2 * 3 * 64 * 4);
+    hipLaunchKernelGGL((k_solve_band_split<CG, 0, PAD, true>), dim3(B + 1), dim3(256), lds1, stream, y, w, z, H, W,
+                       logdet, C, fp);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+int launch_flow_fwd_band(const float *y, const float *w, const float *s, const float *b, const float *Q, float *z,
+                         int B, int C, int H, int W, int k, hipStream_t stream, float *logdet)
+{
+    if (!flow_band_supported(C, H, k))
+        return INVCONV_ERR_VARIANT;
+    const BandFlowParams fp{s, b, Q};
+    auto by_cg = [&](auto pad_tag) -> int {
+        constexpr bool PAD = decltype(pad_tag)::value;
+        if (C <= 8) return launch_flow_band_cg<2, PAD>(y, w, fp, z, B, C, H, W, stream, logdet);
+        if (C <= 12) return launch_flow_band_cg<3, PAD>(y, w, fp, z, B, C, H, W, stream, logdet);
+        return launch_flow_band_cg<4, PAD>(y, w, fp, z, B, C, H, W, stream, logdet);
+    };
+    return C % 4 ? by_cg(std::true_type()) : by_cg(std::false_type());
 }
 
 int launch_solve_band(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,

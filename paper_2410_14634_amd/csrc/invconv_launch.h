@@ -60,6 +60,10 @@ int launch_solve_wave(int dir, const float *in, const float *w, float *out, int 
 bool band_supported(int C, int H, int k);
 int launch_solve_band(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                       hipStream_t stream, float *logdet = nullptr);
+// one flow step's forward pass (y in, z out, the step's log-determinant on the side) on the one-band kernel
+bool flow_band_supported(int C, int H, int k);
+int launch_flow_fwd_band(const float *y, const float *w, const float *s, const float *b, const float *Q, float *z,
+                         int B, int C, int H, int W, int k, hipStream_t stream, float *logdet);
 // many channels (17 .. 48), k = 3: 16x16x4 MFMA per tap, history in an LDS ring
 bool wide_supported(int C, int H, int k);
 int launch_solve_wide(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,

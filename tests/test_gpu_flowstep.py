@@ -21,6 +21,8 @@ FLOW_SHAPES = [  # (B, C, H, W, k)
     # separate passes: rows not a multiple of 4, tall or many-channel images, other kernel sizes
     (3, 3, 13, 7, 3), (2, 3, 130, 40, 3), (64, 12, 16, 16, 3), (2, 12, 128, 128, 3), (2, 8, 50, 17, 3),
     (1, 5, 9, 11, 4), (1, 20, 6, 7, 2), (2, 3, 32, 32, 7), (2, 16, 20, 24, 3), (1, 1, 1, 1, 1),
+    # 5-16 channels on images of one band: the one-band kernel applies the map (forward)
+    (64, 12, 16, 16, 3), (5, 8, 16, 20, 3), (3, 16, 7, 7, 3), (4, 6, 9, 33, 3), (2, 13, 16, 16, 3), (1, 12, 1, 1, 3),
     # more than 16 channels: set-up by sixteen waves, channel map in blocks of output channels, sums on the matrix cores
     (2, 48, 8, 8, 3), (3, 24, 16, 12, 3), (2, 33, 9, 5, 3), (1, 70, 4, 4, 3), (2, 17, 5, 8, 3),
     # 8-16 channels: the pipelined band kernel applies the map in its storers / folds it into its input weights
