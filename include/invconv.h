@@ -205,8 +205,9 @@ invconv_status invconv_logdet(const float *w, int C, int H, int W, int k,
  * C = 3 with k = 5) and batches of 4 MB or more the three layers run as ONE kernel that reads y and writes z,
  * i.e. the HBM traffic of the inverse convolution alone; for a few such images the kernel that solves one image
  * on several waves applies the two neighbours on its way out (one launch, no set-up launch; the backward pass
- * of k = 3 likewise, plus one small launch that finishes the parameter gradients); other shapes run the same
- * arithmetic as separate passes over scratch.
+ * of k = 3 likewise, plus one small launch that finishes the parameter gradients), and so does the forward pass
+ * of 5-16 channels on images of at most 16 rows; other shapes run the same arithmetic as separate passes over
+ * scratch.
  *   s, b [in] C floats each;  Q [in] C*C floats, row = output channel; must be invertible (a singular Q
  *   yields inf/NaN like a zero diagonal of w).
  *   z [out] B*C*H*W, must not alias an input.
