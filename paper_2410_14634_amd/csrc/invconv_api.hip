@@ -726,6 +726,18 @@ invconv_status invconv_flowstep_bwd_ex(const float *z, const float *w, const flo
     }
     // separate passes: x = A^-1 z + e and g = A^T dL/dz into scratch, the backward pass of the inverse
     // convolution on them, the two sums of the neighbours' gradients, and the common last kernel
+    if (flow_bwd_maps_supported(C) && (size_t)B * C * H * W <= ((size_t)1 << 20)) {
+        // up to 4 MB of activations (where launches, not bytes, are what a pass costs): one pass over z and dL/dz
+        // gives x, g and the partial sums of M2 and m1 together.  Beyond that the chunked kernel loses to the
+        // separate passes (4096 x 3x32x32: 270 against 243 us)
+        if (int rc = launch_flow_bwd_maps(z, dLdz, mats, x, g, rows, B, C, H * W, st))
+            return rc;
+        if (int rc = launch_rows_sum(rows, (int)flow_stat_rows(B, H * W), E2, E2, sums, st))
+            return rc;
+        if (int rc = invconv_bwd(x, w, g, dLdy, dLdw, B, C, H, W, k, workspace, lay.bwd_bytes, stream))
+            return rc;
+        return launch_flow_finish(sums, 0, w, s, b, Q, mats, dLdw, dLds, dLdb, dLdQ, logdet_weight, C, H, W, k, st);
+    }
     if (int rc = launch_flow_affine(false, z, mats + CC + C, mats + 2 * CC + C, x, B, C, H * W, st))
         return rc;
     if (int rc = launch_flow_affine(true, dLdz, mats, nullptr, g, B, C, H * W, st))

@@ -335,6 +335,83 @@ __global__ __launch_bounds__(256) void k_flow_stats(const float *__restrict__ gz
     }
 }
 
+// ---------------------------------------------------------------------------
+// Separate-pass backward, first launch: ONE pass over z and dL/dz of a chunk of 128 pixels of one image gives
+//   x = A^-1 z - b/s  and  g = A^T dL/dz  (written out: the inputs of the inverse convolution's backward pass)
+// and, from the tiles while they are in LDS, the chunk's partial sums of M2 and m1 (row layout [C*C | C] as above).
+// It replaces two passes of the channel map and a pass of sums that read x and dL/dz again.  Tile rows are
+// 129 floats apart: the threads of the sums walk rows that start in different banks.
+// ---------------------------------------------------------------------------
+constexpr int kFlowStatStride = kFlowStatPix + 1;
+
+__global__ __launch_bounds__(256) void k_flow_bwd_maps(const float *__restrict__ z, const float *__restrict__ gz,
+                                                      const float *__restrict__ mats, float *__restrict__ x,
+                                                      float *__restrict__ g, float *__restrict__ rows, int C, int HW,
+                                                      int chunks)
+{
+    extern __shared__ float fsm[];
+    constexpr int PS = kFlowStatStride;
+    float *sz = fsm;                        // [C][PS]
+    float *sg = sz + C * PS;                // [C][PS]
+    float *sx = sg + C * PS;                // [C][PS]
+    float *sA = sx + C * PS;                // [C][C]  A
+    float *sAi = sA + C * C;                // [C][C]  A^-1
+    float *se = sAi + C * C;                // [C]     -b/s
+    const int n = blockIdx.x / chunks, ch = blockIdx.x % chunks;
+    const int p0 = ch * kFlowStatPix;
+    const int np = HW - p0 < kFlowStatPix ? HW - p0 : kFlowStatPix;
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < C * kFlowStatPix; idx += 256) {
+        const int c = idx / kFlowStatPix, p = idx % kFlowStatPix;
+        const bool ok = p < np;
+        const size_t src = ((size_t)n * C + c) * HW + p0 + (ok ? p : 0);
+        const float zv = z[src], gv = gz[src];
+        sz[c * PS + p] = ok ? zv : 0.0f;
+        sg[c * PS + p] = ok ? gv : 0.0f;
+    }
+    for (int idx = tid; idx < C * C; idx += 256) {
+        sA[idx] = mats[idx];
+        sAi[idx] = mats[flow_off_Ainv(C) + idx];
+    }
+    for (int idx = tid; idx < C; idx += 256)
+        se[idx] = mats[flow_off_e(C) + idx];
+    __syncthreads();
+    {
+        // thread = (pixel p, half h): channels h, h + 2, ... of that pixel (the channel is the same for a whole wave)
+        const int p = tid & (kFlowStatPix - 1), h = tid >> 7;
+        const bool ok = p < np;
+        for (int i = h; i < C; i += 2) {
+            float xa = se[i], ga = 0.0f;
+            for (int o = 0; o < C; ++o) {
+                xa += sAi[i * C + o] * sz[o * PS + p];
+                ga += sA[o * C + i] * sg[o * PS + p];
+            }
+            sx[i * PS + p] = ok ? xa : 0.0f;        // pixels past the end add nothing to the sums
+            if (ok) {
+                const size_t dst = ((size_t)n * C + i) * HW + p0 + p;
+                x[dst] = xa;
+                g[dst] = ga;
+            }
+        }
+    }
+    __syncthreads();
+    const int E = C * C + C;
+    float *row = rows + (size_t)blockIdx.x * E;
+    for (int e = tid; e < E; e += 256) {
+        float acc = 0.0f;
+        if (e < C * C) {
+            const float *pg = sg + (e / C) * PS, *px = sx + (e % C) * PS;
+            for (int p = 0; p < kFlowStatPix; ++p)
+                acc += pg[p] * px[p];
+        } else {
+            const float *pg = sg + (e - C * C) * PS;
+            for (int p = 0; p < kFlowStatPix; ++p)
+                acc += pg[p];
+        }
+        row[e] = acc;
+    }
+}
+
 // m1 partial sums: one workgroup per (image, channel) plane adds its H*W values of dL/dz in a fixed order
 // (thread t takes elements t, t + 256, ...; then a fixed tree over the 256 threads).  out[n*C + c].
 __global__ __launch_bounds__(256) void k_flow_plane_sum(const float *__restrict__ gz, float *__restrict__ out, int HW)
@@ -802,6 +879,26 @@ int launch_flow_stats(const float *gz, const float *x, float *rows, int B, int C
     if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_flow_stats), lds) || lds > kMaxLdsBytes)
         return INVCONV_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(k_flow_stats, dim3((unsigned)(B * chunks)), dim3(256), lds, stream, gz, x, rows, C, HW, chunks);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+static size_t flow_bwd_maps_lds(int C)
+{
+    return sizeof(float) * (3 * (size_t)C * kFlowStatStride + 2 * (size_t)C * C + C);
+}
+
+bool flow_bwd_maps_supported(int C) { return flow_bwd_maps_lds(C) <= kMaxLdsBytes; }
+
+// x, g and flow_stat_rows(B, HW) rows of [C*C | C] partial sums
+int launch_flow_bwd_maps(const float *z, const float *gz, const float *mats, float *x, float *g, float *rows, int B,
+                         int C, int HW, hipStream_t stream)
+{
+    const int chunks = (HW + kFlowStatPix - 1) / kFlowStatPix;
+    const size_t lds = flow_bwd_maps_lds(C);
+    if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_flow_bwd_maps), lds) || lds > kMaxLdsBytes)
+        return INVCONV_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_flow_bwd_maps, dim3((unsigned)(B * chunks)), dim3(256), lds, stream, z, gz, mats, x, g, rows,
+                       C, HW, chunks);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 

@@ -169,6 +169,9 @@ int launch_flow_affine(bool transposed, const float *in, const float *M, const f
                        int HW, hipStream_t stream);
 int launch_flow_stats(const float *gz, const float *x, float *rows, int B, int C, int HW, hipStream_t stream);
 int launch_rows_sum(const float *rows, int nrows, int stride, int E, float *out, hipStream_t stream);
+bool flow_bwd_maps_supported(int C);
+int launch_flow_bwd_maps(const float *z, const float *gz, const float *mats, float *x, float *g, float *rows, int B,
+                         int C, int HW, hipStream_t stream);
 int launch_flow_plane_sum(const float *gz, float *out, int planes, int HW, hipStream_t stream);
 int launch_flow_finish(const float *sums, int have_dw, const float *w, const float *s, const float *b, const float *Q,
                        const float *mats, float *dLdw, float *dLds, float *dLdb, float *dLdQ, float lw, int C, int H,
