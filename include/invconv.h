@@ -77,7 +77,7 @@ enum {
     INVCONV_VARIANT_BLOCK = 1,    /* one workgroup per image, LDS window, one barrier per anti-diagonal */
     INVCONV_VARIANT_DIAG_LAUNCH = 2, /* one kernel launch per anti-diagonal (capture it in a hipGraph) */
     INVCONV_VARIANT_WAVE = 3,     /* one wave per 64 image rows, lane = row, register/DPP systolic solve (C <= 4 with k = 3, C = 3 also k = 2, 5, 7, 9, 11; H <= 512, k <= 5 beyond 64 rows; bands of one image hand over through LDS) */
-    INVCONV_VARIANT_BAND = 4,     /* one wave per 16-row band, 16x16x4 MFMA systolic solve (C = 5 .. 16; k = 3 with H <= 128; k = 2, 5 and, up to 12 channels, 7 with H <= 64) */
+    INVCONV_VARIANT_BAND = 4,     /* one wave per 16-row band, 16x16x4 MFMA systolic solve (C = 5 .. 16; k = 3 with H <= 128; k = 2, 5, 7 with H <= 64; k = 9, 11 at 8, 12, 16 channels with H <= 64) */
     INVCONV_VARIANT_PERSISTENT = 5, /* one cooperative launch, persistent grid, device-wide barrier per anti-diagonal */
     INVCONV_VARIANT_WAVE_SPLIT = 6 /* the wave solve with a step's matrix instructions split over four waves by the age of their input (same shapes, k >= 3, H <= 64) */
 };

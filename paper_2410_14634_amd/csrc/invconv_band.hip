@@ -46,19 +46,23 @@ constexpr int kRing = 4;        // depth of the band-to-band message ring
 // PAD: the image has Cr < 4 CG channels (5-7, 9-11, 13-15).  The lanes' channel slots beyond Cr carry zero weights in
 // both operand roles, read as zero and are never stored, so the solve is that of the Cr real channels; the folded
 // weights are then laid out with row length Cr.
-template <int CG, int K, int DIR, int MAXT = 512, bool PAD = false>
+// LDSW: the C k^2 / 4 folded taps of a lane do not fit its registers (k = 9, 11; 16 channels at k = 7): they stay in
+// LDS, negated, and every matrix instruction fetches its A operand from there (a fixed address per lane and tap).
+// Lanes whose A row is padding read some valid row: their result rows are never used.
+template <int CG, int K, int DIR, int MAXT = 512, bool PAD = false, bool LDSW = false>
 __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ in, const float *__restrict__ w,
                                                     float *__restrict__ out, int H, int W, int NB, float *logdet,
                                                     int Cr)
 {
+    static_assert(!(PAD && LDSW), "taps in LDS go with channel counts the lanes are laid out for");
     constexpr int C = 4 * CG;
     const int Cs = PAD ? Cr : C;        // channels of the image = row length of the folded weights
     extern __shared__ float smem[];
     float *sL = smem;
     float *sLinv = sL + C * C;
     float *sCf = sLinv + C * C;
-    float *sW = sCf + K * K * C * C;
-    float *sMsg = sW + K * K * C * C;       // [NB][kRing][K][16 groups*4]  (a = 0 unused)
+    float *sW = sCf + K * K * C * C;        // (staging copy of the runtime-C fold; the compile-time-C fold does without)
+    float *sMsg = LDSW ? sW : sW + K * K * C * C;       // [NB][kRing][K][16 groups*4]  (a = 0 unused)
 
     const int tid = threadIdx.x;
     const int band = tid >> 6, lane = tid & 63;
@@ -120,23 +124,37 @@ __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ i
     const int m = n;
     const bool m_ok = (m & 3) < CG && (!PAD || CG * (m >> 2) + (m & 3) < Cs);
     const int om = m_ok ? CG * (m >> 2) + (m & 3) : 0;
-    float wA[K][K][CG], wLi[CG];
+    float wA[LDSW ? 1 : K][LDSW ? 1 : K][CG], wLi[CG];
+    if constexpr (!LDSW) {
 #pragma unroll
-    for (int a = 0; a < K; ++a)
+        for (int a = 0; a < K; ++a)
 #pragma unroll
-        for (int db = 0; db < K; ++db)
+            for (int db = 0; db < K; ++db)
 #pragma unroll
-            for (int jj = 0; jj < CG; ++jj) {
-                const int ii = ch_ok[jj] ? CG * g + jj : 0;
-                const float cf = sCf[((a * K + db) * Cs + om) * Cs + ii];
-                wA[a][db][jj] = m_ok && ch_ok[jj] ? -cf : 0.0f;
-            }
+                for (int jj = 0; jj < CG; ++jj) {
+                    const int ii = ch_ok[jj] ? CG * g + jj : 0;
+                    const float cf = sCf[((a * K + db) * Cs + om) * Cs + ii];
+                    wA[a][db][jj] = m_ok && ch_ok[jj] ? -cf : 0.0f;
+                }
+    }
 #pragma unroll
     for (int jj = 0; jj < CG; ++jj) {
         const float lv = sLinv[om * Cs + (ch_ok[jj] ? CG * g + jj : 0)];
         wLi[jj] = m_ok && ch_ok[jj] ? lv : 0.0f;
     }
-    __syncthreads();        // ring zeroed, weights read
+    if constexpr (LDSW) {
+        for (int idx = tid; idx < K * K * C * C; idx += blockDim.x)
+            sCf[idx] = -sCf[idx];
+    }
+    // A operand of tap (a, db), K slot jj: a register, or this lane's entry of the negated taps in LDS
+    const float *cfp = sCf + om * C + CG * g;
+    auto tapw = [&](int a, int db, int jj) -> float {
+        if constexpr (LDSW)
+            return cfp[(a * K + db) * C * C + jj];
+        else
+            return wA[a][db][jj];
+    };
+    __syncthreads();        // ring zeroed, weights read (or negated in place)
     if (band >= NB) {
         // helper waves of a single-band launch: they only speed up the weight preparation; the last one of the
         // first workgroup also forms the log-determinant when the caller asked for it
@@ -231,7 +249,7 @@ __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ i
                 for (int db = K - 1; db >= 0; --db)     // oldest column first: only db = 0 waits for this step\'s result
 #pragma unroll
                     for (int jj = 0; jj < CG; ++jj)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[a][db][jj], xh[jj][db], acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(tapw(a, db, jj), xh[jj][db], acc, 0, 0, 0);
                 T[a] = acc;
             }
             if (last_row) {
@@ -259,7 +277,7 @@ __global__ __launch_bounds__(MAXT) void k_solve_band(const float *__restrict__ i
                 for (int db = K - 1; db >= 1; --db)
 #pragma unroll
                     for (int jj = 0; jj < CG; ++jj)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wA[0][db][jj], xh[jj][db], acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(tapw(0, db, jj), xh[jj][db], acc, 0, 0, 0);
                 own = acc;
                 const unsigned off = clamp_row(ldoff);
 #pragma unroll
@@ -554,14 +572,19 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
         wave_logdet_any(w, Cs, K, H, W, logdet);
 }
 
+// taps in LDS instead of registers: k = 9 and 11, and k = 7 at 16 channels
+static bool band_taps_in_lds(int Cp, int k) { return k >= 9 || (k == 7 && Cp > 12); }
+
 size_t solve_band_lds_bytes(int C, int k, int NB)
 {
-    return sizeof(float) * (2 * (size_t)C * C + 2 * (size_t)k * k * C * C + (size_t)NB * kRing * k * 64);
+    const size_t copies = band_taps_in_lds(C, k) ? 1 : 2;      // (the staging copy only exists beside register taps)
+    return sizeof(float) * (2 * (size_t)C * C + copies * (size_t)k * k * C * C + (size_t)NB * kRing * k * 64);
 }
 
 // k = 3: at most 8 bands = 512 threads.  Other kernel sizes of the paper's kernel-size ablation (2, 5; 7 up to 12
 // channels) run on the general kernel with at most four bands: a lane then keeps C k^2 / 4 folded taps in registers
-// (147 at 12 channels, k = 7), which k = 9 and 11 do not have.
+// (147 at 12 channels, k = 7).  k = 9 and 11 (and 7 at 16 channels) do not have the registers: their taps stay in
+// LDS (8, 12 or 16 channels only).
 // Channel counts between the sizes the lanes are laid out for (5-7, 9-11, 13-15) run the next size up with the
 // surplus channel slots switched off.
 bool band_supported(int C, int H, int k)
@@ -571,7 +594,9 @@ bool band_supported(int C, int H, int k)
     if (k == 3)
         return H <= 128;
     const int Cp = (C + 3) / 4 * 4;
-    const bool size_ok = k == 2 || k == 5 || (k == 7 && Cp <= 12);
+    const bool size_ok = k == 2 || k == 5 || k == 7 || k == 9 || k == 11;
+    if (band_taps_in_lds(Cp, k) && C != Cp)
+        return false;
     return size_ok && H <= 64 && solve_band_lds_bytes(Cp, k, (H + 15) / 16) <= kMaxLdsBytes;
 }
 
@@ -597,17 +622,22 @@ static int launch_band_ck(int dir, const float *in, const float *w, float *out, 
     const int threads = NB == 1 ? 256 : 64 * NB;
     if (threads > MAXT)
         return INVCONV_ERR_VARIANT;
-    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_band<CG, K, 1, MAXT, PAD>)
-                         : reinterpret_cast<const void *>(&k_solve_band<CG, K, 0, MAXT, PAD>);
-    if (!ensure_dynamic_lds(fn, lds))
-        return INVCONV_ERR_UNSUPPORTED;
-    if (dir)
-        hipLaunchKernelGGL((k_solve_band<CG, K, 1, MAXT, PAD>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W,
-                           NB, logdet, C);
-    else
-        hipLaunchKernelGGL((k_solve_band<CG, K, 0, MAXT, PAD>), dim3(B), dim3(threads), lds, stream, in, w, out, H, W,
-                           NB, logdet, C);
-    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+    constexpr bool LDSW = K >= 9 || (K == 7 && CG == 4);
+    if constexpr (LDSW && PAD) {
+        return INVCONV_ERR_VARIANT;
+    } else {
+        const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_band<CG, K, 1, MAXT, PAD, LDSW>)
+                             : reinterpret_cast<const void *>(&k_solve_band<CG, K, 0, MAXT, PAD, LDSW>);
+        if (!ensure_dynamic_lds(fn, lds))
+            return INVCONV_ERR_UNSUPPORTED;
+        if (dir)
+            hipLaunchKernelGGL((k_solve_band<CG, K, 1, MAXT, PAD, LDSW>), dim3(B), dim3(threads), lds, stream, in, w,
+                               out, H, W, NB, logdet, C);
+        else
+            hipLaunchKernelGGL((k_solve_band<CG, K, 0, MAXT, PAD, LDSW>), dim3(B), dim3(threads), lds, stream, in, w,
+                               out, H, W, NB, logdet, C);
+        return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+    }
 }
 
 // Forward pass of a whole flow step on the one-band kernel: 5-16 channels, k = 3, images of at most 16 rows.
@@ -651,9 +681,9 @@ int launch_solve_band(int dir, const float *in, const float *w, float *out, int 
         if (k == 3) return launch_band_ck<CG, 3, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
         if (k == 2) return launch_band_ck<CG, 2, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
         if (k == 5) return launch_band_ck<CG, 5, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
-        if constexpr (CG <= 3) {
-            if (k == 7) return launch_band_ck<CG, 7, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
-        }
+        if (k == 7) return launch_band_ck<CG, 7, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
+        if (k == 9) return launch_band_ck<CG, 9, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
+        if (k == 11) return launch_band_ck<CG, 11, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
         return INVCONV_ERR_VARIANT;
     };
     auto by_cg = [&](auto pad_tag) -> int {

@@ -83,6 +83,9 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     # 8 / 12 / 16 channels with the other kernel sizes of the kernel-size ablation (band kernel with k = 2, 5, 7)
     (2, 12, 16, 16, 5), (3, 8, 40, 24, 2), (2, 16, 33, 20, 5), (2, 12, 64, 24, 7), (1, 8, 16, 16, 7), (2, 16, 16, 16, 2),
     (2, 12, 20, 12, 2), (1, 16, 64, 9, 5), (3, 12, 7, 50, 5),
+    # 8 / 12 / 16 channels with k = 9 and 11 (and 16 channels with k = 7): band kernel with its folded taps in LDS
+    (3, 12, 16, 16, 9), (2, 12, 20, 12, 11), (2, 8, 33, 20, 9), (2, 16, 16, 16, 7), (1, 16, 40, 9, 9), (2, 16, 16, 16, 11),
+    (1, 8, 64, 8, 11),
     # channel counts between the band kernels' sizes (5-7, 9-11, 13-15): the next size up with the surplus slots off
     (3, 6, 16, 16, 3), (2, 5, 9, 11, 3), (2, 7, 33, 20, 3), (1, 10, 128, 40, 3), (2, 14, 40, 24, 3), (1, 15, 100, 8, 3),
     (2, 6, 20, 20, 2), (2, 10, 33, 16, 5), (1, 9, 40, 12, 7), (40, 6, 32, 32, 3), (2, 13, 16, 30, 3),
