@@ -62,7 +62,7 @@ enum {
     INVCONV_ERR_SHAPE = -2,       /* B, C, H, W or k < 1, B*C*H*W > 2^31 - 1, or one image C*H*W >= 2^29 elements (2 GiB) */
     INVCONV_ERR_UNSUPPORTED = -3, /* shape beyond what the kernels' on-chip buffers hold: a kernel variant asked for by name, the
                                      weight gradient's tiles, or - the default solve falls back to one launch per anti-diagonal
-                                     for shapes no on-chip kernel holds, far slower - more than 4096 kernel entries C k k per
+                                     for shapes no on-chip kernel holds, far slower - more than 8192 kernel entries C k k per
                                      output channel */
     INVCONV_ERR_WORKSPACE = -4,   /* workspace NULL, not 256-byte aligned, smaller than *_workspace_bytes(), or
                                      (entry point without a workspace argument) larger than the library's own */

@@ -197,7 +197,9 @@ __global__ __launch_bounds__(256) void k_solve_one_diagonal(const float *__restr
 // and the new x_o takes its place among the values before channel o + 1 starts (Eq. 1 solved for x, channel
 // by channel).  Two to three orders of magnitude faster than a thread per pixel at 64 channels.
 // ---------------------------------------------------------------------------
-template <int DIR>
+// MAXJ: terms of a kernel row per lane that the registers hold (16, 40 or 64: rows of up to 1024, 2560 or 4096
+// entries); longer rows are read where they are used.
+template <int DIR, int MAXJ>
 __global__ __launch_bounds__(256) void k_solve_diag_wave(const float *__restrict__ in, const float *__restrict__ w,
                                                         float *out, int B, int C, int H, int W, int k, int d)
 {
@@ -223,7 +225,6 @@ __global__ __launch_bounds__(256) void k_solve_diag_wave(const float *__restrict
     __builtin_amdgcn_wave_barrier();
     // Row o + 1 of the kernel (this lane's terms), its diagonal entry and y_{o+1} are fetched while channel o is
     // being solved: the chain over the channels then waits for LDS and the butterfly only, not for memory.
-    constexpr int MAXJ = 16;                    // terms per lane held in registers (rows of up to 1024 entries)
     const int nj = (T + 63) / 64;
     const bool pre = nj <= MAXJ;
     // where this lane's terms sit in a row of the kernel (no division in the loop over the channels): entry
@@ -660,18 +661,14 @@ static int launch_persistent_dir(const float *in, const float *w, float *out, in
     return INVCONV_OK;
 }
 
-// one launch per anti-diagonal, a wave per pixel (see k_solve_diag_wave); refuses kernels of more than 4096
-// entries per output channel (four waves' values have to fit 64 KB of LDS)
-int launch_solve_diag_wave(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                           hipStream_t stream)
+// one launch per anti-diagonal, a wave per pixel (see k_solve_diag_wave); refuses kernels of more than 8192
+// entries per output channel (four waves' values have to fit 128 KB of LDS)
+template <int DIR, int MAXJ>
+static int launch_diag_wave_dj(const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                               hipStream_t stream)
 {
-    const size_t T = (size_t)C * k * k;
-    if (T > 4096)
-        return INVCONV_ERR_UNSUPPORTED;
-    const size_t lds = 4 * T * sizeof(float);
-    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_diag_wave<1>)
-                         : reinterpret_cast<const void *>(&k_solve_diag_wave<0>);
-    if (!ensure_dynamic_lds(fn, lds))
+    const size_t lds = 4 * (size_t)C * k * k * sizeof(float);
+    if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_solve_diag_wave<DIR, MAXJ>), lds))
         return INVCONV_ERR_UNSUPPORTED;
     const int ndiag = H + W - 1;
     for (int d = 0; d < ndiag; ++d) {
@@ -679,14 +676,28 @@ int launch_solve_diag_wave(int dir, const float *in, const float *w, float *out,
         const int rhi = d < H - 1 ? d : H - 1;
         const long long items = (long long)B * (rhi - rlo + 1);
         const unsigned grid = (unsigned)((items + 3) / 4);
-        if (dir)
-            hipLaunchKernelGGL(k_solve_diag_wave<1>, dim3(grid), dim3(256), lds, stream, in, w, out, B, C, H, W, k, d);
-        else
-            hipLaunchKernelGGL(k_solve_diag_wave<0>, dim3(grid), dim3(256), lds, stream, in, w, out, B, C, H, W, k, d);
+        hipLaunchKernelGGL((k_solve_diag_wave<DIR, MAXJ>), dim3(grid), dim3(256), lds, stream, in, w, out, B, C, H, W, k,
+                           d);
         if (hipGetLastError() != hipSuccess)
             return INVCONV_ERR_LAUNCH;
     }
     return INVCONV_OK;
+}
+
+int launch_solve_diag_wave(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                           hipStream_t stream)
+{
+    const size_t T = (size_t)C * k * k;
+    if (T > 8192)
+        return INVCONV_ERR_UNSUPPORTED;
+    if (T <= 1024)
+        return dir ? launch_diag_wave_dj<1, 16>(in, w, out, B, C, H, W, k, stream)
+                   : launch_diag_wave_dj<0, 16>(in, w, out, B, C, H, W, k, stream);
+    if (T <= 2560)
+        return dir ? launch_diag_wave_dj<1, 40>(in, w, out, B, C, H, W, k, stream)
+                   : launch_diag_wave_dj<0, 40>(in, w, out, B, C, H, W, k, stream);
+    return dir ? launch_diag_wave_dj<1, 64>(in, w, out, B, C, H, W, k, stream)
+               : launch_diag_wave_dj<0, 64>(in, w, out, B, C, H, W, k, stream);
 }
 
 int launch_solve_persistent(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W,

@@ -49,9 +49,9 @@ def test_fwd_rejects_bad_arguments():
     assert L.invconv_fwd_ex(y, w, x, 1, 1, 4, 4, 3, None, 99) == b.ERR_VARIANT
     # on-chip buffers too small for this shape: the LDS-window variant asked for by name refuses, and so does the
     # default path when even its last resort (a wave per pixel, one launch per anti-diagonal) cannot hold a row of
-    # the kernel (more than 4096 entries per output channel)
+    # the kernel (more than 8192 entries per output channel)
     assert L.invconv_fwd_ex(y, w, x, 1, 64, 2048, 1024, 11, None, b.VARIANT_BLOCK) == b.ERR_UNSUPPORTED
-    assert L.invconv_fwd(y, w, x, 1, 64, 2048, 1024, 11, None) == b.ERR_UNSUPPORTED
+    assert L.invconv_fwd(y, w, x, 1, 80, 2048, 1024, 11, None) == b.ERR_UNSUPPORTED
 
 
 def test_conv_rejects_bad_arguments():

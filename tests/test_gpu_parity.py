@@ -94,6 +94,7 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     (2, 45, 8, 8, 3), (3, 46, 8, 8, 3), (1, 37, 32, 32, 3),
     # shapes no on-chip kernel holds: one launch per anti-diagonal, a wave per pixel
     (5, 64, 4, 4, 3), (2, 96, 2, 2, 3), (1, 44, 70, 9, 3), (2, 128, 2, 3, 3), (1, 52, 5, 6, 2), (1, 64, 3, 3, 5),
+    (2, 48, 8, 8, 5), (1, 48, 6, 5, 7), (1, 48, 4, 4, 11), (1, 64, 3, 3, 9),     # kernel rows of 1200 to 5808 entries
     # 8 / 12 channels, large batches or tall images: single-layer solves through the pipelined kernel
     (130, 12, 64, 64, 3), (26, 12, 100, 36, 3), (300, 8, 40, 24, 3), (40, 8, 128, 8, 3),
 ]
