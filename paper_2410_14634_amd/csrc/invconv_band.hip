@@ -572,6 +572,266 @@ __global__ __launch_bounds__(256) void k_solve_band_split(const float *__restric
         wave_logdet_any(w, Cs, K, H, W, logdet);
 }
 
+// ---------------------------------------------------------------------------
+// Images of at most 16 rows with the larger kernels of the kernel-size ablation (k = 5, 7, 9, 11): the K K CG matrix
+// instructions of a step split over NF + 2 waves by the age of their input, as the few-channel split solve does
+// (lane = row there, lane (n, g) here).  With x_s the diagonal solved at step s and A[a][db] the folded taps,
+//   T[a]_s    = up(T[a+1]_{s-1}) + A[a][0] x_s + { sum_{db>=1} A[a][db] x_{s-db} }   = Tp[a]_s + F[a]_s
+//   own_{s+1} =                    A[0][1] x_s + { Linv y_{s+1} + sum_{db>=2} A[0][db] x_{s+1-db} }
+//   x_{s+1}   = own_{s+1} + up(T[1]_s)
+// The braces need nothing newer than x_{s-1}.  Wave 0, on the chain of dependent steps, publishes x_s through LDS
+// and issues only the K CG instructions that read it; waves 1 .. NF form the F[a]_s of their rows a (delivered
+// already shifted one row up), the last wave forms O_{s+1}, reads y and stores x.  Every role keeps only its own
+// taps in registers, which is what lets k = 9 and 11 run from registers at all.  One barrier per step.
+// ---------------------------------------------------------------------------
+__host__ __device__ constexpr int band_splitk_nf(int K) { return K >= 7 ? (K - 1) / 2 : 2; }
+
+template <int CG, int K>
+__host__ __device__ constexpr size_t band_splitk_lds_floats()
+{
+    // Linv, folded taps, scratch L; x of the last two steps; messages of the last two steps (slot 0: O, slot a: F[a])
+    return 2 * 16 * CG * CG + (size_t)K * K * 16 * CG * CG + 2 * CG * 64 + 2 * (size_t)K * 64 * 4;
+}
+
+template <int CG, int K, int DIR>
+__global__ __launch_bounds__(64 * (band_splitk_nf(K) + 2)) void k_solve_band_splitk(const float *__restrict__ in,
+                                                                                   const float *__restrict__ w,
+                                                                                   float *__restrict__ out, int H,
+                                                                                   int W, float *logdet)
+{
+    constexpr int C = 4 * CG, NF = band_splitk_nf(K), PER = (K - 1 + NF - 1) / NF, kOWave = NF + 1;
+    extern __shared__ float smem[];
+    float *sL = smem;
+    float *sLinv = sL + C * C;
+    float *sCf = sLinv + C * C;
+    float *sX = sCf + K * K * C * C;                            // [2][CG][64]
+    f32x4 *sM = reinterpret_cast<f32x4 *>(sX + 2 * CG * 64);    // [2][K][64]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const bool row_ok = n < H;
+    const int rr = row_ok ? n : H - 1;
+    const unsigned Wst = row_ok ? (unsigned)W : 0u;
+
+    const size_t img = (size_t)blockIdx.x * C * H * W;
+    const char *chan_src[CG];
+    char *chan_dst[CG];
+#pragma unroll
+    for (int jj = 0; jj < CG; ++jj) {
+        const int ch = CG * g + jj;
+        const size_t cb = img + (size_t)(DIR ? C - 1 - ch : ch) * H * W;
+        chan_src[jj] = reinterpret_cast<const char *>(in + cb);
+        chan_dst[jj] = reinterpret_cast<char *>(out + cb);
+    }
+    constexpr int kStep = DIR ? -4 : 4;
+    const int row0 = 4 * (DIR ? (H - 1 - rr) * W + (W - 1) : rr * W);
+    const int rowlo = DIR ? row0 - 4 * (W - 1) : row0;
+    const int rowhi = DIR ? row0 : row0 + 4 * (W - 1);
+    auto clamp_row = [&](int off) -> unsigned { return (unsigned)(off < rowlo ? rowlo : (off > rowhi ? rowhi : off)); };
+
+    // the last wave reads y: slot u holds the input of the steps congruent to u (first batch before the weight
+    // preparation; the other waves run the same instructions on one common address)
+    float yb[kBandPF][CG];
+#pragma unroll
+    for (int u = 0; u < kBandPF; ++u) {
+        const unsigned off = wave == kOWave ? clamp_row(row0 + kStep * (u - n)) : 0u;
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj)
+            yb[u][jj] = *reinterpret_cast<const float *>((wave == kOWave ? chan_src[jj] : chan_src[0]) + off);
+    }
+
+    fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sCf);         // (the compile-time-C fold needs no staging copy)
+    for (int idx = tid; idx < 2 * CG * 64 + 2 * K * 64 * 4; idx += blockDim.x)
+        sX[idx] = 0.0f;                                         // x and message slots are contiguous
+
+    // A operands: row m = n -> output channel om (rows with m % 4 >= CG are padding: zero weights)
+    const bool m_ok = (n & 3) < CG;
+    const int om = m_ok ? CG * (n >> 2) + (n & 3) : 0;
+    auto tap = [&](int a, int db, int jj) -> float {
+        const float cf = sCf[((a * K + db) * C + om) * C + CG * g + jj];
+        return m_ok ? -cf : 0.0f;
+    };
+#pragma unroll
+    for (int u = 0; u < kBandPF; ++u)
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj)
+            asm volatile("" : "+v"(yb[u][jj]));
+
+    // step s = -1 only lets the last wave prepare O_0 = Linv y_0; the steps after the last diagonal only let it store
+    const int nsteps = 16 + W - 1;
+    const int total = nsteps + 2;       // steps -1 .. total-2, the same for every wave
+    if (wave == 0) {
+        float wC[K][CG];                // wC[a], a >= 1: A[a][0];  wC[0]: A[0][1]
+#pragma unroll
+        for (int a = 0; a < K; ++a)
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj)
+                wC[a][jj] = a == 0 ? tap(0, 1, jj) : tap(a, 0, jj);
+        __syncthreads();
+        f32x4 Tp[K], ownp = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int a = 0; a < K; ++a)
+            Tp[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int s = -1; s < total - 1; ++s) {
+            const f32x4 *mi = sM + ((s - 1) & 1) * K * 64 + lane;
+            f32x4 Fs[K];
+#pragma unroll
+            for (int a = 1; a < K; ++a)
+                Fs[a] = mi[a * 64];
+            const f32x4 own = ownp + mi[0];
+            float xn[CG];
+#pragma unroll
+            for (int j = 0; j < CG; ++j) {
+                xn[j] = own[j] + (from_row_above16(Tp[1][j]) + Fs[1][j]);
+                sX[((s & 1) * CG + j) * 64 + lane] = xn[j];
+            }
+#pragma unroll
+            for (int a = 1; a < K; ++a) {
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (a + 1 < K) {
+#pragma unroll
+                    for (int j = 0; j < CG; ++j)
+                        acc[j] = from_row_above16(Tp[a + 1][j]) + Fs[a + 1][j];
+                }
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wC[a][jj], xn[jj], acc, 0, 0, 0);
+                Tp[a] = acc;
+            }
+            {
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wC[0][jj], xn[jj], acc, 0, 0, 0);
+                ownp = acc;
+            }
+            __syncthreads();
+        }
+    } else if (wave <= NF) {
+        // F[a]_s = sum_{db>=1} A[a][db] x_{s-db} for this wave's rows a = A_LO .. A_LO + PER - 1
+        const int a_lo = (wave - 1) * PER + 1;
+        float wF[PER][K][CG];           // [.][db], db >= 1
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+#pragma unroll
+            for (int db = 1; db < K; ++db)
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    wF[q][db][jj] = a_lo + q < K ? tap(a_lo + q, db, jj) : 0.0f;
+        __syncthreads();
+        float xo[K][CG];                // xo[db] = x_{s-db}, db >= 1
+#pragma unroll
+        for (int db = 0; db < K; ++db)
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj)
+                xo[db][jj] = 0.0f;
+        for (int s = -1; s < total - 1; ++s) {
+#pragma unroll
+            for (int db = K - 1; db >= 2; --db)
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    xo[db][jj] = xo[db - 1][jj];
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj)
+                xo[1][jj] = sX[(((s - 1) & 1) * CG + jj) * 64 + lane];
+            f32x4 *mo = sM + (s & 1) * K * 64 + lane;
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f}, acc2 = acc;
+#pragma unroll
+                for (int db = K - 1; db >= 1; --db)
+#pragma unroll
+                    for (int jj = 0; jj < CG; ++jj) {
+                        if ((db ^ jj) & 1)
+                            acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(wF[q][db][jj], xo[db][jj], acc2, 0, 0, 0);
+                        else
+                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wF[q][db][jj], xo[db][jj], acc, 0, 0, 0);
+                    }
+                acc += acc2;
+                f32x4 up = f32x4{0.f, 0.f, 0.f, 0.f};      // what the row below will add: F[a] of the row above
+#pragma unroll
+                for (int j = 0; j < CG; ++j)
+                    up[j] = from_row_above16(acc[j]);
+                if (a_lo + q < K)
+                    mo[(a_lo + q) * 64] = up;
+            }
+            __syncthreads();
+        }
+    } else {
+        // O_{s+1} = Linv y_{s+1} + sum_{db>=2} A[0][db] x_{s+1-db}; also x_{s-1} to global memory
+        float wO[K][CG], wLi[CG];       // wO[db], db >= 2
+#pragma unroll
+        for (int db = 2; db < K; ++db)
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj)
+                wO[db][jj] = tap(0, db, jj);
+#pragma unroll
+        for (int jj = 0; jj < CG; ++jj) {
+            const float lv = sLinv[om * C + CG * g + jj];
+            wLi[jj] = m_ok ? lv : 0.0f;
+        }
+        __syncthreads();
+        float xo[K][CG];                // xo[db] = x_{s+1-db}, db >= 2
+#pragma unroll
+        for (int db = 0; db < K; ++db)
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj)
+                xo[db][jj] = 0.0f;
+        int ldoff = row0 + kStep * (kBandPF - n);       // unclamped offset of the next refill
+        auto step = [&](int s, int u, bool refill) {
+#pragma unroll
+            for (int db = K - 1; db >= 3; --db)
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    xo[db][jj] = xo[db - 1][jj];
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj)
+                xo[2][jj] = sX[(((s - 1) & 1) * CG + jj) * 64 + lane];
+            const bool in_row = (unsigned)(s + 1 - n) < (unsigned)W;
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f}, acc2 = acc;
+#pragma unroll
+            for (int jj = 0; jj < CG; ++jj)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(wLi[jj], in_row ? yb[u][jj] : 0.0f, acc, 0, 0, 0);
+#pragma unroll
+            for (int db = K - 1; db >= 2; --db)
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    acc2 = __builtin_amdgcn_mfma_f32_16x16x4f32(wO[db][jj], xo[db][jj], acc2, 0, 0, 0);
+            sM[(s & 1) * K * 64 + lane] = acc + acc2;
+            const int c = s - 1 - n;        // column of x_{s-1} = xo[2] in this lane's row
+            if ((unsigned)c < Wst) {
+                const unsigned off = (unsigned)(row0 + kStep * c);
+#pragma unroll
+                for (int j = 0; j < CG; ++j)
+                    *reinterpret_cast<float *>(chan_dst[j] + off) = xo[2][j];
+            }
+            if (refill) {       // the input of step s + 1 + kBandPF
+                const unsigned off = clamp_row(ldoff);
+#pragma unroll
+                for (int jj = 0; jj < CG; ++jj)
+                    yb[u][jj] = *reinterpret_cast<const float *>(chan_src[jj] + off);
+                ldoff += kStep;
+            }
+            __syncthreads();
+        };
+        const int nfull = total / kBandPF;
+        int s0 = -1;
+        for (int blk = 0; blk < nfull; ++blk, s0 += kBandPF) {
+#pragma unroll
+            for (int u = 0; u < kBandPF; ++u)
+                step(s0 + u, u, true);
+        }
+        const int rest = total - nfull * kBandPF;
+#pragma unroll
+        for (int u = 0; u < kBandPF; ++u)
+            if (u < rest)
+                step(s0 + u, u, false);
+    }
+    if (logdet && blockIdx.x == 0 && wave == 1)
+        wave_logdet_any(w, C, K, H, W, logdet);
+}
+
 // taps in LDS instead of registers: k = 9 and 11, and k = 7 at 16 channels
 static bool band_taps_in_lds(int Cp, int k) { return k >= 9 || (k == 7 && Cp > 12); }
 
@@ -615,6 +875,22 @@ static int launch_band_ck(int dir, const float *in, const float *w, float *out, 
             hipLaunchKernelGGL((k_solve_band_split<CG, 0, PAD>), dim3(B), dim3(256), lds1, stream, in, w, out, H, W,
                                logdet, C);
         return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+    }
+    if constexpr (K >= 5 && !PAD) {
+        // one band, a larger kernel: the step split over the waves by the age of its input
+        const size_t ldsk = sizeof(float) * band_splitk_lds_floats<CG, K>();
+        if (NB == 1 && ldsk <= kMaxLdsBytes) {
+            const void *fnk = dir ? reinterpret_cast<const void *>(&k_solve_band_splitk<CG, K, 1>)
+                                  : reinterpret_cast<const void *>(&k_solve_band_splitk<CG, K, 0>);
+            if (!ensure_dynamic_lds(fnk, ldsk))
+                return INVCONV_ERR_UNSUPPORTED;
+            const dim3 blk(64 * (band_splitk_nf(K) + 2));
+            if (dir)
+                hipLaunchKernelGGL((k_solve_band_splitk<CG, K, 1>), dim3(B), blk, ldsk, stream, in, w, out, H, W, logdet);
+            else
+                hipLaunchKernelGGL((k_solve_band_splitk<CG, K, 0>), dim3(B), blk, ldsk, stream, in, w, out, H, W, logdet);
+            return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+        }
     }
     const size_t lds = solve_band_lds_bytes(4 * CG, K, NB);
     constexpr int MAXT = K == 3 ? 512 : 256;

@@ -86,6 +86,9 @@ EDGE_SHAPES = [  # (B, C, H, W, k)
     # 8 / 12 / 16 channels with k = 9 and 11 (and 16 channels with k = 7): band kernel with its folded taps in LDS
     (3, 12, 16, 16, 9), (2, 12, 20, 12, 11), (2, 8, 33, 20, 9), (2, 16, 16, 16, 7), (1, 16, 40, 9, 9), (2, 16, 16, 16, 11),
     (1, 8, 64, 8, 11),
+    # one band and k = 5 ... 11: the step split over four to seven waves by the age of its input
+    (2, 12, 16, 16, 5), (2, 12, 7, 50, 5), (2, 8, 16, 20, 7), (1, 16, 9, 9, 9), (1, 8, 1, 8, 11), (2, 12, 16, 24, 11),
+    (3, 12, 1, 1, 7), (2, 16, 13, 3, 5), (101, 12, 16, 16, 9),
     # channel counts between the band kernels' sizes (5-7, 9-11, 13-15): the next size up with the surplus slots off
     (3, 6, 16, 16, 3), (2, 5, 9, 11, 3), (2, 7, 33, 20, 3), (1, 10, 128, 40, 3), (2, 14, 40, 24, 3), (1, 15, 100, 8, 3),
     (2, 6, 20, 20, 2), (2, 10, 33, 16, 5), (1, 9, 40, 12, 7), (40, 6, 32, 32, 3), (2, 13, 16, 30, 3),
