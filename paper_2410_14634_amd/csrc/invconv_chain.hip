@@ -118,7 +118,7 @@ __global__ __launch_bounds__(64 * (kCIo * chain_io_bands(4 * CG) + 2 * kCIo)) vo
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    fold_weights<DIR, C>(w, C, K, sL, sLinv, sCf, sW);
+    fold_weights_staged<DIR, C>(w, C, K, sL, sLinv, sCf, sW);
     const float *__restrict__ map = MAP ? a.map[stage] : nullptr;
     if (MAP && DIR && map) {
         // solve channel m is true channel C-1-m: the solve's input is y'[m] = sum_j A[C-1-j][C-1-m] in[j],

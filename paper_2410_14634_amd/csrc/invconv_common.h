@@ -186,6 +186,115 @@ __device__ void fold_weights(const float *__restrict__ w, int C, int k,
     __syncthreads();
 }
 
+// The earlier form of the preparation for a compile-time C: the kernel staged in LDS (sW), Linv by one thread per
+// column, the products Linv W_tap from LDS.  Three rounds instead of one, but it keeps fewer values per thread: in
+// the pipelined stack kernel (sixteen waves of 128 registers) it measures 22 us less per launch than the
+// substitution form above, and a launch of that kernel prepares its weights once in half a millisecond.
+template <int DIR, int CT = 0>
+__device__ void fold_weights_staged(const float *__restrict__ w, int C, int k,
+                             float *sL, float *sLinv, float *sCf, float *sW)
+{
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int total = k * k * C * C;
+    // the kernel is read four entries per thread at a time (addresses clamped, no branch around a load),
+    // so that the whole staging costs about one memory latency
+    for (int base = tid; base < total; base += 4 * nt) {
+        float val[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int raw = base + u * nt;
+            const int idx = raw < total ? raw : total - 1;
+            const int i = idx % C, o = (idx / C) % C, tp = idx / (C * C);
+            const int a = k - 1 - tp / k, b = k - 1 - tp % k;
+            const int oo = DIR ? C - 1 - i : o, ii = DIR ? C - 1 - o : i;
+            const float v = w[((oo * C + ii) * k + a) * k + b];
+            val[u] = (tp == 0 && ii > oo) ? 0.0f : v;       // the current-pixel block's upper triangle reads as zero
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + u * nt;
+            if (idx < total) {
+                sW[idx] = val[u];
+                if (idx < C * C)
+                    sL[idx] = val[u];       // tp == 0: idx = o * C + i
+            }
+        }
+    }
+    __syncthreads();
+    if (CT > 0) {
+        // column j of Linv by forward substitution in registers: the needed part of L and the reciprocals
+        // of its diagonal are fetched first, so the chain over o is multiply-adds only (entries above the
+        // diagonal stay zero, so the inner sum needs no lower bound)
+        if (tid < CT) {
+            const int j = tid;
+            constexpr int N = CT > 0 ? CT : 1;
+            float Lr[N][N], rd[N], lv[N];
+#pragma unroll
+            for (int o = 0; o < N; ++o)
+#pragma unroll
+                for (int m = 0; m <= o; ++m)
+                    Lr[o][m] = sL[o * N + m];
+#pragma unroll
+            for (int o = 0; o < N; ++o)
+                rd[o] = 1.0f / Lr[o][o];
+#pragma unroll
+            for (int o = 0; o < N; ++o) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int m = 0; m < o; ++m)
+                    acc += Lr[o][m] * lv[m];
+                lv[o] = (o == j) ? rd[o] : (o > j ? -acc * rd[o] : 0.0f);
+                sLinv[o * N + j] = lv[o];
+            }
+        }
+    } else if (tid < C) {
+        const int j = tid;
+        for (int o = 0; o < j; ++o)
+            sLinv[o * C + j] = 0.0f;
+        sLinv[j * C + j] = 1.0f / sL[j * C + j];
+        for (int o = j + 1; o < C; ++o) {
+            float s = 0.0f;
+            for (int m = j; m < o; ++m)
+                s += sL[o * C + m] * sLinv[m * C + j];
+            sLinv[o * C + j] = -s / sL[o * C + o];
+        }
+    }
+    __syncthreads();
+    if (CT > 0) {
+        // two outputs per trip, so that the LDS reads of one overlap the arithmetic of the other
+        // (entries of Linv above the diagonal are zero, so the full row may be used)
+        for (int idx = tid; idx < total; idx += 2 * nt) {
+            const int idx2 = idx + nt < total ? idx + nt : idx;
+            const int i = idx % CT, o = (idx / CT) % CT, tp = idx / (CT * CT);
+            const int i2 = idx2 % CT, o2 = (idx2 / CT) % CT, tp2 = idx2 / (CT * CT);
+            const float *li = sLinv + o * CT, *wt = sW + tp * CT * CT + i;
+            const float *li2 = sLinv + o2 * CT, *wt2 = sW + tp2 * CT * CT + i2;
+            float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+            for (int j = 0; j < (CT > 0 ? CT : 1); ++j) {
+                s1 += li[j] * wt[j * CT];
+                s2 += li2[j] * wt2[j * CT];
+            }
+            sCf[idx] = tp != 0 ? s1 : 0.0f;
+            if (idx + nt < total)
+                sCf[idx2] = tp2 != 0 ? s2 : 0.0f;
+        }
+    } else {
+        for (int idx = tid; idx < total; idx += nt) {
+            const int i = idx % C, o = (idx / C) % C, tp = idx / (C * C);
+            float s = 0.0f;
+            if (tp != 0) {
+                const float *li = sLinv + o * C;
+                const float *wt = sW + tp * C * C + i;
+                for (int j = 0; j <= o; ++j)
+                    s += li[j] * wt[j * C];
+            }
+            sCf[idx] = s;
+        }
+    }
+    __syncthreads();
+}
+
 // The same preparation for many channels, where a second k*k*C*C staging buffer would not fit LDS: the
 // kernel entries are read from global memory where they are used (every entry C times, from L2).
 // Outputs sL, sLinv (C*C each) and sCf (k*k*C*C) as above.  Ends with a barrier.
