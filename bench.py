@@ -462,6 +462,7 @@ SCALE_SHAPES = {  # (B, C, H, W, k): the paper's image-size / batch-size / kerne
     # a 3x32x32 input after one and two squeezes at the paper's batch size, and the kernel-size ablation on the former
     "b100_c12": (100, 12, 16, 16, 3), "b100_c48": (100, 48, 8, 8, 3), "b100_c12_k2": (100, 12, 16, 16, 2),
     "b100_c12_k5": (100, 12, 16, 16, 5), "b100_c12_k7": (100, 12, 16, 16, 7),
+    "b100_c12_k9": (100, 12, 16, 16, 9), "b100_c12_k11": (100, 12, 16, 16, 11),
     "b1024_c12": (1024, 12, 16, 16, 3),
 }
 
