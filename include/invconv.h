@@ -108,9 +108,11 @@ invconv_status invconv_fwd_logdet(const float *y, const float *w, float *x, floa
  * 64 rows are then cut into bands of 64 rows that run on different compute units and hand their
  * boundary messages over through the workspace (Section 3.3 only needs the pixels of an anti-diagonal
  * to be independent; a band trails the one above by a fixed number of steps); invconv_fwd, which has
- * nowhere to put those messages, keeps all bands of an image in one workgroup.  Other shapes run the
- * kernels invconv_fwd runs.  Results agree to rounding (the banded kernels add a pixel's terms in
- * different orders).
+ * nowhere to put those messages, keeps all bands of an image in one workgroup.  Images of 20 to 48
+ * channels (multiples of 4) with a kernel size of 2, 5, 7, 9 or 11 keep the folded weights of the call
+ * in the workspace and stream them to the matrix cores (invconv_fwd solves those one anti-diagonal per
+ * launch, 15 to 30 times slower).  Other shapes run the kernels invconv_fwd runs.  Results agree to
+ * rounding (the kernels add a pixel's terms in different orders).
  *   workspace [scratch] at least invconv_fwd_workspace_bytes() bytes (never 0 for a valid shape).
  */
 invconv_status invconv_fwd_ws(const float *y, const float *w, float *x,

@@ -10,6 +10,9 @@ size_t solve_ws_bytes(int B, int C, int H, int W, int k)
     // only the few-channel images of more than 64 rows have a kernel that spreads one image over workgroups
     if (!wave_supported(C, H, k) && wave_bands_supported(C, H, W, k))
         return wave_bands_ws_bytes(B, C, H, W, k);
+    // many channels with a kernel size other than 3: the folded weights of the call
+    if (wide_stream_supported(C, H, k))
+        return wide_stream_ws_bytes(C, k);
     return 0;
 }
 
@@ -132,6 +135,8 @@ int solve_variant(int dir, const float *in, const float *w, float *out, int B, i
         }
         if (wide_supported(C, H, k))
             return launch_solve_wide(dir, in, w, out, B, C, H, W, k, stream);
+        if (wide_stream_supported(C, H, k) && ws.base && ws.bytes >= wide_stream_ws_bytes(C, k))
+            return launch_solve_wide_stream(dir, in, w, out, B, C, H, W, k, stream, reinterpret_cast<float *>(ws.base));
         if (check_supported(C, H, k) == INVCONV_OK)
             return launch_solve_block(dir, in, w, out, B, C, H, W, k, stream);
         // nothing on chip holds this shape (more than 48 channels, or a window that outgrows LDS): one launch per

@@ -68,6 +68,12 @@ int launch_flow_fwd_band(const float *y, const float *w, const float *s, const f
 bool wide_supported(int C, int H, int k);
 int launch_solve_wide(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
                       hipStream_t stream, float *logdet = nullptr);
+// many channels (20 .. 48, multiples of 4) with k = 2, 5, 7, 9, 11: the same solve with its folded weights streamed from
+// `gw`, wide_stream_ws_bytes(C, k) bytes of device scratch that a set-up launch of the same call fills
+bool wide_stream_supported(int C, int H, int k);
+size_t wide_stream_ws_bytes(int C, int k);
+int launch_solve_wide_stream(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                             hipStream_t stream, float *gw);
 bool bwd_wave_supported(int C, int H, int W, int k);
 bool bwd_wave_fused_pays(int B, int C, int H, int W, int k);   // false: solve and weight gradient as separate launches
 // one flow step's forward pass (y in, z out, log-determinant of the step on the side) on the split solve, no set-up launch

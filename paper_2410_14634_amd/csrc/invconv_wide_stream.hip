@@ -1,0 +1,270 @@
+// Wavefront solve for many channels (C = 20 .. 48, a multiple of 4) with the OTHER kernel sizes of the paper's
+// kernel-size ablation (k = 2, 5, 7, 9, 11): the shapes its model reaches after two squeezes (Section 4.1) when
+// the kernel is not 3 x 3.  gfx950 only.
+//
+// Same scheme as the 3 x 3 many-channel kernel: folded weights (Linv = inverse of the current-pixel block,
+// Cf_tap = Linv W_tap, so x_p = Linv y_p - sum_tap Cf_tap x_{p - tap}: Eq. 1 rearranged), one workgroup per image,
+// wave (band, ob) owns rows 16 band .. and output channels 16 ob .., all rows in lock step, the results of the
+// last 2k - 1 steps in an LDS ring, one tap = C/4 v_mfma_f32_16x16x4_f32 with a weight tile as A operand and the
+// ring as B operand, one LDS-only barrier per step.
+// What differs: k^2 C^2 folded weights (230 KB at 48 channels and k = 5, 1.1 MB at k = 11) fit neither LDS nor
+// a workgroup's registers, so a set-up launch folds them ONCE per call into the caller's workspace, laid out as the
+// waves read them - 64 consecutive floats per (tap, block of output channels, group of four input channels) - and
+// every wave streams its A operands from there (L2 hits after the first workgroup), one row of taps ahead of the
+// matrix instructions that use them.  Without a workspace these shapes keep the per-diagonal fallback.
+#include "invconv_common.h"
+#include "invconv_launch.h"
+
+namespace invconv {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+__host__ __device__ constexpr int ws_out_blocks(int C) { return (C + 15) / 16; }
+
+// gw[((tp OB + ob) CQ + c4) 64 + lane] = A operand of lane (n, g) = (lane % 16, lane / 16): entry
+// [16 ob + n][4 c4 + g] of Linv (tp = 0) or of -Linv W_tp; rows past C are zeros.  One workgroup per tap.
+template <int DIR>
+__global__ __launch_bounds__(256) void k_wide_fold_stream(const float *__restrict__ w, float *__restrict__ gw, int C,
+                                                         int K)
+{
+    extern __shared__ float fs[];
+    float *sL = fs, *sLinv = sL + C * C, *sT = sLinv + C * C;
+    const int tid = threadIdx.x, tp = blockIdx.x;
+    auto entry = [&](int t, int o, int i) -> float {       // oriented, masked entry (t, o, i)
+        const int a = K - 1 - t / K, b = K - 1 - t % K;
+        const int oo = DIR ? C - 1 - i : o, ii = DIR ? C - 1 - o : i;
+        const float v = w[((oo * C + ii) * K + a) * K + b];
+        return (t == 0 && ii > oo) ? 0.0f : v;
+    };
+    for (int idx = tid; idx < C * C; idx += 256) {
+        sL[idx] = entry(0, idx / C, idx % C);
+        sT[idx] = tp ? entry(tp, idx / C, idx % C) : 0.0f;
+    }
+    __syncthreads();
+    if (tid < C) {      // column j of Linv by forward substitution
+        const int j = tid;
+        for (int o = 0; o < j; ++o)
+            sLinv[o * C + j] = 0.0f;
+        sLinv[j * C + j] = 1.0f / sL[j * C + j];
+        for (int o = j + 1; o < C; ++o) {
+            float s = 0.0f;
+            for (int m = j; m < o; ++m)
+                s += sL[o * C + m] * sLinv[m * C + j];
+            sLinv[o * C + j] = -s / sL[o * C + o];
+        }
+    }
+    __syncthreads();
+    const int OB = ws_out_blocks(C), CQ = C / 4;
+    float *dst = gw + (size_t)tp * OB * CQ * 64;
+    for (int idx = tid; idx < OB * CQ * 64; idx += 256) {
+        const int lane = idx & 63, c4 = (idx >> 6) % CQ, ob = (idx >> 6) / CQ;
+        const int o = 16 * ob + (lane & 15), i = 4 * c4 + (lane >> 4);
+        float val = 0.0f;
+        if (o < C) {
+            if (tp == 0) {
+                val = sLinv[o * C + i];
+            } else {
+                float s = 0.0f;
+                for (int j = 0; j <= o; ++j)
+                    s += sLinv[o * C + j] * sT[j * C + i];
+                val = -s;
+            }
+        }
+        dst[idx] = val;
+    }
+}
+
+// Taps are taken in groups of D whose A operands sit in registers one group ahead: a row of taps (D = K, group =
+// da, member = db) for k >= 5, all four taps for k = 2.
+template <int K>
+__host__ __device__ constexpr int ws_group() { return K == 2 ? 4 : K; }
+
+template <int CQ, int K, int DIR>
+__global__ __launch_bounds__(256) void k_solve_wide_stream(const float *__restrict__ in, const float *__restrict__ gw,
+                                                          float *__restrict__ out, int H, int W, int NB)
+{
+    constexpr int C = 4 * CQ, NT = K * K, R = 2 * K - 1, D = ws_group<K>(), G = NT / D;
+    constexpr int OB = ws_out_blocks(C), CPAD = C + 1;
+    static_assert(NT % D == 0, "whole groups of taps");
+    extern __shared__ float smem[];
+    const int HP = 16 * NB + K - 1;
+    float *ring = smem;                         // [R][HP][CPAD]: x of the last R steps, K - 1 rows of zeros on top
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int band = wave / OB, ob = wave % OB;
+    const int n = lane & 15, g = lane >> 4;
+    for (int idx = tid; idx < R * HP * CPAD; idx += nt)
+        ring[idx] = 0.0f;
+
+    const int r = 16 * band + n;
+    const bool row_ok = r < H;
+    const size_t img = (size_t)blockIdx.x * C * H * W;
+    const int b_row = (r + K - 1) * CPAD + g;                    // + slot * HP * CPAD - da * CPAD + 4 c4
+    const int o_first = 16 * ob + 4 * g;                         // first of this lane's four output channels
+    auto gaddr = [&](int ch, int rr, int cc) -> size_t {
+        return img + ((size_t)(DIR ? C - 1 - ch : ch) * H + (DIR ? H - 1 - rr : rr)) * W + (DIR ? W - 1 - cc : cc);
+    };
+    auto load_y = [&](int t, float (&yv)[CQ]) {
+        const int c = t - r;
+        const bool ok = row_ok && (unsigned)c < (unsigned)W;
+        const int rr = row_ok ? r : 0, cc = ok ? c : 0;
+#pragma unroll
+        for (int c4 = 0; c4 < CQ; ++c4) {
+            const float v = in[gaddr(4 * c4 + g, rr, cc)];
+            yv[c4] = ok ? v : 0.0f;
+        }
+    };
+    // this wave's A operands: group grp, member u, input-channel group c4 at wbase[((grp D + u) OB CQ + c4) 64]
+    const float *wbase = gw + (size_t)ob * CQ * 64 + lane;
+    constexpr int kTapStride = OB * CQ * 64;
+    float aw[D][CQ];
+    auto fetch_group = [&](int grp) {
+#pragma unroll
+        for (int u = 0; u < D; ++u)
+#pragma unroll
+            for (int c4 = 0; c4 < CQ; ++c4)
+                aw[u][c4] = wbase[(size_t)(grp * D + u) * kTapStride + c4 * 64];
+    };
+    fetch_group(0);
+    float ycur[CQ], ynext[CQ];
+    load_y(0, ycur);
+    __syncthreads();        // ring zeroed
+
+    const int nsteps = H + W - 1;
+    int tm = 0;                                                 // t mod R
+    for (int t = 0; t < nsteps; ++t) {
+        load_y(t + 1, ynext);                                   // one step ahead (past the last step: zeros)
+        f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int grp = 0; grp < G; ++grp) {
+            const int gnext = grp + 1 == G ? 0 : grp + 1;       // (the last group fetches the first one of the next step)
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                const int da = D == K ? grp : u / K, db = D == K ? u : u % K, lag = da + db;
+                int slot = tm - lag;
+                slot += slot < 0 ? R : 0;
+                const float *bp = ring + slot * HP * CPAD + b_row - da * CPAD;
+                const bool first = lag == 0;                    // tap 0: Linv y
+                float opb[CQ];
+#pragma unroll
+                for (int c4 = 0; c4 < CQ; ++c4) {
+                    const float xv = bp[4 * c4];
+                    opb[c4] = first ? ycur[c4] : xv;
+                }
+#pragma unroll
+                for (int c4 = 0; c4 < CQ; ++c4) {
+                    if (c4 & 1)
+                        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw[u][c4], opb[c4], acc1, 0, 0, 0);
+                    else
+                        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw[u][c4], opb[c4], acc0, 0, 0, 0);
+                }
+                // the same member of the next group takes the registers just used
+#pragma unroll
+                for (int c4 = 0; c4 < CQ; ++c4)
+                    aw[u][c4] = wbase[(size_t)(gnext * D + u) * kTapStride + c4 * 64];
+            }
+        }
+        const f32x4 acc = acc0 + acc1;
+#pragma unroll
+        for (int c4 = 0; c4 < CQ; ++c4)
+            ycur[c4] = ynext[c4];
+        const int c = t - r;
+        const bool ok = row_ok && (unsigned)c < (unsigned)W;
+        float *rp = ring + tm * HP * CPAD + (r + K - 1) * CPAD + o_first;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (o_first + j < C) {
+                rp[j] = ok ? acc[j] : 0.0f;                     // pixels outside the image count as zeros
+                if (ok)
+                    out[gaddr(o_first + j, r, c)] = acc[j];
+            }
+        }
+        tm = tm + 1 == R ? 0 : tm + 1;
+        // workgroup barrier that orders LDS only: the global stores and the weight fetches stay in flight across it
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    }
+}
+
+size_t ws_ring_bytes(int C, int H, int k)
+{
+    const size_t NB = (H + 15) / 16;
+    return sizeof(float) * (size_t)(2 * k - 1) * (16 * NB + k - 1) * (C + 1);
+}
+
+template <int CQ, int K>
+int launch_stream_ck(int dir, const float *in, const float *gw, float *out, int B, int H, int W, hipStream_t stream)
+{
+    const int NB = (H + 15) / 16;
+    const size_t lds = ws_ring_bytes(4 * CQ, H, K);
+    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide_stream<CQ, K, 1>)
+                         : reinterpret_cast<const void *>(&k_solve_wide_stream<CQ, K, 0>);
+    if (!ensure_dynamic_lds(fn, lds))
+        return INVCONV_ERR_UNSUPPORTED;
+    const dim3 block((unsigned)(64 * NB * ws_out_blocks(4 * CQ)));
+    if (dir)
+        hipLaunchKernelGGL((k_solve_wide_stream<CQ, K, 1>), dim3(B), block, lds, stream, in, gw, out, H, W, NB);
+    else
+        hipLaunchKernelGGL((k_solve_wide_stream<CQ, K, 0>), dim3(B), block, lds, stream, in, gw, out, H, W, NB);
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+template <int CQ>
+int launch_stream_cq(int dir, const float *in, const float *gw, float *out, int B, int H, int W, int k,
+                     hipStream_t stream)
+{
+    switch (k) {
+    case 2: return launch_stream_ck<CQ, 2>(dir, in, gw, out, B, H, W, stream);
+    case 5: return launch_stream_ck<CQ, 5>(dir, in, gw, out, B, H, W, stream);
+    case 7: return launch_stream_ck<CQ, 7>(dir, in, gw, out, B, H, W, stream);
+    case 9: return launch_stream_ck<CQ, 9>(dir, in, gw, out, B, H, W, stream);
+    case 11: return launch_stream_ck<CQ, 11>(dir, in, gw, out, B, H, W, stream);
+    default: return INVCONV_ERR_VARIANT;
+    }
+}
+
+}  // namespace
+
+// at most four waves (bands x blocks of 16 output channels), the ring in LDS
+bool wide_stream_supported(int C, int H, int k)
+{
+    const bool kk = k == 2 || k == 5 || k == 7 || k == 9 || k == 11;
+    return kk && C % 4 == 0 && C >= 20 && C <= 48 && ((H + 15) / 16) * ws_out_blocks(C) <= 4 &&
+           ws_ring_bytes(C, H, k) <= kMaxLdsBytes;
+}
+
+// bytes of workspace the folded weights take
+size_t wide_stream_ws_bytes(int C, int k)
+{
+    return sizeof(float) * (size_t)k * k * ws_out_blocks(C) * (C / 4) * 64;
+}
+
+// `gw`: wide_stream_ws_bytes(C, k) bytes of device scratch, 256-byte aligned
+int launch_solve_wide_stream(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                             hipStream_t stream, float *gw)
+{
+    if (!wide_stream_supported(C, H, k) || !gw)
+        return INVCONV_ERR_VARIANT;
+    const size_t flds = sizeof(float) * 3 * (size_t)C * C;
+    if (dir)
+        hipLaunchKernelGGL(k_wide_fold_stream<1>, dim3(k * k), dim3(256), flds, stream, w, gw, C, k);
+    else
+        hipLaunchKernelGGL(k_wide_fold_stream<0>, dim3(k * k), dim3(256), flds, stream, w, gw, C, k);
+    if (hipGetLastError() != hipSuccess)
+        return INVCONV_ERR_LAUNCH;
+    switch (C / 4) {
+    case 5: return launch_stream_cq<5>(dir, in, gw, out, B, H, W, k, stream);
+    case 6: return launch_stream_cq<6>(dir, in, gw, out, B, H, W, k, stream);
+    case 7: return launch_stream_cq<7>(dir, in, gw, out, B, H, W, k, stream);
+    case 8: return launch_stream_cq<8>(dir, in, gw, out, B, H, W, k, stream);
+    case 9: return launch_stream_cq<9>(dir, in, gw, out, B, H, W, k, stream);
+    case 10: return launch_stream_cq<10>(dir, in, gw, out, B, H, W, k, stream);
+    case 11: return launch_stream_cq<11>(dir, in, gw, out, B, H, W, k, stream);
+    case 12: return launch_stream_cq<12>(dir, in, gw, out, B, H, W, k, stream);
+    default: return INVCONV_ERR_VARIANT;
+    }
+}
+
+}  // namespace invconv

@@ -180,6 +180,38 @@ TALL_SHAPES = [(2, 3, 256, 160, 3), (1, 3, 512, 512, 3), (5, 2, 257, 129, 3), (2
                (1, 3, 129, 256, 3), (70, 3, 256, 128, 3)]
 
 
+WIDE_K_SHAPES = [  # (B, C, H, W, k): many channels with the other kernel sizes of the kernel-size ablation
+    (2, 48, 8, 8, 5), (2, 48, 8, 8, 2), (1, 48, 6, 5, 7), (1, 48, 4, 4, 11), (2, 24, 20, 12, 5), (1, 32, 32, 9, 2),
+    (2, 20, 16, 16, 9), (1, 40, 9, 30, 7), (3, 28, 1, 1, 5), (1, 36, 13, 17, 11), (101, 48, 8, 8, 9),
+]
+
+
+@pytest.mark.parametrize("shape", WIDE_K_SHAPES)
+def test_many_channels_other_kernel_sizes_with_workspace(shape):
+    """With a workspace the folded weights of the call are streamed from it (one workgroup per image on the matrix
+    cores); without one the same shapes take the per-diagonal fallback.  Both against the oracle."""
+    import torch
+    B, C, H, W, k = shape
+    print(f"many channels, k != 3: {shape}", flush=True)
+    cs = inputs.make_case(B, C, H, W, k, seed=sum(shape) + 11, tap_std=0.15 / k)
+    yd, wd, gd = dev(cs["y"]), dev(cs["w"][0]), dev(cs["g"])
+    assert b.fwd_workspace_bytes(B, C, H, W, k) > 256
+    wsf = b.new_workspace(b.fwd_workspace_bytes(B, C, H, W, k))
+    wsb = b.new_workspace(b.bwd_workspace_bytes(B, C, H, W, k))
+    x = b.invconv_fwd(yd, wd, workspace=wsf)
+    v, dw = b.invconv_bwd(x, wd, gd, workspace=wsb)
+    torch.cuda.synchronize()
+    xh = host(x)
+    xr = oracle.invconv_fwd(cs["y"], cs["w"][0], THREADS)
+    vr, dwr = oracle.invconv_bwd(xh, cs["w"][0], cs["g"], THREADS)
+    assert rel_err(xh, xr) <= TOL_ACT and elementwise_ok(xh, xr, TOL_ACT)
+    assert rel_err(host(v), vr) <= TOL_ACT and rel_err(host(dw), dwr) <= TOL_DW
+    if B <= 3:
+        x_plain = b.invconv_fwd(yd, wd)
+        torch.cuda.synchronize()
+        assert rel_err(host(x_plain), xr) <= TOL_ACT
+
+
 @pytest.mark.parametrize("shape", TALL_SHAPES)
 def test_tall_images_with_and_without_workspace_agree(shape):
     """invconv_fwd_ws / invconv_bwd spread the bands of an image over workgroups (logs in the caller's
