@@ -23,13 +23,17 @@ namespace {
 
 __host__ __device__ constexpr int ws_out_blocks(int C) { return (C + 15) / 16; }
 
-// gw[((tp OB + ob) CQ + c4) 64 + lane] = A operand of lane (n, g) = (lane % 16, lane / 16): entry
-// [16 ob + n][4 c4 + g] of Linv (tp = 0) or of -Linv W_tp; rows past C are zeros.  One workgroup per tap.
-template <int DIR>
-__global__ __launch_bounds__(256) void k_wide_fold_stream(const float *__restrict__ w, float *__restrict__ gw, int C,
-                                                         int K)
+// A lane fetches VW = 4, 2 or 1 consecutive A operands (input-channel groups c4 = VW q .. VW q + VW - 1) with one
+// load: few, wide loads keep the number of fetches in flight below what a wave may have outstanding.
+__host__ __device__ constexpr int ws_vec(int CQ) { return CQ % 4 == 0 ? 4 : (CQ % 2 == 0 ? 2 : 1); }
+
+// gw[(((tp OB + ob) CQ/VW + q) 64 + lane) VW + e] = A operand of lane (n, g) = (lane % 16, lane / 16) for c4 = VW q + e:
+// entry [16 ob + n][4 c4 + g] of Linv (tp = 0) or of -Linv W_tp; rows past C are zeros.  One workgroup per tap.
+template <int CQ, int DIR>
+__global__ __launch_bounds__(256) void k_wide_fold_stream(const float *__restrict__ w, float *__restrict__ gw, int K)
 {
-    extern __shared__ float fs[];
+    constexpr int C = 4 * CQ;
+    extern __shared__ __attribute__((aligned(16))) float fs[];
     float *sL = fs, *sLinv = sL + C * C, *sT = sLinv + C * C;
     const int tid = threadIdx.x, tp = blockIdx.x;
     auto entry = [&](int t, int o, int i) -> float {       // oriented, masked entry (t, o, i)
@@ -43,23 +47,44 @@ __global__ __launch_bounds__(256) void k_wide_fold_stream(const float *__restric
         sT[idx] = tp ? entry(tp, idx / C, idx % C) : 0.0f;
     }
     __syncthreads();
-    if (tid < C) {      // column j of Linv by forward substitution
-        const int j = tid;
-        for (int o = 0; o < j; ++o)
-            sLinv[o * C + j] = 0.0f;
-        sLinv[j * C + j] = 1.0f / sL[j * C + j];
-        for (int o = j + 1; o < C; ++o) {
-            float s = 0.0f;
-            for (int m = j; m < o; ++m)
-                s += sL[o * C + m] * sLinv[m * C + j];
-            sLinv[o * C + j] = -s / sL[o * C + o];
+    // Column j of Linv by thread j with the column in registers: every thread runs the same fully unrolled forward
+    // substitution (entries above the diagonal are zeros that take part in the sums), the rows of L come in as
+    // 16-byte reads of addresses common to all lanes, four partial sums per row.
+    if (tid < 64) {
+        const int j = tid < C ? tid : C - 1;
+        float col[C];
+#pragma unroll
+        for (int o = 0; o < C; ++o) {
+            float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            float diag = 1.0f;
+#pragma unroll
+            for (int m4 = 0; m4 <= o / 4; ++m4) {
+                const f32x4 row = *reinterpret_cast<const f32x4 *>(sL + o * C + 4 * m4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (4 * m4 + e < o)
+                        part[e] += row[e] * col[4 * m4 + e];
+                    else if (4 * m4 + e == o)
+                        diag = row[e];
+                }
+            }
+            const float sum = (part[0] + part[1]) + (part[2] + part[3]);
+            const float rd = 1.0f / diag;
+            col[o] = o < j ? 0.0f : (o == j ? rd : -sum * rd);
+        }
+        if (tid < C) {
+#pragma unroll
+            for (int o = 0; o < C; ++o)
+                sLinv[o * C + j] = col[o];
         }
     }
     __syncthreads();
-    const int OB = ws_out_blocks(C), CQ = C / 4;
+    constexpr int OB = ws_out_blocks(C);
     float *dst = gw + (size_t)tp * OB * CQ * 64;
+    constexpr int VW = ws_vec(CQ);
     for (int idx = tid; idx < OB * CQ * 64; idx += 256) {
-        const int lane = idx & 63, c4 = (idx >> 6) % CQ, ob = (idx >> 6) / CQ;
+        const int e = idx % VW, lane = (idx / VW) & 63, q = (idx / (VW * 64)) % (CQ / VW), ob = idx / (CQ * 64);
+        const int c4 = VW * q + e;
         const int o = 16 * ob + (lane & 15), i = 4 * c4 + (lane >> 4);
         float val = 0.0f;
         if (o < C) {
@@ -116,18 +141,24 @@ __global__ __launch_bounds__(256) void k_solve_wide_stream(const float *__restri
             yv[c4] = ok ? v : 0.0f;
         }
     };
-    // this wave's A operands: group grp, member u, input-channel group c4 at wbase[((grp D + u) OB CQ + c4) 64]
-    const float *wbase = gw + (size_t)ob * CQ * 64 + lane;
+    // this wave's A operands of tap tp: VW consecutive floats per lane and load at wbase[tp kTapStride + q 64 VW]
+    constexpr int VW = ws_vec(CQ);
+    typedef float wvec_t __attribute__((ext_vector_type(VW)));
+    const float *wbase = gw + (size_t)ob * CQ * 64 + lane * VW;
     constexpr int kTapStride = OB * CQ * 64;
     float aw[D][CQ];
-    auto fetch_group = [&](int grp) {
+    auto fetch_tap = [&](int tp, float (&dst)[CQ]) {
 #pragma unroll
-        for (int u = 0; u < D; ++u)
+        for (int q = 0; q < CQ / VW; ++q) {
+            const wvec_t v = *reinterpret_cast<const wvec_t *>(wbase + (size_t)tp * kTapStride + q * 64 * VW);
 #pragma unroll
-            for (int c4 = 0; c4 < CQ; ++c4)
-                aw[u][c4] = wbase[(size_t)(grp * D + u) * kTapStride + c4 * 64];
+            for (int e = 0; e < VW; ++e)
+                dst[VW * q + e] = v[e];
+        }
     };
-    fetch_group(0);
+#pragma unroll
+    for (int u = 0; u < D; ++u)
+        fetch_tap(u, aw[u]);
     float ycur[CQ], ynext[CQ];
     load_y(0, ycur);
     __syncthreads();        // ring zeroed
@@ -137,32 +168,45 @@ __global__ __launch_bounds__(256) void k_solve_wide_stream(const float *__restri
     for (int t = 0; t < nsteps; ++t) {
         load_y(t + 1, ynext);                                   // one step ahead (past the last step: zeros)
         f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+        // B operands of tap (grp, u): the ring slot of lag da + db, da rows up (tap 0: the input y of the step)
+        auto read_b = [&](int grp, int u, float (&o)[CQ]) {
+            const int da = D == K ? grp : u / K, db = D == K ? u : u % K, lag = da + db;
+            int slot = tm - lag;
+            slot += slot < 0 ? R : 0;
+            const float *bp = ring + slot * HP * CPAD + b_row - da * CPAD;
+            const bool first = lag == 0;
+#pragma unroll
+            for (int c4 = 0; c4 < CQ; ++c4) {
+                const float xv = bp[4 * c4];
+                o[c4] = first ? ycur[c4] : xv;
+            }
+        };
+        // The operands of the NEXT tap are read from LDS while the matrix cores work on the current one
+        float opc[CQ], opn[CQ];
+        read_b(0, 0, opc);
+#pragma unroll 1
         for (int grp = 0; grp < G; ++grp) {
             const int gnext = grp + 1 == G ? 0 : grp + 1;       // (the last group fetches the first one of the next step)
 #pragma unroll
             for (int u = 0; u < D; ++u) {
-                const int da = D == K ? grp : u / K, db = D == K ? u : u % K, lag = da + db;
-                int slot = tm - lag;
-                slot += slot < 0 ? R : 0;
-                const float *bp = ring + slot * HP * CPAD + b_row - da * CPAD;
-                const bool first = lag == 0;                    // tap 0: Linv y
-                float opb[CQ];
-#pragma unroll
-                for (int c4 = 0; c4 < CQ; ++c4) {
-                    const float xv = bp[4 * c4];
-                    opb[c4] = first ? ycur[c4] : xv;
-                }
+                if (u + 1 < D)
+                    read_b(grp, u + 1, opn);
+                else
+                    read_b(gnext, 0, opn);      // (after the last tap of the step: read and dropped)
+                __builtin_amdgcn_sched_barrier(0);      // keep the reads above ahead of the products below
 #pragma unroll
                 for (int c4 = 0; c4 < CQ; ++c4) {
                     if (c4 & 1)
-                        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw[u][c4], opb[c4], acc1, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw[u][c4], opc[c4], acc1, 0, 0, 0);
                     else
-                        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw[u][c4], opb[c4], acc0, 0, 0, 0);
+                        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw[u][c4], opc[c4], acc0, 0, 0, 0);
                 }
                 // the same member of the next group takes the registers just used
+                fetch_tap(gnext * D + u, aw[u]);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int c4 = 0; c4 < CQ; ++c4)
-                    aw[u][c4] = wbase[(size_t)(gnext * D + u) * kTapStride + c4 * 64];
+                    opc[c4] = opn[c4];
             }
         }
         const f32x4 acc = acc0 + acc1;
@@ -212,9 +256,16 @@ int launch_stream_ck(int dir, const float *in, const float *gw, float *out, int 
 }
 
 template <int CQ>
-int launch_stream_cq(int dir, const float *in, const float *gw, float *out, int B, int H, int W, int k,
+int launch_stream_cq(int dir, const float *in, const float *w, float *gw, float *out, int B, int H, int W, int k,
                      hipStream_t stream)
 {
+    const size_t flds = sizeof(float) * 3 * (size_t)(4 * CQ) * (4 * CQ);
+    if (dir)
+        hipLaunchKernelGGL((k_wide_fold_stream<CQ, 1>), dim3(k * k), dim3(256), flds, stream, w, gw, k);
+    else
+        hipLaunchKernelGGL((k_wide_fold_stream<CQ, 0>), dim3(k * k), dim3(256), flds, stream, w, gw, k);
+    if (hipGetLastError() != hipSuccess)
+        return INVCONV_ERR_LAUNCH;
     switch (k) {
     case 2: return launch_stream_ck<CQ, 2>(dir, in, gw, out, B, H, W, stream);
     case 5: return launch_stream_ck<CQ, 5>(dir, in, gw, out, B, H, W, stream);
@@ -247,22 +298,15 @@ int launch_solve_wide_stream(int dir, const float *in, const float *w, float *ou
 {
     if (!wide_stream_supported(C, H, k) || !gw)
         return INVCONV_ERR_VARIANT;
-    const size_t flds = sizeof(float) * 3 * (size_t)C * C;
-    if (dir)
-        hipLaunchKernelGGL(k_wide_fold_stream<1>, dim3(k * k), dim3(256), flds, stream, w, gw, C, k);
-    else
-        hipLaunchKernelGGL(k_wide_fold_stream<0>, dim3(k * k), dim3(256), flds, stream, w, gw, C, k);
-    if (hipGetLastError() != hipSuccess)
-        return INVCONV_ERR_LAUNCH;
     switch (C / 4) {
-    case 5: return launch_stream_cq<5>(dir, in, gw, out, B, H, W, k, stream);
-    case 6: return launch_stream_cq<6>(dir, in, gw, out, B, H, W, k, stream);
-    case 7: return launch_stream_cq<7>(dir, in, gw, out, B, H, W, k, stream);
-    case 8: return launch_stream_cq<8>(dir, in, gw, out, B, H, W, k, stream);
-    case 9: return launch_stream_cq<9>(dir, in, gw, out, B, H, W, k, stream);
-    case 10: return launch_stream_cq<10>(dir, in, gw, out, B, H, W, k, stream);
-    case 11: return launch_stream_cq<11>(dir, in, gw, out, B, H, W, k, stream);
-    case 12: return launch_stream_cq<12>(dir, in, gw, out, B, H, W, k, stream);
+    case 5: return launch_stream_cq<5>(dir, in, w, gw, out, B, H, W, k, stream);
+    case 6: return launch_stream_cq<6>(dir, in, w, gw, out, B, H, W, k, stream);
+    case 7: return launch_stream_cq<7>(dir, in, w, gw, out, B, H, W, k, stream);
+    case 8: return launch_stream_cq<8>(dir, in, w, gw, out, B, H, W, k, stream);
+    case 9: return launch_stream_cq<9>(dir, in, w, gw, out, B, H, W, k, stream);
+    case 10: return launch_stream_cq<10>(dir, in, w, gw, out, B, H, W, k, stream);
+    case 11: return launch_stream_cq<11>(dir, in, w, gw, out, B, H, W, k, stream);
+    case 12: return launch_stream_cq<12>(dir, in, w, gw, out, B, H, W, k, stream);
     default: return INVCONV_ERR_VARIANT;
     }
 }
