@@ -459,10 +459,12 @@ SCALE_SHAPES = {  # (B, C, H, W, k): the paper's image-size / batch-size / kerne
     "k2": (16, 3, 32, 32, 2), "k5": (16, 3, 32, 32, 5), "k7": (16, 3, 32, 32, 7), "k9": (16, 3, 32, 32, 9),
     "k11": (16, 3, 32, 32, 11), "mnist_like": (128, 1, 28, 28, 3),
     "c48_two_squeezes": (32, 48, 32, 32, 3), "c24": (32, 24, 64, 64, 3), "c32": (64, 32, 32, 32, 3),
-    # a 3x32x32 input after one and two squeezes at the paper's batch size, and the kernel-size ablation on the former
+    # a 3x32x32 input after one and two squeezes at the paper's batch size, and the kernel-size ablation on both
     "b100_c12": (100, 12, 16, 16, 3), "b100_c48": (100, 48, 8, 8, 3), "b100_c12_k2": (100, 12, 16, 16, 2),
     "b100_c12_k5": (100, 12, 16, 16, 5), "b100_c12_k7": (100, 12, 16, 16, 7),
     "b100_c12_k9": (100, 12, 16, 16, 9), "b100_c12_k11": (100, 12, 16, 16, 11),
+    "b100_c48_k2": (100, 48, 8, 8, 2), "b100_c48_k5": (100, 48, 8, 8, 5), "b100_c48_k7": (100, 48, 8, 8, 7),
+    "b100_c48_k9": (100, 48, 8, 8, 9), "b100_c48_k11": (100, 48, 8, 8, 11),
     "b1024_c12": (1024, 12, 16, 16, 3),
 }
 
