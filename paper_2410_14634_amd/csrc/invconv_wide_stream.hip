@@ -30,7 +30,7 @@ __host__ __device__ constexpr int ws_vec(int CQ) { return CQ % 4 == 0 ? 4 : (CQ 
 // gw[(((tp OB + ob) CQ/VW + q) 64 + lane) VW + e] = A operand of lane (n, g) = (lane % 16, lane / 16) for c4 = VW q + e:
 // entry [16 ob + n][4 c4 + g] of Linv (tp = 0) or of -Linv W_tp; rows past C are zeros.  One workgroup per tap.
 template <int CQ, int DIR>
-__global__ __launch_bounds__(256) void k_wide_fold_stream(const float *__restrict__ w, float *__restrict__ gw, int K)
+__global__ __launch_bounds__(1024) void k_wide_fold_stream(const float *__restrict__ w, float *__restrict__ gw, int K)
 {
     constexpr int C = 4 * CQ;
     extern __shared__ __attribute__((aligned(16))) float fs[];
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void k_wide_fold_stream(const float *__restric
         const float v = w[((oo * C + ii) * K + a) * K + b];
         return (t == 0 && ii > oo) ? 0.0f : v;
     };
-    for (int idx = tid; idx < C * C; idx += 256) {
+    for (int idx = tid; idx < C * C; idx += 1024) {
         sL[idx] = entry(0, idx / C, idx % C);
         sT[idx] = tp ? entry(tp, idx / C, idx % C) : 0.0f;
     }
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void k_wide_fold_stream(const float *__restric
     constexpr int OB = ws_out_blocks(C);
     float *dst = gw + (size_t)tp * OB * CQ * 64;
     constexpr int VW = ws_vec(CQ);
-    for (int idx = tid; idx < OB * CQ * 64; idx += 256) {
+    for (int idx = tid; idx < OB * CQ * 64; idx += 1024) {
         const int e = idx % VW, lane = (idx / VW) & 63, q = (idx / (VW * 64)) % (CQ / VW), ob = idx / (CQ * 64);
         const int c4 = VW * q + e;
         const int o = 16 * ob + (lane & 15), i = 4 * c4 + (lane >> 4);
@@ -108,13 +108,17 @@ __host__ __device__ constexpr int ws_group() { return K == 2 ? 4 : K; }
 
 template <int CQ, int K, int DIR>
 __global__ __launch_bounds__(256) void k_solve_wide_stream(const float *__restrict__ in, const float *__restrict__ gw,
-                                                          float *__restrict__ out, int H, int W, int NB)
+                                                          float *__restrict__ out, int B, int H, int W, int NB,
+                                                          int pack)
 {
     constexpr int C = 4 * CQ, NT = K * K, R = 2 * K - 1, D = ws_group<K>(), G = NT / D;
     constexpr int OB = ws_out_blocks(C), CPAD = C + 1;
     static_assert(NT % D == 0, "whole groups of taps");
     extern __shared__ float smem[];
-    const int HP = 16 * NB + K - 1;
+    // pack (images of at most 8 rows): a workgroup takes TWO images, rows n = 0 .. 7 of the 16 pixel columns of an
+    // instruction are the first image's rows and n = 8 .. 15 the second's (half of every product was padding
+    // otherwise); in the ring each image has its own K - 1 rows of zeros on top.
+    const int HP = 16 * NB + (pack ? 2 : 1) * (K - 1);
     float *ring = smem;                         // [R][HP][CPAD]: x of the last R steps, K - 1 rows of zeros on top
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -123,10 +127,13 @@ __global__ __launch_bounds__(256) void k_solve_wide_stream(const float *__restri
     for (int idx = tid; idx < R * HP * CPAD; idx += nt)
         ring[idx] = 0.0f;
 
-    const int r = 16 * band + n;
-    const bool row_ok = r < H;
-    const size_t img = (size_t)blockIdx.x * C * H * W;
-    const int b_row = (r + K - 1) * CPAD + g;                    // + slot * HP * CPAD - da * CPAD + 4 c4
+    const int second = pack ? n >> 3 : 0;                        // which of the workgroup's images
+    const int r = pack ? (n & 7) : 16 * band + n;                // row in the image
+    const int image = pack ? 2 * (int)blockIdx.x + second : (int)blockIdx.x;
+    const bool row_ok = r < H && image < B;
+    const size_t img = (size_t)(image < B ? image : B - 1) * C * H * W;
+    const int ring_row = (pack ? 8 * second + r : r) + (K - 1) * (1 + second);
+    const int b_row = ring_row * CPAD + g;                       // + slot * HP * CPAD - da * CPAD + 4 c4
     const int o_first = 16 * ob + 4 * g;                         // first of this lane's four output channels
     auto gaddr = [&](int ch, int rr, int cc) -> size_t {
         return img + ((size_t)(DIR ? C - 1 - ch : ch) * H + (DIR ? H - 1 - rr : rr)) * W + (DIR ? W - 1 - cc : cc);
@@ -167,55 +174,70 @@ __global__ __launch_bounds__(256) void k_solve_wide_stream(const float *__restri
     int tm = 0;                                                 // t mod R
     for (int t = 0; t < nsteps; ++t) {
         load_y(t + 1, ynext);                                   // one step ahead (past the last step: zeros)
-        f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
-        // B operands of tap (grp, u): the ring slot of lag da + db, da rows up (tap 0: the input y of the step)
+        // four accumulators in turn: with one wave per SIMD a product that adds to the result of the one before the
+        // last still waits for it (two accumulators measured 52 clocks per instruction instead of 32)
+        f32x4 accs[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            accs[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // B operands of tap (grp, u): the ring slot of lag da + db, da rows up; the first member of a group may be
+        // tap 0, whose operand is the input y of the step (a matrix instruction and the other vector instructions of
+        // ONE wave do not overlap, so what a tap costs beside its products is kept to the reads themselves)
         auto read_b = [&](int grp, int u, float (&o)[CQ]) {
             const int da = D == K ? grp : u / K, db = D == K ? u : u % K, lag = da + db;
             int slot = tm - lag;
             slot += slot < 0 ? R : 0;
             const float *bp = ring + slot * HP * CPAD + b_row - da * CPAD;
-            const bool first = lag == 0;
+            if (u == 0) {
+                const bool first = lag == 0;
 #pragma unroll
-            for (int c4 = 0; c4 < CQ; ++c4) {
-                const float xv = bp[4 * c4];
-                o[c4] = first ? ycur[c4] : xv;
+                for (int c4 = 0; c4 < CQ; ++c4) {
+                    const float xv = bp[4 * c4];
+                    o[c4] = first ? ycur[c4] : xv;
+                }
+            } else {
+#pragma unroll
+                for (int c4 = 0; c4 < CQ; ++c4)
+                    o[c4] = bp[4 * c4];
             }
         };
-        // The operands of the NEXT tap are read from LDS while the matrix cores work on the current one
-        float opc[CQ], opn[CQ];
-        read_b(0, 0, opc);
+        // The operands of the NEXT tap are read from LDS while the matrix cores work on the current one: two
+        // buffers taken in turn; a group of an odd number of taps ends on the buffer the next group starts with,
+        // so its last tap reads ahead into the other one and hands over with one copy per group.
+        float opb[2][CQ];
+        read_b(0, 0, opb[0]);
 #pragma unroll 1
         for (int grp = 0; grp < G; ++grp) {
             const int gnext = grp + 1 == G ? 0 : grp + 1;       // (the last group fetches the first one of the next step)
 #pragma unroll
             for (int u = 0; u < D; ++u) {
-                if (u + 1 < D)
-                    read_b(grp, u + 1, opn);
+                constexpr int kLast = D - 1;
+                if (u < kLast)
+                    read_b(grp, u + 1, opb[(u + 1) & 1]);
                 else
-                    read_b(gnext, 0, opn);      // (after the last tap of the step: read and dropped)
+                    read_b(gnext, 0, opb[(kLast & 1) ^ 1]);     // (after the last tap of the step: read and dropped)
                 __builtin_amdgcn_sched_barrier(0);      // keep the reads above ahead of the products below
 #pragma unroll
-                for (int c4 = 0; c4 < CQ; ++c4) {
-                    if (c4 & 1)
-                        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw[u][c4], opc[c4], acc1, 0, 0, 0);
-                    else
-                        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(aw[u][c4], opc[c4], acc0, 0, 0, 0);
-                }
-                // the same member of the next group takes the registers just used
-                fetch_tap(gnext * D + u, aw[u]);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
                 for (int c4 = 0; c4 < CQ; ++c4)
-                    opc[c4] = opn[c4];
+                    accs[c4 & 3] = __builtin_amdgcn_mfma_f32_16x16x4f32(aw[u][c4], opb[u & 1][c4], accs[c4 & 3], 0, 0, 0);
+                // the same member of the next group takes the registers just used (a single group, k = 2, stays)
+                if constexpr (G > 1)
+                    fetch_tap(gnext * D + u, aw[u]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (u == kLast && ((kLast & 1) ^ 1) != 0) {
+#pragma unroll
+                    for (int c4 = 0; c4 < CQ; ++c4)
+                        opb[0][c4] = opb[1][c4];
+                }
             }
         }
-        const f32x4 acc = acc0 + acc1;
+        const f32x4 acc = (accs[0] + accs[1]) + (accs[2] + accs[3]);
 #pragma unroll
         for (int c4 = 0; c4 < CQ; ++c4)
             ycur[c4] = ynext[c4];
         const int c = t - r;
         const bool ok = row_ok && (unsigned)c < (unsigned)W;
-        float *rp = ring + tm * HP * CPAD + (r + K - 1) * CPAD + o_first;
+        float *rp = ring + tm * HP * CPAD + ring_row * CPAD + o_first;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (o_first + j < C) {
@@ -235,7 +257,7 @@ __global__ __launch_bounds__(256) void k_solve_wide_stream(const float *__restri
 size_t ws_ring_bytes(int C, int H, int k)
 {
     const size_t NB = (H + 15) / 16;
-    return sizeof(float) * (size_t)(2 * k - 1) * (16 * NB + k - 1) * (C + 1);
+    return sizeof(float) * (size_t)(2 * k - 1) * (16 * NB + (H <= 8 ? 2 : 1) * (k - 1)) * (C + 1);
 }
 
 template <int CQ, int K>
@@ -248,10 +270,12 @@ int launch_stream_ck(int dir, const float *in, const float *gw, float *out, int 
     if (!ensure_dynamic_lds(fn, lds))
         return INVCONV_ERR_UNSUPPORTED;
     const dim3 block((unsigned)(64 * NB * ws_out_blocks(4 * CQ)));
+    const int pack = H <= 8 ? 1 : 0;
+    const dim3 grid((unsigned)(pack ? (B + 1) / 2 : B));
     if (dir)
-        hipLaunchKernelGGL((k_solve_wide_stream<CQ, K, 1>), dim3(B), block, lds, stream, in, gw, out, H, W, NB);
+        hipLaunchKernelGGL((k_solve_wide_stream<CQ, K, 1>), grid, block, lds, stream, in, gw, out, B, H, W, NB, pack);
     else
-        hipLaunchKernelGGL((k_solve_wide_stream<CQ, K, 0>), dim3(B), block, lds, stream, in, gw, out, H, W, NB);
+        hipLaunchKernelGGL((k_solve_wide_stream<CQ, K, 0>), grid, block, lds, stream, in, gw, out, B, H, W, NB, pack);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
@@ -261,9 +285,9 @@ int launch_stream_cq(int dir, const float *in, const float *w, float *gw, float 
 {
     const size_t flds = sizeof(float) * 3 * (size_t)(4 * CQ) * (4 * CQ);
     if (dir)
-        hipLaunchKernelGGL((k_wide_fold_stream<CQ, 1>), dim3(k * k), dim3(256), flds, stream, w, gw, k);
+        hipLaunchKernelGGL((k_wide_fold_stream<CQ, 1>), dim3(k * k), dim3(1024), flds, stream, w, gw, k);
     else
-        hipLaunchKernelGGL((k_wide_fold_stream<CQ, 0>), dim3(k * k), dim3(256), flds, stream, w, gw, k);
+        hipLaunchKernelGGL((k_wide_fold_stream<CQ, 0>), dim3(k * k), dim3(1024), flds, stream, w, gw, k);
     if (hipGetLastError() != hipSuccess)
         return INVCONV_ERR_LAUNCH;
     switch (k) {
