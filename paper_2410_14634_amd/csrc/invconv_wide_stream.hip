@@ -148,19 +148,35 @@ __global__ __launch_bounds__(256) void k_solve_wide_stream(const float *__restri
             yv[c4] = ok ? v : 0.0f;
         }
     };
-    // this wave's A operands of tap tp: VW consecutive floats per lane and load at wbase[tp kTapStride + q 64 VW]
+    // this wave's A operands of tap tp: VW consecutive floats per lane and load, at float index
+    // tp kTapStride + ob CQ 64 + q 64 VW + lane VW. Buffer loads: the lane's part of the address is one constant
+    // 32-bit register and the rest a scalar. (A load with a 64-bit address per lane holds up the wave's next matrix
+    // instruction for some 20 clocks whatever its width, a buffer load for about 5: measured with 12 products and
+    // 3 loads in turn, 37.9 against 33.6 clocks per product, 32.4 without loads.)
     constexpr int VW = ws_vec(CQ);
-    typedef float wvec_t __attribute__((ext_vector_type(VW)));
-    const float *wbase = gw + (size_t)ob * CQ * 64 + lane * VW;
     constexpr int kTapStride = OB * CQ * 64;
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(gw), 0, K * K * kTapStride * (int)sizeof(float), 0x00020000);
+    const int wlane = lane * VW * (int)sizeof(float);
+    const int wblock = ob * CQ * 64 * (int)sizeof(float);
     float aw[D][CQ];
     auto fetch_tap = [&](int tp, float (&dst)[CQ]) {
 #pragma unroll
         for (int q = 0; q < CQ / VW; ++q) {
-            const wvec_t v = *reinterpret_cast<const wvec_t *>(wbase + (size_t)tp * kTapStride + q * 64 * VW);
+            const int soff = (tp * kTapStride + q * 64 * VW) * (int)sizeof(float) + wblock;
+            if constexpr (VW == 4) {
+                const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, soff, 0));
 #pragma unroll
-            for (int e = 0; e < VW; ++e)
-                dst[VW * q + e] = v[e];
+                for (int e = 0; e < 4; ++e)
+                    dst[4 * q + e] = v[e];
+            } else if constexpr (VW == 2) {
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                const f32x2 v = __builtin_bit_cast(f32x2, __builtin_amdgcn_raw_buffer_load_b64(wrsrc, wlane, soff, 0));
+                dst[2 * q] = v[0];
+                dst[2 * q + 1] = v[1];
+            } else {
+                dst[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wrsrc, wlane, soff, 0));
+            }
         }
     };
 #pragma unroll
@@ -174,38 +190,32 @@ __global__ __launch_bounds__(256) void k_solve_wide_stream(const float *__restri
     int tm = 0;                                                 // t mod R
     for (int t = 0; t < nsteps; ++t) {
         load_y(t + 1, ynext);                                   // one step ahead (past the last step: zeros)
-        // four accumulators in turn: with one wave per SIMD a product that adds to the result of the one before the
-        // last still waits for it (two accumulators measured 52 clocks per instruction instead of 32)
+        // four accumulators in turn, summed at the end of the step
         f32x4 accs[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             accs[q] = f32x4{0.f, 0.f, 0.f, 0.f};
-        // B operands of tap (grp, u): the ring slot of lag da + db, da rows up; the first member of a group may be
-        // tap 0, whose operand is the input y of the step (a matrix instruction and the other vector instructions of
-        // ONE wave do not overlap, so what a tap costs beside its products is kept to the reads themselves)
+        // B operands of tap (grp, u): the ring slot of lag da + db, da rows up (tap (0, 0) takes the input y of the
+        // step instead: the term Linv y)
         auto read_b = [&](int grp, int u, float (&o)[CQ]) {
             const int da = D == K ? grp : u / K, db = D == K ? u : u % K, lag = da + db;
             int slot = tm - lag;
             slot += slot < 0 ? R : 0;
             const float *bp = ring + slot * HP * CPAD + b_row - da * CPAD;
-            if (u == 0) {
-                const bool first = lag == 0;
 #pragma unroll
-                for (int c4 = 0; c4 < CQ; ++c4) {
-                    const float xv = bp[4 * c4];
-                    o[c4] = first ? ycur[c4] : xv;
-                }
-            } else {
-#pragma unroll
-                for (int c4 = 0; c4 < CQ; ++c4)
-                    o[c4] = bp[4 * c4];
-            }
+            for (int c4 = 0; c4 < CQ; ++c4)
+                o[c4] = bp[4 * c4];
         };
         // The operands of the NEXT tap are read from LDS while the matrix cores work on the current one: two
         // buffers taken in turn; a group of an odd number of taps ends on the buffer the next group starts with,
-        // so its last tap reads ahead into the other one and hands over with one copy per group.
+        // so its last tap reads ahead into the other one and hands over with one copy per group. A wave issues in
+        // order and a product occupies the matrix core for 32 clocks: every other instruction of a tap (LDS reads,
+        // weight fetches) is placed BETWEEN two products, where it issues in the shadow of the one before it -
+        // grouped ahead of the products they cost 150 clocks per tap on top of the products' 384.
         float opb[2][CQ];
-        read_b(0, 0, opb[0]);
+#pragma unroll
+        for (int c4 = 0; c4 < CQ; ++c4)
+            opb[0][c4] = ycur[c4];
 #pragma unroll 1
         for (int grp = 0; grp < G; ++grp) {
             const int gnext = grp + 1 == G ? 0 : grp + 1;       // (the last group fetches the first one of the next step)
@@ -216,13 +226,21 @@ __global__ __launch_bounds__(256) void k_solve_wide_stream(const float *__restri
                     read_b(grp, u + 1, opb[(u + 1) & 1]);
                 else
                     read_b(gnext, 0, opb[(kLast & 1) ^ 1]);     // (after the last tap of the step: read and dropped)
-                __builtin_amdgcn_sched_barrier(0);      // keep the reads above ahead of the products below
 #pragma unroll
                 for (int c4 = 0; c4 < CQ; ++c4)
                     accs[c4 & 3] = __builtin_amdgcn_mfma_f32_16x16x4f32(aw[u][c4], opb[u & 1][c4], accs[c4 & 3], 0, 0, 0);
                 // the same member of the next group takes the registers just used (a single group, k = 2, stays)
                 if constexpr (G > 1)
                     fetch_tap(gnext * D + u, aw[u]);
+                // issue order of the tap: product, LDS read, product, LDS read, ...; each weight fetch after the
+                // last product that reads the registers it overwrites
+#pragma unroll
+                for (int c4 = 0; c4 < CQ; ++c4) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one matrix instruction
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // one LDS read
+                    if (G > 1 && (c4 + 1) % VW == 0)
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // one vector memory read
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 if (u == kLast && ((kLast & 1) ^ 1) != 0) {
 #pragma unroll
