@@ -101,26 +101,41 @@ __device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, f
     if (tid < 64) {
         const int j = tid < C ? tid : C - 1;
         float col[C];
+        // row o + 1 travels from LDS (16-byte pieces, the same address for all lanes) while row o is worked on, so
+        // that a row does not start with an LDS round trip (100 x 48x8x8: 2 us of the 8 this inverse took)
+        constexpr int NP = (C + 3) / 4;
+        f32x4 rows[2][NP];
+        rows[0][0] = *reinterpret_cast<const f32x4 *>(sL);
+        // the reciprocals of the diagonal: one division per lane, handed over through the first row of sLinv (this
+        // wave writes its result there only after the last row), instead of one per row on the dependent path
+        if (tid < C)
+            sLinv[j] = 1.0f / sL[j * C + j];
+        float rdv[2];
+        rdv[0] = sLinv[0];
 #pragma unroll
         for (int o = 0; o < C; ++o) {
-            // the row in 16-byte pieces, four partial sums (a single chain of dependent multiply-adds took 6 us
-            // at 48 channels)
+            if (o + 1 < C) {
+#pragma unroll
+                for (int m4 = 0; m4 <= (o + 1) / 4; ++m4)
+                    rows[(o + 1) & 1][m4] = *reinterpret_cast<const f32x4 *>(sL + (o + 1) * C + 4 * m4);
+                rdv[(o + 1) & 1] = sLinv[o + 1];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // four partial sums (a single chain of dependent multiply-adds took 6 us at 48 channels)
             float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            float diag = 1.0f;
 #pragma unroll
             for (int m4 = 0; m4 <= o / 4; ++m4) {
-                const f32x4 row = *reinterpret_cast<const f32x4 *>(sL + o * C + 4 * m4);
+                const f32x4 row = rows[o & 1][m4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (4 * m4 + e < o)
                         part[e] += row[e] * col[4 * m4 + e];
-                    else if (4 * m4 + e == o)
-                        diag = row[e];
                 }
             }
             const float sum = (part[0] + part[1]) + (part[2] + part[3]);
-            const float rd = 1.0f / diag;
+            const float rd = rdv[o & 1];
             col[o] = o < j ? 0.0f : (o == j ? rd : -sum * rd);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (tid < C) {
 #pragma unroll
@@ -347,6 +362,19 @@ __device__ __forceinline__ void wide_read_operands(const float *p, float (&o)[CQ
     }
 }
 
+// Issue order of one tap (CQ matrix products and the LDS reads of the next tap's operands): a product, a read, a
+// product, a read, ... A wave issues in order and a product occupies the matrix core for 32 clocks, so a read placed
+// behind a product issues in its shadow; reads grouped ahead of the products hold the first product up.
+template <int CQ>
+__device__ __forceinline__ void wide_interleave_reads()
+{
+#pragma unroll
+    for (int c4 = 0; c4 < CQ; ++c4) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one matrix instruction
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // one LDS read
+    }
+}
+
 template <int CQ, int DIR, int MAXW, bool PAD>
 __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__restrict__ in,
                                                               const float *__restrict__ w, float *__restrict__ out,
@@ -472,7 +500,6 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
         for (int q = 0; q < 3; ++q) {
             if (q + 1 < 3)
                 read_tap(kCrit[q + 1], t, tm, opb[(q + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);      // keep the reads above ahead of the products below
 #pragma unroll
             for (int c4 = 0; c4 < CQ; ++c4) {
                 if (c4 & 1)
@@ -480,6 +507,7 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
                 else
                     acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wAr[kCrit[q]][c4], opb[q & 1][c4], acc0, 0, 0, 0);
             }
+            wide_interleave_reads<CQ>();
             __builtin_amdgcn_sched_barrier(0);
         }
         // (the first operands of the old taps of step t + 1 are fetched while the result is being stored)
@@ -517,7 +545,6 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
         for (int q = 0; q < 6; ++q) {
             if (q + 1 < 6)
                 read_tap(kPre[q + 1], t + 1, tn, opb[(q + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int c4 = 0; c4 < CQ; ++c4) {
                 if (c4 & 1)
@@ -525,6 +552,7 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
                 else
                     acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(wAr[kPre[q]][c4], opb[q & 1][c4], acc0, 0, 0, 0);
             }
+            wide_interleave_reads<CQ>();
             __builtin_amdgcn_sched_barrier(0);
         }
         tm = tn;
