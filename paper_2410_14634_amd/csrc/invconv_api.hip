@@ -13,7 +13,8 @@ size_t solve_ws_bytes(int B, int C, int H, int W, int k)
     // many channels with a kernel size other than 3: the folded weights of the call
     if (wide_stream_supported(C, H, k))
         return wide_stream_ws_bytes(C, k);
-    return 0;
+    // many channels, 3 x 3: the same, so that the weights are folded once per call and not once per workgroup
+    return wide_prefold_ws_bytes(C, H, k);
 }
 
 }  // namespace invconv
@@ -87,6 +88,13 @@ int solve_variant(int dir, const float *in, const float *w, float *out, int B, i
 
 // `logdet` (forward direction only, may be null): where log|det dx/dy| of one image goes; the few-channel, band and
 // many-channel kernels write it on the side, every other kernel is followed by the small launch invconv_logdet makes.
+// the caller's scratch as the place for the folded weights of a many-channel 3 x 3 solve, if it is large enough
+float *wide_gw(const SolveWs &ws, int C, int H, int k)
+{
+    const size_t need = wide_prefold_ws_bytes(C, H, k);
+    return need && ws.base && ws.bytes >= need ? reinterpret_cast<float *>(ws.base) : nullptr;
+}
+
 int solve(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
           hipStream_t stream, int variant, SolveWs ws = SolveWs{}, float *logdet = nullptr)
 {
@@ -100,7 +108,7 @@ int solve(int dir, const float *in, const float *w, float *out, int B, int C, in
             if (!(chain_supported(1, C, H, W, k) && chain_single_preferred(B, C, H)))
                 return launch_solve_band(dir, in, w, out, B, C, H, W, k, stream, logdet);
         } else if (wide_supported(C, H, k)) {
-            return launch_solve_wide(dir, in, w, out, B, C, H, W, k, stream, logdet);
+            return launch_solve_wide(dir, in, w, out, B, C, H, W, k, stream, logdet, wide_gw(ws, C, H, k));
         }
     }
     if (int s = solve_variant(dir, in, w, out, B, C, H, W, k, stream, variant, ws))
@@ -134,7 +142,7 @@ int solve_variant(int dir, const float *in, const float *w, float *out, int B, i
             return launch_solve_band(dir, in, w, out, B, C, H, W, k, stream);
         }
         if (wide_supported(C, H, k))
-            return launch_solve_wide(dir, in, w, out, B, C, H, W, k, stream);
+            return launch_solve_wide(dir, in, w, out, B, C, H, W, k, stream, nullptr, wide_gw(ws, C, H, k));
         if (wide_stream_supported(C, H, k) && ws.base && ws.bytes >= wide_stream_ws_bytes(C, k))
             return launch_solve_wide_stream(dir, in, w, out, B, C, H, W, k, stream, reinterpret_cast<float *>(ws.base));
         if (check_supported(C, H, k) == INVCONV_OK)

@@ -66,8 +66,12 @@ int launch_flow_fwd_band(const float *y, const float *w, const float *s, const f
                          int B, int C, int H, int W, int k, hipStream_t stream, float *logdet);
 // many channels (17 .. 48), k = 3: 16x16x4 MFMA per tap, history in an LDS ring
 bool wide_supported(int C, int H, int k);
+// gw: null, or wide_prefold_ws_bytes(C, H, k) > 0 bytes of device scratch (256-byte aligned): the weights are then
+// folded once per call by a set-up launch instead of once per workgroup
+size_t wide_prefold_ws_bytes(int C, int H, int k);
 int launch_solve_wide(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                      hipStream_t stream, float *logdet = nullptr);
+                      hipStream_t stream, float *logdet = nullptr, float *gw = nullptr);
+int launch_wide_fold(int dir, const float *w, float *gw, int C, int k, hipStream_t stream);
 // many channels (20 .. 48, multiples of 4) with k = 2, 5, 7, 9, 11: the same solve with its folded weights streamed from
 // `gw`, wide_stream_ws_bytes(C, k) bytes of device scratch that a set-up launch of the same call fills
 bool wide_stream_supported(int C, int H, int k);

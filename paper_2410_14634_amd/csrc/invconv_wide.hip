@@ -18,6 +18,7 @@
 // The transposed solve is the same kernel in mirrored coordinates (DIR = 1).
 #include "invconv_common.h"
 #include "invconv_launch.h"
+#include "invconv_tri_inverse.h"
 #include <type_traits>
 
 namespace invconv {
@@ -40,7 +41,8 @@ __host__ __device__ constexpr int wide_out_blocks(int C) { return (C + 15) / 16;
 constexpr int kWideTapStride = 48;      // row stride of the staged taps: C <= 48, and 48 mod 32 = 16
 __host__ __device__ constexpr size_t wide_fold_scratch_floats(int C)
 {
-    return (size_t)C * C + (size_t)16 * wide_out_blocks(C) * (C + 1) + (size_t)4 * C * kWideTapStride;
+    return (size_t)C * C + (size_t)16 * wide_out_blocks(C) * (C + 1) + (size_t)4 * C * kWideTapStride +
+           tri_inverse_tmp_floats();
 }
 
 // Cr: the channels the image really has (4 CQ - 3 .. 4 CQ); the surplus ones are given an identity current-pixel
@@ -53,7 +55,7 @@ __device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, f
     constexpr int OB = wide_out_blocks(C), OR = 16 * OB, CPAD = C + 1;
     constexpr int LP = C + 1, TP = kWideTapStride;
     static_assert(C <= TP && OR <= TP && NT == 9, "tap staging is laid out for at most 48 channels, 3 x 3 taps");
-    float *sL = scratch, *sLinv = sL + C * C, *sTap = sLinv + OR * LP;       // [C][C], [OR][LP], [4][C][TP]
+    float *sL = scratch, *sLinv = sL + C * C, *sTap = sLinv + OR * LP;       // [C][C], [OR][LP], [4][C][TP], inverse's
     const int tid = threadIdx.x, nt = blockDim.x;
     auto entry = [&](int tp, int o, int i) -> float {
         const int a = K - 1 - tp / K, b = K - 1 - tp % K;
@@ -95,55 +97,9 @@ __device__ __forceinline__ void wide_fold_weights(const float *__restrict__ w, f
         sLinv[C * LP + idx] = 0.0f;
     stage(1);
     __syncthreads();
-    // Inverse of the lower-triangular block, column j by thread j, the column in registers: every thread runs
-    // the same fully unrolled substitution (entries above the diagonal are zeros that take part in the sums),
-    // the matrix entries are the same address for all lanes, and no result travels through LDS on the way.
-    if (tid < 64) {
-        const int j = tid < C ? tid : C - 1;
-        float col[C];
-        // row o + 1 travels from LDS (16-byte pieces, the same address for all lanes) while row o is worked on, so
-        // that a row does not start with an LDS round trip (100 x 48x8x8: 2 us of the 8 this inverse took)
-        constexpr int NP = (C + 3) / 4;
-        f32x4 rows[2][NP];
-        rows[0][0] = *reinterpret_cast<const f32x4 *>(sL);
-        // the reciprocals of the diagonal: one division per lane, handed over through the first row of sLinv (this
-        // wave writes its result there only after the last row), instead of one per row on the dependent path
-        if (tid < C)
-            sLinv[j] = 1.0f / sL[j * C + j];
-        float rdv[2];
-        rdv[0] = sLinv[0];
-#pragma unroll
-        for (int o = 0; o < C; ++o) {
-            if (o + 1 < C) {
-#pragma unroll
-                for (int m4 = 0; m4 <= (o + 1) / 4; ++m4)
-                    rows[(o + 1) & 1][m4] = *reinterpret_cast<const f32x4 *>(sL + (o + 1) * C + 4 * m4);
-                rdv[(o + 1) & 1] = sLinv[o + 1];
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            // four partial sums (a single chain of dependent multiply-adds took 6 us at 48 channels)
-            float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int m4 = 0; m4 <= o / 4; ++m4) {
-                const f32x4 row = rows[o & 1][m4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (4 * m4 + e < o)
-                        part[e] += row[e] * col[4 * m4 + e];
-                }
-            }
-            const float sum = (part[0] + part[1]) + (part[2] + part[3]);
-            const float rd = rdv[o & 1];
-            col[o] = o < j ? 0.0f : (o == j ? rd : -sum * rd);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (tid < C) {
-#pragma unroll
-            for (int o = 0; o < C; ++o)
-                sLinv[o * LP + j] = col[o];
-        }
-    }
-    __syncthreads();
+    // Inverse of the lower-triangular block in 16 x 16 blocks by the whole workgroup (one thread per column, the
+    // column in registers, was a chain of C dependent rows: 8 us of one wave at 48 channels)
+    tri_inverse_blocks<C>(sL, sLinv, LP, sTap + 4 * C * TP);
     for (int it = tid; it < OR * C; it += nt) {
         const int o = it / C, i = it % C;
         sWt[o * CPAD + i] = sLinv[o * LP + i];      // tap 0 (rows past C: zeros)
@@ -375,11 +331,17 @@ __device__ __forceinline__ void wide_interleave_reads()
     }
 }
 
-template <int CQ, int DIR, int MAXW, bool PAD>
+// PRE: the folded weights come from `gw`, where a set-up launch of the same call has put them in the order the lanes
+// hold them (float index ((tp OB + ob) CQ + VW q) 64 + lane VW + e for the A operand c4 = VW q + e of tap tp): the
+// workgroup skips the weight preparation - half the time of a call on 100 images of 48 x 8 x 8 - and needs LDS for
+// its rings only.
+template <int CQ, int DIR, int MAXW, bool PAD, bool PRE>
 __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__restrict__ in,
-                                                              const float *__restrict__ w, float *__restrict__ out,
+                                                              const float *__restrict__ w,
+                                                              const float *__restrict__ gw, float *__restrict__ out,
                                                               int H, int W, int NB, float *logdet, int Cr_arg)
 {
+    static_assert(!(PRE && PAD), "prefolded weights are laid out for whole groups of four channels");
     constexpr int C = 4 * CQ, K = kWideK, NT = K * K, R = kWideRing;
     const int Cr = PAD ? Cr_arg : C;
     constexpr int OB = wide_out_blocks(C), OR = 16 * OB, CPAD = C + 1;
@@ -395,18 +357,31 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
     const int band = wave / OB, ob = wave % OB;
     const int n = lane & 15, g = lane >> 4;
 
-    wide_fold_weights<CQ, DIR, PAD>(w, sWt, sWt + NT * OR * CPAD, Cr);
     // this lane's A operands: row m = n -> output channel 16 ob + n, K slot g -> input channel 4 c4 + g
     float wAr[NT][CQ];
-    {
+    if constexpr (PRE) {
+        constexpr int VW = wide_vec<CQ>();
+        typedef float wvec_t __attribute__((ext_vector_type(VW)));
+        const float *wl = gw + (ob * CQ * 64 + lane * VW);
+#pragma unroll
+        for (int tp = 0; tp < NT; ++tp)
+#pragma unroll
+            for (int q = 0; q < CQ / VW; ++q) {
+                const wvec_t v = *reinterpret_cast<const wvec_t *>(wl + (tp * OB * CQ + VW * q) * 64);
+#pragma unroll
+                for (int e = 0; e < VW; ++e)
+                    wAr[tp][VW * q + e] = v[e];
+            }
+    } else {
+        wide_fold_weights<CQ, DIR, PAD>(w, sWt, sWt + NT * OR * CPAD, Cr);
         const int a_base = (16 * ob + n) * CPAD + g;
 #pragma unroll
         for (int tp = 0; tp < NT; ++tp)
 #pragma unroll
             for (int c4 = 0; c4 < CQ; ++c4)
                 wAr[tp][c4] = sWt[tp * OR * CPAD + a_base + 4 * c4];
+        __syncthreads();
     }
-    __syncthreads();
     for (int idx = tid; idx < (R * HP + 2 * YR) * CP + 16; idx += nt)
         ring[idx] = 0.0f;       // (the flags too: zero bits)
     __syncthreads();
@@ -561,6 +536,13 @@ __global__ __launch_bounds__(64 * MAXW) void k_solve_wide_reg(const float *__res
         wave_logdet_any(w, Cr, K, H, W, logdet);
 }
 
+// the rings, the two input slots and the step flags
+static size_t wide_reg_run_lds_bytes(int C, int H)
+{
+    const size_t NB = (H + 15) / 16, CQ = C / 4, CP = C + (CQ % 4 == 0 ? 4 : (CQ % 2 == 0 ? 2 : 1));
+    return sizeof(float) * (((size_t)kWideRing * (16 * NB + kWideK - 1) + 2 * 16 * NB) * CP + 16);
+}
+
 static size_t wide_reg_lds_bytes(int C, int H)
 {
     const size_t NB = (H + 15) / 16, OR = 16 * (size_t)wide_out_blocks(C), CPAD = C + 1;
@@ -579,13 +561,33 @@ static bool wide_reg_supported(int C, int H)
 
 template <int CQ, int MAXW, bool PAD>
 static int launch_wide_reg(int dir, const float *in, const float *w, float *out, int B, int Cr, int H, int W,
-                           hipStream_t stream, float *logdet)
+                           hipStream_t stream, float *logdet, float *gw)
 {
     constexpr int C = 4 * CQ;
     const int NB = (H + 15) / 16;
+    if constexpr (!PAD) {
+        if (gw) {
+            // the weights folded once for the call by a launch of their own, the solve with the waves it needs
+            if (int s = launch_wide_fold(dir, w, gw, C, kWideK, stream))
+                return s;
+            const size_t lds = wide_reg_run_lds_bytes(C, H);
+            const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 1, MAXW, false, true>)
+                                 : reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 0, MAXW, false, true>);
+            if (!ensure_dynamic_lds(fn, lds))
+                return INVCONV_ERR_UNSUPPORTED;
+            const dim3 block((unsigned)(64 * NB * wide_out_blocks(C)));
+            if (dir)
+                hipLaunchKernelGGL((k_solve_wide_reg<CQ, 1, MAXW, false, true>), dim3(B), block, lds, stream, in, w, gw,
+                                   out, H, W, NB, logdet, Cr);
+            else
+                hipLaunchKernelGGL((k_solve_wide_reg<CQ, 0, MAXW, false, true>), dim3(B), block, lds, stream, in, w, gw,
+                                   out, H, W, NB, logdet, Cr);
+            return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+        }
+    }
     const size_t lds = wide_reg_lds_bytes(C, H);
-    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 1, MAXW, PAD>)
-                         : reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 0, MAXW, PAD>);
+    const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 1, MAXW, PAD, false>)
+                         : reinterpret_cast<const void *>(&k_solve_wide_reg<CQ, 0, MAXW, PAD, false>);
     if (!ensure_dynamic_lds(fn, lds))
         return INVCONV_ERR_UNSUPPORTED;
     // up to one workgroup per compute unit: eight waves at least, the ones the solve does not use help with the
@@ -596,11 +598,11 @@ static int launch_wide_reg(int dir, const float *in, const float *w, float *out,
         waves = 8 < MAXW ? 8 : MAXW;
     const dim3 block((unsigned)(64 * waves));
     if (dir)
-        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 1, MAXW, PAD>), dim3(B), block, lds, stream, in, w, out, H, W, NB,
-                           logdet, Cr);
+        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 1, MAXW, PAD, false>), dim3(B), block, lds, stream, in, w,
+                           (const float *)nullptr, out, H, W, NB, logdet, Cr);
     else
-        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 0, MAXW, PAD>), dim3(B), block, lds, stream, in, w, out, H, W, NB,
-                           logdet, Cr);
+        hipLaunchKernelGGL((k_solve_wide_reg<CQ, 0, MAXW, PAD, false>), dim3(B), block, lds, stream, in, w,
+                           (const float *)nullptr, out, H, W, NB, logdet, Cr);
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
@@ -621,14 +623,14 @@ bool wide_supported(int C, int H, int k)
 
 template <int CQ, bool PAD>
 static int launch_wide_cq(int dir, const float *in, const float *w, float *out, int B, int Cr, int H, int W,
-                          hipStream_t stream, float *logdet)
+                          hipStream_t stream, float *logdet, float *gw)
 {
     constexpr int C = 4 * CQ;
     const int NB = (H + 15) / 16;
     if (wide_reg_supported(C, H))
         return NB * wide_out_blocks(C) <= 8
-                   ? launch_wide_reg<CQ, 8, PAD>(dir, in, w, out, B, Cr, H, W, stream, logdet)
-                   : launch_wide_reg<CQ, 12, PAD>(dir, in, w, out, B, Cr, H, W, stream, logdet);
+                   ? launch_wide_reg<CQ, 8, PAD>(dir, in, w, out, B, Cr, H, W, stream, logdet, gw)
+                   : launch_wide_reg<CQ, 12, PAD>(dir, in, w, out, B, Cr, H, W, stream, logdet, gw);
     const size_t lds = wide_lds_bytes(C, H);
     const void *fn = dir ? reinterpret_cast<const void *>(&k_solve_wide<CQ, 1, PAD>)
                          : reinterpret_cast<const void *>(&k_solve_wide<CQ, 0, PAD>);
@@ -642,22 +644,31 @@ static int launch_wide_cq(int dir, const float *in, const float *w, float *out, 
     return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
 }
 
-int launch_solve_wide(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
-                      hipStream_t stream, float *logdet)
+// bytes of scratch with which the weights are folded once per call instead of once per workgroup (0: not for this shape)
+size_t wide_prefold_ws_bytes(int C, int H, int k)
 {
+    return wide_supported(C, H, k) && C % 4 == 0 && C >= 20 && wide_reg_supported(C, H) ? wide_stream_ws_bytes(C, k) : 0;
+}
+
+// gw: null, or wide_prefold_ws_bytes(C, H, k) > 0 bytes of device scratch, 256-byte aligned
+int launch_solve_wide(int dir, const float *in, const float *w, float *out, int B, int C, int H, int W, int k,
+                      hipStream_t stream, float *logdet, float *gw)
+{
+    if (gw && !wide_prefold_ws_bytes(C, H, k))
+        gw = nullptr;
     if (!wide_supported(C, H, k))
         return INVCONV_ERR_VARIANT;
     auto by_cq = [&](auto pad_tag) -> int {
         constexpr bool PAD = decltype(pad_tag)::value;
         switch ((C + 3) / 4) {
-        case 5: return launch_wide_cq<5, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
-        case 6: return launch_wide_cq<6, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
-        case 7: return launch_wide_cq<7, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
-        case 8: return launch_wide_cq<8, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
-        case 9: return launch_wide_cq<9, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
-        case 10: return launch_wide_cq<10, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
-        case 11: return launch_wide_cq<11, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
-        case 12: return launch_wide_cq<12, PAD>(dir, in, w, out, B, C, H, W, stream, logdet);
+        case 5: return launch_wide_cq<5, PAD>(dir, in, w, out, B, C, H, W, stream, logdet, gw);
+        case 6: return launch_wide_cq<6, PAD>(dir, in, w, out, B, C, H, W, stream, logdet, gw);
+        case 7: return launch_wide_cq<7, PAD>(dir, in, w, out, B, C, H, W, stream, logdet, gw);
+        case 8: return launch_wide_cq<8, PAD>(dir, in, w, out, B, C, H, W, stream, logdet, gw);
+        case 9: return launch_wide_cq<9, PAD>(dir, in, w, out, B, C, H, W, stream, logdet, gw);
+        case 10: return launch_wide_cq<10, PAD>(dir, in, w, out, B, C, H, W, stream, logdet, gw);
+        case 11: return launch_wide_cq<11, PAD>(dir, in, w, out, B, C, H, W, stream, logdet, gw);
+        case 12: return launch_wide_cq<12, PAD>(dir, in, w, out, B, C, H, W, stream, logdet, gw);
         default: return INVCONV_ERR_VARIANT;
         }
     };

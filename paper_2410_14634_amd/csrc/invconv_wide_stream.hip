@@ -14,6 +14,7 @@
 // matrix instructions that use them.  Without a workspace these shapes keep the per-diagonal fallback.
 #include "invconv_common.h"
 #include "invconv_launch.h"
+#include "invconv_tri_inverse.h"
 
 namespace invconv {
 
@@ -47,38 +48,8 @@ __global__ __launch_bounds__(1024) void k_wide_fold_stream(const float *__restri
         sT[idx] = tp ? entry(tp, idx / C, idx % C) : 0.0f;
     }
     __syncthreads();
-    // Column j of Linv by thread j with the column in registers: every thread runs the same fully unrolled forward
-    // substitution (entries above the diagonal are zeros that take part in the sums), the rows of L come in as
-    // 16-byte reads of addresses common to all lanes, four partial sums per row.
-    if (tid < 64) {
-        const int j = tid < C ? tid : C - 1;
-        float col[C];
-#pragma unroll
-        for (int o = 0; o < C; ++o) {
-            float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            float diag = 1.0f;
-#pragma unroll
-            for (int m4 = 0; m4 <= o / 4; ++m4) {
-                const f32x4 row = *reinterpret_cast<const f32x4 *>(sL + o * C + 4 * m4);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (4 * m4 + e < o)
-                        part[e] += row[e] * col[4 * m4 + e];
-                    else if (4 * m4 + e == o)
-                        diag = row[e];
-                }
-            }
-            const float sum = (part[0] + part[1]) + (part[2] + part[3]);
-            const float rd = 1.0f / diag;
-            col[o] = o < j ? 0.0f : (o == j ? rd : -sum * rd);
-        }
-        if (tid < C) {
-#pragma unroll
-            for (int o = 0; o < C; ++o)
-                sLinv[o * C + j] = col[o];
-        }
-    }
-    __syncthreads();
+    // Linv in 16 x 16 blocks by the whole workgroup
+    tri_inverse_blocks<C>(sL, sLinv, C, sT + C * C);
     constexpr int OB = ws_out_blocks(C);
     float *dst = gw + (size_t)tp * OB * CQ * 64;
     constexpr int VW = ws_vec(CQ);
@@ -298,16 +269,22 @@ int launch_stream_ck(int dir, const float *in, const float *gw, float *out, int 
 }
 
 template <int CQ>
-int launch_stream_cq(int dir, const float *in, const float *w, float *gw, float *out, int B, int H, int W, int k,
-                     hipStream_t stream)
+int launch_fold_cq(int dir, const float *w, float *gw, int k, hipStream_t stream)
 {
-    const size_t flds = sizeof(float) * 3 * (size_t)(4 * CQ) * (4 * CQ);
+    const size_t flds = sizeof(float) * (3 * (size_t)(4 * CQ) * (4 * CQ) + tri_inverse_tmp_floats());
     if (dir)
         hipLaunchKernelGGL((k_wide_fold_stream<CQ, 1>), dim3(k * k), dim3(1024), flds, stream, w, gw, k);
     else
         hipLaunchKernelGGL((k_wide_fold_stream<CQ, 0>), dim3(k * k), dim3(1024), flds, stream, w, gw, k);
-    if (hipGetLastError() != hipSuccess)
-        return INVCONV_ERR_LAUNCH;
+    return hipGetLastError() == hipSuccess ? INVCONV_OK : INVCONV_ERR_LAUNCH;
+}
+
+template <int CQ>
+int launch_stream_cq(int dir, const float *in, const float *w, float *gw, float *out, int B, int H, int W, int k,
+                     hipStream_t stream)
+{
+    if (int s = launch_fold_cq<CQ>(dir, w, gw, k, stream))
+        return s;
     switch (k) {
     case 2: return launch_stream_ck<CQ, 2>(dir, in, gw, out, B, H, W, stream);
     case 5: return launch_stream_ck<CQ, 5>(dir, in, gw, out, B, H, W, stream);
@@ -332,6 +309,24 @@ bool wide_stream_supported(int C, int H, int k)
 size_t wide_stream_ws_bytes(int C, int k)
 {
     return sizeof(float) * (size_t)k * k * ws_out_blocks(C) * (C / 4) * 64;
+}
+
+// The set-up launch alone: C = 20 .. 48 in multiples of 4, any k; fills wide_stream_ws_bytes(C, k) bytes at `gw`.
+int launch_wide_fold(int dir, const float *w, float *gw, int C, int k, hipStream_t stream)
+{
+    if (C % 4 || C < 20 || C > 48 || !gw)
+        return INVCONV_ERR_VARIANT;
+    switch (C / 4) {
+    case 5: return launch_fold_cq<5>(dir, w, gw, k, stream);
+    case 6: return launch_fold_cq<6>(dir, w, gw, k, stream);
+    case 7: return launch_fold_cq<7>(dir, w, gw, k, stream);
+    case 8: return launch_fold_cq<8>(dir, w, gw, k, stream);
+    case 9: return launch_fold_cq<9>(dir, w, gw, k, stream);
+    case 10: return launch_fold_cq<10>(dir, w, gw, k, stream);
+    case 11: return launch_fold_cq<11>(dir, w, gw, k, stream);
+    case 12: return launch_fold_cq<12>(dir, w, gw, k, stream);
+    default: return INVCONV_ERR_VARIANT;
+    }
 }
 
 // `gw`: wide_stream_ws_bytes(C, k) bytes of device scratch, 256-byte aligned

@@ -212,6 +212,37 @@ def test_many_channels_other_kernel_sizes_with_workspace(shape):
         assert rel_err(host(x_plain), xr) <= TOL_ACT
 
 
+WIDE_WS_SHAPES = [  # (B, C, H, W, k): many channels, 3 x 3, every group count C/4 = 5 .. 12, one to several bands
+    (2, 48, 8, 8, 3), (3, 20, 5, 7, 3), (2, 24, 40, 9, 3), (1, 28, 33, 6, 3), (2, 32, 64, 5, 3), (1, 36, 17, 17, 3),
+    (2, 40, 20, 9, 3), (1, 44, 16, 3, 3), (1, 48, 64, 4, 3), (101, 48, 8, 8, 3), (2, 22, 9, 9, 3),
+]
+
+
+@pytest.mark.parametrize("shape", WIDE_WS_SHAPES)
+def test_many_channels_with_workspace_fold_the_weights_once(shape):
+    """Many channels, 3 x 3: a call that brings a workspace folds the weights once, by a launch of its own, and
+    its workgroups read them from there; a call without one folds them in every workgroup (and so does a channel
+    count that is no multiple of 4, whose workspace is the header alone).  Both against the oracle."""
+    import torch
+    B, C, H, W, k = shape
+    print(f"many channels, k = 3, workspace: {shape}", flush=True)
+    cs = inputs.make_case(B, C, H, W, k, seed=sum(shape) + 13, tap_std=0.05)
+    yd, wd, gd = dev(cs["y"]), dev(cs["w"][0]), dev(cs["g"])
+    assert (b.fwd_workspace_bytes(B, C, H, W, k) > 256) == (C % 4 == 0)
+    wsf = b.new_workspace(b.fwd_workspace_bytes(B, C, H, W, k))
+    wsb = b.new_workspace(b.bwd_workspace_bytes(B, C, H, W, k))
+    x = b.invconv_fwd(yd, wd, workspace=wsf)
+    x_plain = b.invconv_fwd(yd, wd)
+    v, dw = b.invconv_bwd(x, wd, gd, workspace=wsb)
+    torch.cuda.synchronize()
+    xh = host(x)
+    xr = oracle.invconv_fwd(cs["y"], cs["w"][0], THREADS)
+    vr, dwr = oracle.invconv_bwd(xh, cs["w"][0], cs["g"], THREADS)
+    assert rel_err(xh, xr) <= TOL_ACT and elementwise_ok(xh, xr, TOL_ACT)
+    assert rel_err(host(x_plain), xr) <= TOL_ACT and elementwise_ok(host(x_plain), xr, TOL_ACT)
+    assert rel_err(host(v), vr) <= TOL_ACT and rel_err(host(dw), dwr) <= TOL_DW
+
+
 @pytest.mark.parametrize("shape", TALL_SHAPES)
 def test_tall_images_with_and_without_workspace_agree(shape):
     """invconv_fwd_ws / invconv_bwd spread the bands of an image over workgroups (logs in the caller's
