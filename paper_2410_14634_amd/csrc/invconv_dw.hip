@@ -283,7 +283,7 @@ bool dw_mfma_supported(int C, int k)
 
 // Row chunking of pass 1 for one block of Cv output x Cx input channels: tiles (or the reduction buffer that reuses
 // them) must fit the LDS budget.  p.nparts = B * G partial rows per block, G workgroups per image each looping over chunks.
-static DwPlan plan_dw_mfma_block(int B, int Cv, int C, int H, int W, int k)
+static DwPlan plan_dw_mfma_block(int B, int Cv, int C, int H, int W, int k, int nblocks = 1)
 {
     DwPlan p{};
     const int CM = Cv > C ? Cv : C;
@@ -309,7 +309,13 @@ static DwPlan plan_dw_mfma_block(int B, int Cv, int C, int H, int W, int k)
     const size_t budget = stream_shape ? kDwStreamLdsBudget : kDwLdsBudget;
     if (lds_for(1) > budget)
         return p;
-    int rt = H < 8 ? H : 8;
+    // chunks of 8 rows; kernels of more than 9 rows take 16, so that a chunk still covers the k - 1 halo rows the
+    // streaming mode carries over from the chunk before - where that still leaves a workgroup per compute unit
+    // (the blocks of a blocked result that share a launch count as images here)
+    const int shared = nblocks < kChainMaxLayers ? nblocks : kChainMaxLayers;
+    const bool tall_chunks = stream_shape && k - 1 > 8 && (long)B * shared * ((H + 15) / 16) >= 320;
+    const int rt_max = tall_chunks ? 16 : 8;
+    int rt = H < rt_max ? H : rt_max;
     while (rt > 1 && (lds_for(rt) > budget || (stream_shape && rt > k - 1 && CM * rt * (W / 4) > 256 * kDwPre)))
         --rt;
     p.rt = rt;
@@ -383,7 +389,7 @@ static DwPlan plan_dw_mfma_block(int B, int Cv, int C, int H, int W, int k)
     // Workgroups per image: a workgroup streams through a contiguous range of chunks and re-reads only the
     // k-1 halo rows at the start of its range, so few long ranges are better than many short ones, as long
     // as every compute unit gets a workgroup or two per layer.
-    int g = (320 + B - 1) / B;
+    int g = (320 + B * shared - 1) / (B * shared);
     if (g > p.nchunks) g = p.nchunks;
     if (g < 1) g = 1;
     g = (p.nchunks + (p.nchunks + g - 1) / g - 1) / ((p.nchunks + g - 1) / g);      // no empty workgroups
@@ -403,10 +409,10 @@ DwPlan plan_dw_mfma(int B, int C, int H, int W, int k)
         return plan_dw_mfma_block(B, C, C, H, W, k);        // one GEMM
     // blocks of cbv output x cbx input channels: the plan of one block; up to kChainMaxLayers blocks share a
     // launch, each with its own partial rows
-    DwPlan p = plan_dw_mfma_block(B, cbv, cbx, H, W, k);
+    const size_t nblocks = (size_t)((C + cbv - 1) / cbv) * ((C + cbx - 1) / cbx);
+    DwPlan p = plan_dw_mfma_block(B, cbv, cbx, H, W, k, (int)nblocks);
     p.cb = p.rt ? cbv : 0;
     p.cbx = cbx;
-    const size_t nblocks = (size_t)((C + cbv - 1) / cbv) * ((C + cbx - 1) / cbx);
     p.bytes *= nblocks < (size_t)kChainMaxLayers ? nblocks : (size_t)kChainMaxLayers;
     return p;
 }
