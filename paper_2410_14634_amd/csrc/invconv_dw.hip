@@ -45,10 +45,14 @@ constexpr size_t kDwStreamLdsBudget = 72 * 1024;   // streaming mode: two workgr
 template <int NS>
 __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *__restrict__ part, int B, int C,
                                                         int H, int W, int k, int RT, int nchunks, int G, int vec,
-                                                        int XW, int SXC, int SVC, int Cv, int Ctot, int pstride)
+                                                        int XW, int SXC, int SVC, int Cv, int Ctot, int pstride,
+                                                        int ipw, int Btot)
 {
     extern __shared__ float smem[];
-    // blockIdx = ((layer * B + n) * G + cg); this workgroup takes chunks cg, cg+G, ... of image n
+    // blockIdx = ((layer * B + n) * G + cg); this workgroup takes chunks cg, cg+G, ... of image n.
+    // ipw > 1 (images of a single chunk, G = 1): B counts groups of ipw images and the workgroup takes the images
+    // n ipw .. of the Btot there are, one after the other, into the same accumulators - one partial row per group
+    // instead of one per image (1024 images of 48 x 8 x 8 wrote and re-read 85 MB of partial sums)
     const int cg = blockIdx.x % G, n = (blockIdx.x / G) % B, layer = blockIdx.x / (G * B);
     if (batch.cx[layer]) {      // a block of a larger result: its own channel counts (tiles are laid out for the launch's)
         C = batch.cx[layer];
@@ -83,7 +87,10 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
 
     const int cpw = (nchunks + G - 1) / G;          // chunks cg*cpw .. of image n, contiguous
     const int c_begin = cg * cpw, c_end = (c_begin + cpw < nchunks) ? c_begin + cpw : nchunks;
-    const size_t img = (size_t)n * Ctot * H * W;
+    const size_t img_stride = (size_t)Ctot * H * W;
+    const int n_first = ipw > 1 ? n * ipw : n;
+    const int trips = ipw > 1 ? (Btot - n_first < ipw ? Btot - n_first : ipw) : c_end - c_begin;
+    size_t img = (size_t)n_first * img_stride;
 
     // streaming mode: this thread's pieces of a chunk (loop invariant): piece i is float4 c4 of row r of channel ch
     float4 pv[kDwPre], px[kDwPre], ph[kDwPre];
@@ -128,7 +135,8 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
         }
     }
 
-    for (int chunk = c_begin; chunk < c_end; ++chunk) {
+    for (int it = 0; it < trips; ++it) {
+        const int chunk = ipw > 1 ? 0 : c_begin + it;
         const int r0 = chunk * RT;
         const int rows = (H - r0 < RT) ? H - r0 : RT;
         const int xrows = rows + k - 1;
@@ -145,7 +153,8 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
                         if (r >= RT - (k - 1))      // last rows of the chunk before: rows 0 .. k-2 of the tile
                             *reinterpret_cast<float4 *>(sx + p_xl[i] - RT * XW) = ph[i];
                     }
-                    ph[i] = px[i];
+                    if (ipw <= 1)
+                        ph[i] = px[i];      // (single-chunk images: nothing above the chunk, ph stays zero)
                 }
             }
         } else if (vec) {
@@ -154,7 +163,7 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
                 const int c4 = idx % W4, rr = idx / W4;         // rr = ch*rows + r
                 const int ch = rr / rows, r = rr - ch * rows;
                 const float4 val = *reinterpret_cast<const float4 *>(
-                    v + (((size_t)n * Ctot + ch) * H + r0 + r) * W + 4 * c4);
+                    v + img + ((size_t)ch * H + r0 + r) * W + 4 * c4);
                 *reinterpret_cast<float4 *>(sv + ch * SVC + r * W + 4 * c4) = val;
             }
             const int X4 = (W + halo) / 4, H4 = halo / 4;      // the first H4 pieces of a row are the halo
@@ -164,33 +173,34 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
                 const int gr = r0 - (k - 1) + r;
                 float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (gr >= 0 && c4 >= H4)
-                    val = *reinterpret_cast<const float4 *>(x + (((size_t)n * Ctot + ch) * H + gr) * W + 4 * (c4 - H4));
+                    val = *reinterpret_cast<const float4 *>(x + img + ((size_t)ch * H + gr) * W + 4 * (c4 - H4));
                 *reinterpret_cast<float4 *>(sx + ch * SXC + r * XW + 4 * c4) = val;
             }
         } else {
             for (int idx = tid; idx < Cv * rows * W; idx += 256) {
                 const int c = idx % W, r = (idx / W) % rows, ch = idx / (W * rows);
-                sv[ch * SVC + r * W + c] = v[(((size_t)n * Ctot + ch) * H + r0 + r) * W + c];
+                sv[ch * SVC + r * W + c] = v[img + ((size_t)ch * H + r0 + r) * W + c];
             }
             const int xcols = W + halo;
             for (int idx = tid; idx < C * xrows * xcols; idx += 256) {
                 const int cc = idx % xcols, rr = (idx / xcols) % xrows, ch = idx / (xcols * xrows);
                 const int gr = r0 - (k - 1) + rr, gc = cc - halo;
                 sx[ch * SXC + rr * XW + cc] =
-                    (gr >= 0 && gc >= 0) ? x[(((size_t)n * Ctot + ch) * H + gr) * W + gc] : 0.0f;
+                    (gr >= 0 && gc >= 0) ? x[img + ((size_t)ch * H + gr) * W + gc] : 0.0f;
             }
         }
         __syncthreads();
-        if (vec == 2 && chunk + 1 < c_end) {
-            // the next chunk travels while the matrix cores work on this one
-            const int rn = r0 + RT;
+        if (vec == 2 && it + 1 < trips) {
+            // the next chunk (or the next image's only chunk) travels while the matrix cores work on this one
+            const int rn = ipw > 1 ? 0 : r0 + RT;
+            const size_t img_n = ipw > 1 ? img + img_stride : img;
 #pragma unroll
             for (int i = 0; i < kDwPre; ++i) {
                 const bool in = p_r[i] >= 0 && rn + p_r[i] < H;
-                const size_t go = img + (p_r[i] >= 0 ? p_go[i] : 0) + (size_t)(in ? rn : 0) * W;
+                const size_t go = img_n + (p_r[i] >= 0 ? p_go[i] : 0) + (size_t)(in ? rn : 0) * W;
                 // (a piece whose channel is missing in one of the blocks reads the block's first channel: unused)
-                const float4 a4 = *reinterpret_cast<const float4 *>(v + (p_hv[i] ? go : img));
-                const float4 b4 = *reinterpret_cast<const float4 *>(x + (p_hx[i] ? go : img));
+                const float4 a4 = *reinterpret_cast<const float4 *>(v + (p_hv[i] ? go : img_n));
+                const float4 b4 = *reinterpret_cast<const float4 *>(x + (p_hx[i] ? go : img_n));
                 pv[i] = a4;
                 px[i] = in ? b4 : make_float4(0.f, 0.f, 0.f, 0.f);
             }
@@ -243,6 +253,8 @@ __global__ __launch_bounds__(256) void k_dw_partial_mfma(DwBatch batch, float *_
                     acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bp[boff[s]], acc[s], 0, 0, 0);
             }
         }
+        if (ipw > 1)
+            img += img_stride;
     }
     __syncthreads();        // tiles no longer needed
     // lane (nn, g = kk) register (s, j) holds entry (o = 4g + j, col = 16s + nn)
@@ -394,7 +406,14 @@ static DwPlan plan_dw_mfma_block(int B, int Cv, int C, int H, int W, int k, int 
     if (g < 1) g = 1;
     g = (p.nchunks + (p.nchunks + g - 1) / g - 1) / ((p.nchunks + g - 1) / g);      // no empty workgroups
     p.groups = g;
-    p.nparts = (size_t)B * g;
+    // images of a single chunk in large batches: a workgroup takes several, as long as three workgroups per
+    // compute unit are left
+    p.ipw = 1;
+    if (p.nchunks == 1) {
+        const long ipw = (long)B * shared / 768;
+        p.ipw = ipw > 16 ? 16 : (ipw > 1 ? (int)ipw : 1);
+    }
+    p.nparts = (size_t)((B + p.ipw - 1) / p.ipw) * g;
     p.lds = lds_with(rt, p.xw, p.sxc);
     p.bytes = ((p.nparts * P * sizeof(float)) + 255) / 256 * 256;
     return p;
@@ -431,7 +450,8 @@ DwPlan plan_dw_mfma_layers(int layers, int B, int C, int H, int W, int k)
     if (g < 1) g = 1;
     g = (p.nchunks + (p.nchunks + g - 1) / g - 1) / ((p.nchunks + g - 1) / g);      // no empty workgroups
     p.groups = g;
-    p.nparts = (size_t)B * g;
+    const int ipw = p.ipw > 1 ? p.ipw : 1;
+    p.nparts = (size_t)((B + ipw - 1) / ipw) * g;
     return p;
 }
 
@@ -450,8 +470,10 @@ static bool launch_ns(const DwBatch &batch, int layers, float *part, const DwPla
         vec = 2;
     if (!ensure_dynamic_lds(reinterpret_cast<const void *>(&k_dw_partial_mfma<NS>), p.lds))
         return false;
+    const int ipw = p.ipw > 1 ? p.ipw : 1;
     hipLaunchKernelGGL(k_dw_partial_mfma<NS>, dim3((unsigned)(p.nparts * layers)), dim3(256), p.lds, stream, batch,
-                       part, B, C, H, W, k, p.rt, p.nchunks, p.groups, vec, p.xw, p.sxc, p.svc, Cv, Ctot, pstride);
+                       part, (B + ipw - 1) / ipw, C, H, W, k, p.rt, p.nchunks, p.groups, vec, p.xw, p.sxc, p.svc, Cv,
+                       Ctot, pstride, ipw, B);
     return true;
 }
 

@@ -39,6 +39,7 @@ struct DwPlan {
     int nchunks;     // row chunks per image
     int cw, ncol;    // generic pass 1: columns per chunk, column chunks per row chunk (cw = W, ncol = 1 unless W is too wide for LDS)
     int groups;      // matrix-core pass 1: workgroups per image, each looping over chunks
+    int ipw;         // matrix-core pass 1: images a workgroup takes one after the other (0 or 1: one; more only for images of a single chunk)
     int cb, cbx;     // matrix-core pass 1: 0, or the output / input channels of a block of dL/dw when the result is formed in blocks (more than 16 channels, or more columns C k k than a wave has accumulators)
     int xw, sxc, svc; // matrix-core pass 1: row and channel strides of the x tile, channel stride of the v tile (padded against LDS bank conflicts)
     size_t nparts;   // workgroups of pass 1 = rows of the partial-sum matrix

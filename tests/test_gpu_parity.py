@@ -212,6 +212,28 @@ def test_many_channels_other_kernel_sizes_with_workspace(shape):
         assert rel_err(host(x_plain), xr) <= TOL_ACT
 
 
+MANY_SMALL_IMAGES = [  # (B, C, H, W, k): images of one row chunk in batches large enough for 2 .. 16 per workgroup
+    (201, 48, 8, 8, 3), (1700, 12, 4, 4, 3), (331, 24, 8, 8, 5), (1537, 16, 8, 4, 3), (13000, 8, 2, 2, 3),
+]
+
+
+@pytest.mark.parametrize("shape", MANY_SMALL_IMAGES)
+def test_weight_gradient_of_many_small_images(shape):
+    """Large batches of images that fit one row chunk: a workgroup of the weight-gradient kernel takes several
+    images one after the other into the same accumulators (ragged last group included)."""
+    import torch
+    B, C, H, W, k = shape
+    print(f"many small images: {shape}", flush=True)
+    cs = inputs.make_case(B, C, H, W, k, seed=sum(shape) + 17, tap_std=0.15 / k)
+    wd, gd = dev(cs["w"][0]), dev(cs["g"])
+    xd = b.invconv_fwd(dev(cs["y"]), wd)
+    ws = b.new_workspace(b.bwd_workspace_bytes(B, C, H, W, k))
+    v, dw = b.invconv_bwd(xd, wd, gd, workspace=ws)
+    torch.cuda.synchronize()
+    vr, dwr = oracle.invconv_bwd(host(xd), cs["w"][0], cs["g"], THREADS)
+    assert rel_err(host(v), vr) <= TOL_ACT and rel_err(host(dw), dwr) <= TOL_DW
+
+
 WIDE_WS_SHAPES = [  # (B, C, H, W, k): many channels, 3 x 3, every group count C/4 = 5 .. 12, one to several bands
     (2, 48, 8, 8, 3), (3, 20, 5, 7, 3), (2, 24, 40, 9, 3), (1, 28, 33, 6, 3), (2, 32, 64, 5, 3), (1, 36, 17, 17, 3),
     (2, 40, 20, 9, 3), (1, 44, 16, 3, 3), (1, 48, 64, 4, 3), (101, 48, 8, 8, 3), (2, 22, 9, 9, 3),
