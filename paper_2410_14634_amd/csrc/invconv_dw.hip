@@ -406,11 +406,12 @@ static DwPlan plan_dw_mfma_block(int B, int Cv, int C, int H, int W, int k, int 
     if (g < 1) g = 1;
     g = (p.nchunks + (p.nchunks + g - 1) / g - 1) / ((p.nchunks + g - 1) / g);      // no empty workgroups
     p.groups = g;
-    // images of a single chunk in large batches: a workgroup takes several, as long as three workgroups per
-    // compute unit are left
+    // images of a single chunk in large batches: a workgroup takes several, as long as one and a half workgroups
+    // per compute unit are left - or three quarters of one for the blocks of a blocked result, whose rows of
+    // partial sums are long (measured at 48, 32, 24 and 12 channels on 8 x 8 images, 100 to 4096 of them)
     p.ipw = 1;
     if (p.nchunks == 1) {
-        const long ipw = (long)B * shared / 768;
+        const long ipw = (long)B * shared / (nblocks > 1 ? 192 : 384);
         p.ipw = ipw > 16 ? 16 : (ipw > 1 ? (int)ipw : 1);
     }
     p.nparts = (size_t)((B + p.ipw - 1) / p.ipw) * g;
