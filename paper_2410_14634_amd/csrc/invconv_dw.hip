@@ -322,10 +322,11 @@ static DwPlan plan_dw_mfma_block(int B, int Cv, int C, int H, int W, int k, int 
     if (lds_for(1) > budget)
         return p;
     // chunks of 8 rows; kernels of more than 9 rows take 16, so that a chunk still covers the k - 1 halo rows the
-    // streaming mode carries over from the chunk before - where that still leaves a workgroup per compute unit
+    // streaming mode carries over from the chunk before, and so do images of at most 16 rows, which are then one
+    // chunk and can go several to a workgroup - where that still leaves a workgroup per compute unit
     // (the blocks of a blocked result that share a launch count as images here)
     const int shared = nblocks < kChainMaxLayers ? nblocks : kChainMaxLayers;
-    const bool tall_chunks = stream_shape && k - 1 > 8 && (long)B * shared * ((H + 15) / 16) >= 320;
+    const bool tall_chunks = stream_shape && (k - 1 > 8 || H <= 16) && (long)B * shared * ((H + 15) / 16) >= 320;
     const int rt_max = tall_chunks ? 16 : 8;
     int rt = H < rt_max ? H : rt_max;
     while (rt > 1 && (lds_for(rt) > budget || (stream_shape && rt > k - 1 && CM * rt * (W / 4) > 256 * kDwPre)))
