@@ -215,6 +215,7 @@ def test_many_channels_other_kernel_sizes_with_workspace(shape):
 MANY_SMALL_IMAGES = [  # (B, C, H, W, k): images of one row chunk in batches large enough for 2 .. 16 per workgroup
     (201, 48, 8, 8, 3), (1700, 12, 4, 4, 3), (331, 24, 8, 8, 5), (1537, 16, 8, 4, 3), (13000, 8, 2, 2, 3),
     (1030, 12, 16, 16, 3), (401, 24, 13, 16, 3), (513, 12, 10, 16, 7),      # 9 to 16 rows: one chunk of 16 rows
+    (601, 12, 4, 8, 7),                                                      # fewer rows than the kernel's halo
 ]
 
 
