@@ -465,7 +465,7 @@ SCALE_SHAPES = {  # (B, C, H, W, k): the paper's image-size / batch-size / kerne
     "b100_c12_k9": (100, 12, 16, 16, 9), "b100_c12_k11": (100, 12, 16, 16, 11),
     "b100_c48_k2": (100, 48, 8, 8, 2), "b100_c48_k5": (100, 48, 8, 8, 5), "b100_c48_k7": (100, 48, 8, 8, 7),
     "b100_c48_k9": (100, 48, 8, 8, 9), "b100_c48_k11": (100, 48, 8, 8, 11),
-    "b1024_c12": (1024, 12, 16, 16, 3),
+    "b1024_c12": (1024, 12, 16, 16, 3), "b1024_c48": (1024, 48, 8, 8, 3),
 }
 
 
