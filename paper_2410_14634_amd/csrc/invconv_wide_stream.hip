@@ -43,9 +43,26 @@ __global__ __launch_bounds__(1024) void k_wide_fold_stream(const float *__restri
         const float v = w[((oo * C + ii) * K + a) * K + b];
         return (t == 0 && ii > oo) ? 0.0f : v;
     };
-    for (int idx = tid; idx < C * C; idx += 1024) {
-        sL[idx] = entry(0, idx / C, idx % C);
-        sT[idx] = tp ? entry(tp, idx / C, idx % C) : 0.0f;
+    {
+        // all of a thread's entries in flight before the first goes to LDS
+        constexpr int NL = (C * C + 1023) / 1024;
+        float a[NL], t[NL];
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            const int idx = tid + 1024 * u;
+            const bool ok = idx < C * C;
+            const int o = ok ? idx / C : 0, i = ok ? idx % C : 0;
+            a[u] = entry(0, o, i);
+            t[u] = tp ? entry(tp, o, i) : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            const int idx = tid + 1024 * u;
+            if (idx < C * C) {
+                sL[idx] = a[u];
+                sT[idx] = t[u];
+            }
+        }
     }
     __syncthreads();
     // Linv in 16 x 16 blocks by the whole workgroup
@@ -53,22 +70,36 @@ __global__ __launch_bounds__(1024) void k_wide_fold_stream(const float *__restri
     constexpr int OB = ws_out_blocks(C);
     float *dst = gw + (size_t)tp * OB * CQ * 64;
     constexpr int VW = ws_vec(CQ);
-    for (int idx = tid; idx < OB * CQ * 64; idx += 1024) {
-        const int e = idx % VW, lane = (idx / VW) & 63, q = (idx / (VW * 64)) % (CQ / VW), ob = idx / (CQ * 64);
-        const int c4 = VW * q + e;
-        const int o = 16 * ob + (lane & 15), i = 4 * c4 + (lane >> 4);
-        float val = 0.0f;
-        if (o < C) {
-            if (tp == 0) {
-                val = sLinv[o * C + i];
-            } else {
-                float s = 0.0f;
-                for (int j = 0; j <= o; ++j)
-                    s += sLinv[o * C + j] * sT[j * C + i];
-                val = -s;
+    if (tp == 0) {
+        for (int idx = tid; idx < OB * CQ * 64; idx += 1024) {
+            const int e = idx % VW, lane = (idx / VW) & 63, q = (idx / (VW * 64)) % (CQ / VW), ob = idx / (CQ * 64);
+            const int o = 16 * ob + (lane & 15), i = 4 * (VW * q + e) + (lane >> 4);
+            dst[idx] = o < C ? sLinv[o * C + i] : 0.0f;
+        }
+        return;
+    }
+    // -Linv W_tp on the matrix cores: a task is one 16 x 16 block of the product, a wave per task; Linv is lower
+    // triangular, so a block of rows 16 ob .. needs only the first 4 (ob + 1) of the C/4 instructions.  Rows past C
+    // are written as zeros.
+    const int wave = tid >> 6, lane = tid & 63, n = lane & 15, g = lane >> 4;
+    for (int task = wave; task < OB * OB; task += 16) {
+        const int ob = task / OB, ib = task % OB;
+        const int o_a = 16 * ob + n, i_b = 16 * ib + n;
+        const int nc = 4 * (ob + 1) < CQ ? 4 * (ob + 1) : CQ;
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < nc; ++c) {
+            const float av = sLinv[(o_a < C ? o_a : 0) * C + 4 * c + g];
+            const float bv = sT[(4 * c + g) * C + (i_b < C ? i_b : 0)];
+            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(o_a < C ? av : 0.0f, i_b < C ? bv : 0.0f, acc, 0, 0, 0);
+        }
+        if (i_b < C) {
+            const int c4 = i_b >> 2, gi = i_b & 3;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int m = 4 * g + j;        // row 16 ob + m of the product, held by lane (m, gi) of wave ob
+                dst[ob * CQ * 64 + ((c4 / VW) * 64 + m + 16 * gi) * VW + c4 % VW] = -acc[j];
             }
         }
-        dst[idx] = val;
     }
 }
 
